@@ -1,0 +1,131 @@
+"""ctypes wrapper around the plain-C oracle (numpy arrays in, numpy arrays out).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the CPU-baseline leg of
+the benchmark; never by the library or its Python binding.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rago_oracle.c")
+_LIB = os.path.join(_HERE, "librago_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add, OpenMP over queries)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _arr(a, dt):
+    return np.ascontiguousarray(np.asarray(a), dtype=dt)
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+I64 = ctypes.c_int64
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def coarse(Q, C):
+    Q, C = _arr(Q, np.float32), _arr(C, np.float32)
+    S = np.empty((Q.shape[0], C.shape[0]), np.float32)
+    _chk(_load().oracle_coarse(_p(Q), _p(C), I64(Q.shape[0]), I64(C.shape[0]), I64(Q.shape[1]), _p(S)), "coarse")
+    return S
+
+
+def select(S, nprobe):
+    S = _arr(S, np.float32)
+    probes = np.empty((S.shape[0], nprobe), np.int32)
+    _chk(_load().oracle_select(_p(S), I64(S.shape[0]), I64(S.shape[1]), I64(nprobe), _p(probes)), "select")
+    return probes
+
+
+def lut_f32(Q, C, CB, probes):
+    Q, C, CB, probes = _arr(Q, np.float32), _arr(C, np.float32), _arr(CB, np.float32), _arr(probes, np.int32)
+    nq, d = Q.shape
+    m = CB.shape[0]
+    L = np.empty((nq, probes.shape[1], m, 256), np.float32)
+    _chk(_load().oracle_lut_f32(_p(Q), _p(C), _p(CB), _p(probes), I64(nq), I64(probes.shape[1]), I64(d), I64(m),
+                                _p(L)), "lut_f32")
+    return L
+
+
+def quantise(L):
+    L = _arr(L, np.float32)
+    nq, nprobe, m, _ = L.shape
+    LUT8 = np.empty(L.shape, np.uint8)
+    B = np.empty((nq, nprobe), np.int32)
+    delta = np.empty(nq, np.float32)
+    _chk(_load().oracle_quantise(_p(L), I64(nq), I64(nprobe), I64(m), _p(LUT8), _p(B), _p(delta)), "quantise")
+    return LUT8, B, delta
+
+
+def scan_topk(probes, LUT8, B, delta, list_offsets, codes, ids, k):
+    probes, LUT8, B = _arr(probes, np.int32), _arr(LUT8, np.uint8), _arr(B, np.int32)
+    delta = None if delta is None else _arr(delta, np.float32)
+    off, codes, ids = _arr(list_offsets, np.int64), _arr(codes, np.uint8), _arr(ids, np.int64)
+    nq, nprobe = probes.shape
+    m = codes.shape[1]
+    oi, osc, ois = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32), np.empty((nq, k), np.int32)
+    _chk(_load().oracle_scan_topk(_p(probes), _p(LUT8), _p(B), _p(delta), _p(off), _p(codes), _p(ids), I64(nq),
+                                  I64(nprobe), I64(m), I64(k), _p(oi), _p(ois), _p(osc)), "scan_topk")
+    return oi, ois, osc
+
+
+def adc_f32_topk(probes, L, list_offsets, codes, ids, k):
+    probes, L = _arr(probes, np.int32), _arr(L, np.float32)
+    off, codes, ids = _arr(list_offsets, np.int64), _arr(codes, np.uint8), _arr(ids, np.int64)
+    nq, nprobe = probes.shape
+    oi, osc = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32)
+    _chk(_load().oracle_adc_f32_topk(_p(probes), _p(L), _p(off), _p(codes), _p(ids), I64(nq), I64(nprobe),
+                                     I64(codes.shape[1]), I64(k), _p(oi), _p(osc)), "adc_f32_topk")
+    return oi, osc
+
+
+def ivfpq_search(Q, index, nprobe, k):
+    """index: dict with numpy arrays centroids, codebooks, list_offsets, codes, ids."""
+    Q = _arr(Q, np.float32)
+    C, CB = _arr(index["centroids"], np.float32), _arr(index["codebooks"], np.float32)
+    off, codes, ids = _arr(index["list_offsets"], np.int64), _arr(index["codes"], np.uint8), _arr(index["ids"], np.int64)
+    nq, d = Q.shape
+    oi, osc, ois = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32), np.empty((nq, k), np.int32)
+    probes, delta = np.empty((nq, nprobe), np.int32), np.empty(nq, np.float32)
+    _chk(_load().oracle_ivfpq_search(_p(Q), I64(nq), I64(d), _p(C), I64(C.shape[0]), _p(CB), I64(CB.shape[0]),
+                                     _p(off), _p(codes), _p(ids), I64(nprobe), I64(k), _p(oi), _p(osc), _p(ois),
+                                     _p(probes), _p(delta)), "ivfpq_search")
+    return dict(ids=oi, scores=osc, iscores=ois, probes=probes, delta=delta)
+
+
+def flat_search(corpus_bits, query_bits, k):
+    """corpus_bits uint16 [R][n][d], query_bits uint16 [R][nq][d]: raw bf16 bit patterns."""
+    X, Qb = _arr(corpus_bits, np.uint16), _arr(query_bits, np.uint16)
+    R, n, d = X.shape
+    nqr = Qb.shape[1]
+    oi, osc = np.empty((R, nqr, k), np.int64), np.empty((R, nqr, k), np.float32)
+    _chk(_load().oracle_flat_search(_p(X), _p(Qb), I64(R), I64(n), I64(nqr), I64(d), I64(k), _p(oi), _p(osc)),
+         "flat_search")
+    return oi, osc

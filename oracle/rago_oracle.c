@@ -1,0 +1,277 @@
+/*
+ * CPU oracle for IVF-PQ search and exact flat search.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, step-by-step statement of what the retrieval stage computes, used to
+ * check the HIP library and as the timed CPU baseline.  Nothing in the product path may
+ * call it, and it shares no code, header, table or helper with the HIP path.
+ *
+ * What the paper fixes: vector search returns the K most similar vectors to a D-dim query
+ * from a database (Section 2, "Vector search for retrieval"); IVF-PQ = inverted-file index
+ * + product quantisation, one byte per 4-16 dimensions (Section 2); a query scans only a
+ * P_scan fraction of the database, cost = bytes of PQ codes scanned (Section 3.3,
+ * "Retrieval component"); small per-request corpora are searched by brute-force kNN
+ * (Section 5.2).  The paper gives no listing for IVF-PQ, so the steps below are the standard
+ * algorithm with every unspecified choice (metric, residual PQ, table quantisation,
+ * tie-breaks, padding) fixed as documented at each function.
+ *
+ * Metric: inner product, larger = better.  All pointers are host memory.  Floating point:
+ * fp64 accumulation rounded once to fp32 where stated; compile with -ffp-contract=off so
+ * no multiply-add is fused.
+ *
+ * Pins (tests/, CPU-only): exhaustive reconstruct-and-matmul ADC at nprobe = nlist, the
+ * look-up-table sum identity, an integer-exact worked case, quantisation error bound and
+ * end points, brute-force sorts with forced ties, numpy matmul for coarse and flat scores.
+ * Parity unpinned: absolute recall values on synthetic data (data-dependent; reported only).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define KSUB 256
+
+enum { ORACLE_OK = 0, ORACLE_EINVAL = -1, ORACLE_ENOMEM = -2 };
+
+/* ---- ordered selection: the best `k` of a stream under (key descending, id ascending) ---- */
+typedef struct { double key; int64_t id; } cand_t;
+
+static int better(cand_t a, cand_t b) { return a.key > b.key || (a.key == b.key && a.id < b.id); }
+
+/* best[0..*cnt) is kept sorted best-first; equivalent to sorting everything and taking k. */
+static void offer(cand_t* best, int64_t* cnt, int64_t k, cand_t c) {
+    if (k <= 0) return;
+    if (*cnt == k && !better(c, best[k - 1])) return;
+    int64_t i = (*cnt < k) ? (*cnt)++ : k - 1;
+    while (i > 0 && better(c, best[i - 1])) { best[i] = best[i - 1]; --i; }
+    best[i] = c;
+}
+
+/* ---- step 1: coarse scores S[q][l] = <Q[q], C[l]>, fp64 accumulate -> fp32 (IVF level, Section 2) ---- */
+int oracle_coarse(const float* Q, const float* C, int64_t nq, int64_t nlist, int64_t d, float* S) {
+    if (!Q || !C || !S || nq < 0 || nlist <= 0 || d <= 0) return ORACLE_EINVAL;
+    for (int64_t q = 0; q < nq; ++q)
+        for (int64_t l = 0; l < nlist; ++l) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < d; ++t) acc += (double)Q[q * d + t] * (double)C[l * d + t];
+            S[q * nlist + l] = (float)acc;
+        }
+    return ORACLE_OK;
+}
+
+/* ---- step 2: the nprobe lists with the largest S, ties -> lower list number, in rank order
+ *      (the scanned subset of Section 3.3) ---- */
+int oracle_select(const float* S, int64_t nq, int64_t nlist, int64_t nprobe, int32_t* probes) {
+    if (!S || !probes || nq < 0 || nprobe <= 0 || nprobe > nlist) return ORACLE_EINVAL;
+    cand_t* best = (cand_t*)malloc(sizeof(cand_t) * (size_t)nprobe);
+    if (!best) return ORACLE_ENOMEM;
+    for (int64_t q = 0; q < nq; ++q) {
+        int64_t cnt = 0;
+        for (int64_t l = 0; l < nlist; ++l) {
+            cand_t c = { (double)S[q * nlist + l], l };
+            offer(best, &cnt, nprobe, c);
+        }
+        for (int64_t p = 0; p < nprobe; ++p) probes[q * nprobe + p] = (int32_t)best[p].id;
+    }
+    free(best);
+    return ORACLE_OK;
+}
+
+/* ---- step 3: fp32 look-up tables of the residual PQ, one per (query, probed list).
+ *      A database vector in list l with code (c_0..c_{m-1}) is reconstructed as
+ *      C[l] + concat_j CB[j][c_j]; its score with q splits over the m sub-spaces, so
+ *      L[q,p][j][c] = < q_j , C[l]_j + CB[j][c] >  (fp64 accumulate -> fp32). ---- */
+int oracle_lut_f32(const float* Q, const float* C, const float* CB, const int32_t* probes,
+                   int64_t nq, int64_t nprobe, int64_t d, int64_t m, float* L) {
+    if (!Q || !C || !CB || !probes || !L || m <= 0 || d % m) return ORACLE_EINVAL;
+    const int64_t dsub = d / m;
+    for (int64_t q = 0; q < nq; ++q)
+        for (int64_t p = 0; p < nprobe; ++p) {
+            const int64_t l = probes[q * nprobe + p];
+            for (int64_t j = 0; j < m; ++j)
+                for (int64_t c = 0; c < KSUB; ++c) {
+                    double acc = 0.0;
+                    for (int64_t t = 0; t < dsub; ++t)
+                        acc += (double)Q[q * d + j * dsub + t] *
+                               ((double)C[l * d + j * dsub + t] + (double)CB[(j * KSUB + c) * dsub + t]);
+                    L[(((q * nprobe + p) * m + j) * KSUB) + c] = (float)acc;
+                }
+        }
+    return ORACLE_OK;
+}
+
+/* ---- step 4: 8-bit tables (the lower-precision, memory-bound PQ variant of Section 2).
+ *      lo/hi = min/max over c of one sub-table; one step per QUERY,
+ *      delta_q = max_{p,j}(hi - lo) / 255 (fp32; 1 if zero), so integer scores of different
+ *      lists of a query are comparable; LUT8 = clamp(rne((L - lo) / delta_q), 0, 255) in
+ *      fp32; the dropped offsets go into one integer bias per (query, probe):
+ *      B = rne( (sum_j lo_j in fp64) / delta_q ). ---- */
+int oracle_quantise(const float* L, int64_t nq, int64_t nprobe, int64_t m,
+                    uint8_t* LUT8, int32_t* B, float* delta) {
+    if (!L || !LUT8 || !B || !delta) return ORACLE_EINVAL;
+    for (int64_t q = 0; q < nq; ++q) {
+        float range = 0.0f;
+        for (int64_t pj = 0; pj < nprobe * m; ++pj) {
+            const float* row = L + (q * nprobe * m + pj) * KSUB;
+            float lo = row[0], hi = row[0];
+            for (int c = 1; c < KSUB; ++c) { if (row[c] < lo) lo = row[c]; if (row[c] > hi) hi = row[c]; }
+            if (hi - lo > range) range = hi - lo;
+        }
+        float dq = range / 255.0f;
+        if (!(dq > 0.0f)) dq = 1.0f;
+        delta[q] = dq;
+        for (int64_t p = 0; p < nprobe; ++p) {
+            double losum = 0.0;
+            for (int64_t j = 0; j < m; ++j) {
+                const float* row = L + ((q * nprobe + p) * m + j) * KSUB;
+                uint8_t* out = LUT8 + ((q * nprobe + p) * m + j) * KSUB;
+                float lo = row[0];
+                for (int c = 1; c < KSUB; ++c) if (row[c] < lo) lo = row[c];
+                for (int c = 0; c < KSUB; ++c) {
+                    float r = nearbyintf((row[c] - lo) / dq);
+                    out[c] = (uint8_t)(r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r));
+                }
+                losum += (double)lo;
+            }
+            B[q * nprobe + p] = (int32_t)nearbyint(losum / (double)dq);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---- steps 5-6: integer ADC scan of every vector of every probed list,
+ *      I = B[q,p] + sum_j LUT8[q,p][j][code_j]; best k by (I descending, id ascending);
+ *      scores = (float)I * delta_q; short results padded with (-1, INT32_MIN, -inf). ---- */
+int oracle_scan_topk(const int32_t* probes, const uint8_t* LUT8, const int32_t* B, const float* delta,
+                     const int64_t* list_offsets, const uint8_t* codes, const int64_t* ids,
+                     int64_t nq, int64_t nprobe, int64_t m, int64_t k,
+                     int64_t* out_ids, int32_t* out_iscores, float* out_scores) {
+    if (!probes || !LUT8 || !B || !list_offsets || !codes || !ids || !out_ids || k <= 0) return ORACLE_EINVAL;
+    int rc = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < nq; ++q) {
+        cand_t* best = (cand_t*)malloc(sizeof(cand_t) * (size_t)k);
+        if (!best) { rc = ORACLE_ENOMEM; continue; }
+        int64_t cnt = 0;
+        for (int64_t p = 0; p < nprobe; ++p) {
+            const int64_t l = probes[q * nprobe + p];
+            const uint8_t* lut = LUT8 + (q * nprobe + p) * m * KSUB;
+            for (int64_t i = list_offsets[l]; i < list_offsets[l + 1]; ++i) {
+                int32_t I = B[q * nprobe + p];
+                for (int64_t j = 0; j < m; ++j) I += lut[j * KSUB + codes[i * m + j]];
+                cand_t c = { (double)I, ids[i] };
+                offer(best, &cnt, k, c);
+            }
+        }
+        for (int64_t r = 0; r < k; ++r) {
+            const int have = r < cnt;
+            out_ids[q * k + r] = have ? best[r].id : -1;
+            const int32_t I = have ? (int32_t)best[r].key : INT32_MIN;
+            if (out_iscores) out_iscores[q * k + r] = I;
+            if (out_scores) out_scores[q * k + r] = have ? (float)I * (delta ? delta[q] : 1.0f) : -INFINITY;
+        }
+        free(best);
+    }
+    return rc;
+}
+
+/* ---- step 7 (checking mode, never compared with the HIP path): ADC without table
+ *      quantisation, F = fp32( sum_j L[q,p][j][code_j] in fp64 ), best k by (F desc, id asc). ---- */
+int oracle_adc_f32_topk(const int32_t* probes, const float* L, const int64_t* list_offsets,
+                        const uint8_t* codes, const int64_t* ids, int64_t nq, int64_t nprobe,
+                        int64_t m, int64_t k, int64_t* out_ids, float* out_scores) {
+    if (!probes || !L || !list_offsets || !codes || !ids || !out_ids || !out_scores || k <= 0) return ORACLE_EINVAL;
+    cand_t* best = (cand_t*)malloc(sizeof(cand_t) * (size_t)k);
+    if (!best) return ORACLE_ENOMEM;
+    for (int64_t q = 0; q < nq; ++q) {
+        int64_t cnt = 0;
+        for (int64_t p = 0; p < nprobe; ++p) {
+            const int64_t l = probes[q * nprobe + p];
+            const float* lut = L + (q * nprobe + p) * m * KSUB;
+            for (int64_t i = list_offsets[l]; i < list_offsets[l + 1]; ++i) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < m; ++j) acc += (double)lut[j * KSUB + codes[i * m + j]];
+                cand_t c = { (double)(float)acc, ids[i] };
+                offer(best, &cnt, k, c);
+            }
+        }
+        for (int64_t r = 0; r < k; ++r) {
+            out_ids[q * k + r] = r < cnt ? best[r].id : -1;
+            out_scores[q * k + r] = r < cnt ? (float)best[r].key : -INFINITY;
+        }
+    }
+    free(best);
+    return ORACLE_OK;
+}
+
+/* ---- whole search, steps 1-6 chained query by query (so the fp32 tables of only one query
+ *      are alive at a time).  Optional outputs may be NULL. ---- */
+int oracle_ivfpq_search(const float* Q, int64_t nq, int64_t d, const float* C, int64_t nlist,
+                        const float* CB, int64_t m, const int64_t* list_offsets, const uint8_t* codes,
+                        const int64_t* ids, int64_t nprobe, int64_t k,
+                        int64_t* out_ids, float* out_scores, int32_t* out_iscores,
+                        int32_t* out_probes, float* out_delta) {
+    if (!Q || !C || !CB || !out_ids || nprobe <= 0 || nprobe > nlist || k <= 0 || m <= 0 || d % m) return ORACLE_EINVAL;
+    int rc = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < nq; ++q) {
+        float* S = (float*)malloc(sizeof(float) * (size_t)nlist);
+        int32_t* pr = (int32_t*)malloc(sizeof(int32_t) * (size_t)nprobe);
+        float* L = (float*)malloc(sizeof(float) * (size_t)(nprobe * m * KSUB));
+        uint8_t* L8 = (uint8_t*)malloc((size_t)(nprobe * m * KSUB));
+        int32_t* B = (int32_t*)malloc(sizeof(int32_t) * (size_t)nprobe);
+        float dq = 1.0f;
+        int r = (S && pr && L && L8 && B) ? ORACLE_OK : ORACLE_ENOMEM;
+        if (!r) r = oracle_coarse(Q + q * d, C, 1, nlist, d, S);
+        if (!r) r = oracle_select(S, 1, nlist, nprobe, pr);
+        if (!r) r = oracle_lut_f32(Q + q * d, C, CB, pr, 1, nprobe, d, m, L);
+        if (!r) r = oracle_quantise(L, 1, nprobe, m, L8, B, &dq);
+        if (!r) r = oracle_scan_topk(pr, L8, B, &dq, list_offsets, codes, ids, 1, nprobe, m, k,
+                                     out_ids + q * k, out_iscores ? out_iscores + q * k : NULL,
+                                     out_scores ? out_scores + q * k : NULL);
+        if (!r && out_probes) memcpy(out_probes + q * nprobe, pr, sizeof(int32_t) * (size_t)nprobe);
+        if (!r && out_delta) out_delta[q] = dq;
+        if (r) rc = r;
+        free(S); free(pr); free(L); free(L8); free(B);
+    }
+    return rc;
+}
+
+/* ---- exact flat search over small per-request corpora (brute-force kNN, Section 5.2):
+ *      s[r][q][i] = fp32( sum_t bf16(Q) * bf16(X) in fp64 ), best k by (s desc, i asc).
+ *      bf16 = upper 16 bits of an IEEE fp32. ---- */
+static float bf16_to_f32(uint16_t h) { uint32_t u = (uint32_t)h << 16; float f; memcpy(&f, &u, 4); return f; }
+
+int oracle_flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t n, int64_t nqr,
+                       int64_t d, int64_t k, int64_t* out_ids, float* out_scores) {
+    if (!X || !Qb || !out_ids || !out_scores || R < 0 || n < 0 || nqr < 0 || d <= 0 || k <= 0) return ORACLE_EINVAL;
+    int rc = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t rq = 0; rq < R * nqr; ++rq) {
+        const int64_t r = rq / nqr;
+        cand_t* best = (cand_t*)malloc(sizeof(cand_t) * (size_t)k);
+        if (!best) { rc = ORACLE_ENOMEM; continue; }
+        int64_t cnt = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < d; ++t)
+                acc += (double)bf16_to_f32(Qb[rq * d + t]) * (double)bf16_to_f32(X[(r * n + i) * d + t]);
+            cand_t c = { (double)(float)acc, i };
+            offer(best, &cnt, k, c);
+        }
+        for (int64_t j = 0; j < k; ++j) {
+            out_ids[rq * k + j] = j < cnt ? best[j].id : -1;
+            out_scores[rq * k + j] = j < cnt ? (float)best[j].key : -INFINITY;
+        }
+        free(best);
+    }
+    return rc;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

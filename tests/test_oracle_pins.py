@@ -1,0 +1,328 @@
+"""CPU-only pins of the oracle against closed forms, identities, library routines and brute force."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from helpers import list_of, reconstruct, to_np, topk_desc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def rnd():
+    ix = to_np(synth.random_index(n=1500, d=16, m=4, nlist=8, seed=11, empty_lists=(3,), dup_codes=40,
+                                  shuffle_ids=True))
+    g = torch.Generator().manual_seed(5)
+    Q = torch.nn.functional.normalize(torch.randn(6, 16, generator=g), dim=1).numpy()
+    return ix, Q
+
+
+@pytest.fixture(scope="module")
+def trained():
+    cfg = synth.TINY.scaled(n=20000, d=32, m=8, nlist=32, components=32, train_n=8000, pq_train_n=4096,
+                            kmeans_iters=5)
+    ix = to_np(synth.build_index(cfg))
+    Q = synth.make_queries(cfg, 12).numpy()
+    return cfg, ix, Q
+
+
+# ------------------------------------------------------------------ step 1: coarse = a plain matmul
+def test_coarse_equals_fp64_matmul(rnd):
+    ix, Q = rnd
+    S = oracle.coarse(Q, ix["centroids"])
+    ref = (Q.astype(np.float64) @ ix["centroids"].astype(np.float64).T)
+    assert S.shape == ref.shape and S.dtype == np.float32
+    assert np.max(np.abs(S - ref)) <= 2 ** -24 * np.max(np.abs(ref)) * 1.01
+    # a transposed operand or a wrong stride would break the per-entry dot product
+    assert abs(S[2, 5] - float(np.dot(Q[2].astype(np.float64), ix["centroids"][5].astype(np.float64)))) < 1e-7
+
+
+# ------------------------------------------------------------------ step 2: selection with forced ties
+def test_select_order_and_ties():
+    S = np.array([[0.5, 0.9, 0.9, -1.0, 0.5, 0.9, 0.1],
+                  [0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0]], np.float32)
+    p = oracle.select(S, 4)
+    assert p.tolist() == [[1, 2, 5, 0], [0, 1, 2, 3]]
+    g = np.random.default_rng(0)
+    S = g.integers(0, 6, size=(5, 40)).astype(np.float32)      # many exact ties
+    p = oracle.select(S, 9)
+    for q in range(5):
+        ref, _ = topk_desc(S[q].astype(np.float64), np.arange(40), 9)
+        assert p[q].tolist() == ref.tolist()
+    with pytest.raises(RuntimeError):
+        oracle.select(S, 41)                                   # nprobe > nlist is an error
+
+
+# ------------------------------------------------------------------ step 3: table identities
+def test_lut_sum_identity_is_score_of_reconstruction(rnd):
+    ix, Q = rnd
+    probes = np.tile(np.arange(8, dtype=np.int32), (Q.shape[0], 1))     # every list, in list order
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    xhat, lst, codes = reconstruct(ix), list_of(ix), ix["codes"]
+    ref = Q.astype(np.float64) @ xhat.T                                  # [nq][n]
+    m = codes.shape[1]
+    for q in range(Q.shape[0]):
+        got = sum(L[q, lst, j, codes[:, j]].astype(np.float64) for j in range(m))
+        assert np.max(np.abs(got - ref[q])) < 1e-6
+
+
+def test_lut_difference_between_lists_is_constant_in_c(rnd):
+    ix, Q = rnd
+    probes = np.tile(np.array([0, 5, 7], np.int32), (Q.shape[0], 1))
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes).astype(np.float64)
+    dsub = 16 // 4
+    for a, b in ((0, 1), (1, 2)):
+        diff = L[:, a] - L[:, b]                                         # [nq][m][256]
+        assert np.max(diff.max(axis=2) - diff.min(axis=2)) < 1e-6
+        la, lb = probes[0, a], probes[0, b]
+        for j in range(4):                                               # and equals <q_j, C[la]_j - C[lb]_j>
+            sl = slice(j * dsub, (j + 1) * dsub)
+            ref = Q[:, sl].astype(np.float64) @ (ix["centroids"][la, sl] - ix["centroids"][lb, sl]).astype(np.float64)
+            assert np.max(np.abs(diff[:, j, 17] - ref)) < 1e-6
+
+
+# ------------------------------------------------------------------ steps 3-6: integer-exact worked case
+def _read_golden():
+    vals = {}
+    for line in open(os.path.join(GOLDEN, "integer_case.txt")):
+        if line.startswith("#") or "=" not in line:
+            continue
+        k, v = line.split("=")
+        vals[k.strip()] = np.array([float(t) for t in v.split()], np.float32)
+    return vals
+
+
+def test_integer_exact_case():
+    v = _read_golden()
+    q = v["q"][None, :]
+    C = np.stack([v["C0"], v["C1"]])
+    CB = np.zeros((2, 256, 2), np.float32)
+    c = np.arange(256)
+    CB[0, :, 0] = c
+    CB[1, :, 0] = (c % 16) - 8
+    CB[1, :, 1] = (c // 16) - 8
+    g = np.random.default_rng(3)
+    n0, n1 = 300, 200
+    codes = g.integers(0, 256, size=(n0 + n1, 2)).astype(np.uint8)
+    codes[0] = (255, 0)
+    codes[1] = (0, 255)
+    off = np.array([0, n0, n0 + n1], np.int64)
+    ids = np.arange(n0 + n1, dtype=np.int64)
+    probes = np.array([[1, 0]], np.int32)
+    L = oracle.lut_f32(q, C, CB, probes)
+    LUT8, B, delta = oracle.quantise(L)
+    assert delta[0] == 1.0
+    assert LUT8[0, :, 0].min() == 0 and LUT8[0, :, 0].max() == 255 and LUT8[0, :, 1].max() == 75
+    k = n0 + n1
+    oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, off, codes, ids, k)
+    # closed form: exact integer inner product with the reconstruction
+    lst = np.repeat([0, 1], [n0, n1])
+    xhat = C[lst].astype(np.int64)
+    xhat[:, 0] += codes[:, 0]
+    xhat[:, 2] += (codes[:, 1] % 16).astype(np.int64) - 8
+    xhat[:, 3] += (codes[:, 1] // 16).astype(np.int64) - 8
+    exact = xhat @ v["q"].astype(np.int64)
+    rid, rkey = topk_desc(exact, ids, k)
+    assert oi[0].tolist() == rid.tolist()
+    assert ois[0].tolist() == rkey.tolist()
+    assert osc[0].tolist() == rkey.astype(np.float32).tolist()
+
+
+# ------------------------------------------------------------------ step 4: quantisation invariants
+def test_quantisation_endpoints_and_error_bound(trained):
+    cfg, ix, Q = trained
+    S = oracle.coarse(Q, ix["centroids"])
+    probes = oracle.select(S, 6)
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    LUT8, B, delta = oracle.quantise(L)
+    m = cfg.m
+    rng = L.max(axis=3) - L.min(axis=3)                                   # [nq][np][m]
+    assert np.array_equal(delta, (rng.reshape(len(Q), -1).max(axis=1) / np.float32(255.0)).astype(np.float32))
+    amin = L.argmin(axis=3)
+    assert np.all(np.take_along_axis(LUT8, amin[..., None], axis=3) == 0)
+    for q in range(len(Q)):                                               # widest sub-table reaches 255
+        p, j = np.unravel_index(rng[q].argmax(), rng[q].shape)
+        assert LUT8[q, p, j, L[q, p, j].argmax()] == 255
+    # table values are the rounded affine map of L, and monotone in L
+    recon = L.min(axis=3, keepdims=True).astype(np.float64) + LUT8 * delta[:, None, None, None].astype(np.float64)
+    assert np.max(np.abs(recon - L) / delta[:, None, None, None]) <= 0.5 + 1e-3
+    # |delta*I - F| <= delta*(m+1)/2 for every scanned vector (F = unquantised ADC score)
+    k = 50
+    oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    row_of_id = np.empty(cfg.n, np.int64)
+    row_of_id[ix["ids"]] = np.arange(cfg.n)
+    xhat = reconstruct(ix)
+    for q in range(len(Q)):
+        F = xhat[row_of_id[oi[q]]] @ Q[q].astype(np.float64)
+        assert np.max(np.abs(osc[q] - F)) <= delta[q] * (m + 1) / 2 * (1 + 1e-4)
+        assert np.array_equal(osc[q], ois[q].astype(np.float32) * delta[q])
+
+
+def test_zero_range_tables_give_unit_step():
+    Q = np.zeros((1, 8), np.float32)                                      # every table entry is 0
+    C = np.ones((2, 8), np.float32)
+    CB = np.ones((2, 256, 4), np.float32)
+    L = oracle.lut_f32(Q, C, CB, np.array([[0, 1]], np.int32))
+    LUT8, B, delta = oracle.quantise(L)
+    assert delta[0] == 1.0 and not LUT8.any() and not B.any()
+
+
+# ------------------------------------------------------------------ steps 5-6: brute force, ties, padding
+def _brute_integer(ix, probes, LUT8, B, k):
+    off, codes, ids = ix["list_offsets"], ix["codes"], ix["ids"]
+    out = []
+    for q in range(probes.shape[0]):
+        cand = []
+        for p, l in enumerate(probes[q]):
+            for i in range(off[l], off[l + 1]):
+                I = int(B[q, p]) + sum(int(LUT8[q, p, j, codes[i, j]]) for j in range(codes.shape[1]))
+                cand.append((-I, int(ids[i])))
+        cand.sort()
+        out.append(cand[:k])
+    return out
+
+
+def test_integer_scan_vs_python_brute_force_with_ties(rnd):
+    ix, Q = rnd
+    S = oracle.coarse(Q, ix["centroids"])
+    probes = oracle.select(S, 4)
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    LUT8, B, delta = oracle.quantise(L)
+    LUT8 = (LUT8 // 32).astype(np.uint8)            # coarse tables: massive exact ties, id order decides
+    k = 25
+    oi, ois, _ = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    ref = _brute_integer(ix, probes, LUT8, B, k)
+    ties = 0
+    for q in range(len(Q)):
+        assert [(-int(s), int(i)) for s, i in zip(ois[q], oi[q])] == ref[q]
+        ties += len(ois[q]) - len(set(ois[q].tolist()))
+    assert ties > 20
+
+
+def test_padding_when_fewer_candidates_than_k(rnd):
+    ix, Q = rnd
+    probes = np.tile(np.array([[3]], np.int32), (len(Q), 1))             # list 3 is empty
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    LUT8, B, delta = oracle.quantise(L)
+    oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], 5)
+    assert np.all(oi == -1) and np.all(ois == np.iinfo(np.int32).min) and np.all(np.isneginf(osc))
+    small = int(np.diff(ix["list_offsets"]).argmin())
+    probes[:] = 0
+    n0 = int(ix["list_offsets"][1] - ix["list_offsets"][0])
+    oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], n0 + 3)
+    assert np.all(oi[:, :n0] >= 0) and np.all(oi[:, n0:] == -1) and np.all(np.isneginf(osc[:, n0:]))
+    assert all(sorted(oi[q, :n0].tolist()) == sorted(ix["ids"][:n0].tolist()) for q in range(len(Q)))
+
+
+# ------------------------------------------------------------------ step 7 / nprobe = nlist: exhaustive ADC
+def test_all_lists_probed_equals_exhaustive_adc(trained):
+    cfg, ix, Q = trained
+    S = oracle.coarse(Q, ix["centroids"])
+    probes = oracle.select(S, cfg.nlist)
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    k = 20
+    oi, osc = oracle.adc_f32_topk(probes, L, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    full = Q.astype(np.float64) @ reconstruct(ix).T                        # [nq][n], independent path
+    for q in range(len(Q)):
+        rid, rkey = topk_desc(full[q], ix["ids"], k)
+        assert np.max(np.abs(osc[q] - rkey)) < 2e-6
+        assert len(set(oi[q].tolist()) & set(rid.tolist())) >= k - 1       # fp32 rounding may swap a near-tie
+    # the integer path keeps almost all of them and each winner is within the quantisation bound
+    LUT8, B, delta = oracle.quantise(L)
+    qi, qis, qsc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    row_of_id = np.empty(cfg.n, np.int64)
+    row_of_id[ix["ids"]] = np.arange(cfg.n)
+    overlap = 0
+    for q in range(len(Q)):
+        overlap += len(set(qi[q].tolist()) & set(oi[q].tolist()))
+        assert np.all(full[q][row_of_id[qi[q]]] >= osc[q, k - 1] - delta[q] * (cfg.m + 1))
+    assert overlap >= 0.8 * k * len(Q)
+
+
+def test_single_list_is_plain_pq_scan():
+    ix = to_np(synth.random_index(n=400, d=8, m=2, nlist=1, seed=2))
+    Q = np.random.default_rng(1).standard_normal((3, 8)).astype(np.float32)
+    r = oracle.ivfpq_search(Q, ix, 1, 400)
+    assert np.all(r["probes"] == 0)
+    assert all(sorted(r["ids"][q].tolist()) == list(range(400)) for q in range(3))
+    full = Q.astype(np.float64) @ reconstruct(ix).T
+    for q in range(3):                                                     # integer order follows the true order
+        top_true = set(np.argsort(-full[q])[:40].tolist())
+        assert len(top_true & set(r["ids"][q, :40].tolist())) >= 30
+
+
+# ------------------------------------------------------------------ recall against exact kNN
+def test_recall_monotone_in_nprobe_and_lossless_pq_is_exact():
+    # few mixture components split over many lists, so the number of probed lists matters
+    cfg = synth.TINY.scaled(n=12000, d=32, m=16, nlist=32, components=3, train_n=6000, pq_train_n=4096,
+                            kmeans_iters=5, seed=77)
+    ix = to_np(synth.build_index(cfg))
+    Q = synth.make_queries(cfg, 16).numpy()
+    X = ix["vectors"].astype(np.float64)
+    k = 10
+    exact = np.argsort(-(Q.astype(np.float64) @ X.T), axis=1, kind="stable")[:, :k]
+    rec = []
+    for nprobe in (1, 2, 4, 8, 32):
+        S = oracle.coarse(Q, ix["centroids"])
+        probes = oracle.select(S, nprobe)
+        L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+        oi, _ = oracle.adc_f32_topk(probes, L, ix["list_offsets"], ix["codes"], ix["ids"], k)
+        rec.append(np.mean([len(set(oi[q].tolist()) & set(exact[q].tolist())) / k for q in range(len(Q))]))
+    assert all(b >= a - 1e-9 for a, b in zip(rec, rec[1:])) and rec[-1] > rec[0] + 0.1, rec
+    # a database vector used as the query finds its own list first
+    own = oracle.select(oracle.coarse(ix["vectors"][:50], ix["centroids"]), 1)[:, 0]
+    lst_of_id = np.empty(cfg.n, np.int64)
+    lst_of_id[ix["ids"]] = list_of(ix)
+    assert np.array_equal(own, lst_of_id[:50])
+    # lossless PQ: dsub = 1 and residual coordinates drawn from the 256 codewords themselves
+    g = np.random.default_rng(9)
+    d, nlist, n = 6, 4, 300
+    C = g.standard_normal((nlist, d)).astype(np.float32)
+    CB = g.standard_normal((d, 256, 1)).astype(np.float32)
+    lst = np.sort(g.integers(0, nlist, n))
+    codes = g.integers(0, 256, (n, d)).astype(np.uint8)
+    off = np.searchsorted(lst, np.arange(nlist + 1)).astype(np.int64)
+    idx = dict(centroids=C, codebooks=CB, list_offsets=off, codes=codes, ids=np.arange(n, dtype=np.int64))
+    Xl = reconstruct(idx)                                                  # the database IS its reconstruction
+    Ql = g.standard_normal((5, d)).astype(np.float32)
+    probes = np.tile(np.arange(nlist, dtype=np.int32), (5, 1))
+    oi, osc = oracle.adc_f32_topk(probes, oracle.lut_f32(Ql, C, CB, probes), off, codes, idx["ids"], 7)
+    ex = np.argsort(-(Ql.astype(np.float64) @ Xl.T), axis=1, kind="stable")[:, :7]
+    assert np.array_equal(oi, ex)
+
+
+# ------------------------------------------------------------------ whole search = its stages chained
+def test_search_equals_stage_chain(trained):
+    cfg, ix, Q = trained
+    r = oracle.ivfpq_search(Q, ix, 5, 15)
+    S = oracle.coarse(Q, ix["centroids"])
+    probes = oracle.select(S, 5)
+    LUT8, B, delta = oracle.quantise(oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes))
+    oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], 15)
+    assert np.array_equal(r["probes"], probes) and np.array_equal(r["delta"], delta)
+    assert np.array_equal(r["ids"], oi) and np.array_equal(r["iscores"], ois) and np.array_equal(r["scores"], osc)
+
+
+# ------------------------------------------------------------------ flat search = matmul + stable argsort
+def test_flat_equals_matmul_and_stable_argsort():
+    cfg = synth.FLAT
+    corpus, queries = synth.make_flat(cfg, requests=2, n=700)
+    corpus[1, 5] = corpus[1, 300]                                          # duplicate rows: exact ties
+    corpus[1, 301] = corpus[1, 300]
+    queries[1, 0] = corpus[1, 300]
+    cb = corpus.view(torch.int16).numpy().view(np.uint16)
+    qb = queries.view(torch.int16).numpy().view(np.uint16)
+    oi, osc = oracle.flat_search(cb, qb, 32)
+    ref = torch.einsum("rqd,rnd->rqn", queries.double(), corpus.double()).numpy()
+    for r in range(2):
+        for q in range(cfg.nq):
+            order = np.argsort(-ref[r, q].astype(np.float32), kind="stable")[:32]
+            assert np.allclose(osc[r, q], ref[r, q][oi[r, q]], rtol=0, atol=1e-6)
+            assert oi[r, q].tolist() == order.tolist()
+    assert oi[1, 0, :3].tolist() == [5, 300, 301]
+    oi, osc = oracle.flat_search(cb[:, :3], qb, 5)                          # fewer rows than k: padded
+    assert np.all(oi[:, :, 3:] == -1) and np.all(np.isneginf(osc[:, :, 3:]))
