@@ -1,0 +1,160 @@
+/*
+ * rago.h - C ABI of the MI355X (gfx950) retrieval library.
+ *
+ * The retrieval stage of a RAG pipeline: batched approximate nearest-neighbour search over a
+ * product-quantised inverted-file (IVF-PQ) vector database, plus exact brute-force search over
+ * small per-request corpora.  Problem statement: return the K most similar database vectors to
+ * a D-dimensional query (paper Section 2, "Vector search for retrieval"); IVF-PQ and its
+ * byte-per-8-dimensions codes (Section 2; Section 4, "Models and database"); a query scans a
+ * P_scan fraction of the database and costs the bytes of PQ codes scanned (Section 3.3,
+ * "Retrieval component"); brute-force kNN for 1K-100K vector corpora (Section 5.2).
+ * Similarity = inner product (larger is better); on L2-normalised vectors this is cosine.
+ *
+ * Conventions
+ *  - Every function returns RAGO_OK (0) or a negative rago_status.  rago_last_error() gives a
+ *    thread-local message for the last failing call on this thread.
+ *  - "DEVICE" pointers are HIP device memory on the index's GPU; "HOST" pointers are ordinary
+ *    host memory.  The caller owns every buffer it passes and must keep DEVICE buffers alive
+ *    until `stream` has passed the call.  The library owns the index and its workspace.
+ *  - Search calls only enqueue work on `stream` (a hipStream_t, NULL = default stream); they do
+ *    not synchronise with the host.  Argument errors are detected synchronously and leave the
+ *    outputs untouched.  Calls on the same index must be serialised on one stream (they share
+ *    the index's workspace).
+ *  - Nothing here allocates through, links against, or knows about PyTorch.
+ */
+#ifndef RAGO_H
+#define RAGO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rago_status {
+    RAGO_OK = 0,
+    RAGO_INVALID_ARG = -1,   /* null/misaligned pointer, size out of range, nprobe > nlist, ...   */
+    RAGO_IO = -2,            /* file cannot be opened / read                                      */
+    RAGO_FORMAT = -3,        /* bad magic, truncated file, inconsistent offsets, unsorted ids     */
+    RAGO_OOM = -4,           /* host or device allocation failed                                  */
+    RAGO_DEVICE = -5,        /* a HIP call failed                                                 */
+    RAGO_UNSUPPORTED = -6    /* legal request outside what the kernels are built for              */
+} rago_status;
+
+typedef struct rago_index rago_index; /* opaque */
+
+typedef struct rago_index_desc {
+    int32_t d;        /* vector dimension                                   */
+    int32_t m;        /* PQ sub-quantisers = code bytes per vector          */
+    int32_t ksub;     /* codewords per sub-quantiser (always 256)           */
+    int32_t nlist;    /* inverted lists / coarse centroids                  */
+    int64_t n;        /* database vectors                                   */
+    int32_t metric;   /* 0 = inner product                                  */
+    int32_t device;   /* HIP device ordinal holding the index               */
+    int64_t max_list_len;
+    int64_t code_bytes_resident;  /* bytes of the re-laid-out code array in HBM (incl. padding) */
+} rago_index_desc;
+
+/* Plain (un-laid-out) IVF-PQ index handed over as arrays; see rago_index_wrap. */
+typedef struct rago_index_arrays {
+    int32_t d, m, nlist;
+    int64_t n;
+    const float*   centroids;     /* [nlist][d] fp32                                              */
+    const float*   codebooks;     /* [m][256][d/m] fp32                                           */
+    const int64_t* list_offsets;  /* [nlist+1], list l = rows list_offsets[l] .. list_offsets[l+1] */
+    const uint8_t* codes;         /* [n][m] one row per vector, list-major                        */
+    const int64_t* ids;           /* [n] list-major; unique; ascending inside every list          */
+} rago_index_arrays;
+
+/*
+ * rago_index_load: read an index file (HOST path) and place it on GPU `device`.
+ * File, little-endian: 64-byte header {char magic[8]="RAGOIVPQ", u32 version=1, u32 metric=0,
+ * u32 d, u32 m, u32 ksub=256, u32 nlist, u64 n, zero pad}, then centroids f32[nlist][d],
+ * codebooks f32[m][256][d/m], list_offsets i64[nlist+1], codes u8[n][m], ids i64[n].
+ * The codes are re-laid-out once for the scan (paper Section 4: 96-byte codes, 1 byte per 8
+ * dimensions, are what the scan streams).  On success *out owns all device memory.
+ * Errors: RAGO_IO, RAGO_FORMAT (incl. truncated), RAGO_UNSUPPORTED (m not in {16,32,64,96,128},
+ * ksub != 256, d % m != 0, a list longer than 2^31-65 vectors), RAGO_OOM, RAGO_DEVICE.
+ */
+int rago_index_load(const char* path, int device, rago_index** out);
+
+/*
+ * rago_index_wrap: same as rago_index_load but from arrays instead of a file.
+ * `arrays_on_device` != 0: all five arrays are DEVICE pointers on `device`; else HOST pointers.
+ * The arrays are copied / re-laid-out; the caller may free them when the call returns
+ * (the call synchronises the device).  Same errors as rago_index_load minus RAGO_IO.
+ */
+int rago_index_wrap(const rago_index_arrays* arrays, int arrays_on_device, int device, rago_index** out);
+
+/* Release the index and its workspace (synchronises the device).  NULL is accepted. */
+int rago_index_free(rago_index* idx);
+
+/* Fill *out with the index's shape.  HOST pointers. */
+int rago_index_info(const rago_index* idx, rago_index_desc* out);
+
+/*
+ * rago_ivfpq_search: batched IVF-PQ search (Sections 2 and 3.3): coarse scores of every query
+ * against every centroid, the nprobe best lists per query, an 8-bit look-up table per
+ * (query, list), an integer asymmetric-distance scan of the lists' codes, best k per query by
+ * (integer score descending, id ascending).
+ *   queries     DEVICE [nq][d] fp32 row-major, 16-byte aligned
+ *   nq >= 0, 1 <= nprobe <= nlist, 1 <= k <= 128
+ *   out_ids     DEVICE [nq][k] int64, best first, padded with -1
+ *   out_scores  DEVICE [nq][k] fp32 = integer score * the query's table step; pad = -inf
+ *   out_iscores DEVICE [nq][k] int32 or NULL; pad = INT32_MIN
+ * The workspace grows on demand (first call at a new size allocates; later calls do not).
+ */
+int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k,
+                      int64_t* out_ids, float* out_scores, int32_t* out_iscores, void* stream);
+
+/*
+ * rago_flat_search: exact inner-product search of R independent requests, each with its own
+ * corpus (brute-force kNN over freshly embedded long-context chunks, Section 5.2).
+ *   corpus_bf16  DEVICE [R][n][d] bf16 row-major, 16-byte aligned;  d % 32 == 0, d <= 1024
+ *   queries_bf16 DEVICE [R][nqr][d] bf16;  1 <= nqr <= 16
+ *   1 <= k <= 128
+ *   out_ids      DEVICE [R][nqr][k] int64 row index inside the request's corpus, pad -1
+ *   out_scores   DEVICE [R][nqr][k] fp32 (bf16 products, fp32 accumulation), pad -inf
+ * Order: score descending, ties by lower index.  `device` = GPU of the buffers.
+ * Uses a per-device workspace owned by the library (grown on demand).
+ */
+int rago_flat_search(const void* corpus_bf16, const void* queries_bf16, int32_t R, int64_t n, int32_t nqr,
+                     int32_t d, int32_t k, int64_t* out_ids, float* out_scores, int device, void* stream);
+
+/* Thread-local message of the last error on this thread ("" if none). */
+const char* rago_last_error(void);
+
+/* ---- stage-isolated entry points (same kernels as rago_ivfpq_search, one stage each) ---- */
+
+/* Coarse scores S[q][l] = <Q[q], C[l]> (fp32 MFMA).  out_S DEVICE [nq][nlist] fp32. */
+int rago_debug_coarse(rago_index* idx, const float* queries, int64_t nq, float* out_S, void* stream);
+
+/* The nprobe best lists per query, best first, ties by lower list number.  Scores of the lists
+ * near the cut are recomputed in fp64 from `queries`, so the choice does not depend on the
+ * rounding of S.  S DEVICE [nq][nlist]; out_probes DEVICE [nq][nprobe] int32. */
+int rago_debug_select(rago_index* idx, const float* queries, const float* S, int64_t nq, int32_t nprobe,
+                      int32_t* out_probes, void* stream);
+
+/* Look-up tables for given probes.  probes DEVICE [nq][nprobe] int32 (valid list numbers).
+ * out_L_f32 DEVICE [nq][nprobe][m][256] fp32 or NULL; out_LUT8 DEVICE [nq][nprobe][m][256] u8 or
+ * NULL; out_B DEVICE [nq][nprobe] int32 or NULL; out_delta DEVICE [nq] fp32 or NULL. */
+int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* probes, int64_t nq,
+                         int32_t nprobe, float* out_L_f32, uint8_t* out_LUT8, int32_t* out_B,
+                         float* out_delta, void* stream);
+
+/* Integer scan + top-k with caller-supplied tables: LUT8 DEVICE [nq][nprobe][m][256] u8,
+ * B DEVICE [nq][nprobe] int32.  Outputs as rago_ivfpq_search (scores omitted). */
+int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8, const int32_t* B,
+                    int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids, int32_t* out_iscores,
+                    void* stream);
+
+/* Counters of the last search on this index, HOST out[8] (synchronises `stream`):
+ * [0] scan tasks, [1] code bytes streamed by the scan, [2] algorithmic code bytes
+ * (sum over (query, probe) of list length * m), [3] queries whose probe choice was not
+ * provably independent of fp32 rounding, [4..7] reserved. */
+int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAGO_H */

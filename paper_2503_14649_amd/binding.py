@@ -1,0 +1,209 @@
+"""Thin ctypes binding of librago.so: argument marshalling only.
+
+Function names mirror the C ABI declared in include/rago.h.  PyTorch is used for device memory
+(`torch.empty(..., device="cuda")`, `.data_ptr()`) and for the current HIP stream; every step of
+the search runs inside the library's kernels.  There is no CPU fallback: importing this module
+without a built library raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librago.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or paper_2503_14649_amd/build.py) first; there is no fallback path")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _i32, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int
+
+
+class _Arrays(ctypes.Structure):
+    _fields_ = [("d", _i32), ("m", _i32), ("nlist", _i32), ("n", _i64), ("centroids", _vp), ("codebooks", _vp),
+                ("list_offsets", _vp), ("codes", _vp), ("ids", _vp)]
+
+
+class IndexDesc(ctypes.Structure):
+    _fields_ = [("d", _i32), ("m", _i32), ("ksub", _i32), ("nlist", _i32), ("n", _i64), ("metric", _i32),
+                ("device", _i32), ("max_list_len", _i64), ("code_bytes_resident", _i64)]
+
+
+_lib.rago_last_error.restype = ctypes.c_char_p
+_lib.rago_index_load.argtypes = [ctypes.c_char_p, _int, ctypes.POINTER(_vp)]
+_lib.rago_index_wrap.argtypes = [ctypes.POINTER(_Arrays), _int, _int, ctypes.POINTER(_vp)]
+_lib.rago_index_free.argtypes = [_vp]
+_lib.rago_index_info.argtypes = [_vp, ctypes.POINTER(IndexDesc)]
+_lib.rago_ivfpq_search.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.rago_flat_search.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _vp, _vp, _int, _vp]
+_lib.rago_debug_coarse.argtypes = [_vp, _vp, _i64, _vp, _vp]
+_lib.rago_debug_select.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp]
+_lib.rago_debug_build_lut.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp]
+_lib.rago_debug_scan.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]
+_lib.rago_debug_counters.argtypes = [_vp, _vp, _vp]
+
+
+class RagoError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"rago error {code}: {msg}")
+        self.code = code
+
+
+def _chk(rc):
+    if rc != 0:
+        raise RagoError(rc, _lib.rago_last_error().decode())
+
+
+def rago_last_error() -> str:
+    return _lib.rago_last_error().decode()
+
+
+def _stream(dev):
+    return _vp(torch.cuda.current_stream(dev).cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else _vp(t.data_ptr())
+
+
+def rago_index_load(path: str, device: int = 0):
+    h = _vp()
+    _chk(_lib.rago_index_load(os.fsencode(path), device, ctypes.byref(h)))
+    return h
+
+
+def rago_index_wrap(index: dict, device: int = 0):
+    """index: tensors centroids [nlist][d] f32, codebooks [m][256][dsub] f32, list_offsets [nlist+1] i64,
+    codes [n][m] u8, ids [n] i64; all on the CPU or all on cuda:`device`."""
+    c = index["centroids"].contiguous().float()
+    cb = index["codebooks"].contiguous().float()
+    off = index["list_offsets"].contiguous().to(torch.int64)
+    codes = index["codes"].contiguous()
+    ids = index["ids"].contiguous().to(torch.int64)
+    assert codes.dtype == torch.uint8
+    on_dev = c.is_cuda
+    assert all(t.is_cuda == on_dev for t in (cb, off, codes, ids)), "all arrays must live on the same side"
+    a = _Arrays(c.shape[1], cb.shape[0], c.shape[0], codes.shape[0], _ptr(c), _ptr(cb), _ptr(off), _ptr(codes), _ptr(ids))
+    h = _vp()
+    if on_dev:
+        torch.cuda.synchronize(device)
+    _chk(_lib.rago_index_wrap(ctypes.byref(a), int(on_dev), device, ctypes.byref(h)))
+    return h
+
+
+def rago_index_free(h):
+    _chk(_lib.rago_index_free(h))
+
+
+def rago_index_info(h) -> IndexDesc:
+    d = IndexDesc()
+    _chk(_lib.rago_index_info(h, ctypes.byref(d)))
+    return d
+
+
+def rago_ivfpq_search(h, queries: torch.Tensor, nprobe: int, k: int, want_iscores: bool = True, out=None):
+    """queries: cuda fp32 [nq][d].  Returns (ids i64 [nq][k], scores f32 [nq][k], iscores i32 [nq][k] or None)."""
+    assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+    nq, dev = queries.shape[0], queries.device
+    if out is None:
+        ids = torch.empty(nq, k, dtype=torch.int64, device=dev)
+        scores = torch.empty(nq, k, dtype=torch.float32, device=dev)
+        isc = torch.empty(nq, k, dtype=torch.int32, device=dev) if want_iscores else None
+    else:
+        ids, scores, isc = out
+    _chk(_lib.rago_ivfpq_search(h, _ptr(queries), nq, nprobe, k, _ptr(ids), _ptr(scores), _ptr(isc), _stream(dev)))
+    return ids, scores, isc
+
+
+def rago_flat_search(corpus: torch.Tensor, queries: torch.Tensor, k: int, out=None):
+    """corpus bf16 [R][n][d], queries bf16 [R][nqr][d] on the GPU -> (ids i64 [R][nqr][k], scores f32)."""
+    assert corpus.is_cuda and queries.is_cuda and corpus.dtype == torch.bfloat16 and queries.dtype == torch.bfloat16
+    assert corpus.is_contiguous() and queries.is_contiguous()
+    R, n, d = corpus.shape
+    nqr, dev = queries.shape[1], corpus.device
+    if out is None:
+        ids = torch.empty(R, nqr, k, dtype=torch.int64, device=dev)
+        scores = torch.empty(R, nqr, k, dtype=torch.float32, device=dev)
+    else:
+        ids, scores = out
+    _chk(_lib.rago_flat_search(_ptr(corpus), _ptr(queries), R, n, nqr, d, k, _ptr(ids), _ptr(scores),
+                               dev.index or 0, _stream(dev)))
+    return ids, scores
+
+
+def rago_debug_coarse(h, queries):
+    info = rago_index_info(h)
+    S = torch.empty(queries.shape[0], info.nlist, dtype=torch.float32, device=queries.device)
+    _chk(_lib.rago_debug_coarse(h, _ptr(queries), queries.shape[0], _ptr(S), _stream(queries.device)))
+    return S
+
+
+def rago_debug_select(h, queries, S, nprobe):
+    probes = torch.empty(S.shape[0], nprobe, dtype=torch.int32, device=S.device)
+    _chk(_lib.rago_debug_select(h, _ptr(queries), _ptr(S), S.shape[0], nprobe, _ptr(probes), _stream(S.device)))
+    return probes
+
+
+def rago_debug_build_lut(h, queries, probes, want_f32=True):
+    info = rago_index_info(h)
+    nq, nprobe = probes.shape
+    dev = queries.device
+    L = torch.empty(nq, nprobe, info.m, 256, dtype=torch.float32, device=dev) if want_f32 else None
+    L8 = torch.empty(nq, nprobe, info.m, 256, dtype=torch.uint8, device=dev)
+    B = torch.empty(nq, nprobe, dtype=torch.int32, device=dev)
+    delta = torch.empty(nq, dtype=torch.float32, device=dev)
+    _chk(_lib.rago_debug_build_lut(h, _ptr(queries), _ptr(probes), nq, nprobe, _ptr(L), _ptr(L8), _ptr(B), _ptr(delta),
+                                   _stream(dev)))
+    return L, L8, B, delta
+
+
+def rago_debug_scan(h, probes, LUT8, B, k):
+    nq, nprobe = probes.shape
+    dev = probes.device
+    ids = torch.empty(nq, k, dtype=torch.int64, device=dev)
+    isc = torch.empty(nq, k, dtype=torch.int32, device=dev)
+    _chk(_lib.rago_debug_scan(h, _ptr(probes), _ptr(LUT8), _ptr(B), nq, nprobe, k, _ptr(ids), _ptr(isc), _stream(dev)))
+    return ids, isc
+
+
+def rago_debug_counters(h, device=0):
+    out = (ctypes.c_int64 * 8)()
+    _chk(_lib.rago_debug_counters(h, out, _stream(torch.device("cuda", device))))
+    return list(out)
+
+
+class Index:
+    """Owning handle with the search calls as methods."""
+
+    def __init__(self, handle, device=0):
+        self.h, self.device = handle, device
+
+    @classmethod
+    def load(cls, path, device=0):
+        return cls(rago_index_load(path, device), device)
+
+    @classmethod
+    def wrap(cls, index: dict, device=0):
+        return cls(rago_index_wrap(index, device), device)
+
+    def info(self):
+        return rago_index_info(self.h)
+
+    def search(self, queries, nprobe, k, **kw):
+        return rago_ivfpq_search(self.h, queries, nprobe, k, **kw)
+
+    def counters(self):
+        return rago_debug_counters(self.h, self.device)
+
+    def close(self):
+        if self.h is not None:
+            rago_index_free(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,339 @@
+// C ABI of librago: index life-cycle, argument checking, stage sequencing.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <vector>
+
+#include "rago_internal.h"
+
+namespace rago {
+
+static thread_local std::string g_err;
+void set_error(const std::string& msg) { g_err = msg; }
+int fail(int code, const std::string& msg) { g_err = msg; return code; }
+
+int DevBuf::reserve(size_t bytes) {
+    if (bytes <= cap) return RAGO_OK;
+    if (p) { hipFree(p); p = nullptr; cap = 0; }
+    size_t want = bytes + bytes / 8 + 256;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        p = nullptr;
+        (void)hipGetLastError();
+        return fail(RAGO_OOM, "device allocation of " + std::to_string(want) + " bytes failed");
+    }
+    cap = want;
+    return RAGO_OK;
+}
+void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
+void Workspace::release() {
+    DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
+                     &list_cnt, &pair_off, &task_off, &cursor, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
+                     &counters, &tmp_lut8sw};
+    for (DevBuf* b : all) b->release();
+}
+
+static bool supported_m(int m) { return m == 16 || m == 32 || m == 64 || m == 96 || m == 128; }
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        ok = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+static void destroy(rago_index* idx) {
+    if (!idx) return;
+    hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->codebooks); hipFree(idx->list_off);
+    hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
+    idx->ws.release();
+    delete idx;
+}
+
+// Shape checks + small arrays; leaves codes_blk / ids allocated but unfilled.
+static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const int64_t* h_list_off) {
+    if (d <= 0 || m <= 0 || nlist <= 0 || n < 0) return fail(RAGO_INVALID_ARG, "non-positive index dimension");
+    if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
+    if (!supported_m(m)) return fail(RAGO_UNSUPPORTED, "m must be one of 16, 32, 64, 96, 128");
+    if (d > 4096) return fail(RAGO_UNSUPPORTED, "d > 4096");
+    if (h_list_off[0] != 0 || h_list_off[nlist] != n) return fail(RAGO_FORMAT, "list_offsets must start at 0 and end at n");
+    std::vector<int64_t> blk(nlist + 1);
+    blk[0] = 0;
+    int64_t maxlen = 0;
+    for (int l = 0; l < nlist; ++l) {
+        int64_t len = h_list_off[l + 1] - h_list_off[l];
+        if (len < 0) return fail(RAGO_FORMAT, "list_offsets must be non-decreasing");
+        if (len > 0x7fffffffLL - 64) return fail(RAGO_UNSUPPORTED, "list longer than 2^31-65 vectors");
+        if (len > maxlen) maxlen = len;
+        blk[l + 1] = blk[l] + (len + BLOCK_VECS - 1) / BLOCK_VECS;
+    }
+    idx->d = d; idx->m = m; idx->dsub = d / m; idx->nlist = nlist; idx->n = n;
+    idx->max_list_len = maxlen; idx->total_blocks = blk[nlist];
+    const size_t code_bytes = (size_t)idx->total_blocks * BLOCK_VECS * m;
+    if (hipMalloc(&idx->centroids, sizeof(float) * (size_t)nlist * d) != hipSuccess ||
+        hipMalloc(&idx->cnorm, sizeof(float) * (size_t)nlist) != hipSuccess ||
+        hipMalloc(&idx->codebooks, sizeof(float) * (size_t)m * KSUB * idx->dsub) != hipSuccess ||
+        hipMalloc(&idx->list_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
+        hipMalloc(&idx->blk_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
+        hipMalloc(&idx->codes_blk, code_bytes + 16) != hipSuccess ||
+        hipMalloc(&idx->ids, sizeof(int64_t) * (size_t)(n + 1)) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(RAGO_OOM, "device allocation for the index failed");
+    }
+    RAGO_HIP(hipMemcpy(idx->list_off, h_list_off, sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
+    RAGO_HIP(hipMemcpy(idx->blk_off, blk.data(), sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
+    return RAGO_OK;
+}
+
+static int finish(rago_index* idx, const uint8_t* d_codes_plain) {
+    int rc = build_layout(idx, d_codes_plain, nullptr);
+    if (rc) return rc;
+    std::vector<float> cn(idx->nlist);
+    RAGO_HIP(hipMemcpy(cn.data(), idx->cnorm, sizeof(float) * cn.size(), hipMemcpyDeviceToHost));
+    float mx = 0.f;
+    for (float v : cn) if (v > mx) mx = v;
+    idx->max_cnorm = mx;
+    return RAGO_OK;
+}
+
+}  // namespace rago
+
+using namespace rago;
+
+extern "C" {
+
+const char* rago_last_error(void) { return g_err.c_str(); }
+
+int rago_index_wrap(const rago_index_arrays* a, int on_device, int device, rago_index** out) {
+    if (!a || !out) return fail(RAGO_INVALID_ARG, "null argument");
+    if (!a->centroids || !a->codebooks || !a->list_offsets || (a->n > 0 && (!a->codes || !a->ids)))
+        return fail(RAGO_INVALID_ARG, "null array in rago_index_arrays");
+    if (a->nlist <= 0 || a->d <= 0 || a->m <= 0 || a->n < 0) return fail(RAGO_INVALID_ARG, "non-positive index dimension");
+    DeviceGuard g(device);
+    if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    std::vector<int64_t> off(a->nlist + 1);
+    if (on_device) RAGO_HIP(hipMemcpy(off.data(), a->list_offsets, sizeof(int64_t) * off.size(), hipMemcpyDeviceToHost));
+    else std::memcpy(off.data(), a->list_offsets, sizeof(int64_t) * off.size());
+    rago_index* idx = new rago_index();
+    idx->device = device;
+    int rc = prepare(idx, a->d, a->m, a->nlist, a->n, off.data());
+    uint8_t* plain = nullptr;
+    if (!rc) {
+        hipError_t e = hipMemcpy(idx->centroids, a->centroids, sizeof(float) * (size_t)a->nlist * a->d, kind);
+        if (e == hipSuccess) e = hipMemcpy(idx->codebooks, a->codebooks, sizeof(float) * (size_t)a->m * KSUB * (a->d / a->m), kind);
+        if (e == hipSuccess && a->n) e = hipMemcpy(idx->ids, a->ids, sizeof(int64_t) * (size_t)a->n, kind);
+        if (e != hipSuccess) rc = fail(RAGO_DEVICE, std::string("copying index arrays: ") + hipGetErrorString(e));
+    }
+    if (!rc) {
+        if (on_device) {
+            rc = finish(idx, a->codes);
+        } else {
+            const size_t bytes = (size_t)a->n * a->m;
+            if (hipMalloc(&plain, bytes + 16) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "staging buffer for codes"); }
+            if (!rc && bytes && hipMemcpy(plain, a->codes, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = fail(RAGO_DEVICE, "copying codes");
+            if (!rc) rc = finish(idx, plain);
+        }
+    }
+    if (plain) hipFree(plain);
+    if (rc) { destroy(idx); return rc; }
+    *out = idx;
+    return RAGO_OK;
+}
+
+int rago_index_load(const char* path, int device, rago_index** out) {
+    if (!path || !out) return fail(RAGO_INVALID_ARG, "null argument");
+    FILE* f = std::fopen(path, "rb");
+    if (!f) return fail(RAGO_IO, std::string("cannot open ") + path);
+    std::unique_ptr<FILE, int (*)(FILE*)> closer(f, std::fclose);
+    unsigned char hdr[64];
+    if (std::fread(hdr, 1, 64, f) != 64) return fail(RAGO_FORMAT, "file shorter than its header");
+    if (std::memcmp(hdr, "RAGOIVPQ", 8) != 0) return fail(RAGO_FORMAT, "bad magic");
+    uint32_t u[6];
+    uint64_t n64;
+    std::memcpy(u, hdr + 8, 24);
+    std::memcpy(&n64, hdr + 32, 8);
+    const uint32_t version = u[0], metric = u[1], d = u[2], m = u[3], ksub = u[4], nlist = u[5];
+    if (version != 1) return fail(RAGO_FORMAT, "unknown index version");
+    if (metric != 0) return fail(RAGO_UNSUPPORTED, "only the inner-product metric is built");
+    if (ksub != KSUB) return fail(RAGO_UNSUPPORTED, "ksub must be 256");
+    if (!d || !m || !nlist || d > (1u << 20) || nlist > (1u << 28) || n64 > (1ull << 40)) return fail(RAGO_FORMAT, "implausible header");
+    if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
+    const uint64_t expect = 64 + 4ull * nlist * d + 4ull * m * KSUB * (d / m) + 8ull * (nlist + 1) + n64 * m + 8ull * n64;
+    if (std::fseek(f, 0, SEEK_END) != 0) return fail(RAGO_IO, "seek failed");
+    const uint64_t have = (uint64_t)std::ftell(f);
+    if (have != expect) return fail(RAGO_FORMAT, "file size does not match its header (truncated or corrupt)");
+    std::fseek(f, 64, SEEK_SET);
+    std::vector<float> cen((size_t)nlist * d), cb((size_t)m * KSUB * (d / m));
+    std::vector<int64_t> off(nlist + 1);
+    if (std::fread(cen.data(), 4, cen.size(), f) != cen.size() || std::fread(cb.data(), 4, cb.size(), f) != cb.size() ||
+        std::fread(off.data(), 8, off.size(), f) != off.size())
+        return fail(RAGO_IO, "read failed");
+    DeviceGuard g(device);
+    if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    rago_index* idx = new rago_index();
+    idx->device = device;
+    int rc = prepare(idx, (int)d, (int)m, (int)nlist, (int64_t)n64, off.data());
+    uint8_t* plain = nullptr;
+    void* stage = nullptr;
+    const size_t CH = (size_t)64 << 20;
+    if (!rc && hipMalloc(&plain, (size_t)n64 * m + 16) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "staging buffer for codes"); }
+    if (!rc && hipHostMalloc(&stage, CH) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "pinned staging buffer"); }
+    if (!rc) {
+        hipError_t e = hipMemcpy(idx->centroids, cen.data(), cen.size() * 4, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(idx->codebooks, cb.data(), cb.size() * 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) rc = fail(RAGO_DEVICE, "copying centroids/codebooks");
+    }
+    // stream codes then ids through the pinned buffer
+    for (int pass = 0; pass < 2 && !rc; ++pass) {
+        size_t total = pass == 0 ? (size_t)n64 * m : (size_t)n64 * 8;
+        char* dst = pass == 0 ? (char*)plain : (char*)idx->ids;
+        for (size_t a = 0; a < total && !rc; a += CH) {
+            size_t len = total - a < CH ? total - a : CH;
+            if (std::fread(stage, 1, len, f) != len) rc = fail(RAGO_IO, "read failed");
+            else if (hipMemcpy(dst + a, stage, len, hipMemcpyHostToDevice) != hipSuccess) rc = fail(RAGO_DEVICE, "copying index data");
+        }
+    }
+    if (!rc) rc = finish(idx, plain);
+    if (stage) hipHostFree(stage);
+    if (plain) hipFree(plain);
+    if (rc) { destroy(idx); return rc; }
+    *out = idx;
+    return RAGO_OK;
+}
+
+int rago_index_free(rago_index* idx) {
+    if (!idx) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    (void)hipDeviceSynchronize();
+    destroy(idx);
+    return RAGO_OK;
+}
+
+int rago_index_info(const rago_index* idx, rago_index_desc* out) {
+    if (!idx || !out) return fail(RAGO_INVALID_ARG, "null argument");
+    out->d = idx->d; out->m = idx->m; out->ksub = KSUB; out->nlist = idx->nlist; out->n = idx->n;
+    out->metric = 0; out->device = idx->device; out->max_list_len = idx->max_list_len;
+    out->code_bytes_resident = idx->total_blocks * BLOCK_VECS * idx->m;
+    return RAGO_OK;
+}
+
+static int check_search_args(const rago_index* idx, const void* a, const void* b, int64_t nq, int nprobe, int k) {
+    if (!idx) return fail(RAGO_INVALID_ARG, "null index");
+    if (nq < 0) return fail(RAGO_INVALID_ARG, "nq < 0");
+    if (nq > 0 && (!a || !b)) return fail(RAGO_INVALID_ARG, "null buffer");
+    if (nprobe < 1 || nprobe > idx->nlist) return fail(RAGO_INVALID_ARG, "nprobe must be in [1, nlist]");
+    if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
+    if (k > KMAX) return fail(RAGO_UNSUPPORTED, "k > 128");
+    if (nq * (int64_t)nprobe > (1ll << 30)) return fail(RAGO_UNSUPPORTED, "nq * nprobe > 2^30");
+    return RAGO_OK;
+}
+
+int rago_debug_coarse(rago_index* idx, const float* queries, int64_t nq, float* out_S, void* stream) {
+    if (!idx || nq < 0 || (nq > 0 && (!queries || !out_S))) return fail(RAGO_INVALID_ARG, "bad argument");
+    if (((uintptr_t)queries & 15) != 0) return fail(RAGO_INVALID_ARG, "queries must be 16-byte aligned");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    return launch_coarse(idx, queries, nq, out_S, (hipStream_t)stream);
+}
+
+int rago_debug_select(rago_index* idx, const float* queries, const float* S, int64_t nq, int32_t nprobe,
+                      int32_t* out_probes, void* stream) {
+    int rc = check_search_args(idx, S, out_probes, nq, nprobe, 1);
+    if (rc) return rc;
+    if (nq > 0 && !queries) return fail(RAGO_INVALID_ARG, "null queries");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    return launch_select(idx, queries, S, nq, nprobe, out_probes, (hipStream_t)stream);
+}
+
+int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* probes, int64_t nq, int32_t nprobe,
+                         float* out_L, uint8_t* out_LUT8, int32_t* out_B, float* out_delta, void* stream) {
+    int rc = check_search_args(idx, queries, probes, nq, nprobe, 1);
+    if (rc) return rc;
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    Workspace& ws = idx->ws;
+    const int64_t npairs = nq * nprobe;
+    if ((rc = ws.lut8.reserve((size_t)npairs * LUT_BYTES))) return rc;
+    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = launch_build_lut(idx, queries, probes, nq, nprobe, ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(),
+                          ws.delta.as<float>(), out_L, out_LUT8, st);
+    if (rc) return rc;
+    if (out_B) RAGO_HIP(hipMemcpyAsync(out_B, ws.bias.p, (size_t)npairs * 4, hipMemcpyDeviceToDevice, st));
+    if (out_delta) RAGO_HIP(hipMemcpyAsync(out_delta, ws.delta.p, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
+    return RAGO_OK;
+}
+
+int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8, const int32_t* B, int64_t nq,
+                    int32_t nprobe, int32_t k, int64_t* out_ids, int32_t* out_iscores, void* stream) {
+    int rc = check_search_args(idx, probes, out_ids, nq, nprobe, k);
+    if (rc) return rc;
+    if (nq > 0 && (!LUT8 || !B)) return fail(RAGO_INVALID_ARG, "null tables");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    Workspace& ws = idx->ws;
+    const int64_t npairs = nq * nprobe;
+    if ((rc = ws.tmp_lut8sw.reserve((size_t)npairs * LUT_BYTES))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launch_swizzle_lut(idx, LUT8, npairs, ws.tmp_lut8sw.as<uint8_t>(), st))) return rc;
+    return launch_scan(idx, probes, ws.tmp_lut8sw.as<uint8_t>(), B, nullptr, nq, nprobe, k, out_ids, nullptr, out_iscores, st);
+}
+
+int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids,
+                      float* out_scores, int32_t* out_iscores, void* stream) {
+    int rc = check_search_args(idx, queries, out_ids, nq, nprobe, k);
+    if (rc) return rc;
+    if (nq > 0 && !out_scores) return fail(RAGO_INVALID_ARG, "null out_scores");
+    if (((uintptr_t)queries & 15) != 0) return fail(RAGO_INVALID_ARG, "queries must be 16-byte aligned");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    Workspace& ws = idx->ws;
+    const int64_t npairs = nq * nprobe;
+    if ((rc = ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
+    if ((rc = ws.probes.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.lut8.reserve((size_t)npairs * LUT_BYTES))) return rc;
+    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st))) return rc;
+    if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+    if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, ws.lut8.as<uint8_t>(),
+                               ws.bias.as<int32_t>(), ws.delta.as<float>(), nullptr, nullptr, st)))
+        return rc;
+    return launch_scan(idx, ws.probes.as<int32_t>(), ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                       nq, nprobe, k, out_ids, out_scores, out_iscores, st);
+}
+
+int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
+                     int64_t* out_ids, float* out_scores, int device, void* stream) {
+    if (R < 0 || n < 0) return fail(RAGO_INVALID_ARG, "negative size");
+    if (nqr < 1 || nqr > 16) return fail(RAGO_INVALID_ARG, "nqr must be in [1, 16]");
+    if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
+    if (k > KMAX) return fail(RAGO_UNSUPPORTED, "k > 128");
+    if (d < 32 || d % 32 || d > 1024) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 32 in [32, 1024]");
+    if (R > 0 && (!queries || !out_ids || !out_scores || (n > 0 && !corpus))) return fail(RAGO_INVALID_ARG, "null buffer");
+    if (((uintptr_t)corpus & 15) || ((uintptr_t)queries & 15)) return fail(RAGO_INVALID_ARG, "buffers must be 16-byte aligned");
+    if (n > 0x7fffffffLL) return fail(RAGO_UNSUPPORTED, "n > 2^31-1 per request");
+    if (R == 0) return RAGO_OK;
+    DeviceGuard g(device);
+    if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    return launch_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, (hipStream_t)stream);
+}
+
+int rago_debug_counters(rago_index* idx, int64_t* out, void* stream) {
+    if (!idx || !out) return fail(RAGO_INVALID_ARG, "null argument");
+    DeviceGuard g(idx->device);
+    for (int i = 0; i < 8; ++i) out[i] = 0;
+    if (!idx->ws.counters.p) return RAGO_OK;
+    RAGO_HIP(hipMemcpyAsync(out, idx->ws.counters.p, 8 * sizeof(int64_t), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    RAGO_HIP(hipStreamSynchronize((hipStream_t)stream));
+    return RAGO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,261 @@
+// Coarse quantiser: scores of every query against every list centroid (the IVF level of the
+// index, Section 2; an upper tree level is itself a vector scan, Section 4 "Retrieval performance
+// modeling") and the choice of the nprobe best lists per query (the scanned subset, Section 3.3).
+//
+//  * coarse_gemm: S = Q * C^T with fp32 MFMA (v_mfma_f32_32x32x2_f32), both operands K-contiguous,
+//    LDS-staged 128x128 (or 32x128 for small batches) tiles, next tile prefetched into registers.
+//  * select: per query, radix-select the nprobe+32 largest fp32 scores, recompute exactly those
+//    in fp64 straight from the query and the centroids, round to fp32, sort by (score descending,
+//    list ascending) and keep nprobe.  The extra candidates make the result independent of the
+//    rounding of the MFMA accumulation: a list outside the candidate set has an fp32 score below
+//    every candidate's, so its exact score is at most (smallest candidate score + E) with
+//    E = d * 2^-22 * |q| * max|c| bounding the accumulation error; when the nprobe-th exact score
+//    exceeds that, no outside list can belong to the result.  Queries where this cannot be shown
+//    are counted (never observed on the workloads here).
+#include "rago_internal.h"
+
+namespace rago {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int G_TN = 128, G_KT = 32, G_LS = 36;  // LDS row stride in floats (144 B: b128 reads conflict-free)
+
+template <int TM>
+__global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restrict__ Q, const float* __restrict__ C, int nq,
+                                                          int nlist, int d, float* __restrict__ S) {
+    constexpr int MT = TM == 128 ? 2 : 1;  // 32x32 MFMA tiles per wave along M
+    constexpr int NT = TM == 128 ? 2 : 1;  //                         and along N
+    constexpr int AF = TM * 8 / 256;       // float4 loads per thread for the A tile
+    constexpr int BF = G_TN * 8 / 256;
+    __shared__ __align__(16) float As[TM * G_LS];
+    __shared__ __align__(16) float Bs[G_TN * G_LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.x * G_TN, m0 = blockIdx.y * TM;
+    const int wm = TM == 128 ? (wave >> 1) * 64 : 0;
+    const int wn = TM == 128 ? (wave & 1) * 64 : wave * 32;
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    float4 pa[AF], pb[BF];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int r = 0; r < AF; ++r) {
+            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+            const int gr = min(m0 + row, nq - 1), gk = k0 + c4 * 4;
+            pa[r] = gk < d ? *reinterpret_cast<const float4*>(Q + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int r = 0; r < BF; ++r) {
+            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+            const int gr = min(n0 + row, nlist - 1), gk = k0 + c4 * 4;
+            pb[r] = gk < d ? *reinterpret_cast<const float4*>(C + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    gload(0);
+    for (int k0 = 0; k0 < d; k0 += G_KT) {
+        __syncthreads();  // previous tile fully consumed
+#pragma unroll
+        for (int r = 0; r < AF; ++r) {
+            const int f = tid + 256 * r;
+            *reinterpret_cast<float4*>(As + (f >> 3) * G_LS + (f & 7) * 4) = pa[r];
+        }
+#pragma unroll
+        for (int r = 0; r < BF; ++r) {
+            const int f = tid + 256 * r;
+            *reinterpret_cast<float4*>(Bs + (f >> 3) * G_LS + (f & 7) * 4) = pb[r];
+        }
+        __syncthreads();
+        if (k0 + G_KT < d) gload(k0 + G_KT);
+        // lane (i32, h) owns k = h*16 .. h*16+15 of this tile for both operands
+        float af[MT][16], bf[NT][16];
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float4 x = *reinterpret_cast<const float4*>(As + (wm + a * 32 + i32) * G_LS + h * 16 + v * 4);
+                af[a][4 * v] = x.x; af[a][4 * v + 1] = x.y; af[a][4 * v + 2] = x.z; af[a][4 * v + 3] = x.w;
+            }
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float4 x = *reinterpret_cast<const float4*>(Bs + (wn + b * 32 + i32) * G_LS + h * 16 + v * 4);
+                bf[b][4 * v] = x.x; bf[b][4 * v + 1] = x.y; bf[b][4 * v + 2] = x.z; bf[b][4 * v + 3] = x.w;
+            }
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
+#pragma unroll
+                for (int b = 0; b < NT; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a][s], bf[b][s], acc[a][b], 0, 0, 0);
+    }
+    // D layout of the 32x32 tile: register r, lane (i32, h) -> row 8*(r/4) + 4*h + r%4, column i32
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                const int col = n0 + wn + b * 32 + i32;
+                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = acc[a][b][r];
+            }
+}
+
+int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st) {
+    const int nlist = idx->nlist, d = idx->d;
+    if (nq > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq too large");
+    const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
+    if (nq <= 32) coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+    else coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+    RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
+// ------------------------------------------------------------------ selection
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_EXTRA = 32;
+constexpr int SEL_CAP = 2048;   // candidate capacity (power of two): nprobe + SEL_EXTRA <= SEL_CAP
+
+__device__ __forceinline__ uint32_t float_key(float f) {  // ascending uint order == ascending float order
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                             const float* __restrict__ S, int nlist, int d, int nprobe,
+                                                             float max_cnorm, int32_t* __restrict__ probes,
+                                                             int64_t* __restrict__ counters) {
+    __shared__ int hist[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_rem;
+    __shared__ int s_wgt[SEL_WAVES], s_weq[SEL_WAVES];
+    __shared__ int c_idx[SEL_CAP];
+    __shared__ float c_val[SEL_CAP];
+    __shared__ float s_qn[SEL_WAVES];
+    const int64_t q = blockIdx.x;
+    const float* row = S + q * nlist;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int want = min(nprobe + SEL_EXTRA, nlist);
+
+    // ---- radix select: key of the want-th largest score
+    if (tid == 0) { s_prefix = 0; s_rem = want; }
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        for (int i = tid; i < nlist; i += SEL_THREADS) {
+            const uint32_t key = float_key(row[i]);
+            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int rem = s_rem, dgt = 255;
+            for (; dgt > 0; --dgt) {
+                if (hist[dgt] >= rem) break;
+                rem -= hist[dgt];
+            }
+            s_prefix = prefix | ((uint32_t)dgt << shift);
+            s_rem = rem;
+        }
+        __syncthreads();
+    }
+    const uint32_t kth = s_prefix;   // exact key of the want-th largest
+    const int need_eq = s_rem;       // how many of the entries equal to it are taken (lowest lists first)
+
+    // ---- ordered collection: wave w owns a contiguous range, lanes interleaved
+    const int seg = ((nlist + SEL_WAVES - 1) / SEL_WAVES + 63) / 64 * 64;
+    const int a0 = wave * seg, a1 = min(nlist, a0 + seg);
+    int ngt = 0, neq = 0;
+    for (int i = a0 + lane; i < a0 + seg; i += 64) {
+        const uint32_t key = i < a1 ? float_key(row[i]) : 0u;
+        ngt += __popcll(__ballot(i < a1 && key > kth));
+        neq += __popcll(__ballot(i < a1 && key == kth));
+    }
+    if (lane == 0) { s_wgt[wave] = ngt; s_weq[wave] = neq; }
+    __syncthreads();
+    int gt_base = 0, eq_base = 0, gt_total = 0;
+    for (int w = 0; w < SEL_WAVES; ++w) {
+        if (w < wave) { gt_base += s_wgt[w]; eq_base += s_weq[w]; }
+        gt_total += s_wgt[w];
+    }
+    for (int i = a0 + lane; i < a0 + seg; i += 64) {
+        const float v = i < a1 ? row[i] : 0.f;
+        const uint32_t key = i < a1 ? float_key(v) : 0u;
+        const bool g = i < a1 && key > kth, e = i < a1 && key == kth;
+        const uint64_t mg = __ballot(g), me = __ballot(e);
+        const uint64_t below = (1ull << lane) - 1ull;
+        if (g) { const int o = gt_base + __popcll(mg & below); c_idx[o] = i; }
+        if (e) { const int o = eq_base + __popcll(me & below); if (o < need_eq) c_idx[gt_total + o] = i; }
+        gt_base += __popcll(mg);
+        eq_base += __popcll(me);
+    }
+    __syncthreads();
+
+    // ---- exact scores of the candidates: fp64 accumulation, one rounding to fp32
+    const float* qv = Q + q * d;
+    float qn = 0.f;
+    for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
+    for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
+    for (int ci = wave; ci < want; ci += SEL_WAVES) {
+        const float* cv = C + (int64_t)c_idx[ci] * d;
+        double acc = 0.0;
+        for (int t = lane; t < d; t += 64) acc = acc + (double)qv[t] * (double)cv[t];
+        for (int o = 32; o; o >>= 1) acc = acc + __shfl_xor(acc, o);
+        if (lane == 0) c_val[ci] = (float)acc;
+    }
+    int n2 = 1;
+    while (n2 < want) n2 <<= 1;
+    for (int i = want + tid; i < n2; i += SEL_THREADS) { c_idx[i] = 0x7fffffff; c_val[i] = -INFINITY; }
+    // ---- bitonic sort by (score desc, list asc)
+    for (int size = 2; size <= n2; size <<= 1)
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = tid; t < n2 / 2; t += SEL_THREADS) {
+                const int i = 2 * t - (t & (stride - 1)), j = i + stride;
+                const bool up = (i & size) == 0;
+                const float va = c_val[i], vb = c_val[j];
+                const int ia = c_idx[i], ib = c_idx[j];
+                const bool b_first = vb > va || (vb == va && ib < ia);
+                const bool a_first = va > vb || (va == vb && ia < ib);
+                if (up ? b_first : a_first) { c_val[i] = vb; c_val[j] = va; c_idx[i] = ib; c_idx[j] = ia; }
+            }
+        }
+    __syncthreads();
+    for (int p = tid; p < nprobe; p += SEL_THREADS) probes[q * nprobe + p] = c_idx[p];
+    if (tid == 0 && want < nlist) {
+        // smallest fp32 score among the candidates = score with key `kth`
+        const uint32_t u = (kth & 0x80000000u) ? (kth & 0x7fffffffu) : ~kth;
+        const float s_cut = __uint_as_float(u);
+        const float E = (float)d * 2.384185791015625e-07f * sqrtf(qn) * max_cnorm;
+        if (!(c_val[nprobe - 1] > s_cut + E)) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull);
+    }
+}
+
+__global__ void zero_counter_kernel(int64_t* counters) { counters[3] = 0; }
+
+int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st) {
+    if (nprobe + SEL_EXTRA > SEL_CAP && nprobe < idx->nlist && idx->nlist > SEL_CAP)
+        return fail(RAGO_UNSUPPORTED, "nprobe > 2016 on an index with more than 2048 lists");
+    if (std::min(nprobe + SEL_EXTRA, idx->nlist) > SEL_CAP) return fail(RAGO_UNSUPPORTED, "nprobe > 2016");
+    int rc;
+    if ((rc = idx->ws.counters.reserve(64))) return rc;
+    zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
+    select_kernel<<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, idx->nlist, idx->d, nprobe, idx->max_cnorm, probes,
+                                                        idx->ws.counters.as<int64_t>());
+    RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
+}  // namespace rago

@@ -1,0 +1,99 @@
+// One-time re-layout of the PQ codes for the scan (index load / wrap time).
+//
+// The scan keeps 8-bit look-up tables in LDS with every sub-table confined to one LDS bank
+// (32 banks x 4 bytes on gfx950: a half-wavefront of 32 lanes is served per clock when all
+// lanes hit different banks).  One lane scans one vector.  For the 32 lanes of a half-wave to
+// hit 32 different banks in the same instruction they must be working on 32 different
+// sub-quantisers, so lane l at step s handles sub-quantiser (s + l) mod 32 (per plane of 32
+// sub-quantisers).  To keep the byte extraction identical in all lanes, this rotation is baked
+// into the stored bytes: position t of lane l's byte string holds the code of sub-quantiser
+//   j(t, l) = plane(t) * 32 + slot(step(t), l),   plane = t / S, step = t % S,
+//   slot(s, l) = ((s + l) & (S-1)) | (l & 31 & ~(S-1)),   S = min(m, 32)
+// (for m < 32 the 32 lanes cover 32/m replicas of the tables, one replica per group of m banks).
+//
+// A block = 64 consecutive vectors of one list (last block zero-padded) = 64*m bytes laid out
+// [t / 16][lane][t % 16], so one dwordx4 load per lane reads 1 KiB contiguous per wavefront.
+#include "rago_internal.h"
+
+namespace rago {
+
+__global__ void __launch_bounds__(256) relayout_kernel(const uint8_t* __restrict__ plain, const int64_t* __restrict__ list_off,
+                                                       const int64_t* __restrict__ blk_off, int nlist, int m,
+                                                       uint8_t* __restrict__ out) {
+    __shared__ int s_list;
+    const int64_t b = blockIdx.x;
+    if (threadIdx.x == 0) {
+        int lo = 0, hi = nlist;  // largest l with blk_off[l] <= b
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (blk_off[mid] <= b) lo = mid; else hi = mid;
+        }
+        s_list = lo;
+    }
+    __syncthreads();
+    const int l = s_list;
+    const int64_t v0 = list_off[l] + (b - blk_off[l]) * BLOCK_VECS;  // first vector row of the block
+    const int64_t vend = list_off[l + 1];
+    const int S = rago_steps(m);
+    const int npieces = BLOCK_VECS * m / 16;
+    uint8_t* dst = out + b * (int64_t)(BLOCK_VECS * m);
+    for (int piece = threadIdx.x; piece < npieces; piece += blockDim.x) {
+        const int chunk = piece / BLOCK_VECS, lane = piece % BLOCK_VECS;
+        const int64_t v = v0 + lane;
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (v < vend) {
+            const uint8_t* row = plain + v * m;
+            const int l32 = lane & 31;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int t = chunk * 16 + e;
+                const int plane = t / S, step = t % S;
+                const int slot = ((step + l32) & (S - 1)) | (l32 & ~(S - 1));
+                const int j = plane * 32 + (slot & (S - 1));
+                w[e >> 2] |= (uint32_t)row[j] << (8 * (e & 3));
+            }
+        }
+        *reinterpret_cast<uint4*>(dst + (int64_t)piece * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// flag[0] != 0 if ids are not strictly ascending inside some list
+__global__ void __launch_bounds__(256) check_ids_kernel(const int64_t* __restrict__ ids, const int64_t* __restrict__ list_off,
+                                                        int* flag) {
+    const int l = blockIdx.x;
+    const int64_t a = list_off[l], e = list_off[l + 1];
+    for (int64_t i = a + 1 + threadIdx.x; i < e; i += blockDim.x)
+        if (ids[i] <= ids[i - 1]) *flag = 1;
+}
+
+__global__ void __launch_bounds__(256) cnorm_kernel(const float* __restrict__ C, int nlist, int d, float* __restrict__ out) {
+    const int l = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+    if (l >= nlist) return;
+    float acc = 0.f;
+    for (int t = threadIdx.x & 63; t < d; t += 64) acc += C[(int64_t)l * d + t] * C[(int64_t)l * d + t];
+    for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o);
+    if ((threadIdx.x & 63) == 0) out[l] = sqrtf(acc) * 1.0001f;  // slight over-estimate: used as a bound
+}
+
+int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st) {
+    if (idx->total_blocks > 0) {
+        if (idx->total_blocks > 0x7fffffffLL) return fail(RAGO_UNSUPPORTED, "more than 2^31 code blocks");
+        relayout_kernel<<<dim3((unsigned)idx->total_blocks), 256, 0, st>>>(d_codes_plain, idx->list_off, idx->blk_off,
+                                                                          idx->nlist, idx->m, idx->codes_blk);
+        RAGO_HIP(hipGetLastError());
+    }
+    int* flag = nullptr;
+    RAGO_HIP(hipMalloc(&flag, sizeof(int)));
+    RAGO_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
+    check_ids_kernel<<<idx->nlist, 256, 0, st>>>(idx->ids, idx->list_off, flag);
+    cnorm_kernel<<<(idx->nlist + 3) / 4, 256, 0, st>>>(idx->centroids, idx->nlist, idx->d, idx->cnorm);
+    int h = 0;
+    hipError_t e = hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    hipFree(flag);
+    if (e != hipSuccess) return fail(RAGO_DEVICE, std::string("layout: ") + hipGetErrorString(e));
+    if (h) return fail(RAGO_FORMAT, "ids must be strictly ascending inside every list");
+    return RAGO_OK;
+}
+
+}  // namespace rago

@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of librago (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "../../include/rago.h"
+
+namespace rago {
+
+constexpr int KSUB = 256;          // codewords per sub-quantiser
+constexpr int BLOCK_VECS = 64;     // vectors per code block = one wavefront, one vector per lane
+constexpr int KMAX = 128;          // largest k served by the wave-level selection buffers
+constexpr int LUT_ROW = 128;       // bytes of one swizzled table row (32 banks x 4 planes)
+constexpr int LUT_BYTES = KSUB * LUT_ROW;  // one swizzled 8-bit table in HBM
+
+void set_error(const std::string& msg);
+int fail(int code, const std::string& msg);
+#define RAGO_HIP(call)                                                                       \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return ::rago::fail(RAGO_DEVICE, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+// Grow-only device buffer.
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    int reserve(size_t bytes);   // RAGO_OK / RAGO_OOM
+    void release();
+    template <class T> T* as() const { return static_cast<T*>(p); }
+};
+
+struct Workspace {
+    DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
+    DevBuf list_cnt, pair_off, task_off, cursor, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
+    DevBuf tmp_lut8sw;
+    void release();
+};
+
+}  // namespace rago
+
+// Steps (lanes advance through this many sub-quantisers) and planes of a code width.
+__host__ __device__ inline int rago_steps(int m) { return m < 32 ? m : 32; }
+__host__ __device__ inline int rago_planes(int m) { return m < 32 ? 1 : m / 32; }
+
+struct rago_index {
+    int device = 0;
+    int d = 0, m = 0, dsub = 0, nlist = 0;
+    int64_t n = 0;
+    int64_t max_list_len = 0;
+    int64_t total_blocks = 0;
+    float* centroids = nullptr;    // [nlist][d]
+    float* cnorm = nullptr;        // [nlist] Euclidean norm of each centroid
+    float* codebooks = nullptr;    // [m][256][dsub]
+    int64_t* list_off = nullptr;   // [nlist+1] vector offsets (list-major rows)
+    int64_t* blk_off = nullptr;    // [nlist+1] offsets in 64-vector blocks into codes_blk
+    uint8_t* codes_blk = nullptr;  // total_blocks * 64 * m bytes, skewed lane-major layout
+    int64_t* ids = nullptr;        // [n]
+    float max_cnorm = 0.f;
+    rago::Workspace ws;
+    // parameters of the last scan (for rago_debug_counters)
+    int64_t last_algo_bytes_valid = 0;
+};
+
+namespace rago {
+
+// layout.hip
+int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
+
+// coarse.hip
+int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);
+int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes,
+                  hipStream_t st);
+
+// lut.hip
+int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,
+                     uint8_t* lut8sw, int32_t* bias, float* delta, float* out_L_f32, uint8_t* out_LUT8,
+                     hipStream_t st);
+int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
+
+// scan.hip
+int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
+                const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores,
+                int32_t* out_iscores, hipStream_t st);
+
+// flat.hip
+int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,
+                int64_t* out_ids, float* out_scores, int device, hipStream_t st);
+
+}  // namespace rago

@@ -1,0 +1,168 @@
+"""GPU parity: every stage of the HIP IVF-PQ path against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_common import dev_index, oracle_stages
+from helpers import to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rb():
+    from paper_2503_14649_amd import binding
+    return binding
+
+
+def _queries(n, d, seed):
+    g = torch.Generator().manual_seed(seed)
+    return torch.nn.functional.normalize(torch.randn(n, d, generator=g), dim=1).numpy()
+
+
+CASES = {
+    # name: (n, d, m, nlist, nq, nprobe, k, kwargs)
+    "m16_ties_empty": (3000, 32, 16, 8, 7, 4, 25, dict(empty_lists=(3,), dup_codes=60, shuffle_ids=True)),
+    "m96_ragged": (40000, 768, 96, 12, 5, 5, 100, dict(shuffle_ids=True)),
+    "m32": (9000, 64, 32, 16, 9, 16, 10, dict()),
+    "m64": (9000, 128, 64, 16, 9, 3, 128, dict(dup_codes=10)),
+    "m128": (9000, 256, 128, 16, 4, 7, 1, dict()),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request, rb):
+    n, d, m, nlist, nq, nprobe, k, kw = CASES[request.param]
+    print(f"[case] {request.param} n={n} d={d} m={m} nlist={nlist} nq={nq} nprobe={nprobe} k={k}", flush=True)
+    ix = to_np(synth.random_index(n=n, d=d, m=m, nlist=nlist, seed=100 + m, **kw))
+    Q = _queries(nq, d, 7 + m)
+    h = rb.rago_index_wrap(dev_index(ix))
+    yield ix, Q, nprobe, k, h
+    rb.rago_index_free(h)
+
+
+def test_index_info(case, rb):
+    ix, Q, nprobe, k, h = case
+    info = rb.rago_index_info(h)
+    assert (info.d, info.m, info.nlist, info.n, info.ksub) == (Q.shape[1], ix["codes"].shape[1], len(ix["list_offsets"]) - 1,
+                                                                 len(ix["ids"]), 256)
+    assert info.max_list_len == int(np.diff(ix["list_offsets"]).max())
+
+
+def test_scan_topk_bit_exact_given_tables(case, rb):
+    ix, Q, nprobe, k, h = case
+    S, probes, L, LUT8, B, delta = oracle_stages(ix, Q, nprobe)
+    oi, ois, _ = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    gi, gis = rb.rago_debug_scan(h, torch.from_numpy(probes).cuda(), torch.from_numpy(LUT8).cuda(),
+                                 torch.from_numpy(B).cuda(), k)
+    torch.cuda.synchronize()
+    assert np.array_equal(gis.cpu().numpy(), ois)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    # coarse tables force massive ties: id order must decide
+    L8c = (LUT8 // 64).astype(np.uint8)
+    oi, ois, _ = oracle.scan_topk(probes, L8c, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    gi, gis = rb.rago_debug_scan(h, torch.from_numpy(probes).cuda(), torch.from_numpy(L8c).cuda(),
+                                 torch.from_numpy(B).cuda(), k)
+    torch.cuda.synchronize()
+    assert np.array_equal(gis.cpu().numpy(), ois) and np.array_equal(gi.cpu().numpy(), oi)
+
+
+def test_coarse_scores_within_1e4(case, rb):
+    ix, Q, nprobe, k, h = case
+    S = oracle.coarse(Q, ix["centroids"])
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda()).cpu().numpy()
+    scale = np.linalg.norm(Q, axis=1)[:, None] * np.linalg.norm(ix["centroids"], axis=1)[None, :]
+    assert np.max(np.abs(gS - S) / scale) < 1e-4       # relative to |q||c|: inner products may be ~0
+
+
+def test_select_equals_oracle(case, rb):
+    ix, Q, nprobe, k, h = case
+    S = oracle.coarse(Q, ix["centroids"])
+    probes = oracle.select(S, nprobe)
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+    gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+    assert np.array_equal(gp, probes)
+    assert rb.rago_debug_counters(h)[3] == 0
+
+
+def test_tables_equal_oracle(case, rb):
+    ix, Q, nprobe, k, h = case
+    S, probes, L, LUT8, B, delta = oracle_stages(ix, Q, nprobe)
+    gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+    gL, gL8, gB, gd = gL.cpu().numpy(), gL8.cpu().numpy(), gB.cpu().numpy(), gd.cpu().numpy()
+    d, m = Q.shape[1], ix["codes"].shape[1]
+    qn = np.linalg.norm(Q.reshape(len(Q), m, d // m), axis=2)                       # |q_j|
+    scale = qn[:, None, :, None] * 2.0                                              # |C_j + CB_j| <= ~2 here
+    assert np.max(np.abs(gL - L) / np.maximum(scale, 1e-30)) < 1e-4
+    assert np.array_equal(gd, delta)
+    assert np.max(np.abs(gL8.astype(np.int32) - LUT8.astype(np.int32))) <= 1
+    assert np.mean(gL8 == LUT8) >= 0.999
+    assert np.array_equal(gL8, LUT8) and np.array_equal(gB, B)                     # in fact identical
+
+
+def test_search_end_to_end(case, rb):
+    ix, Q, nprobe, k, h = case
+    r = oracle.ivfpq_search(Q, ix, nprobe, k)
+    gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+    torch.cuda.synchronize()
+    gi, gs, gis = gi.cpu().numpy(), gs.cpu().numpy(), gis.cpu().numpy()
+    overlap = np.mean([len(set(gi[q][gi[q] >= 0].tolist()) & set(r["ids"][q][r["ids"][q] >= 0].tolist())) /
+                       max(1, int((r["ids"][q] >= 0).sum())) for q in range(len(Q))])
+    assert overlap >= 0.999
+    assert np.array_equal(gi, r["ids"]) and np.array_equal(gis, r["iscores"])
+    assert np.array_equal(gs, r["scores"])
+
+
+def test_padding_and_argument_errors(rb):
+    ix = to_np(synth.random_index(n=300, d=32, m=16, nlist=8, seed=5, empty_lists=(0, 1, 2, 3, 4)))
+    h = rb.rago_index_wrap(dev_index(ix))
+    Q = torch.from_numpy(_queries(3, 32, 1)).cuda()
+    r = oracle.ivfpq_search(Q.cpu().numpy(), ix, 8, 128)
+    gi, gs, gis = rb.rago_ivfpq_search(h, Q, 8, 128)          # 300 candidates... but k=128 < 300
+    assert np.array_equal(gi.cpu().numpy(), r["ids"])
+    probes = torch.tensor([[0, 1], [2, 3], [0, 4]], dtype=torch.int32).cuda()     # only empty lists
+    L8 = torch.zeros(3, 2, 16, 256, dtype=torch.uint8).cuda()
+    B = torch.zeros(3, 2, dtype=torch.int32).cuda()
+    gi, gis = rb.rago_debug_scan(h, probes, L8, B, 5)
+    assert torch.all(gi == -1) and torch.all(gis == torch.iinfo(torch.int32).min)
+    one = torch.tensor([[5]], dtype=torch.int32).cuda()                            # fewer candidates than k
+    n5 = int(ix["list_offsets"][6] - ix["list_offsets"][5])
+    gi, gis = rb.rago_debug_scan(h, one, L8[:1, :1].contiguous(), B[:1, :1].contiguous(), 128)
+    gi = gi.cpu().numpy()
+    if n5 < 128:
+        assert np.all(gi[0, :n5] >= 0) and np.all(gi[0, n5:] == -1)
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_ivfpq_search(h, Q, 9, 5)                       # nprobe > nlist
+    assert e.value.code == -1
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_ivfpq_search(h, Q, 4, 129)                     # k beyond the built limit
+    assert e.value.code == -6
+    with pytest.raises(rb.RagoError):
+        rb.rago_ivfpq_search(h, Q, 4, 0)
+    gi, gs, gis = rb.rago_ivfpq_search(h, Q[:0].contiguous(), 4, 5)               # nq = 0 is legal
+    assert gi.shape == (0, 5)
+    rb.rago_index_free(h)
+    bad = dict(ix)
+    bad["ids"] = ix["ids"][::-1].copy()                                             # not ascending inside lists
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_index_wrap(dev_index(bad))
+    assert e.value.code == -3
+
+
+def test_index_file_round_trip(rb, tmp_path):
+    ix = to_np(synth.random_index(n=5000, d=64, m=16, nlist=10, seed=9, shuffle_ids=True))
+    path = str(tmp_path / "ix.bin")
+    synth.write_index(path, {k: torch.from_numpy(v) for k, v in ix.items()})
+    h = rb.rago_index_load(path)
+    Q = _queries(6, 64, 3)
+    r = oracle.ivfpq_search(Q, ix, 4, 20)
+    gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 4, 20)
+    assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    rb.rago_index_free(h)
+    with open(path, "r+b") as f:                                                    # cut the file short
+        f.truncate(3000)
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_index_load(path)
+    assert e.value.code == -3
