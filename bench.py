@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X retrieval library on synthetic workloads of the paper's shapes.
+
+Default: the hyperscale shard (1e9 vectors x 96-byte PQ codes, nlist 65536; 1024 queries,
+nprobe 128, k 100).  One step = one whole rago_ivfpq_search call (coarse GEMM, list selection,
+table build, ADC scan, top-k merge) over the query batch, inputs resident in HBM.
+
+Prints ONE JSON line (see README/DESIGN): whole-job queries/s, the scan kernel's roofline
+figures measured live with HIP events inside the library, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def scaled_cfg(cfg, f):
+    if f == 1.0:
+        return cfg
+    import synth  # noqa: F401
+    return cfg.scaled(n=max(10000, int(cfg.n * f)), nlist=max(64, int(cfg.nlist * f)),
+                      components=max(16, int(cfg.components * f)), train_n=max(20000, int(cfg.train_n * f)))
+
+
+def read_traffic(workload):
+    """HBM bytes per scan-kernel launch from the committed rocprofv3 --pmc summary, if present."""
+    p = os.path.join(ROOT, "profiles", f"scan_m96_{workload}_pmc.txt")
+    if not os.path.exists(p):
+        return None
+    vals = {}
+    for line in open(p):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.strip().split()[0])
+            except ValueError:
+                pass
+    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    return None
+
+
+def host_subindex(index, probes_np):
+    """Plain index on the host holding only the lists in `probes_np` (others empty)."""
+    import numpy as np
+    import torch
+    off = index["list_offsets"].cpu().numpy()
+    nlist = len(off) - 1
+    lists = np.unique(probes_np)
+    lens = np.zeros(nlist, np.int64)
+    lens[lists] = off[lists + 1] - off[lists]
+    new_off = np.zeros(nlist + 1, np.int64)
+    new_off[1:] = np.cumsum(lens)
+    m = index["codes"].shape[1]
+    codes = np.empty((int(new_off[-1]), m), np.uint8)
+    ids = np.empty(int(new_off[-1]), np.int64)
+    for l in lists:
+        a, b = int(off[l]), int(off[l + 1])
+        codes[new_off[l]:new_off[l + 1]] = index["codes"][a:b].cpu().numpy()
+        ids[new_off[l]:new_off[l + 1]] = index["ids"][a:b].cpu().numpy()
+    return dict(centroids=index["centroids"].cpu().numpy(), codebooks=index["codebooks"].cpu().numpy(),
+                list_offsets=new_off, codes=codes, ids=ids)
+
+
+def run_ivfpq(args):
+    import numpy as np
+    import torch
+    import synth
+    from paper_2503_14649_amd import binding as rb
+
+    base = {"hyper": synth.HYPER, "mid": synth.MID, "tiny": synth.TINY, "iter": synth.HYPER}[args.workload]
+    cfg = scaled_cfg(base, args.scale)
+    dev = "cuda:0"
+    t0 = time.time()
+    last = [0.0]
+
+    def prog(b, n):
+        if time.time() - last[0] > 20:
+            last[0] = time.time()
+            log(f"generated {b / 1e6:.0f}M / {n / 1e6:.0f}M vectors ({time.time() - t0:.0f}s)")
+
+    log(f"building {cfg.name} index: n={cfg.n} d={cfg.d} m={cfg.m} nlist={cfg.nlist} on {dev}")
+    index = synth.build_index(cfg, device=dev, keep_vectors=False, progress=prog)
+    torch.cuda.synchronize()
+    lens = (index["list_offsets"][1:] - index["list_offsets"][:-1])
+    log(f"index built in {time.time() - t0:.0f}s; list length min/median/max = "
+        f"{int(lens.min())}/{int(lens.median())}/{int(lens.max())}")
+    nq, nprobe, k = cfg.nq, cfg.nprobe, cfg.k
+    if args.workload == "iter":
+        nprobe, k = synth.ITER_NPROBE, synth.ITER_K
+    Q = synth.make_queries(cfg, max(nq, 16), device=dev)
+
+    # ---- CPU-oracle sample (needs the plain codes, so fetch them before they are released)
+    cpu = None
+    sample_ref = None
+    ns = min(args.cpu_queries, nq) if args.cpu_queries > 0 else 0
+    if ns:
+        import oracle
+        Qs = Q[:ns].cpu().numpy()
+        cen = index["centroids"].cpu().numpy()
+        pr = oracle.select(oracle.coarse(Qs, cen), nprobe)
+        sub = host_subindex(index, pr)
+        log(f"oracle sample: {ns} queries, {sub['codes'].nbytes / 1e9:.2f} GB of codes on the host")
+        oracle.ivfpq_search(Qs[:1], sub, nprobe, k)                 # warm-up (library load, page-in)
+        t1 = time.time()
+        sample_ref = oracle.ivfpq_search(Qs, sub, nprobe, k)
+        dt = time.time() - t1
+        cpu = {"value": ns / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{ns} of {nq} queries on the full index (only the lists they probe copied to the host), "
+                         f"{dt:.2f}s wall, OpenMP over queries"}
+        log(f"oracle: {ns / dt:.2f} queries/s on {oracle.num_threads()} threads")
+        del sub
+
+    h = rb.rago_index_wrap(index, 0)
+    info = rb.rago_index_info(h)
+    del index["codes"]
+    torch.cuda.empty_cache()
+    log(f"index wrapped ({info.code_bytes_resident / 1e9:.1f} GB of codes resident); total setup {time.time() - t0:.0f}s")
+
+    if args.workload == "iter":
+        return run_iter(args, rb, h, Q, cfg, cpu)
+
+    Qb = Q[:nq].contiguous()
+    out = (torch.empty(nq, k, dtype=torch.int64, device=dev), torch.empty(nq, k, dtype=torch.float32, device=dev),
+           torch.empty(nq, k, dtype=torch.int32, device=dev))
+    for _ in range(args.warmup):
+        rb.rago_ivfpq_search(h, Qb, nprobe, k, out=out)
+    torch.cuda.synchronize()
+    rb.rago_debug_profile(h, True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        rb.rago_ivfpq_search(h, Qb, nprobe, k, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    stages, ncalls = rb.rago_debug_stage_ms(h)
+    rb.rago_debug_profile(h, False)
+    cnt = rb.rago_debug_counters(h)
+    algo_bytes, streamed = cnt[2], cnt[1]
+    scan_ms = stages["scan"]
+    achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    parity = None
+    if sample_ref is not None:
+        gi, gis = out[0][:ns].cpu().numpy(), out[2][:ns].cpu().numpy()
+        ov = float(np.mean([len(set(gi[q].tolist()) & set(sample_ref["ids"][q].tolist())) / k for q in range(ns)]))
+        parity = {"queries": ns, "topk_id_overlap": ov,
+                  "ids_bit_exact": bool(np.array_equal(gi, sample_ref["ids"])),
+                  "iscores_bit_exact": bool(np.array_equal(gis, sample_ref["iscores"]))}
+    traffic = read_traffic(cfg.name) if args.scale == 1.0 else None
+    rec = {
+        "metric": "ivfpq_queries_per_s_1Bx96B_shard" if cfg.name == "hyper" and args.scale == 1.0 else f"ivfpq_queries_per_s_{cfg.name}",
+        "value": nq / (ms * 1e-3), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={cfg.n} d={cfg.d} m={cfg.m} nlist={cfg.nlist} nq={nq} nprobe={nprobe} k={k}",
+                   "scale": args.scale},
+        "roofline": {"bound": "hbm", "kernel": f"scan_kernel<{cfg.m}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,
+                     "kernel_ms": scan_ms, "launches_timed": ncalls},
+        "stage_ms": stages,
+        "scan_tasks": cnt[0], "inexact_probe_queries": cnt[3],
+        "list_len_min_med_max": [int(lens.min()), int(lens.median()), int(lens.max())],
+        "cpu_baseline": cpu, "parity_sample": parity,
+    }
+    print(json.dumps(rec), flush=True)
+    rb.rago_index_free(h)
+
+
+def run_iter(args, rb, h, Q, cfg, cpu):
+    """Iterative retrieval: 8 sequential rounds per request chain at batch 1 / 4 / 16."""
+    import numpy as np
+    import torch
+    import synth
+    nprobe, k = synth.ITER_NPROBE, synth.ITER_K
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed * 10 + 9)
+    res = {}
+    for b in synth.ITER_BATCHES:
+        lat = []
+        out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
+               torch.empty(b, k, dtype=torch.int32, device="cuda"))
+        chains = max(args.steps, 4)
+        for c in range(chains + 1):
+            q = Q[:b].contiguous() if c == 0 else synth.make_queries(cfg, b, device="cuda", stream=20 + c)
+            for r in range(synth.ITER_ROUNDS):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                rb.rago_ivfpq_search(h, q, nprobe, k, out=out)
+                e1.record()
+                torch.cuda.synchronize()
+                if c > 0:
+                    lat.append(e0.elapsed_time(e1))
+                q = synth.drift_queries(q, synth.ITER_DRIFT, g)
+        lat = np.array(lat)
+        res[str(b)] = {"round_ms_median": float(np.median(lat)), "round_ms_p99": float(np.percentile(lat, 99)),
+                       "queries_per_s": float(b / (np.median(lat) * 1e-3))}
+    rec = {"metric": "ivfpq_iterative_round_latency", "value": res["1"]["round_ms_median"], "unit": "ms", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": f"iterative on {cfg.name}: n={cfg.n} nlist={cfg.nlist} nprobe={nprobe} k={k} rounds=8 "
+                                  f"batches=1/4/16 drift_sigma={synth.ITER_DRIFT}", "scale": args.scale},
+           "per_batch": res, "cpu_baseline": cpu}
+    print(json.dumps(rec), flush=True)
+    rb.rago_index_free(h)
+
+
+def run_flat(args):
+    import numpy as np
+    import torch
+    import synth
+    from paper_2503_14649_amd import binding as rb
+    cfg = synth.FLAT
+    R = max(1, int(cfg.requests * min(1.0, args.scale * 4))) if args.scale < 1.0 else cfg.requests
+    corpus, queries = synth.make_flat(cfg, requests=R, device="cuda:0")
+    out = (torch.empty(R, cfg.nq, cfg.k, dtype=torch.int64, device="cuda"),
+           torch.empty(R, cfg.nq, cfg.k, dtype=torch.float32, device="cuda"))
+    for _ in range(args.warmup):
+        rb.rago_flat_search(corpus, queries, cfg.k, out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        rb.rago_flat_search(corpus, queries, cfg.k, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    algo = R * cfg.n * cfg.d * 2
+    cpu = None
+    if args.cpu_queries > 0:
+        import oracle
+        rs = min(2, R)
+        cb = corpus[:rs].cpu().view(torch.int16).numpy().view(np.uint16)
+        qb = queries[:rs].cpu().view(torch.int16).numpy().view(np.uint16)
+        t1 = time.time()
+        oi, osc = oracle.flat_search(cb, qb, cfg.k)
+        dt = time.time() - t1
+        gi = out[0][:rs].cpu().numpy()
+        ov = float(np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / cfg.k for r in range(rs) for q in range(cfg.nq)]))
+        cpu = {"value": rs / dt, "unit": "requests/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{rs} of {R} requests, {dt:.2f}s wall", "topk_id_overlap": ov}
+    achieved = algo / (ms * 1e-3) / 1e9
+    rec = {"metric": "flat_requests_per_s", "value": R / (ms * 1e-3), "unit": "requests/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"flat: R={R} n={cfg.n} d={cfg.d} nq={cfg.nq} k={cfg.k}", "scale": args.scale},
+           "roofline": {"bound": "hbm", "kernel": "flat_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes_per_launch": algo},
+           "cpu_baseline": cpu}
+    print(json.dumps(rec), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="hyper", choices=["hyper", "mid", "tiny", "iter", "flat"])
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink n/nlist/components by this factor (development runs)")
+    ap.add_argument("--cpu-queries", type=int, default=32, help="queries in the CPU-oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one GPU's shard at real shape); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if args.workload == "flat":
+        run_flat(args)
+    else:
+        run_ivfpq(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -154,6 +154,14 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
  * provably independent of fp32 rounding, [4..7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
+/* Per-stage timing of rago_ivfpq_search with HIP events recorded on the caller's stream.
+ * rago_debug_profile(idx, 1) starts (and resets) recording for up to 64 following search calls,
+ * (idx, 0) stops it.  rago_debug_stage_ms waits for the recorded calls and returns, averaged over
+ * them, HOST out_ms[8] = {coarse GEMM, selection, table build, scan bookkeeping, scan kernel,
+ * merge, whole call, 0} in milliseconds and *out_calls = number of calls averaged. */
+int rago_debug_profile(rago_index* idx, int enable);
+int rago_debug_stage_ms(rago_index* idx, float* out_ms, int32_t* out_calls);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,6 +43,8 @@ _lib.rago_debug_select.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp]
 _lib.rago_debug_build_lut.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp]
 _lib.rago_debug_scan.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]
 _lib.rago_debug_counters.argtypes = [_vp, _vp, _vp]
+_lib.rago_debug_profile.argtypes = [_vp, _int]
+_lib.rago_debug_stage_ms.argtypes = [_vp, _vp, _vp]
 
 
 class RagoError(RuntimeError):
@@ -172,6 +174,20 @@ def rago_debug_counters(h, device=0):
     out = (ctypes.c_int64 * 8)()
     _chk(_lib.rago_debug_counters(h, out, _stream(torch.device("cuda", device))))
     return list(out)
+
+
+STAGES = ("coarse", "select", "lut", "scan_setup", "scan", "merge", "total")
+
+
+def rago_debug_profile(h, enable: bool):
+    _chk(_lib.rago_debug_profile(h, int(enable)))
+
+
+def rago_debug_stage_ms(h):
+    out = (ctypes.c_float * 8)()
+    n = ctypes.c_int32()
+    _chk(_lib.rago_debug_stage_ms(h, out, ctypes.byref(n)))
+    return {name: float(out[i]) for i, name in enumerate(STAGES)}, int(n.value)
 
 
 class Index:

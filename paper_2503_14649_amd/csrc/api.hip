@@ -50,6 +50,8 @@ static void destroy(rago_index* idx) {
     hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->codebooks); hipFree(idx->list_off);
     hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
     idx->ws.release();
+    if (idx->prof.created)
+        for (auto& c : idx->prof.ev) for (auto& e : c) hipEventDestroy(e);
     delete idx;
 }
 
@@ -301,13 +303,53 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
     hipStream_t st = (hipStream_t)stream;
+    hipEvent_t* ev = nullptr;
+    if (idx->prof.on && idx->prof.ncalls < PROF_CALLS) ev = idx->prof.ev[idx->prof.ncalls];
+    if (ev) RAGO_HIP(hipEventRecord(ev[0], st));
     if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st))) return rc;
+    if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
     if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+    if (ev) RAGO_HIP(hipEventRecord(ev[2], st));
     if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, ws.lut8.as<uint8_t>(),
                                ws.bias.as<int32_t>(), ws.delta.as<float>(), nullptr, nullptr, st)))
         return rc;
-    return launch_scan(idx, ws.probes.as<int32_t>(), ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
-                       nq, nprobe, k, out_ids, out_scores, out_iscores, st);
+    if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
+    rc = launch_scan(idx, ws.probes.as<int32_t>(), ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                     nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev);
+    if (!rc && ev) ++idx->prof.ncalls;
+    return rc;
+}
+
+int rago_debug_profile(rago_index* idx, int enable) {
+    if (!idx) return fail(RAGO_INVALID_ARG, "null index");
+    DeviceGuard g(idx->device);
+    if (enable && !idx->prof.created) {
+        for (auto& c : idx->prof.ev)
+            for (auto& e : c) RAGO_HIP(hipEventCreate(&e));
+        idx->prof.created = true;
+    }
+    idx->prof.on = enable != 0;
+    if (enable) idx->prof.ncalls = 0;
+    return RAGO_OK;
+}
+
+int rago_debug_stage_ms(rago_index* idx, float* out_ms, int32_t* out_calls) {
+    if (!idx || !out_ms || !out_calls) return fail(RAGO_INVALID_ARG, "null argument");
+    DeviceGuard g(idx->device);
+    for (int i = 0; i < 8; ++i) out_ms[i] = 0.f;
+    *out_calls = idx->prof.ncalls;
+    for (int c = 0; c < idx->prof.ncalls; ++c) {
+        RAGO_HIP(hipEventSynchronize(idx->prof.ev[c][PROF_EVENTS - 1]));
+        for (int i = 0; i + 1 < PROF_EVENTS; ++i) {
+            float ms = 0.f;
+            RAGO_HIP(hipEventElapsedTime(&ms, idx->prof.ev[c][i], idx->prof.ev[c][i + 1]));
+            out_ms[i] += ms / idx->prof.ncalls;
+        }
+        float ms = 0.f;
+        RAGO_HIP(hipEventElapsedTime(&ms, idx->prof.ev[c][0], idx->prof.ev[c][PROF_EVENTS - 1]));
+        out_ms[6] += ms / idx->prof.ncalls;
+    }
+    return RAGO_OK;
 }
 
 int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,

@@ -45,6 +45,16 @@ struct Workspace {
 __host__ __device__ inline int rago_steps(int m) { return m < 32 ? m : 32; }
 __host__ __device__ inline int rago_planes(int m) { return m < 32 ? 1 : m / 32; }
 
+namespace rago {
+constexpr int PROF_CALLS = 64, PROF_EVENTS = 7;
+struct Profiler {
+    bool on = false;
+    bool created = false;
+    int ncalls = 0;
+    hipEvent_t ev[PROF_CALLS][PROF_EVENTS];
+};
+}  // namespace rago
+
 struct rago_index {
     int device = 0;
     int d = 0, m = 0, dsub = 0, nlist = 0;
@@ -60,6 +70,7 @@ struct rago_index {
     int64_t* ids = nullptr;        // [n]
     float max_cnorm = 0.f;
     rago::Workspace ws;
+    rago::Profiler prof;
     // parameters of the last scan (for rago_debug_counters)
     int64_t last_algo_bytes_valid = 0;
 };
@@ -83,7 +94,7 @@ int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npair
 // scan.hip
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
                 const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores,
-                int32_t* out_iscores, hipStream_t st);
+                int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr);
 
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,

@@ -574,7 +574,8 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
 }
 
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias, const float* delta,
-                int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores, int32_t* out_iscores, hipStream_t st) {
+                int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores, int32_t* out_iscores, hipStream_t st,
+                hipEvent_t* ev) {
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
@@ -623,6 +624,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
         n_cu = pr.multiProcessorCount;
     }
     const int grid = 2 * n_cu;
+    if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
     switch (idx->m) {
         case 16: rc = launch_scan_kernel<16>(P, grid, st); break;
         case 32: rc = launch_scan_kernel<32>(P, grid, st); break;
@@ -632,8 +634,10 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
         default: return fail(RAGO_UNSUPPORTED, "code width");
     }
     if (rc) return rc;
+    if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
     merge_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
     RAGO_HIP(hipGetLastError());
+    if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
     return RAGO_OK;
 }
 

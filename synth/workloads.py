@@ -186,6 +186,14 @@ def _assign_exact(x: torch.Tensor, c: torch.Tensor, chunk: int = 65536) -> torch
     return out
 
 
+def _native_encode_available() -> bool:
+    try:
+        from . import native
+        return native.available()
+    except Exception:
+        return False
+
+
 def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = None,
                 chunk: int = 1 << 20, progress=None) -> Dict[str, torch.Tensor]:
     """Generate the database and train/encode an IVF-PQ index for it.
@@ -212,37 +220,51 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     codebooks = _pq_train(res, cfg.m, cfg.kmeans_iters, g_train)
     del xt, sub, res
 
-    cand = None
-    if cfg.assign == "component":
-        mu = torch.nn.functional.normalize(mix.means, dim=1)
-        cand = (mu @ centroids.T).topk(16, dim=1).indices              # [G][16]
-    elif cfg.assign != "exact":
-        raise ValueError(cfg.assign)
-
     n = cfg.n
     codes_arr = torch.empty(n, cfg.m, dtype=torch.uint8, device=dev)   # arrival (= id) order
     lists_arr = torch.empty(n, dtype=torch.int32, device=dev)
     vectors = torch.empty(n, cfg.d, device=dev) if keep_vectors else None
-    for a in range(0, n, chunk):
-        b = min(n, a + chunk)
-        x, comp = mix.sample(b - a, g_db)
-        if cand is None:
-            li = _assign_exact(x, centroids)
+    use_native = dev.type == "cuda" and _native_encode_available()
+
+    def emit(a, x, li):
+        b = a + x.shape[0]
+        if use_native:
+            from . import native
+            native.pq_encode(x.contiguous(), centroids, li.contiguous(), codebooks, codes_arr[a:b])
         else:
-            cc = cand[comp]                                            # [b][16]
-            best = torch.full((b - a,), -float("inf"), device=dev)
-            li = torch.zeros(b - a, dtype=torch.int64, device=dev)
-            for t in range(cc.shape[1]):
-                s = (x * centroids[cc[:, t]]).sum(1)
-                upd = s > best
-                best = torch.where(upd, s, best)
-                li = torch.where(upd, cc[:, t], li)
-        codes_arr[a:b] = pq_encode(x - centroids[li], codebooks)
+            codes_arr[a:b] = pq_encode(x - centroids[li], codebooks)
         lists_arr[a:b] = li.to(torch.int32)
         if vectors is not None:
             vectors[a:b] = x
         if progress:
             progress(b, n)
+
+    if cfg.assign == "exact":
+        for a in range(0, n, chunk):
+            x, _ = mix.sample(min(n, a + chunk) - a, g_db)
+            emit(a, x, _assign_exact(x, centroids))
+    elif cfg.assign == "component":
+        # component-major stream: every component contributes ceil(n / G) consecutive samples, so
+        # the 16 candidate centroids are shared by a whole slab and scored with one batched GEMM
+        G = cfg.components
+        mu = torch.nn.functional.normalize(mix.means, dim=1)
+        cand = (mu @ centroids.T).topk(min(16, cfg.nlist), dim=1).indices          # [G][16]
+        per = -(-n // G)
+        gc = max(1, chunk // per)
+        a = 0
+        for g0 in range(0, G, gc):
+            if a >= n:
+                break
+            comps = torch.arange(g0, min(G, g0 + gc), device=dev)
+            x = mix.raw(comps.repeat_interleave(per), g_db)
+            x = torch.nn.functional.normalize(x, dim=1)
+            sc = torch.bmm(x.view(comps.numel(), per, cfg.d), centroids[cand[comps]].transpose(1, 2))   # [gc][per][16]
+            li = torch.gather(cand[comps], 1, sc.argmax(2)).reshape(-1)
+            take = min(x.shape[0], n - a)
+            emit(a, x[:take], li[:take])
+            a += take
+    else:
+        raise ValueError(cfg.assign)
 
     order = torch.sort(lists_arr, stable=True).indices                 # ids ascend inside a list
     counts = torch.bincount(lists_arr.to(torch.int64), minlength=cfg.nlist)
