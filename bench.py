@@ -122,6 +122,7 @@ def run_ivfpq(args):
         log(f"oracle: {ns / dt:.2f} queries/s on {oracle.num_threads()} threads")
         del sub
 
+    torch.cuda.empty_cache()
     h = rb.rago_index_wrap(index, 0)
     info = rb.rago_index_info(h)
     del index["codes"]

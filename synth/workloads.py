@@ -275,6 +275,8 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     for a in range(0, n, 1 << 24):
         codes[a:a + (1 << 24)] = codes_arr[order[a:a + (1 << 24)]]
     del codes_arr
+    if dev.type == "cuda":
+        torch.cuda.empty_cache()
     out = dict(centroids=centroids, codebooks=codebooks, list_offsets=offsets, codes=codes,
                ids=order.to(torch.int64))
     if vectors is not None:
