@@ -135,6 +135,13 @@ def run_ivfpq(args):
     Qb = Q[:nq].contiguous()
     out = (torch.empty(nq, k, dtype=torch.int64, device=dev), torch.empty(nq, k, dtype=torch.float32, device=dev),
            torch.empty(nq, k, dtype=torch.int32, device=dev))
+    if args.calib_copy_gib > 0:     # a copy of known size for scaling hardware byte counters
+        a = torch.empty(int(args.calib_copy_gib * (1 << 30)), dtype=torch.uint8, device=dev).fill_(1)
+        b = torch.empty_like(a)
+        rb.rago_debug_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
     for _ in range(args.warmup):
         rb.rago_ivfpq_search(h, Qb, nprobe, k, out=out)
     torch.cuda.synchronize()
@@ -270,6 +277,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="hyper", choices=["hyper", "mid", "tiny", "iter", "flat"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n/nlist/components by this factor (development runs)")
+    ap.add_argument("--calib-copy-gib", type=float, default=0.0,
+                    help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=32, help="queries in the CPU-oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -154,6 +154,11 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
  * provably independent of fp32 rounding, [4..7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
+/* Plain copy kernel (rago_calib_copy_kernel) of `bytes` bytes, DEVICE src -> DEVICE dst, both
+ * 16-byte aligned, bytes % 16 == 0, on the current device: a transfer of known size against which
+ * hardware HBM byte counters are calibrated when the scan is profiled. */
+int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
 /* Per-stage timing of rago_ivfpq_search with HIP events recorded on the caller's stream.
  * rago_debug_profile(idx, 1) starts (and resets) recording for up to 64 following search calls,
  * (idx, 0) stops it.  rago_debug_stage_ms waits for the recorded calls and returns, averaged over

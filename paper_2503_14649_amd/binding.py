@@ -43,6 +43,7 @@ _lib.rago_debug_select.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp]
 _lib.rago_debug_build_lut.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp]
 _lib.rago_debug_scan.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]
 _lib.rago_debug_counters.argtypes = [_vp, _vp, _vp]
+_lib.rago_debug_copy.argtypes = [_vp, _vp, _i64, _vp]
 _lib.rago_debug_profile.argtypes = [_vp, _int]
 _lib.rago_debug_stage_ms.argtypes = [_vp, _vp, _vp]
 
@@ -174,6 +175,12 @@ def rago_debug_counters(h, device=0):
     out = (ctypes.c_int64 * 8)()
     _chk(_lib.rago_debug_counters(h, out, _stream(torch.device("cuda", device))))
     return list(out)
+
+
+def rago_debug_copy(src: torch.Tensor, dst: torch.Tensor):
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _chk(_lib.rago_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(src.device)))
 
 
 STAGES = ("coarse", "select", "lut", "scan_setup", "scan", "merge", "total")

@@ -368,6 +368,12 @@ int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t
     return launch_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, (hipStream_t)stream);
 }
 
+int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream) {
+    if (!src || !dst || bytes < 0 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+        return fail(RAGO_INVALID_ARG, "copy needs 16-byte aligned buffers and a size that is a multiple of 16");
+    return launch_calib_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream) {
     if (!idx || !out) return fail(RAGO_INVALID_ARG, "null argument");
     DeviceGuard g(idx->device);

@@ -75,6 +75,18 @@ __global__ void __launch_bounds__(256) cnorm_kernel(const float* __restrict__ C,
     if ((threadIdx.x & 63) == 0) out[l] = sqrtf(acc) * 1.0001f;  // slight over-estimate: used as a bound
 }
 
+// Plain device-to-device copy of known size: the yardstick that hardware byte counters are
+// scaled by when a profile of the scan is taken.
+__global__ void __launch_bounds__(256) rago_calib_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st) {
+    rago_calib_copy_kernel<<<8192, 256, 0, st>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+    RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st) {
     if (idx->total_blocks > 0) {
         if (idx->total_blocks > 0x7fffffffLL) return fail(RAGO_UNSUPPORTED, "more than 2^31 code blocks");

@@ -79,6 +79,7 @@ namespace rago {
 
 // layout.hip
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
+int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 
 // coarse.hip
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);
