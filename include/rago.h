@@ -110,7 +110,7 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
 /*
  * rago_flat_search: exact inner-product search of R independent requests, each with its own
  * corpus (brute-force kNN over freshly embedded long-context chunks, Section 5.2).
- *   corpus_bf16  DEVICE [R][n][d] bf16 row-major, 16-byte aligned;  d % 32 == 0, d <= 1024
+ *   corpus_bf16  DEVICE [R][n][d] bf16 row-major, 16-byte aligned;  d in {64,128,256,384,512,768,1024}
  *   queries_bf16 DEVICE [R][nqr][d] bf16;  1 <= nqr <= 16
  *   1 <= k <= 128
  *   out_ids      DEVICE [R][nqr][k] int64 row index inside the request's corpus, pad -1

@@ -358,7 +358,7 @@ int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t
     if (nqr < 1 || nqr > 16) return fail(RAGO_INVALID_ARG, "nqr must be in [1, 16]");
     if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
     if (k > KMAX) return fail(RAGO_UNSUPPORTED, "k > 128");
-    if (d < 32 || d % 32 || d > 1024) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 32 in [32, 1024]");
+    if (d < 64 || d % 64 || d > 1024) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 64 in [64, 1024]");
     if (R > 0 && (!queries || !out_ids || !out_scores || (n > 0 && !corpus))) return fail(RAGO_INVALID_ARG, "null buffer");
     if (((uintptr_t)corpus & 15) || ((uintptr_t)queries & 15)) return fail(RAGO_INVALID_ARG, "buffers must be 16-byte aligned");
     if (n > 0x7fffffffLL) return fail(RAGO_UNSUPPORTED, "n > 2^31-1 per request");

@@ -1,0 +1,83 @@
+"""GPU parity: exact bf16 flat search (HIP, MFMA) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rb():
+    from paper_2503_14649_amd import binding
+    return binding
+
+
+def _bits(t):
+    return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def _check(rb, corpus, queries, k):
+    gi, gs = rb.rago_flat_search(corpus.cuda(), queries.cuda(), k)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    oi, osc = oracle.flat_search(_bits(corpus), _bits(queries), k)
+    R, nq = queries.shape[:2]
+    n = corpus.shape[1]
+    kk = min(k, n)
+    assert np.all(gi[:, :, kk:] == -1) and np.all(np.isneginf(gs[:, :, kk:]))
+    # scores: bf16 products are exact in fp32, only the accumulation order differs; |q||x| ~ 1
+    assert np.max(np.abs(gs[:, :, :kk] - osc[:, :, :kk])) < 1e-4
+    ov = np.mean([len(set(gi[r, q, :kk].tolist()) & set(oi[r, q, :kk].tolist())) / kk for r in range(R) for q in range(nq)])
+    assert ov >= 0.999, ov
+    # each returned score is the true score of the returned row (fp64 reference), order is non-increasing
+    ref = torch.einsum("rqd,rnd->rqn", queries.double(), corpus.double()).numpy()
+    for r in range(R):
+        for q in range(nq):
+            assert np.max(np.abs(ref[r, q][gi[r, q, :kk]] - gs[r, q, :kk])) < 1e-5
+            assert np.all(np.diff(gs[r, q, :kk]) <= 0)
+            same = np.diff(gs[r, q, :kk]) == 0
+            assert np.all(np.diff(gi[r, q, :kk])[same] > 0)          # equal scores: lower row first
+    return gi, gs, oi, osc
+
+
+@pytest.mark.parametrize("R,n,nq,k", [(2, 700, 16, 32), (3, 5000, 5, 128), (1, 20, 16, 32), (2, 1, 3, 4), (2, 30000, 16, 32)])
+def test_flat_matches_oracle(rb, R, n, nq, k):
+    print(f"[flat] R={R} n={n} nq={nq} k={k}", flush=True)
+    cfg = synth.FLAT
+    corpus, queries = synth.make_flat(cfg, requests=R, n=n)
+    queries = queries[:, :nq].contiguous()
+    _check(rb, corpus, queries, k)
+
+
+def test_flat_duplicate_rows_tie_by_lower_index(rb):
+    cfg = synth.FLAT
+    corpus, queries = synth.make_flat(cfg, requests=1, n=3000)
+    for i in (17, 300, 301, 1700, 2999):
+        corpus[0, i] = corpus[0, 5]
+    queries[0, 0] = corpus[0, 5]
+    gi, gs, oi, osc = _check(rb, corpus, queries, 32)
+    assert gi[0, 0, :6].tolist() == [5, 17, 300, 301, 1700, 2999]
+    assert np.array_equal(gi[0, 0, :6], oi[0, 0, :6])
+
+
+def test_flat_other_dims_and_errors(rb):
+    g = torch.Generator().manual_seed(3)
+    for d in (64, 128, 256, 1024):
+        corpus = torch.nn.functional.normalize(torch.randn(2, 900, d, generator=g), dim=2).to(torch.bfloat16)
+        queries = torch.nn.functional.normalize(torch.randn(2, 7, d, generator=g), dim=2).to(torch.bfloat16)
+        _check(rb, corpus, queries, 10)
+    c = torch.zeros(1, 10, 96, dtype=torch.bfloat16).cuda()
+    q = torch.zeros(1, 2, 96, dtype=torch.bfloat16).cuda()
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_flat_search(c, q, 4)
+    assert e.value.code == -6
+    c = torch.zeros(1, 10, 128, dtype=torch.bfloat16).cuda()
+    q = torch.zeros(1, 17, 128, dtype=torch.bfloat16).cuda()
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_flat_search(c, q, 4)
+    assert e.value.code == -1
+    gi, gs = rb.rago_flat_search(c[:, :0].contiguous(), q[:, :4].contiguous(), 4)   # empty corpus: all padding
+    assert torch.all(gi == -1)
