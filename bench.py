@@ -201,7 +201,10 @@ def run_iter(args, rb, h, Q, cfg, cpu):
         out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
                torch.empty(b, k, dtype=torch.int32, device="cuda"))
         chains = max(args.steps, 4)
+        rb.rago_debug_profile(h, False)
         for c in range(chains + 1):
+            if c == 1:
+                rb.rago_debug_profile(h, True)
             q = Q[:b].contiguous() if c == 0 else synth.make_queries(cfg, b, device="cuda", stream=20 + c)
             for r in range(synth.ITER_ROUNDS):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -213,8 +216,9 @@ def run_iter(args, rb, h, Q, cfg, cpu):
                     lat.append(e0.elapsed_time(e1))
                 q = synth.drift_queries(q, synth.ITER_DRIFT, g)
         lat = np.array(lat)
+        stages, _ = rb.rago_debug_stage_ms(h)
         res[str(b)] = {"round_ms_median": float(np.median(lat)), "round_ms_p99": float(np.percentile(lat, 99)),
-                       "queries_per_s": float(b / (np.median(lat) * 1e-3))}
+                       "queries_per_s": float(b / (np.median(lat) * 1e-3)), "stage_ms": stages}
     rec = {"metric": "ivfpq_iterative_round_latency", "value": res["1"]["round_ms_median"], "unit": "ms", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
