@@ -151,7 +151,9 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
 /* Counters of the last search on this index, HOST out[8] (synchronises `stream`):
  * [0] scan tasks, [1] code bytes streamed by the scan, [2] algorithmic code bytes
  * (sum over (query, probe) of list length * m), [3] queries whose probe choice was not
- * provably independent of fp32 rounding, [4..7] reserved. */
+ * provably independent of fp32 rounding, [4] table entries whose rounding had to be evaluated per
+ * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
+ * for every pair, [6..7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
 /* Plain copy kernel (rago_calib_copy_kernel) of `bytes` bytes, DEVICE src -> DEVICE dst, both

@@ -29,7 +29,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &cursor, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw};
+                     &counters, &tmp_lut8sw, &amb, &patch};
     for (DevBuf* b : all) b->release();
 }
 
@@ -258,17 +258,13 @@ int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* p
     if (rc) return rc;
     if (nq == 0) return RAGO_OK;
     DeviceGuard g(idx->device);
-    Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
-    if ((rc = ws.lut8.reserve((size_t)npairs * LUT_BYTES))) return rc;
-    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    rc = launch_build_lut(idx, queries, probes, nq, nprobe, ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(),
-                          ws.delta.as<float>(), out_L, out_LUT8, st);
+    LutTables T;
+    rc = launch_build_lut(idx, queries, probes, nq, nprobe, &T, out_L, out_LUT8, st);
     if (rc) return rc;
-    if (out_B) RAGO_HIP(hipMemcpyAsync(out_B, ws.bias.p, (size_t)npairs * 4, hipMemcpyDeviceToDevice, st));
-    if (out_delta) RAGO_HIP(hipMemcpyAsync(out_delta, ws.delta.p, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
+    if (out_B) RAGO_HIP(hipMemcpyAsync(out_B, T.bias, (size_t)npairs * 4, hipMemcpyDeviceToDevice, st));
+    if (out_delta) RAGO_HIP(hipMemcpyAsync(out_delta, T.delta, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
     return RAGO_OK;
 }
 
@@ -284,7 +280,7 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
     if ((rc = ws.tmp_lut8sw.reserve((size_t)npairs * LUT_BYTES))) return rc;
     hipStream_t st = (hipStream_t)stream;
     if ((rc = launch_swizzle_lut(idx, LUT8, npairs, ws.tmp_lut8sw.as<uint8_t>(), st))) return rc;
-    return launch_scan(idx, probes, ws.tmp_lut8sw.as<uint8_t>(), B, nullptr, nq, nprobe, k, out_ids, nullptr, out_iscores, st);
+    return launch_scan(idx, probes, ws.tmp_lut8sw.as<uint8_t>(), B, nullptr, nullptr, nq, nprobe, k, out_ids, nullptr, out_iscores, st);
 }
 
 int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids,
@@ -299,9 +295,6 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     const int64_t npairs = nq * nprobe;
     if ((rc = ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
     if ((rc = ws.probes.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.lut8.reserve((size_t)npairs * LUT_BYTES))) return rc;
-    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = nullptr;
     if (idx->prof.on && idx->prof.ncalls < PROF_CALLS) ev = idx->prof.ev[idx->prof.ncalls];
@@ -310,12 +303,11 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
     if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[2], st));
-    if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, ws.lut8.as<uint8_t>(),
-                               ws.bias.as<int32_t>(), ws.delta.as<float>(), nullptr, nullptr, st)))
-        return rc;
+    LutTables T;
+    if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st))) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
-    rc = launch_scan(idx, ws.probes.as<int32_t>(), ws.lut8.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
-                     nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev);
+    rc = launch_scan(idx, ws.probes.as<int32_t>(), nullptr, T.bias, &T, T.delta, nq, nprobe, k, out_ids, out_scores,
+                     out_iscores, st, ev);
     if (!rc && ev) ++idx->prof.ncalls;
     return rc;
 }

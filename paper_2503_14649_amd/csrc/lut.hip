@@ -13,9 +13,21 @@
 // (probability ~1e-9 per entry).  min/max commute with the monotone rounding, so lo/hi come from
 // the per-query extrema of T.
 //
-// Output table layout ("swizzled", what the scan copies into LDS): [pair][c][128] with byte
+// In exact arithmetic (L - lo) / delta does not depend on the probed list: it is
+// u = (T - Tmin) / delta.  The fp32 evaluation prescribed above differs from u by at most
+//   eta_0 = 2^-24 * ((2 M + range) / delta + 256),   M = max |lo|,|hi| over the query's pairs,
+// (two roundings of magnitude <= M, one of the difference <= range, one of the quotient <= 256).
+// So one BASE table per query, rne(u), is the exact per-pair table wherever u is farther than
+// eta = 2 eta_0 from every half-integer; the few entries closer than that ("ambiguous", ~1e-3 of
+// a table) are evaluated per pair with the prescribed fp32 expression and stored as PATCHES.
+// The scan loads the base table of the query and overwrites the patched bytes.  If a query has
+// more ambiguous entries than AMB_MAX (nearly constant tables), its pairs are flagged and every
+// consumer evaluates the full per-pair table with the same expression instead.
+//
+// Table layout ("swizzled", what the scan copies into LDS): [c][128] with byte
 // slot*4 + plane = entry c of sub-quantiser plane*32 + slot; for m < 32 the m sub-tables are
 // replicated 32/m times over the 32 slots.
+#include "lut_common.h"
 #include "rago_internal.h"
 
 namespace rago {
@@ -45,16 +57,17 @@ __global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q,
     }
 }
 
-// Per pair: t64[pair][j]; per query: running max of (hi - lo) as float bits (values are >= 0).
+// Per pair: t64[pair][j]; per query: running max of (hi - lo) and of |lo|,|hi| as float bits (>= 0).
 __global__ void __launch_bounds__(128) lut_pair_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                        const int32_t* __restrict__ probes, int nprobe, int d, int m,
                                                        const double* __restrict__ Tmin, const double* __restrict__ Tmax,
-                                                       double* __restrict__ t64, uint32_t* __restrict__ range_bits) {
+                                                       double* __restrict__ t64, uint32_t* __restrict__ range_bits,
+                                                       uint32_t* __restrict__ mag_bits) {
     const int64_t pair = blockIdx.x;
     const int64_t q = pair / nprobe;
     const int l = probes[pair];
     const int dsub = d / m;
-    float rng = 0.f;
+    float rng = 0.f, mag = 0.f;
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
         const float* qv = Q + q * d + j * dsub;
         const float* cv = C + (int64_t)l * d + j * dsub;
@@ -63,60 +76,126 @@ __global__ void __launch_bounds__(128) lut_pair_kernel(const float* __restrict__
         t64[pair * m + j] = acc;
         const float lo = (float)(Tmin[q * m + j] + acc), hi = (float)(Tmax[q * m + j] + acc);
         rng = fmaxf(rng, hi - lo);
+        mag = fmaxf(mag, fmaxf(fabsf(lo), fabsf(hi)));
     }
-    for (int o = 32; o; o >>= 1) rng = fmaxf(rng, __shfl_xor(rng, o));
-    if ((threadIdx.x & 63) == 0 && rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
+    for (int o = 32; o; o >>= 1) { rng = fmaxf(rng, __shfl_xor(rng, o)); mag = fmaxf(mag, __shfl_xor(mag, o)); }
+    if ((threadIdx.x & 63) == 0) {
+        if (rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
+        if (mag > 0.f) atomicMax(mag_bits + q, __float_as_uint(mag));
+    }
 }
 
-// Per pair: quantise.  256 threads = one per codeword c (one table row each).
-template <bool PLAIN>
-__global__ void __launch_bounds__(256) lut_quant_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
-                                                        const double* __restrict__ t64, const uint32_t* __restrict__ range_bits,
-                                                        int nprobe, int m, uint8_t* __restrict__ lut8sw, int32_t* __restrict__ bias,
-                                                        float* __restrict__ delta, float* __restrict__ out_L,
-                                                        uint8_t* __restrict__ out_LUT8) {
-    __shared__ double s_t[128];
-    __shared__ float s_lo[128];
-    const int64_t pair = blockIdx.x;
-    const int64_t q = pair / nprobe;
+// Per query: base table (swizzled) + list of ambiguous entries.  256 threads = one per codeword.
+__global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+                                                       const uint32_t* __restrict__ range_bits, const uint32_t* __restrict__ mag_bits,
+                                                       int m, uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
+                                                       int32_t* __restrict__ namb, float* __restrict__ delta,
+                                                       int64_t* __restrict__ counters) {
+    __shared__ int s_n;
+    const int64_t q = blockIdx.x;
     const int c = threadIdx.x;
-    float dq = __uint_as_float(range_bits[q]) / 255.0f;
-    if (!(dq > 0.0f)) dq = 1.0f;
-    if (c < m) {
-        const double t = t64[pair * m + c];
-        s_t[c] = t;
-        s_lo[c] = (float)(Tmin[q * m + c] + t);
-    }
+    if (c == 0) s_n = 0;
     __syncthreads();
-    if (c == 0) {
-        double losum = 0.0;
-        for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
-        bias[pair] = (int32_t)rint(losum / (double)dq);
-        if (pair % nprobe == 0) delta[q] = dq;
-    }
+    const float range = __uint_as_float(range_bits[q]);
+    const float dq = lut_step(range);
+    const double eta = lut_eta(range, __uint_as_float(mag_bits[q]), dq);
     uint32_t row[LUT_ROW / 4];
 #pragma unroll
     for (int i = 0; i < LUT_ROW / 4; ++i) row[i] = 0;
     const double* Tq = T64 + q * m * KSUB + c;
     const int S = rago_steps(m);
     for (int j = 0; j < m; ++j) {
-        const float L = (float)(Tq[(int64_t)j * KSUB] + s_t[j]);
-        float r = rintf(__fdiv_rn(L - s_lo[j], dq));
-        r = r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r);
-        const uint32_t v = (uint32_t)r;
-        if (PLAIN) {
-            if (out_L) out_L[(pair * m + j) * KSUB + c] = L;
-            if (out_LUT8) out_LUT8[(pair * m + j) * KSUB + c] = (uint8_t)v;
-        }
+        const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) / (double)dq;
+        double r = rint(u);
+        r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
         const int slot = j & (S - 1), plane = j >> 5;
-        row[slot] |= v << (8 * plane);   // slot*4 + plane = byte `plane` of dword `slot`
+        row[slot] |= (uint32_t)r << (8 * plane);
+        if (fabs((u - floor(u)) - 0.5) <= eta) {
+            for (int rep = slot; rep < 32; rep += S) {     // every replica of the sub-table (m < 32)
+                const int i = atomicAdd(&s_n, 1);
+                if (i < AMB_MAX) amb_addr[q * AMB_MAX + i] = (uint16_t)(c * 256 + rep * 4 + plane);
+            }
+        }
     }
-    if (S < 32) {                        // replicate the m sub-tables over all 32 slots
+    if (S < 32) {
         for (int s = S; s < 32; ++s) row[s] = row[s & (S - 1)];
     }
-    uint4* dst = reinterpret_cast<uint4*>(lut8sw + pair * LUT_BYTES + (int64_t)c * LUT_ROW);
+    uint4* dst = reinterpret_cast<uint4*>(lut_base + q * LUT_BYTES + (int64_t)c * LUT_ROW);
 #pragma unroll
     for (int i = 0; i < LUT_ROW / 16; ++i) dst[i] = make_uint4(row[4 * i], row[4 * i + 1], row[4 * i + 2], row[4 * i + 3]);
+    __syncthreads();
+    if (c == 0) {
+        namb[q] = s_n > AMB_MAX ? AMB_MAX + 1 : s_n;   // AMB_MAX + 1 = "evaluate per pair"
+        delta[q] = dq;
+        if (s_n > AMB_MAX) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), 1ull);
+        else atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)s_n);
+    }
+}
+
+// Per pair: bias and the exact values of the query's ambiguous entries.
+__global__ void __launch_bounds__(128) lut_patch_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+                                                        const double* __restrict__ t64, const uint32_t* __restrict__ range_bits,
+                                                        const uint16_t* __restrict__ amb_addr, const int32_t* __restrict__ namb,
+                                                        int nprobe, int m, int32_t* __restrict__ bias, uint8_t* __restrict__ patch_val) {
+    __shared__ double s_t[128];
+    __shared__ float s_lo[128];
+    const int64_t pair = blockIdx.x;
+    const int64_t q = pair / nprobe;
+    const float dq = lut_step(__uint_as_float(range_bits[q]));
+    if ((int)threadIdx.x < m) {
+        const double t = t64[pair * m + threadIdx.x];
+        s_t[threadIdx.x] = t;
+        s_lo[threadIdx.x] = (float)(Tmin[q * m + threadIdx.x] + t);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double losum = 0.0;
+        for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
+        bias[pair] = (int32_t)rint(losum / (double)dq);
+    }
+    const int n = namb[q];
+    if (n > AMB_MAX) return;
+    const int S = rago_steps(m);
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const int addr = amb_addr[q * AMB_MAX + i];
+        const int c = addr >> 8, slot = (addr >> 2) & 31, plane = addr & 3;
+        const int j = plane * 32 + (slot & (S - 1));
+        patch_val[pair * AMB_MAX + i] = lut_entry(T64[(q * m + j) * KSUB + c], s_t[j], s_lo[j], dq);
+    }
+}
+
+// Plain per-pair tables [pair][m][256] (u8 and/or fp32) for inspection: base + patches, or the
+// full evaluation for flagged queries.
+__global__ void __launch_bounds__(256) lut_expand_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+                                                         const double* __restrict__ t64, const uint32_t* __restrict__ range_bits,
+                                                         const uint8_t* __restrict__ lut_base, const uint16_t* __restrict__ amb_addr,
+                                                         const int32_t* __restrict__ namb, const uint8_t* __restrict__ patch_val,
+                                                         int nprobe, int m, float* __restrict__ out_L, uint8_t* __restrict__ out_LUT8) {
+    const int64_t pair = blockIdx.x;
+    const int64_t q = pair / nprobe;
+    const int c = threadIdx.x;
+    const float dq = lut_step(__uint_as_float(range_bits[q]));
+    const int n = namb[q];
+    const int S = rago_steps(m);
+    for (int j = 0; j < m; ++j) {
+        const double t = t64[pair * m + j];
+        const double Tv = T64[(q * m + j) * KSUB + c];
+        if (out_L) out_L[(pair * m + j) * KSUB + c] = (float)(Tv + t);
+        if (out_LUT8) {
+            uint8_t v;
+            if (n > AMB_MAX) v = lut_entry(Tv, t, (float)(Tmin[q * m + j] + t), dq);
+            else v = lut_base[q * LUT_BYTES + (int64_t)c * LUT_ROW + (j & (S - 1)) * 4 + (j >> 5)];
+            out_LUT8[(pair * m + j) * KSUB + c] = v;
+        }
+    }
+    if (!out_LUT8 || n > AMB_MAX) return;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const int addr = amb_addr[q * AMB_MAX + i];
+        const int cc = addr >> 8, slot = (addr >> 2) & 31, plane = addr & 3;
+        const int j = plane * 32 + (slot & (S - 1));
+        out_LUT8[(pair * m + j) * KSUB + cc] = patch_val[pair * AMB_MAX + i];
+    }
 }
 
 // plain [pair][m][256] u8 -> swizzled [pair][256][128]
@@ -149,29 +228,51 @@ int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npair
     return RAGO_OK;
 }
 
-int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, uint8_t* lut8sw,
-                     int32_t* bias, float* delta, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st) {
+int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, LutTables* out,
+                     float* out_L_f32, uint8_t* out_LUT8, hipStream_t st) {
     Workspace& ws = idx->ws;
     const int m = idx->m, d = idx->d;
     const int64_t npairs = nq * nprobe;
     int rc;
     if ((rc = ws.T64.reserve((size_t)nq * m * KSUB * 8))) return rc;
     if ((rc = ws.Tmin.reserve((size_t)nq * m * 8))) return rc;
-    if ((rc = ws.Tmax.reserve((size_t)nq * m * 8 + (size_t)nq * 4))) return rc;   // + range bits per query
+    if ((rc = ws.Tmax.reserve((size_t)nq * m * 8 + (size_t)nq * 8))) return rc;   // + range and magnitude bits per query
     if ((rc = ws.pair_lo.reserve((size_t)npairs * m * 8))) return rc;
+    if ((rc = ws.lut8.reserve((size_t)nq * LUT_BYTES))) return rc;
+    if ((rc = ws.amb.reserve((size_t)nq * AMB_MAX * 2 + (size_t)nq * 4))) return rc;
+    if ((rc = ws.patch.reserve((size_t)npairs * AMB_MAX))) return rc;
+    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
     double* Tmax = ws.Tmax.as<double>();
     uint32_t* range_bits = reinterpret_cast<uint32_t*>(Tmax + nq * m);
-    fill_u32_kernel<<<64, 256, 0, st>>>(range_bits, 0u, nq);
+    uint32_t* mag_bits = range_bits + nq;
+    uint16_t* amb_addr = ws.amb.as<uint16_t>();
+    int32_t* namb = reinterpret_cast<int32_t*>(amb_addr + nq * AMB_MAX);
+    if ((rc = ws.counters.reserve(64))) return rc;
+    fill_u32_kernel<<<64, 256, 0, st>>>(range_bits, 0u, 2 * nq);
+    fill_u32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<uint32_t*>(ws.counters.as<int64_t>() + 4), 0u, 4);
     lut_T_kernel<<<dim3((unsigned)nq, m), 256, 0, st>>>(q, idx->codebooks, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax);
     lut_pair_kernel<<<(unsigned)npairs, 128, 0, st>>>(q, idx->centroids, probes, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
-                                                      ws.pair_lo.as<double>(), range_bits);
+                                                      ws.pair_lo.as<double>(), range_bits, mag_bits);
+    lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,
+                                                  ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(), ws.counters.as<int64_t>());
+    lut_patch_kernel<<<(unsigned)npairs, 128, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
+                                                       amb_addr, namb, nprobe, m, ws.bias.as<int32_t>(), ws.patch.as<uint8_t>());
     if (out_L_f32 || out_LUT8)
-        lut_quant_kernel<true><<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(),
-                                                                 range_bits, nprobe, m, lut8sw, bias, delta, out_L_f32, out_LUT8);
-    else
-        lut_quant_kernel<false><<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(),
-                                                                  range_bits, nprobe, m, lut8sw, bias, delta, nullptr, nullptr);
+        lut_expand_kernel<<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
+                                                            ws.lut8.as<uint8_t>(), amb_addr, namb, ws.patch.as<uint8_t>(), nprobe, m,
+                                                            out_L_f32, out_LUT8);
     RAGO_HIP(hipGetLastError());
+    out->lut_base = ws.lut8.as<uint8_t>();
+    out->amb_addr = amb_addr;
+    out->namb = namb;
+    out->patch_val = ws.patch.as<uint8_t>();
+    out->T64 = ws.T64.as<double>();
+    out->Tmin = ws.Tmin.as<double>();
+    out->t64 = ws.pair_lo.as<double>();
+    out->range_bits = range_bits;
+    out->bias = ws.bias.as<int32_t>();
+    out->delta = ws.delta.as<float>();
     return RAGO_OK;
 }
 

@@ -1,0 +1,44 @@
+// The one fp32 expression that defines an 8-bit table entry, shared by every kernel that may
+// have to evaluate it (patch builder, table expansion, the scan's per-pair path).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rago {
+
+constexpr int AMB_MAX = 512;   // ambiguous entries kept per query; more -> per-pair evaluation
+
+__device__ __forceinline__ float lut_step(float range) {
+    const float dq = range / 255.0f;
+    return dq > 0.0f ? dq : 1.0f;
+}
+
+// Half-width of the zone around a half-integer in which the per-pair fp32 result may differ from
+// rne((T - Tmin) / delta): twice the bound 2^-24 * ((2 M + range) / delta + 256).
+__device__ __forceinline__ double lut_eta(float range, float mag, float dq) {
+    return 2.0 * 5.9604644775390625e-08 * ((2.0 * (double)mag + (double)range) / (double)dq + 256.0);
+}
+
+// LUT8 entry from the fp64 per-query part Tv, the fp64 per-pair part t and the pair's fp32 minimum.
+__device__ __forceinline__ uint8_t lut_entry(double Tv, double t, float lo, float dq) {
+    const float L = (float)(Tv + t);
+    float r = rintf(__fdiv_rn(L - lo, dq));
+    r = r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r);
+    return (uint8_t)r;
+}
+
+// Everything a consumer needs to obtain the table of one (query, list) pair.
+struct LutTables {
+    const uint8_t* lut_base;    // [nq][256][128] swizzled base tables
+    const uint16_t* amb_addr;   // [nq][AMB_MAX] LDS byte offsets (code*256 + slot*4 + plane) of ambiguous entries
+    const int32_t* namb;        // [nq] number of ambiguous entries, AMB_MAX + 1 = evaluate per pair
+    const uint8_t* patch_val;   // [npairs][AMB_MAX] exact values of those entries
+    const double* T64;          // [nq][m][256]
+    const double* Tmin;         // [nq][m]
+    const double* t64;          // [npairs][m]
+    const uint32_t* range_bits; // [nq] float bits of max (hi - lo)
+    const int32_t* bias;        // [npairs]
+    const float* delta;         // [nq]
+};
+
+}  // namespace rago

@@ -5,6 +5,7 @@
 #include <string>
 
 #include "../../include/rago.h"
+#include "lut_common.h"
 
 namespace rago {
 
@@ -35,7 +36,7 @@ struct DevBuf {
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, cursor, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw;
+    DevBuf tmp_lut8sw, amb, patch;
     void release();
 };
 
@@ -88,14 +89,15 @@ int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, i
 
 // lut.hip
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,
-                     uint8_t* lut8sw, int32_t* bias, float* delta, float* out_L_f32, uint8_t* out_LUT8,
-                     hipStream_t st);
+                     LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st);
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
 
 // scan.hip
+// Tables come either per pair (`lut8sw` [npairs][256][128] + `bias`, `tables` null) or as per-query
+// base tables with per-pair patches (`tables`, `lut8sw` null).
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
-                const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores,
-                int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr);
+                const LutTables* tables, const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids,
+                float* out_scores, int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr);
 
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,

@@ -44,8 +44,10 @@ struct ScanParams {
     const int64_t* list_off;
     const int64_t* ids;
     const int32_t* probes;       // [npairs] list of each pair
-    const uint8_t* lut8sw;       // [npairs][256][128] swizzled tables
+    const uint8_t* lut8sw;       // [npairs][256][128] swizzled per-pair tables, or null: use `T`
+    LutTables T;                 // per-query base tables + per-pair patches
     const int32_t* bias;         // [npairs]
+    int m;
     const int32_t* pair_sorted;  // pairs grouped by list
     const int32_t* pair_off;     // [nlist+1]
     const int32_t* task_off;     // [nlist+1]
@@ -223,11 +225,48 @@ __device__ __forceinline__ void offer(bool valid, uint32_t sum, uint32_t pos, ui
     cnt += add;
 }
 
+// Copy swizzled tables (256 rows of 128 B) into the two halves of the 256-byte LDS rows; a null
+// source leaves that half untouched.
+__device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB, uint8_t* lut) {
+    uint4 ta[4], tb[4];
+    if (srcA) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ta[r] = srcA[threadIdx.x + r * SCAN_THREADS];
+    }
+    if (srcB) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tb[r] = srcB[threadIdx.x + r * SCAN_THREADS];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int piece = threadIdx.x + r * SCAN_THREADS;
+        uint8_t* dst = lut + (piece >> 3) * 256 + (piece & 7) * 16;
+        if (srcA) *reinterpret_cast<uint4*>(dst) = ta[r];
+        if (srcB) *reinterpret_cast<uint4*>(dst + 128) = tb[r];
+    }
+}
+
+struct ScanParams;
+__device__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot);
+
 template <int MPAD>
 __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t* blk, int lane) {
     const uint4* p = reinterpret_cast<const uint4*>(blk) + lane;
 #pragma unroll
     for (int i = 0; i < MPAD / 16; ++i) w[i] = p[i * 64];
+}
+
+// Full per-pair evaluation of a table straight into an LDS slot (queries whose tables are too
+// flat for the base + patch form).
+__device__ __noinline__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot) {
+    const int m = P.m, S = rago_steps(m);
+    const float dq = lut_step(__uint_as_float(P.T.range_bits[q]));
+    for (int e = threadIdx.x; e < m * KSUB; e += SCAN_THREADS) {
+        const int j = e >> 8, c = e & 255;
+        const double t = P.T.t64[(int64_t)pair * m + j];
+        const uint8_t v = lut_entry(P.T.T64[((int64_t)q * m + j) * KSUB + c], t, (float)(P.T.Tmin[(int64_t)q * m + j] + t), dq);
+        for (int rep = j & (S - 1); rep < 32; rep += S) slot[c * 256 + rep * 4 + (j >> 5)] = v;
+    }
 }
 
 // ------------------------------------------------------------------ the scan kernel
@@ -254,6 +293,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         off[g] = v;
     }
     const int ntasks = P.task_off[P.nlist];
+    int loadedA = -1, loadedB = -1;   // query whose base table currently sits in each LDS slot
     // selectors live in SGPRs (VOP3 takes no literal on gfx9); the asm fence keeps them out of constant folding
     uint32_t sel0 = RAGO_SEL0, sel1 = RAGO_SEL1, sel2 = RAGO_SEL2, sel3 = RAGO_SEL3;
     const int k = P.k;
@@ -288,33 +328,40 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         const int qA = pairA / P.nprobe, qB = pairB >= 0 ? pairB / P.nprobe : 0;
 
         // ---- tables into LDS (rows of 128 B into rows of 256 B), thresholds
-        {
+        if (P.lut8sw) {
             const uint4* srcA = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)pairA * LUT_BYTES);
             const uint4* srcB = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)(pairB >= 0 ? pairB : pairA) * LUT_BYTES);
-            uint4 ta[4], tb[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) ta[r] = srcA[threadIdx.x + r * SCAN_THREADS];
-            if (pairB >= 0) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) tb[r] = srcB[threadIdx.x + r * SCAN_THREADS];
+            copy_table(srcA, pairB >= 0 ? srcB : nullptr, lut);
+            loadedA = loadedB = -1;
+        } else {
+            // base table of the query (kept while consecutive tasks use the same query in this slot),
+            // then the pair's patches; flagged queries are evaluated entry by entry
+            const int nA = P.T.namb[qA], nB = pairB >= 0 ? P.T.namb[qB] : 0;
+            const bool baseA = nA <= AMB_MAX && loadedA != qA;
+            const bool baseB = pairB >= 0 && nB <= AMB_MAX && loadedB != qB;
+            copy_table(baseA ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qA * LUT_BYTES) : nullptr,
+                       baseB ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qB * LUT_BYTES) : nullptr, lut);
+            if (nA > AMB_MAX) eval_table(P, pairA, qA, lut);
+            if (pairB >= 0 && nB > AMB_MAX) eval_table(P, pairB, qB, lut + 128);
+            if (baseA || baseB) __syncthreads();   // patches overwrite bytes of the freshly copied rows
+            if (nA <= AMB_MAX)
+                for (int i = threadIdx.x; i < nA; i += SCAN_THREADS)
+                    lut[P.T.amb_addr[(int64_t)qA * AMB_MAX + i]] = P.T.patch_val[(int64_t)pairA * AMB_MAX + i];
+            if (pairB >= 0 && nB <= AMB_MAX)
+                for (int i = threadIdx.x; i < nB; i += SCAN_THREADS)
+                    lut[128 + P.T.amb_addr[(int64_t)qB * AMB_MAX + i]] = P.T.patch_val[(int64_t)pairB * AMB_MAX + i];
+            loadedA = nA <= AMB_MAX ? qA : -1;
+            if (pairB >= 0) loadedB = nB <= AMB_MAX ? qB : -1;
+        }
+        if (threadIdx.x < 2) {
+            const int pr = threadIdx.x == 0 ? pairA : pairB;
+            int32_t t0 = 0;
+            if (pr >= 0) {
+                const int32_t g = __hip_atomic_load(P.tauq + (threadIdx.x == 0 ? qA : qB), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int64_t t = (int64_t)g - (threadIdx.x == 0 ? biasA : biasB);
+                t0 = t <= 0 ? 0 : (t > 0x7fffffff ? 0x7fffffff : (int32_t)t);
             }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int piece = threadIdx.x + r * SCAN_THREADS;
-                uint8_t* dst = lut + (piece >> 3) * 256 + (piece & 7) * 16;
-                *reinterpret_cast<uint4*>(dst) = ta[r];
-                if (pairB >= 0) *reinterpret_cast<uint4*>(dst + 128) = tb[r];
-            }
-            if (threadIdx.x < 2) {
-                const int pr = threadIdx.x == 0 ? pairA : pairB;
-                int32_t t0 = 0;
-                if (pr >= 0) {
-                    const int32_t g = __hip_atomic_load(P.tauq + (threadIdx.x == 0 ? qA : qB), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const int64_t t = (int64_t)g - (threadIdx.x == 0 ? biasA : biasB);
-                    t0 = t <= 0 ? 0 : (t > 0x7fffffff ? 0x7fffffff : (int32_t)t);
-                }
-                sh[2 + threadIdx.x] = t0;
-            }
+            sh[2 + threadIdx.x] = t0;
         }
         __syncthreads();
 
@@ -573,9 +620,9 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
     return RAGO_OK;
 }
 
-int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias, const float* delta,
-                int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores, int32_t* out_iscores, hipStream_t st,
-                hipEvent_t* ev) {
+int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias, const LutTables* tables,
+                const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
+                hipStream_t st, hipEvent_t* ev) {
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
@@ -599,7 +646,8 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
 
     ScanParams P;
     P.codes = idx->codes_blk; P.blk_off = idx->blk_off; P.list_off = idx->list_off; P.ids = idx->ids;
-    P.probes = probes; P.lut8sw = lut8sw; P.bias = bias;
+    P.probes = probes; P.lut8sw = lut8sw; P.bias = bias; P.m = idx->m;
+    if (tables) P.T = *tables; else P.T = LutTables{};
     P.pair_sorted = ws.pair_sorted.as<int32_t>(); P.pair_off = ws.pair_off.as<int32_t>();
     P.task_off = ws.task_off.as<int32_t>(); P.task_counter = ws.task_off.as<int32_t>() + nlist + 1;
     P.tauq = ws.tauq.as<int32_t>(); P.part_I = ws.part_I.as<int32_t>(); P.part_id = ws.part_id.as<int64_t>();

@@ -322,14 +322,15 @@ def make_flat(cfg: FlatConfig, requests: Optional[int] = None, n: Optional[int] 
 
 # --------------------------------------------------------------------------- hand-made tiny index
 def random_index(n: int, d: int, m: int, nlist: int, seed: int, empty_lists=(), dup_codes: int = 0,
-                 shuffle_ids: bool = False) -> Dict[str, torch.Tensor]:
+                 shuffle_ids: bool = False, cb_scale: float = 0.3) -> Dict[str, torch.Tensor]:
     """Small index with random (untrained) centroids/codebooks/codes for brute-force checks.
     `empty_lists`: list numbers forced empty; `dup_codes`: that many vectors get a copy of
     another vector's code in the same list (forces exact score ties); `shuffle_ids`: ids are a
-    random permutation instead of 0..n-1 (still ascending inside each list)."""
+    random permutation instead of 0..n-1 (still ascending inside each list); `cb_scale`: magnitude of the
+    codewords relative to the centroids (tiny values give nearly constant look-up tables)."""
     g = _gen(seed, "cpu")
     centroids = torch.randn(nlist, d, generator=g) / math.sqrt(d)
-    codebooks = 0.3 * torch.randn(m, KSUB, d // m, generator=g) / math.sqrt(d)
+    codebooks = cb_scale * torch.randn(m, KSUB, d // m, generator=g) / math.sqrt(d)
     live = torch.tensor([l for l in range(nlist) if l not in set(empty_lists)])
     li = live[torch.randint(0, live.numel(), (n,), generator=g)]
     order = torch.sort(li, stable=True).indices

@@ -29,6 +29,10 @@ CASES = {
     "m32": (9000, 64, 32, 16, 9, 16, 10, dict()),
     "m64": (9000, 128, 64, 16, 9, 3, 128, dict(dup_codes=10)),
     "m128": (9000, 256, 128, 16, 4, 7, 1, dict()),
+    # codewords 1e5 times smaller than centroids: tables are flat relative to their magnitude, every entry
+    # is rounding-ambiguous, so the library must take its entry-by-entry evaluation path
+    "m96_flat_tables": (6000, 768, 96, 6, 4, 3, 20, dict(cb_scale=3e-6)),
+    "m16_flat_tables": (4000, 32, 16, 6, 5, 4, 20, dict(cb_scale=3e-6, dup_codes=20)),
 }
 
 
@@ -100,6 +104,12 @@ def test_tables_equal_oracle(case, rb):
     assert np.max(np.abs(gL8.astype(np.int32) - LUT8.astype(np.int32))) <= 1
     assert np.mean(gL8 == LUT8) >= 0.999
     assert np.array_equal(gL8, LUT8) and np.array_equal(gB, B)                     # in fact identical
+    cnt = rb.rago_debug_counters(h)
+    flat = np.abs(ix["codebooks"]).max() < 1e-4
+    if flat:
+        assert cnt[5] == len(Q)                 # every query took the entry-by-entry path
+    else:
+        assert cnt[5] == 0 and 0 < cnt[4] < 0.02 * len(Q) * m * 256     # base table + a few per-pair entries
 
 
 def test_search_end_to_end(case, rb):
