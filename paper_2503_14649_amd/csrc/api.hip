@@ -28,8 +28,8 @@ int DevBuf::reserve(size_t bytes) {
 void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
-                     &list_cnt, &pair_off, &task_off, &cursor, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch};
+                     &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched};
     for (DevBuf* b : all) b->release();
 }
 
@@ -230,6 +230,7 @@ static int check_search_args(const rago_index* idx, const void* a, const void* b
     if (nprobe < 1 || nprobe > idx->nlist) return fail(RAGO_INVALID_ARG, "nprobe must be in [1, nlist]");
     if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
     if (k > KMAX) return fail(RAGO_UNSUPPORTED, "k > 128");
+    if (nprobe > 2048) return fail(RAGO_UNSUPPORTED, "nprobe > 2048");
     if (nq * (int64_t)nprobe > (1ll << 30)) return fail(RAGO_UNSUPPORTED, "nq * nprobe > 2^30");
     return RAGO_OK;
 }

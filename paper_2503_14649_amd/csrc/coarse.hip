@@ -131,33 +131,65 @@ __device__ __forceinline__ uint32_t float_key(float f) {  // ascending uint orde
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// REG = fp32 scores held per thread (nlist <= REG * 1024: the row is read from memory once).
+// REG = 0: rows of any length, re-read from L2 in every pass.
+template <int REG>
 __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                              const float* __restrict__ S, int nlist, int d, int nprobe,
                                                              float max_cnorm, int32_t* __restrict__ probes,
                                                              int64_t* __restrict__ counters) {
+    // 32 copies of every bin, copy = lane % 32: the lanes of a half-wave never share an LDS word,
+    // so the atomics run at full rate even when all scores fall into one bin (pass 0: same exponent)
+    __shared__ int hist32[256 * 32];
     __shared__ int hist[256];
     __shared__ uint32_t s_prefix;
-    __shared__ int s_rem;
-    __shared__ int s_wgt[SEL_WAVES], s_weq[SEL_WAVES];
+    __shared__ int s_rem, s_ngt, s_neq;
+    __shared__ int s_weq[SEL_WAVES];
     __shared__ int c_idx[SEL_CAP];
     __shared__ float c_val[SEL_CAP];
-    __shared__ float s_qn[SEL_WAVES];
     const int64_t q = blockIdx.x;
     const float* row = S + q * nlist;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int want = min(nprobe + SEL_EXTRA, nlist);
+    constexpr int NR = REG > 0 ? REG : 1;
+    uint32_t key[NR];
+    if (REG > 0) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const int i = r * SEL_THREADS + tid;
+            key[r] = i < nlist ? float_key(row[i]) : 0u;      // 0 sorts below every real score
+        }
+    }
+    const int nrounds = REG > 0 ? REG : (nlist + SEL_THREADS - 1) / SEL_THREADS;
+    auto key_at = [&](int r) -> uint32_t {
+        if (REG > 0) return key[r];
+        const int i = r * SEL_THREADS + tid;
+        return i < nlist ? float_key(row[i]) : 0u;
+    };
 
     // ---- radix select: key of the want-th largest score
-    if (tid == 0) { s_prefix = 0; s_rem = want; }
+    if (tid == 0) { s_prefix = 0; s_rem = want; s_ngt = 0; s_neq = 0; }
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
+        for (int i = tid; i < 256 * 32; i += SEL_THREADS) hist32[i] = 0;
         __syncthreads();
         const uint32_t prefix = s_prefix;
         const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int i = tid; i < nlist; i += SEL_THREADS) {
-            const uint32_t key = float_key(row[i]);
-            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+        auto count = [&](uint32_t kk, int i) {
+            if (i < nlist && (kk & himask) == prefix) atomicAdd(&hist32[(((kk >> shift) & 255u) << 5) | (lane & 31)], 1);
+        };
+        if (REG > 0) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) count(key[r], r * SEL_THREADS + tid);
+        } else {
+            for (int r = 0; r < nrounds; ++r) count(key_at(r), r * SEL_THREADS + tid);
+        }
+        __syncthreads();
+        if (tid < 256) {
+            int tot = 0;
+#pragma unroll
+            for (int c = 0; c < 32; ++c) tot += hist32[(tid << 5) | ((c + tid) & 31)];   // rotated: no bank conflicts
+            hist[tid] = tot;
         }
         __syncthreads();
         if (tid == 0) {
@@ -173,33 +205,64 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     }
     const uint32_t kth = s_prefix;   // exact key of the want-th largest
     const int need_eq = s_rem;       // how many of the entries equal to it are taken (lowest lists first)
+    const int total_eq = hist[(kth)&255];
+    const int gt_total = want - need_eq;
 
-    // ---- ordered collection: wave w owns a contiguous range, lanes interleaved
-    const int seg = ((nlist + SEL_WAVES - 1) / SEL_WAVES + 63) / 64 * 64;
-    const int a0 = wave * seg, a1 = min(nlist, a0 + seg);
-    int ngt = 0, neq = 0;
-    for (int i = a0 + lane; i < a0 + seg; i += 64) {
-        const uint32_t key = i < a1 ? float_key(row[i]) : 0u;
-        ngt += __popcll(__ballot(i < a1 && key > kth));
-        neq += __popcll(__ballot(i < a1 && key == kth));
+    // ---- collection: entries above the cut in any order; entries AT the cut by ascending list
+    auto collect_gt = [&](uint32_t kk, int i) {
+        const bool g = i < nlist && kk > kth;
+        const uint64_t mg = __ballot(g);
+        if (mg) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_ngt, __popcll(mg));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (g) c_idx[base + __popcll(mg & ((1ull << lane) - 1ull))] = i;
+        }
+    };
+    if (REG > 0) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) collect_gt(key[r], r * SEL_THREADS + tid);
+    } else {
+        for (int r = 0; r < nrounds; ++r) collect_gt(key_at(r), r * SEL_THREADS + tid);
     }
-    if (lane == 0) { s_wgt[wave] = ngt; s_weq[wave] = neq; }
-    __syncthreads();
-    int gt_base = 0, eq_base = 0, gt_total = 0;
-    for (int w = 0; w < SEL_WAVES; ++w) {
-        if (w < wave) { gt_base += s_wgt[w]; eq_base += s_weq[w]; }
-        gt_total += s_wgt[w];
-    }
-    for (int i = a0 + lane; i < a0 + seg; i += 64) {
-        const float v = i < a1 ? row[i] : 0.f;
-        const uint32_t key = i < a1 ? float_key(v) : 0u;
-        const bool g = i < a1 && key > kth, e = i < a1 && key == kth;
-        const uint64_t mg = __ballot(g), me = __ballot(e);
-        const uint64_t below = (1ull << lane) - 1ull;
-        if (g) { const int o = gt_base + __popcll(mg & below); c_idx[o] = i; }
-        if (e) { const int o = eq_base + __popcll(me & below); if (o < need_eq) c_idx[gt_total + o] = i; }
-        gt_base += __popcll(mg);
-        eq_base += __popcll(me);
+    if (total_eq == need_eq) {       // every tie is taken: order is irrelevant here (sorted later)
+        auto collect_eq = [&](uint32_t kk, int i) {
+            const bool e = i < nlist && kk == kth;
+            const uint64_t me = __ballot(e);
+            if (me) {
+                int base = 0;
+                if (lane == 0) base = atomicAdd(&s_neq, __popcll(me));
+                base = __builtin_amdgcn_readfirstlane(base);
+                if (e) c_idx[gt_total + base + __popcll(me & ((1ull << lane) - 1ull))] = i;
+            }
+        };
+        if (REG > 0) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) collect_eq(key[r], r * SEL_THREADS + tid);
+        } else {
+            for (int r = 0; r < nrounds; ++r) collect_eq(key_at(r), r * SEL_THREADS + tid);
+        }
+    } else {
+        // ties straddle the cut (rare): walk the row in list order, round by round
+        int eq_base = 0;
+        for (int r = 0; r < nrounds && eq_base < need_eq; ++r) {
+            const int i = r * SEL_THREADS + tid;
+            uint32_t kk = 0;
+            if (REG > 0) {
+#pragma unroll
+                for (int rr = 0; rr < NR; ++rr) if (rr == r) kk = key[rr];
+            } else kk = key_at(r);
+            const bool e = i < nlist && kk == kth;
+            const uint64_t me = __ballot(e);
+            __syncthreads();
+            if (lane == 0) s_weq[wave] = __popcll(me);
+            __syncthreads();
+            int before = 0, tot = 0;
+            for (int w = 0; w < SEL_WAVES; ++w) { if (w < wave) before += s_weq[w]; tot += s_weq[w]; }
+            const int o = eq_base + before + __popcll(me & ((1ull << lane) - 1ull));
+            if (e && o < need_eq) c_idx[gt_total + o] = i;
+            eq_base += tot;
+        }
     }
     __syncthreads();
 
@@ -208,12 +271,22 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     float qn = 0.f;
     for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
     for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
-    for (int ci = wave; ci < want; ci += SEL_WAVES) {
-        const float* cv = C + (int64_t)c_idx[ci] * d;
-        double acc = 0.0;
-        for (int t = lane; t < d; t += 64) acc = acc + (double)qv[t] * (double)cv[t];
-        for (int o = 32; o; o >>= 1) acc = acc + __shfl_xor(acc, o);
-        if (lane == 0) c_val[ci] = (float)acc;
+    // (four candidates per wave at a time, so four rows are in flight instead of one)
+    for (int c0 = wave * 4; c0 < want; c0 += SEL_WAVES * 4) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        const float* cv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d;
+        for (int t = lane; t < d; t += 64) {
+            const double qt = (double)qv[t];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
+            if (lane == 0 && c0 + u < want) c_val[c0 + u] = (float)acc[u];
+        }
     }
     int n2 = 1;
     while (n2 < want) n2 <<= 1;
@@ -252,8 +325,16 @@ int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, i
     int rc;
     if ((rc = idx->ws.counters.reserve(64))) return rc;
     zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
-    select_kernel<<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, idx->nlist, idx->d, nprobe, idx->max_cnorm, probes,
-                                                        idx->ws.counters.as<int64_t>());
+    int64_t* cnt = idx->ws.counters.as<int64_t>();
+    const int nl = idx->nlist;
+    if (nl <= 8 * SEL_THREADS)
+        select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+    else if (nl <= 32 * SEL_THREADS)
+        select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+    else if (nl <= 64 * SEL_THREADS)
+        select_kernel<64><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+    else
+        select_kernel<0><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }

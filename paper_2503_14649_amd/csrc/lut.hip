@@ -34,9 +34,15 @@ namespace rago {
 
 // T64[q][j][c], Tmin/Tmax[q][j].  grid (nq, m), 256 threads = one per codeword.
 __global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int d, int m,
-                                                    double* __restrict__ T64, double* __restrict__ Tmin, double* __restrict__ Tmax) {
+                                                    double* __restrict__ T64, double* __restrict__ Tmin, double* __restrict__ Tmax,
+                                                    uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
+                                                    int64_t* __restrict__ counters) {
     const int j = blockIdx.y, c = threadIdx.x;
     const int64_t q = blockIdx.x;
+    if (j == 0 && c == 0) {   // running maxima of the pair kernel and the table counters start at zero
+        range_bits[q] = 0u; mag_bits[q] = 0u;
+        if (q == 0) { counters[4] = 0; counters[5] = 0; }
+    }
     const int dsub = d / m;
     const float* qv = Q + q * d + j * dsub;
     const float* cb = CB + ((int64_t)j * KSUB + c) * dsub;
@@ -249,9 +255,8 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     uint16_t* amb_addr = ws.amb.as<uint16_t>();
     int32_t* namb = reinterpret_cast<int32_t*>(amb_addr + nq * AMB_MAX);
     if ((rc = ws.counters.reserve(64))) return rc;
-    fill_u32_kernel<<<64, 256, 0, st>>>(range_bits, 0u, 2 * nq);
-    fill_u32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<uint32_t*>(ws.counters.as<int64_t>() + 4), 0u, 4);
-    lut_T_kernel<<<dim3((unsigned)nq, m), 256, 0, st>>>(q, idx->codebooks, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax);
+    lut_T_kernel<<<dim3((unsigned)nq, m), 256, 0, st>>>(q, idx->codebooks, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax,
+                                                        range_bits, mag_bits, ws.counters.as<int64_t>());
     lut_pair_kernel<<<(unsigned)npairs, 128, 0, st>>>(q, idx->centroids, probes, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
                                                       ws.pair_lo.as<double>(), range_bits, mag_bits);
     lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,

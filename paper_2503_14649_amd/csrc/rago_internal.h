@@ -35,8 +35,8 @@ struct DevBuf {
 
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
-    DevBuf list_cnt, pair_off, task_off, cursor, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch;
+    DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
+    DevBuf tmp_lut8sw, amb, patch, touched;
     void release();
 };
 

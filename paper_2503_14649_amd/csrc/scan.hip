@@ -36,7 +36,8 @@ constexpr int SCAN_WAVES = 8;
 constexpr int SCAN_THREADS = SCAN_WAVES * 64;
 constexpr int CAPW = 192;  // keys per (wave, pair) buffer: k <= 128 survivors + one block of 64
 constexpr int LUT_LDS = 65536;
-constexpr int SCAN_LDS = LUT_LDS + SCAN_WAVES * 2 * CAPW * 4 + 256;
+constexpr int SCAN_LDS = LUT_LDS + SCAN_WAVES * 2 * CAPW * 4 + 512;
+constexpr int DESC_INTS = 20;   // task descriptor in LDS (see fetch_task)
 
 struct ScanParams {
     const uint8_t* codes;
@@ -49,9 +50,8 @@ struct ScanParams {
     const int32_t* bias;         // [npairs]
     int m;
     const int32_t* pair_sorted;  // pairs grouped by list
-    const int32_t* pair_off;     // [nlist+1]
-    const int32_t* task_off;     // [nlist+1]
-    int32_t* task_counter;
+    const int4* task_table;      // [ntasks] {list, chunk, pairA, pairB (-1: none)}
+    int32_t* ctrl;               // [0] task counter, [1] number of tasks
     int32_t* tauq;               // [nq] lower bound of the k-th best integer score
     int32_t* part_I;             // [npairs][maxchunks][k]
     int64_t* part_id;
@@ -226,8 +226,11 @@ __device__ __forceinline__ void offer(bool valid, uint32_t sum, uint32_t pos, ui
 }
 
 // Copy swizzled tables (256 rows of 128 B) into the two halves of the 256-byte LDS rows; a null
-// source leaves that half untouched.
-__device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB, uint8_t* lut) {
+// source leaves that half untouched.  `between` runs after the loads are issued and before their
+// data is needed (the caller puts the first code-block loads there, so they queue behind the
+// table loads instead of in front of them: the load counter retires in order).
+template <class F>
+__device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB, uint8_t* lut, F between) {
     uint4 ta[4], tb[4];
     if (srcA) {
 #pragma unroll
@@ -237,6 +240,7 @@ __device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB,
 #pragma unroll
         for (int r = 0; r < 4; ++r) tb[r] = srcB[threadIdx.x + r * SCAN_THREADS];
     }
+    between();
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int piece = threadIdx.x + r * SCAN_THREADS;
@@ -249,16 +253,25 @@ __device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB,
 struct ScanParams;
 __device__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot);
 
+// The code stream is read through pointers explicitly in the global address space: a generic
+// (flat) load would also count on the LDS/scalar wait counter and every hand-placed
+// s_waitcnt lgkmcnt in the look-up code would then wait for HBM.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
+
 template <int MPAD>
 __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t* blk, int lane) {
-    const uint4* p = reinterpret_cast<const uint4*>(blk) + lane;
+    global_u32x4_ptr p = (global_u32x4_ptr)(reinterpret_cast<const u32x4*>(blk) + lane);
 #pragma unroll
-    for (int i = 0; i < MPAD / 16; ++i) w[i] = p[i * 64];
+    for (int i = 0; i < MPAD / 16; ++i) {
+        const u32x4 v = p[i * 64];
+        w[i] = make_uint4(v.x, v.y, v.z, v.w);
+    }
 }
 
 // Full per-pair evaluation of a table straight into an LDS slot (queries whose tables are too
 // flat for the base + patch form).
-__device__ __noinline__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot) {
+__device__ __forceinline__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot) {
     const int m = P.m, S = rago_steps(m);
     const float dq = lut_step(__uint_as_float(P.T.range_bits[q]));
     for (int e = threadIdx.x; e < m * KSUB; e += SCAN_THREADS) {
@@ -266,6 +279,31 @@ __device__ __noinline__ void eval_table(const ScanParams& P, int pair, int q, ui
         const double t = P.T.t64[(int64_t)pair * m + j];
         const uint8_t v = lut_entry(P.T.T64[((int64_t)q * m + j) * KSUB + c], t, (float)(P.T.Tmin[(int64_t)q * m + j] + t), dq);
         for (int rep = j & (S - 1); rep < 32; rep += S) slot[c * 256 + rep * 4 + (j >> 5)] = v;
+    }
+}
+
+// Claim the next task and put everything its prologue needs into LDS (run by ONE wave; all
+// values are wave-uniform so the loads are scalar).  d[0] = task number or -1 when none is left.
+__device__ __forceinline__ void fetch_task(const ScanParams& P, int ntasks, int32_t* d, int lane) {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(P.ctrl, 1);
+    t = __builtin_amdgcn_readfirstlane(t);
+    if (t >= ntasks) {
+        if (lane == 0) d[0] = -1;
+        return;
+    }
+    const int4 rec = P.task_table[t];
+    const int l = rec.x, pairA = rec.z, pairB = rec.w;
+    const int64_t b0 = P.blk_off[l], v0 = P.list_off[l];
+    const int nblk = (int)(P.blk_off[l + 1] - b0), len = (int)(P.list_off[l + 1] - v0);
+    const int qA = pairA / P.nprobe, qB = pairB >= 0 ? pairB / P.nprobe : 0;
+    const int biasA = P.bias[pairA], biasB = pairB >= 0 ? P.bias[pairB] : 0;
+    int nA = 0, nB = 0;
+    if (!P.lut8sw) { nA = P.T.namb[qA]; nB = pairB >= 0 ? P.T.namb[qB] : 0; }
+    if (lane == 0) {
+        d[0] = t; d[1] = l; d[2] = rec.y; d[3] = pairA; d[4] = pairB; d[5] = biasA; d[6] = biasB; d[7] = qA; d[8] = qB;
+        d[9] = (int32_t)(uint32_t)b0; d[10] = (int32_t)(b0 >> 32); d[11] = nblk;
+        d[12] = (int32_t)(uint32_t)v0; d[13] = (int32_t)(v0 >> 32); d[14] = len; d[15] = nA; d[16] = nB;
     }
 }
 
@@ -277,7 +315,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
     uint8_t* lut = smem;
     uint32_t* cand = reinterpret_cast<uint32_t*>(smem + LUT_LDS);                         // [wave][pair][CAPW]
     int32_t* sh = reinterpret_cast<int32_t*>(smem + LUT_LDS + SCAN_WAVES * 2 * CAPW * 4);  // scalars
-    // sh[0] task number, sh[2..3] tau per pair (sum units), sh[8 + wave*2 + pair] wave counts
+    // sh[2..3] tau per pair (sum units), sh[8 + wave*2 + pair] wave counts, sh[32..] descriptors
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     uint32_t off[S / 4];
@@ -292,64 +330,78 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         }
         off[g] = v;
     }
-    const int ntasks = P.task_off[P.nlist];
+    const int ntasks = P.ctrl[1];
     int loadedA = -1, loadedB = -1;   // query whose base table currently sits in each LDS slot
     // selectors live in SGPRs (VOP3 takes no literal on gfx9); the asm fence keeps them out of constant folding
     uint32_t sel0 = RAGO_SEL0, sel1 = RAGO_SEL1, sel2 = RAGO_SEL2, sel3 = RAGO_SEL3;
     const int k = P.k;
+    int32_t* desc = sh + 32;          // two task descriptors: the running task and the prefetched next one
 
-    for (;;) {
-        if (threadIdx.x == 0) sh[0] = atomicAdd(P.task_counter, 1);
-        __syncthreads();
-        const int tid = __builtin_amdgcn_readfirstlane(sh[0]);
-        if (tid >= ntasks) break;
-        // ---- decode the task
-        int lo = 0, hi = P.nlist;  // largest l with task_off[l] <= tid
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (P.task_off[mid] <= tid) lo = mid; else hi = mid;
-        }
-        const int l = lo;
-        const int rem = tid - P.task_off[l];
-        const int npl = P.pair_off[l + 1] - P.pair_off[l];
-        const int ngroups = (npl + 1) >> 1;
-        const int chunk = rem / ngroups, grp = rem - chunk * ngroups;
-        const int pairA = P.pair_sorted[P.pair_off[l] + 2 * grp];
-        const int pairB = (2 * grp + 1 < npl) ? P.pair_sorted[P.pair_off[l] + 2 * grp + 1] : -1;
-        const int64_t b0 = P.blk_off[l];
-        const int nblk_list = (int)(P.blk_off[l + 1] - b0);
-        const int64_t v0 = P.list_off[l];
-        const int len = (int)(P.list_off[l + 1] - v0);
+    if (wave == SCAN_WAVES - 1) fetch_task(P, ntasks, desc, lane);
+    __syncthreads();
+    for (int cur = 0;; cur ^= 1) {
+        const int32_t* D = desc + cur * DESC_INTS;
+        const int tid = __builtin_amdgcn_readfirstlane(D[0]);
+        if (tid < 0) break;           // every wave reads the same descriptor: all leave together
+        const int chunk = __builtin_amdgcn_readfirstlane(D[2]);
+        const int pairA = __builtin_amdgcn_readfirstlane(D[3]), pairB = __builtin_amdgcn_readfirstlane(D[4]);
+        const int biasA = __builtin_amdgcn_readfirstlane(D[5]), biasB = __builtin_amdgcn_readfirstlane(D[6]);
+        const int qA = __builtin_amdgcn_readfirstlane(D[7]), qB = __builtin_amdgcn_readfirstlane(D[8]);
+        const int64_t b0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[10]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[9]);
+        const int nblk_list = __builtin_amdgcn_readfirstlane(D[11]);
+        const int64_t v0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[13]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[12]);
+        const int len = __builtin_amdgcn_readfirstlane(D[14]);
+        const int nA = __builtin_amdgcn_readfirstlane(D[15]), nB = __builtin_amdgcn_readfirstlane(D[16]);
         const int cb0 = chunk * P.CH;
         const int nb = min(P.CH, nblk_list - cb0);
         const int cvec0 = cb0 * BLOCK_VECS;          // first vector of the chunk inside the list
         const int cvecs = min(len - cvec0, nb * BLOCK_VECS);
-        const int biasA = P.bias[pairA], biasB = pairB >= 0 ? P.bias[pairB] : 0;
-        const int qA = pairA / P.nprobe, qB = pairB >= 0 ? pairB / P.nprobe : 0;
+        // the wave's first block is requested before the tables are touched
+        constexpr int64_t BLK_BYTES = BLOCK_VECS * MPAD;
+        const uint8_t* base = P.codes + (b0 + cb0) * BLK_BYTES;
+        uint4 cur_w[MPAD / 16], nxt_w[MPAD / 16];
+        int b = wave;
+        // (every load of the stream is unconditional, with the block number clamped into the chunk: a
+        // conditional prefetch makes the compiler wait for ALL outstanding loads before each use)
+        auto first_load = [&]() { load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane); };
 
         // ---- tables into LDS (rows of 128 B into rows of 256 B), thresholds
         if (P.lut8sw) {
             const uint4* srcA = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)pairA * LUT_BYTES);
             const uint4* srcB = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)(pairB >= 0 ? pairB : pairA) * LUT_BYTES);
-            copy_table(srcA, pairB >= 0 ? srcB : nullptr, lut);
+            copy_table(srcA, pairB >= 0 ? srcB : nullptr, lut, first_load);
             loadedA = loadedB = -1;
         } else {
             // base table of the query (kept while consecutive tasks use the same query in this slot),
             // then the pair's patches; flagged queries are evaluated entry by entry
-            const int nA = P.T.namb[qA], nB = pairB >= 0 ? P.T.namb[qB] : 0;
             const bool baseA = nA <= AMB_MAX && loadedA != qA;
             const bool baseB = pairB >= 0 && nB <= AMB_MAX && loadedB != qB;
+            // Patches are written by the wave that copies the 16-byte piece they fall into, so program
+            // order inside the wave puts them after the copy and no workgroup barrier is needed in between.
+            // Piece of LDS offset a: row a >> 8, column (a & 127) >> 4; copied by thread (piece & 511).
+            // (the arrays always hold AMB_MAX entries, so the first 64 can be read unconditionally)
+            const bool useA = nA <= AMB_MAX, useB = pairB >= 0 && nB <= AMB_MAX;
+            const uint32_t a0 = P.T.amb_addr[(int64_t)qA * AMB_MAX + lane];
+            const uint32_t v0 = P.T.patch_val[(int64_t)pairA * AMB_MAX + lane];
+            const uint32_t a1 = P.T.amb_addr[(int64_t)(pairB >= 0 ? qB : qA) * AMB_MAX + lane];
+            const uint32_t v1 = P.T.patch_val[(int64_t)(pairB >= 0 ? pairB : pairA) * AMB_MAX + lane];
             copy_table(baseA ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qA * LUT_BYTES) : nullptr,
-                       baseB ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qB * LUT_BYTES) : nullptr, lut);
+                       baseB ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qB * LUT_BYTES) : nullptr, lut, first_load);
             if (nA > AMB_MAX) eval_table(P, pairA, qA, lut);
             if (pairB >= 0 && nB > AMB_MAX) eval_table(P, pairB, qB, lut + 128);
-            if (baseA || baseB) __syncthreads();   // patches overwrite bytes of the freshly copied rows
-            if (nA <= AMB_MAX)
-                for (int i = threadIdx.x; i < nA; i += SCAN_THREADS)
-                    lut[P.T.amb_addr[(int64_t)qA * AMB_MAX + i]] = P.T.patch_val[(int64_t)pairA * AMB_MAX + i];
-            if (pairB >= 0 && nB <= AMB_MAX)
-                for (int i = threadIdx.x; i < nB; i += SCAN_THREADS)
-                    lut[128 + P.T.amb_addr[(int64_t)qB * AMB_MAX + i]] = P.T.patch_val[(int64_t)pairB * AMB_MAX + i];
+            auto owner = [](uint32_t a) { return ((((a >> 8) << 3) | ((a & 127u) >> 4)) & 511u) >> 6; };
+            if (useA && lane < nA && owner(a0) == (uint32_t)wave) lut[a0] = (uint8_t)v0;
+            if (useB && lane < nB && owner(a1) == (uint32_t)wave) lut[128 + a1] = (uint8_t)v1;
+            if (useA)
+                for (int i = 64 + lane; i < nA; i += 64) {
+                    const uint32_t a = P.T.amb_addr[(int64_t)qA * AMB_MAX + i];
+                    if (owner(a) == (uint32_t)wave) lut[a] = P.T.patch_val[(int64_t)pairA * AMB_MAX + i];
+                }
+            if (useB)
+                for (int i = 64 + lane; i < nB; i += 64) {
+                    const uint32_t a = P.T.amb_addr[(int64_t)qB * AMB_MAX + i];
+                    if (owner(a) == (uint32_t)wave) lut[128 + a] = P.T.patch_val[(int64_t)pairB * AMB_MAX + i];
+                }
             loadedA = nA <= AMB_MAX ? qA : -1;
             if (pairB >= 0) loadedB = nB <= AMB_MAX ? qB : -1;
         }
@@ -362,6 +414,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
                 t0 = t <= 0 ? 0 : (t > 0x7fffffff ? 0x7fffffff : (int32_t)t);
             }
             sh[2 + threadIdx.x] = t0;
+            if (threadIdx.x == 0) sh[4] = SCAN_WAVES;   // next unclaimed block of the chunk
         }
         __syncthreads();
 
@@ -370,8 +423,8 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         uint32_t* bufB = cand + (wave * 2 + 1) * CAPW;
         int cntA = 0, cntB = 0;
         uint32_t thrA = (uint32_t)sh[2], thrB = (uint32_t)sh[3];
-        const uint8_t* base = P.codes + (b0 + cb0) * (int64_t)(BLOCK_VECS * MPAD);
-        uint4 cur[MPAD / 16], nxt[MPAD / 16];
+        // one wave claims and decodes the next task while its first loads are in flight
+        if (wave == SCAN_WAVES - 1) fetch_task(P, ntasks, desc + (cur ^ 1) * DESC_INTS, lane);
         auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
             const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
             const bool valid = (int)pos < cvecs;
@@ -390,17 +443,23 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
                 offer(valid, sa, pos, bufA, cntA, thrA, sh + 2, k, lane);
             }
         };
-        constexpr int64_t BLK_BYTES = BLOCK_VECS * MPAD;
-        int b = wave;
-        if (b < nb) load_block<MPAD>(cur, base + (int64_t)b * BLK_BYTES, lane);
-        for (; b < nb; b += 2 * SCAN_WAVES) {   // ping-pong between the two register sets
-            const int b1 = b + SCAN_WAVES, b2 = b + 2 * SCAN_WAVES;
-            if (b1 < nb) load_block<MPAD>(nxt, base + (int64_t)b1 * BLK_BYTES, lane);
-            process(cur, b);
-            if (b1 < nb) {
-                if (b2 < nb) load_block<MPAD>(cur, base + (int64_t)b2 * BLK_BYTES, lane);
-                process(nxt, b1);
-            }
+        // blocks beyond each wave's first are claimed from an LDS counter: a wave that was held up
+        // (the one that fetched the next task, one that pruned) simply takes fewer
+        auto claim = [&]() {
+            int v = 0;
+            if (lane == 0) v = atomicAdd(&sh[4], 1);
+            return __builtin_amdgcn_readfirstlane(v);
+        };
+        int bn = claim();
+        load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
+        while (b < nb) {                       // ping-pong between the two register sets
+            process(cur_w, b);
+            b = claim();
+            load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane);
+            if (bn >= nb) break;               // claims are monotonic: nothing newer can be valid either
+            process(nxt_w, bn);
+            bn = claim();
+            load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
         }
         // ---- task result: every wave trims its buffers to k, then one wave per pair merges
         if (cntA > k) wave_prune(bufA, cntA, k, lane);
@@ -449,69 +508,115 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
 }
 
 // ------------------------------------------------------------------ task bookkeeping kernels
-__global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+// The (query, list) pairs are grouped by list without ever touching all nlist lists: the first
+// pair that reaches a list registers it in `touched`; prefix sums run over the touched lists only
+// (at most one per pair), so a single query costs a few hundred entries, not nlist.
+// ctrl[0] task counter, ctrl[1] number of tasks, ctrl[2] number of touched lists.
+__global__ void scan_init_kernel(int32_t* __restrict__ list_cnt2, int64_t n2, int32_t* __restrict__ tauq, int64_t nq,
+                                 int32_t* __restrict__ ctrl) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = i; j < n2; j += stride) list_cnt2[j] = 0;     // list_cnt and cursor
+    for (int64_t j = i; j < nq; j += stride) tauq[j] = INT32_MIN;
+    if (i < 4) ctrl[i] = 0;
 }
 
-__global__ void count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int32_t* __restrict__ list_cnt) {
+__global__ void count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int32_t* __restrict__ list_cnt,
+                                   int32_t* __restrict__ touched, int32_t* __restrict__ ctrl) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < npairs) atomicAdd(&list_cnt[probes[i]], 1);
+    if (i >= npairs) return;
+    const int l = probes[i];
+    if (atomicAdd(&list_cnt[l], 1) == 0) touched[atomicAdd(&ctrl[2], 1)] = l;
 }
 
-// Exclusive prefix sums over lists (one workgroup): pair_off, task_off, and the byte counters.
-__global__ void __launch_bounds__(1024) list_offsets_kernel(const int32_t* __restrict__ list_cnt, const int64_t* __restrict__ blk_off,
-                                                            const int64_t* __restrict__ list_off, int nlist, int CH, int m,
-                                                            int32_t* __restrict__ pair_off, int32_t* __restrict__ task_off,
-                                                            int32_t* __restrict__ task_counter, int64_t* __restrict__ counters) {
-    __shared__ int s_p[1024], s_t[1024];
+// Exclusive prefix sums over the touched lists (one workgroup, 4 entries per thread and tile).
+__global__ void __launch_bounds__(1024) touched_offsets_kernel(const int32_t* __restrict__ touched, const int32_t* __restrict__ list_cnt,
+                                                               const int64_t* __restrict__ blk_off, const int64_t* __restrict__ list_off,
+                                                               int CH, int m, int32_t* __restrict__ list_slot,
+                                                               int32_t* __restrict__ pair_off, int32_t* __restrict__ task_off,
+                                                               int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
+    __shared__ int s_wp[16], s_wt[16];
     __shared__ unsigned long long s_bytes[2];
-    const int t = threadIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int n = ctrl[2];
     if (t < 2) s_bytes[t] = 0;
-    const int per = (nlist + 1023) / 1024;
-    const int a = min(nlist, t * per), e = min(nlist, a + per);
-    int sp = 0, stt = 0;
+    int carry_p = 0, carry_t = 0;
     unsigned long long streamed = 0, algo = 0;
-    for (int l = a; l < e; ++l) {
-        const int c = list_cnt[l];
-        const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
-        sp += c;
-        stt += ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
-        streamed += (unsigned long long)((c + 1) >> 1) * nblk * (BLOCK_VECS * m);
-        algo += (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
-    }
-    s_p[t] = sp; s_t[t] = stt;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        int vp = 0, vt = 0;
-        if (t >= o) { vp = s_p[t - o]; vt = s_t[t - o]; }
+    for (int base = 0; base < n; base += 4096) {
+        int vp[4], vt[4], ll[4];
+        int sp = 0, st = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = base + t * 4 + e;
+            vp[e] = 0; vt[e] = 0; ll[e] = -1;
+            if (i < n) {
+                const int l = touched[i];
+                const int c = list_cnt[l];
+                const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
+                ll[e] = l; vp[e] = c; vt[e] = ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
+                streamed += (unsigned long long)((c + 1) >> 1) * nblk * (BLOCK_VECS * m);
+                algo += (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
+            }
+            sp += vp[e]; st += vt[e];
+        }
+        int ip = sp, it = st;                      // inclusive scan across the wave
+        for (int o = 1; o < 64; o <<= 1) {
+            const int a = __shfl_up(ip, o), b = __shfl_up(it, o);
+            if (lane >= o) { ip += a; it += b; }
+        }
+        __syncthreads();                           // previous tile's wave totals consumed
+        if (lane == 63) { s_wp[wave] = ip; s_wt[wave] = it; }
         __syncthreads();
-        s_p[t] += vp; s_t[t] += vt;
-        __syncthreads();
-    }
-    int bp = s_p[t] - sp, bt = s_t[t] - stt;  // exclusive
-    for (int l = a; l < e; ++l) {
-        const int c = list_cnt[l];
-        const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
-        pair_off[l] = bp; task_off[l] = bt;
-        bp += c;
-        bt += ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
+        int wp = 0, wt = 0, tot_p = 0, tot_t = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) { wp += s_wp[w]; wt += s_wt[w]; }
+            tot_p += s_wp[w]; tot_t += s_wt[w];
+        }
+        int ep = carry_p + wp + ip - sp, et = carry_t + wt + it - st;   // exclusive offsets of this thread's first entry
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = base + t * 4 + e;
+            if (i < n) { pair_off[i] = ep; task_off[i] = et; list_slot[ll[e]] = i; }
+            ep += vp[e]; et += vt[e];
+        }
+        carry_p += tot_p; carry_t += tot_t;
     }
     atomicAdd(&s_bytes[0], streamed);
     atomicAdd(&s_bytes[1], algo);
     __syncthreads();
-    if (t == 1023) {
-        pair_off[nlist] = s_p[1023]; task_off[nlist] = s_t[1023];
-        *task_counter = 0;
-        counters[0] = s_t[1023]; counters[1] = (int64_t)s_bytes[0]; counters[2] = (int64_t)s_bytes[1];
+    if (t == 0) {
+        pair_off[n] = carry_p; task_off[n] = carry_t;
+        ctrl[0] = 0; ctrl[1] = carry_t;
+        counters[0] = carry_t; counters[1] = (int64_t)s_bytes[0]; counters[2] = (int64_t)s_bytes[1];
     }
 }
 
-__global__ void scatter_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, const int32_t* __restrict__ pair_off,
-                                     int32_t* __restrict__ cursor, int32_t* __restrict__ pair_sorted) {
+__global__ void scatter_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, const int32_t* __restrict__ list_slot,
+                                     const int32_t* __restrict__ pair_off, int32_t* __restrict__ cursor,
+                                     int32_t* __restrict__ pair_sorted) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= npairs) return;
     const int l = probes[i];
-    pair_sorted[pair_off[l] + atomicAdd(&cursor[l], 1)] = (int32_t)i;
+    pair_sorted[pair_off[list_slot[l]] + atomicAdd(&cursor[l], 1)] = (int32_t)i;
+}
+
+// One record per task: binary search of the touched list, then chunk / pair group.
+__global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restrict__ task_off, const int32_t* __restrict__ pair_off,
+                                                         const int32_t* __restrict__ pair_sorted, const int32_t* __restrict__ touched,
+                                                         const int32_t* __restrict__ ctrl, int64_t max_tasks, int4* __restrict__ table) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= max_tasks || t >= ctrl[1]) return;
+    int lo = 0, hi = ctrl[2];   // largest slot with task_off[slot] <= t
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (task_off[mid] <= (int)t) lo = mid; else hi = mid;
+    }
+    const int rem = (int)t - task_off[lo];
+    const int npl = pair_off[lo + 1] - pair_off[lo];
+    const int ngroups = (npl + 1) >> 1;
+    const int chunk = rem / ngroups, grp = rem - chunk * ngroups;   // groups of one chunk are consecutive tasks
+    const int pa = pair_sorted[pair_off[lo] + 2 * grp];
+    const int pb = (2 * grp + 1 < npl) ? pair_sorted[pair_off[lo] + 2 * grp + 1] : -1;
+    table[t] = make_int4(touched[lo], chunk, pa, pb);
 }
 
 // ------------------------------------------------------------------ per-query merge of the task results
@@ -548,61 +653,73 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
     __shared__ int64_t sId[MERGE_CAP];
     __shared__ int s_cnt;
     const int q = blockIdx.x, k = P.k;
-    const int nslots = P.nprobe * P.maxchunks;
-    int32_t tau = P.tauq[q];
-    int fill = 0;              // entries currently held (sorted, best first) in [0, fill)
-    // slots per round so that even if every entry passes the buffer cannot overflow
-    const int per_round_safe = (MERGE_CAP - k) / k;
-    int s0 = 0;
-    while (s0 < nslots) {
-        // optimistic: take all remaining slots if the entries passing `tau` fit
-        if (threadIdx.x == 0) s_cnt = 0;
+    int32_t tau = P.tauq[q];   // k candidates of this query reach tau: nothing below can be in the result
+    // Slots = (probe, chunk) pairs that exist: chunk counts per probe are prefix-summed in LDS
+    // (s_pre), then one thread per slot reads the slot's count and its few surviving entries.
+    __shared__ int s_pre[2049];            // nprobe <= 2048 (enforced by the selection stage / argument check)
+    for (int p = threadIdx.x; p < P.nprobe; p += MERGE_THREADS) {
+        const int l = P.probes[q * P.nprobe + p];
+        const int nblk = (int)(P.blk_off[l + 1] - P.blk_off[l]);
+        s_pre[p + 1] = (nblk + P.CH - 1) / P.CH;
+    }
+    if (threadIdx.x == 0) s_pre[0] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        for (int p = 0; p < P.nprobe; ++p) s_pre[p + 1] += s_pre[p];
+    __syncthreads();
+    const int nslots = s_pre[P.nprobe];
+    auto gather = [&](int s0, int s1, int base_fill) {
+        if (threadIdx.x == 0) s_cnt = base_fill;
         __syncthreads();
-        int local = 0;
-        for (int e = threadIdx.x; e < (nslots - s0) * k; e += MERGE_THREADS) {
-            const int slot = s0 + e / k, r = e % k;
-            const int64_t gs = ((int64_t)q * P.nprobe + slot / P.maxchunks) * P.maxchunks + slot % P.maxchunks;
-            const int l = P.probes[q * P.nprobe + slot / P.maxchunks];
-            const int nblk = (int)(P.blk_off[l + 1] - P.blk_off[l]);
-            if (slot % P.maxchunks < (nblk + P.CH - 1) / P.CH && r < P.part_cnt[gs] && P.part_I[gs * k + r] >= tau) ++local;
-        }
-        if (local) atomicAdd(&s_cnt, local);
-        __syncthreads();
-        const int passing = s_cnt;
-        const int s1 = (fill + passing <= MERGE_CAP) ? nslots : min(nslots, s0 + per_round_safe);
-        __syncthreads();
-        if (threadIdx.x == 0) s_cnt = fill;
-        __syncthreads();
-        for (int e = threadIdx.x; e < (s1 - s0) * k; e += MERGE_THREADS) {
-            const int slot = s0 + e / k, r = e % k;
-            const int64_t gs = ((int64_t)q * P.nprobe + slot / P.maxchunks) * P.maxchunks + slot % P.maxchunks;
-            const int l = P.probes[q * P.nprobe + slot / P.maxchunks];
-            const int nblk = (int)(P.blk_off[l + 1] - P.blk_off[l]);
-            if (slot % P.maxchunks < (nblk + P.CH - 1) / P.CH && r < P.part_cnt[gs]) {
+        for (int s = s0 + threadIdx.x; s < s1; s += MERGE_THREADS) {
+            int lo = 0, hi = P.nprobe;     // probe p with s_pre[p] <= s < s_pre[p + 1]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_pre[mid] <= s) lo = mid; else hi = mid;
+            }
+            const int64_t gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (s - s_pre[lo]);
+            const int n = P.part_cnt[gs];
+            for (int r = 0; r < n; ++r) {
                 const int32_t I = P.part_I[gs * k + r];
                 if (I >= tau) {
                     const int o = atomicAdd(&s_cnt, 1);
-                    sI[o] = I; sId[o] = P.part_id[gs * k + r];
+                    if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.part_id[gs * k + r]; }
                 }
             }
         }
         __syncthreads();
-        const int have = s_cnt;
+        return s_cnt;
+    };
+    auto sort_keep_k = [&](int have) {
         int n2 = 1;
         while (n2 < have) n2 <<= 1;
         for (int i = have + threadIdx.x; i < n2; i += MERGE_THREADS) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
         if (n2 > 1) bitonic_sort(sI, sId, n2); else __syncthreads();
-        fill = min(have, k);
-        if (fill == k && sI[k - 1] > tau) tau = sI[k - 1];
-        s0 = s1;
-        __syncthreads();
+        return min(have, k);
+    };
+    // optimistic: everything that passes tau fits the buffer (the usual case by far)
+    int have = gather(0, nslots, 0);
+    int fill;
+    if (have <= MERGE_CAP) {
+        fill = sort_keep_k(have);
+    } else {
+        // rounds small enough that even if every entry passes the buffer cannot overflow
+        const int per_round = (MERGE_CAP - k) / k;
+        fill = 0;
+        for (int s0 = 0; s0 < nslots; s0 += per_round) {
+            __syncthreads();
+            have = gather(s0, min(nslots, s0 + per_round), fill);
+            fill = sort_keep_k(have);
+            if (fill == k && sI[k - 1] > tau) tau = sI[k - 1];
+        }
     }
+    __syncthreads();
     for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
-        const bool have = r < fill;
-        const int32_t I = have ? sI[r] : INT32_MIN;
-        out_ids[(int64_t)q * k + r] = have ? sId[r] : -1;
+        const bool ok = r < fill;
+        const int32_t I = ok ? sI[r] : INT32_MIN;
+        out_ids[(int64_t)q * k + r] = ok ? sId[r] : -1;
         if (out_iscores) out_iscores[(int64_t)q * k + r] = I;
-        if (out_scores) out_scores[(int64_t)q * k + r] = have ? (float)I * (delta ? delta[q] : 1.0f) : -INFINITY;
+        if (out_scores) out_scores[(int64_t)q * k + r] = ok ? (float)I * (delta ? delta[q] : 1.0f) : -INFINITY;
     }
 }
 
@@ -628,41 +745,51 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     const int nlist = idx->nlist;
     // chunk length: aim at ~2048 tasks, between 16 and 256 blocks
     const double avgblk = (double)idx->total_blocks / nlist;
+    // (pairs of one list share a pass when several queries are in the batch: ~1.5 pairs per task)
+    const double share = nq > 1 ? 1.5 : 1.0;
     int CH = 16;
-    while (CH < 256 && (double)npairs * avgblk / (2.0 * CH) > 2048.0) CH <<= 1;
+    while (CH < 256 && (double)npairs * avgblk / (share * CH) > 2048.0) CH <<= 1;
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
     const int maxchunks = (int)std::max<int64_t>(1, (maxblk + CH - 1) / CH);
     if ((double)npairs * maxchunks * k > 4.0e9) return fail(RAGO_UNSUPPORTED, "nq * nprobe * chunks * k too large for the workspace");
     int rc;
-    if ((rc = ws.list_cnt.reserve((size_t)(2 * nlist + 2) * 4))) return rc;   // list_cnt + cursor
-    if ((rc = ws.pair_off.reserve((size_t)(nlist + 1) * 4))) return rc;
-    if ((rc = ws.task_off.reserve((size_t)(nlist + 2) * 4))) return rc;       // + task counter
+    if ((rc = ws.list_cnt.reserve((size_t)(3 * nlist + 8) * 4))) return rc;   // list_cnt, cursor, list_slot, ctrl
+    if ((rc = ws.pair_off.reserve((size_t)(npairs + 2) * 4))) return rc;      // per touched list
+    if ((rc = ws.task_off.reserve((size_t)(npairs + 2) * 4))) return rc;
+    if ((rc = ws.touched.reserve((size_t)(npairs + 2) * 4))) return rc;
     if ((rc = ws.pair_sorted.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.tauq.reserve((size_t)nq * 4))) return rc;
     if ((rc = ws.part_I.reserve((size_t)npairs * maxchunks * k * 4))) return rc;
     if ((rc = ws.part_id.reserve((size_t)npairs * maxchunks * k * 8))) return rc;
     if ((rc = ws.part_cnt.reserve((size_t)npairs * maxchunks * 4))) return rc;
     if ((rc = ws.counters.reserve(64))) return rc;
+    const int64_t max_tasks = npairs * maxchunks;
+    if ((rc = ws.task_table.reserve((size_t)max_tasks * 16))) return rc;
 
+    int32_t* list_cnt = ws.list_cnt.as<int32_t>();
+    int32_t* cursor = list_cnt + nlist;
+    int32_t* list_slot = list_cnt + 2 * nlist;
+    int32_t* ctrl = list_cnt + 3 * nlist;
     ScanParams P;
     P.codes = idx->codes_blk; P.blk_off = idx->blk_off; P.list_off = idx->list_off; P.ids = idx->ids;
     P.probes = probes; P.lut8sw = lut8sw; P.bias = bias; P.m = idx->m;
     if (tables) P.T = *tables; else P.T = LutTables{};
-    P.pair_sorted = ws.pair_sorted.as<int32_t>(); P.pair_off = ws.pair_off.as<int32_t>();
-    P.task_off = ws.task_off.as<int32_t>(); P.task_counter = ws.task_off.as<int32_t>() + nlist + 1;
+    P.pair_sorted = ws.pair_sorted.as<int32_t>();
+    P.task_table = ws.task_table.as<int4>();
+    P.ctrl = ctrl;
     P.tauq = ws.tauq.as<int32_t>(); P.part_I = ws.part_I.as<int32_t>(); P.part_id = ws.part_id.as<int64_t>();
     P.part_cnt = ws.part_cnt.as<int32_t>();
     P.nlist = nlist; P.nprobe = nprobe; P.k = k; P.CH = CH; P.maxchunks = maxchunks;
 
-    int32_t* list_cnt = ws.list_cnt.as<int32_t>();
-    int32_t* cursor = list_cnt + nlist + 1;
-    fill_i32_kernel<<<256, 256, 0, st>>>(list_cnt, 0, 2 * nlist + 2);
-    fill_i32_kernel<<<64, 256, 0, st>>>(P.tauq, INT32_MIN, nq);
     const unsigned pg = (unsigned)((npairs + 255) / 256);
-    count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_cnt);
-    list_offsets_kernel<<<1, 1024, 0, st>>>(list_cnt, idx->blk_off, idx->list_off, nlist, CH, idx->m, ws.pair_off.as<int32_t>(),
-                                            ws.task_off.as<int32_t>(), P.task_counter, ws.counters.as<int64_t>());
-    scatter_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, P.pair_off, cursor, ws.pair_sorted.as<int32_t>());
+    scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl);
+    count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_cnt, ws.touched.as<int32_t>(), ctrl);
+    touched_offsets_kernel<<<1, 1024, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, idx->m, list_slot,
+                                               ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ctrl, ws.counters.as<int64_t>());
+    scatter_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_slot, ws.pair_off.as<int32_t>(), cursor, ws.pair_sorted.as<int32_t>());
+    task_table_kernel<<<(unsigned)((max_tasks + 255) / 256), 256, 0, st>>>(ws.task_off.as<int32_t>(), ws.pair_off.as<int32_t>(),
+                                                                           P.pair_sorted, ws.touched.as<int32_t>(), ctrl, max_tasks,
+                                                                           ws.task_table.as<int4>());
     RAGO_HIP(hipGetLastError());
 
     static int n_cu = 0;

@@ -125,6 +125,27 @@ def test_search_end_to_end(case, rb):
     assert np.array_equal(gs, r["scores"])
 
 
+def test_select_with_massive_ties(rb):
+    """Duplicate centroids and a zero query: coarse scores tie exactly across the nprobe cut; lower list wins."""
+    ix = to_np(synth.random_index(n=4000, d=64, m=16, nlist=300, seed=21))
+    cen = ix["centroids"].copy()
+    for l in range(300):                       # only 7 distinct centroids
+        cen[l] = ix["centroids"][l % 7]
+    ix["centroids"] = cen
+    Q = _queries(5, 64, 2)
+    Q[3] = 0.0                                 # every score is exactly 0
+    h = rb.rago_index_wrap(dev_index(ix))
+    for nprobe in (1, 40, 45, 130, 300):
+        probes = oracle.select(oracle.coarse(Q, cen), nprobe)
+        gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+        gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+        assert np.array_equal(gp, probes), nprobe
+    r = oracle.ivfpq_search(Q, ix, 45, 10)
+    gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 45, 10)
+    assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    rb.rago_index_free(h)
+
+
 def test_padding_and_argument_errors(rb):
     ix = to_np(synth.random_index(n=300, d=32, m=16, nlist=8, seed=5, empty_lists=(0, 1, 2, 3, 4)))
     h = rb.rago_index_wrap(dev_index(ix))
