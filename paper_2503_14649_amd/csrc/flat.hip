@@ -13,10 +13,13 @@
 //  * queries sit in LDS (row stride padded by 16 B so the 16 query rows fall in different banks).
 //  * a workgroup (4 waves) streams one slab of one request; a wave takes 16-row blocks, the next
 //    block's 24 loads are in flight while the current block is multiplied.
-//  * selection: 64-bit keys (ordered score bits << 32 | ~row) appended to per-query LDS buffers
-//    when they reach the query's running threshold; every 256 rows the workgroup synchronises and
-//    prunes buffers that grew beyond k with a wave-level radix select, which also raises the
-//    threshold.  Each slab writes <= k keys per query; a second kernel merges the slabs.
+//  * selection: a score is a candidate when its histogram bin (width 1/128) is not below the
+//    query's threshold bin; candidates are appended as 64-bit keys (ordered score bits << 32 |
+//    ~row) to a per-(slab, query) area in HBM and counted in a per-query LDS histogram.  Every 256
+//    rows the workgroup synchronises and 16 lanes move each query's threshold to the highest bin
+//    that still has k candidates at or above it, so after the first round only ~k/round new keys
+//    appear.  An area that could overflow is cut back to its best k with a wave-level radix select
+//    (rare).  Each slab leaves <= k keys per query; a second kernel merges the slabs.
 #include "rago_internal.h"
 
 namespace rago {
@@ -29,6 +32,8 @@ constexpr int FLAT_WAVES = 4;
 constexpr int FLAT_RB = 4;                                  // 16-row blocks per wave between barriers
 constexpr int FLAT_ROUND_ROWS = FLAT_WAVES * FLAT_RB * 16;  // 256 rows per workgroup round
 constexpr int FLAT_MAXD = 1024;
+constexpr int FLAT_CAP = 1024;                              // candidate keys per (slab, query) in the HBM scratch
+constexpr int FLAT_BINS = 256;                              // score histogram bins per query
 
 __device__ __forceinline__ uint32_t fkey(float f) {
     const uint32_t u = __float_as_uint(f);
@@ -40,40 +45,67 @@ __device__ __forceinline__ float fkey_inv(uint32_t k) {
 __device__ __forceinline__ int lane_rank64(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
-
-// k-th largest of up to NR*64 non-zero 64-bit keys held NR per lane (wave-uniform result).
-template <int NR>
-__device__ __forceinline__ uint64_t select_kth64(const uint64_t (&r)[NR], int k) {
-    uint64_t prefix = 0;
-    int rem = k;
-    for (int bit = 63; bit >= 0; --bit) {
-        const uint64_t test = prefix | (1ull << bit);
-        const uint64_t hm = ~((1ull << bit) - 1ull);
-        int c1 = 0;
-#pragma unroll
-        for (int i = 0; i < NR; ++i) c1 += __popcll(__ballot((r[i] & hm) == test));
-        if (c1 >= rem) prefix = test; else rem -= c1;
-    }
-    return prefix;
+// Monotone map of a score to a histogram bin (bins of width 1/128 over [-1, 1], clamped: for
+// unit-norm embeddings every score falls inside; outside it the filter only gets coarser).
+__device__ __forceinline__ int score_bin(float s) {
+    const float x = (s + 1.0f) * 128.0f;
+    return x <= 0.0f ? 0 : (x >= 255.0f ? 255 : (int)x);
 }
 
-constexpr int FLAT_NR = (KMAX + FLAT_ROUND_ROWS + 63) / 64;   // registers per lane to hold a full buffer
-
-// Keep the best k of buf[0..cnt) (cnt > k); returns the k-th key.
-__device__ __forceinline__ uint64_t prune64(uint64_t* buf, int cnt, int k, int lane) {
-    uint64_t r[FLAT_NR];
+// k-th largest of up to NR*64 non-zero 64-bit keys held NR per lane (wave-uniform result).
+// Two 32-bit radix selects: first on the score half; the row half only among keys that tie on
+// the k-th score, and only if not all of them are wanted.
+template <int NR>
+__device__ __forceinline__ uint64_t select_kth64(const uint64_t (&r)[NR], int k) {
+    uint32_t prefix = 0;
+    int rem = k;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t test = prefix | (1u << bit);
+        const uint32_t hm = ~((1u << bit) - 1u);
+        int c1 = 0;
 #pragma unroll
-    for (int i = 0; i < FLAT_NR; ++i) r[i] = (lane + 64 * i < cnt) ? buf[lane + 64 * i] : 0ull;
-    const uint64_t kth = select_kth64<FLAT_NR>(r, k);
+        for (int i = 0; i < NR; ++i) c1 += __popcll(__ballot(r[i] != 0ull && ((uint32_t)(r[i] >> 32) & hm) == test));
+        if (c1 >= rem) prefix = test; else rem -= c1;
+    }
+    // rem of the keys whose score half equals prefix are wanted (those with the lowest rows)
+    int ties = 0;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) ties += __popcll(__ballot(r[i] != 0ull && (uint32_t)(r[i] >> 32) == prefix));
+    uint32_t low = 0;
+    if (ties > rem) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t test = low | (1u << bit);
+            const uint32_t hm = ~((1u << bit) - 1u);
+            int c1 = 0;
+#pragma unroll
+            for (int i = 0; i < NR; ++i) c1 += __popcll(__ballot(r[i] != 0ull && (uint32_t)(r[i] >> 32) == prefix && ((uint32_t)r[i] & hm) == test));
+            if (c1 >= rem) low = test; else rem -= c1;
+        }
+    }
+    return ((uint64_t)prefix << 32) | low;
+}
+
+// Keep the best k of buf[0..cnt) (k < cnt <= NR*64), compacted to buf[0..k).
+template <int NR>
+__device__ __forceinline__ void prune64_n(uint64_t* buf, int cnt, int k, int lane) {
+    uint64_t r[NR];
+#pragma unroll
+    for (int i = 0; i < NR; ++i)   // read at device scope: other waves of the workgroup wrote these keys
+        r[i] = (lane + 64 * i < cnt) ? __hip_atomic_load(buf + lane + 64 * i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+    const uint64_t kth = select_kth64<NR>(r, k);
     int base = 0;
 #pragma unroll
-    for (int i = 0; i < FLAT_NR; ++i) {
+    for (int i = 0; i < NR; ++i) {
         const bool keep = r[i] >= kth && r[i] != 0ull;
         const uint64_t mask = __ballot(keep);
         if (keep) buf[base + lane_rank64(mask)] = r[i];
         base += __popcll(mask);
     }
-    return kth;
+}
+
+__device__ __forceinline__ void prune64(uint64_t* buf, int cnt, int k, int lane) {
+    if (cnt <= 5 * 64) prune64_n<5>(buf, cnt, k, lane);
+    else prune64_n<FLAT_CAP / 64>(buf, cnt, k, lane);
 }
 
 struct FlatParams {
@@ -82,25 +114,30 @@ struct FlatParams {
     int64_t n;
     int R, nqr, d, k, nslab;
     int64_t slab_rows;        // rows per slab (multiple of 16)
-    uint64_t* part_keys;      // [R][nslab][16][k]
+    uint64_t* cand;           // [R][nslab][16][FLAT_CAP] candidate keys of each slab (its first k = the slab's result)
     int32_t* part_cnt;        // [R][nslab][16]
+    int32_t* shared_tbin;     // [R][16] threshold bin reached by any slab of the request (zero between calls)
 };
+
+typedef uint32_t f_u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) f_u32x4* f_global_ptr;
 
 template <int D>
 __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatParams P) {
     constexpr int NP = D / 64;              // 128-byte segments per row
     constexpr int QS = D * 2 + 16;          // padded query row stride in LDS (bytes)
     extern __shared__ __align__(16) uint8_t smem[];
-    uint8_t* qs = smem;                                               // 16 * QS
-    const int capq = P.k + FLAT_ROUND_ROWS;
-    uint64_t* bufs = reinterpret_cast<uint64_t*>(smem + 16 * QS);     // [16][capq]
-    int32_t* cnt = reinterpret_cast<int32_t*>(bufs + 16 * capq);      // [16]
-    uint32_t* thr = reinterpret_cast<uint32_t*>(cnt + 16);            // [16] ordered score bits
+    uint8_t* qs = smem;                                                       // 16 * QS
+    uint16_t* hist = reinterpret_cast<uint16_t*>(smem + 16 * QS);             // [16][FLAT_BINS] candidates per score bin
+    int32_t* cnt = reinterpret_cast<int32_t*>(hist + 16 * FLAT_BINS);         // [16]
+    int32_t* tbin = cnt + 16;                                                 // [16] lowest bin that can still hold a top-k score
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int r = blockIdx.x / P.nslab, slab = blockIdx.x % P.nslab;
     const int64_t row0 = (int64_t)slab * P.slab_rows;
     const int64_t row1 = min(P.n, row0 + P.slab_rows);
+    const int64_t pbase = ((int64_t)r * P.nslab + slab) * 16;
+    uint64_t* mycand = P.cand + pbase * FLAT_CAP;
 
     // queries of this request into LDS (zero rows beyond nqr)
     for (int idx = tid; idx < 16 * (D / 8); idx += FLAT_THREADS) {
@@ -109,16 +146,23 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
         if (qrow < P.nqr) v = *reinterpret_cast<const uint4*>(P.queries + ((int64_t)r * P.nqr + qrow) * D + c * 8);
         *reinterpret_cast<uint4*>(qs + qrow * QS + c * 16) = v;
     }
-    if (tid < 16) { cnt[tid] = 0; thr[tid] = 0u; }
+    for (int idx = tid; idx < 16 * FLAT_BINS; idx += FLAT_THREADS) hist[idx] = 0;
+    if (tid < 16) { cnt[tid] = 0; tbin[tid] = 0; }
     __syncthreads();
 
     const uint16_t* X = P.corpus + (int64_t)r * P.n * D;
     uint4 a[2 * NP], an[2 * NP];
+    // loads are unconditional (row clamped into the corpus): a conditional prefetch would make the
+    // compiler wait for every outstanding load before each use
     auto load_rows = [&](uint4 (&dst)[2 * NP], int64_t rb) {   // rb = first row of a 16-row block
-        const int64_t row = min(rb + i16, P.n - 1);
-        const uint4* p = reinterpret_cast<const uint4*>(X + row * D + g * 16);
+        const int64_t row = max((int64_t)0, min(rb + i16, P.n - 1));
+        f_global_ptr p = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + row * D + g * 16));
 #pragma unroll
-        for (int sp = 0; sp < NP; ++sp) { dst[2 * sp] = p[sp * 8]; dst[2 * sp + 1] = p[sp * 8 + 1]; }
+        for (int sp = 0; sp < NP; ++sp) {
+            const f_u32x4 v0 = p[sp * 8], v1 = p[sp * 8 + 1];
+            dst[2 * sp] = make_uint4(v0.x, v0.y, v0.z, v0.w);
+            dst[2 * sp + 1] = make_uint4(v1.x, v1.y, v1.z, v1.w);
+        }
     };
     auto multiply = [&](const uint4 (&src)[2 * NP], int64_t rb) {
         v4f acc = {0.f, 0.f, 0.f, 0.f};
@@ -130,69 +174,109 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp]), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp + 1]), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
         }
-        // acc[e] = score of row rb + 4*g + e with query i16
-        const uint32_t t = thr[i16];
+        // acc[e] = score of row rb + 4*g + e with query i16.  One counter update per lane for its (up to
+        // four) candidates; the histogram updates and the key stores need no reply.
+        const int tb = tbin[i16];
+        int bins[4];
+        int npass = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int64_t row = rb + 4 * g + e;
-            const uint32_t key = fkey(acc[e]);
-            if (row < row1 && i16 < P.nqr && key >= t) {
-                const int pos = atomicAdd(&cnt[i16], 1);
-                bufs[i16 * capq + pos] = ((uint64_t)key << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)row);
+            bins[e] = score_bin(acc[e]);
+            const bool pass = rb + 4 * g + e < row1 && i16 < P.nqr && bins[e] >= tb;
+            if (!pass) bins[e] = -1;
+            npass += pass;
+        }
+        if (npass) {
+            int pos = atomicAdd(&cnt[i16], npass);                  // < FLAT_CAP: see the round-end check
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (bins[e] >= 0) {
+                    atomicAdd(reinterpret_cast<unsigned int*>(hist) + ((i16 * FLAT_BINS + bins[e]) >> 1), (bins[e] & 1) ? 0x10000u : 1u);
+                    mycand[(int64_t)i16 * FLAT_CAP + pos++] =
+                        ((uint64_t)fkey(acc[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(rb + 4 * g + e));
+                }
             }
         }
     };
 
+    int shared_seen = 0;   // what the request-wide threshold word held one round ago (threads < nqr)
     // rounds of 256 rows: wave w owns blocks w*FLAT_RB .. +FLAT_RB of the round
-    int64_t rb = row0 + (int64_t)wave * FLAT_RB * 16;
-    if (rb < row1) load_rows(a, rb);
+    if (row0 < row1) load_rows(a, row0 + (int64_t)wave * FLAT_RB * 16);
     for (int64_t round0 = row0; round0 < row1; round0 += FLAT_ROUND_ROWS) {
 #pragma unroll 1
         for (int bb = 0; bb < FLAT_RB; bb += 2) {
             const int64_t r0 = round0 + ((int64_t)wave * FLAT_RB + bb) * 16, r1 = r0 + 16;
             int64_t r2 = r0 + 32;
             if (bb + 2 >= FLAT_RB) r2 = round0 + FLAT_ROUND_ROWS + (int64_t)wave * FLAT_RB * 16;   // first block of next round
-            if (r1 < row1) load_rows(an, r1);
+            load_rows(an, r1);
             if (r0 < row1) multiply(a, r0);
-            if (r2 < row1) load_rows(a, r2);
+            load_rows(a, r2);
             if (r1 < row1) multiply(an, r1);
         }
         __syncthreads();
-        // buffers that can no longer absorb a full round are cut back to the best k
+        // Per query (one wave each, four queries per wave): first cut an area back to its best k if it
+        // could overflow in the next round (256 more keys at worst) and rebuild its histogram from the
+        // survivors; then move the threshold to the highest bin b that has at least k candidates in
+        // bins >= b.  Every candidate counted is a real row, so the k-th best score is not below bin b.
         for (int qj = wave; qj < P.nqr; qj += FLAT_WAVES) {
+            uint32_t* hq = reinterpret_cast<uint32_t*>(hist + qj * FLAT_BINS);    // two 16-bit bins per word
             const int c = cnt[qj];
-            if (c > P.k) {
-                const uint64_t kth = prune64(bufs + qj * capq, c, P.k, lane);
-                if (lane == 0) { cnt[qj] = P.k; thr[qj] = (uint32_t)(kth >> 32); }
+            if (c + FLAT_ROUND_ROWS > FLAT_CAP) {
+                uint64_t* buf = mycand + (int64_t)qj * FLAT_CAP;
+                prune64(buf, c, P.k, lane);
+                for (int w = lane; w < FLAT_BINS / 2; w += 64) hq[w] = 0;
+                if (lane == 0) cnt[qj] = P.k;
+                for (int e = lane; e < P.k; e += 64) {
+                    const int bin = score_bin(fkey_inv((uint32_t)(__hip_atomic_load(buf + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32)));
+                    atomicAdd(hq + (bin >> 1), (bin & 1) ? 0x10000u : 1u);
+                }
+            }
+            // lane L sums bins 4L..4L+3; suffix sums over lanes; the highest lane reaching k holds the bin
+            const uint32_t w0 = hq[2 * lane], w1 = hq[2 * lane + 1];
+            const int h0 = w0 & 0xffff, h1 = w0 >> 16, h2 = w1 & 0xffff, h3 = w1 >> 16;
+            int suf = h0 + h1 + h2 + h3;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_down(suf, o);
+                if (lane + o < 64) suf += v;
+            }
+            const uint64_t reach = __ballot(suf >= P.k);
+            if (reach) {
+                const int L = 63 - __builtin_clzll(reach);
+                if (lane == L) {
+                    int cum = suf - (h0 + h1 + h2 + h3), b = 4 * L + 3;
+                    const int hh[4] = {h0, h1, h2, h3};
+                    for (; b > 4 * L; --b) {
+                        cum += hh[b - 4 * L];
+                        if (cum >= P.k) break;
+                    }
+                    if (b > tbin[qj]) tbin[qj] = b;
+                }
             }
         }
         __syncthreads();
+        // k rows of this request at or above a bin, seen by ANY slab, bound the request's k-th best: the
+        // bins are exchanged through one word per (request, query).  The reply of this round's atomic is
+        // only looked at after the next round, so its latency is never waited for.
+        if (tid < P.nqr) {
+            if (shared_seen > tbin[tid]) tbin[tid] = shared_seen;
+            shared_seen = atomicMax(P.shared_tbin + r * 16 + tid, tbin[tid]);
+        }
+        __syncthreads();
     }
-    // slab result
-    const int64_t pbase = ((int64_t)r * P.nslab + slab) * 16;
-    for (int qj = wave; qj < P.nqr; qj += FLAT_WAVES) {
-        const int c = cnt[qj];
-        for (int e = lane; e < c; e += 64) P.part_keys[(pbase + qj) * P.k + e] = bufs[qj * capq + e];
-        if (lane == 0) P.part_cnt[pbase + qj] = c;
+    // slab result: everything collected (the merge filters it with the request's final threshold bin)
+    if (tid < P.nqr) {
+        P.part_cnt[pbase + tid] = cnt[tid];
+        atomicMax(P.shared_tbin + r * 16 + tid, tbin[tid]);
     }
 }
 
-// One workgroup per (request, query): sort the slabs' keys descending, write the best k.
+// One workgroup per (request, query): keep the slabs' keys whose score bin reaches the request's
+// final threshold bin (at least k rows do, and nothing below it can be in the result), sort them
+// descending, write the best k.  If more than FM_CAP keys pass (many equal scores), slabs are
+// folded in one at a time, keeping the best k after each.
 constexpr int FM_THREADS = 256;
-__global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams P, int n2, int64_t* __restrict__ out_ids,
-                                                                float* __restrict__ out_scores) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    uint64_t* keys = reinterpret_cast<uint64_t*>(smem);   // [n2]
-    __shared__ int s_cnt;
-    const int r = blockIdx.x / P.nqr, q = blockIdx.x % P.nqr;
-    if (threadIdx.x == 0) s_cnt = 0;
-    for (int i = threadIdx.x; i < n2; i += FM_THREADS) keys[i] = 0ull;
-    __syncthreads();
-    for (int e = threadIdx.x; e < P.nslab * P.k; e += FM_THREADS) {
-        const int slab = e / P.k, j = e % P.k;
-        const int64_t pb = ((int64_t)r * P.nslab + slab) * 16 + q;
-        if (j < P.part_cnt[pb]) keys[atomicAdd(&s_cnt, 1)] = P.part_keys[pb * P.k + j];
-    }
+constexpr int FM_CAP = 4096;
+__device__ void fm_sort_desc(uint64_t* keys, int n2) {
     for (int size = 2; size <= n2; size <<= 1)
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             __syncthreads();
@@ -204,10 +288,56 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
             }
         }
     __syncthreads();
-    const int have = min(s_cnt, P.k);
+}
+
+__global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams P, int64_t* __restrict__ out_ids,
+                                                                float* __restrict__ out_scores) {
+    __shared__ uint64_t keys[FM_CAP];
+    __shared__ int s_cnt;
+    const int r = blockIdx.x / P.nqr, q = blockIdx.x % P.nqr;
+    const int tb = P.shared_tbin[r * 16 + q];
+    auto gather = [&](int slab0, int slab1, int base) {   // append passing keys of slabs [slab0, slab1) after keys[0..base)
+        if (threadIdx.x == 0) s_cnt = base;
+        __syncthreads();
+        for (int slab = slab0; slab < slab1; ++slab) {
+            const int64_t pb = ((int64_t)r * P.nslab + slab) * 16 + q;
+            const int c = P.part_cnt[pb];
+            for (int j = threadIdx.x; j < c; j += FM_THREADS) {
+                const uint64_t key = P.cand[pb * FLAT_CAP + j];
+                if (score_bin(fkey_inv((uint32_t)(key >> 32))) >= tb) {
+                    const int o = atomicAdd(&s_cnt, 1);
+                    if (o < FM_CAP) keys[o] = key;
+                }
+            }
+        }
+        __syncthreads();
+        return s_cnt;
+    };
+    auto sort_keep = [&](int have) {
+        int n2 = 2;
+        while (n2 < have) n2 <<= 1;
+        for (int i = have + threadIdx.x; i < n2; i += FM_THREADS) keys[i] = 0ull;
+        fm_sort_desc(keys, n2);
+        return min(have, P.k);
+    };
+    int have = gather(0, P.nslab, 0);
+    int fill;
+    if (have <= FM_CAP) {
+        fill = sort_keep(have);
+    } else {
+        fill = 0;
+        const int per = (FM_CAP - P.k) / FLAT_CAP;   // slabs per pass that always fit (>= 3)
+        for (int s0 = 0; s0 < P.nslab; s0 += per) {
+            __syncthreads();
+            have = gather(s0, min(P.nslab, s0 + per), fill);
+            fill = sort_keep(have);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) P.shared_tbin[r * 16 + q] = 0;   // ready for the next call
     for (int j = threadIdx.x; j < P.k; j += FM_THREADS) {
         const int64_t o = ((int64_t)r * P.nqr + q) * P.k + j;
-        if (j < have) {
+        if (j < fill) {
             out_ids[o] = (int64_t)(0xFFFFFFFFu - (uint32_t)keys[j]);
             out_scores[o] = fkey_inv((uint32_t)(keys[j] >> 32));
         } else {
@@ -217,14 +347,14 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
     }
 }
 
-static DevBuf g_flat_keys[16], g_flat_cnt[16];
+static DevBuf g_flat_keys[16], g_flat_cnt[16], g_flat_tbin[16];
 
 template <int D>
 static int launch_flat_d(const FlatParams& P, int grid, size_t lds, hipStream_t st) {
     static bool attr_done = false;
     if (!attr_done) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(flat_scan_kernel<D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (D * 2 + 16) + 16 * (KMAX + FLAT_ROUND_ROWS) * 8 + 128));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (D * 2 + 16) + 16 * FLAT_BINS * 2 + 256));
         attr_done = true;
     }
     flat_scan_kernel<D><<<grid, FLAT_THREADS, lds, st>>>(P);
@@ -240,20 +370,30 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
     P.corpus = static_cast<const uint16_t*>(corpus);
     P.queries = static_cast<const uint16_t*>(queries);
     P.n = n; P.R = R; P.nqr = nqr; P.d = d; P.k = k;
-    // slabs: ~1024 workgroups in total, at least one round each, merge fits 4096 keys
-    int nslab = (int)std::min<int64_t>((1024 + R - 1) / R, (n + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS);
-    nslab = std::max(1, std::min(nslab, 4096 / k));
+    // slabs: at least one round each
+    // one resident wave of workgroups (2 per CU): per-slab start-up (unfiltered first round) is paid once per slot
+    const int target = 512;
+    int nslab = (int)std::min<int64_t>((target + R - 1) / R, (n + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS);
+    nslab = std::max(1, nslab);
     int64_t slab_rows = (n + nslab - 1) / nslab;
     slab_rows = (slab_rows + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS * FLAT_ROUND_ROWS;
     if (slab_rows == 0) slab_rows = FLAT_ROUND_ROWS;
     nslab = (int)std::max<int64_t>(1, (n + slab_rows - 1) / slab_rows);
     P.nslab = nslab; P.slab_rows = slab_rows;
     int rc;
-    if ((rc = g_flat_keys[device].reserve((size_t)R * nslab * 16 * k * 8))) return rc;
+    if ((rc = g_flat_keys[device].reserve((size_t)R * nslab * 16 * FLAT_CAP * 8))) return rc;
     if ((rc = g_flat_cnt[device].reserve((size_t)R * nslab * 16 * 4))) return rc;
-    P.part_keys = g_flat_keys[device].as<uint64_t>();
+    P.cand = g_flat_keys[device].as<uint64_t>();
     P.part_cnt = g_flat_cnt[device].as<int32_t>();
-    const size_t lds = 16 * (size_t)(d * 2 + 16) + 16 * (size_t)(k + FLAT_ROUND_ROWS) * 8 + 128;
+    {
+        const size_t need = (size_t)R * 16 * 4;
+        if (need > g_flat_tbin[device].cap) {          // (re)allocation: start from all-zero bins
+            if ((rc = g_flat_tbin[device].reserve(need))) return rc;
+            RAGO_HIP(hipMemsetAsync(g_flat_tbin[device].p, 0, g_flat_tbin[device].cap, st));
+        }
+        P.shared_tbin = g_flat_tbin[device].as<int32_t>();
+    }
+    const size_t lds = 16 * (size_t)(d * 2 + 16) + 16 * FLAT_BINS * 2 + 256;
     const int grid = R * nslab;
     switch (d) {
         case 64: rc = launch_flat_d<64>(P, grid, lds, st); break;
@@ -266,9 +406,7 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
         default: return fail(RAGO_UNSUPPORTED, "d must be one of 64, 128, 256, 384, 512, 768, 1024");
     }
     if (rc) return rc;
-    int n2 = 2;
-    while (n2 < nslab * k) n2 <<= 1;
-    flat_merge_kernel<<<R * nqr, FM_THREADS, (size_t)n2 * 8, st>>>(P, n2, out_ids, out_scores);
+    flat_merge_kernel<<<R * nqr, FM_THREADS, 0, st>>>(P, out_ids, out_scores);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
