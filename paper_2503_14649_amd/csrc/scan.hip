@@ -315,7 +315,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
     uint8_t* lut = smem;
     uint32_t* cand = reinterpret_cast<uint32_t*>(smem + LUT_LDS);                         // [wave][pair][CAPW]
     int32_t* sh = reinterpret_cast<int32_t*>(smem + LUT_LDS + SCAN_WAVES * 2 * CAPW * 4);  // scalars
-    // sh[2..3] tau per pair (sum units), sh[8 + wave*2 + pair] wave counts, sh[32..] descriptors
+    // sh[2..3] tau per pair (sum units), sh[4] block counter, sh[5] finisher ticket, sh[8 + wave*2 + pair] wave counts, sh[32..] descriptors
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     uint32_t off[S / 4];
@@ -414,7 +414,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
                 t0 = t <= 0 ? 0 : (t > 0x7fffffff ? 0x7fffffff : (int32_t)t);
             }
             sh[2 + threadIdx.x] = t0;
-            if (threadIdx.x == 0) sh[4] = SCAN_WAVES;   // next unclaimed block of the chunk
+            if (threadIdx.x == 0) { sh[4] = SCAN_WAVES; sh[5] = 0; }   // next unclaimed block of the chunk; finisher ticket
         }
         __syncthreads();
 
@@ -424,7 +424,6 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         int cntA = 0, cntB = 0;
         uint32_t thrA = (uint32_t)sh[2], thrB = (uint32_t)sh[3];
         // one wave claims and decodes the next task while its first loads are in flight
-        if (wave == SCAN_WAVES - 1) fetch_task(P, ntasks, desc + (cur ^ 1) * DESC_INTS, lane);
         auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
             const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
             const bool valid = (int)pos < cvecs;
@@ -460,6 +459,14 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
             process(nxt_w, bn);
             bn = claim();
             load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
+        }
+        // The first wave to run out of blocks claims and decodes the next task while the others finish
+        // (claiming it at the start of the chunk instead costs ~5 % of the kernel: the claiming wave's
+        // scalar-load chain then delays its share of the stream).
+        {
+            int ticket = 0;
+            if (lane == 0) ticket = atomicAdd(&sh[5], 1);
+            if (__builtin_amdgcn_readfirstlane(ticket) == 0) fetch_task(P, ntasks, desc + (cur ^ 1) * DESC_INTS, lane);
         }
         // ---- task result: every wave trims its buffers to k, then one wave per pair merges
         if (cntA > k) wave_prune(bufA, cntA, k, lane);
