@@ -283,7 +283,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n/nlist/components by this factor (development runs)")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
-    ap.add_argument("--cpu-queries", type=int, default=32, help="queries in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one GPU's shard at real shape); --gpus must be 1", file=sys.stderr)

@@ -231,22 +231,27 @@ __device__ __forceinline__ void offer(bool valid, uint32_t sum, uint32_t pos, ui
 // table loads instead of in front of them: the load counter retires in order).
 template <class F>
 __device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB, uint8_t* lut, F between) {
-    uint4 ta[4], tb[4];
+    // (named scalars, not arrays: conditionally filled arrays end up in scratch memory)
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    uint4 a0 = z, a1 = z, a2 = z, a3 = z, b0 = z, b1 = z, b2 = z, b3 = z;
+    const int t = threadIdx.x;
+    if (srcA) { a0 = srcA[t]; a1 = srcA[t + SCAN_THREADS]; a2 = srcA[t + 2 * SCAN_THREADS]; a3 = srcA[t + 3 * SCAN_THREADS]; }
+    if (srcB) { b0 = srcB[t]; b1 = srcB[t + SCAN_THREADS]; b2 = srcB[t + 2 * SCAN_THREADS]; b3 = srcB[t + 3 * SCAN_THREADS]; }
+    between();
+    // piece p = 16 bytes: row p >> 3, column (p & 7) * 16 of the 128-byte table row
+    uint8_t* d0 = lut + (t >> 3) * 256 + (t & 7) * 16;
+    constexpr int STEP = (SCAN_THREADS >> 3) * 256;   // rows advanced by SCAN_THREADS pieces
     if (srcA) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) ta[r] = srcA[threadIdx.x + r * SCAN_THREADS];
+        *reinterpret_cast<uint4*>(d0) = a0;
+        *reinterpret_cast<uint4*>(d0 + STEP) = a1;
+        *reinterpret_cast<uint4*>(d0 + 2 * STEP) = a2;
+        *reinterpret_cast<uint4*>(d0 + 3 * STEP) = a3;
     }
     if (srcB) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) tb[r] = srcB[threadIdx.x + r * SCAN_THREADS];
-    }
-    between();
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int piece = threadIdx.x + r * SCAN_THREADS;
-        uint8_t* dst = lut + (piece >> 3) * 256 + (piece & 7) * 16;
-        if (srcA) *reinterpret_cast<uint4*>(dst) = ta[r];
-        if (srcB) *reinterpret_cast<uint4*>(dst + 128) = tb[r];
+        *reinterpret_cast<uint4*>(d0 + 128) = b0;
+        *reinterpret_cast<uint4*>(d0 + 128 + STEP) = b1;
+        *reinterpret_cast<uint4*>(d0 + 128 + 2 * STEP) = b2;
+        *reinterpret_cast<uint4*>(d0 + 128 + 3 * STEP) = b3;
     }
 }
 
