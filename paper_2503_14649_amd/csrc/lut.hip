@@ -32,62 +32,74 @@
 
 namespace rago {
 
-// T64[q][j][c], Tmin/Tmax[q][j].  grid (nq, m), 256 threads = one per codeword.
-__global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int d, int m,
+// T64[q][j][c], Tmin/Tmax[q][j].  grid (nq, ceil(m / tj)), 256 threads = one per codeword, tj sub-quantisers per block.
+constexpr int LUT_TJ = 8;   // at most; `tj` sub-quantisers per block (1 for small batches: latency, 8 for large: fewer blocks)
+__global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int d, int m, int tj,
                                                     double* __restrict__ T64, double* __restrict__ Tmin, double* __restrict__ Tmax,
                                                     uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
                                                     int64_t* __restrict__ counters) {
-    const int j = blockIdx.y, c = threadIdx.x;
+    __shared__ double s_mn[LUT_TJ][4], s_mx[LUT_TJ][4];
+    const int c = threadIdx.x;
     const int64_t q = blockIdx.x;
-    if (j == 0 && c == 0) {   // running maxima of the pair kernel and the table counters start at zero
+    const int dsub = d / m;
+    if (blockIdx.y == 0 && c == 0) {   // running maxima of the pair kernel and the table counters start at zero
         range_bits[q] = 0u; mag_bits[q] = 0u;
         if (q == 0) { counters[4] = 0; counters[5] = 0; }
     }
-    const int dsub = d / m;
-    const float* qv = Q + q * d + j * dsub;
-    const float* cb = CB + ((int64_t)j * KSUB + c) * dsub;
-    double acc = 0.0;
-    for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cb[t];
-    T64[(q * m + j) * KSUB + c] = acc;
-    double mn = acc, mx = acc;
-    for (int o = 32; o; o >>= 1) {
-        mn = fmin(mn, __shfl_xor(mn, o));
-        mx = fmax(mx, __shfl_xor(mx, o));
+    for (int jj = 0; jj < tj; ++jj) {
+        const int j = blockIdx.y * tj + jj;
+        if (j >= m) break;
+        const float* qv = Q + q * d + j * dsub;
+        const float* cb = CB + ((int64_t)j * KSUB + c) * dsub;
+        double acc = 0.0;
+        for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cb[t];
+        T64[(q * m + j) * KSUB + c] = acc;
+        double mn = acc, mx = acc;
+        for (int o = 32; o; o >>= 1) {
+            mn = fmin(mn, __shfl_xor(mn, o));
+            mx = fmax(mx, __shfl_xor(mx, o));
+        }
+        if ((c & 63) == 0) { s_mn[jj][c >> 6] = mn; s_mx[jj][c >> 6] = mx; }
     }
-    __shared__ double s_mn[4], s_mx[4];
-    if ((c & 63) == 0) { s_mn[c >> 6] = mn; s_mx[c >> 6] = mx; }
     __syncthreads();
-    if (c == 0) {
-        Tmin[q * m + j] = fmin(fmin(s_mn[0], s_mn[1]), fmin(s_mn[2], s_mn[3]));
-        Tmax[q * m + j] = fmax(fmax(s_mx[0], s_mx[1]), fmax(s_mx[2], s_mx[3]));
+    if (c < tj && blockIdx.y * tj + c < m) {
+        const int j = blockIdx.y * tj + c;
+        Tmin[q * m + j] = fmin(fmin(s_mn[c][0], s_mn[c][1]), fmin(s_mn[c][2], s_mn[c][3]));
+        Tmax[q * m + j] = fmax(fmax(s_mx[c][0], s_mx[c][1]), fmax(s_mx[c][2], s_mx[c][3]));
     }
 }
 
 // Per pair: t64[pair][j]; per query: running max of (hi - lo) and of |lo|,|hi| as float bits (>= 0).
-__global__ void __launch_bounds__(128) lut_pair_kernel(const float* __restrict__ Q, const float* __restrict__ C,
-                                                       const int32_t* __restrict__ probes, int nprobe, int d, int m,
+// One wave per pair (lanes = sub-quantisers), `ppw` consecutive pairs per wave, 4 waves per block.
+__global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                       const int32_t* __restrict__ probes, int64_t npairs, int ppw, int nprobe, int d, int m,
                                                        const double* __restrict__ Tmin, const double* __restrict__ Tmax,
                                                        double* __restrict__ t64, uint32_t* __restrict__ range_bits,
                                                        uint32_t* __restrict__ mag_bits) {
-    const int64_t pair = blockIdx.x;
-    const int64_t q = pair / nprobe;
-    const int l = probes[pair];
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int dsub = d / m;
-    float rng = 0.f, mag = 0.f;
-    for (int j = threadIdx.x; j < m; j += blockDim.x) {
-        const float* qv = Q + q * d + j * dsub;
-        const float* cv = C + (int64_t)l * d + j * dsub;
-        double acc = 0.0;
-        for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cv[t];
-        t64[pair * m + j] = acc;
-        const float lo = (float)(Tmin[q * m + j] + acc), hi = (float)(Tmax[q * m + j] + acc);
-        rng = fmaxf(rng, hi - lo);
-        mag = fmaxf(mag, fmaxf(fabsf(lo), fabsf(hi)));
-    }
-    for (int o = 32; o; o >>= 1) { rng = fmaxf(rng, __shfl_xor(rng, o)); mag = fmaxf(mag, __shfl_xor(mag, o)); }
-    if ((threadIdx.x & 63) == 0) {
-        if (rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
-        if (mag > 0.f) atomicMax(mag_bits + q, __float_as_uint(mag));
+    for (int pp = 0; pp < ppw; ++pp) {
+        const int64_t pair = w * ppw + pp;
+        if (pair >= npairs) return;
+        const int64_t q = pair / nprobe;
+        const int l = probes[pair];
+        float rng = 0.f, mag = 0.f;
+        for (int j = lane; j < m; j += 64) {
+            const float* qv = Q + q * d + j * dsub;
+            const float* cv = C + (int64_t)l * d + j * dsub;
+            double acc = 0.0;
+            for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cv[t];
+            t64[pair * m + j] = acc;
+            const float lo = (float)(Tmin[q * m + j] + acc), hi = (float)(Tmax[q * m + j] + acc);
+            rng = fmaxf(rng, hi - lo);
+            mag = fmaxf(mag, fmaxf(fabsf(lo), fabsf(hi)));
+        }
+        for (int o = 32; o; o >>= 1) { rng = fmaxf(rng, __shfl_xor(rng, o)); mag = fmaxf(mag, __shfl_xor(mag, o)); }
+        if (lane == 0) {
+            if (rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
+            if (mag > 0.f) atomicMax(mag_bits + q, __float_as_uint(mag));
+        }
     }
 }
 
@@ -255,9 +267,10 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     uint16_t* amb_addr = ws.amb.as<uint16_t>();
     int32_t* namb = reinterpret_cast<int32_t*>(amb_addr + nq * AMB_MAX);
     if ((rc = ws.counters.reserve(64))) return rc;
-    lut_T_kernel<<<dim3((unsigned)nq, m), 256, 0, st>>>(q, idx->codebooks, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax,
+    const int tj = nq >= 64 ? LUT_TJ : 1, ppw = npairs >= 32768 ? 8 : 1;
+    lut_T_kernel<<<dim3((unsigned)nq, (m + tj - 1) / tj), 256, 0, st>>>(q, idx->codebooks, d, m, tj, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax,
                                                         range_bits, mag_bits, ws.counters.as<int64_t>());
-    lut_pair_kernel<<<(unsigned)npairs, 128, 0, st>>>(q, idx->centroids, probes, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
+    lut_pair_kernel<<<(unsigned)((npairs + 4 * ppw - 1) / (4 * ppw)), 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
                                                       ws.pair_lo.as<double>(), range_bits, mag_bits);
     lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,
                                                   ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(), ws.counters.as<int64_t>());

@@ -525,52 +525,69 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
 // (at most one per pair), so a single query costs a few hundred entries, not nlist.
 // ctrl[0] task counter, ctrl[1] number of tasks, ctrl[2] number of touched lists.
 __global__ void scan_init_kernel(int32_t* __restrict__ list_cnt2, int64_t n2, int32_t* __restrict__ tauq, int64_t nq,
-                                 int32_t* __restrict__ ctrl) {
+                                 int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = i; j < n2; j += stride) list_cnt2[j] = 0;     // list_cnt and cursor
     for (int64_t j = i; j < nq; j += stride) tauq[j] = INT32_MIN;
     if (i < 4) ctrl[i] = 0;
+    if (i == 0) { counters[1] = 0; counters[2] = 0; }
 }
 
-__global__ void count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int32_t* __restrict__ list_cnt,
-                                   int32_t* __restrict__ touched, int32_t* __restrict__ ctrl) {
+__global__ void __launch_bounds__(256) count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int32_t* __restrict__ list_cnt,
+                                                          int32_t* __restrict__ touched, int32_t* __restrict__ ctrl) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= npairs) return;
-    const int l = probes[i];
-    if (atomicAdd(&list_cnt[l], 1) == 0) touched[atomicAdd(&ctrl[2], 1)] = l;
+    const int lane = threadIdx.x & 63;
+    int l = -1;
+    bool first = false;
+    if (i < npairs) {
+        l = probes[i];
+        first = atomicAdd(&list_cnt[l], 1) == 0;
+    }
+    const uint64_t m = __ballot(first);         // one slot reservation per wave, not per list
+    if (m) {
+        int base = 0;
+        if (lane == __builtin_ctzll(m)) base = atomicAdd(&ctrl[2], __popcll(m));
+        base = __builtin_amdgcn_readlane(base, __builtin_ctzll(m));
+        if (first) touched[base + __popcll(m & ((1ull << lane) - 1ull))] = l;
+    }
 }
 
-// Exclusive prefix sums over the touched lists (one workgroup, 4 entries per thread and tile).
-__global__ void __launch_bounds__(1024) touched_offsets_kernel(const int32_t* __restrict__ touched, const int32_t* __restrict__ list_cnt,
-                                                               const int64_t* __restrict__ blk_off, const int64_t* __restrict__ list_off,
-                                                               int CH, int m, int32_t* __restrict__ list_slot,
-                                                               int32_t* __restrict__ pair_off, int32_t* __restrict__ task_off,
-                                                               int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
+// Per touched list: its pair count and task count (any number of workgroups), and where it sits.
+__global__ void __launch_bounds__(256) touched_values_kernel(const int32_t* __restrict__ touched, const int32_t* __restrict__ list_cnt,
+                                                             const int64_t* __restrict__ blk_off, const int64_t* __restrict__ list_off,
+                                                             int CH, int m, int64_t max_n, const int32_t* __restrict__ ctrl,
+                                                             int32_t* __restrict__ list_slot, int32_t* __restrict__ vp,
+                                                             int32_t* __restrict__ vt, int64_t* __restrict__ counters) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long streamed = 0, algo = 0;
+    if (i < max_n && i < ctrl[2]) {
+        const int l = touched[i];
+        const int c = list_cnt[l];
+        const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
+        list_slot[l] = (int)i;
+        vp[i] = c;
+        vt[i] = ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
+        streamed = (unsigned long long)((c + 1) >> 1) * nblk * (BLOCK_VECS * m);
+        algo = (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
+    }
+    for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
+    if ((threadIdx.x & 63) == 0 && (streamed | algo)) {
+        atomicAdd(reinterpret_cast<unsigned long long*>(counters + 1), streamed);
+        atomicAdd(reinterpret_cast<unsigned long long*>(counters + 2), algo);
+    }
+}
+
+// Exclusive prefix sums (in place) of the per-list pair and task counts: one workgroup, coalesced.
+__global__ void __launch_bounds__(1024) touched_scan_kernel(int32_t* __restrict__ vp, int32_t* __restrict__ vt,
+                                                            int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
     __shared__ int s_wp[16], s_wt[16];
-    __shared__ unsigned long long s_bytes[2];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int n = ctrl[2];
-    if (t < 2) s_bytes[t] = 0;
     int carry_p = 0, carry_t = 0;
-    unsigned long long streamed = 0, algo = 0;
-    for (int base = 0; base < n; base += 4096) {
-        int vp[4], vt[4], ll[4];
-        int sp = 0, st = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = base + t * 4 + e;
-            vp[e] = 0; vt[e] = 0; ll[e] = -1;
-            if (i < n) {
-                const int l = touched[i];
-                const int c = list_cnt[l];
-                const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
-                ll[e] = l; vp[e] = c; vt[e] = ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
-                streamed += (unsigned long long)((c + 1) >> 1) * nblk * (BLOCK_VECS * m);
-                algo += (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
-            }
-            sp += vp[e]; st += vt[e];
-        }
-        int ip = sp, it = st;                      // inclusive scan across the wave
+    for (int base = 0; base < n; base += 1024) {
+        const int i = base + t;
+        const int p = i < n ? vp[i] : 0, q = i < n ? vt[i] : 0;
+        int ip = p, it = q;                        // inclusive scan across the wave
         for (int o = 1; o < 64; o <<= 1) {
             const int a = __shfl_up(ip, o), b = __shfl_up(it, o);
             if (lane >= o) { ip += a; it += b; }
@@ -583,22 +600,13 @@ __global__ void __launch_bounds__(1024) touched_offsets_kernel(const int32_t* __
             if (w < wave) { wp += s_wp[w]; wt += s_wt[w]; }
             tot_p += s_wp[w]; tot_t += s_wt[w];
         }
-        int ep = carry_p + wp + ip - sp, et = carry_t + wt + it - st;   // exclusive offsets of this thread's first entry
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = base + t * 4 + e;
-            if (i < n) { pair_off[i] = ep; task_off[i] = et; list_slot[ll[e]] = i; }
-            ep += vp[e]; et += vt[e];
-        }
+        if (i < n) { vp[i] = carry_p + wp + ip - p; vt[i] = carry_t + wt + it - q; }
         carry_p += tot_p; carry_t += tot_t;
     }
-    atomicAdd(&s_bytes[0], streamed);
-    atomicAdd(&s_bytes[1], algo);
-    __syncthreads();
     if (t == 0) {
-        pair_off[n] = carry_p; task_off[n] = carry_t;
+        vp[n] = carry_p; vt[n] = carry_t;
         ctrl[0] = 0; ctrl[1] = carry_t;
-        counters[0] = carry_t; counters[1] = (int64_t)s_bytes[0]; counters[2] = (int64_t)s_bytes[1];
+        counters[0] = carry_t;
     }
 }
 
@@ -794,10 +802,11 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     P.nlist = nlist; P.nprobe = nprobe; P.k = k; P.CH = CH; P.maxchunks = maxchunks;
 
     const unsigned pg = (unsigned)((npairs + 255) / 256);
-    scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl);
+    scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl, ws.counters.as<int64_t>());
     count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_cnt, ws.touched.as<int32_t>(), ctrl);
-    touched_offsets_kernel<<<1, 1024, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, idx->m, list_slot,
-                                               ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ctrl, ws.counters.as<int64_t>());
+    touched_values_kernel<<<pg, 256, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, idx->m, npairs, ctrl,
+                                              list_slot, ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ws.counters.as<int64_t>());
+    touched_scan_kernel<<<1, 1024, 0, st>>>(ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ctrl, ws.counters.as<int64_t>());
     scatter_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_slot, ws.pair_off.as<int32_t>(), cursor, ws.pair_sorted.as<int32_t>());
     task_table_kernel<<<(unsigned)((max_tasks + 255) / 256), 256, 0, st>>>(ws.task_off.as<int32_t>(), ws.pair_off.as<int32_t>(),
                                                                            P.pair_sorted, ws.touched.as<int32_t>(), ctrl, max_tasks,
