@@ -7,9 +7,9 @@
 // HBM-bound, the MFMA only keeps the arithmetic off the vector ALUs.
 //  * v_mfma_f32_16x16x32_bf16: M = 16 corpus rows, N = 16 queries of the request, K = 32.
 //    Lane (i = lane%16, g = lane/16) supplies 8 bf16 of row i; both operands use the same
-//    lane -> k mapping, and k may be permuted freely inside the sum, so every lane loads 32
-//    contiguous bytes per 128-byte row segment (two dwordx4, two MFMA steps): each cache line is
-//    consumed whole by four lanes in back-to-back instructions.
+//    lane -> k mapping, and k may be permuted freely inside the sum, so the four lanes of a row
+//    load 64 contiguous bytes per instruction and the two halves of each 128-byte row segment are
+//    consumed by back-to-back instructions (two dwordx4 per lane, two MFMA steps).
 //  * queries sit in LDS (row stride padded by 16 B so the 16 query rows fall in different banks).
 //  * a workgroup (4 waves) streams one slab of one request; a wave takes 16-row blocks, the next
 //    block's 24 loads are in flight while the current block is multiplied.
@@ -156,21 +156,21 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
     // compiler wait for every outstanding load before each use
     auto load_rows = [&](uint4 (&dst)[2 * NP], int64_t rb) {   // rb = first row of a 16-row block
         const int64_t row = max((int64_t)0, min(rb + i16, P.n - 1));
-        f_global_ptr p = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + row * D + g * 16));
+        f_global_ptr p = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + row * D + g * 8));
 #pragma unroll
         for (int sp = 0; sp < NP; ++sp) {
-            const f_u32x4 v0 = p[sp * 8], v1 = p[sp * 8 + 1];
+            const f_u32x4 v0 = p[sp * 8], v1 = p[sp * 8 + 4];
             dst[2 * sp] = make_uint4(v0.x, v0.y, v0.z, v0.w);
             dst[2 * sp + 1] = make_uint4(v1.x, v1.y, v1.z, v1.w);
         }
     };
     auto multiply = [&](const uint4 (&src)[2 * NP], int64_t rb) {
         v4f acc = {0.f, 0.f, 0.f, 0.f};
-        const uint8_t* qrow = qs + i16 * QS + g * 32;
+        const uint8_t* qrow = qs + i16 * QS + g * 16;
 #pragma unroll
         for (int sp = 0; sp < NP; ++sp) {
             const uint4 b0 = *reinterpret_cast<const uint4*>(qrow + sp * 128);
-            const uint4 b1 = *reinterpret_cast<const uint4*>(qrow + sp * 128 + 16);
+            const uint4 b1 = *reinterpret_cast<const uint4*>(qrow + sp * 128 + 64);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp]), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp + 1]), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
         }
