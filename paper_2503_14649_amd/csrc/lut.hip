@@ -24,9 +24,10 @@
 // more ambiguous entries than AMB_MAX (nearly constant tables), its pairs are flagged and every
 // consumer evaluates the full per-pair table with the same expression instead.
 //
-// Table layout ("swizzled", what the scan copies into LDS): [c][128] with byte
-// slot*4 + plane = entry c of sub-quantiser plane*32 + slot; for m < 32 the m sub-tables are
-// replicated 32/m times over the 32 slots.
+// Table layout in HBM ("plane-major", what the scan interleaves into LDS): [plane][c][slot], one
+// byte each = entry c of sub-quantiser plane*32 + slot; for m < 32 the m sub-tables are
+// replicated 32/m times over the 32 slots.  A table occupies planes * 8192 bytes of its
+// LUT_BYTES stride.
 #include "lut_common.h"
 #include "rago_internal.h"
 
@@ -103,7 +104,7 @@ __global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__
     }
 }
 
-// Per query: base table (swizzled) + list of ambiguous entries.  256 threads = one per codeword.
+// Per query: base table (plane-major) + list of ambiguous entries.  256 threads = one per codeword.
 __global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
                                                        const uint32_t* __restrict__ range_bits, const uint32_t* __restrict__ mag_bits,
                                                        int m, uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
@@ -117,30 +118,36 @@ __global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict_
     const float range = __uint_as_float(range_bits[q]);
     const float dq = lut_step(range);
     const double eta = lut_eta(range, __uint_as_float(mag_bits[q]), dq);
-    uint32_t row[LUT_ROW / 4];
-#pragma unroll
-    for (int i = 0; i < LUT_ROW / 4; ++i) row[i] = 0;
     const double* Tq = T64 + q * m * KSUB + c;
-    const int S = rago_steps(m);
-    for (int j = 0; j < m; ++j) {
-        const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) / (double)dq;
-        double r = rint(u);
-        r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
-        const int slot = j & (S - 1), plane = j >> 5;
-        row[slot] |= (uint32_t)r << (8 * plane);
-        if (fabs((u - floor(u)) - 0.5) <= eta) {
-            for (int rep = slot; rep < 32; rep += S) {     // every replica of the sub-table (m < 32)
-                const int i = atomicAdd(&s_n, 1);
-                if (i < AMB_MAX) amb_addr[q * AMB_MAX + i] = (uint16_t)(c * 256 + rep * 4 + plane);
+    const int S = rago_steps(m), planes = rago_planes(m);
+    for (int plane = 0; plane < planes; ++plane) {
+        uint32_t row[8];                      // 32 slots of this plane, one byte each
+#pragma unroll
+        for (int i = 0; i < 8; ++i) row[i] = 0;
+#pragma unroll
+        for (int slot = 0; slot < 32; ++slot) {
+            if (slot >= S) continue;
+            const int j = plane * 32 + slot;
+            const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) / (double)dq;
+            double r = rint(u);
+            r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
+            row[slot >> 2] |= (uint32_t)r << (8 * (slot & 3));
+            if (fabs((u - floor(u)) - 0.5) <= eta) {
+                for (int rep = slot; rep < 32; rep += S) {     // every replica of the sub-table (m < 32)
+                    const int i = atomicAdd(&s_n, 1);
+                    if (i < AMB_MAX) amb_addr[q * AMB_MAX + i] = (uint16_t)(plane * LUT_PLANE + c * 32 + rep);
+                }
             }
         }
-    }
-    if (S < 32) {
-        for (int s = S; s < 32; ++s) row[s] = row[s & (S - 1)];
-    }
-    uint4* dst = reinterpret_cast<uint4*>(lut_base + q * LUT_BYTES + (int64_t)c * LUT_ROW);
+        if (S < 32) {
 #pragma unroll
-    for (int i = 0; i < LUT_ROW / 16; ++i) dst[i] = make_uint4(row[4 * i], row[4 * i + 1], row[4 * i + 2], row[4 * i + 3]);
+            for (int i = 0; i < 8; ++i)
+                if (i * 4 >= S) row[i] = row[i & (S / 4 - 1)];
+        }
+        uint4* dst = reinterpret_cast<uint4*>(lut_base + q * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
+        dst[0] = make_uint4(row[0], row[1], row[2], row[3]);
+        dst[1] = make_uint4(row[4], row[5], row[6], row[7]);
+    }
     __syncthreads();
     if (c == 0) {
         namb[q] = s_n > AMB_MAX ? AMB_MAX + 1 : s_n;   // AMB_MAX + 1 = "evaluate per pair"
@@ -176,7 +183,7 @@ __global__ void __launch_bounds__(128) lut_patch_kernel(const double* __restrict
     const int S = rago_steps(m);
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const int addr = amb_addr[q * AMB_MAX + i];
-        const int c = addr >> 8, slot = (addr >> 2) & 31, plane = addr & 3;
+        const int plane = addr / LUT_PLANE, c = (addr >> 5) & 255, slot = addr & 31;
         const int j = plane * 32 + (slot & (S - 1));
         patch_val[pair * AMB_MAX + i] = lut_entry(T64[(q * m + j) * KSUB + c], s_t[j], s_lo[j], dq);
     }
@@ -202,7 +209,7 @@ __global__ void __launch_bounds__(256) lut_expand_kernel(const double* __restric
         if (out_LUT8) {
             uint8_t v;
             if (n > AMB_MAX) v = lut_entry(Tv, t, (float)(Tmin[q * m + j] + t), dq);
-            else v = lut_base[q * LUT_BYTES + (int64_t)c * LUT_ROW + (j & (S - 1)) * 4 + (j >> 5)];
+            else v = lut_base[q * LUT_BYTES + (int64_t)(j >> 5) * LUT_PLANE + c * 32 + (j & (S - 1))];
             out_LUT8[(pair * m + j) * KSUB + c] = v;
         }
     }
@@ -210,30 +217,30 @@ __global__ void __launch_bounds__(256) lut_expand_kernel(const double* __restric
     __syncthreads();
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const int addr = amb_addr[q * AMB_MAX + i];
-        const int cc = addr >> 8, slot = (addr >> 2) & 31, plane = addr & 3;
+        const int plane = addr / LUT_PLANE, cc = (addr >> 5) & 255, slot = addr & 31;
         const int j = plane * 32 + (slot & (S - 1));
         out_LUT8[(pair * m + j) * KSUB + cc] = patch_val[pair * AMB_MAX + i];
     }
 }
 
-// plain [pair][m][256] u8 -> swizzled [pair][256][128]
+// plain [pair][m][256] u8 -> plane-major [pair][plane][256][32]
 __global__ void __launch_bounds__(256) lut_swizzle_kernel(const uint8_t* __restrict__ plain, int m, uint8_t* __restrict__ lut8sw) {
     const int64_t pair = blockIdx.x;
     const int c = threadIdx.x;
-    uint32_t row[LUT_ROW / 4];
+    const int S = rago_steps(m), planes = rago_planes(m);
+    for (int plane = 0; plane < planes; ++plane) {
+        uint32_t row[8];
 #pragma unroll
-    for (int i = 0; i < LUT_ROW / 4; ++i) row[i] = 0;
-    const int S = rago_steps(m);
-    for (int j = 0; j < m; ++j) {
-        const uint32_t v = plain[(pair * m + j) * KSUB + c];
-        row[j & (S - 1)] |= v << (8 * (j >> 5));
-    }
-    if (S < 32) {
-        for (int s = S; s < 32; ++s) row[s] = row[s & (S - 1)];
-    }
-    uint4* dst = reinterpret_cast<uint4*>(lut8sw + pair * LUT_BYTES + (int64_t)c * LUT_ROW);
+        for (int i = 0; i < 8; ++i) row[i] = 0;
 #pragma unroll
-    for (int i = 0; i < LUT_ROW / 16; ++i) dst[i] = make_uint4(row[4 * i], row[4 * i + 1], row[4 * i + 2], row[4 * i + 3]);
+        for (int slot = 0; slot < 32; ++slot) {
+            const uint32_t v = plain[(pair * m + plane * 32 + (slot & (S - 1))) * KSUB + c];
+            row[slot >> 2] |= v << (8 * (slot & 3));
+        }
+        uint4* dst = reinterpret_cast<uint4*>(lut8sw + pair * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
+        dst[0] = make_uint4(row[0], row[1], row[2], row[3]);
+        dst[1] = make_uint4(row[4], row[5], row[6], row[7]);
+    }
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int64_t n) {

@@ -29,8 +29,8 @@ __device__ __forceinline__ uint8_t lut_entry(double Tv, double t, float lo, floa
 
 // Everything a consumer needs to obtain the table of one (query, list) pair.
 struct LutTables {
-    const uint8_t* lut_base;    // [nq][256][128] swizzled base tables
-    const uint16_t* amb_addr;   // [nq][AMB_MAX] LDS byte offsets (code*256 + slot*4 + plane) of ambiguous entries
+    const uint8_t* lut_base;    // [nq][plane][256][32] base tables
+    const uint16_t* amb_addr;   // [nq][AMB_MAX] positions (plane*8192 + code*32 + slot) of ambiguous entries
     const int32_t* namb;        // [nq] number of ambiguous entries, AMB_MAX + 1 = evaluate per pair
     const uint8_t* patch_val;   // [npairs][AMB_MAX] exact values of those entries
     const double* T64;          // [nq][m][256]

@@ -12,8 +12,8 @@ namespace rago {
 constexpr int KSUB = 256;          // codewords per sub-quantiser
 constexpr int BLOCK_VECS = 64;     // vectors per code block = one wavefront, one vector per lane
 constexpr int KMAX = 128;          // largest k served by the wave-level selection buffers
-constexpr int LUT_ROW = 128;       // bytes of one swizzled table row (32 banks x 4 planes)
-constexpr int LUT_BYTES = KSUB * LUT_ROW;  // one swizzled 8-bit table in HBM
+constexpr int LUT_PLANE = KSUB * 32;       // bytes of one plane of a table: [c][slot], 32 sub-quantisers
+constexpr int LUT_BYTES = 4 * LUT_PLANE;   // stride of one 8-bit table in HBM (planes * LUT_PLANE bytes used)
 
 void set_error(const std::string& msg);
 int fail(int code, const std::string& msg);
@@ -93,7 +93,7 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
 
 // scan.hip
-// Tables come either per pair (`lut8sw` [npairs][256][128] + `bias`, `tables` null) or as per-query
+// Tables come either per pair (`lut8sw` [npairs][plane][256][32] + `bias`, `tables` null) or as per-query
 // base tables with per-pair patches (`tables`, `lut8sw` null).
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
                 const LutTables* tables, const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids,

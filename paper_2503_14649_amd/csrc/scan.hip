@@ -7,37 +7,54 @@
 // and per query the best k of all its pairs by (I descending, id ascending).
 //
 // Work organisation
-//  * pairs are grouped by list; a task = (list, chunk of <= CH 64-vector blocks, up to two pairs
-//    of that list).  Both pairs' tables sit in LDS at once, so a code byte fetched once serves
-//    two queries.  Persistent workgroups pull task numbers from one atomic counter; consecutive
-//    task numbers share list and chunk, so repeats of a chunk hit in cache.
-//  * LDS table layout (64 KiB): byte address = code * 256 + slot * 4 + plane (+128 for the
-//    second pair).  `slot` selects the bank, so a sub-table lives in ONE bank; the 32 lanes of a
-//    half-wave always work on 32 different slots (see layout.hip), which makes every ds_read_u8
-//    conflict-free whatever the code values are.  The address is built with a single v_perm_b32
-//    from the code dword and a per-lane register holding slot*4 for four consecutive steps;
-//    plane and pair select ride in the instruction's immediate offset.
+//  * pairs are grouped by list; a task = (list, chunk of <= CH 64-vector blocks, up to FOUR pairs
+//    of that list).  The four pairs' tables sit in LDS interleaved byte by byte, so a code byte
+//    fetched once from HBM serves four queries with ONE 32-bit LDS read.  Persistent workgroups
+//    (one per CU) pull task numbers from one atomic counter.
+//  * LDS table layout: byte address = plane * 32768 + code * 128 + slot * 4 + cell, where the
+//    four cells of a dword belong to the four pairs (pair 0..3 in bytes 0, 2, 1, 3).  `slot`
+//    selects the bank, so a sub-table lives in ONE bank; the 32 lanes of a half-wave always work
+//    on 32 different slots (see layout.hip), which makes every ds_read_b32 conflict-free whatever
+//    the code values are.  One v_perm_b32 places two code bytes next to the lane's slot bytes
+//    (slot * 8), a bit-field extract / funnel shift by one bit turns each half into
+//    code * 128 + slot * 4; planes ride in the immediate offset (and, beyond its 64 KiB reach, in
+//    a flag bit of the slot byte and the funnel shift's upper operand).
+//  * accumulation is packed: with at most two pairs the cells in bytes 1 and 3 are zero and a plain
+//    32-bit add accumulates two 16-bit sums at once (sums are <= 128 * 255 < 2^16); with three or
+//    four pairs the odd bytes of two look-ups are gathered by one v_perm_b32 into 16-bit lanes of
+//    their own accumulators and subtracted from the running 32-bit sum at the end of the block.
 //  * one lane = one vector: 6 x dwordx4 loads (m = 96) per lane per block, 1 KiB contiguous per
 //    wave and load, next block's loads issued before the current block is processed.
-//  * selection: scores are <= 24480 so (score << 16 | 0xFFFF - position in chunk) is a 32-bit
+//  * selection: scores are <= 32640 so (score << 16 | 0xFFFF - position in chunk) is a 32-bit
 //    key whose order is (score desc, position asc) = (score desc, id asc) inside one list.
-//    Each wave keeps a private LDS buffer of keys above a running threshold and prunes it to the
-//    best k with a radix select on ballots (no barriers, no atomics in the streaming loop).
+//    Each wave keeps a private LDS buffer of keys per pair above a running threshold and prunes it
+//    to the best k with a radix select on ballots (no barriers, no atomics in the streaming loop).
 //    Thresholds are shared through LDS (per task) and through a per-query word in HBM
 //    (atomicMax of each finished task's k-th best score): a candidate below a score that k other
 //    candidates of the same query already reach can never be in the result.
-//  * each task writes <= k (I, id) entries; a final kernel per query merges them, sorts by
-//    (I desc, id asc) and writes ids / scores.
+//  * each task writes <= k (I, id) entries per pair; the waves that merge a finished task's
+//    buffers do so while the other waves already load the next task's tables; a final kernel per
+//    query merges the task results, sorts by (I desc, id asc) and writes ids / scores.
+#include <type_traits>
+
 #include "rago_internal.h"
 
 namespace rago {
 
-constexpr int SCAN_WAVES = 8;
-constexpr int SCAN_THREADS = SCAN_WAVES * 64;
-constexpr int CAPW = 192;  // keys per (wave, pair) buffer: k <= 128 survivors + one block of 64
-constexpr int LUT_LDS = 65536;
-constexpr int SCAN_LDS = LUT_LDS + SCAN_WAVES * 2 * CAPW * 4 + 512;
-constexpr int DESC_INTS = 20;   // task descriptor in LDS (see fetch_task)
+constexpr int NPMAX = 4;        // pairs (tables) per pass
+constexpr int CAPW = 192;       // keys per (wave, pair) buffer: k <= 128 survivors + one block of 64
+constexpr int DESC_INTS = 28;   // task descriptor in LDS (see fetch_task)
+constexpr int SH_INTS = 256;    // scalars + two descriptors
+
+template <int MPAD>
+struct ScanShape {
+    static constexpr int S = MPAD < 32 ? MPAD : 32;            // steps per plane
+    static constexpr int PLANES = MPAD < 32 ? 1 : MPAD / 32;
+    static constexpr int NW = MPAD > 96 ? 8 : 16;              // waves per workgroup (LDS-limited)
+    static constexpr int NT = NW * 64;
+    static constexpr int LUT_LDS = PLANES * 4 * LUT_PLANE;     // four interleaved tables
+    static constexpr int LDS = LUT_LDS + NW * NPMAX * CAPW * 4 + SH_INTS * 4 + NPMAX * 256 * 4;   // + merge histograms
+};
 
 struct ScanParams {
     const uint8_t* codes;
@@ -45,16 +62,16 @@ struct ScanParams {
     const int64_t* list_off;
     const int64_t* ids;
     const int32_t* probes;       // [npairs] list of each pair
-    const uint8_t* lut8sw;       // [npairs][256][128] swizzled per-pair tables, or null: use `T`
+    const uint8_t* lut8sw;       // [npairs] plane-major per-pair tables (stride LUT_BYTES), or null: use `T`
     LutTables T;                 // per-query base tables + per-pair patches
     const int32_t* bias;         // [npairs]
     int m;
     const int32_t* pair_sorted;  // pairs grouped by list
-    const int4* task_table;      // [ntasks] {list, chunk, pairA, pairB (-1: none)}
+    const int4* task_table;      // [ntasks] {list, chunk, first position in pair_sorted, number of pairs}
     int32_t* ctrl;               // [0] task counter, [1] number of tasks
     int32_t* tauq;               // [nq] lower bound of the k-th best integer score
     int32_t* part_I;             // [npairs][maxchunks][k]
-    int64_t* part_id;
+    int64_t* part_row;           // same shape: row of the entry in the list-major arrays
     int32_t* part_cnt;           // [npairs][maxchunks]
     int nlist, nprobe, k, CH, maxchunks;
 };
@@ -98,114 +115,125 @@ __device__ __forceinline__ uint32_t wave_prune(uint32_t* buf, int& cnt, int k, i
     return kth;
 }
 
-// All lookups of one 64-vector block: lane = vector.  Hand-scheduled: the compiler serialises
-// the byte loads behind full LDS waits and spills when given the plain C++ form.
+// Eight look-ups (two code dwords of one plane) in all resident tables at once.  Hand-scheduled:
+// the compiler serialises LDS reads behind full waits and spills when given the plain C++ form.
 //
-// One code dword `w` holds 4 consecutive steps of one plane; `o` holds slot*4 of those 4 steps.
-// v_perm_b32 puts code byte kb into byte 1 and o's byte kb into byte 0: address = code*256 + slot*4.
-// Selector kb = 0x0c0c0000 | (4+kb) << 8 | kb.  The table region starts at LDS address 0.
+// A code dword `w` holds 4 consecutive steps of one plane; `o` holds slot*8 of those 4 steps.
+// v_perm_b32 with selector SEL_A (SEL_B) builds {code1, slot1*8, code0, slot0*8} (codes 3, 2);
+// bits [16:1] of that are code0*128 + slot0*4 (+32768 when bit 0 of the next slot byte is set: the
+// flagged copies of `o` used for planes 2 and 3), and a funnel shift by 17 gives code1*128 +
+// slot1*4 with `HI` shifted in above (HI * 32768).  The table region starts at LDS address 0.
 // Each asm statement drains its own LDS reads (lgkmcnt(0)) before it ends, so the compiler's
 // own wait counts around it stay valid.
-#define RAGO_SEL0 0x0c0c0400u
-#define RAGO_SEL1 0x0c0c0501u
-#define RAGO_SEL2 0x0c0c0602u
-#define RAGO_SEL3 0x0c0c0703u
+#define RAGO_SEL_A 0x05010400u
+#define RAGO_SEL_B 0x07030602u
+#define RAGO_SEL_O1 0x0c050c01u   // {0, hi.byte1, 0, lo.byte1}
+#define RAGO_SEL_O3 0x0c070c03u   // {0, hi.byte3, 0, lo.byte3}
 
-// 16 lookups of one table (one dwordx4 = 4 code dwords, all in plane PL), added into `sum`.
-template <int PL>
-__device__ __forceinline__ void lookup16(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, uint32_t o0, uint32_t o1,
-                                         uint32_t o2, uint32_t o3, uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3,
-                                         uint32_t& sum) {
-    uint32_t t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile(
-        "v_perm_b32 %[t0], %[w0], %[o0], %[s0]\n v_perm_b32 %[t1], %[w0], %[o0], %[s1]\n"
-        "v_perm_b32 %[t2], %[w0], %[o0], %[s2]\n v_perm_b32 %[t3], %[w0], %[o0], %[s3]\n"
-        "ds_read_u8 %[t0], %[t0] offset:%[pl]\n ds_read_u8 %[t1], %[t1] offset:%[pl]\n"
-        "ds_read_u8 %[t2], %[t2] offset:%[pl]\n ds_read_u8 %[t3], %[t3] offset:%[pl]\n"
-        "v_perm_b32 %[t4], %[w1], %[o1], %[s0]\n v_perm_b32 %[t5], %[w1], %[o1], %[s1]\n"
-        "v_perm_b32 %[t6], %[w1], %[o1], %[s2]\n v_perm_b32 %[t7], %[w1], %[o1], %[s3]\n"
-        "ds_read_u8 %[t4], %[t4] offset:%[pl]\n ds_read_u8 %[t5], %[t5] offset:%[pl]\n"
-        "ds_read_u8 %[t6], %[t6] offset:%[pl]\n ds_read_u8 %[t7], %[t7] offset:%[pl]\n"
-        "v_perm_b32 %[t8], %[w2], %[o2], %[s0]\n v_perm_b32 %[t9], %[w2], %[o2], %[s1]\n"
-        "v_perm_b32 %[t10], %[w2], %[o2], %[s2]\n v_perm_b32 %[t11], %[w2], %[o2], %[s3]\n"
-        "ds_read_u8 %[t8], %[t8] offset:%[pl]\n ds_read_u8 %[t9], %[t9] offset:%[pl]\n"
-        "ds_read_u8 %[t10], %[t10] offset:%[pl]\n ds_read_u8 %[t11], %[t11] offset:%[pl]\n"
-        "v_perm_b32 %[t12], %[w3], %[o3], %[s0]\n v_perm_b32 %[t13], %[w3], %[o3], %[s1]\n"
-        "v_perm_b32 %[t14], %[w3], %[o3], %[s2]\n v_perm_b32 %[t15], %[w3], %[o3], %[s3]\n"
-        "ds_read_u8 %[t12], %[t12] offset:%[pl]\n ds_read_u8 %[t13], %[t13] offset:%[pl]\n"
-        "ds_read_u8 %[t14], %[t14] offset:%[pl]\n ds_read_u8 %[t15], %[t15] offset:%[pl]\n"
-        "s_waitcnt lgkmcnt(10)\n"
-        "v_add3_u32 %[t0], %[t0], %[t1], %[t2]\n v_add3_u32 %[t3], %[t3], %[t4], %[t5]\n"
-        "s_waitcnt lgkmcnt(4)\n"
-        "v_add3_u32 %[t6], %[t6], %[t7], %[t8]\n v_add3_u32 %[t9], %[t9], %[t10], %[t11]\n"
-        "v_add3_u32 %[sum], %[sum], %[t0], %[t3]\n"
-        "s_waitcnt lgkmcnt(0)\n"
-        "v_add3_u32 %[t12], %[t12], %[t13], %[t14]\n v_add3_u32 %[t6], %[t6], %[t9], %[t15]\n"
-        "v_add3_u32 %[sum], %[sum], %[t6], %[t12]\n"
-        : [sum] "+v"(sum), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3), [t4] "=&v"(t4), [t5] "=&v"(t5),
-          [t6] "=&v"(t6), [t7] "=&v"(t7), [t8] "=&v"(t8), [t9] "=&v"(t9), [t10] "=&v"(t10), [t11] "=&v"(t11),
-          [t12] "=&v"(t12), [t13] "=&v"(t13), [t14] "=&v"(t14), [t15] "=&v"(t15)
-        : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3), [o0] "v"(o0), [o1] "v"(o1), [o2] "v"(o2), [o3] "v"(o3),
-          [s0] "s"(s0), [s1] "s"(s1), [s2] "s"(s2), [s3] "s"(s3), [pl] "n"(PL)
-        : "memory");
+#define RAGO_LK_ADDR(W, O, A, B, C, D)                         \
+    "v_perm_b32 %[" #B "], %[" #W "], %[" #O "], %[sa]\n"      \
+    "v_perm_b32 %[" #D "], %[" #W "], %[" #O "], %[sb]\n"      \
+    "v_bfe_u32 %[" #A "], %[" #B "], 1, 16\n"                  \
+    "v_alignbit_b32 %[" #B "], %[hi], %[" #B "], 17\n"         \
+    "v_bfe_u32 %[" #C "], %[" #D "], 1, 16\n"                  \
+    "v_alignbit_b32 %[" #D "], %[hi], %[" #D "], 17\n"
+#define RAGO_LK_EXTRA(A, C) "v_add_u32 %[" #A "], 0x8000, %[" #A "]\n v_add_u32 %[" #C "], 0x8000, %[" #C "]\n"
+#define RAGO_LK_READ(A, B, C, D)                                                                   \
+    "ds_read_b32 %[" #A "], %[" #A "] offset:%[imm]\n ds_read_b32 %[" #B "], %[" #B "] offset:%[imm]\n" \
+    "ds_read_b32 %[" #C "], %[" #C "] offset:%[imm]\n ds_read_b32 %[" #D "], %[" #D "] offset:%[imm]\n"
+#define RAGO_LK_ALL(A, B, C, D) \
+    "v_add3_u32 %[all], %[all], %[" #A "], %[" #B "]\n v_add3_u32 %[all], %[all], %[" #C "], %[" #D "]\n"
+#define RAGO_LK_ODD(A, B, C, D, SEL, ACC)                                                          \
+    "v_perm_b32 %[p0], %[" #B "], %[" #A "], %[" #SEL "]\n v_perm_b32 %[p1], %[" #D "], %[" #C "], %[" #SEL "]\n" \
+    "v_add3_u32 %[" #ACC "], %[" #ACC "], %[p0], %[p1]\n"
+#define RAGO_LK_OPERANDS                                                                                       \
+    : [all] "+v"(all), [o1] "+v"(o1), [o3] "+v"(o3), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3), \
+      [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7), [p0] "=&v"(p0), [p1] "=&v"(p1)            \
+    : [w0] "v"(w0), [w1] "v"(w1), [oa] "v"(oa), [ob] "v"(ob), [sa] "s"(sa), [sb] "s"(sb), [so1] "s"(so1),      \
+      [so3] "s"(so3), [imm] "n"(IMM), [hi] "n"(HI)                                                             \
+    : "memory"
+
+// NPV = 2: cells 0 and 2 only (the others hold zeros); 3: + cell 1; 4: all four.
+template <int NPV, int IMM, int HI, bool EXTRA>
+__device__ __forceinline__ void lookup8(uint32_t w0, uint32_t w1, uint32_t oa, uint32_t ob, uint32_t sa, uint32_t sb,
+                                        uint32_t so1, uint32_t so3, uint32_t& all, uint32_t& o1, uint32_t& o3) {
+    uint32_t t0, t1, t2, t3, t4, t5, t6, t7, p0, p1;
+    if constexpr (!EXTRA && NPV == 2) {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ALL(t4, t5, t6, t7) RAGO_LK_OPERANDS);
+    } else if constexpr (!EXTRA && NPV == 3) {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ODD(t0, t1, t2, t3, so1, o1) RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ODD(t4, t5, t6, t7, so1, o1) RAGO_LK_ALL(t4, t5, t6, t7)
+                     RAGO_LK_OPERANDS);
+    } else if constexpr (!EXTRA && NPV == 4) {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ODD(t0, t1, t2, t3, so1, o1) RAGO_LK_ODD(t0, t1, t2, t3, so3, o3)
+                     RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ODD(t4, t5, t6, t7, so1, o1) RAGO_LK_ODD(t4, t5, t6, t7, so3, o3)
+                     RAGO_LK_ALL(t4, t5, t6, t7) RAGO_LK_OPERANDS);
+    } else if constexpr (EXTRA && NPV == 2) {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_EXTRA(t0, t2) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_EXTRA(t4, t6) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ALL(t4, t5, t6, t7) RAGO_LK_OPERANDS);
+    } else if constexpr (EXTRA && NPV == 3) {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_EXTRA(t0, t2) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_EXTRA(t4, t6) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ODD(t0, t1, t2, t3, so1, o1) RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ODD(t4, t5, t6, t7, so1, o1) RAGO_LK_ALL(t4, t5, t6, t7)
+                     RAGO_LK_OPERANDS);
+    } else {
+        asm volatile(RAGO_LK_ADDR(w0, oa, t0, t1, t2, t3) RAGO_LK_EXTRA(t0, t2) RAGO_LK_READ(t0, t1, t2, t3)
+                     RAGO_LK_ADDR(w1, ob, t4, t5, t6, t7) RAGO_LK_EXTRA(t4, t6) RAGO_LK_READ(t4, t5, t6, t7)
+                     "s_waitcnt lgkmcnt(4)\n" RAGO_LK_ODD(t0, t1, t2, t3, so1, o1) RAGO_LK_ODD(t0, t1, t2, t3, so3, o3)
+                     RAGO_LK_ALL(t0, t1, t2, t3)
+                     "s_waitcnt lgkmcnt(0)\n" RAGO_LK_ODD(t4, t5, t6, t7, so1, o1) RAGO_LK_ODD(t4, t5, t6, t7, so3, o3)
+                     RAGO_LK_ALL(t4, t5, t6, t7) RAGO_LK_OPERANDS);
+    }
 }
 
-// 8 lookups (2 code dwords) in each of the two resident tables (second table at +128).
-template <int PL>
-__device__ __forceinline__ void lookup8x2(uint32_t w0, uint32_t w1, uint32_t o0, uint32_t o1, uint32_t s0, uint32_t s1,
-                                          uint32_t s2, uint32_t s3, uint32_t& suma, uint32_t& sumb) {
-    uint32_t t0, t1, t2, t3, t4, t5, t6, t7, u0, u1, u2, u3, u4, u5, u6, u7;
-    asm volatile(
-        "v_perm_b32 %[t0], %[w0], %[o0], %[s0]\n v_perm_b32 %[t1], %[w0], %[o0], %[s1]\n"
-        "v_perm_b32 %[t2], %[w0], %[o0], %[s2]\n v_perm_b32 %[t3], %[w0], %[o0], %[s3]\n"
-        "ds_read_u8 %[u0], %[t0] offset:%[pb]\n ds_read_u8 %[u1], %[t1] offset:%[pb]\n"
-        "ds_read_u8 %[u2], %[t2] offset:%[pb]\n ds_read_u8 %[u3], %[t3] offset:%[pb]\n"
-        "ds_read_u8 %[t0], %[t0] offset:%[pa]\n ds_read_u8 %[t1], %[t1] offset:%[pa]\n"
-        "ds_read_u8 %[t2], %[t2] offset:%[pa]\n ds_read_u8 %[t3], %[t3] offset:%[pa]\n"
-        "v_perm_b32 %[t4], %[w1], %[o1], %[s0]\n v_perm_b32 %[t5], %[w1], %[o1], %[s1]\n"
-        "v_perm_b32 %[t6], %[w1], %[o1], %[s2]\n v_perm_b32 %[t7], %[w1], %[o1], %[s3]\n"
-        "ds_read_u8 %[u4], %[t4] offset:%[pb]\n ds_read_u8 %[u5], %[t5] offset:%[pb]\n"
-        "ds_read_u8 %[u6], %[t6] offset:%[pb]\n ds_read_u8 %[u7], %[t7] offset:%[pb]\n"
-        "ds_read_u8 %[t4], %[t4] offset:%[pa]\n ds_read_u8 %[t5], %[t5] offset:%[pa]\n"
-        "ds_read_u8 %[t6], %[t6] offset:%[pa]\n ds_read_u8 %[t7], %[t7] offset:%[pa]\n"
-        "s_waitcnt lgkmcnt(12)\n"
-        "v_add3_u32 %[sumb], %[sumb], %[u0], %[u1]\n v_add_u32 %[u2], %[u2], %[u3]\n"
-        "s_waitcnt lgkmcnt(8)\n"
-        "v_add3_u32 %[suma], %[suma], %[t0], %[t1]\n v_add_u32 %[t2], %[t2], %[t3]\n"
-        "s_waitcnt lgkmcnt(4)\n"
-        "v_add3_u32 %[u4], %[u4], %[u5], %[u6]\n v_add3_u32 %[sumb], %[sumb], %[u2], %[u7]\n"
-        "s_waitcnt lgkmcnt(0)\n"
-        "v_add3_u32 %[t4], %[t4], %[t5], %[t6]\n v_add3_u32 %[suma], %[suma], %[t2], %[t7]\n"
-        "v_add_u32 %[sumb], %[sumb], %[u4]\n v_add_u32 %[suma], %[suma], %[t4]\n"
-        : [suma] "+v"(suma), [sumb] "+v"(sumb), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
-          [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7), [u0] "=&v"(u0), [u1] "=&v"(u1), [u2] "=&v"(u2),
-          [u3] "=&v"(u3), [u4] "=&v"(u4), [u5] "=&v"(u5), [u6] "=&v"(u6), [u7] "=&v"(u7)
-        : [w0] "v"(w0), [w1] "v"(w1), [o0] "v"(o0), [o1] "v"(o1), [s0] "s"(s0), [s1] "s"(s1), [s2] "s"(s2), [s3] "s"(s3),
-          [pa] "n"(PL), [pb] "n"(PL + 128)
-        : "memory");
-}
+struct Sel { uint32_t a, b, o1, o3; };
 
-template <int MPAD, int Q, int I>
-__device__ __forceinline__ void block_sums_chunk(const uint4 (&w)[MPAD / 16], const uint32_t (&off)[(MPAD < 32 ? MPAD : 32) / 4],
-                                                 uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, uint32_t& sa, uint32_t& sb) {
-    constexpr int S = MPAD < 32 ? MPAD : 32;
+template <int MPAD, int NPV, int I>
+__device__ __forceinline__ void block_sums_chunk(const uint4 (&w)[MPAD / 16], const uint32_t (&off)[ScanShape<MPAD>::S / 4],
+                                                 const Sel& sel, uint32_t& all, uint32_t& o1, uint32_t& o3) {
+    constexpr int S = ScanShape<MPAD>::S;
     constexpr int PL = (I * 16) / S;               // plane of this dwordx4
     constexpr int G = ((I * 16) % S) / 4;          // first of its four step groups
-    if (Q == 1) {
-        lookup16<PL>(w[I].x, w[I].y, w[I].z, w[I].w, off[G], off[G + 1], off[G + 2], off[G + 3], s0, s1, s2, s3, sa);
+    constexpr int IMM = PL >= 1 ? 32768 : 0;
+    constexpr int HI = PL == 2 ? 1 : (PL == 3 ? 2 : 0);
+    if constexpr (PL < 2) {
+        lookup8<NPV, IMM, HI, false>(w[I].x, w[I].y, off[G], off[G + 1], sel.a, sel.b, sel.o1, sel.o3, all, o1, o3);
+        lookup8<NPV, IMM, HI, false>(w[I].z, w[I].w, off[G + 2], off[G + 3], sel.a, sel.b, sel.o1, sel.o3, all, o1, o3);
     } else {
-        lookup8x2<PL>(w[I].x, w[I].y, off[G], off[G + 1], s0, s1, s2, s3, sa, sb);
-        lookup8x2<PL>(w[I].z, w[I].w, off[G + 2], off[G + 3], s0, s1, s2, s3, sa, sb);
+        // (+32768 for the even look-ups of planes 2 and 3: bit 0 of the following slot byte)
+        constexpr uint32_t F = 0x01000100u;
+        lookup8<NPV, IMM, HI, PL == 3>(w[I].x, w[I].y, off[G] | F, off[G + 1] | F, sel.a, sel.b, sel.o1, sel.o3, all, o1, o3);
+        lookup8<NPV, IMM, HI, PL == 3>(w[I].z, w[I].w, off[G + 2] | F, off[G + 3] | F, sel.a, sel.b, sel.o1, sel.o3, all, o1, o3);
     }
-    if constexpr (I + 1 < MPAD / 16) block_sums_chunk<MPAD, Q, I + 1>(w, off, s0, s1, s2, s3, sa, sb);
+    if constexpr (I + 1 < MPAD / 16) block_sums_chunk<MPAD, NPV, I + 1>(w, off, sel, all, o1, o3);
 }
 
-template <int MPAD, int Q>
-__device__ __forceinline__ void block_sums(const uint4 (&w)[MPAD / 16], const uint32_t (&off)[(MPAD < 32 ? MPAD : 32) / 4],
-                                           uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, uint32_t& sa, uint32_t& sb) {
-    sa = 0;
-    sb = 0;
-    block_sums_chunk<MPAD, Q, 0>(w, off, s0, s1, s2, s3, sa, sb);
+// Sums of one 64-vector block (lane = vector) for the pairs in cells 0..NPV-1: sum[pair].
+template <int MPAD, int NPV>
+__device__ __forceinline__ void block_sums(const uint4 (&w)[MPAD / 16], const uint32_t (&off)[ScanShape<MPAD>::S / 4],
+                                           const Sel& sel, uint32_t (&sum)[NPMAX]) {
+    uint32_t all = 0, o1 = 0, o3 = 0;
+    block_sums_chunk<MPAD, NPV, 0>(w, off, sel, all, o1, o3);
+    // cells: pair 0 = byte 0, pair 1 = byte 2, pair 2 = byte 1, pair 3 = byte 3
+    const uint32_t s2 = (o1 & 0xFFFFu) + (o1 >> 16), s3 = (o3 & 0xFFFFu) + (o3 >> 16);
+    uint32_t even = all;
+    if (NPV >= 3) even -= s2 << 8;
+    if (NPV >= 4) even -= s3 << 24;
+    sum[0] = even & 0xFFFFu;
+    sum[1] = even >> 16;
+    sum[2] = s2;
+    sum[3] = s3;
 }
 
 // Append the lanes whose sum reaches the threshold to the wave's key buffer (prune when full).
@@ -225,44 +253,13 @@ __device__ __forceinline__ void offer(bool valid, uint32_t sum, uint32_t pos, ui
     cnt += add;
 }
 
-// Copy swizzled tables (256 rows of 128 B) into the two halves of the 256-byte LDS rows; a null
-// source leaves that half untouched.  `between` runs after the loads are issued and before their
-// data is needed (the caller puts the first code-block loads there, so they queue behind the
-// table loads instead of in front of them: the load counter retires in order).
-template <class F>
-__device__ __forceinline__ void copy_table(const uint4* srcA, const uint4* srcB, uint8_t* lut, F between) {
-    // (named scalars, not arrays: conditionally filled arrays end up in scratch memory)
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    uint4 a0 = z, a1 = z, a2 = z, a3 = z, b0 = z, b1 = z, b2 = z, b3 = z;
-    const int t = threadIdx.x;
-    if (srcA) { a0 = srcA[t]; a1 = srcA[t + SCAN_THREADS]; a2 = srcA[t + 2 * SCAN_THREADS]; a3 = srcA[t + 3 * SCAN_THREADS]; }
-    if (srcB) { b0 = srcB[t]; b1 = srcB[t + SCAN_THREADS]; b2 = srcB[t + 2 * SCAN_THREADS]; b3 = srcB[t + 3 * SCAN_THREADS]; }
-    between();
-    // piece p = 16 bytes: row p >> 3, column (p & 7) * 16 of the 128-byte table row
-    uint8_t* d0 = lut + (t >> 3) * 256 + (t & 7) * 16;
-    constexpr int STEP = (SCAN_THREADS >> 3) * 256;   // rows advanced by SCAN_THREADS pieces
-    if (srcA) {
-        *reinterpret_cast<uint4*>(d0) = a0;
-        *reinterpret_cast<uint4*>(d0 + STEP) = a1;
-        *reinterpret_cast<uint4*>(d0 + 2 * STEP) = a2;
-        *reinterpret_cast<uint4*>(d0 + 3 * STEP) = a3;
-    }
-    if (srcB) {
-        *reinterpret_cast<uint4*>(d0 + 128) = b0;
-        *reinterpret_cast<uint4*>(d0 + 128 + STEP) = b1;
-        *reinterpret_cast<uint4*>(d0 + 128 + 2 * STEP) = b2;
-        *reinterpret_cast<uint4*>(d0 + 128 + 3 * STEP) = b3;
-    }
-}
-
-struct ScanParams;
-__device__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot);
-
-// The code stream is read through pointers explicitly in the global address space: a generic
-// (flat) load would also count on the LDS/scalar wait counter and every hand-placed
-// s_waitcnt lgkmcnt in the look-up code would then wait for HBM.
+// The code stream and the tables are read through pointers explicitly in the global address
+// space: a generic (flat) load would also count on the LDS/scalar wait counter and every
+// hand-placed s_waitcnt lgkmcnt in the look-up code would then wait for HBM.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
+typedef const __attribute__((address_space(1))) u32x2* global_u32x2_ptr;
 
 template <int MPAD>
 __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t* blk, int lane) {
@@ -274,21 +271,89 @@ __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t*
     }
 }
 
-// Full per-pair evaluation of a table straight into an LDS slot (queries whose tables are too
+__device__ __forceinline__ int cell_byte(int pair_slot) { return pair_slot == 0 ? 0 : (pair_slot == 1 ? 2 : (pair_slot == 2 ? 1 : 3)); }
+
+// Everything a wave holds of a task before the task's tables are in LDS: the scalars of its
+// descriptor and, in flight from HBM, its share of the tables, the first 64 patches of each
+// pair and the query's current bound.
+struct Task {
+    int tid, chunk, np, nb, cvecs;
+    int pair[NPMAX], bias[NPMAX], qq[NPMAX], namb[NPMAX];
+    const uint8_t* base;     // first code block of the chunk
+    unsigned use, evalm;     // cells with a base table / cells evaluated entry by entry
+    bool same;               // the cells already hold these queries' base tables
+};
+
+template <int MPAD>
+struct TableRegs {
+    static constexpr int PER = ScanShape<MPAD>::PLANES * 1024 / ScanShape<MPAD>::NT;
+    static_assert(ScanShape<MPAD>::PLANES * 1024 % ScanShape<MPAD>::NT == 0, "pieces must divide over the threads");
+    u32x2 a[PER], b[PER], c[PER], d[PER];
+    uint32_t pa[NPMAX], pv[NPMAX];
+    int32_t tau;
+};
+
+// Interleave up to four plane-major tables (HBM, [plane][c][slot] bytes) into the LDS table
+// region: dword (plane, c, slot) = {src0, src2, src1, src3} bytes; `use` bit s clear = zeros in
+// that cell.  Piece p = 8 consecutive entries (8 source bytes per table, 32 bytes of LDS),
+// handled by thread p mod NT.  Loading and storing are separate so that the round trip to HBM
+// overlaps the end of the previous task.
+template <int MPAD>
+__device__ __forceinline__ void load_tables(TableRegs<MPAD>& R, const uint8_t* s0, const uint8_t* s1, const uint8_t* s2,
+                                            const uint8_t* s3) {
+    // every source pointer must be readable (absent tables alias a present one)
+#pragma unroll
+    for (int r = 0; r < TableRegs<MPAD>::PER; ++r) {
+        const int p = threadIdx.x + r * ScanShape<MPAD>::NT;
+        R.a[r] = ((global_u32x2_ptr)s0)[p];
+        R.b[r] = ((global_u32x2_ptr)s1)[p];
+        R.c[r] = ((global_u32x2_ptr)s2)[p];
+        R.d[r] = ((global_u32x2_ptr)s3)[p];
+    }
+}
+
+template <int MPAD>
+__device__ __forceinline__ void store_tables(const TableRegs<MPAD>& R, unsigned use, uint8_t* lut) {
+    const uint32_t m0 = (use & 1u) ? ~0u : 0u, m1 = (use & 2u) ? ~0u : 0u, m2 = (use & 4u) ? ~0u : 0u, m3 = (use & 8u) ? ~0u : 0u;
+#pragma unroll
+    for (int r = 0; r < TableRegs<MPAD>::PER; ++r) {
+        const int p = threadIdx.x + r * ScanShape<MPAD>::NT;
+        uint4 out[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t aw = (h ? R.a[r].y : R.a[r].x) & m0, bw = (h ? R.b[r].y : R.b[r].x) & m1;
+            const uint32_t cw = (h ? R.c[r].y : R.c[r].x) & m2, dw = (h ? R.d[r].y : R.d[r].x) & m3;
+            // bytes 0 and 1 of a dword come from tables 0 and 2, bytes 2 and 3 from tables 1 and 3
+            const uint32_t lo01 = __builtin_amdgcn_perm(cw, aw, 0x05010400u), lo23 = __builtin_amdgcn_perm(cw, aw, 0x07030602u);
+            const uint32_t hi01 = __builtin_amdgcn_perm(dw, bw, 0x05010400u), hi23 = __builtin_amdgcn_perm(dw, bw, 0x07030602u);
+            out[h] = make_uint4(__builtin_amdgcn_perm(hi01, lo01, 0x05040100u), __builtin_amdgcn_perm(hi01, lo01, 0x07060302u),
+                                __builtin_amdgcn_perm(hi23, lo23, 0x05040100u), __builtin_amdgcn_perm(hi23, lo23, 0x07060302u));
+        }
+        uint4* dst = reinterpret_cast<uint4*>(lut + (int64_t)p * 32);
+        dst[0] = out[0];
+        dst[1] = out[1];
+    }
+}
+
+// Full per-pair evaluation of a table straight into its LDS cells (queries whose tables are too
 // flat for the base + patch form).
-__device__ __forceinline__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* slot) {
+template <int NT>
+__device__ __forceinline__ void eval_table(const ScanParams& P, int pair, int q, uint8_t* cell) {
     const int m = P.m, S = rago_steps(m);
     const float dq = lut_step(__uint_as_float(P.T.range_bits[q]));
-    for (int e = threadIdx.x; e < m * KSUB; e += SCAN_THREADS) {
+    for (int e = threadIdx.x; e < m * KSUB; e += NT) {
         const int j = e >> 8, c = e & 255;
         const double t = P.T.t64[(int64_t)pair * m + j];
         const uint8_t v = lut_entry(P.T.T64[((int64_t)q * m + j) * KSUB + c], t, (float)(P.T.Tmin[(int64_t)q * m + j] + t), dq);
-        for (int rep = j & (S - 1); rep < 32; rep += S) slot[c * 256 + rep * 4 + (j >> 5)] = v;
+        for (int rep = j & (S - 1); rep < 32; rep += S) cell[((j >> 5) * LUT_PLANE + c * 32 + rep) * 4] = v;
     }
 }
 
 // Claim the next task and put everything its prologue needs into LDS (run by ONE wave; all
 // values are wave-uniform so the loads are scalar).  d[0] = task number or -1 when none is left.
+// d[1] list, d[2] chunk, d[3] pairs in the task, d[4..7] pair, d[8..11] bias, d[12..15] query,
+// d[16..19] ambiguous entries of the query, d[20..21] first block, d[22] blocks of the list,
+// d[23..24] first vector, d[25] vectors of the list.
 __device__ __forceinline__ void fetch_task(const ScanParams& P, int ntasks, int32_t* d, int lane) {
     int t = 0;
     if (lane == 0) t = atomicAdd(P.ctrl, 1);
@@ -298,29 +363,158 @@ __device__ __forceinline__ void fetch_task(const ScanParams& P, int ntasks, int3
         return;
     }
     const int4 rec = P.task_table[t];
-    const int l = rec.x, pairA = rec.z, pairB = rec.w;
+    const int l = rec.x, np = rec.w;
     const int64_t b0 = P.blk_off[l], v0 = P.list_off[l];
     const int nblk = (int)(P.blk_off[l + 1] - b0), len = (int)(P.list_off[l + 1] - v0);
-    const int qA = pairA / P.nprobe, qB = pairB >= 0 ? pairB / P.nprobe : 0;
-    const int biasA = P.bias[pairA], biasB = pairB >= 0 ? P.bias[pairB] : 0;
-    int nA = 0, nB = 0;
-    if (!P.lut8sw) { nA = P.T.namb[qA]; nB = pairB >= 0 ? P.T.namb[qB] : 0; }
+    int pr[NPMAX], q[NPMAX], bias[NPMAX], na[NPMAX];
+#pragma unroll
+    for (int s = 0; s < NPMAX; ++s) {
+        pr[s] = P.pair_sorted[rec.z + (s < np ? s : 0)];
+        q[s] = pr[s] / P.nprobe;
+        bias[s] = P.bias[pr[s]];
+        na[s] = P.lut8sw ? 0 : P.T.namb[q[s]];
+    }
     if (lane == 0) {
-        d[0] = t; d[1] = l; d[2] = rec.y; d[3] = pairA; d[4] = pairB; d[5] = biasA; d[6] = biasB; d[7] = qA; d[8] = qB;
-        d[9] = (int32_t)(uint32_t)b0; d[10] = (int32_t)(b0 >> 32); d[11] = nblk;
-        d[12] = (int32_t)(uint32_t)v0; d[13] = (int32_t)(v0 >> 32); d[14] = len; d[15] = nA; d[16] = nB;
+        d[0] = t; d[1] = l; d[2] = rec.y; d[3] = np;
+#pragma unroll
+        for (int s = 0; s < NPMAX; ++s) { d[4 + s] = pr[s]; d[8 + s] = bias[s]; d[12 + s] = q[s]; d[16 + s] = na[s]; }
+        d[20] = (int32_t)(uint32_t)b0; d[21] = (int32_t)(b0 >> 32); d[22] = nblk;
+        d[23] = (int32_t)(uint32_t)v0; d[24] = (int32_t)(v0 >> 32); d[25] = len;
+    }
+}
+
+// A finished task's result (<= k entries per pair) is produced by one wave per pair cell from the
+// keys of all the workgroup's buffers of that cell, between the barrier that ends the task's
+// stream and the one that starts the next task's.  The keys stay in the LDS buffers and are
+// re-read on every pass (a register copy of up to 2 x NW keys per lane would have to live
+// alongside the next task's table data, which is in flight at this point).
+//
+// When the buffers hold k keys or more, the k-th largest is found by 8-bit radix passes over a
+// 256-bin LDS histogram owned by the wave (a ballot radix select costs 32 wave-wide votes per
+// key register, far too many here).  The passes start at the highest bit on which the keys
+// differ: the bits above it are common to all keys, and a histogram of them would pile every key
+// onto one LDS address.
+template <int NW, class F>
+__device__ __forceinline__ void for_each_key(const uint32_t* cand, int s, int myn, int lane, F f) {
+#pragma unroll 4
+    for (int w = 0; w < NW; ++w) {
+        const int n = __builtin_amdgcn_readlane(myn, w);
+        const uint32_t* bw = cand + (w * NPMAX + s) * CAPW;
+        const uint32_t k0 = bw[lane], k1 = bw[lane + 64];       // (inside the buffer's CAPW entries whatever its fill)
+        f(lane < n ? k0 : 0u);
+        f(lane + 64 < n ? k1 : 0u);
+    }
+}
+
+template <int NW>
+__device__ __forceinline__ uint32_t select_kth_lds(const uint32_t* cand, int s, int myn, int k, uint32_t* hist, int lane) {
+    uint32_t orv = 0u, andv = ~0u;
+    for_each_key<NW>(cand, s, myn, lane, [&](uint32_t key) {
+        orv |= key;
+        andv &= key ? key : ~0u;
+    });
+#pragma unroll
+    for (int o = 32; o; o >>= 1) {
+        orv |= __shfl_xor(orv, o);
+        andv &= __shfl_xor(andv, o);
+    }
+    orv = __builtin_amdgcn_readfirstlane(orv);
+    andv = __builtin_amdgcn_readfirstlane(andv);
+    const uint32_t vary = orv & ~andv;
+    if (vary == 0u) return orv;                    // one distinct key
+    const int hb = 31 - __builtin_clz(vary);
+    uint32_t mask = hb == 31 ? 0u : ~((2u << hb) - 1u);   // bits decided so far
+    uint32_t prefix = orv & mask;
+    int rem = k;
+    for (int shift = hb > 7 ? hb - 7 : 0;; shift = shift > 8 ? shift - 8 : 0) {
+        reinterpret_cast<uint4*>(hist)[lane] = make_uint4(0u, 0u, 0u, 0u);   // (LDS operations of one wave execute in order)
+        for_each_key<NW>(cand, s, myn, lane, [&](uint32_t key) {
+            if (key != 0u && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        });
+        const uint4 h = reinterpret_cast<const uint4*>(hist)[lane];          // bins 4*lane .. 4*lane + 3
+        const int c = (int)(h.x + h.y + h.z + h.w);
+        int sfx = c;                                                           // keys in this lane's bins and all higher ones
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_down(sfx, o);
+            if (lane + o < 64) sfx += t;
+        }
+        const uint64_t reach = __ballot(sfx >= rem);                           // never empty: at least `rem` keys match the prefix
+        const int L = 63 - __builtin_clzll(reach);
+        int need = rem - (__builtin_amdgcn_readlane(sfx, L) - __builtin_amdgcn_readlane(c, L));
+        const int hw = __builtin_amdgcn_readlane((int)h.w, L), hz = __builtin_amdgcn_readlane((int)h.z, L);
+        const int hy = __builtin_amdgcn_readlane((int)h.y, L);
+        int dgt;
+        if (hw >= need) dgt = 3;
+        else if (hw + hz >= need) { dgt = 2; need -= hw; }
+        else if (hw + hz + hy >= need) { dgt = 1; need -= hw + hz; }
+        else { dgt = 0; need -= hw + hz + hy; }
+        rem = need;
+        // (a window may overlap bits decided before: the keys still in play agree on them)
+        prefix = (prefix & ~(255u << shift)) | ((uint32_t)(4 * L + dgt) << shift);
+        mask |= 255u << shift;
+        if (shift == 0) break;
+    }
+    return prefix;
+}
+
+template <int NW>
+__device__ __forceinline__ void merge_task(const ScanParams& P, const int32_t* D, int s, const uint32_t* cand, const int32_t* sh,
+                                           uint32_t* hist, int lane) {
+    const int k = P.k;
+    const int chunk = __builtin_amdgcn_readfirstlane(D[2]);
+    const int pr = __builtin_amdgcn_readfirstlane(D[4 + s]), bias = __builtin_amdgcn_readfirstlane(D[8 + s]);
+    const int q = __builtin_amdgcn_readfirstlane(D[12 + s]);
+    const int64_t v0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[24]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[23]);
+    const int myn = lane < NW ? sh[8 + lane * NPMAX + s] : 0;     // lane w: fill of wave w's buffer
+    int total = myn;
+#pragma unroll
+    for (int o = 32; o; o >>= 1) total += __shfl_xor(total, o);
+    total = __builtin_amdgcn_readfirstlane(total);
+    uint32_t kth = 1u;
+    if (total >= k) kth = select_kth_lds<NW>(cand, s, myn, k, hist, lane);
+    const int64_t slot = (int64_t)pr * P.maxchunks + chunk;
+    int32_t* oI = P.part_I + slot * k;
+    int64_t* orow = P.part_row + slot * k;
+    // (rows, not ids: translating them here would put a dependent HBM round trip into every step
+    // of this loop; the final merge looks up the ids of the few entries that survive)
+    const int64_t row0 = v0 + (int64_t)chunk * P.CH * BLOCK_VECS;
+    int base_o = 0;
+    for_each_key<NW>(cand, s, myn, lane, [&](uint32_t key) {
+        const bool keep = key >= kth && key != 0u;
+        const uint64_t mask = __ballot(keep);
+        if (mask != 0) {
+            if (keep) {
+                const int o = base_o + lane_rank(mask);
+                oI[o] = bias + (int32_t)(key >> 16);
+                orow[o] = row0 + (int64_t)(0xFFFFu - (key & 0xFFFFu));
+            }
+            base_o += __popcll(mask);
+        }
+    });
+    if (lane == 0) {
+        P.part_cnt[slot] = base_o;
+        // k entries reach the k-th key's score: a valid lower bound of the query's k-th best
+        if (total >= k) atomicMax(P.tauq + q, bias + (int32_t)(kth >> 16));
     }
 }
 
 // ------------------------------------------------------------------ the scan kernel
+// Per task: [install] tables from registers into LDS, patches, thresholds - barrier - [stream] -
+// next task's descriptor (first wave to finish) and, as soon as a wave has that descriptor, its
+// share of the next task's table loads - trim own buffers - barrier - [merge] (one wave per pair)
+// while the table loads are in flight - back to [install].
 template <int MPAD>
-__global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams P) {
-    constexpr int S = MPAD < 32 ? MPAD : 32;
+__global__ void __launch_bounds__(ScanShape<MPAD>::NT) scan_kernel(const ScanParams P) {
+    using SH = ScanShape<MPAD>;
+    constexpr int S = SH::S, NW = SH::NW, NT = SH::NT;
     extern __shared__ __align__(16) uint8_t smem[];
     uint8_t* lut = smem;
-    uint32_t* cand = reinterpret_cast<uint32_t*>(smem + LUT_LDS);                         // [wave][pair][CAPW]
-    int32_t* sh = reinterpret_cast<int32_t*>(smem + LUT_LDS + SCAN_WAVES * 2 * CAPW * 4);  // scalars
-    // sh[2..3] tau per pair (sum units), sh[4] block counter, sh[5] finisher ticket, sh[8 + wave*2 + pair] wave counts, sh[32..] descriptors
+    uint32_t* cand = reinterpret_cast<uint32_t*>(smem + SH::LUT_LDS);                          // [wave][pair][CAPW]
+    int32_t* sh = reinterpret_cast<int32_t*>(smem + SH::LUT_LDS + NW * NPMAX * CAPW * 4);      // scalars
+    uint32_t* hist = reinterpret_cast<uint32_t*>(sh + SH_INTS);                                // [pair][256] merge histograms
+    // sh[0..3] tau per pair (sum units), sh[4] block counter, sh[5] finisher ticket,
+    // sh[8 + wave*4 + pair] wave counts, sh[80..] three task descriptors
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     uint32_t off[S / 4];
@@ -331,191 +525,225 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
         for (int b = 0; b < 4; ++b) {
             const int step = g * 4 + b, l32 = lane & 31;
             const int slot = ((step + l32) & (S - 1)) | (l32 & ~(S - 1));
-            v |= (uint32_t)(slot * 4) << (8 * b);
+            v |= (uint32_t)(slot * 8) << (8 * b);
         }
         off[g] = v;
     }
     const int ntasks = P.ctrl[1];
-    int loadedA = -1, loadedB = -1;   // query whose base table currently sits in each LDS slot
-    // selectors live in SGPRs (VOP3 takes no literal on gfx9); the asm fence keeps them out of constant folding
-    uint32_t sel0 = RAGO_SEL0, sel1 = RAGO_SEL1, sel2 = RAGO_SEL2, sel3 = RAGO_SEL3;
+    int loaded0 = -3, loaded1 = -3, loaded2 = -3, loaded3 = -3;   // query whose base table sits in each cell (-2: zeros)
+    Sel sel{RAGO_SEL_A, RAGO_SEL_B, RAGO_SEL_O1, RAGO_SEL_O3};
     const int k = P.k;
-    int32_t* desc = sh + 32;          // two task descriptors: the running task and the prefetched next one
+    int32_t* desc = sh + 80;          // ring of three task descriptors: the previous (being merged) / running task, the next, the one after
+    constexpr int64_t BLK_BYTES = BLOCK_VECS * MPAD;
 
-    if (wave == SCAN_WAVES - 1) fetch_task(P, ntasks, desc, lane);
-    __syncthreads();
-    for (int cur = 0;; cur ^= 1) {
-        const int32_t* D = desc + cur * DESC_INTS;
-        const int tid = __builtin_amdgcn_readfirstlane(D[0]);
-        if (tid < 0) break;           // every wave reads the same descriptor: all leave together
-        const int chunk = __builtin_amdgcn_readfirstlane(D[2]);
-        const int pairA = __builtin_amdgcn_readfirstlane(D[3]), pairB = __builtin_amdgcn_readfirstlane(D[4]);
-        const int biasA = __builtin_amdgcn_readfirstlane(D[5]), biasB = __builtin_amdgcn_readfirstlane(D[6]);
-        const int qA = __builtin_amdgcn_readfirstlane(D[7]), qB = __builtin_amdgcn_readfirstlane(D[8]);
-        const int64_t b0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[10]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[9]);
-        const int nblk_list = __builtin_amdgcn_readfirstlane(D[11]);
-        const int64_t v0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[13]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[12]);
-        const int len = __builtin_amdgcn_readfirstlane(D[14]);
-        const int nA = __builtin_amdgcn_readfirstlane(D[15]), nB = __builtin_amdgcn_readfirstlane(D[16]);
-        const int cb0 = chunk * P.CH;
-        const int nb = min(P.CH, nblk_list - cb0);
-        const int cvec0 = cb0 * BLOCK_VECS;          // first vector of the chunk inside the list
-        const int cvecs = min(len - cvec0, nb * BLOCK_VECS);
-        // the wave's first block is requested before the tables are touched
-        constexpr int64_t BLK_BYTES = BLOCK_VECS * MPAD;
-        const uint8_t* base = P.codes + (b0 + cb0) * BLK_BYTES;
-        uint4 cur_w[MPAD / 16], nxt_w[MPAD / 16];
-        int b = wave;
-        // (every load of the stream is unconditional, with the block number clamped into the chunk: a
-        // conditional prefetch makes the compiler wait for ALL outstanding loads before each use)
-        auto first_load = [&]() { load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane); };
+    uint4 cur_w[MPAD / 16], nxt_w[MPAD / 16];
+    TableRegs<MPAD> R;
 
-        // ---- tables into LDS (rows of 128 B into rows of 256 B), thresholds
-        if (P.lut8sw) {
-            const uint4* srcA = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)pairA * LUT_BYTES);
-            const uint4* srcB = reinterpret_cast<const uint4*>(P.lut8sw + (int64_t)(pairB >= 0 ? pairB : pairA) * LUT_BYTES);
-            copy_table(srcA, pairB >= 0 ? srcB : nullptr, lut, first_load);
-            loadedA = loadedB = -1;
-        } else {
-            // base table of the query (kept while consecutive tasks use the same query in this slot),
-            // then the pair's patches; flagged queries are evaluated entry by entry
-            const bool baseA = nA <= AMB_MAX && loadedA != qA;
-            const bool baseB = pairB >= 0 && nB <= AMB_MAX && loadedB != qB;
-            // Patches are written by the wave that copies the 16-byte piece they fall into, so program
-            // order inside the wave puts them after the copy and no workgroup barrier is needed in between.
-            // Piece of LDS offset a: row a >> 8, column (a & 127) >> 4; copied by thread (piece & 511).
-            // (the arrays always hold AMB_MAX entries, so the first 64 can be read unconditionally)
-            const bool useA = nA <= AMB_MAX, useB = pairB >= 0 && nB <= AMB_MAX;
-            const uint32_t a0 = P.T.amb_addr[(int64_t)qA * AMB_MAX + lane];
-            const uint32_t v0 = P.T.patch_val[(int64_t)pairA * AMB_MAX + lane];
-            const uint32_t a1 = P.T.amb_addr[(int64_t)(pairB >= 0 ? qB : qA) * AMB_MAX + lane];
-            const uint32_t v1 = P.T.patch_val[(int64_t)(pairB >= 0 ? pairB : pairA) * AMB_MAX + lane];
-            copy_table(baseA ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qA * LUT_BYTES) : nullptr,
-                       baseB ? reinterpret_cast<const uint4*>(P.T.lut_base + (int64_t)qB * LUT_BYTES) : nullptr, lut, first_load);
-            if (nA > AMB_MAX) eval_table(P, pairA, qA, lut);
-            if (pairB >= 0 && nB > AMB_MAX) eval_table(P, pairB, qB, lut + 128);
-            auto owner = [](uint32_t a) { return ((((a >> 8) << 3) | ((a & 127u) >> 4)) & 511u) >> 6; };
-            if (useA && lane < nA && owner(a0) == (uint32_t)wave) lut[a0] = (uint8_t)v0;
-            if (useB && lane < nB && owner(a1) == (uint32_t)wave) lut[128 + a1] = (uint8_t)v1;
-            if (useA)
-                for (int i = 64 + lane; i < nA; i += 64) {
-                    const uint32_t a = P.T.amb_addr[(int64_t)qA * AMB_MAX + i];
-                    if (owner(a) == (uint32_t)wave) lut[a] = P.T.patch_val[(int64_t)pairA * AMB_MAX + i];
-                }
-            if (useB)
-                for (int i = 64 + lane; i < nB; i += 64) {
-                    const uint32_t a = P.T.amb_addr[(int64_t)qB * AMB_MAX + i];
-                    if (owner(a) == (uint32_t)wave) lut[128 + a] = P.T.patch_val[(int64_t)pairB * AMB_MAX + i];
-                }
-            loadedA = nA <= AMB_MAX ? qA : -1;
-            if (pairB >= 0) loadedB = nB <= AMB_MAX ? qB : -1;
+    // descriptor -> task scalars (all wave-uniform)
+    auto decode = [&](const int32_t* D, Task& T) {
+        T.tid = __builtin_amdgcn_readfirstlane(D[0]);
+        T.chunk = __builtin_amdgcn_readfirstlane(D[2]);
+        T.np = __builtin_amdgcn_readfirstlane(D[3]);
+#pragma unroll
+        for (int s = 0; s < NPMAX; ++s) {
+            T.pair[s] = __builtin_amdgcn_readfirstlane(D[4 + s]);
+            T.bias[s] = __builtin_amdgcn_readfirstlane(D[8 + s]);
+            T.qq[s] = __builtin_amdgcn_readfirstlane(D[12 + s]);
+            T.namb[s] = __builtin_amdgcn_readfirstlane(D[16 + s]);
         }
-        if (threadIdx.x < 2) {
-            const int pr = threadIdx.x == 0 ? pairA : pairB;
+        const int64_t b0 = ((int64_t)__builtin_amdgcn_readfirstlane(D[21]) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(D[20]);
+        const int nblk_list = __builtin_amdgcn_readfirstlane(D[22]);
+        const int len = __builtin_amdgcn_readfirstlane(D[25]);
+        const int cb0 = T.chunk * P.CH;
+        T.nb = min(P.CH, nblk_list - cb0);
+        T.cvecs = min(len - cb0 * BLOCK_VECS, T.nb * BLOCK_VECS);
+        T.base = P.codes + (b0 + cb0) * BLK_BYTES;
+        T.use = 0; T.evalm = 0;
+        if (P.lut8sw) {
+            T.use = (1u << T.np) - 1u;
+            T.same = false;
+        } else {
+            int want[NPMAX];
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s) {
+                want[s] = s < T.np ? (T.namb[s] <= AMB_MAX ? T.qq[s] : -1) : -2;
+                if (want[s] >= 0) T.use |= 1u << s;
+                if (want[s] == -1) T.evalm |= 1u << s;
+            }
+            // (the cells hold the running task's tables by the time this one is installed)
+            T.same = want[0] == loaded0 && want[1] == loaded1 && want[2] == loaded2 && want[3] == loaded3 && T.evalm == 0;
+        }
+    };
+    // everything of a task that comes from HBM before its stream: requested as early as possible.
+    // (every field of R is written on every path, with zeros where nothing is loaded: a field that
+    // is only written under a condition keeps its old value alive across the whole task loop, and
+    // the table registers then get spilled)
+    auto issue_tables = [&](const int32_t* D, const Task& T) {
+        const bool live = T.tid >= 0;
+        R.tau = INT32_MIN;
+        if (live && threadIdx.x < NPMAX && (int)threadIdx.x < T.np)
+            R.tau = __hip_atomic_load(P.tauq + D[12 + threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (live && !P.lut8sw) {
+            // (the arrays always hold AMB_MAX entries, so the first 64 can be read unconditionally)
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s) {
+                R.pa[s] = P.T.amb_addr[(int64_t)T.qq[s] * AMB_MAX + lane];
+                R.pv[s] = P.T.patch_val[(int64_t)T.pair[s] * AMB_MAX + lane];
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s) { R.pa[s] = 0u; R.pv[s] = 0u; }
+        }
+        if (live && !T.same) {
+            const uint8_t* tb = P.lut8sw ? P.lut8sw : P.T.lut_base;
+            const int* ix = P.lut8sw ? T.pair : T.qq;
+            load_tables<MPAD>(R, tb + (int64_t)ix[0] * LUT_BYTES, tb + (int64_t)ix[1] * LUT_BYTES, tb + (int64_t)ix[2] * LUT_BYTES,
+                              tb + (int64_t)ix[3] * LUT_BYTES);
+        } else {
+#pragma unroll
+            for (int r = 0; r < TableRegs<MPAD>::PER; ++r) { R.a[r] = 0u; R.b[r] = 0u; R.c[r] = 0u; R.d[r] = 0u; }
+        }
+    };
+
+    // Descriptors are claimed TWO tasks ahead: the one a wave needs when it finishes its share of the
+    // running task (to request the next task's tables) is then always in place, on every wave, at the
+    // same point of the program.
+    if (wave == NW - 1) {
+        fetch_task(P, ntasks, desc, lane);
+        fetch_task(P, ntasks, desc + DESC_INTS, lane);
+    }
+    __syncthreads();
+    Task T;
+    decode(desc, T);
+    if (T.tid < 0) return;            // nothing to do (every wave reads the same descriptor)
+    issue_tables(desc, T);
+    // The wave's first block.  The stream's loads are issued unconditionally and at fixed places of
+    // the program, this one included: the compiler counts outstanding loads statically, and a load
+    // that is issued on some paths only makes it wait for ALL outstanding loads before each use.
+    load_block<MPAD>(cur_w, T.base + (int64_t)min(wave, T.nb - 1) * BLK_BYTES, lane);
+    bool have_prev = false;
+    for (int cur = 0;; cur = cur == 2 ? 0 : cur + 1) {
+        const int32_t* D = desc + cur * DESC_INTS;
+        const int nxt = cur == 2 ? 0 : cur + 1, prv = cur == 0 ? 2 : cur - 1;   // ring positions of the next / previous task
+        // ---- result of the previous task: one wave per pair
+        if (have_prev) {
+            const int32_t* Dp = desc + prv * DESC_INTS;
+            if (wave < __builtin_amdgcn_readfirstlane(Dp[3])) merge_task<NW>(P, Dp, wave, cand, sh, hist + wave * 256, lane);
+        }
+        if (T.tid < 0) break;         // every wave reads the same descriptor: all leave together
+        const int np = T.np;
+
+        // ---- install: tables into LDS, patches, thresholds
+        if (!T.same) store_tables<MPAD>(R, T.use, lut);
+        if (T.evalm) {                // rare: the cells' dwords are shared, so the other tables must be in place first
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s)
+                if (T.evalm & (1u << s)) eval_table<NT>(P, T.pair[s], T.qq[s], lut + cell_byte(s));
+        }
+        if (!P.lut8sw) {
+            // Patches are written by the wave that copies the 32-byte piece they fall into, so program
+            // order inside the wave puts them after the copy and no workgroup barrier is needed in between.
+            auto owner = [](uint32_t e) { return (int)(((e >> 3) & (uint32_t)(NT - 1)) >> 6); };
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s) {
+                if (!(T.use & (1u << s))) continue;
+                if (lane < T.namb[s] && owner(R.pa[s]) == wave) lut[R.pa[s] * 4 + cell_byte(s)] = (uint8_t)R.pv[s];
+                for (int i = 64 + lane; i < T.namb[s]; i += 64) {
+                    const uint32_t e = P.T.amb_addr[(int64_t)T.qq[s] * AMB_MAX + i];
+                    if (owner(e) == wave) lut[e * 4 + cell_byte(s)] = P.T.patch_val[(int64_t)T.pair[s] * AMB_MAX + i];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NPMAX; ++s) {
+                const int w = s < np ? (T.namb[s] <= AMB_MAX ? T.qq[s] : -1) : -2;
+                if (s == 0) loaded0 = w; else if (s == 1) loaded1 = w; else if (s == 2) loaded2 = w; else loaded3 = w;
+            }
+        }
+        if (threadIdx.x < NPMAX) {
+            const int s = threadIdx.x;
             int32_t t0 = 0;
-            if (pr >= 0) {
-                const int32_t g = __hip_atomic_load(P.tauq + (threadIdx.x == 0 ? qA : qB), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const int64_t t = (int64_t)g - (threadIdx.x == 0 ? biasA : biasB);
+            if (s < np) {
+                const int64_t t = (int64_t)R.tau - D[8 + s];
                 t0 = t <= 0 ? 0 : (t > 0x7fffffff ? 0x7fffffff : (int32_t)t);
             }
-            sh[2 + threadIdx.x] = t0;
-            if (threadIdx.x == 0) { sh[4] = SCAN_WAVES; sh[5] = 0; }   // next unclaimed block of the chunk; finisher ticket
+            sh[s] = t0;
+            if (s == 0) { sh[4] = NW; sh[5] = 0; }   // next unclaimed block; finisher ticket
         }
         __syncthreads();
 
-        // ---- stream the chunk: wave w takes blocks w, w+8, ...
-        uint32_t* bufA = cand + (wave * 2 + 0) * CAPW;
-        uint32_t* bufB = cand + (wave * 2 + 1) * CAPW;
-        int cntA = 0, cntB = 0;
-        uint32_t thrA = (uint32_t)sh[2], thrB = (uint32_t)sh[3];
-        // one wave claims and decodes the next task while its first loads are in flight
-        auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
-            const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
-            const bool valid = (int)pos < cvecs;
-            uint32_t sa, sb;
-            if (pairB >= 0) {
-                block_sums<MPAD, 2>(w, off, sel0, sel1, sel2, sel3, sa, sb);
-                const uint32_t ta = (uint32_t)sh[2], tb = (uint32_t)sh[3];
-                if (ta > thrA) thrA = ta;
-                if (tb > thrB) thrB = tb;
-                offer(valid, sa, pos, bufA, cntA, thrA, sh + 2, k, lane);
-                offer(valid, sb, pos, bufB, cntB, thrB, sh + 3, k, lane);
-            } else {
-                block_sums<MPAD, 1>(w, off, sel0, sel1, sel2, sel3, sa, sb);
-                const uint32_t ta = (uint32_t)sh[2];
-                if (ta > thrA) thrA = ta;
-                offer(valid, sa, pos, bufA, cntA, thrA, sh + 2, k, lane);
-            }
-        };
-        // blocks beyond each wave's first are claimed from an LDS counter: a wave that was held up
-        // (the one that fetched the next task, one that pruned) simply takes fewer
+        // ---- stream the chunk: wave w starts with block w, further blocks are claimed from an LDS counter
+        // (a wave that was held up - the one that fetched the next task, one that pruned - simply takes fewer)
+        const uint8_t* base = T.base;
+        const int nb = T.nb, cvecs = T.cvecs;
+        int b = wave;
+        int cnt[NPMAX] = {0, 0, 0, 0};
+        uint32_t thr[NPMAX];
+#pragma unroll
+        for (int s = 0; s < NPMAX; ++s) thr[s] = (uint32_t)sh[s];
         auto claim = [&]() {
             int v = 0;
             if (lane == 0) v = atomicAdd(&sh[4], 1);
             return __builtin_amdgcn_readfirstlane(v);
         };
-        int bn = claim();
-        load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
-        while (b < nb) {                       // ping-pong between the two register sets
-            process(cur_w, b);
-            b = claim();
-            load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane);
-            if (bn >= nb) break;               // claims are monotonic: nothing newer can be valid either
-            process(nxt_w, bn);
-            bn = claim();
+        // (unconditional loads, the block number clamped into the chunk)
+        auto stream = [&](auto npv_tag) {
+            constexpr int NPV = decltype(npv_tag)::value;
+            auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
+                const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
+                const bool valid = (int)pos < cvecs;
+                uint32_t sum[NPMAX];
+                block_sums<MPAD, NPV>(w, off, sel, sum);
+#pragma unroll
+                for (int s = 0; s < NPV; ++s) {
+                    if (s < np) {
+                        const uint32_t ta = (uint32_t)sh[s];
+                        if (ta > thr[s]) thr[s] = ta;
+                        offer(valid, sum[s], pos, cand + (wave * NPMAX + s) * CAPW, cnt[s], thr[s], sh + s, k, lane);
+                    }
+                }
+            };
+            int bn = claim();
             load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
-        }
-        // The first wave to run out of blocks claims and decodes the next task while the others finish
-        // (claiming it at the start of the chunk instead costs ~5 % of the kernel: the claiming wave's
-        // scalar-load chain then delays its share of the stream).
+            while (b < nb) {                       // ping-pong between the two register sets
+                process(cur_w, b);
+                b = claim();
+                load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane);
+                if (bn >= nb) break;               // claims are monotonic: nothing newer can be valid either
+                process(nxt_w, bn);
+                bn = claim();
+                load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
+            }
+        };
+        if (np <= 2) stream(std::integral_constant<int, 2>{});
+        else if (np == 3) stream(std::integral_constant<int, 3>{});
+        else stream(std::integral_constant<int, 4>{});
+        // ---- the next task's tables, patches and bound: requested by every wave as soon as it has run out of blocks
+        const int32_t* Dn = desc + nxt * DESC_INTS;
+        Task Tn;
+        decode(Dn, Tn);
+        issue_tables(Dn, Tn);
+        // (and the wave's first block of it; after the last task: any readable block)
+        load_block<MPAD>(cur_w, Tn.tid >= 0 ? Tn.base + (int64_t)min(wave, Tn.nb - 1) * BLK_BYTES : T.base, lane);
+        // ---- the first wave to run out of blocks claims the task after the next while the others finish (its
+        // descriptor replaces the previous task's, whose merge ended before this task's stream began)
         {
             int ticket = 0;
             if (lane == 0) ticket = atomicAdd(&sh[5], 1);
-            if (__builtin_amdgcn_readfirstlane(ticket) == 0) fetch_task(P, ntasks, desc + (cur ^ 1) * DESC_INTS, lane);
-        }
-        // ---- task result: every wave trims its buffers to k, then one wave per pair merges
-        if (cntA > k) wave_prune(bufA, cntA, k, lane);
-        if (cntB > k) wave_prune(bufB, cntB, k, lane);
-        if (lane == 0) { sh[8 + wave * 2] = cntA; sh[8 + wave * 2 + 1] = cntB; }
-        __syncthreads();
-        if (wave < 2 && (wave == 0 || pairB >= 0)) {
-            const int pr = wave == 0 ? pairA : pairB;
-            const int bias = wave == 0 ? biasA : biasB;
-            uint32_t r[2 * SCAN_WAVES];
-            int total = 0;
-#pragma unroll
-            for (int w = 0; w < SCAN_WAVES; ++w) {
-                const int c = sh[8 + w * 2 + wave];
-                const uint32_t* bw = cand + (w * 2 + wave) * CAPW;
-                r[2 * w] = lane < c ? bw[lane] : 0u;
-                r[2 * w + 1] = lane + 64 < c ? bw[lane + 64] : 0u;
-                total += c;
-            }
-            uint32_t kth = 1u;
-            if (total >= k) kth = select_kth<2 * SCAN_WAVES>(r, k);
-            const int64_t slot = (int64_t)pr * P.maxchunks + chunk;
-            int32_t* oI = P.part_I + slot * k;
-            int64_t* oid = P.part_id + slot * k;
-            const int64_t* idp = P.ids + v0 + cvec0;
-            int base_o = 0;
-#pragma unroll
-            for (int i = 0; i < 2 * SCAN_WAVES; ++i) {
-                const bool keep = r[i] >= kth && r[i] != 0u;
-                const uint64_t mask = __ballot(keep);
-                if (keep) {
-                    const int o = base_o + lane_rank(mask);
-                    oI[o] = bias + (int32_t)(r[i] >> 16);
-                    oid[o] = idp[0xFFFFu - (r[i] & 0xFFFFu)];
-                }
-                base_o += __popcll(mask);
-            }
-            if (lane == 0) {
-                P.part_cnt[slot] = base_o;
-                // k entries reach the k-th key's score: a valid lower bound of the query's k-th best
-                if (total >= k) atomicMax(P.tauq + (wave == 0 ? qA : qB), bias + (int32_t)(kth >> 16));
+            if (__builtin_amdgcn_readfirstlane(ticket) == 0) {
+                if (Tn.tid >= 0) fetch_task(P, ntasks, desc + prv * DESC_INTS, lane);
+                else if (lane == 0) desc[prv * DESC_INTS] = -1;
             }
         }
+        // ---- every wave trims its buffers to k
+#pragma unroll
+        for (int s = 0; s < NPMAX; ++s) {
+            if (s < np && cnt[s] > k) wave_prune(cand + (wave * NPMAX + s) * CAPW, cnt[s], k, lane);
+            if (lane == 0) sh[8 + wave * NPMAX + s] = cnt[s];
+        }
         __syncthreads();
+        T = Tn;
+        have_prev = true;
     }
 }
 
@@ -533,13 +761,19 @@ __global__ void scan_init_kernel(int32_t* __restrict__ list_cnt2, int64_t n2, in
     if (i == 0) { counters[1] = 0; counters[2] = 0; }
 }
 
-__global__ void __launch_bounds__(256) count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int32_t* __restrict__ list_cnt,
-                                                          int32_t* __restrict__ touched, int32_t* __restrict__ ctrl) {
+// `phase` 0: only each query's best list (probe rank 0), 1: only the other ranks, 2: all pairs.  Lists
+// are scanned in the order they are registered here; running phase 0 before phase 1 puts every
+// query's best list among the first tasks, so its bound on the k-th best score is tight early and
+// fewer of its later tasks collect k candidates or more.
+__global__ void __launch_bounds__(256) count_pairs_kernel(const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int phase,
+                                                          int32_t* __restrict__ list_cnt, int32_t* __restrict__ touched,
+                                                          int32_t* __restrict__ ctrl) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
     int l = -1;
     bool first = false;
-    if (i < npairs) {
+    const bool mine = i < npairs && (phase == 2 || ((i % nprobe) == 0) == (phase == 0));
+    if (mine) {
         l = probes[i];
         first = atomicAdd(&list_cnt[l], 1) == 0;
     }
@@ -566,8 +800,8 @@ __global__ void __launch_bounds__(256) touched_values_kernel(const int32_t* __re
         const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
         list_slot[l] = (int)i;
         vp[i] = c;
-        vt[i] = ((c + 1) >> 1) * ((nblk + CH - 1) / CH);
-        streamed = (unsigned long long)((c + 1) >> 1) * nblk * (BLOCK_VECS * m);
+        vt[i] = ((c + NPMAX - 1) / NPMAX) * ((nblk + CH - 1) / CH);
+        streamed = (unsigned long long)((c + NPMAX - 1) / NPMAX) * nblk * (BLOCK_VECS * m);
         algo = (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
     }
     for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
@@ -621,7 +855,7 @@ __global__ void scatter_pairs_kernel(const int32_t* __restrict__ probes, int64_t
 
 // One record per task: binary search of the touched list, then chunk / pair group.
 __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restrict__ task_off, const int32_t* __restrict__ pair_off,
-                                                         const int32_t* __restrict__ pair_sorted, const int32_t* __restrict__ touched,
+                                                         const int32_t* __restrict__ touched,
                                                          const int32_t* __restrict__ ctrl, int64_t max_tasks, int4* __restrict__ table) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= max_tasks || t >= ctrl[1]) return;
@@ -632,11 +866,12 @@ __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restri
     }
     const int rem = (int)t - task_off[lo];
     const int npl = pair_off[lo + 1] - pair_off[lo];
-    const int ngroups = (npl + 1) >> 1;
+    const int ngroups = (npl + NPMAX - 1) / NPMAX;
     const int chunk = rem / ngroups, grp = rem - chunk * ngroups;   // groups of one chunk are consecutive tasks
-    const int pa = pair_sorted[pair_off[lo] + 2 * grp];
-    const int pb = (2 * grp + 1 < npl) ? pair_sorted[pair_off[lo] + 2 * grp + 1] : -1;
-    table[t] = make_int4(touched[lo], chunk, pa, pb);
+    // the list's pairs are spread evenly over its groups (5 pairs = 3 + 2, not 4 + 1: fewer cells per look-up)
+    const int per = npl / ngroups, extra = npl - per * ngroups;
+    const int first = grp * per + min(grp, extra);
+    table[t] = make_int4(touched[lo], chunk, pair_off[lo] + first, per + (grp < extra ? 1 : 0));
 }
 
 // ------------------------------------------------------------------ per-query merge of the task results
@@ -703,7 +938,7 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
                 const int32_t I = P.part_I[gs * k + r];
                 if (I >= tau) {
                     const int o = atomicAdd(&s_cnt, 1);
-                    if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.part_id[gs * k + r]; }
+                    if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[gs * k + r]]; }
                 }
             }
         }
@@ -749,10 +984,10 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
     static bool attr_done = false;
     if (!attr_done) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kernel<MPAD>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, SCAN_LDS));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, ScanShape<MPAD>::LDS));
         attr_done = true;
     }
-    scan_kernel<MPAD><<<grid, SCAN_THREADS, SCAN_LDS, st>>>(P);
+    scan_kernel<MPAD><<<grid, ScanShape<MPAD>::NT, ScanShape<MPAD>::LDS, st>>>(P);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
@@ -763,12 +998,13 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
-    // chunk length: aim at ~2048 tasks, between 16 and 256 blocks
+    // chunk length: aim at ~2048 tasks, between 16 and 512 blocks
     const double avgblk = (double)idx->total_blocks / nlist;
-    // (pairs of one list share a pass when several queries are in the batch: ~1.5 pairs per task)
-    const double share = nq > 1 ? 1.5 : 1.0;
+    // (pairs of one list share a pass when several queries are in the batch: ~2 pairs per task)
+    const double share = nq > 1 ? 2.0 : 1.0;
     int CH = 16;
-    while (CH < 256 && (double)npairs * avgblk / (share * CH) > 2048.0) CH <<= 1;
+    // (<= 512 blocks: the position half of a key, 0xFFFF - position, then never vanishes, so a key is never 0 = "empty")
+    while (CH < 512 && (double)npairs * avgblk / (share * CH) > 2048.0) CH <<= 1;
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
     const int maxchunks = (int)std::max<int64_t>(1, (maxblk + CH - 1) / CH);
     if ((double)npairs * maxchunks * k > 4.0e9) return fail(RAGO_UNSUPPORTED, "nq * nprobe * chunks * k too large for the workspace");
@@ -797,19 +1033,24 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     P.pair_sorted = ws.pair_sorted.as<int32_t>();
     P.task_table = ws.task_table.as<int4>();
     P.ctrl = ctrl;
-    P.tauq = ws.tauq.as<int32_t>(); P.part_I = ws.part_I.as<int32_t>(); P.part_id = ws.part_id.as<int64_t>();
+    P.tauq = ws.tauq.as<int32_t>(); P.part_I = ws.part_I.as<int32_t>(); P.part_row = ws.part_id.as<int64_t>();
     P.part_cnt = ws.part_cnt.as<int32_t>();
     P.nlist = nlist; P.nprobe = nprobe; P.k = k; P.CH = CH; P.maxchunks = maxchunks;
 
     const unsigned pg = (unsigned)((npairs + 255) / 256);
     scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl, ws.counters.as<int64_t>());
-    count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_cnt, ws.touched.as<int32_t>(), ctrl);
+    if (nq >= 64) {
+        count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, nprobe, 0, list_cnt, ws.touched.as<int32_t>(), ctrl);
+        count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, nprobe, 1, list_cnt, ws.touched.as<int32_t>(), ctrl);
+    } else {
+        count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, nprobe, 2, list_cnt, ws.touched.as<int32_t>(), ctrl);
+    }
     touched_values_kernel<<<pg, 256, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, idx->m, npairs, ctrl,
                                               list_slot, ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ws.counters.as<int64_t>());
     touched_scan_kernel<<<1, 1024, 0, st>>>(ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ctrl, ws.counters.as<int64_t>());
     scatter_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_slot, ws.pair_off.as<int32_t>(), cursor, ws.pair_sorted.as<int32_t>());
     task_table_kernel<<<(unsigned)((max_tasks + 255) / 256), 256, 0, st>>>(ws.task_off.as<int32_t>(), ws.pair_off.as<int32_t>(),
-                                                                           P.pair_sorted, ws.touched.as<int32_t>(), ctrl, max_tasks,
+                                                                           ws.touched.as<int32_t>(), ctrl, max_tasks,
                                                                            ws.task_table.as<int4>());
     RAGO_HIP(hipGetLastError());
 
@@ -819,7 +1060,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
         RAGO_HIP(hipGetDeviceProperties(&pr, idx->device));
         n_cu = pr.multiProcessorCount;
     }
-    const int grid = 2 * n_cu;
+    const int grid = n_cu;           // one workgroup per CU: the four interleaved tables fill most of its LDS
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
     switch (idx->m) {
         case 16: rc = launch_scan_kernel<16>(P, grid, st); break;
