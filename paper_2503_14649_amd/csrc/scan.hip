@@ -35,14 +35,17 @@
 //  * each task writes <= k (I, id) entries per pair; the waves that merge a finished task's
 //    buffers do so while the other waves already load the next task's tables; a final kernel per
 //    query merges the task results, sorts by (I desc, id asc) and writes ids / scores.
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
 #include <type_traits>
 
-#include "rago_internal.h"
+#include "scan_common.h"
 
 namespace rago {
 
 constexpr int NPMAX = 4;        // pairs (tables) per pass
-constexpr int CAPW = 192;       // keys per (wave, pair) buffer: k <= 128 survivors + one block of 64
 constexpr int DESC_INTS = 28;   // task descriptor in LDS (see fetch_task)
 constexpr int SH_INTS = 256;    // scalars + two descriptors
 
@@ -55,65 +58,6 @@ struct ScanShape {
     static constexpr int LUT_LDS = PLANES * 4 * LUT_PLANE;     // four interleaved tables
     static constexpr int LDS = LUT_LDS + NW * NPMAX * CAPW * 4 + SH_INTS * 4 + NPMAX * 256 * 4;   // + merge histograms
 };
-
-struct ScanParams {
-    const uint8_t* codes;
-    const int64_t* blk_off;
-    const int64_t* list_off;
-    const int64_t* ids;
-    const int32_t* probes;       // [npairs] list of each pair
-    const uint8_t* lut8sw;       // [npairs] plane-major per-pair tables (stride LUT_BYTES), or null: use `T`
-    LutTables T;                 // per-query base tables + per-pair patches
-    const int32_t* bias;         // [npairs]
-    int m;
-    const int32_t* pair_sorted;  // pairs grouped by list
-    const int4* task_table;      // [ntasks] {list, chunk, first position in pair_sorted, number of pairs}
-    int32_t* ctrl;               // [0] task counter, [1] number of tasks
-    int32_t* tauq;               // [nq] lower bound of the k-th best integer score
-    int32_t* part_I;             // [npairs][maxchunks][k]
-    int64_t* part_row;           // same shape: row of the entry in the list-major arrays
-    int32_t* part_cnt;           // [npairs][maxchunks]
-    int nlist, nprobe, k, CH, maxchunks;
-};
-
-// ------------------------------------------------------------------ small helpers
-__device__ __forceinline__ int lane_rank(uint64_t mask) {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-}
-
-// k-th largest of the non-zero keys held NR per lane by one wave (wave-uniform result).
-template <int NR>
-__device__ __forceinline__ uint32_t select_kth(const uint32_t (&r)[NR], int k) {
-    uint32_t prefix = 0;
-    int rem = k;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t test = prefix | (1u << bit);
-        const uint32_t hm = ~((1u << bit) - 1u);
-        int c1 = 0;
-#pragma unroll
-        for (int i = 0; i < NR; ++i) c1 += __popcll(__ballot((r[i] & hm) == test));
-        if (c1 >= rem) prefix = test; else rem -= c1;
-    }
-    return prefix;
-}
-
-// Keep the best k keys of buf[0..cnt) (cnt > k), compacted to buf[0..k); returns the k-th key.
-__device__ __forceinline__ uint32_t wave_prune(uint32_t* buf, int& cnt, int k, int lane) {
-    uint32_t r[CAPW / 64];
-#pragma unroll
-    for (int i = 0; i < CAPW / 64; ++i) r[i] = (lane + 64 * i < cnt) ? buf[lane + 64 * i] : 0u;
-    const uint32_t kth = select_kth<CAPW / 64>(r, k);
-    int base = 0;
-#pragma unroll
-    for (int i = 0; i < CAPW / 64; ++i) {
-        const bool keep = r[i] >= kth && r[i] != 0u;
-        const uint64_t mask = __ballot(keep);
-        if (keep) buf[base + lane_rank(mask)] = r[i];
-        base += __popcll(mask);
-    }
-    cnt = base;
-    return kth;
-}
 
 // Eight look-ups (two code dwords of one plane) in all resident tables at once.  Hand-scheduled:
 // the compiler serialises LDS reads behind full waits and spills when given the plain C++ form.
@@ -234,41 +178,6 @@ __device__ __forceinline__ void block_sums(const uint4 (&w)[MPAD / 16], const ui
     sum[1] = even >> 16;
     sum[2] = s2;
     sum[3] = s3;
-}
-
-// Append the lanes whose sum reaches the threshold to the wave's key buffer (prune when full).
-__device__ __forceinline__ void offer(bool valid, uint32_t sum, uint32_t pos, uint32_t* buf, int& cnt, uint32_t& thr,
-                                      int32_t* sh_tau, int k, int lane) {
-    const bool c = valid && sum >= thr;
-    const uint64_t mask = __ballot(c);
-    if (mask == 0) return;
-    const int add = __popcll(mask);
-    if (cnt + add > CAPW) {
-        const uint32_t kth = wave_prune(buf, cnt, k, lane);
-        const uint32_t t = kth >> 16;
-        if (t > thr) thr = t;
-        if (lane == 0) atomicMax(sh_tau, (int32_t)thr);
-    }
-    if (c) buf[cnt + lane_rank(mask)] = (sum << 16) | (0xFFFFu - pos);
-    cnt += add;
-}
-
-// The code stream and the tables are read through pointers explicitly in the global address
-// space: a generic (flat) load would also count on the LDS/scalar wait counter and every
-// hand-placed s_waitcnt lgkmcnt in the look-up code would then wait for HBM.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
-typedef const __attribute__((address_space(1))) u32x2* global_u32x2_ptr;
-
-template <int MPAD>
-__device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t* blk, int lane) {
-    global_u32x4_ptr p = (global_u32x4_ptr)(reinterpret_cast<const u32x4*>(blk) + lane);
-#pragma unroll
-    for (int i = 0; i < MPAD / 16; ++i) {
-        const u32x4 v = p[i * 64];
-        w[i] = make_uint4(v.x, v.y, v.z, v.w);
-    }
 }
 
 __device__ __forceinline__ int cell_byte(int pair_slot) { return pair_slot == 0 ? 0 : (pair_slot == 1 ? 2 : (pair_slot == 2 ? 1 : 3)); }
@@ -789,7 +698,7 @@ __global__ void __launch_bounds__(256) count_pairs_kernel(const int32_t* __restr
 // Per touched list: its pair count and task count (any number of workgroups), and where it sits.
 __global__ void __launch_bounds__(256) touched_values_kernel(const int32_t* __restrict__ touched, const int32_t* __restrict__ list_cnt,
                                                              const int64_t* __restrict__ blk_off, const int64_t* __restrict__ list_off,
-                                                             int CH, int m, int64_t max_n, const int32_t* __restrict__ ctrl,
+                                                             int CH, int group, int m, int64_t max_n, const int32_t* __restrict__ ctrl,
                                                              int32_t* __restrict__ list_slot, int32_t* __restrict__ vp,
                                                              int32_t* __restrict__ vt, int64_t* __restrict__ counters) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -800,8 +709,8 @@ __global__ void __launch_bounds__(256) touched_values_kernel(const int32_t* __re
         const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
         list_slot[l] = (int)i;
         vp[i] = c;
-        vt[i] = ((c + NPMAX - 1) / NPMAX) * ((nblk + CH - 1) / CH);
-        streamed = (unsigned long long)((c + NPMAX - 1) / NPMAX) * nblk * (BLOCK_VECS * m);
+        vt[i] = ((c + group - 1) / group) * ((nblk + CH - 1) / CH);
+        streamed = (unsigned long long)((c + group - 1) / group) * nblk * (BLOCK_VECS * m);
         algo = (unsigned long long)c * (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
     }
     for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
@@ -855,7 +764,7 @@ __global__ void scatter_pairs_kernel(const int32_t* __restrict__ probes, int64_t
 
 // One record per task: binary search of the touched list, then chunk / pair group.
 __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restrict__ task_off, const int32_t* __restrict__ pair_off,
-                                                         const int32_t* __restrict__ touched,
+                                                         const int32_t* __restrict__ touched, int group,
                                                          const int32_t* __restrict__ ctrl, int64_t max_tasks, int4* __restrict__ table) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= max_tasks || t >= ctrl[1]) return;
@@ -866,7 +775,7 @@ __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restri
     }
     const int rem = (int)t - task_off[lo];
     const int npl = pair_off[lo + 1] - pair_off[lo];
-    const int ngroups = (npl + NPMAX - 1) / NPMAX;
+    const int ngroups = (npl + group - 1) / group;
     const int chunk = rem / ngroups, grp = rem - chunk * ngroups;   // groups of one chunk are consecutive tasks
     // the list's pairs are spread evenly over its groups (5 pairs = 3 + 2, not 4 + 1: fewer cells per look-up)
     const int per = npl / ngroups, extra = npl - per * ngroups;
@@ -998,13 +907,28 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
-    // chunk length: aim at ~2048 tasks, between 16 and 512 blocks
+    // Which kernel: the wide one (four pairs per pass, one workgroup per CU) pays a fixed price per task
+    // that only long tasks amortise; short lists and small batches go to the narrow one (two pairs per
+    // pass, two workgroups per CU).  RAGO_SCAN_KERNEL=wide|narrow in the environment overrides the choice
+    // (tests run every case through both).
+    // Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key, 0xFFFF - position, then
+    // never vanishes, so a key is never 0 = "empty")
     const double avgblk = (double)idx->total_blocks / nlist;
-    // (pairs of one list share a pass when several queries are in the batch: ~2 pairs per task)
-    const double share = nq > 1 ? 2.0 : 1.0;
-    int CH = 16;
-    // (<= 512 blocks: the position half of a key, 0xFFFF - position, then never vanishes, so a key is never 0 = "empty")
-    while (CH < 512 && (double)npairs * avgblk / (share * CH) > 2048.0) CH <<= 1;
+    auto chunk_len = [&](double pairs_per_task, int cap) {
+        int c = 16;
+        while (c < cap && (double)npairs * avgblk / (pairs_per_task * c) > 2048.0) c <<= 1;
+        return c;
+    };
+    const int CH_wide = chunk_len(nq > 1 ? 2.0 : 1.0, 512);
+    // (measured on a 1e9 x 96 B index with 65536 lists: the wide kernel wins from about two pairs per list up,
+    // where a good share of the lists is probed by three queries or more)
+    bool wide = std::min((double)CH_wide, avgblk) >= 64.0 && (double)npairs >= 1.5 * nlist;
+    if (const char* force = getenv("RAGO_SCAN_KERNEL")) {
+        if (!strcmp(force, "wide")) wide = true;
+        else if (!strcmp(force, "narrow")) wide = false;
+    }
+    const int CH = wide ? CH_wide : chunk_len(nq > 1 ? 1.5 : 1.0, 256);
+    const int group = wide ? NPMAX : 2;          // pairs of one list per task
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
     const int maxchunks = (int)std::max<int64_t>(1, (maxblk + CH - 1) / CH);
     if ((double)npairs * maxchunks * k > 4.0e9) return fail(RAGO_UNSUPPORTED, "nq * nprobe * chunks * k too large for the workspace");
@@ -1045,12 +969,12 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     } else {
         count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, nprobe, 2, list_cnt, ws.touched.as<int32_t>(), ctrl);
     }
-    touched_values_kernel<<<pg, 256, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, idx->m, npairs, ctrl,
+    touched_values_kernel<<<pg, 256, 0, st>>>(ws.touched.as<int32_t>(), list_cnt, idx->blk_off, idx->list_off, CH, group, idx->m, npairs, ctrl,
                                               list_slot, ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ws.counters.as<int64_t>());
     touched_scan_kernel<<<1, 1024, 0, st>>>(ws.pair_off.as<int32_t>(), ws.task_off.as<int32_t>(), ctrl, ws.counters.as<int64_t>());
     scatter_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, list_slot, ws.pair_off.as<int32_t>(), cursor, ws.pair_sorted.as<int32_t>());
     task_table_kernel<<<(unsigned)((max_tasks + 255) / 256), 256, 0, st>>>(ws.task_off.as<int32_t>(), ws.pair_off.as<int32_t>(),
-                                                                           ws.touched.as<int32_t>(), ctrl, max_tasks,
+                                                                           ws.touched.as<int32_t>(), group, ctrl, max_tasks,
                                                                            ws.task_table.as<int4>());
     RAGO_HIP(hipGetLastError());
 
@@ -1060,15 +984,19 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
         RAGO_HIP(hipGetDeviceProperties(&pr, idx->device));
         n_cu = pr.multiProcessorCount;
     }
-    const int grid = n_cu;           // one workgroup per CU: the four interleaved tables fill most of its LDS
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
-    switch (idx->m) {
-        case 16: rc = launch_scan_kernel<16>(P, grid, st); break;
-        case 32: rc = launch_scan_kernel<32>(P, grid, st); break;
-        case 64: rc = launch_scan_kernel<64>(P, grid, st); break;
-        case 96: rc = launch_scan_kernel<96>(P, grid, st); break;
-        case 128: rc = launch_scan_kernel<128>(P, grid, st); break;
-        default: return fail(RAGO_UNSUPPORTED, "code width");
+    if (!wide) {
+        rc = launch_scan_narrow(P, n_cu, st);
+    } else {
+        const int grid = n_cu;       // one workgroup per CU: the four interleaved tables fill most of its LDS
+        switch (idx->m) {
+            case 16: rc = launch_scan_kernel<16>(P, grid, st); break;
+            case 32: rc = launch_scan_kernel<32>(P, grid, st); break;
+            case 64: rc = launch_scan_kernel<64>(P, grid, st); break;
+            case 96: rc = launch_scan_kernel<96>(P, grid, st); break;
+            case 128: rc = launch_scan_kernel<128>(P, grid, st); break;
+            default: return fail(RAGO_UNSUPPORTED, "code width");
+        }
     }
     if (rc) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[5], st));

@@ -1,4 +1,6 @@
 """GPU parity: every stage of the HIP IVF-PQ path against the CPU oracle, through the C ABI."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -47,6 +49,14 @@ def case(request, rb):
     rb.rago_index_free(h)
 
 
+@pytest.fixture(params=["wide", "narrow"])
+def scan_kernel(request):
+    """Run the test once through each of the library's two scan kernels (the library otherwise picks by task length)."""
+    os.environ["RAGO_SCAN_KERNEL"] = request.param
+    yield request.param
+    del os.environ["RAGO_SCAN_KERNEL"]
+
+
 def test_index_info(case, rb):
     ix, Q, nprobe, k, h = case
     info = rb.rago_index_info(h)
@@ -55,7 +65,7 @@ def test_index_info(case, rb):
     assert info.max_list_len == int(np.diff(ix["list_offsets"]).max())
 
 
-def test_scan_topk_bit_exact_given_tables(case, rb):
+def test_scan_topk_bit_exact_given_tables(case, rb, scan_kernel):
     ix, Q, nprobe, k, h = case
     S, probes, L, LUT8, B, delta = oracle_stages(ix, Q, nprobe)
     oi, ois, _ = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
@@ -112,7 +122,7 @@ def test_tables_equal_oracle(case, rb):
         assert cnt[5] == 0 and 0 < cnt[4] < 0.02 * len(Q) * m * 256     # base table + a few per-pair entries
 
 
-def test_search_end_to_end(case, rb):
+def test_search_end_to_end(case, rb, scan_kernel):
     ix, Q, nprobe, k, h = case
     r = oracle.ivfpq_search(Q, ix, nprobe, k)
     gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
@@ -125,7 +135,7 @@ def test_search_end_to_end(case, rb):
     assert np.array_equal(gs, r["scores"])
 
 
-def test_select_with_massive_ties(rb):
+def test_select_with_massive_ties(rb, scan_kernel):
     """Duplicate centroids and a zero query: coarse scores tie exactly across the nprobe cut; lower list wins."""
     ix = to_np(synth.random_index(n=4000, d=64, m=16, nlist=300, seed=21))
     cen = ix["centroids"].copy()
@@ -146,7 +156,7 @@ def test_select_with_massive_ties(rb):
     rb.rago_index_free(h)
 
 
-def test_padding_and_argument_errors(rb):
+def test_padding_and_argument_errors(rb, scan_kernel):
     ix = to_np(synth.random_index(n=300, d=32, m=16, nlist=8, seed=5, empty_lists=(0, 1, 2, 3, 4)))
     h = rb.rago_index_wrap(dev_index(ix))
     Q = torch.from_numpy(_queries(3, 32, 1)).cuda()
