@@ -3,13 +3,16 @@
 // modeling") and the choice of the nprobe best lists per query (the scanned subset, Section 3.3).
 //
 //  * coarse_gemm: S = Q * C^T with fp32 MFMA (v_mfma_f32_32x32x2_f32), both operands K-contiguous,
-//    LDS-staged 128x128 (or 32x128 for small batches) tiles, next tile prefetched into registers.
+//    LDS-staged 128x128 (or 32x128 for small batches) tiles, next tile prefetched into registers;
+//    from 128 queries up the product runs on the bf16 matrix cores with every operand split into
+//    two bf16 terms (three products per term pair).
 //  * select: per query, radix-select the nprobe+32 largest fp32 scores, recompute exactly those
 //    in fp64 straight from the query and the centroids, round to fp32, sort by (score descending,
 //    list ascending) and keep nprobe.  The extra candidates make the result independent of the
 //    rounding of the MFMA accumulation: a list outside the candidate set has an fp32 score below
 //    every candidate's, so its exact score is at most (smallest candidate score + E) with
-//    E = d * 2^-22 * |q| * max|c| bounding the accumulation error; when the nprobe-th exact score
+//    E = (d * 2^-22 + 2^-16) * |q| * max|c| bounding the accumulation error and that of the split
+//    product; when the nprobe-th exact score
 //    exceeds that, no outside list can belong to the result.  Queries where this cannot be shown
 //    are counted (never observed on the workloads here).
 #include "rago_internal.h"
@@ -110,12 +113,156 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
             }
 }
 
+// ---- large batches: the same product on the bf16 matrix cores, each fp32 operand split into two
+// bf16 terms x = hi + lo (hi = bf16(x), lo = bf16(x - hi), |x - hi - lo| <= 2^-18 |x|) and
+//     <q, c> ~ sum q_hi c_hi + q_hi c_lo + q_lo c_hi           (fp32 accumulation)
+// whose error, lo * lo dropped and the two roundings of lo, is at most 3 * 2^-18 * |q| |c|: an
+// order of magnitude inside the 1e-4 the scores are held to, at 16x the fp32 MFMA rate per
+// instruction.  The centroids are split once when the index is loaded, the queries on their way
+// into LDS.  v_mfma_f32_32x32x16_bf16: lane (i32, h) supplies k = 8h .. 8h+7 of row i32 of both
+// operands; 128x128 tile per workgroup, 64x64 per wave.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+constexpr int X_T = 128, X_KT = 32, X_LS = 40;   // LDS row stride in bf16 (80 B: b128 reads conflict-free)
+
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ x, int64_t n, uint16_t* __restrict__ hi,
+                                                         uint16_t* __restrict__ lo) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float v = x[i];
+        const uint32_t h = bf16_rne(v);
+        hi[i] = (uint16_t)h;
+        lo[i] = (uint16_t)bf16_rne(v - __uint_as_float(h << 16));
+    }
+}
+
+int launch_split_centroids(rago_index* idx, hipStream_t st) {
+    split_bf16_kernel<<<2048, 256, 0, st>>>(idx->centroids, (int64_t)idx->nlist * idx->d, idx->cen_hi, idx->cen_lo);
+    RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
+// Workgroup b works on centroid tile (b / 8 / nqt) * 8 + b % 8 and query tile (b / 8) % nqt: the
+// nqt workgroups that share a centroid tile are dispatched back to back onto the same XCD
+// (workgroups go round-robin over the 8 XCDs), so the tile is fetched from HBM once and then
+// served by that XCD's L2.
+__global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
+                                                                const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
+                                                                int nct, float* __restrict__ S) {
+    __shared__ __align__(16) uint16_t Ah[X_T * X_LS], Al[X_T * X_LS], Bh[X_T * X_LS], Bl[X_T * X_LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int r8 = blockIdx.x >> 3;
+    const int ct = (r8 / nqt) * 8 + (blockIdx.x & 7), qt = r8 % nqt;
+    if (ct >= nct) return;
+    const int n0 = ct * X_T, m0 = qt * X_T;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    float4 pa[4];
+    uint4 pbh[2], pbl[2];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {          // A: 128 rows x 8 float4
+            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+            const int gr = min(m0 + row, nq - 1), gk = k0 + c4 * 4;
+            pa[r] = gk < d ? *reinterpret_cast<const float4*>(Q + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {          // B: 128 rows x 4 x (8 bf16), twice
+            const int f = tid + 256 * r, row = f >> 2, c8 = f & 3;
+            const int gr = min(n0 + row, nlist - 1), gk = k0 + c8 * 8;
+            const bool in = gk < d;
+            pbh[r] = in ? *reinterpret_cast<const uint4*>(Chi + (int64_t)gr * d + gk) : make_uint4(0u, 0u, 0u, 0u);
+            pbl[r] = in ? *reinterpret_cast<const uint4*>(Clo + (int64_t)gr * d + gk) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    gload(0);
+    for (int k0 = 0; k0 < d; k0 += X_KT) {
+        __syncthreads();  // previous tile fully consumed
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+            const float v[4] = {pa[r].x, pa[r].y, pa[r].z, pa[r].w};
+            uint32_t hh[4], ll[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                hh[e] = bf16_rne(v[e]);
+                ll[e] = bf16_rne(v[e] - __uint_as_float(hh[e] << 16));
+            }
+            *reinterpret_cast<uint2*>(Ah + row * X_LS + c4 * 4) = make_uint2(hh[0] | (hh[1] << 16), hh[2] | (hh[3] << 16));
+            *reinterpret_cast<uint2*>(Al + row * X_LS + c4 * 4) = make_uint2(ll[0] | (ll[1] << 16), ll[2] | (ll[3] << 16));
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int f = tid + 256 * r, row = f >> 2, c8 = f & 3;
+            *reinterpret_cast<uint4*>(Bh + row * X_LS + c8 * 8) = pbh[r];
+            *reinterpret_cast<uint4*>(Bl + row * X_LS + c8 * 8) = pbl[r];
+        }
+        __syncthreads();
+        if (k0 + X_KT < d) gload(k0 + X_KT);
+#pragma unroll
+        for (int ks = 0; ks < X_KT / 16; ++ks) {
+            bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const int o = (wm + a * 32 + i32) * X_LS + ks * 16 + h * 8;
+                ah[a] = *reinterpret_cast<const bf16x8*>(Ah + o);
+                al[a] = *reinterpret_cast<const bf16x8*>(Al + o);
+            }
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int o = (wn + b * 32 + i32) * X_LS + ks * 16 + h * 8;
+                bh[b] = *reinterpret_cast<const bf16x8*>(Bh + o);
+                bl[b] = *reinterpret_cast<const bf16x8*>(Bl + o);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
+                }
+        }
+    }
+    // D layout of the 32x32 tile: register r, lane (i32, h) -> row 8*(r/4) + 4*h + r%4, column i32
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                const int col = n0 + wn + b * 32 + i32;
+                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = acc[a][b][r];
+            }
+}
+
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st) {
     const int nlist = idx->nlist, d = idx->d;
     if (nq > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq too large");
     const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
-    if (nq <= 32) coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
-    else coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+    if (nq <= 32) {
+        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+    } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
+        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+    } else {
+        const int nqt = (int)((nq + X_T - 1) / X_T), nct = (nlist + X_T - 1) / X_T;
+        const int64_t grid = (int64_t)((nct + 7) / 8) * 8 * nqt;
+        if (grid > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq * nlist too large");
+        coarse_gemm_split_kernel<<<(unsigned)grid, 256, 0, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, S);
+    }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
@@ -311,7 +458,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         // smallest fp32 score among the candidates = score with key `kth`
         const uint32_t u = (kth & 0x80000000u) ? (kth & 0x7fffffffu) : ~kth;
         const float s_cut = __uint_as_float(u);
-        const float E = (float)d * 2.384185791015625e-07f * sqrtf(qn) * max_cnorm;
+        const float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
         if (!(c_val[nprobe - 1] > s_cut + E)) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull);
     }
 }

@@ -64,6 +64,8 @@ struct rago_index {
     int64_t total_blocks = 0;
     float* centroids = nullptr;    // [nlist][d]
     float* cnorm = nullptr;        // [nlist] Euclidean norm of each centroid
+    uint16_t* cen_hi = nullptr;    // [nlist][d] bf16(centroid)
+    uint16_t* cen_lo = nullptr;    // [nlist][d] bf16(centroid - cen_hi): centroid = hi + lo to 2^-18 relative
     float* codebooks = nullptr;    // [m][256][dsub]
     int64_t* list_off = nullptr;   // [nlist+1] vector offsets (list-major rows)
     int64_t* blk_off = nullptr;    // [nlist+1] offsets in 64-vector blocks into codes_blk
@@ -84,6 +86,7 @@ int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st)
 
 // coarse.hip
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);
+int launch_split_centroids(rago_index* idx, hipStream_t st);
 int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes,
                   hipStream_t st);
 

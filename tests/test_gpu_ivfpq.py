@@ -91,6 +91,26 @@ def test_coarse_scores_within_1e4(case, rb):
     assert np.max(np.abs(gS - S) / scale) < 1e-4       # relative to |q||c|: inner products may be ~0
 
 
+@pytest.mark.parametrize("nq", [20, 100, 300])
+def test_coarse_and_select_by_batch_size(rb, nq):
+    """The three coarse-score kernels (32-row and 128-row fp32 tiles, split-bf16 tiles from 128 queries up) on
+    ragged tiles: nlist and nq are not multiples of 128, d is not a multiple of the 32-wide K tile."""
+    ix = to_np(synth.random_index(n=20000, d=80, m=16, nlist=1000, seed=77))
+    Q = _queries(nq, 80, 5)
+    h = rb.rago_index_wrap(dev_index(ix))
+    S = oracle.coarse(Q, ix["centroids"])
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+    scale = np.linalg.norm(Q, axis=1)[:, None] * np.linalg.norm(ix["centroids"], axis=1)[None, :]
+    err = np.max(np.abs(gS.cpu().numpy() - S) / scale)
+    print(f"[coarse] nq={nq} max error relative to |q||c|: {err:.2e}", flush=True)
+    assert err < 1e-4
+    for nprobe in (1, 50, 1000):
+        gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+        assert np.array_equal(gp, oracle.select(S, nprobe)), nprobe
+        assert rb.rago_debug_counters(h)[3] == 0
+    rb.rago_index_free(h)
+
+
 def test_select_equals_oracle(case, rb):
     ix, Q, nprobe, k, h = case
     S = oracle.coarse(Q, ix["centroids"])
