@@ -290,7 +290,8 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     __shared__ int hist32[256 * 32];
     __shared__ int hist[256];
     __shared__ uint32_t s_prefix;
-    __shared__ int s_rem, s_ngt, s_neq;
+    __shared__ int s_rem, s_rem_next, s_ngt, s_neq;
+    __shared__ int s_sfx[256];
     __shared__ int s_weq[SEL_WAVES];
     __shared__ int c_idx[SEL_CAP];
     __shared__ float c_val[SEL_CAP];
@@ -332,24 +333,38 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
             for (int r = 0; r < nrounds; ++r) count(key_at(r), r * SEL_THREADS + tid);
         }
         __syncthreads();
+        // digit = the highest bin whose count, together with all higher bins, reaches `rem`:
+        // thread t < 256 owns bin t; suffix sums inside each of the four waves, then across them
         if (tid < 256) {
             int tot = 0;
 #pragma unroll
             for (int c = 0; c < 32; ++c) tot += hist32[(tid << 5) | ((c + tid) & 31)];   // rotated: no bank conflicts
             hist[tid] = tot;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            int rem = s_rem, dgt = 255;
-            for (; dgt > 0; --dgt) {
-                if (hist[dgt] >= rem) break;
-                rem -= hist[dgt];
+            int sfx = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_down(sfx, o);
+                if (lane + o < 64) sfx += t;
             }
-            s_prefix = prefix | ((uint32_t)dgt << shift);
-            s_rem = rem;
+            if (lane == 0) s_weq[wave] = sfx;        // total of this wave's 64 bins
+            s_sfx[tid] = sfx;
         }
         __syncthreads();
+        if (tid < 256) {
+            int above = 0;                           // keys in the bins of the higher waves
+            for (int w = wave + 1; w < 4; ++w) above += s_weq[w];
+            const int rem = s_rem;
+            const int mine = s_sfx[tid] + above;     // keys in bins >= tid
+            const int next = mine - hist[tid];       // keys in bins > tid
+            if (mine >= rem && next < rem) {         // exactly one bin (counts are >= 0, the total is >= rem)
+                s_prefix = prefix | ((uint32_t)tid << shift);
+                s_rem_next = rem - next;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) s_rem = s_rem_next;
     }
+    __syncthreads();
     const uint32_t kth = s_prefix;   // exact key of the want-th largest
     const int need_eq = s_rem;       // how many of the entries equal to it are taken (lowest lists first)
     const int total_eq = hist[(kth)&255];
@@ -418,41 +433,60 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     float qn = 0.f;
     for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
     for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
-    // (four candidates per wave at a time, so four rows are in flight instead of one)
-    for (int c0 = wave * 4; c0 < want; c0 += SEL_WAVES * 4) {
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        const float* cv[4];
+    // (eight candidates per wave at a time: the rows come from HBM at random, and the time of this step is
+    // the number of such rounds times the latency of a loaded memory system)
+    constexpr int RU = 8;
+    for (int c0 = wave * RU; c0 < want; c0 += SEL_WAVES * RU) {
+        double acc[RU];
+        const float* cv[RU];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d;
+        for (int u = 0; u < RU; ++u) { acc[u] = 0.0; cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d; }
         for (int t = lane; t < d; t += 64) {
             const double qt = (double)qv[t];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
+            for (int u = 0; u < RU; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < RU; ++u) {
             for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
             if (lane == 0 && c0 + u < want) c_val[c0 + u] = (float)acc[u];
         }
     }
-    int n2 = 1;
-    while (n2 < want) n2 <<= 1;
-    for (int i = want + tid; i < n2; i += SEL_THREADS) { c_idx[i] = 0x7fffffff; c_val[i] = -INFINITY; }
-    // ---- bitonic sort by (score desc, list asc)
-    for (int size = 2; size <= n2; size <<= 1)
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int t = tid; t < n2 / 2; t += SEL_THREADS) {
-                const int i = 2 * t - (t & (stride - 1)), j = i + stride;
-                const bool up = (i & size) == 0;
-                const float va = c_val[i], vb = c_val[j];
-                const int ia = c_idx[i], ib = c_idx[j];
-                const bool b_first = vb > va || (vb == va && ib < ia);
-                const bool a_first = va > vb || (va == vb && ia < ib);
-                if (up ? b_first : a_first) { c_val[i] = vb; c_val[j] = va; c_idx[i] = ib; c_idx[j] = ia; }
-            }
-        }
     __syncthreads();
+    if (want <= SEL_THREADS) {
+        // ---- order by (score desc, list asc): every candidate counts those that come before it
+        // (all lanes read the same LDS word at a time: a broadcast) and writes its list to that rank
+        int mine_i = 0x7fffffff, rank = 0;
+        float mine_v = -INFINITY;
+        if (tid < want) { mine_i = c_idx[tid]; mine_v = c_val[tid]; }
+        for (int j = 0; j < want; ++j) {
+            const float vj = c_val[j];
+            const int ij = c_idx[j];
+            rank += (vj > mine_v || (vj == mine_v && ij < mine_i)) ? 1 : 0;
+        }
+        __syncthreads();                             // every c_idx / c_val read is done
+        if (tid < want) { c_idx[rank] = mine_i; c_val[rank] = mine_v; }   // (ranks are a permutation: lists are distinct)
+        __syncthreads();
+    } else {
+        int n2 = 1;
+        while (n2 < want) n2 <<= 1;
+        for (int i = want + tid; i < n2; i += SEL_THREADS) { c_idx[i] = 0x7fffffff; c_val[i] = -INFINITY; }
+        // ---- bitonic sort by (score desc, list asc)
+        for (int size = 2; size <= n2; size <<= 1)
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                __syncthreads();
+                for (int t = tid; t < n2 / 2; t += SEL_THREADS) {
+                    const int i = 2 * t - (t & (stride - 1)), j = i + stride;
+                    const bool up = (i & size) == 0;
+                    const float va = c_val[i], vb = c_val[j];
+                    const int ia = c_idx[i], ib = c_idx[j];
+                    const bool b_first = vb > va || (vb == va && ib < ia);
+                    const bool a_first = va > vb || (va == vb && ia < ib);
+                    if (up ? b_first : a_first) { c_val[i] = vb; c_val[j] = va; c_idx[i] = ib; c_idx[j] = ia; }
+                }
+            }
+        __syncthreads();
+    }
     for (int p = tid; p < nprobe; p += SEL_THREADS) probes[q * nprobe + p] = c_idx[p];
     if (tid == 0 && want < nlist) {
         // smallest fp32 score among the candidates = score with key `kth`

@@ -33,45 +33,61 @@
 
 namespace rago {
 
-// T64[q][j][c], Tmin/Tmax[q][j].  grid (nq, ceil(m / tj)), 256 threads = one per codeword, tj sub-quantisers per block.
-constexpr int LUT_TJ = 8;   // at most; `tj` sub-quantisers per block (1 for small batches: latency, 8 for large: fewer blocks)
-__global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int d, int m, int tj,
+// <a, b> over one sub-vector, accumulated left to right in fp64 without fused multiply-add.
+// DSUB = 0: any length (`dsub`), else the compile-time length (vector loads, unrolled).
+template <int DSUB>
+__device__ __forceinline__ double subdot(const float* __restrict__ a, const float* __restrict__ b, int dsub) {
+    double acc = 0.0;
+    if constexpr (DSUB == 8) {
+        const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(b), b1 = *reinterpret_cast<const float4*>(b + 4);
+        acc = acc + (double)a0.x * (double)b0.x; acc = acc + (double)a0.y * (double)b0.y;
+        acc = acc + (double)a0.z * (double)b0.z; acc = acc + (double)a0.w * (double)b0.w;
+        acc = acc + (double)a1.x * (double)b1.x; acc = acc + (double)a1.y * (double)b1.y;
+        acc = acc + (double)a1.z * (double)b1.z; acc = acc + (double)a1.w * (double)b1.w;
+    } else {
+        for (int t = 0; t < dsub; ++t) acc = acc + (double)a[t] * (double)b[t];
+    }
+    return acc;
+}
+
+// T64[q][j][c], Tmin/Tmax[q][j].  One wave per (query, sub-quantiser): lane handles codewords
+// lane, lane + 64, lane + 128, lane + 192; 4 waves per block.
+template <int DSUB>
+__global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int64_t nq, int d, int m,
                                                     double* __restrict__ T64, double* __restrict__ Tmin, double* __restrict__ Tmax,
                                                     uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
                                                     int64_t* __restrict__ counters) {
-    __shared__ double s_mn[LUT_TJ][4], s_mx[LUT_TJ][4];
-    const int c = threadIdx.x;
-    const int64_t q = blockIdx.x;
-    const int dsub = d / m;
-    if (blockIdx.y == 0 && c == 0) {   // running maxima of the pair kernel and the table counters start at zero
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= nq * m) return;
+    const int64_t q = w / m;
+    const int j = (int)(w - q * m);
+    const int dsub = DSUB ? DSUB : d / m;
+    if (j == 0 && lane == 0) {   // running maxima of the pair kernel and the table counters start at zero
         range_bits[q] = 0u; mag_bits[q] = 0u;
         if (q == 0) { counters[4] = 0; counters[5] = 0; }
     }
-    for (int jj = 0; jj < tj; ++jj) {
-        const int j = blockIdx.y * tj + jj;
-        if (j >= m) break;
-        const float* qv = Q + q * d + j * dsub;
-        const float* cb = CB + ((int64_t)j * KSUB + c) * dsub;
-        double acc = 0.0;
-        for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cb[t];
+    const float* qv = Q + q * d + j * dsub;
+    double mn = 0.0, mx = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        const double acc = subdot<DSUB>(qv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
         T64[(q * m + j) * KSUB + c] = acc;
-        double mn = acc, mx = acc;
-        for (int o = 32; o; o >>= 1) {
-            mn = fmin(mn, __shfl_xor(mn, o));
-            mx = fmax(mx, __shfl_xor(mx, o));
-        }
-        if ((c & 63) == 0) { s_mn[jj][c >> 6] = mn; s_mx[jj][c >> 6] = mx; }
+        mn = i ? fmin(mn, acc) : acc;
+        mx = i ? fmax(mx, acc) : acc;
     }
-    __syncthreads();
-    if (c < tj && blockIdx.y * tj + c < m) {
-        const int j = blockIdx.y * tj + c;
-        Tmin[q * m + j] = fmin(fmin(s_mn[c][0], s_mn[c][1]), fmin(s_mn[c][2], s_mn[c][3]));
-        Tmax[q * m + j] = fmax(fmax(s_mx[c][0], s_mx[c][1]), fmax(s_mx[c][2], s_mx[c][3]));
+    for (int o = 32; o; o >>= 1) {
+        mn = fmin(mn, __shfl_xor(mn, o));
+        mx = fmax(mx, __shfl_xor(mx, o));
     }
+    if (lane == 0) { Tmin[q * m + j] = mn; Tmax[q * m + j] = mx; }
 }
 
 // Per pair: t64[pair][j]; per query: running max of (hi - lo) and of |lo|,|hi| as float bits (>= 0).
 // One wave per pair (lanes = sub-quantisers), `ppw` consecutive pairs per wave, 4 waves per block.
+template <int DSUB>
 __global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                        const int32_t* __restrict__ probes, int64_t npairs, int ppw, int nprobe, int d, int m,
                                                        const double* __restrict__ Tmin, const double* __restrict__ Tmax,
@@ -79,7 +95,7 @@ __global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__
                                                        uint32_t* __restrict__ mag_bits) {
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int dsub = d / m;
+    const int dsub = DSUB ? DSUB : d / m;
     for (int pp = 0; pp < ppw; ++pp) {
         const int64_t pair = w * ppw + pp;
         if (pair >= npairs) return;
@@ -87,10 +103,7 @@ __global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__
         const int l = probes[pair];
         float rng = 0.f, mag = 0.f;
         for (int j = lane; j < m; j += 64) {
-            const float* qv = Q + q * d + j * dsub;
-            const float* cv = C + (int64_t)l * d + j * dsub;
-            double acc = 0.0;
-            for (int t = 0; t < dsub; ++t) acc = acc + (double)qv[t] * (double)cv[t];
+            const double acc = subdot<DSUB>(Q + q * d + j * dsub, C + (int64_t)l * d + j * dsub, dsub);
             t64[pair * m + j] = acc;
             const float lo = (float)(Tmin[q * m + j] + acc), hi = (float)(Tmax[q * m + j] + acc);
             rng = fmaxf(rng, hi - lo);
@@ -274,11 +287,19 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     uint16_t* amb_addr = ws.amb.as<uint16_t>();
     int32_t* namb = reinterpret_cast<int32_t*>(amb_addr + nq * AMB_MAX);
     if ((rc = ws.counters.reserve(64))) return rc;
-    const int tj = nq >= 64 ? LUT_TJ : 1, ppw = npairs >= 32768 ? 8 : 1;
-    lut_T_kernel<<<dim3((unsigned)nq, (m + tj - 1) / tj), 256, 0, st>>>(q, idx->codebooks, d, m, tj, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax,
-                                                        range_bits, mag_bits, ws.counters.as<int64_t>());
-    lut_pair_kernel<<<(unsigned)((npairs + 4 * ppw - 1) / (4 * ppw)), 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
-                                                      ws.pair_lo.as<double>(), range_bits, mag_bits);
+    const int ppw = npairs >= 32768 ? 8 : 1;
+    const unsigned tg = (unsigned)((nq * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
+    if (d / m == 8 && d % 4 == 0) {      // (16-byte loads of the sub-vectors)
+        lut_T_kernel<8><<<tg, 256, 0, st>>>(q, idx->codebooks, nq, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, range_bits, mag_bits,
+                                            ws.counters.as<int64_t>());
+        lut_pair_kernel<8><<<pgrid, 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
+                                                  ws.pair_lo.as<double>(), range_bits, mag_bits);
+    } else {
+        lut_T_kernel<0><<<tg, 256, 0, st>>>(q, idx->codebooks, nq, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, range_bits, mag_bits,
+                                            ws.counters.as<int64_t>());
+        lut_pair_kernel<0><<<pgrid, 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
+                                                  ws.pair_lo.as<double>(), range_bits, mag_bits);
+    }
     lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,
                                                   ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(), ws.counters.as<int64_t>());
     lut_patch_kernel<<<(unsigned)npairs, 128, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
