@@ -98,11 +98,15 @@ int rago_index_info(const rago_index* idx, rago_index_desc* out);
  * (query, list), an integer asymmetric-distance scan of the lists' codes, best k per query by
  * (integer score descending, id ascending).
  *   queries     DEVICE [nq][d] fp32 row-major, 16-byte aligned
- *   nq >= 0, 1 <= nprobe <= nlist, 1 <= k <= 128
+ *   nq >= 0, 1 <= nprobe <= min(nlist, 2048), nq * nprobe <= 2^30, 1 <= k <= 128
+ *   (RAGO_INVALID_ARG for nprobe > nlist or k < 1, RAGO_UNSUPPORTED beyond the other limits)
  *   out_ids     DEVICE [nq][k] int64, best first, padded with -1
  *   out_scores  DEVICE [nq][k] fp32 = integer score * the query's table step; pad = -inf
  *   out_iscores DEVICE [nq][k] int32 or NULL; pad = INT32_MIN
  * The workspace grows on demand (first call at a new size allocates; later calls do not).
+ * The scan runs one of two kernels, chosen from the batch and list sizes (long tasks with lists
+ * shared by several queries: four (query, list) pairs per pass of a list; otherwise two);
+ * RAGO_SCAN_KERNEL=wide|narrow in the environment forces one of them (results are identical).
  */
 int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k,
                       int64_t* out_ids, float* out_scores, int32_t* out_iscores, void* stream);
@@ -126,7 +130,8 @@ const char* rago_last_error(void);
 
 /* ---- stage-isolated entry points (same kernels as rago_ivfpq_search, one stage each) ---- */
 
-/* Coarse scores S[q][l] = <Q[q], C[l]> (fp32 MFMA).  out_S DEVICE [nq][nlist] fp32. */
+/* Coarse scores S[q][l] = <Q[q], C[l]> (fp32 MFMA; from 128 queries up bf16 MFMA on operands split
+ * into two bf16 terms; either way within 1e-4 |q||c| of the exact product).  out_S DEVICE [nq][nlist] fp32. */
 int rago_debug_coarse(rago_index* idx, const float* queries, int64_t nq, float* out_S, void* stream);
 
 /* The nprobe best lists per query, best first, ties by lower list number.  Scores of the lists
@@ -149,7 +154,8 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
                     void* stream);
 
 /* Counters of the last search on this index, HOST out[8] (synchronises `stream`):
- * [0] scan tasks, [1] code bytes streamed by the scan, [2] algorithmic code bytes
+ * [0] scan tasks, [1] code bytes streamed by the scan (a pass over a list serves up to four, or
+ * two, of its pairs), [2] algorithmic code bytes
  * (sum over (query, probe) of list length * m), [3] queries whose probe choice was not
  * provably independent of fp32 rounding, [4] table entries whose rounding had to be evaluated per
  * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
