@@ -50,10 +50,14 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
-def coarse(Q, C):
+METRICS = {"ip": 0, "l2": 1}
+
+
+def coarse(Q, C, metric="ip"):
     Q, C = _arr(Q, np.float32), _arr(C, np.float32)
     S = np.empty((Q.shape[0], C.shape[0]), np.float32)
-    _chk(_load().oracle_coarse(_p(Q), _p(C), I64(Q.shape[0]), I64(C.shape[0]), I64(Q.shape[1]), _p(S)), "coarse")
+    fn = _load().oracle_coarse_l2 if METRICS[metric] else _load().oracle_coarse
+    _chk(fn(_p(Q), _p(C), I64(Q.shape[0]), I64(C.shape[0]), I64(Q.shape[1]), _p(S)), "coarse")
     return S
 
 
@@ -64,13 +68,13 @@ def select(S, nprobe):
     return probes
 
 
-def lut_f32(Q, C, CB, probes):
+def lut_f32(Q, C, CB, probes, metric="ip"):
     Q, C, CB, probes = _arr(Q, np.float32), _arr(C, np.float32), _arr(CB, np.float32), _arr(probes, np.int32)
     nq, d = Q.shape
     m = CB.shape[0]
     L = np.empty((nq, probes.shape[1], m, 256), np.float32)
-    _chk(_load().oracle_lut_f32(_p(Q), _p(C), _p(CB), _p(probes), I64(nq), I64(probes.shape[1]), I64(d), I64(m),
-                                _p(L)), "lut_f32")
+    fn = _load().oracle_lut_f32_l2 if METRICS[metric] else _load().oracle_lut_f32
+    _chk(fn(_p(Q), _p(C), _p(CB), _p(probes), I64(nq), I64(probes.shape[1]), I64(d), I64(m), _p(L)), "lut_f32")
     return L
 
 
@@ -106,8 +110,9 @@ def adc_f32_topk(probes, L, list_offsets, codes, ids, k):
     return oi, osc
 
 
-def ivfpq_search(Q, index, nprobe, k):
-    """index: dict with numpy arrays centroids, codebooks, list_offsets, codes, ids."""
+def ivfpq_search(Q, index, nprobe, k, metric="ip"):
+    """index: dict with numpy arrays centroids, codebooks, list_offsets, codes, ids.
+    metric "ip" = inner product, "l2" = minus squared Euclidean distance."""
     Q = _arr(Q, np.float32)
     C, CB = _arr(index["centroids"], np.float32), _arr(index["codebooks"], np.float32)
     off, codes, ids = _arr(index["list_offsets"], np.int64), _arr(index["codes"], np.uint8), _arr(index["ids"], np.int64)
@@ -115,8 +120,8 @@ def ivfpq_search(Q, index, nprobe, k):
     oi, osc, ois = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32), np.empty((nq, k), np.int32)
     probes, delta = np.empty((nq, nprobe), np.int32), np.empty(nq, np.float32)
     _chk(_load().oracle_ivfpq_search(_p(Q), I64(nq), I64(d), _p(C), I64(C.shape[0]), _p(CB), I64(CB.shape[0]),
-                                     _p(off), _p(codes), _p(ids), I64(nprobe), I64(k), _p(oi), _p(osc), _p(ois),
-                                     _p(probes), _p(delta)), "ivfpq_search")
+                                     _p(off), _p(codes), _p(ids), I64(nprobe), I64(k), ctypes.c_int(METRICS[metric]),
+                                     _p(oi), _p(osc), _p(ois), _p(probes), _p(delta)), "ivfpq_search")
     return dict(ids=oi, scores=osc, iscores=ois, probes=probes, delta=delta)
 
 

@@ -14,13 +14,19 @@
  * algorithm with every unspecified choice (metric, residual PQ, table quantisation,
  * tie-breaks, padding) fixed as documented at each function.
  *
- * Metric: inner product, larger = better.  All pointers are host memory.  Floating point:
- * fp64 accumulation rounded once to fp32 where stated; compile with -ffp-contract=off so
- * no multiply-add is fused.
+ * Metric: inner product, larger = better (metric 0), or the Euclidean distance the paper names
+ * first among its similarity notions (Section 2), as similarity = MINUS the squared distance, so
+ * that larger = better there too and every later step is shared (metric 1).  All pointers are
+ * host memory.  Floating point: fp64 accumulation rounded once to fp32 where stated; compile
+ * with -ffp-contract=off so no multiply-add is fused.
  *
  * Pins (tests/, CPU-only): exhaustive reconstruct-and-matmul ADC at nprobe = nlist, the
  * look-up-table sum identity, an integer-exact worked case, quantisation error bound and
- * end points, brute-force sorts with forced ties, numpy matmul for coarse and flat scores.
+ * end points, brute-force sorts with forced ties, numpy matmul for coarse and flat scores;
+ * Euclidean metric: numpy distances for the coarse scores, the table sum identity against an
+ * independent reconstruction, zero entries at exact matches, its relation to the inner-product
+ * tables through the norms, exhaustive search at nprobe = nlist, agreement with the inner-product
+ * ranking on lossless codes of unit vectors.
  * Parity unpinned: absolute recall values on synthetic data (data-dependent; reported only).
  */
 #include <math.h>
@@ -54,6 +60,21 @@ int oracle_coarse(const float* Q, const float* C, int64_t nq, int64_t nlist, int
             double acc = 0.0;
             for (int64_t t = 0; t < d; ++t) acc += (double)Q[q * d + t] * (double)C[l * d + t];
             S[q * nlist + l] = (float)acc;
+        }
+    return ORACLE_OK;
+}
+
+/* ---- step 1, Euclidean metric: S[q][l] = -|Q[q] - C[l]|^2, fp64 accumulate -> fp32 ---- */
+int oracle_coarse_l2(const float* Q, const float* C, int64_t nq, int64_t nlist, int64_t d, float* S) {
+    if (!Q || !C || !S || nq < 0 || nlist <= 0 || d <= 0) return ORACLE_EINVAL;
+    for (int64_t q = 0; q < nq; ++q)
+        for (int64_t l = 0; l < nlist; ++l) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < d; ++t) {
+                const double diff = (double)Q[q * d + t] - (double)C[l * d + t];
+                acc += diff * diff;
+            }
+            S[q * nlist + l] = (float)(-acc);
         }
     return ORACLE_OK;
 }
@@ -94,6 +115,30 @@ int oracle_lut_f32(const float* Q, const float* C, const float* CB, const int32_
                         acc += (double)Q[q * d + j * dsub + t] *
                                ((double)C[l * d + j * dsub + t] + (double)CB[(j * KSUB + c) * dsub + t]);
                     L[(((q * nprobe + p) * m + j) * KSUB) + c] = (float)acc;
+                }
+        }
+    return ORACLE_OK;
+}
+
+/* ---- step 3, Euclidean metric: the squared distance to the reconstruction splits over the m
+ *      sub-spaces as well, but not into a per-query and a per-list part:
+ *      L[q,p][j][c] = - | q_j - (C[l]_j + CB[j][c]) |^2  (fp64 accumulate -> fp32). ---- */
+int oracle_lut_f32_l2(const float* Q, const float* C, const float* CB, const int32_t* probes,
+                      int64_t nq, int64_t nprobe, int64_t d, int64_t m, float* L) {
+    if (!Q || !C || !CB || !probes || !L || m <= 0 || d % m) return ORACLE_EINVAL;
+    const int64_t dsub = d / m;
+    for (int64_t q = 0; q < nq; ++q)
+        for (int64_t p = 0; p < nprobe; ++p) {
+            const int64_t l = probes[q * nprobe + p];
+            for (int64_t j = 0; j < m; ++j)
+                for (int64_t c = 0; c < KSUB; ++c) {
+                    double acc = 0.0;
+                    for (int64_t t = 0; t < dsub; ++t) {
+                        const double diff = (double)Q[q * d + j * dsub + t] -
+                                            ((double)C[l * d + j * dsub + t] + (double)CB[(j * KSUB + c) * dsub + t]);
+                        acc += diff * diff;
+                    }
+                    L[(((q * nprobe + p) * m + j) * KSUB) + c] = (float)(-acc);
                 }
         }
     return ORACLE_OK;
@@ -204,13 +249,15 @@ int oracle_adc_f32_topk(const int32_t* probes, const float* L, const int64_t* li
 }
 
 /* ---- whole search, steps 1-6 chained query by query (so the fp32 tables of only one query
- *      are alive at a time).  Optional outputs may be NULL. ---- */
+ *      are alive at a time).  metric 0 = inner product, 1 = minus squared Euclidean distance.
+ *      Optional outputs may be NULL. ---- */
 int oracle_ivfpq_search(const float* Q, int64_t nq, int64_t d, const float* C, int64_t nlist,
                         const float* CB, int64_t m, const int64_t* list_offsets, const uint8_t* codes,
-                        const int64_t* ids, int64_t nprobe, int64_t k,
+                        const int64_t* ids, int64_t nprobe, int64_t k, int metric,
                         int64_t* out_ids, float* out_scores, int32_t* out_iscores,
                         int32_t* out_probes, float* out_delta) {
     if (!Q || !C || !CB || !out_ids || nprobe <= 0 || nprobe > nlist || k <= 0 || m <= 0 || d % m) return ORACLE_EINVAL;
+    if (metric != 0 && metric != 1) return ORACLE_EINVAL;
     int rc = ORACLE_OK;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t q = 0; q < nq; ++q) {
@@ -221,9 +268,10 @@ int oracle_ivfpq_search(const float* Q, int64_t nq, int64_t d, const float* C, i
         int32_t* B = (int32_t*)malloc(sizeof(int32_t) * (size_t)nprobe);
         float dq = 1.0f;
         int r = (S && pr && L && L8 && B) ? ORACLE_OK : ORACLE_ENOMEM;
-        if (!r) r = oracle_coarse(Q + q * d, C, 1, nlist, d, S);
+        if (!r) r = metric ? oracle_coarse_l2(Q + q * d, C, 1, nlist, d, S) : oracle_coarse(Q + q * d, C, 1, nlist, d, S);
         if (!r) r = oracle_select(S, 1, nlist, nprobe, pr);
-        if (!r) r = oracle_lut_f32(Q + q * d, C, CB, pr, 1, nprobe, d, m, L);
+        if (!r) r = metric ? oracle_lut_f32_l2(Q + q * d, C, CB, pr, 1, nprobe, d, m, L)
+                           : oracle_lut_f32(Q + q * d, C, CB, pr, 1, nprobe, d, m, L);
         if (!r) r = oracle_quantise(L, 1, nprobe, m, L8, B, &dq);
         if (!r) r = oracle_scan_topk(pr, L8, B, &dq, list_offsets, codes, ids, 1, nprobe, m, k,
                                      out_ids + q * k, out_iscores ? out_iscores + q * k : NULL,

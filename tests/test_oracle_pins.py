@@ -326,3 +326,111 @@ def test_flat_equals_matmul_and_stable_argsort():
     assert oi[1, 0, :3].tolist() == [5, 300, 301]
     oi, osc = oracle.flat_search(cb[:, :3], qb, 5)                          # fewer rows than k: padded
     assert np.all(oi[:, :, 3:] == -1) and np.all(np.isneginf(osc[:, :, 3:]))
+
+
+# ------------------------------------------------------------------ Euclidean metric (similarity = minus squared distance)
+def test_l2_coarse_equals_numpy_distances(rnd):
+    ix, Q = rnd
+    S = oracle.coarse(Q, ix["centroids"], metric="l2")
+    diff = Q.astype(np.float64)[:, None, :] - ix["centroids"].astype(np.float64)[None, :, :]
+    ref = -np.sum(diff * diff, axis=2)
+    assert S.dtype == np.float32 and np.all(S <= 0)
+    assert np.max(np.abs(S - ref)) <= 2 ** -24 * np.max(np.abs(ref)) * 1.01
+    # nearest centroid by distance = the probe of rank 0
+    assert np.array_equal(oracle.select(S, 1)[:, 0], np.argmin(-ref, axis=1))
+    # a query that IS a centroid is at distance exactly 0 from it
+    S0 = oracle.coarse(ix["centroids"][:3], ix["centroids"], metric="l2")
+    assert np.all(S0[np.arange(3), np.arange(3)] == 0.0)
+
+
+def test_l2_lut_sum_identity_zero_entries_and_relation_to_ip(rnd):
+    ix, Q = rnd
+    nl = len(ix["centroids"])
+    probes = np.tile(np.arange(nl, dtype=np.int32), (Q.shape[0], 1))
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="l2")
+    assert np.all(L <= 0)
+    xhat, lst, codes = reconstruct(ix), list_of(ix), ix["codes"]
+    m = codes.shape[1]
+    dsub = Q.shape[1] // m
+    for q in range(Q.shape[0]):
+        got = sum(L[q, lst, j, codes[:, j]].astype(np.float64) for j in range(m))
+        ref = -np.sum((Q[q].astype(np.float64)[None, :] - xhat) ** 2, axis=1)      # independent: reconstruct, subtract
+        assert np.max(np.abs(got - ref)) < 1e-5
+    # relation to the inner-product tables through the norms: |a - b|^2 = |a|^2 - 2<a,b> + |b|^2
+    Lip = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="ip").astype(np.float64)
+    C, CB = ix["centroids"].astype(np.float64), ix["codebooks"].astype(np.float64)
+    for q, p, j in ((0, 1, 0), (3, 6, 2), (5, 0, m - 1)):
+        qj = Q[q, j * dsub:(j + 1) * dsub].astype(np.float64)
+        tgt = C[p, j * dsub:(j + 1) * dsub][None, :] + CB[j]                       # [256][dsub]
+        ref = -(qj @ qj - 2.0 * Lip[q, p, j] + np.sum(tgt * tgt, axis=1))
+        assert np.max(np.abs(L[q, p, j] - ref)) < 1e-5
+    # unlike the inner product, the tables of two lists do NOT differ by a constant in c
+    dlt = L[0, 0, 1].astype(np.float64) - L[0, 5, 1].astype(np.float64)
+    assert np.ptp(dlt) > 1e-3
+    # a query sub-vector that equals centroid + codeword gives an entry of exactly 0, the table's maximum
+    Qz = Q.copy()
+    Qz[2, 0:dsub] = (ix["centroids"][4, 0:dsub].astype(np.float64) + ix["codebooks"][0, 77].astype(np.float64)).astype(np.float32)
+    Lz = oracle.lut_f32(Qz[2:3], ix["centroids"], ix["codebooks"], np.array([[4]], np.int32), metric="l2")
+    exact = np.all((ix["centroids"][4, 0:dsub].astype(np.float64) + ix["codebooks"][0, 77].astype(np.float64)).astype(np.float32).astype(np.float64)
+                   == ix["centroids"][4, 0:dsub].astype(np.float64) + ix["codebooks"][0, 77].astype(np.float64))
+    if exact:
+        assert Lz[0, 0, 0, 77] == 0.0
+    assert abs(Lz[0, 0, 0, 77]) < 1e-12 and np.argmax(Lz[0, 0, 0]) == 77
+
+
+def test_l2_all_lists_probed_equals_exhaustive_and_search_chain(trained):
+    cfg, ix, Q = trained
+    S = oracle.coarse(Q, ix["centroids"], metric="l2")
+    probes = oracle.select(S, cfg.nlist)
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="l2")
+    k = 20
+    oi, osc = oracle.adc_f32_topk(probes, L, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    xhat = reconstruct(ix)
+    full = -np.sum((Q.astype(np.float64)[:, None, :] - xhat[None, :, :]) ** 2, axis=2)    # [nq][n], independent path
+    for q in range(len(Q)):
+        rid, rkey = topk_desc(full[q], ix["ids"], k)
+        assert np.max(np.abs(osc[q] - rkey)) < 5e-6
+        assert len(set(oi[q].tolist()) & set(rid.tolist())) >= k - 1
+    # the whole search = its stages chained, with the quantisation bound on every winner
+    nprobe = 6
+    r = oracle.ivfpq_search(Q, ix, nprobe, k, metric="l2")
+    pr = oracle.select(S, nprobe)
+    Lp = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], pr, metric="l2")
+    LUT8, B, delta = oracle.quantise(Lp)
+    qi, qis, qsc = oracle.scan_topk(pr, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    assert np.array_equal(r["probes"], pr) and np.array_equal(r["ids"], qi) and np.array_equal(r["iscores"], qis)
+    assert np.array_equal(r["scores"], qsc) and np.array_equal(r["delta"], delta)
+    row_of_id = np.empty(cfg.n, np.int64)
+    row_of_id[ix["ids"]] = np.arange(cfg.n)
+    for q in range(len(Q)):
+        true = full[q][row_of_id[qi[q]]]
+        assert np.all(np.abs(qsc[q].astype(np.float64) - true) <= delta[q] * (cfg.m + 1) / 2 + 1e-5)   # |delta*I - F| bound
+
+
+def test_l2_and_ip_rank_unit_vectors_alike_on_lossless_codes():
+    # dsub = 1, residual coordinates drawn from the codewords: the database IS its reconstruction.
+    # Rows are scaled to unit norm by construction of the query only: |q - x|^2 = |q|^2 + |x|^2 - 2<q,x>,
+    # so with all |x| equal the two metrics must rank the database identically.
+    g = np.random.default_rng(19)
+    d, nlist, n = 6, 4, 300
+    C = np.zeros((nlist, d), np.float32)
+    vals = np.array([-0.5, 0.5], np.float32)                                  # every coordinate is +-0.5: |x|^2 = d/4 for all x
+    CB = np.zeros((d, 256, 1), np.float32)
+    CB[:, :, 0] = vals[g.integers(0, 2, (d, 256))]
+    lst = np.sort(g.integers(0, nlist, n))
+    codes = g.integers(0, 256, (n, d)).astype(np.uint8)
+    off = np.searchsorted(lst, np.arange(nlist + 1)).astype(np.int64)
+    idx = dict(centroids=C, codebooks=CB, list_offsets=off, codes=codes, ids=np.arange(n, dtype=np.int64))
+    X = reconstruct(idx)
+    assert np.allclose(np.sum(X * X, axis=1), d / 4)
+    Ql = g.standard_normal((5, d)).astype(np.float32)
+    probes = np.tile(np.arange(nlist, dtype=np.int32), (5, 1))
+    k = n                                                                      # full ranking
+    i_ip, s_ip = oracle.adc_f32_topk(probes, oracle.lut_f32(Ql, C, CB, probes, metric="ip"), off, codes, idx["ids"], k)
+    i_l2, s_l2 = oracle.adc_f32_topk(probes, oracle.lut_f32(Ql, C, CB, probes, metric="l2"), off, codes, idx["ids"], k)
+    for q in range(5):
+        # same ranking up to exact ties (many rows coincide): compare the score sequences through the identity
+        qn = float(np.sum(Ql[q].astype(np.float64) ** 2))
+        assert np.max(np.abs(s_l2[q].astype(np.float64) - (-(qn + d / 4 - 2.0 * s_ip[q].astype(np.float64))))) < 1e-5
+        ex = np.lexsort((idx["ids"], np.sum((Ql[q].astype(np.float64)[None, :] - X) ** 2, axis=1)))[:10]
+        assert set(i_l2[q, :10].tolist()) == set(ex.tolist()) or np.isclose(s_l2[q, 9], s_l2[q, 10])
