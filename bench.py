@@ -109,12 +109,12 @@ def run_ivfpq(args):
         import oracle
         Qs = Q[:ns].cpu().numpy()
         cen = index["centroids"].cpu().numpy()
-        pr = oracle.select(oracle.coarse(Qs, cen), nprobe)
+        pr = oracle.select(oracle.coarse(Qs, cen, metric=args.metric), nprobe)
         sub = host_subindex(index, pr)
         log(f"oracle sample: {ns} queries, {sub['codes'].nbytes / 1e9:.2f} GB of codes on the host")
-        oracle.ivfpq_search(Qs[:1], sub, nprobe, k)                 # warm-up (library load, page-in)
+        oracle.ivfpq_search(Qs[:1], sub, nprobe, k, metric=args.metric)   # warm-up (library load, page-in)
         t1 = time.time()
-        sample_ref = oracle.ivfpq_search(Qs, sub, nprobe, k)
+        sample_ref = oracle.ivfpq_search(Qs, sub, nprobe, k, metric=args.metric)
         dt = time.time() - t1
         cpu = {"value": ns / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{ns} of {nq} queries on the full index (only the lists they probe copied to the host), "
@@ -123,7 +123,7 @@ def run_ivfpq(args):
         del sub
 
     torch.cuda.empty_cache()
-    h = rb.rago_index_wrap(index, 0)
+    h = rb.rago_index_wrap(index, 0, metric=args.metric)
     info = rb.rago_index_info(h)
     del index["codes"]
     torch.cuda.empty_cache()
@@ -167,14 +167,15 @@ def run_ivfpq(args):
         parity = {"queries": ns, "topk_id_overlap": ov,
                   "ids_bit_exact": bool(np.array_equal(gi, sample_ref["ids"])),
                   "iscores_bit_exact": bool(np.array_equal(gis, sample_ref["iscores"]))}
-    traffic = read_traffic(cfg.name) if args.scale == 1.0 else None
+    traffic = read_traffic(cfg.name) if args.scale == 1.0 and args.metric == "ip" else None
     rec = {
-        "metric": "ivfpq_queries_per_s_1Bx96B_shard" if cfg.name == "hyper" and args.scale == 1.0 else f"ivfpq_queries_per_s_{cfg.name}",
+        "metric": ("ivfpq_queries_per_s_1Bx96B_shard" if cfg.name == "hyper" and args.scale == 1.0 else f"ivfpq_queries_per_s_{cfg.name}")
+                  + ("" if args.metric == "ip" else "_l2"),
         "value": nq / (ms * 1e-3), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n} d={cfg.d} m={cfg.m} nlist={cfg.nlist} nq={nq} nprobe={nprobe} k={k}",
-                   "scale": args.scale},
+                   "scale": args.scale, "similarity": args.metric},
         "roofline": {"bound": "hbm", "kernel": f"scan_kernel<{cfg.m}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,
@@ -284,6 +285,8 @@ def main():
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
+                    help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one GPU's shard at real shape); --gpus must be 1", file=sys.stderr)

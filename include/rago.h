@@ -49,7 +49,7 @@ typedef struct rago_index_desc {
     int32_t ksub;     /* codewords per sub-quantiser (always 256)           */
     int32_t nlist;    /* inverted lists / coarse centroids                  */
     int64_t n;        /* database vectors                                   */
-    int32_t metric;   /* 0 = inner product                                  */
+    int32_t metric;   /* 0 = inner product, 1 = Euclidean (see rago_index_arrays) */
     int32_t device;   /* HIP device ordinal holding the index               */
     int64_t max_list_len;
     int64_t code_bytes_resident;  /* bytes of the re-laid-out code array in HBM (incl. padding) */
@@ -58,6 +58,9 @@ typedef struct rago_index_desc {
 /* Plain (un-laid-out) IVF-PQ index handed over as arrays; see rago_index_wrap. */
 typedef struct rago_index_arrays {
     int32_t d, m, nlist;
+    int32_t metric;               /* 0 = inner product (larger is better); 1 = Euclidean: similarity is MINUS the
+                                     squared distance to the reconstruction, so larger is better there too and
+                                     scores come back <= 0 (Section 2 names both notions)                        */
     int64_t n;
     const float*   centroids;     /* [nlist][d] fp32                                              */
     const float*   codebooks;     /* [m][256][d/m] fp32                                           */
@@ -68,7 +71,7 @@ typedef struct rago_index_arrays {
 
 /*
  * rago_index_load: read an index file (HOST path) and place it on GPU `device`.
- * File, little-endian: 64-byte header {char magic[8]="RAGOIVPQ", u32 version=1, u32 metric=0,
+ * File, little-endian: 64-byte header {char magic[8]="RAGOIVPQ", u32 version=1, u32 metric (0 or 1),
  * u32 d, u32 m, u32 ksub=256, u32 nlist, u64 n, zero pad}, then centroids f32[nlist][d],
  * codebooks f32[m][256][d/m], list_offsets i64[nlist+1], codes u8[n][m], ids i64[n].
  * The codes are re-laid-out once for the scan (paper Section 4: 96-byte codes, 1 byte per 8
@@ -96,7 +99,9 @@ int rago_index_info(const rago_index* idx, rago_index_desc* out);
  * rago_ivfpq_search: batched IVF-PQ search (Sections 2 and 3.3): coarse scores of every query
  * against every centroid, the nprobe best lists per query, an 8-bit look-up table per
  * (query, list), an integer asymmetric-distance scan of the lists' codes, best k per query by
- * (integer score descending, id ascending).
+ * (integer score descending, id ascending).  Under the Euclidean metric the coarse scores are
+ * -|q - c|^2 and the tables -|q_j - (c_j + codeword)|^2; they then no longer split into a
+ * per-query and a per-list part, so a full table is computed for every (query, list) pair.
  *   queries     DEVICE [nq][d] fp32 row-major, 16-byte aligned
  *   nq >= 0, 1 <= nprobe <= min(nlist, 2048), nq * nprobe <= 2^30, 1 <= k <= 128
  *   (RAGO_INVALID_ARG for nprobe > nlist or k < 1, RAGO_UNSUPPORTED beyond the other limits)

@@ -22,7 +22,7 @@ _vp, _i64, _i32, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.
 
 
 class _Arrays(ctypes.Structure):
-    _fields_ = [("d", _i32), ("m", _i32), ("nlist", _i32), ("n", _i64), ("centroids", _vp), ("codebooks", _vp),
+    _fields_ = [("d", _i32), ("m", _i32), ("nlist", _i32), ("metric", _i32), ("n", _i64), ("centroids", _vp), ("codebooks", _vp),
                 ("list_offsets", _vp), ("codes", _vp), ("ids", _vp)]
 
 
@@ -77,9 +77,13 @@ def rago_index_load(path: str, device: int = 0):
     return h
 
 
-def rago_index_wrap(index: dict, device: int = 0):
+METRICS = {"ip": 0, "l2": 1}
+
+
+def rago_index_wrap(index: dict, device: int = 0, metric="ip"):
     """index: tensors centroids [nlist][d] f32, codebooks [m][256][dsub] f32, list_offsets [nlist+1] i64,
-    codes [n][m] u8, ids [n] i64; all on the CPU or all on cuda:`device`."""
+    codes [n][m] u8, ids [n] i64; all on the CPU or all on cuda:`device`.
+    metric: "ip" (inner product) or "l2" (similarity = minus the squared Euclidean distance)."""
     c = index["centroids"].contiguous().float()
     cb = index["codebooks"].contiguous().float()
     off = index["list_offsets"].contiguous().to(torch.int64)
@@ -88,7 +92,8 @@ def rago_index_wrap(index: dict, device: int = 0):
     assert codes.dtype == torch.uint8
     on_dev = c.is_cuda
     assert all(t.is_cuda == on_dev for t in (cb, off, codes, ids)), "all arrays must live on the same side"
-    a = _Arrays(c.shape[1], cb.shape[0], c.shape[0], codes.shape[0], _ptr(c), _ptr(cb), _ptr(off), _ptr(codes), _ptr(ids))
+    a = _Arrays(c.shape[1], cb.shape[0], c.shape[0], METRICS[metric] if isinstance(metric, str) else int(metric), codes.shape[0],
+                _ptr(c), _ptr(cb), _ptr(off), _ptr(codes), _ptr(ids))
     h = _vp()
     if on_dev:
         torch.cuda.synchronize(device)
@@ -208,8 +213,8 @@ class Index:
         return cls(rago_index_load(path, device), device)
 
     @classmethod
-    def wrap(cls, index: dict, device=0):
-        return cls(rago_index_wrap(index, device), device)
+    def wrap(cls, index: dict, device=0, metric="ip"):
+        return cls(rago_index_wrap(index, device, metric), device)
 
     def info(self):
         return rago_index_info(self.h)

@@ -29,7 +29,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2};
     for (DevBuf* b : all) b->release();
 }
 
@@ -47,7 +47,7 @@ struct DeviceGuard {
 
 static void destroy(rago_index* idx) {
     if (!idx) return;
-    hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->list_off);
+    hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cn2); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->list_off);
     hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
     idx->ws.release();
     if (idx->prof.created)
@@ -56,7 +56,9 @@ static void destroy(rago_index* idx) {
 }
 
 // Shape checks + small arrays; leaves codes_blk / ids allocated but unfilled.
-static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const int64_t* h_list_off) {
+static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const int64_t* h_list_off, int metric) {
+    if (metric != 0 && metric != 1) return fail(RAGO_UNSUPPORTED, "metric must be 0 (inner product) or 1 (Euclidean)");
+    idx->metric = metric;
     if (d <= 0 || m <= 0 || nlist <= 0 || n < 0) return fail(RAGO_INVALID_ARG, "non-positive index dimension");
     if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
     if (!supported_m(m)) return fail(RAGO_UNSUPPORTED, "m must be one of 16, 32, 64, 96, 128");
@@ -77,6 +79,7 @@ static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const in
     const size_t code_bytes = (size_t)idx->total_blocks * BLOCK_VECS * m;
     if (hipMalloc(&idx->centroids, sizeof(float) * (size_t)nlist * d) != hipSuccess ||
         hipMalloc(&idx->cnorm, sizeof(float) * (size_t)nlist) != hipSuccess ||
+        hipMalloc(&idx->cn2, sizeof(float) * (size_t)nlist) != hipSuccess ||
         hipMalloc(&idx->cen_hi, sizeof(uint16_t) * (size_t)nlist * d) != hipSuccess ||
         hipMalloc(&idx->cen_lo, sizeof(uint16_t) * (size_t)nlist * d) != hipSuccess ||
         hipMalloc(&idx->codebooks, sizeof(float) * (size_t)m * KSUB * idx->dsub) != hipSuccess ||
@@ -125,7 +128,7 @@ int rago_index_wrap(const rago_index_arrays* a, int on_device, int device, rago_
     else std::memcpy(off.data(), a->list_offsets, sizeof(int64_t) * off.size());
     rago_index* idx = new rago_index();
     idx->device = device;
-    int rc = prepare(idx, a->d, a->m, a->nlist, a->n, off.data());
+    int rc = prepare(idx, a->d, a->m, a->nlist, a->n, off.data(), a->metric);
     uint8_t* plain = nullptr;
     if (!rc) {
         hipError_t e = hipMemcpy(idx->centroids, a->centroids, sizeof(float) * (size_t)a->nlist * a->d, kind);
@@ -163,7 +166,7 @@ int rago_index_load(const char* path, int device, rago_index** out) {
     std::memcpy(&n64, hdr + 32, 8);
     const uint32_t version = u[0], metric = u[1], d = u[2], m = u[3], ksub = u[4], nlist = u[5];
     if (version != 1) return fail(RAGO_FORMAT, "unknown index version");
-    if (metric != 0) return fail(RAGO_UNSUPPORTED, "only the inner-product metric is built");
+    if (metric > 1) return fail(RAGO_UNSUPPORTED, "metric must be 0 (inner product) or 1 (Euclidean)");
     if (ksub != KSUB) return fail(RAGO_UNSUPPORTED, "ksub must be 256");
     if (!d || !m || !nlist || d > (1u << 20) || nlist > (1u << 28) || n64 > (1ull << 40)) return fail(RAGO_FORMAT, "implausible header");
     if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
@@ -181,7 +184,7 @@ int rago_index_load(const char* path, int device, rago_index** out) {
     if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
     rago_index* idx = new rago_index();
     idx->device = device;
-    int rc = prepare(idx, (int)d, (int)m, (int)nlist, (int64_t)n64, off.data());
+    int rc = prepare(idx, (int)d, (int)m, (int)nlist, (int64_t)n64, off.data(), (int)metric);
     uint8_t* plain = nullptr;
     void* stage = nullptr;
     const size_t CH = (size_t)64 << 20;
@@ -221,7 +224,7 @@ int rago_index_free(rago_index* idx) {
 int rago_index_info(const rago_index* idx, rago_index_desc* out) {
     if (!idx || !out) return fail(RAGO_INVALID_ARG, "null argument");
     out->d = idx->d; out->m = idx->m; out->ksub = KSUB; out->nlist = idx->nlist; out->n = idx->n;
-    out->metric = 0; out->device = idx->device; out->max_list_len = idx->max_list_len;
+    out->metric = idx->metric; out->device = idx->device; out->max_list_len = idx->max_list_len;
     out->code_bytes_resident = idx->total_blocks * BLOCK_VECS * idx->m;
     return RAGO_OK;
 }
@@ -264,11 +267,20 @@ int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* p
     DeviceGuard g(idx->device);
     const int64_t npairs = nq * nprobe;
     hipStream_t st = (hipStream_t)stream;
-    LutTables T;
-    rc = launch_build_lut(idx, queries, probes, nq, nprobe, &T, out_L, out_LUT8, st);
-    if (rc) return rc;
-    if (out_B) RAGO_HIP(hipMemcpyAsync(out_B, T.bias, (size_t)npairs * 4, hipMemcpyDeviceToDevice, st));
-    if (out_delta) RAGO_HIP(hipMemcpyAsync(out_delta, T.delta, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
+    const int32_t* bias;
+    const float* delta;
+    if (idx->metric == 1) {
+        if ((rc = launch_build_lut_l2(idx, queries, probes, nq, nprobe, out_L, out_LUT8, st))) return rc;
+        bias = idx->ws.bias.as<int32_t>();
+        delta = idx->ws.delta.as<float>();
+    } else {
+        LutTables T;
+        if ((rc = launch_build_lut(idx, queries, probes, nq, nprobe, &T, out_L, out_LUT8, st))) return rc;
+        bias = T.bias;
+        delta = T.delta;
+    }
+    if (out_B) RAGO_HIP(hipMemcpyAsync(out_B, bias, (size_t)npairs * 4, hipMemcpyDeviceToDevice, st));
+    if (out_delta) RAGO_HIP(hipMemcpyAsync(out_delta, delta, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
     return RAGO_OK;
 }
 
@@ -307,11 +319,19 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
     if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[2], st));
-    LutTables T;
-    if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st))) return rc;
-    if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
-    rc = launch_scan(idx, ws.probes.as<int32_t>(), nullptr, T.bias, &T, T.delta, nq, nprobe, k, out_ids, out_scores,
-                     out_iscores, st, ev);
+    if (idx->metric == 1) {
+        // Euclidean metric: one full table per pair, handed to the scan like caller-supplied tables
+        if ((rc = launch_build_lut_l2(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, nullptr, nullptr, st))) return rc;
+        if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
+        rc = launch_scan(idx, ws.probes.as<int32_t>(), ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), nullptr,
+                         ws.delta.as<float>(), nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev);
+    } else {
+        LutTables T;
+        if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st))) return rc;
+        if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
+        rc = launch_scan(idx, ws.probes.as<int32_t>(), nullptr, T.bias, &T, T.delta, nq, nprobe, k, out_ids, out_scores,
+                         out_iscores, st, ev);
+    }
     if (!rc && ev) ++idx->prof.ncalls;
     return rc;
 }

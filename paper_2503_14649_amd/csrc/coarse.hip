@@ -23,9 +23,15 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int G_TN = 128, G_KT = 32, G_LS = 36;  // LDS row stride in floats (144 B: b128 reads conflict-free)
 
+// qn2 / cn2 null: S = <q, c>.  Else (Euclidean metric) S = 2 <q, c> - |c|^2 - |q|^2 = -|q - c|^2.
+__device__ __forceinline__ float coarse_score(float ip, int row, int col, const float* __restrict__ qn2, const float* __restrict__ cn2) {
+    return qn2 ? 2.0f * ip - cn2[col] - qn2[row] : ip;
+}
+
 template <int TM>
 __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restrict__ Q, const float* __restrict__ C, int nq,
-                                                          int nlist, int d, float* __restrict__ S) {
+                                                          int nlist, int d, const float* __restrict__ qn2,
+                                                          const float* __restrict__ cn2, float* __restrict__ S) {
     constexpr int MT = TM == 128 ? 2 : 1;  // 32x32 MFMA tiles per wave along M
     constexpr int NT = TM == 128 ? 2 : 1;  //                         and along N
     constexpr int AF = TM * 8 / 256;       // float4 loads per thread for the A tile
@@ -109,7 +115,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 const int col = n0 + wn + b * 32 + i32;
-                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = acc[a][b][r];
+                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = coarse_score(acc[a][b][r], row, col, qn2, cn2);
             }
 }
 
@@ -151,7 +157,8 @@ int launch_split_centroids(rago_index* idx, hipStream_t st) {
 // served by that XCD's L2.
 __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
                                                                 const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
-                                                                int nct, float* __restrict__ S) {
+                                                                int nct, const float* __restrict__ qn2,
+                                                                const float* __restrict__ cn2, float* __restrict__ S) {
     __shared__ __align__(16) uint16_t Ah[X_T * X_LS], Al[X_T * X_LS], Bh[X_T * X_LS], Bl[X_T * X_LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
@@ -245,23 +252,41 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 const int col = n0 + wn + b * 32 + i32;
-                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = acc[a][b][r];
+                if (row < nq && col < nlist) S[(int64_t)row * nlist + col] = coarse_score(acc[a][b][r], row, col, qn2, cn2);
             }
+}
+
+// |q|^2 per query (fp64 accumulation, one rounding): one wave per query
+__global__ void __launch_bounds__(256) qnorm2_kernel(const float* __restrict__ Q, int64_t nq, int d, float* __restrict__ out) {
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nq) return;
+    double acc = 0.0;
+    for (int t = threadIdx.x & 63; t < d; t += 64) acc = acc + (double)Q[q * d + t] * (double)Q[q * d + t];
+    for (int o = 32; o; o >>= 1) acc = acc + __shfl_xor(acc, o);
+    if ((threadIdx.x & 63) == 0) out[q] = (float)acc;
 }
 
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st) {
     const int nlist = idx->nlist, d = idx->d;
     if (nq > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq too large");
+    const float *qn2 = nullptr, *cn2 = nullptr;
+    if (idx->metric == 1) {
+        int rc = idx->ws.qn2.reserve((size_t)nq * 4);
+        if (rc) return rc;
+        qnorm2_kernel<<<(unsigned)((nq + 3) / 4), 256, 0, st>>>(q, nq, d, idx->ws.qn2.as<float>());
+        qn2 = idx->ws.qn2.as<float>();
+        cn2 = idx->cn2;
+    }
     const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
     if (nq <= 32) {
-        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S);
     } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
-        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, S);
+        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S);
     } else {
         const int nqt = (int)((nq + X_T - 1) / X_T), nct = (nlist + X_T - 1) / X_T;
         const int64_t grid = (int64_t)((nct + 7) / 8) * 8 * nqt;
         if (grid > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq * nlist too large");
-        coarse_gemm_split_kernel<<<(unsigned)grid, 256, 0, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, S);
+        coarse_gemm_split_kernel<<<(unsigned)grid, 256, 0, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S);
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
@@ -283,7 +308,7 @@ __device__ __forceinline__ uint32_t float_key(float f) {  // ascending uint orde
 template <int REG>
 __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                              const float* __restrict__ S, int nlist, int d, int nprobe,
-                                                             float max_cnorm, int32_t* __restrict__ probes,
+                                                             float max_cnorm, int metric, int32_t* __restrict__ probes,
                                                              int64_t* __restrict__ counters) {
     // 32 copies of every bin, copy = lane % 32: the lanes of a half-wave never share an LDS word,
     // so the atomics run at full rate even when all scores fall into one bin (pass 0: same exponent)
@@ -441,15 +466,26 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         const float* cv[RU];
 #pragma unroll
         for (int u = 0; u < RU; ++u) { acc[u] = 0.0; cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d; }
-        for (int t = lane; t < d; t += 64) {
-            const double qt = (double)qv[t];
+        if (metric == 1) {
+            for (int t = lane; t < d; t += 64) {
+                const double qt = (double)qv[t];
 #pragma unroll
-            for (int u = 0; u < RU; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
+                for (int u = 0; u < RU; ++u) {
+                    const double diff = qt - (double)cv[u][t];
+                    acc[u] = acc[u] + diff * diff;
+                }
+            }
+        } else {
+            for (int t = lane; t < d; t += 64) {
+                const double qt = (double)qv[t];
+#pragma unroll
+                for (int u = 0; u < RU; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
+            }
         }
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
             for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
-            if (lane == 0 && c0 + u < want) c_val[c0 + u] = (float)acc[u];
+            if (lane == 0 && c0 + u < want) c_val[c0 + u] = metric == 1 ? (float)(-acc[u]) : (float)acc[u];
         }
     }
     __syncthreads();
@@ -492,7 +528,9 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         // smallest fp32 score among the candidates = score with key `kth`
         const uint32_t u = (kth & 0x80000000u) ? (kth & 0x7fffffffu) : ~kth;
         const float s_cut = __uint_as_float(u);
-        const float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
+        // (Euclidean: twice the product's error, plus the roundings of the two squared norms and of the sum)
+        float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
+        if (metric == 1) E = 2.0f * E + 4.76837158203125e-07f * (qn + max_cnorm * max_cnorm);
         if (!(c_val[nprobe - 1] > s_cut + E)) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull);
     }
 }
@@ -509,13 +547,13 @@ int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, i
     int64_t* cnt = idx->ws.counters.as<int64_t>();
     const int nl = idx->nlist;
     if (nl <= 8 * SEL_THREADS)
-        select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+        select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
     else if (nl <= 32 * SEL_THREADS)
-        select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+        select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
     else if (nl <= 64 * SEL_THREADS)
-        select_kernel<64><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+        select_kernel<64><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
     else
-        select_kernel<0><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, probes, cnt);
+        select_kernel<0><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }

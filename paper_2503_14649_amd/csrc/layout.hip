@@ -66,13 +66,22 @@ __global__ void __launch_bounds__(256) check_ids_kernel(const int64_t* __restric
         if (ids[i] <= ids[i - 1]) *flag = 1;
 }
 
-__global__ void __launch_bounds__(256) cnorm_kernel(const float* __restrict__ C, int nlist, int d, float* __restrict__ out) {
+__global__ void __launch_bounds__(256) cnorm_kernel(const float* __restrict__ C, int nlist, int d, float* __restrict__ out,
+                                                    float* __restrict__ out2) {
     const int l = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
     if (l >= nlist) return;
     float acc = 0.f;
-    for (int t = threadIdx.x & 63; t < d; t += 64) acc += C[(int64_t)l * d + t] * C[(int64_t)l * d + t];
-    for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o);
-    if ((threadIdx.x & 63) == 0) out[l] = sqrtf(acc) * 1.0001f;  // slight over-estimate: used as a bound
+    double acc2 = 0.0;
+    for (int t = threadIdx.x & 63; t < d; t += 64) {
+        const float v = C[(int64_t)l * d + t];
+        acc += v * v;
+        acc2 = acc2 + (double)v * (double)v;
+    }
+    for (int o = 32; o; o >>= 1) { acc += __shfl_xor(acc, o); acc2 = acc2 + __shfl_xor(acc2, o); }
+    if ((threadIdx.x & 63) == 0) {
+        out[l] = sqrtf(acc) * 1.0001f;  // slight over-estimate: used as a bound
+        out2[l] = (float)acc2;          // |c|^2 for the Euclidean coarse scores
+    }
 }
 
 // Plain device-to-device copy of known size: the yardstick that hardware byte counters are
@@ -98,7 +107,7 @@ int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st) 
     RAGO_HIP(hipMalloc(&flag, sizeof(int)));
     RAGO_HIP(hipMemsetAsync(flag, 0, sizeof(int), st));
     check_ids_kernel<<<idx->nlist, 256, 0, st>>>(idx->ids, idx->list_off, flag);
-    cnorm_kernel<<<(idx->nlist + 3) / 4, 256, 0, st>>>(idx->centroids, idx->nlist, idx->d, idx->cnorm);
+    cnorm_kernel<<<(idx->nlist + 3) / 4, 256, 0, st>>>(idx->centroids, idx->nlist, idx->d, idx->cnorm, idx->cn2);
     int h = 0;
     hipError_t e = hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);

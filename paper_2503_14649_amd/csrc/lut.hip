@@ -28,6 +28,8 @@
 // byte each = entry c of sub-quantiser plane*32 + slot; for m < 32 the m sub-tables are
 // replicated 32/m times over the 32 slots.  A table occupies planes * 8192 bytes of its
 // LUT_BYTES stride.
+#include <algorithm>
+
 #include "lut_common.h"
 #include "rago_internal.h"
 
@@ -256,6 +258,110 @@ __global__ void __launch_bounds__(256) lut_swizzle_kernel(const uint8_t* __restr
     }
 }
 
+// ------------------------------------------------------------------ Euclidean metric
+// L[q,p][j][c] = -|q_j - (C[l]_j + CB[j][c])|^2 does not split into a per-query and a per-list part,
+// so every (query, list) pair gets a full table, in two passes because the step is per query:
+// pass 1 finds each sub-table's minimum and the query's largest range, pass 2 evaluates the entries
+// again, quantises them and writes the pair's plane-major table (staged in LDS so that the store to
+// HBM is contiguous), bias and, for inspection, plain copies.  One workgroup per pair, one wave per
+// sub-quantiser at a time, lane = codewords lane, lane + 64, lane + 128, lane + 192.
+template <int DSUB>
+__device__ __forceinline__ float l2_entry(const float* __restrict__ qv, const float* __restrict__ cv, const float* __restrict__ cb,
+                                          int dsub) {
+    double acc = 0.0;
+    if constexpr (DSUB == 8) {
+        const float4 q0 = *reinterpret_cast<const float4*>(qv), q1 = *reinterpret_cast<const float4*>(qv + 4);
+        const float4 c0 = *reinterpret_cast<const float4*>(cv), c1 = *reinterpret_cast<const float4*>(cv + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(cb), b1 = *reinterpret_cast<const float4*>(cb + 4);
+        const float qa[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        const float ca[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float ba[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const double diff = (double)qa[t] - ((double)ca[t] + (double)ba[t]);
+            acc = acc + diff * diff;
+        }
+    } else {
+        for (int t = 0; t < dsub; ++t) {
+            const double diff = (double)qv[t] - ((double)cv[t] + (double)cb[t]);
+            acc = acc + diff * diff;
+        }
+    }
+    return (float)(-acc);
+}
+
+template <int DSUB>
+__global__ void __launch_bounds__(256) lut_l2_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                           const float* __restrict__ CB, const int32_t* __restrict__ probes,
+                                                           int nprobe, int d, int m, float* __restrict__ lo_out,
+                                                           uint32_t* __restrict__ range_bits) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t pair = blockIdx.x;
+    const int64_t q = pair / nprobe;
+    const int l = probes[pair];
+    const int dsub = DSUB ? DSUB : d / m;
+    float rng = 0.f;
+    for (int j = wave; j < m; j += 4) {
+        const float* qv = Q + q * d + j * dsub;
+        const float* cv = C + (int64_t)l * d + j * dsub;
+        float mn = 0.f, mx = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            const float v = l2_entry<DSUB>(qv, cv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
+            mn = i ? fminf(mn, v) : v;
+            mx = i ? fmaxf(mx, v) : v;
+        }
+        for (int o = 32; o; o >>= 1) { mn = fminf(mn, __shfl_xor(mn, o)); mx = fmaxf(mx, __shfl_xor(mx, o)); }
+        if (lane == 0) lo_out[pair * m + j] = mn;
+        rng = fmaxf(rng, mx - mn);
+    }
+    if (lane == 0 && rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
+}
+
+template <int DSUB>
+__global__ void __launch_bounds__(256) lut_l2_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                           const float* __restrict__ CB, const int32_t* __restrict__ probes,
+                                                           int nprobe, int d, int m, const float* __restrict__ lo_in,
+                                                           const uint32_t* __restrict__ range_bits, uint8_t* __restrict__ tables,
+                                                           int32_t* __restrict__ bias, float* __restrict__ delta,
+                                                           float* __restrict__ out_L, uint8_t* __restrict__ out_LUT8) {
+    __shared__ __align__(16) uint8_t tab[LUT_BYTES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t pair = blockIdx.x;
+    const int64_t q = pair / nprobe;
+    const int l = probes[pair];
+    const int dsub = DSUB ? DSUB : d / m;
+    const int S = rago_steps(m), planes = rago_planes(m);
+    const float dq = lut_step(__uint_as_float(range_bits[q]));
+    for (int j = wave; j < m; j += 4) {
+        const float* qv = Q + q * d + j * dsub;
+        const float* cv = C + (int64_t)l * d + j * dsub;
+        const float lo = lo_in[pair * m + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            const float L = l2_entry<DSUB>(qv, cv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
+            float r = rintf(__fdiv_rn(L - lo, dq));
+            r = r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r);
+            const uint8_t v = (uint8_t)r;
+            for (int rep = j & (S - 1); rep < 32; rep += S) tab[(j >> 5) * LUT_PLANE + c * 32 + rep] = v;
+            if (out_L) out_L[(pair * m + j) * KSUB + c] = L;
+            if (out_LUT8) out_LUT8[(pair * m + j) * KSUB + c] = v;
+        }
+    }
+    __syncthreads();
+    uint4* dst = reinterpret_cast<uint4*>(tables + pair * LUT_BYTES);
+    const uint4* src = reinterpret_cast<const uint4*>(tab);
+    for (int i = threadIdx.x; i < planes * LUT_PLANE / 16; i += 256) dst[i] = src[i];
+    if (threadIdx.x == 0) {
+        double losum = 0.0;
+        for (int j = 0; j < m; ++j) losum = losum + (double)lo_in[pair * m + j];
+        bias[pair] = (int32_t)rint(losum / (double)dq);
+        if (pair % nprobe == 0) delta[q] = dq;
+    }
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -319,6 +425,37 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     out->range_bits = range_bits;
     out->bias = ws.bias.as<int32_t>();
     out->delta = ws.delta.as<float>();
+    return RAGO_OK;
+}
+
+int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, float* out_L_f32,
+                        uint8_t* out_LUT8, hipStream_t st) {
+    Workspace& ws = idx->ws;
+    const int m = idx->m, d = idx->d;
+    const int64_t npairs = nq * nprobe;
+    int rc;
+    if ((rc = ws.tmp_lut8sw.reserve((size_t)npairs * LUT_BYTES))) return rc;
+    if ((rc = ws.pair_lo.reserve((size_t)npairs * m * 8))) return rc;         // per-(pair, sub-quantiser) minima (fp32)
+    if ((rc = ws.Tmax.reserve((size_t)nq * m * 8 + (size_t)nq * 8))) return rc;   // the range words live behind the fp64 maxima
+    if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ws.counters.reserve(64))) return rc;
+    uint32_t* range_bits = reinterpret_cast<uint32_t*>(ws.Tmax.as<double>() + nq * m);
+    float* lo = ws.pair_lo.as<float>();
+    fill_u32_kernel<<<(unsigned)std::min<int64_t>(1024, (nq + 255) / 256), 256, 0, st>>>(range_bits, 0u, nq);
+    fill_u32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<uint32_t*>(ws.counters.as<int64_t>() + 4), 0u, 4);   // counters [4], [5]
+    if (d / m == 8 && d % 4 == 0) {
+        lut_l2_range_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
+        lut_l2_quant_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
+                                                                ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                                                                out_L_f32, out_LUT8);
+    } else {
+        lut_l2_range_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
+        lut_l2_quant_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
+                                                                ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                                                                out_L_f32, out_LUT8);
+    }
+    RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
 

@@ -36,7 +36,7 @@ struct DevBuf {
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2;
     void release();
 };
 
@@ -59,11 +59,13 @@ struct Profiler {
 struct rago_index {
     int device = 0;
     int d = 0, m = 0, dsub = 0, nlist = 0;
+    int metric = 0;                // 0 inner product, 1 Euclidean (similarity = minus squared distance)
     int64_t n = 0;
     int64_t max_list_len = 0;
     int64_t total_blocks = 0;
     float* centroids = nullptr;    // [nlist][d]
     float* cnorm = nullptr;        // [nlist] Euclidean norm of each centroid
+    float* cn2 = nullptr;          // [nlist] squared norm (fp64 accumulation, one rounding)
     uint16_t* cen_hi = nullptr;    // [nlist][d] bf16(centroid)
     uint16_t* cen_lo = nullptr;    // [nlist][d] bf16(centroid - cen_hi): centroid = hi + lo to 2^-18 relative
     float* codebooks = nullptr;    // [m][256][dsub]
@@ -94,6 +96,10 @@ int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, i
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,
                      LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st);
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
+// Euclidean metric: one full table per pair (plane-major, stride LUT_BYTES) into ws.tmp_lut8sw, biases into
+// ws.bias, steps into ws.delta; optional plain copies for inspection.
+int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, float* out_L_f32,
+                        uint8_t* out_LUT8, hipStream_t st);
 
 // scan.hip
 // Tables come either per pair (`lut8sw` [npairs][plane][256][32] + `bias`, `tables` null) or as per-query

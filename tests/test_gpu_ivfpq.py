@@ -227,3 +227,72 @@ def test_index_file_round_trip(rb, tmp_path):
     with pytest.raises(rb.RagoError) as e:
         rb.rago_index_load(path)
     assert e.value.code == -3
+
+
+# ------------------------------------------------------------------ Euclidean metric
+L2_CASES = {
+    # name: (n, d, m, nlist, nq, nprobe, k, kwargs)
+    "l2_m96": (30000, 768, 96, 12, 6, 5, 100, dict(shuffle_ids=True)),
+    "l2_m16_ties_empty": (3000, 32, 16, 8, 7, 4, 25, dict(empty_lists=(3,), dup_codes=60, shuffle_ids=True)),
+    "l2_m64": (9000, 128, 64, 16, 9, 3, 128, dict(dup_codes=10)),
+    "l2_m128_dsub5": (6000, 640, 128, 10, 4, 7, 10, dict()),
+}
+
+
+@pytest.fixture(scope="module", params=list(L2_CASES))
+def l2case(request, rb):
+    n, d, m, nlist, nq, nprobe, k, kw = L2_CASES[request.param]
+    print(f"[case] {request.param} n={n} d={d} m={m} nlist={nlist} nq={nq} nprobe={nprobe} k={k}", flush=True)
+    ix = to_np(synth.random_index(n=n, d=d, m=m, nlist=nlist, seed=300 + m, **kw))
+    Q = _queries(nq, d, 17 + m)
+    h = rb.rago_index_wrap(dev_index(ix), metric="l2")
+    yield ix, Q, nprobe, k, h
+    rb.rago_index_free(h)
+
+
+def test_l2_stages_equal_oracle(l2case, rb):
+    ix, Q, nprobe, k, h = l2case
+    assert rb.rago_index_info(h).metric == 1
+    S = oracle.coarse(Q, ix["centroids"], metric="l2")
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+    # natural magnitude of -|q - c|^2 computed as 2<q,c> - |c|^2 - |q|^2: (|q| + |c|)^2
+    scale = (np.linalg.norm(Q, axis=1)[:, None] + np.linalg.norm(ix["centroids"], axis=1)[None, :]) ** 2
+    assert np.max(np.abs(gS.cpu().numpy() - S) / scale) < 1e-4
+    probes = oracle.select(S, nprobe)
+    gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+    assert np.array_equal(gp, probes)
+    assert rb.rago_debug_counters(h)[3] == 0
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="l2")
+    LUT8, B, delta = oracle.quantise(L)
+    gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+    assert np.array_equal(gL.cpu().numpy(), L)              # same fp64 expression, same order: bit-identical
+    assert np.array_equal(gd.cpu().numpy(), delta)
+    assert np.array_equal(gL8.cpu().numpy(), LUT8) and np.array_equal(gB.cpu().numpy(), B)
+
+
+def test_l2_search_end_to_end(l2case, rb, scan_kernel):
+    ix, Q, nprobe, k, h = l2case
+    r = oracle.ivfpq_search(Q, ix, nprobe, k, metric="l2")
+    gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+    torch.cuda.synchronize()
+    gi, gs, gis = gi.cpu().numpy(), gs.cpu().numpy(), gis.cpu().numpy()
+    assert np.array_equal(gi, r["ids"]) and np.array_equal(gis, r["iscores"])
+    assert np.array_equal(gs, r["scores"])
+    have = r["ids"] >= 0
+    assert np.all(gs[have] <= 0)                            # minus a squared distance (up to the table step)
+
+
+def test_l2_large_batch_coarse(rb):
+    """The split-bf16 coarse kernel (128 queries and more) with the Euclidean epilogue."""
+    ix = to_np(synth.random_index(n=20000, d=80, m=16, nlist=1000, seed=78))
+    Q = _queries(300, 80, 6)
+    h = rb.rago_index_wrap(dev_index(ix), metric="l2")
+    S = oracle.coarse(Q, ix["centroids"], metric="l2")
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+    scale = (np.linalg.norm(Q, axis=1)[:, None] + np.linalg.norm(ix["centroids"], axis=1)[None, :]) ** 2
+    assert np.max(np.abs(gS.cpu().numpy() - S) / scale) < 1e-4
+    for nprobe in (1, 50):
+        gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+        assert np.array_equal(gp, oracle.select(S, nprobe)), nprobe
+        assert rb.rago_debug_counters(h)[3] == 0
+    rb.rago_index_free(h)
