@@ -218,8 +218,35 @@ def run_iter(args, rb, h, Q, cfg, cpu):
                 q = synth.drift_queries(q, synth.ITER_DRIFT, g)
         lat = np.array(lat)
         stages, _ = rb.rago_debug_stage_ms(h)
+        rb.rago_debug_profile(h, False)
+        # the same rounds with the whole search of one round captured once in a HIP graph and replayed
+        # (the call only enqueues kernels on the caller's stream, so it can be captured as it is)
+        q_static = Q[:b].clone()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            rb.rago_ivfpq_search(h, q_static, nprobe, k, out=out)
+        glat, same = [], True
+        for c in range(chains):
+            q = synth.make_queries(cfg, b, device="cuda", stream=20 + c + 1)
+            for r in range(synth.ITER_ROUNDS):
+                q_static.copy_(q)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                glat.append(e0.elapsed_time(e1))
+                if c == 0 and r < 2:                 # replays against the eager call on the same queries
+                    gi = out[0].clone()
+                    ei = rb.rago_ivfpq_search(h, q, nprobe, k)[0]
+                    same = same and bool(torch.equal(gi, ei))
+                q = synth.drift_queries(q, synth.ITER_DRIFT, g)
+        glat = np.array(glat)
         res[str(b)] = {"round_ms_median": float(np.median(lat)), "round_ms_p99": float(np.percentile(lat, 99)),
-                       "queries_per_s": float(b / (np.median(lat) * 1e-3)), "stage_ms": stages}
+                       "queries_per_s": float(b / (np.median(lat) * 1e-3)), "stage_ms": stages,
+                       "graph_round_ms_median": float(np.median(glat)), "graph_round_ms_p99": float(np.percentile(glat, 99)),
+                       "graph_equals_eager": same}
     rec = {"metric": "ivfpq_iterative_round_latency", "value": res["1"]["round_ms_median"], "unit": "ms", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",

@@ -296,3 +296,32 @@ def test_l2_large_batch_coarse(rb):
         assert np.array_equal(gp, oracle.select(S, nprobe)), nprobe
         assert rb.rago_debug_counters(h)[3] == 0
     rb.rago_index_free(h)
+
+
+def test_search_replayed_from_a_hip_graph(rb):
+    """The search only enqueues kernels on the caller's stream (no allocation once the workspace has its size, no
+    host read-back, no memset node), so a caller may capture it.  Every replay, with eager work and
+    synchronisation in between, must equal the eager call on the same queries."""
+    ix = to_np(synth.random_index(n=30000, d=64, m=32, nlist=40, seed=91))
+    h = rb.rago_index_wrap(dev_index(ix))
+    nq, nprobe, k = 6, 9, 20
+    q_static = torch.from_numpy(_queries(nq, 64, 1)).cuda()
+    out = (torch.empty(nq, k, dtype=torch.int64, device="cuda"), torch.empty(nq, k, dtype=torch.float32, device="cuda"),
+           torch.empty(nq, k, dtype=torch.int32, device="cuda"))
+    rb.rago_ivfpq_search(h, q_static, nprobe, k, out=out)        # sizes the workspace
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rb.rago_ivfpq_search(h, q_static, nprobe, k, out=out)
+    for rep in range(4):
+        Q = _queries(nq, 64, 10 + rep)
+        q_static.copy_(torch.from_numpy(Q).cuda())
+        graph.replay()
+        torch.cuda.synchronize()
+        gi, gis = out[0].cpu().numpy().copy(), out[2].cpu().numpy().copy()
+        r = oracle.ivfpq_search(Q, ix, nprobe, k)
+        assert np.array_equal(gi, r["ids"]) and np.array_equal(gis, r["iscores"]), rep
+        ei, _, eis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)      # eager work between replays
+        torch.cuda.synchronize()
+        assert np.array_equal(ei.cpu().numpy(), gi)
+    rb.rago_index_free(h)
