@@ -68,6 +68,19 @@ def select(S, nprobe):
     return probes
 
 
+def select_tree(Q, upper, C, nsp, nprobe, metric="ip"):
+    """Probes through an upper level: `upper` = dict(super_centroids [nsuper][d], super_offsets [nsuper+1],
+    super_lists [nlist]); returns (probes [nq][nprobe], kept groups [nq][nsp])."""
+    Q, C = _arr(Q, np.float32), _arr(C, np.float32)
+    SC = _arr(upper["super_centroids"], np.float32)
+    soff, sl = _arr(upper["super_offsets"], np.int64), _arr(upper["super_lists"], np.int32)
+    nq, d = Q.shape
+    probes, sup = np.empty((nq, nprobe), np.int32), np.empty((nq, nsp), np.int32)
+    _chk(_load().oracle_select_tree(_p(Q), _p(SC), _p(soff), _p(sl), _p(C), I64(nq), I64(SC.shape[0]), I64(C.shape[0]), I64(d),
+                                    I64(nsp), I64(nprobe), ctypes.c_int(METRICS[metric]), _p(probes), _p(sup)), "select_tree")
+    return probes, sup
+
+
 def lut_f32(Q, C, CB, probes, metric="ip"):
     Q, C, CB, probes = _arr(Q, np.float32), _arr(C, np.float32), _arr(CB, np.float32), _arr(probes, np.int32)
     nq, d = Q.shape

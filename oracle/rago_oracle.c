@@ -97,6 +97,42 @@ int oracle_select(const float* S, int64_t nq, int64_t nlist, int64_t nprobe, int
     return ORACLE_OK;
 }
 
+/* ---- steps 1-2 with an upper level over the lists (the multi-level tree of Section 4, "Models
+ *      and database"; searching an upper level is itself a vector scan, Section 4 "Retrieval
+ *      performance modeling").  The lists are partitioned into nsuper groups: group s holds the
+ *      lists super_lists[super_offsets[s] .. super_offsets[s+1]) and has a centroid SC[s].  A query
+ *      scores the nsuper group centroids, keeps the nsp best groups (ties -> lower group), scores
+ *      only the lists of those groups, and takes the nprobe best of them (ties -> lower list).
+ *      Lists outside the kept groups count as -inf: when the kept groups hold fewer than nprobe
+ *      lists, the lowest-numbered other lists fill up.  Scores as in step 1 for the metric. ---- */
+int oracle_select_tree(const float* Q, const float* SC, const int64_t* super_offsets, const int32_t* super_lists,
+                       const float* C, int64_t nq, int64_t nsuper, int64_t nlist, int64_t d, int64_t nsp,
+                       int64_t nprobe, int metric, int32_t* probes, int32_t* out_supers) {
+    if (!Q || !SC || !super_offsets || !super_lists || !C || !probes) return ORACLE_EINVAL;
+    if (nsuper <= 0 || nsp <= 0 || nsp > nsuper || nprobe <= 0 || nprobe > nlist || (metric != 0 && metric != 1)) return ORACLE_EINVAL;
+    float* Ssup = (float*)malloc(sizeof(float) * (size_t)nsuper);
+    int32_t* sup = (int32_t*)malloc(sizeof(int32_t) * (size_t)nsp);
+    float* S = (float*)malloc(sizeof(float) * (size_t)nlist);
+    int rc = (Ssup && sup && S) ? ORACLE_OK : ORACLE_ENOMEM;
+    for (int64_t q = 0; q < nq && !rc; ++q) {
+        const float* qv = Q + q * d;
+        rc = metric ? oracle_coarse_l2(qv, SC, 1, nsuper, d, Ssup) : oracle_coarse(qv, SC, 1, nsuper, d, Ssup);
+        if (!rc) rc = oracle_select(Ssup, 1, nsuper, nsp, sup);
+        if (rc) break;
+        for (int64_t l = 0; l < nlist; ++l) S[l] = -INFINITY;
+        for (int64_t i = 0; i < nsp; ++i)
+            for (int64_t e = super_offsets[sup[i]]; e < super_offsets[sup[i] + 1]; ++e) {
+                const int64_t l = super_lists[e];
+                if (l < 0 || l >= nlist) { rc = ORACLE_EINVAL; break; }
+                rc = metric ? oracle_coarse_l2(qv, C + l * d, 1, 1, d, S + l) : oracle_coarse(qv, C + l * d, 1, 1, d, S + l);
+            }
+        if (!rc) rc = oracle_select(S, 1, nlist, nprobe, probes + q * nprobe);
+        if (!rc && out_supers) memcpy(out_supers + q * nsp, sup, sizeof(int32_t) * (size_t)nsp);
+    }
+    free(Ssup); free(sup); free(S);
+    return rc;
+}
+
 /* ---- step 3: fp32 look-up tables of the residual PQ, one per (query, probed list).
  *      A database vector in list l with code (c_0..c_{m-1}) is reconstructed as
  *      C[l] + concat_j CB[j][c_j]; its score with q splits over the m sub-spaces, so

@@ -434,3 +434,67 @@ def test_l2_and_ip_rank_unit_vectors_alike_on_lossless_codes():
         assert np.max(np.abs(s_l2[q].astype(np.float64) - (-(qn + d / 4 - 2.0 * s_ip[q].astype(np.float64))))) < 1e-5
         ex = np.lexsort((idx["ids"], np.sum((Ql[q].astype(np.float64)[None, :] - X) ** 2, axis=1)))[:10]
         assert set(i_l2[q, :10].tolist()) == set(ex.tolist()) or np.isclose(s_l2[q, 9], s_l2[q, 10])
+
+
+# ------------------------------------------------------------------ upper level over the lists (two-level coarse search)
+def _upper(nlist, nsuper, d, seed, dup=False):
+    g = np.random.default_rng(seed)
+    owner = g.integers(0, nsuper, nlist)
+    owner[:nsuper] = np.arange(nsuper)                     # no empty group ... except when asked for below
+    order = np.lexsort((np.arange(nlist), owner))          # by group, ascending list inside a group
+    off = np.searchsorted(owner[order], np.arange(nsuper + 1)).astype(np.int64)
+    SC = g.standard_normal((nsuper, d)).astype(np.float32)
+    if dup:
+        SC[1] = SC[0]                                      # exact tie between two groups
+    return dict(super_centroids=SC, super_offsets=off, super_lists=order.astype(np.int32)), owner
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_tree_select_equals_brute_force_and_exhaustive_limit(metric):
+    g = np.random.default_rng(3)
+    nlist, nsuper, d, nq = 60, 7, 12, 9
+    C = g.standard_normal((nlist, d)).astype(np.float32)
+    C[11] = C[10]                                          # tie between two lists
+    Q = g.standard_normal((nq, d)).astype(np.float32)
+    upper, owner = _upper(nlist, nsuper, d, 5, dup=True)
+
+    def score(A, B):                                       # independent numpy formulation
+        A, B = A.astype(np.float64), B.astype(np.float64)
+        if metric == "ip":
+            return (A @ B.T).astype(np.float32).astype(np.float64)
+        return (-np.sum((A[:, None, :] - B[None, :, :]) ** 2, axis=2)).astype(np.float32).astype(np.float64)
+
+    Ssup, S = score(Q, upper["super_centroids"]), score(Q, C)
+    for nsp, nprobe in ((2, 5), (3, 9), (1, 4), (nsuper, 13)):
+        probes, sup = oracle.select_tree(Q, upper, C, nsp, nprobe, metric=metric)
+        for q in range(nq):
+            keep = np.lexsort((np.arange(nsuper), -Ssup[q]))[:nsp]
+            assert sup[q].tolist() == keep.tolist()
+            member = np.isin(owner, keep)
+            key = np.where(member, S[q], -np.inf)
+            ref = np.lexsort((np.arange(nlist), -key))[:nprobe]
+            assert probes[q].tolist() == ref.tolist(), (nsp, nprobe, q)
+        if nsp == nsuper:                                  # every group kept = the exhaustive coarse search
+            assert np.array_equal(probes, oracle.select(oracle.coarse(Q, C, metric=metric), nprobe))
+    # duplicated group centroids: the lower group wins the tie (query 0 made to favour them)
+    Q2 = np.tile(upper["super_centroids"][0], (1, 1)).astype(np.float32) * (1.0 if metric == "ip" else 1.0)
+    _, sup = oracle.select_tree(Q2, upper, C, 1, 1, metric=metric)
+    if metric == "l2":
+        assert sup[0, 0] == 0                              # distance 0 to groups 0 and 1: lower number
+
+
+def test_tree_select_fills_up_with_low_lists_when_groups_are_small():
+    g = np.random.default_rng(8)
+    nlist, d = 20, 6
+    C = g.standard_normal((nlist, d)).astype(np.float32)
+    # three groups: {17, 19}, {3}, all the rest
+    lists = np.array([17, 19, 3] + [l for l in range(nlist) if l not in (3, 17, 19)], np.int32)
+    upper = dict(super_centroids=np.stack([C[17], C[3], C[0]]).astype(np.float32),
+                 super_offsets=np.array([0, 2, 3, nlist], np.int64), super_lists=lists)
+    Q = (C[17:18] * 3.0).astype(np.float32)                # clearly closest (by inner product) to group 0
+    probes, sup = oracle.select_tree(Q, upper, C, 1, 5)
+    assert sup[0, 0] == 0
+    first = sorted(probes[0, :2].tolist())
+    assert first == [17, 19] and probes[0, 2:].tolist() == [0, 1, 2]      # -inf elsewhere: lowest list numbers fill up
+    with pytest.raises(RuntimeError):
+        oracle.select_tree(Q, upper, C, 4, 5)              # more groups than exist
