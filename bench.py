@@ -130,7 +130,7 @@ def run_ivfpq(args):
     log(f"index wrapped ({info.code_bytes_resident / 1e9:.1f} GB of codes resident); total setup {time.time() - t0:.0f}s")
 
     if args.workload == "iter":
-        return run_iter(args, rb, h, Q, cfg, cpu)
+        return run_iter(args, rb, h, Q, cfg, cpu, index["centroids"])
 
     Qb = Q[:nq].contiguous()
     out = (torch.empty(nq, k, dtype=torch.int64, device=dev), torch.empty(nq, k, dtype=torch.float32, device=dev),
@@ -189,7 +189,7 @@ def run_ivfpq(args):
     rb.rago_index_free(h)
 
 
-def run_iter(args, rb, h, Q, cfg, cpu):
+def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
     """Iterative retrieval: 8 sequential rounds per request chain at batch 1 / 4 / 16."""
     import numpy as np
     import torch
@@ -247,12 +247,51 @@ def run_iter(args, rb, h, Q, cfg, cpu):
                        "queries_per_s": float(b / (np.median(lat) * 1e-3)), "stage_ms": stages,
                        "graph_round_ms_median": float(np.median(glat)), "graph_round_ms_p99": float(np.percentile(glat, 99)),
                        "graph_equals_eager": same}
+    # ---- the same rounds with probes chosen through an upper level over the lists (two-level coarse search)
+    tree = None
+    if args.upper:
+        nsuper, nsp = (int(x) for x in args.upper.split(","))
+        t1 = time.time()
+        upper = synth.build_upper_level(cen_dev, nsuper, seed=cfg.seed * 10 + 7)
+        sizes = (upper["super_offsets"][1:] - upper["super_offsets"][:-1])
+        rb.rago_index_set_upper_level(h, upper)
+        log(f"upper level: {nsuper} groups in {time.time() - t1:.1f}s, lists per group min/median/max = "
+            f"{int(sizes.min())}/{int(sizes.median())}/{int(sizes.max())}; keeping {nsp} groups per query")
+        tree = {"nsuper": nsuper, "nsp": nsp, "group_size_min_med_max": [int(sizes.min()), int(sizes.median()), int(sizes.max())],
+                "per_batch": {}}
+        for b in synth.ITER_BATCHES:
+            out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
+                   torch.empty(b, k, dtype=torch.int32, device="cuda"))
+            lat, agree = [], []
+            for c in range(max(args.steps, 4) + 1):
+                q = synth.make_queries(cfg, b, device="cuda", stream=20 + c)
+                for r in range(synth.ITER_ROUNDS):
+                    rb.rago_index_set_upper_probe(h, nsp)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    rb.rago_ivfpq_search(h, q, nprobe, k, out=out)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    if c > 0:
+                        lat.append(e0.elapsed_time(e1))
+                    if c == 1:                         # agreement of the results with the exhaustive list level
+                        ti = out[0].clone()
+                        rb.rago_index_set_upper_probe(h, 0)
+                        ei = rb.rago_ivfpq_search(h, q, nprobe, k)[0]
+                        agree.append(float(np.mean([len(set(ti[i].tolist()) & set(ei[i].tolist())) / k for i in range(b)])))
+                    q = synth.drift_queries(q, synth.ITER_DRIFT, g)
+            lat = np.array(lat)
+            # (round 0 = queries near the data; later rounds drift away from it and their nearest lists scatter)
+            tree["per_batch"][str(b)] = {"round_ms_median": float(np.median(lat)), "round_ms_p99": float(np.percentile(lat, 99)),
+                                         "topk_overlap_with_exhaustive_coarse_round0": agree[0],
+                                         "topk_overlap_with_exhaustive_coarse_all_rounds": float(np.mean(agree))}
+        rb.rago_index_set_upper_probe(h, 0)
     rec = {"metric": "ivfpq_iterative_round_latency", "value": res["1"]["round_ms_median"], "unit": "ms", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
            "config": {"workload": f"iterative on {cfg.name}: n={cfg.n} nlist={cfg.nlist} nprobe={nprobe} k={k} rounds=8 "
                                   f"batches=1/4/16 drift_sigma={synth.ITER_DRIFT}", "scale": args.scale},
-           "per_batch": res, "cpu_baseline": cpu}
+           "per_batch": res, "upper_level": tree, "cpu_baseline": cpu}
     print(json.dumps(rec), flush=True)
     rb.rago_index_free(h)
 
@@ -312,6 +351,7 @@ def main():
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--upper", default="", help="iter workload: also run with an upper level over the lists, 'groups,kept' (e.g. 256,8)")
     ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
                     help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()

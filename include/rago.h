@@ -89,6 +89,24 @@ int rago_index_load(const char* path, int device, rago_index** out);
  */
 int rago_index_wrap(const rago_index_arrays* arrays, int arrays_on_device, int device, rago_index** out);
 
+/*
+ * rago_index_set_upper_level: give the index an upper level over its lists (the paper's database is
+ * a multi-level tree, Section 4): nsuper groups of lists, group s = the lists
+ * super_lists[super_offsets[s] .. super_offsets[s+1]) with centroid super_centroids[s].
+ *   super_centroids [nsuper][d] fp32, super_offsets [nsuper+1] int64 (0 .. nlist, non-decreasing),
+ *   super_lists [nlist] int32: every list exactly once, ascending inside a group;
+ *   arrays_on_device as in rago_index_wrap.  The arrays are copied.  nsuper = 0 removes the level.
+ * rago_index_set_upper_probe: number of groups a query keeps (nsp).  0 (the default) = score every
+ * list centroid as before.  With nsp >= 1 a search scores the nsuper group centroids, keeps the nsp
+ * best groups (ties -> lower group), scores only their lists and probes the nprobe best of them
+ * (ties -> lower list); lists of other groups count as -inf, so if the kept groups hold fewer than
+ * nprobe lists the lowest-numbered other lists fill up.  Errors: RAGO_INVALID_ARG (no upper level,
+ * nsp > nsuper, malformed arrays), RAGO_UNSUPPORTED (nsuper > 8192 or nsp * largest group > 8192).
+ */
+int rago_index_set_upper_level(rago_index* idx, int32_t nsuper, const float* super_centroids, const int64_t* super_offsets,
+                               const int32_t* super_lists, int arrays_on_device);
+int rago_index_set_upper_probe(rago_index* idx, int32_t nsp);
+
 /* Release the index and its workspace (synchronises the device).  NULL is accepted. */
 int rago_index_free(rago_index* idx);
 
@@ -138,6 +156,11 @@ const char* rago_last_error(void);
 /* Coarse scores S[q][l] = <Q[q], C[l]> (fp32 MFMA; from 128 queries up bf16 MFMA on operands split
  * into two bf16 terms; either way within 1e-4 |q||c| of the exact product).  out_S DEVICE [nq][nlist] fp32. */
 int rago_debug_coarse(rago_index* idx, const float* queries, int64_t nq, float* out_S, void* stream);
+
+/* Probes through the upper level (rago_index_set_upper_probe >= 1), the stage the search then runs
+ * instead of the two above.  out_probes DEVICE [nq][nprobe] int32; out_groups DEVICE [nq][nsp] int32 or NULL. */
+int rago_debug_select_tree(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t* out_probes,
+                           int32_t* out_groups, void* stream);
 
 /* The nprobe best lists per query, best first, ties by lower list number.  Scores of the lists
  * near the cut are recomputed in fp64 from `queries`, so the choice does not depend on the

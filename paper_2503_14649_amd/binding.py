@@ -38,6 +38,9 @@ _lib.rago_index_free.argtypes = [_vp]
 _lib.rago_index_info.argtypes = [_vp, ctypes.POINTER(IndexDesc)]
 _lib.rago_ivfpq_search.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.rago_flat_search.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _vp, _vp, _int, _vp]
+_lib.rago_index_set_upper_level.argtypes = [_vp, _i32, _vp, _vp, _vp, _int]
+_lib.rago_index_set_upper_probe.argtypes = [_vp, _i32]
+_lib.rago_debug_select_tree.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp]
 _lib.rago_debug_coarse.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.rago_debug_select.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp]
 _lib.rago_debug_build_lut.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp]
@@ -101,6 +104,26 @@ def rago_index_wrap(index: dict, device: int = 0, metric="ip"):
     return h
 
 
+def rago_index_set_upper_level(h, upper: dict | None):
+    """upper: tensors super_centroids [nsuper][d] f32, super_offsets [nsuper+1] i64, super_lists [nlist] i32, all on the
+    CPU or all on the GPU; None removes the level."""
+    if upper is None:
+        _chk(_lib.rago_index_set_upper_level(h, 0, None, None, None, 0))
+        return
+    sc = upper["super_centroids"].contiguous().float()
+    off = upper["super_offsets"].contiguous().to(torch.int64)
+    sl = upper["super_lists"].contiguous().to(torch.int32)
+    on_dev = sc.is_cuda
+    assert off.is_cuda == on_dev and sl.is_cuda == on_dev, "all arrays must live on the same side"
+    if on_dev:
+        torch.cuda.synchronize(sc.device)
+    _chk(_lib.rago_index_set_upper_level(h, sc.shape[0], _ptr(sc), _ptr(off), _ptr(sl), int(on_dev)))
+
+
+def rago_index_set_upper_probe(h, nsp: int):
+    _chk(_lib.rago_index_set_upper_probe(h, nsp))
+
+
 def rago_index_free(h):
     _chk(_lib.rago_index_free(h))
 
@@ -146,6 +169,17 @@ def rago_debug_coarse(h, queries):
     S = torch.empty(queries.shape[0], info.nlist, dtype=torch.float32, device=queries.device)
     _chk(_lib.rago_debug_coarse(h, _ptr(queries), queries.shape[0], _ptr(S), _stream(queries.device)))
     return S
+
+
+def rago_debug_select_tree(h, queries, nprobe, nsp):
+    """Probes through the upper level (nsp = the value given to rago_index_set_upper_probe): (probes, kept groups)."""
+    queries = queries.contiguous()
+    dev = queries.device
+    nq = queries.shape[0]
+    probes = torch.empty(nq, nprobe, dtype=torch.int32, device=dev)
+    groups = torch.empty(nq, nsp, dtype=torch.int32, device=dev)
+    _chk(_lib.rago_debug_select_tree(h, _ptr(queries), nq, nprobe, _ptr(probes), _ptr(groups), _stream(dev)))
+    return probes, groups
 
 
 def rago_debug_select(h, queries, S, nprobe):

@@ -49,6 +49,7 @@ static void destroy(rago_index* idx) {
     if (!idx) return;
     hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cn2); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->list_off);
     hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
+    hipFree(idx->sup_cen); hipFree(idx->sup_off); hipFree(idx->sup_lists); hipFree(idx->sup_of);
     idx->ws.release();
     if (idx->prof.created)
         for (auto& c : idx->prof.ev) for (auto& e : c) hipEventDestroy(e);
@@ -213,6 +214,66 @@ int rago_index_load(const char* path, int device, rago_index** out) {
     return RAGO_OK;
 }
 
+int rago_index_set_upper_level(rago_index* idx, int32_t nsuper, const float* super_centroids, const int64_t* super_offsets,
+                               const int32_t* super_lists, int on_device) {
+    if (!idx) return fail(RAGO_INVALID_ARG, "null index");
+    DeviceGuard g(idx->device);
+    (void)hipDeviceSynchronize();
+    hipFree(idx->sup_cen); hipFree(idx->sup_off); hipFree(idx->sup_lists); hipFree(idx->sup_of);
+    idx->sup_cen = nullptr; idx->sup_off = nullptr; idx->sup_lists = nullptr; idx->sup_of = nullptr;
+    idx->nsuper = 0; idx->nsp = 0; idx->max_group = 0;
+    if (nsuper == 0) return RAGO_OK;
+    if (nsuper < 0 || !super_centroids || !super_offsets || !super_lists) return fail(RAGO_INVALID_ARG, "bad upper-level argument");
+    if (nsuper > tree_cap()) return fail(RAGO_UNSUPPORTED, "more than 8192 groups");
+    const int nlist = idx->nlist;
+    std::vector<int64_t> off(nsuper + 1);
+    std::vector<int32_t> lists(nlist), of(nlist, -1);
+    if (on_device) {
+        RAGO_HIP(hipMemcpy(off.data(), super_offsets, off.size() * 8, hipMemcpyDeviceToHost));
+        RAGO_HIP(hipMemcpy(lists.data(), super_lists, lists.size() * 4, hipMemcpyDeviceToHost));
+    } else {
+        std::memcpy(off.data(), super_offsets, off.size() * 8);
+        std::memcpy(lists.data(), super_lists, lists.size() * 4);
+    }
+    if (off[0] != 0 || off[nsuper] != nlist) return fail(RAGO_INVALID_ARG, "super_offsets must run from 0 to nlist");
+    int64_t largest = 0;
+    for (int s = 0; s < nsuper; ++s) {
+        if (off[s + 1] < off[s]) return fail(RAGO_INVALID_ARG, "super_offsets must be non-decreasing");
+        largest = std::max(largest, off[s + 1] - off[s]);
+        for (int64_t e = off[s]; e < off[s + 1]; ++e) {
+            const int32_t l = lists[e];
+            if (l < 0 || l >= nlist || of[l] != -1) return fail(RAGO_INVALID_ARG, "super_lists must hold every list exactly once");
+            if (e > off[s] && lists[e - 1] >= l) return fail(RAGO_INVALID_ARG, "lists must ascend inside a group");
+            of[l] = s;
+        }
+    }
+    if (hipMalloc(&idx->sup_cen, sizeof(float) * (size_t)nsuper * idx->d) != hipSuccess ||
+        hipMalloc(&idx->sup_off, sizeof(int64_t) * (size_t)(nsuper + 1)) != hipSuccess ||
+        hipMalloc(&idx->sup_lists, sizeof(int32_t) * (size_t)nlist) != hipSuccess ||
+        hipMalloc(&idx->sup_of, sizeof(int32_t) * (size_t)nlist) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(RAGO_OOM, "device allocation for the upper level failed");
+    }
+    RAGO_HIP(hipMemcpy(idx->sup_cen, super_centroids, sizeof(float) * (size_t)nsuper * idx->d,
+                       on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+    RAGO_HIP(hipMemcpy(idx->sup_off, off.data(), off.size() * 8, hipMemcpyHostToDevice));
+    RAGO_HIP(hipMemcpy(idx->sup_lists, lists.data(), lists.size() * 4, hipMemcpyHostToDevice));
+    RAGO_HIP(hipMemcpy(idx->sup_of, of.data(), of.size() * 4, hipMemcpyHostToDevice));
+    idx->nsuper = nsuper;
+    idx->max_group = (int)largest;
+    return RAGO_OK;
+}
+
+int rago_index_set_upper_probe(rago_index* idx, int32_t nsp) {
+    if (!idx) return fail(RAGO_INVALID_ARG, "null index");
+    if (nsp < 0) return fail(RAGO_INVALID_ARG, "nsp < 0");
+    if (nsp > 0 && idx->nsuper == 0) return fail(RAGO_INVALID_ARG, "the index has no upper level");
+    if (nsp > idx->nsuper) return fail(RAGO_INVALID_ARG, "nsp > nsuper");
+    if ((int64_t)nsp * idx->max_group > tree_cap()) return fail(RAGO_UNSUPPORTED, "nsp * largest group > 8192");
+    idx->nsp = nsp;
+    return RAGO_OK;
+}
+
 int rago_index_free(rago_index* idx) {
     if (!idx) return RAGO_OK;
     DeviceGuard g(idx->device);
@@ -257,6 +318,20 @@ int rago_debug_select(rago_index* idx, const float* queries, const float* S, int
     if (nq == 0) return RAGO_OK;
     DeviceGuard g(idx->device);
     return launch_select(idx, queries, S, nq, nprobe, out_probes, (hipStream_t)stream);
+}
+
+int rago_debug_select_tree(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t* out_probes,
+                           int32_t* out_groups, void* stream) {
+    int rc = check_search_args(idx, queries, out_probes, nq, nprobe, 1);
+    if (rc) return rc;
+    if (idx->nsp < 1) return fail(RAGO_INVALID_ARG, "no groups are kept (rago_index_set_upper_probe)");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launch_select_tree(idx, queries, nq, nprobe, out_probes, st))) return rc;
+    if (out_groups)
+        RAGO_HIP(hipMemcpyAsync(out_groups, idx->ws.cand_idx.p, (size_t)nq * idx->nsp * 4, hipMemcpyDeviceToDevice, st));
+    return RAGO_OK;
 }
 
 int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* probes, int64_t nq, int32_t nprobe,
@@ -309,15 +384,21 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     DeviceGuard g(idx->device);
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
-    if ((rc = ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
     if ((rc = ws.probes.reserve((size_t)npairs * 4))) return rc;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = nullptr;
     if (idx->prof.on && idx->prof.ncalls < PROF_CALLS) ev = idx->prof.ev[idx->prof.ncalls];
     if (ev) RAGO_HIP(hipEventRecord(ev[0], st));
-    if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st))) return rc;
-    if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
-    if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+    if (idx->nsp > 0) {
+        // through the upper level: both steps in one (the coarse-score slot of the stage times stays empty)
+        if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
+        if ((rc = launch_select_tree(idx, queries, nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+    } else {
+        if ((rc = ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
+        if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st))) return rc;
+        if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
+        if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+    }
     if (ev) RAGO_HIP(hipEventRecord(ev[2], st));
     if (idx->metric == 1) {
         // Euclidean metric: one full table per pair, handed to the scan like caller-supplied tables

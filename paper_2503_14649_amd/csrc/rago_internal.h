@@ -74,6 +74,12 @@ struct rago_index {
     uint8_t* codes_blk = nullptr;  // total_blocks * 64 * m bytes, skewed lane-major layout
     int64_t* ids = nullptr;        // [n]
     float max_cnorm = 0.f;
+    // optional upper level over the lists (tree.hip): groups of lists with a centroid each
+    int nsuper = 0, nsp = 0, max_group = 0;   // groups, groups kept per query (0: exhaustive list level), largest group
+    float* sup_cen = nullptr;      // [nsuper][d]
+    int64_t* sup_off = nullptr;    // [nsuper+1] into sup_lists
+    int32_t* sup_lists = nullptr;  // [nlist] lists grouped by group, ascending inside a group
+    int32_t* sup_of = nullptr;     // [nlist] group of each list
     rago::Workspace ws;
     rago::Profiler prof;
     // parameters of the last scan (for rago_debug_counters)
@@ -91,6 +97,10 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
 int launch_split_centroids(rago_index* idx, hipStream_t st);
 int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes,
                   hipStream_t st);
+
+// tree.hip
+int launch_select_tree(rago_index* idx, const float* q, int64_t nq, int nprobe, int32_t* probes, hipStream_t st);
+int tree_cap();
 
 // lut.hip
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,

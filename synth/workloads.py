@@ -284,6 +284,27 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     return out
 
 
+def build_upper_level(centroids: torch.Tensor, nsuper: int, seed: int, iters: int = 10, spherical: bool = True) -> dict:
+    """An upper level over the lists: Lloyd k-means of the list centroids into `nsuper` groups (seeded), every
+    list in the group of its nearest group centroid.  `spherical` (for inner-product search over unit-norm
+    data): cluster the directions of the centroids and give every group centroid unit norm, so that the
+    inner product with a query ranks groups by direction and not by how tight a group happens to be.
+    Returns super_centroids [nsuper][d] f32, super_offsets [nsuper+1] i64, super_lists [nlist] i32 (lists
+    grouped by group, ascending inside a group)."""
+    g = _gen(seed, centroids.device)
+    x = centroids.float()
+    if spherical:
+        x = torch.nn.functional.normalize(x, dim=1)
+    sc = kmeans(x, nsuper, iters, g)
+    if spherical:
+        sc = torch.nn.functional.normalize(sc, dim=1)
+    owner = _nearest_l2(x, sc)
+    order = torch.argsort(owner * centroids.shape[0] + torch.arange(centroids.shape[0], device=centroids.device))
+    off = torch.zeros(nsuper + 1, dtype=torch.int64, device=centroids.device)
+    off[1:] = torch.cumsum(torch.bincount(owner, minlength=nsuper), 0)
+    return dict(super_centroids=sc.contiguous(), super_offsets=off, super_lists=order.to(torch.int32).contiguous())
+
+
 def make_queries(cfg: IvfPqConfig, nq: Optional[int] = None, device="cpu", noise: float = 0.1,
                  stream: int = 4) -> torch.Tensor:
     """Queries = un-normalised mixture samples + N(0, noise^2) per coordinate, then L2-normalised."""

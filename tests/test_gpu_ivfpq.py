@@ -325,3 +325,46 @@ def test_search_replayed_from_a_hip_graph(rb):
         torch.cuda.synchronize()
         assert np.array_equal(ei.cpu().numpy(), gi)
     rb.rago_index_free(h)
+
+
+# ------------------------------------------------------------------ upper level over the lists
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_probes_through_upper_level_equal_oracle(rb, metric, scan_kernel):
+    ix = to_np(synth.random_index(n=40000, d=64, m=16, nlist=500, seed=61))
+    upper = synth.build_upper_level(torch.from_numpy(ix["centroids"]), 24, seed=3)
+    upper_np = to_np(upper)
+    sizes = np.diff(upper_np["super_offsets"])
+    Q = _queries(11, 64, 4)
+    Q[3] = ix["centroids"][7] / np.linalg.norm(ix["centroids"][7])
+    h = rb.rago_index_wrap(dev_index(ix), metric=metric)
+    with pytest.raises(rb.RagoError):
+        rb.rago_index_set_upper_probe(h, 2)                   # no upper level yet
+    rb.rago_index_set_upper_level(h, {k: v.cuda() for k, v in upper.items()})
+    with pytest.raises(rb.RagoError):
+        rb.rago_index_set_upper_probe(h, 25)                  # more groups than exist
+    k = 20
+    for nsp, nprobe in ((1, 5), (3, 40), (24, 64), (1, int(sizes.max()) + 3)):   # the last one needs the fill-up rule for small groups
+        rb.rago_index_set_upper_probe(h, nsp)
+        probes, groups = oracle.select_tree(Q, upper_np, ix["centroids"], nsp, nprobe, metric=metric)
+        gp, gg = rb.rago_debug_select_tree(h, torch.from_numpy(Q).cuda(), nprobe, nsp)
+        assert np.array_equal(gg.cpu().numpy(), groups), (nsp, nprobe)
+        assert np.array_equal(gp.cpu().numpy(), probes), (nsp, nprobe)
+        # whole search = the oracle's later stages on those probes
+        L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric=metric)
+        LUT8, B, delta = oracle.quantise(L)
+        oi, ois, osc = oracle.scan_topk(probes, LUT8, B, delta, ix["list_offsets"], ix["codes"], ix["ids"], k)
+        gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gis.cpu().numpy(), ois)
+        assert np.array_equal(gs.cpu().numpy(), osc)
+    # every group kept = the exhaustive search of the list level
+    rb.rago_index_set_upper_probe(h, 24)
+    a = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 30, k)[0].cpu().numpy()
+    rb.rago_index_set_upper_probe(h, 0)
+    b = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 30, k)[0].cpu().numpy()
+    assert np.array_equal(a, b)
+    # malformed levels are refused
+    bad = {k: v.clone() for k, v in upper.items()}
+    bad["super_lists"][0] = bad["super_lists"][1]
+    with pytest.raises(rb.RagoError):
+        rb.rago_index_set_upper_level(h, bad)
+    rb.rago_index_free(h)
