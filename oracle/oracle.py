@@ -123,11 +123,23 @@ def adc_f32_topk(probes, L, list_offsets, codes, ids, k):
     return oi, osc
 
 
+def expand_pq4(codebooks16):
+    """Codebooks of a 4-bit PQ index [m][16][dsub] -> the 256-word codebooks of its code bytes [m/2][256][2*dsub]."""
+    cb = _arr(codebooks16, np.float32)
+    m, ks, dsub = cb.shape
+    assert ks == 16
+    out = np.empty((m // 2, 256, 2 * dsub), np.float32)
+    _chk(_load().oracle_expand_pq4(_p(cb), I64(m), I64(dsub), _p(out)), "expand_pq4")
+    return out
+
+
 def ivfpq_search(Q, index, nprobe, k, metric="ip"):
     """index: dict with numpy arrays centroids, codebooks, list_offsets, codes, ids.
     metric "ip" = inner product, "l2" = minus squared Euclidean distance."""
     Q = _arr(Q, np.float32)
     C, CB = _arr(index["centroids"], np.float32), _arr(index["codebooks"], np.float32)
+    if CB.shape[1] == 16:              # 4-bit PQ: search on the codebooks of its code bytes
+        CB = expand_pq4(CB)
     off, codes, ids = _arr(index["list_offsets"], np.int64), _arr(index["codes"], np.uint8), _arr(index["ids"], np.int64)
     nq, d = Q.shape
     oi, osc, ois = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32), np.empty((nq, k), np.int32)

@@ -284,6 +284,24 @@ int oracle_adc_f32_topk(const int32_t* probes, const float* L, const int64_t* li
     return ORACLE_OK;
 }
 
+/* ---- 4-bit product quantisation (Section 2: a byte of code covers 4 to 16 dimensions).  Two
+ *      consecutive sub-quantisers of 16 codewords share a code byte, the even one in the low
+ *      nibble.  A byte b of sub-quantisers (2j, 2j+1) therefore is one symbol of a 256-word
+ *      codebook over their joint sub-space, word b = CB16[2j][b & 15] followed by
+ *      CB16[2j+1][b >> 4]; every other step of the search takes that codebook, with m/2
+ *      sub-quantisers of twice the width, unchanged (the table of a byte is the table of its joint
+ *      word, so quantisation to 8 bits is per byte, like the scan that consumes it).
+ *      CB16 [m][16][dsub] -> CB256 [m/2][256][2*dsub]. ---- */
+int oracle_expand_pq4(const float* CB16, int64_t m, int64_t dsub, float* CB256) {
+    if (!CB16 || !CB256 || m <= 0 || (m & 1) || dsub <= 0) return ORACLE_EINVAL;
+    for (int64_t j = 0; j < m / 2; ++j)
+        for (int64_t b = 0; b < KSUB; ++b)
+            for (int64_t t = 0; t < 2 * dsub; ++t)
+                CB256[(j * KSUB + b) * 2 * dsub + t] = t < dsub ? CB16[((2 * j) * 16 + (b & 15)) * dsub + t]
+                                                                 : CB16[((2 * j + 1) * 16 + (b >> 4)) * dsub + (t - dsub)];
+    return ORACLE_OK;
+}
+
 /* ---- whole search, steps 1-6 chained query by query (so the fp32 tables of only one query
  *      are alive at a time).  metric 0 = inner product, 1 = minus squared Euclidean distance.
  *      Optional outputs may be NULL. ---- */

@@ -3,7 +3,8 @@
 Layout: 64-byte header {magic "RAGOIVPQ", u32 version=1, u32 metric (0 = inner product),
 u32 d, u32 m, u32 ksub, u32 nlist, u64 n, zero padding} followed, back to back, by
 centroids f32[nlist][d], codebooks f32[m][ksub][d/m], list_offsets i64[nlist+1],
-codes u8[n][m] (list-major, one row per vector) and ids i64[n] (list-major).
+codes u8[n][m] (list-major, one row per vector; u8[n][m/2] when ksub = 16: two 4-bit codes per byte, the
+even sub-quantiser in the low nibble) and ids i64[n] (list-major).
 """
 import struct
 

@@ -343,22 +343,24 @@ def make_flat(cfg: FlatConfig, requests: Optional[int] = None, n: Optional[int] 
 
 # --------------------------------------------------------------------------- hand-made tiny index
 def random_index(n: int, d: int, m: int, nlist: int, seed: int, empty_lists=(), dup_codes: int = 0,
-                 shuffle_ids: bool = False, cb_scale: float = 0.3) -> Dict[str, torch.Tensor]:
+                 shuffle_ids: bool = False, cb_scale: float = 0.3, ksub: int = KSUB) -> Dict[str, torch.Tensor]:
     """Small index with random (untrained) centroids/codebooks/codes for brute-force checks.
     `empty_lists`: list numbers forced empty; `dup_codes`: that many vectors get a copy of
     another vector's code in the same list (forces exact score ties); `shuffle_ids`: ids are a
     random permutation instead of 0..n-1 (still ascending inside each list); `cb_scale`: magnitude of the
-    codewords relative to the centroids (tiny values give nearly constant look-up tables)."""
+    codewords relative to the centroids (tiny values give nearly constant look-up tables); `ksub` = 16: a 4-bit
+    PQ index, m sub-quantisers of 16 codewords, two per code byte (even one in the low nibble)."""
     g = _gen(seed, "cpu")
     centroids = torch.randn(nlist, d, generator=g) / math.sqrt(d)
-    codebooks = cb_scale * torch.randn(m, KSUB, d // m, generator=g) / math.sqrt(d)
+    assert ksub in (16, KSUB)
+    codebooks = cb_scale * torch.randn(m, ksub, d // m, generator=g) / math.sqrt(d)
     live = torch.tensor([l for l in range(nlist) if l not in set(empty_lists)])
     li = live[torch.randint(0, live.numel(), (n,), generator=g)]
     order = torch.sort(li, stable=True).indices
     counts = torch.bincount(li, minlength=nlist)
     offsets = torch.zeros(nlist + 1, dtype=torch.int64)
     offsets[1:] = counts.cumsum(0)
-    codes = torch.randint(0, KSUB, (n, m), generator=g, dtype=torch.int64).to(torch.uint8)
+    codes = torch.randint(0, KSUB, (n, m if ksub == KSUB else m // 2), generator=g, dtype=torch.int64).to(torch.uint8)
     for _ in range(dup_codes):
         l = int(live[torch.randint(0, live.numel(), (1,), generator=g)])
         a, b = int(offsets[l]), int(offsets[l + 1])

@@ -498,3 +498,47 @@ def test_tree_select_fills_up_with_low_lists_when_groups_are_small():
     assert first == [17, 19] and probes[0, 2:].tolist() == [0, 1, 2]      # -inf elsewhere: lowest list numbers fill up
     with pytest.raises(RuntimeError):
         oracle.select_tree(Q, upper, C, 4, 5)              # more groups than exist
+
+
+# ------------------------------------------------------------------ 4-bit PQ: two sub-quantisers per code byte
+def _reconstruct_pq4(ix):
+    """x_hat from nibbles, independent of the byte-codebook expansion."""
+    C, CB = ix["centroids"].astype(np.float64), ix["codebooks"].astype(np.float64)      # CB [m][16][dsub]
+    codes = ix["codes"]
+    m = CB.shape[0]
+    parts = []
+    for j in range(m):
+        nib = (codes[:, j // 2] >> (4 * (j & 1))) & 15
+        parts.append(CB[j][nib])
+    return C[list_of(ix)] + np.concatenate(parts, axis=1)
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_pq4_tables_and_search_match_reconstruction_from_nibbles(metric):
+    ix = to_np(synth.random_index(n=1200, d=24, m=12, nlist=6, seed=41, ksub=16, dup_codes=30, shuffle_ids=True))
+    assert ix["codebooks"].shape == (12, 16, 2) and ix["codes"].shape == (1200, 6)
+    CB = oracle.expand_pq4(ix["codebooks"])
+    assert CB.shape == (6, 256, 4)
+    # word b of byte j = codeword (b & 15) of sub-quantiser 2j, then codeword (b >> 4) of sub-quantiser 2j+1
+    assert np.array_equal(CB[2, 0xA7, :2], ix["codebooks"][4, 7]) and np.array_equal(CB[2, 0xA7, 2:], ix["codebooks"][5, 10])
+    g = np.random.default_rng(4)
+    Q = g.standard_normal((5, 24)).astype(np.float32)
+    probes = np.tile(np.arange(6, dtype=np.int32), (5, 1))
+    L = oracle.lut_f32(Q, ix["centroids"], CB, probes, metric=metric)
+    xhat, lst, codes = _reconstruct_pq4(ix), list_of(ix), ix["codes"]
+    ref = Q.astype(np.float64) @ xhat.T if metric == "ip" else -np.sum((Q.astype(np.float64)[:, None, :] - xhat[None]) ** 2, axis=2)
+    for q in range(5):
+        got = sum(L[q, lst, j, codes[:, j]].astype(np.float64) for j in range(6))
+        assert np.max(np.abs(got - ref[q])) < 1e-5
+    # every list probed: the unquantised search is the exhaustive ranking of the nibble reconstruction
+    k = 15
+    oi, osc = oracle.adc_f32_topk(probes, L, ix["list_offsets"], ix["codes"], ix["ids"], k)
+    for q in range(5):
+        rid, rkey = topk_desc(ref[q], ix["ids"], k)
+        assert np.max(np.abs(osc[q] - rkey)) < 5e-6
+        assert len(set(oi[q].tolist()) & set(rid.tolist())) >= k - 1
+    # the whole search takes the 4-bit index as it is
+    r = oracle.ivfpq_search(Q, ix, 3, k, metric=metric)
+    ix8 = dict(ix, codebooks=CB)
+    r8 = oracle.ivfpq_search(Q, ix8, 3, k, metric=metric)
+    assert np.array_equal(r["ids"], r8["ids"]) and np.array_equal(r["iscores"], r8["iscores"])
