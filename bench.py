@@ -81,6 +81,8 @@ def run_ivfpq(args):
 
     base = {"hyper": synth.HYPER, "mid": synth.MID, "tiny": synth.TINY, "iter": synth.HYPER}[args.workload]
     cfg = scaled_cfg(base, args.scale)
+    if args.ksub != 256 or args.m:
+        cfg = cfg.scaled(ksub=args.ksub, m=args.m or cfg.m, name=f"{cfg.name}-m{args.m or cfg.m}x{args.ksub}")
     dev = "cuda:0"
     t0 = time.time()
     last = [0.0]
@@ -175,8 +177,8 @@ def run_ivfpq(args):
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n} d={cfg.d} m={cfg.m} nlist={cfg.nlist} nq={nq} nprobe={nprobe} k={k}",
-                   "scale": args.scale, "similarity": args.metric},
-        "roofline": {"bound": "hbm", "kernel": f"scan_kernel<{cfg.m}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                   "scale": args.scale, "similarity": args.metric, "ksub": cfg.ksub},
+        "roofline": {"bound": "hbm", "kernel": f"scan_kernel<{cfg.m // 2 if cfg.ksub == 16 else cfg.m}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,
                      "kernel_ms": scan_ms, "launches_timed": ncalls},
@@ -352,6 +354,9 @@ def main():
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--upper", default="", help="iter workload: also run with an upper level over the lists, 'groups,kept' (e.g. 256,8)")
+    ap.add_argument("--ksub", type=int, default=256, choices=[256, 16],
+                    help="codewords per sub-quantiser; 16 = 4-bit codes, two sub-quantisers per code byte")
+    ap.add_argument("--m", type=int, default=0, help="sub-quantisers (default: the workload's)")
     ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
                     help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()

@@ -45,8 +45,8 @@ typedef struct rago_index rago_index; /* opaque */
 
 typedef struct rago_index_desc {
     int32_t d;        /* vector dimension                                   */
-    int32_t m;        /* PQ sub-quantisers = code bytes per vector          */
-    int32_t ksub;     /* codewords per sub-quantiser (always 256)           */
+    int32_t m;        /* PQ sub-quantisers (code bytes per vector = m for ksub 256, m/2 for ksub 16) */
+    int32_t ksub;     /* codewords per sub-quantiser: 256 or 16             */
     int32_t nlist;    /* inverted lists / coarse centroids                  */
     int64_t n;        /* database vectors                                   */
     int32_t metric;   /* 0 = inner product, 1 = Euclidean (see rago_index_arrays) */
@@ -62,22 +62,31 @@ typedef struct rago_index_arrays {
                                      squared distance to the reconstruction, so larger is better there too and
                                      scores come back <= 0 (Section 2 names both notions)                        */
     int64_t n;
+    int32_t ksub;                 /* codewords per sub-quantiser: 256 (0 means 256) = one code byte each, the
+                                     paper's configuration (Section 4); 16 = 4-bit codes, two sub-quantisers per
+                                     byte, sub-quantiser 2i in the low nibble of byte i and 2i+1 in the high one */
+    int32_t reserved;             /* set to 0                                                      */
     const float*   centroids;     /* [nlist][d] fp32                                              */
-    const float*   codebooks;     /* [m][256][d/m] fp32                                           */
+    const float*   codebooks;     /* [m][ksub][d/m] fp32                                          */
     const int64_t* list_offsets;  /* [nlist+1], list l = rows list_offsets[l] .. list_offsets[l+1] */
-    const uint8_t* codes;         /* [n][m] one row per vector, list-major                        */
+    const uint8_t* codes;         /* [n][m] (ksub 256) or [n][m/2] (ksub 16), one row per vector, list-major */
     const int64_t* ids;           /* [n] list-major; unique; ascending inside every list          */
 } rago_index_arrays;
 
 /*
  * rago_index_load: read an index file (HOST path) and place it on GPU `device`.
  * File, little-endian: 64-byte header {char magic[8]="RAGOIVPQ", u32 version=1, u32 metric (0 or 1),
- * u32 d, u32 m, u32 ksub=256, u32 nlist, u64 n, zero pad}, then centroids f32[nlist][d],
- * codebooks f32[m][256][d/m], list_offsets i64[nlist+1], codes u8[n][m], ids i64[n].
+ * u32 d, u32 m, u32 ksub (256 or 16), u32 nlist, u64 n, zero pad}, then centroids f32[nlist][d],
+ * codebooks f32[m][ksub][d/m], list_offsets i64[nlist+1], codes u8[n][m] (u8[n][m/2] for ksub 16,
+ * nibble order as in rago_index_arrays), ids i64[n].  A 4-bit index is searched as the 8-bit index
+ * it is equivalent to: a code byte is one symbol of the 256 concatenations of its two sub-quantisers'
+ * codewords, so tables, scores and results are those of an index with m/2 sub-quantisers over d/(m/2)
+ * dimensions each.
  * The codes are re-laid-out once for the scan (paper Section 4: 96-byte codes, 1 byte per 8
  * dimensions, are what the scan streams).  On success *out owns all device memory.
- * Errors: RAGO_IO, RAGO_FORMAT (incl. truncated), RAGO_UNSUPPORTED (m not in {16,32,64,96,128},
- * ksub != 256, d % m != 0, a list longer than 2^31-65 vectors), RAGO_OOM, RAGO_DEVICE.
+ * Errors: RAGO_IO, RAGO_FORMAT (incl. truncated), RAGO_UNSUPPORTED (code bytes per vector not in
+ * {16,32,64,96,128}, ksub not 256 or 16, d % m != 0, a list longer than 2^31-65 vectors), RAGO_OOM,
+ * RAGO_DEVICE.
  */
 int rago_index_load(const char* path, int device, rago_index** out);
 
@@ -169,6 +178,7 @@ int rago_debug_select(rago_index* idx, const float* queries, const float* S, int
                       int32_t* out_probes, void* stream);
 
 /* Look-up tables for given probes.  probes DEVICE [nq][nprobe] int32 (valid list numbers).
+ * Here and in rago_debug_scan, m counts CODE BYTES per vector (half the sub-quantisers of a 4-bit index).
  * out_L_f32 DEVICE [nq][nprobe][m][256] fp32 or NULL; out_LUT8 DEVICE [nq][nprobe][m][256] u8 or
  * NULL; out_B DEVICE [nq][nprobe] int32 or NULL; out_delta DEVICE [nq] fp32 or NULL. */
 int rago_debug_build_lut(rago_index* idx, const float* queries, const int32_t* probes, int64_t nq,

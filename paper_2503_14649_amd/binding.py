@@ -22,7 +22,8 @@ _vp, _i64, _i32, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.
 
 
 class _Arrays(ctypes.Structure):
-    _fields_ = [("d", _i32), ("m", _i32), ("nlist", _i32), ("metric", _i32), ("n", _i64), ("centroids", _vp), ("codebooks", _vp),
+    _fields_ = [("d", _i32), ("m", _i32), ("nlist", _i32), ("metric", _i32), ("n", _i64), ("ksub", _i32), ("reserved", _i32),
+                ("centroids", _vp), ("codebooks", _vp),
                 ("list_offsets", _vp), ("codes", _vp), ("ids", _vp)]
 
 
@@ -84,8 +85,8 @@ METRICS = {"ip": 0, "l2": 1}
 
 
 def rago_index_wrap(index: dict, device: int = 0, metric="ip"):
-    """index: tensors centroids [nlist][d] f32, codebooks [m][256][dsub] f32, list_offsets [nlist+1] i64,
-    codes [n][m] u8, ids [n] i64; all on the CPU or all on cuda:`device`.
+    """index: tensors centroids [nlist][d] f32, codebooks [m][ksub][dsub] f32 (ksub 256, or 16 for 4-bit codes),
+    list_offsets [nlist+1] i64, codes [n][m] u8 ([n][m/2] with ksub 16), ids [n] i64; all on the CPU or all on cuda:`device`.
     metric: "ip" (inner product) or "l2" (similarity = minus the squared Euclidean distance)."""
     c = index["centroids"].contiguous().float()
     cb = index["codebooks"].contiguous().float()
@@ -96,7 +97,7 @@ def rago_index_wrap(index: dict, device: int = 0, metric="ip"):
     on_dev = c.is_cuda
     assert all(t.is_cuda == on_dev for t in (cb, off, codes, ids)), "all arrays must live on the same side"
     a = _Arrays(c.shape[1], cb.shape[0], c.shape[0], METRICS[metric] if isinstance(metric, str) else int(metric), codes.shape[0],
-                _ptr(c), _ptr(cb), _ptr(off), _ptr(codes), _ptr(ids))
+                cb.shape[1], 0, _ptr(c), _ptr(cb), _ptr(off), _ptr(codes), _ptr(ids))
     h = _vp()
     if on_dev:
         torch.cuda.synchronize(device)
@@ -192,8 +193,9 @@ def rago_debug_build_lut(h, queries, probes, want_f32=True):
     info = rago_index_info(h)
     nq, nprobe = probes.shape
     dev = queries.device
-    L = torch.empty(nq, nprobe, info.m, 256, dtype=torch.float32, device=dev) if want_f32 else None
-    L8 = torch.empty(nq, nprobe, info.m, 256, dtype=torch.uint8, device=dev)
+    mb = info.m // 2 if info.ksub == 16 else info.m          # code bytes per vector = tables per (query, list) pair
+    L = torch.empty(nq, nprobe, mb, 256, dtype=torch.float32, device=dev) if want_f32 else None
+    L8 = torch.empty(nq, nprobe, mb, 256, dtype=torch.uint8, device=dev)
     B = torch.empty(nq, nprobe, dtype=torch.int32, device=dev)
     delta = torch.empty(nq, dtype=torch.float32, device=dev)
     _chk(_lib.rago_debug_build_lut(h, _ptr(queries), _ptr(probes), nq, nprobe, _ptr(L), _ptr(L8), _ptr(B), _ptr(delta),

@@ -57,11 +57,20 @@ static void destroy(rago_index* idx) {
 }
 
 // Shape checks + small arrays; leaves codes_blk / ids allocated but unfilled.
-static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const int64_t* h_list_off, int metric) {
+// `m` and `ksub` are the caller's: with ksub = 16 two sub-quantisers share a code byte and the
+// index continues as an 8-bit one over m/2 bytes (the caller's codebooks are expanded by set_codebooks).
+static int prepare(rago_index* idx, int d, int m, int ksub, int nlist, int64_t n, const int64_t* h_list_off, int metric) {
     if (metric != 0 && metric != 1) return fail(RAGO_UNSUPPORTED, "metric must be 0 (inner product) or 1 (Euclidean)");
     idx->metric = metric;
     if (d <= 0 || m <= 0 || nlist <= 0 || n < 0) return fail(RAGO_INVALID_ARG, "non-positive index dimension");
+    if (ksub != KSUB && ksub != 16) return fail(RAGO_UNSUPPORTED, "ksub must be 256 or 16");
     if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
+    idx->user_m = m; idx->user_ksub = ksub;
+    if (ksub == 16) {
+        if (m % 2) return fail(RAGO_UNSUPPORTED, "with ksub = 16, m must be even");
+        m /= 2;
+        if (!supported_m(m)) return fail(RAGO_UNSUPPORTED, "with ksub = 16, m must be one of 32, 64, 128, 192, 256");
+    }
     if (!supported_m(m)) return fail(RAGO_UNSUPPORTED, "m must be one of 16, 32, 64, 96, 128");
     if (d > 4096) return fail(RAGO_UNSUPPORTED, "d > 4096");
     if (h_list_off[0] != 0 || h_list_off[nlist] != n) return fail(RAGO_FORMAT, "list_offsets must start at 0 and end at n");
@@ -94,6 +103,22 @@ static int prepare(rago_index* idx, int d, int m, int nlist, int64_t n, const in
     RAGO_HIP(hipMemcpy(idx->list_off, h_list_off, sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
     RAGO_HIP(hipMemcpy(idx->blk_off, blk.data(), sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
     return RAGO_OK;
+}
+
+// Codebooks as the caller holds them ([user_m][user_ksub][d / user_m]) -> idx->codebooks.
+static int set_codebooks(rago_index* idx, const float* src, hipMemcpyKind kind) {
+    const size_t floats = (size_t)idx->user_m * idx->user_ksub * (idx->d / idx->user_m);
+    if (idx->user_ksub == KSUB) {
+        RAGO_HIP(hipMemcpy(idx->codebooks, src, floats * 4, kind));
+        return RAGO_OK;
+    }
+    float* small = nullptr;
+    if (hipMalloc(&small, floats * 4) != hipSuccess) { (void)hipGetLastError(); return fail(RAGO_OOM, "staging buffer for codebooks"); }
+    hipError_t e = hipMemcpy(small, src, floats * 4, kind);
+    int rc = e == hipSuccess ? launch_expand_pq4(small, idx->user_m, idx->d / idx->user_m, idx->codebooks, nullptr)
+                             : fail(RAGO_DEVICE, std::string("copying codebooks: ") + hipGetErrorString(e));
+    hipFree(small);
+    return rc;
 }
 
 static int finish(rago_index* idx, const uint8_t* d_codes_plain) {
@@ -129,19 +154,19 @@ int rago_index_wrap(const rago_index_arrays* a, int on_device, int device, rago_
     else std::memcpy(off.data(), a->list_offsets, sizeof(int64_t) * off.size());
     rago_index* idx = new rago_index();
     idx->device = device;
-    int rc = prepare(idx, a->d, a->m, a->nlist, a->n, off.data(), a->metric);
+    int rc = prepare(idx, a->d, a->m, a->ksub ? a->ksub : KSUB, a->nlist, a->n, off.data(), a->metric);
     uint8_t* plain = nullptr;
     if (!rc) {
         hipError_t e = hipMemcpy(idx->centroids, a->centroids, sizeof(float) * (size_t)a->nlist * a->d, kind);
-        if (e == hipSuccess) e = hipMemcpy(idx->codebooks, a->codebooks, sizeof(float) * (size_t)a->m * KSUB * (a->d / a->m), kind);
         if (e == hipSuccess && a->n) e = hipMemcpy(idx->ids, a->ids, sizeof(int64_t) * (size_t)a->n, kind);
         if (e != hipSuccess) rc = fail(RAGO_DEVICE, std::string("copying index arrays: ") + hipGetErrorString(e));
     }
+    if (!rc) rc = set_codebooks(idx, a->codebooks, kind);
     if (!rc) {
         if (on_device) {
             rc = finish(idx, a->codes);
         } else {
-            const size_t bytes = (size_t)a->n * a->m;
+            const size_t bytes = (size_t)a->n * idx->m;
             if (hipMalloc(&plain, bytes + 16) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "staging buffer for codes"); }
             if (!rc && bytes && hipMemcpy(plain, a->codes, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = fail(RAGO_DEVICE, "copying codes");
             if (!rc) rc = finish(idx, plain);
@@ -168,15 +193,17 @@ int rago_index_load(const char* path, int device, rago_index** out) {
     const uint32_t version = u[0], metric = u[1], d = u[2], m = u[3], ksub = u[4], nlist = u[5];
     if (version != 1) return fail(RAGO_FORMAT, "unknown index version");
     if (metric > 1) return fail(RAGO_UNSUPPORTED, "metric must be 0 (inner product) or 1 (Euclidean)");
-    if (ksub != KSUB) return fail(RAGO_UNSUPPORTED, "ksub must be 256");
+    if (ksub != KSUB && ksub != 16) return fail(RAGO_UNSUPPORTED, "ksub must be 256 or 16");
+    if (ksub == 16 && m % 2) return fail(RAGO_UNSUPPORTED, "with ksub = 16, m must be even");
+    const uint64_t cbytes = ksub == 16 ? m / 2 : m;   // code bytes per vector
     if (!d || !m || !nlist || d > (1u << 20) || nlist > (1u << 28) || n64 > (1ull << 40)) return fail(RAGO_FORMAT, "implausible header");
     if (d % m) return fail(RAGO_UNSUPPORTED, "d must be a multiple of m");
-    const uint64_t expect = 64 + 4ull * nlist * d + 4ull * m * KSUB * (d / m) + 8ull * (nlist + 1) + n64 * m + 8ull * n64;
+    const uint64_t expect = 64 + 4ull * nlist * d + 4ull * m * ksub * (d / m) + 8ull * (nlist + 1) + n64 * cbytes + 8ull * n64;
     if (std::fseek(f, 0, SEEK_END) != 0) return fail(RAGO_IO, "seek failed");
     const uint64_t have = (uint64_t)std::ftell(f);
     if (have != expect) return fail(RAGO_FORMAT, "file size does not match its header (truncated or corrupt)");
     std::fseek(f, 64, SEEK_SET);
-    std::vector<float> cen((size_t)nlist * d), cb((size_t)m * KSUB * (d / m));
+    std::vector<float> cen((size_t)nlist * d), cb((size_t)m * ksub * (d / m));
     std::vector<int64_t> off(nlist + 1);
     if (std::fread(cen.data(), 4, cen.size(), f) != cen.size() || std::fread(cb.data(), 4, cb.size(), f) != cb.size() ||
         std::fread(off.data(), 8, off.size(), f) != off.size())
@@ -185,20 +212,20 @@ int rago_index_load(const char* path, int device, rago_index** out) {
     if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
     rago_index* idx = new rago_index();
     idx->device = device;
-    int rc = prepare(idx, (int)d, (int)m, (int)nlist, (int64_t)n64, off.data(), (int)metric);
+    int rc = prepare(idx, (int)d, (int)m, (int)ksub, (int)nlist, (int64_t)n64, off.data(), (int)metric);
     uint8_t* plain = nullptr;
     void* stage = nullptr;
     const size_t CH = (size_t)64 << 20;
-    if (!rc && hipMalloc(&plain, (size_t)n64 * m + 16) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "staging buffer for codes"); }
+    if (!rc && hipMalloc(&plain, (size_t)n64 * cbytes + 16) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "staging buffer for codes"); }
     if (!rc && hipHostMalloc(&stage, CH) != hipSuccess) { (void)hipGetLastError(); rc = fail(RAGO_OOM, "pinned staging buffer"); }
     if (!rc) {
         hipError_t e = hipMemcpy(idx->centroids, cen.data(), cen.size() * 4, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(idx->codebooks, cb.data(), cb.size() * 4, hipMemcpyHostToDevice);
-        if (e != hipSuccess) rc = fail(RAGO_DEVICE, "copying centroids/codebooks");
+        if (e != hipSuccess) rc = fail(RAGO_DEVICE, "copying centroids");
     }
+    if (!rc) rc = set_codebooks(idx, cb.data(), hipMemcpyHostToDevice);
     // stream codes then ids through the pinned buffer
     for (int pass = 0; pass < 2 && !rc; ++pass) {
-        size_t total = pass == 0 ? (size_t)n64 * m : (size_t)n64 * 8;
+        size_t total = pass == 0 ? (size_t)n64 * cbytes : (size_t)n64 * 8;
         char* dst = pass == 0 ? (char*)plain : (char*)idx->ids;
         for (size_t a = 0; a < total && !rc; a += CH) {
             size_t len = total - a < CH ? total - a : CH;
@@ -284,7 +311,7 @@ int rago_index_free(rago_index* idx) {
 
 int rago_index_info(const rago_index* idx, rago_index_desc* out) {
     if (!idx || !out) return fail(RAGO_INVALID_ARG, "null argument");
-    out->d = idx->d; out->m = idx->m; out->ksub = KSUB; out->nlist = idx->nlist; out->n = idx->n;
+    out->d = idx->d; out->m = idx->user_m; out->ksub = idx->user_ksub; out->nlist = idx->nlist; out->n = idx->n;
     out->metric = idx->metric; out->device = idx->device; out->max_list_len = idx->max_list_len;
     out->code_bytes_resident = idx->total_blocks * BLOCK_VECS * idx->m;
     return RAGO_OK;

@@ -13,6 +13,7 @@
 //
 // A block = 64 consecutive vectors of one list (last block zero-padded) = 64*m bytes laid out
 // [t / 16][lane][t % 16], so one dwordx4 load per lane reads 1 KiB contiguous per wavefront.
+#include <algorithm>
 #include "rago_internal.h"
 
 namespace rago {
@@ -93,6 +94,32 @@ __global__ void __launch_bounds__(256) rago_calib_copy_kernel(const uint4* __res
 int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st) {
     rago_calib_copy_kernel<<<8192, 256, 0, st>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
     RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
+// 4-bit product quantisation (a finer-grained trade of code size against accuracy than Section 4's
+// one byte per 8 dimensions): a code byte holds two sub-quantisers of 16 codewords, the even one in
+// its low nibble.  Read as ONE symbol, that byte indexes the 256 concatenations of the two sets of
+// codewords over the joint sub-space; this kernel writes that 256-word codebook ([m/2][256][2 dsub],
+// pure copies), after which the index is an ordinary 8-bit one with m/2 code bytes.
+__global__ void __launch_bounds__(256) expand_pq4_kernel(const float* __restrict__ cb16, int m, int dsub, float* __restrict__ cb256) {
+    const int64_t total = (int64_t)(m / 2) * 256 * 2 * dsub;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i % (2 * dsub));
+        const int b = (int)((i / (2 * dsub)) % 256);
+        const int j = (int)(i / ((int64_t)2 * dsub * 256));
+        const int sub = t < dsub ? 2 * j : 2 * j + 1;
+        const int nib = t < dsub ? (b & 15) : (b >> 4);
+        cb256[i] = cb16[((int64_t)sub * 16 + nib) * dsub + (t < dsub ? t : t - dsub)];
+    }
+}
+
+int launch_expand_pq4(const float* d_cb16, int m, int dsub, float* d_cb256, hipStream_t st) {
+    const int64_t total = (int64_t)(m / 2) * 256 * 2 * dsub;
+    const int blocks = (int)std::min<int64_t>((total + 255) / 256, 4096);
+    expand_pq4_kernel<<<blocks, 256, 0, st>>>(d_cb16, m, dsub, d_cb256);
+    RAGO_HIP(hipGetLastError());
+    RAGO_HIP(hipStreamSynchronize(st));
     return RAGO_OK;
 }
 

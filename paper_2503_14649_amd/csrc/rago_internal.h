@@ -58,7 +58,8 @@ struct Profiler {
 
 struct rago_index {
     int device = 0;
-    int d = 0, m = 0, dsub = 0, nlist = 0;
+    int d = 0, m = 0, dsub = 0, nlist = 0;   // m = code bytes per vector, dsub = dimensions one byte covers
+    int user_m = 0, user_ksub = 256;         // as handed over: with 16-word sub-quantisers user_m = 2 m
     int metric = 0;                // 0 inner product, 1 Euclidean (similarity = minus squared distance)
     int64_t n = 0;
     int64_t max_list_len = 0;
@@ -91,6 +92,7 @@ namespace rago {
 // layout.hip
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
 int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
+int launch_expand_pq4(const float* d_cb16, int m, int dsub, float* d_cb256, hipStream_t st);
 
 // coarse.hip
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);

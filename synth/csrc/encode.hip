@@ -47,6 +47,10 @@ extern "C" int synth_pq_encode(const float* x, const float* centroids, const int
         case 4: encode_kernel<4><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
         case 8: encode_kernel<8><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
         case 16: encode_kernel<16><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
+        case 3: encode_kernel<3><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
+        case 6: encode_kernel<6><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
+        case 12: encode_kernel<12><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
+        case 24: encode_kernel<24><<<grid, 256, 0, st>>>(x, centroids, list, cb, n, d, m, codes); break;
         default: return -1;
     }
     return hipGetLastError() == hipSuccess ? 0 : -2;

@@ -44,6 +44,7 @@ class IvfPqConfig:
     assign: str = "exact"   # "exact" | "component" (see build_index)
     kmeans_iters: int = 8
     pq_train_n: int = 65536
+    ksub: int = 256         # codewords per sub-quantiser; 16 = 4-bit codes, two per byte (m/2 bytes per code)
 
     def scaled(self, **kw) -> "IvfPqConfig":
         return dataclasses.replace(self, **kw)
@@ -138,19 +139,19 @@ def kmeans(x: torch.Tensor, kc: int, iters: int, g: torch.Generator) -> torch.Te
     return c
 
 
-def _pq_train(res: torch.Tensor, m: int, iters: int, g: torch.Generator) -> torch.Tensor:
-    """Per-subspace k-means on residuals: returns codebooks [m][256][dsub]."""
+def _pq_train(res: torch.Tensor, m: int, iters: int, g: torch.Generator, ksub: int = KSUB) -> torch.Tensor:
+    """Per-subspace k-means on residuals: returns codebooks [m][ksub][dsub]."""
     n, d = res.shape
     dsub = d // m
     r = res.view(n, m, dsub).permute(1, 0, 2).contiguous()            # [m][n][dsub]
-    idx = torch.randperm(n, generator=g, device=res.device)[:KSUB]
-    if idx.numel() < KSUB:
-        idx = torch.randint(0, n, (KSUB,), generator=g, device=res.device)
-    cb = r[:, idx, :].clone()                                          # [m][256][dsub]
+    idx = torch.randperm(n, generator=g, device=res.device)[:ksub]
+    if idx.numel() < ksub:
+        idx = torch.randint(0, n, (ksub,), generator=g, device=res.device)
+    cb = r[:, idx, :].clone()                                          # [m][ksub][dsub]
     for _ in range(iters):
         a = _pq_assign(r, cb)                                          # [m][n]
         one = torch.ones_like(a, dtype=res.dtype)
-        cnt = torch.zeros(m, KSUB, device=res.device, dtype=res.dtype).scatter_add_(1, a, one)
+        cnt = torch.zeros(m, ksub, device=res.device, dtype=res.dtype).scatter_add_(1, a, one)
         s = torch.zeros_like(cb).scatter_add_(1, a.unsqueeze(2).expand(-1, -1, dsub), r)
         nz = cnt > 0
         cb = torch.where(nz.unsqueeze(2), s / cnt.clamp(min=1).unsqueeze(2), cb)
@@ -166,6 +167,17 @@ def _pq_assign(r: torch.Tensor, cb: torch.Tensor, chunk: int = 32768) -> torch.T
         sc = torch.bmm(r[:, a:a + chunk, :], cb.transpose(1, 2)) - half.unsqueeze(1)
         out[:, a:a + chunk] = sc.argmax(2)
     return out
+
+
+def pairs_of_codewords(cb16: torch.Tensor) -> torch.Tensor:
+    """[m][16][dsub] -> [m/2][256][2 dsub]: entry b of pair i = codeword (b & 15) of sub-quantiser 2i followed by
+    codeword (b >> 4) of sub-quantiser 2i+1 (the byte layout of a 4-bit code).  Used to ENCODE the database only."""
+    m, ks, dsub = cb16.shape
+    assert ks == 16 and m % 2 == 0
+    b = torch.arange(256, device=cb16.device)
+    lo = cb16[0::2][:, b & 15, :]                                      # [m/2][256][dsub]
+    hi = cb16[1::2][:, b >> 4, :]
+    return torch.cat([lo, hi], dim=2).contiguous()
 
 
 def pq_encode(res: torch.Tensor, cb: torch.Tensor) -> torch.Tensor:
@@ -199,8 +211,8 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     """Generate the database and train/encode an IVF-PQ index for it.
 
     Returns a dict of tensors on `device`:
-      centroids [nlist][d] f32, codebooks [m][256][dsub] f32, list_offsets [nlist+1] i64,
-      codes [n][m] u8 (list-major, plain rows), ids [n] i64 (list-major, ascending inside
+      centroids [nlist][d] f32, codebooks [m][ksub][dsub] f32, list_offsets [nlist+1] i64,
+      codes [n][m] u8 ([n][m/2] with cfg.ksub = 16; list-major, plain rows), ids [n] i64 (list-major, ascending inside
       a list), and `vectors` [n][d] f32 (id-major) when kept.
     `assign="component"`: the list of a sample is chosen among the 16 centroids with the
     largest inner product to its mixture component's normalised mean instead of among all
@@ -217,11 +229,18 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     centroids = kmeans(xt, cfg.nlist, cfg.kmeans_iters, g_train)
     sub = xt[: cfg.pq_train_n]
     res = sub - centroids[_assign_exact(sub, centroids)]
-    codebooks = _pq_train(res, cfg.m, cfg.kmeans_iters, g_train)
+    codebooks = _pq_train(res, cfg.m, cfg.kmeans_iters, g_train, cfg.ksub)
     del xt, sub, res
+    user_codebooks = codebooks
+    code_bytes = cfg.m
+    if cfg.ksub == 16:
+        # the nearest pair of 16-word codewords is the nearest of their 256 concatenations (squared distance
+        # adds over the two halves), so encoding against the concatenations yields the packed byte directly
+        codebooks = pairs_of_codewords(codebooks)
+        code_bytes = cfg.m // 2
 
     n = cfg.n
-    codes_arr = torch.empty(n, cfg.m, dtype=torch.uint8, device=dev)   # arrival (= id) order
+    codes_arr = torch.empty(n, code_bytes, dtype=torch.uint8, device=dev)   # arrival (= id) order
     lists_arr = torch.empty(n, dtype=torch.int32, device=dev)
     vectors = torch.empty(n, cfg.d, device=dev) if keep_vectors else None
     use_native = dev.type == "cuda" and _native_encode_available()
@@ -277,7 +296,7 @@ def build_index(cfg: IvfPqConfig, device="cpu", keep_vectors: Optional[bool] = N
     del codes_arr
     if dev.type == "cuda":
         torch.cuda.empty_cache()
-    out = dict(centroids=centroids, codebooks=codebooks, list_offsets=offsets, codes=codes,
+    out = dict(centroids=centroids, codebooks=user_codebooks, list_offsets=offsets, codes=codes,
                ids=order.to(torch.int64))
     if vectors is not None:
         out["vectors"] = vectors

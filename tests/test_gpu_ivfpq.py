@@ -368,3 +368,86 @@ def test_probes_through_upper_level_equal_oracle(rb, metric, scan_kernel):
     with pytest.raises(rb.RagoError):
         rb.rago_index_set_upper_level(h, bad)
     rb.rago_index_free(h)
+
+
+# ------------------------------------------------------------------ 4-bit product quantisation
+PQ4_CASES = {
+    # name: (n, d, sub-quantisers, nlist, nq, nprobe, k, kwargs): code bytes per vector = sub-quantisers / 2
+    "pq4_m192": (30000, 768, 192, 12, 6, 5, 100, dict(shuffle_ids=True)),
+    "pq4_m32_ties_empty": (3000, 64, 32, 8, 7, 4, 25, dict(empty_lists=(3,), dup_codes=60, shuffle_ids=True)),
+    "pq4_m64_dsub3": (9000, 192, 64, 16, 9, 3, 128, dict(dup_codes=10)),
+}
+
+
+@pytest.fixture(scope="module", params=list(PQ4_CASES))
+def pq4case(request):
+    n, d, m, nlist, nq, nprobe, k, kw = PQ4_CASES[request.param]
+    print(f"[case] {request.param} n={n} d={d} m={m} ksub=16 nlist={nlist} nq={nq} nprobe={nprobe} k={k}", flush=True)
+    ix = to_np(synth.random_index(n=n, d=d, m=m, nlist=nlist, seed=500 + m, ksub=16, **kw))
+    assert ix["codebooks"].shape == (m, 16, d // m) and ix["codes"].shape == (n, m // 2)
+    return ix, _queries(nq, d, 27 + m), nprobe, k
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_pq4_tables_equal_oracle(pq4case, rb, metric):
+    """The library's tables for a 4-bit index are the oracle's tables over the 256-word codebook of its code bytes."""
+    ix, Q, nprobe, k = pq4case
+    h = rb.rago_index_wrap(dev_index(ix), metric=metric)
+    try:
+        info = rb.rago_index_info(h)
+        assert (info.m, info.ksub, info.metric) == (ix["codebooks"].shape[0], 16, rb.METRICS[metric])
+        S = oracle.coarse(Q, ix["centroids"], metric=metric)
+        probes = oracle.select(S, nprobe)
+        L = oracle.lut_f32(Q, ix["centroids"], oracle.expand_pq4(ix["codebooks"]), probes, metric=metric)
+        LUT8, B, delta = oracle.quantise(L)
+        gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+        assert gL8.shape == LUT8.shape                                              # [nq][nprobe][m/2][256]
+        if metric == "l2":
+            assert np.array_equal(gL.cpu().numpy(), L)
+        else:
+            m2 = ix["codes"].shape[1]
+            qn = np.linalg.norm(Q.reshape(len(Q), m2, -1), axis=2)
+            assert np.max(np.abs(gL.cpu().numpy() - L) / np.maximum(2.0 * qn[:, None, :, None], 1e-30)) < 1e-4
+        assert np.array_equal(gd.cpu().numpy(), delta)
+        assert np.array_equal(gL8.cpu().numpy(), LUT8) and np.array_equal(gB.cpu().numpy(), B)
+    finally:
+        rb.rago_index_free(h)
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_pq4_search_end_to_end(pq4case, rb, metric, scan_kernel):
+    ix, Q, nprobe, k = pq4case
+    r = oracle.ivfpq_search(Q, ix, nprobe, k, metric=metric)
+    h = rb.rago_index_wrap(dev_index(ix), metric=metric)
+    try:
+        gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+        torch.cuda.synchronize()
+        assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+        assert np.array_equal(gs.cpu().numpy(), r["scores"])
+    finally:
+        rb.rago_index_free(h)
+
+
+def test_pq4_index_file_and_argument_errors(rb, tmp_path):
+    ix = to_np(synth.random_index(n=5000, d=64, m=32, nlist=10, seed=19, shuffle_ids=True, ksub=16))
+    path = str(tmp_path / "ix4.bin")
+    synth.write_index(path, {k: torch.from_numpy(v) for k, v in ix.items()})
+    h = rb.rago_index_load(path)
+    Q = _queries(6, 64, 5)
+    r = oracle.ivfpq_search(Q, ix, 4, 20)
+    gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 4, 20)
+    assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    info = rb.rago_index_info(h)
+    assert (info.m, info.ksub) == (32, 16)
+    rb.rago_index_free(h)
+    # 24 sub-quantisers of 16 words = 12 code bytes: not a width the scan is built for
+    bad = to_np(synth.random_index(n=500, d=48, m=24, nlist=4, seed=3, ksub=16))
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_index_wrap(dev_index(bad))
+    assert e.value.code == -6
+    # a codebook with 64 words per sub-quantiser is neither format
+    odd = dict(dev_index(to_np(synth.random_index(n=500, d=64, m=16, nlist=4, seed=3))))
+    odd["codebooks"] = odd["codebooks"][:, :64].contiguous()
+    with pytest.raises(rb.RagoError) as e:
+        rb.rago_index_wrap(odd)
+    assert e.value.code == -6
