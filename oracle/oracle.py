@@ -150,12 +150,13 @@ def ivfpq_search(Q, index, nprobe, k, metric="ip"):
     return dict(ids=oi, scores=osc, iscores=ois, probes=probes, delta=delta)
 
 
-def flat_search(corpus_bits, query_bits, k):
-    """corpus_bits uint16 [R][n][d], query_bits uint16 [R][nq][d]: raw bf16 bit patterns."""
+def flat_search(corpus_bits, query_bits, k, fmt="bf16"):
+    """corpus_bits uint16 [R][n][d], query_bits uint16 [R][nq][d]: raw bit patterns of bf16 (default) or IEEE
+    binary16 (`fmt="f16"`) numbers."""
     X, Qb = _arr(corpus_bits, np.uint16), _arr(query_bits, np.uint16)
     R, n, d = X.shape
     nqr = Qb.shape[1]
     oi, osc = np.empty((R, nqr, k), np.int64), np.empty((R, nqr, k), np.float32)
-    _chk(_load().oracle_flat_search(_p(X), _p(Qb), I64(R), I64(n), I64(nqr), I64(d), I64(k), _p(oi), _p(osc)),
-         "flat_search")
+    fn = {"bf16": _load().oracle_flat_search, "f16": _load().oracle_flat_search_f16}[fmt]
+    _chk(fn(_p(X), _p(Qb), I64(R), I64(n), I64(nqr), I64(d), I64(k), _p(oi), _p(osc)), "flat_search")
     return oi, osc

@@ -343,8 +343,20 @@ int oracle_ivfpq_search(const float* Q, int64_t nq, int64_t d, const float* C, i
  *      bf16 = upper 16 bits of an IEEE fp32. ---- */
 static float bf16_to_f32(uint16_t h) { uint32_t u = (uint32_t)h << 16; float f; memcpy(&f, &u, 4); return f; }
 
-int oracle_flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t n, int64_t nqr,
-                       int64_t d, int64_t k, int64_t* out_ids, float* out_scores) {
+/* IEEE 754 binary16 (1 sign, 5 exponent, 10 fraction bits; the format the paper caches freshly
+ * encoded chunks in, Section 5.2): value = (-1)^s 2^(e-15) (1 + f/1024), e = 0: (-1)^s 2^-14 f/1024,
+ * e = 31: infinity (f = 0) or NaN. */
+static double f16_to_f64(uint16_t h) {
+    const int s = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return s ? -v : v;
+}
+
+static int flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t n, int64_t nqr,
+                       int64_t d, int64_t k, int half, int64_t* out_ids, float* out_scores) {
     if (!X || !Qb || !out_ids || !out_scores || R < 0 || n < 0 || nqr < 0 || d <= 0 || k <= 0) return ORACLE_EINVAL;
     int rc = ORACLE_OK;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -355,8 +367,10 @@ int oracle_flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t
         int64_t cnt = 0;
         for (int64_t i = 0; i < n; ++i) {
             double acc = 0.0;
-            for (int64_t t = 0; t < d; ++t)
-                acc += (double)bf16_to_f32(Qb[rq * d + t]) * (double)bf16_to_f32(X[(r * n + i) * d + t]);
+            for (int64_t t = 0; t < d; ++t) {
+                const uint16_t a = Qb[rq * d + t], b = X[(r * n + i) * d + t];
+                acc += half ? f16_to_f64(a) * f16_to_f64(b) : (double)bf16_to_f32(a) * (double)bf16_to_f32(b);
+            }
             cand_t c = { (double)(float)acc, i };
             offer(best, &cnt, k, c);
         }
@@ -367,6 +381,17 @@ int oracle_flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t
         free(best);
     }
     return rc;
+}
+
+int oracle_flat_search(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t n, int64_t nqr,
+                       int64_t d, int64_t k, int64_t* out_ids, float* out_scores) {
+    return flat_search(X, Qb, R, n, nqr, d, k, 0, out_ids, out_scores);
+}
+
+/* The same search over binary16 bit patterns (finite values). */
+int oracle_flat_search_f16(const uint16_t* X, const uint16_t* Qb, int64_t R, int64_t n, int64_t nqr,
+                           int64_t d, int64_t k, int64_t* out_ids, float* out_scores) {
+    return flat_search(X, Qb, R, n, nqr, d, k, 1, out_ids, out_scores);
 }
 
 int oracle_num_threads(void) {

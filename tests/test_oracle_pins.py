@@ -328,6 +328,49 @@ def test_flat_equals_matmul_and_stable_argsort():
     assert np.all(oi[:, :, 3:] == -1) and np.all(np.isneginf(osc[:, :, 3:]))
 
 
+def test_flat_f16_decodes_every_finite_pattern_as_numpy_does():
+    """One-dimensional corpora holding every finite binary16 pattern (subnormals, both zeros), query 1.0: a score is
+    the value itself, exactly; equal values (+0 and -0) rank by lower row."""
+    bits = np.array([b for b in range(65536) if (b >> 10) & 31 != 31], np.uint16)
+    assert bits.size == 63488
+    rng = np.random.default_rng(5)
+    bits = bits[rng.permutation(bits.size)].reshape(62, 1024, 1)
+    one = np.full((62, 1, 1), 0x3C00, np.uint16)
+    oi, osc = oracle.flat_search(bits, one, 1024, fmt="f16")
+    vals = bits.view(np.float16).astype(np.float32)[:, :, 0]
+    for r in range(62):
+        order = np.argsort(-vals[r], kind="stable")
+        assert oi[r, 0].tolist() == order.tolist()
+        assert np.array_equal(osc[r, 0], vals[r][order])
+    two = np.full((62, 1, 1), 0xC000, np.uint16)                            # query -2.0: signs and order flip
+    oi2, osc2 = oracle.flat_search(bits, two, 5, fmt="f16")
+    for r in range(62):
+        order = np.argsort(2.0 * vals[r], kind="stable")[:5]
+        assert oi2[r, 0].tolist() == order.tolist() and np.array_equal(osc2[r, 0], -2.0 * vals[r][order])
+
+
+def test_flat_f16_equals_matmul_and_stable_argsort():
+    cfg = synth.FLAT
+    corpus, queries = synth.make_flat(cfg, requests=2, n=700)
+    corpus, queries = corpus.float().half(), queries.float().half()
+    corpus[1, 5] = corpus[1, 300]
+    corpus[1, 301] = corpus[1, 300]
+    queries[1, 0] = corpus[1, 300]
+    cb = corpus.view(torch.int16).numpy().view(np.uint16)
+    qb = queries.view(torch.int16).numpy().view(np.uint16)
+    assert np.any((cb >> 10) & 31 == 0)                                     # the data holds subnormals
+    oi, osc = oracle.flat_search(cb, qb, 32, fmt="f16")
+    ref = torch.einsum("rqd,rnd->rqn", queries.double(), corpus.double()).numpy()
+    for r in range(2):
+        for q in range(cfg.nq):
+            order = np.argsort(-ref[r, q].astype(np.float32), kind="stable")[:32]
+            assert np.allclose(osc[r, q], ref[r, q][oi[r, q]], rtol=0, atol=1e-7)
+            assert oi[r, q].tolist() == order.tolist()
+    assert oi[1, 0, :3].tolist() == [5, 300, 301]
+    bi, _ = oracle.flat_search(cb, qb, 32)                                  # the same bits read as bf16 rank differently
+    assert not np.array_equal(bi, oi)
+
+
 # ------------------------------------------------------------------ Euclidean metric (similarity = minus squared distance)
 def test_l2_coarse_equals_numpy_distances(rnd):
     ix, Q = rnd
