@@ -306,15 +306,19 @@ def run_flat(args):
     cfg = synth.FLAT
     R = max(1, int(cfg.requests * min(1.0, args.scale * 4))) if args.scale < 1.0 else cfg.requests
     corpus, queries = synth.make_flat(cfg, requests=R, device="cuda:0")
+    half = args.flat_format == "f16"
+    if half:
+        corpus, queries = corpus.to(torch.float16), queries.to(torch.float16)   # same embeddings, stored as binary16
+    search = rb.rago_flat_search_f16 if half else rb.rago_flat_search
     out = (torch.empty(R, cfg.nq, cfg.k, dtype=torch.int64, device="cuda"),
            torch.empty(R, cfg.nq, cfg.k, dtype=torch.float32, device="cuda"))
     for _ in range(args.warmup):
-        rb.rago_flat_search(corpus, queries, cfg.k, out=out)
+        search(corpus, queries, cfg.k, out=out)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        rb.rago_flat_search(corpus, queries, cfg.k, out=out)
+        search(corpus, queries, cfg.k, out=out)
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
@@ -326,16 +330,16 @@ def run_flat(args):
         cb = corpus[:rs].cpu().view(torch.int16).numpy().view(np.uint16)
         qb = queries[:rs].cpu().view(torch.int16).numpy().view(np.uint16)
         t1 = time.time()
-        oi, osc = oracle.flat_search(cb, qb, cfg.k)
+        oi, osc = oracle.flat_search(cb, qb, cfg.k, fmt=args.flat_format)
         dt = time.time() - t1
         gi = out[0][:rs].cpu().numpy()
         ov = float(np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / cfg.k for r in range(rs) for q in range(cfg.nq)]))
         cpu = {"value": rs / dt, "unit": "requests/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{rs} of {R} requests, {dt:.2f}s wall", "topk_id_overlap": ov}
     achieved = algo / (ms * 1e-3) / 1e9
-    rec = {"metric": "flat_requests_per_s", "value": R / (ms * 1e-3), "unit": "requests/s", "n_gpus": 1, "steps": args.steps,
+    rec = {"metric": "flat_requests_per_s" + ("_f16" if half else ""), "value": R / (ms * 1e-3), "unit": "requests/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "bf16", "data": "synthetic",
+           "dtype": args.flat_format, "data": "synthetic",
            "config": {"workload": f"flat: R={R} n={cfg.n} d={cfg.d} nq={cfg.nq} k={cfg.k}", "scale": args.scale},
            "roofline": {"bound": "hbm", "kernel": "flat_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes_per_launch": algo},
@@ -354,6 +358,7 @@ def main():
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--upper", default="", help="iter workload: also run with an upper level over the lists, 'groups,kept' (e.g. 256,8)")
+    ap.add_argument("--flat-format", default="bf16", choices=["bf16", "f16"], help="flat workload: number format of the embeddings")
     ap.add_argument("--ksub", type=int, default=256, choices=[256, 16],
                     help="codewords per sub-quantiser; 16 = 4-bit codes, two sub-quantisers per code byte")
     ap.add_argument("--m", type=int, default=0, help="sub-quantisers (default: the workload's)")

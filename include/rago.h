@@ -157,6 +157,16 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
 int rago_flat_search(const void* corpus_bf16, const void* queries_bf16, int32_t R, int64_t n, int32_t nqr,
                      int32_t d, int32_t k, int64_t* out_ids, float* out_scores, int device, void* stream);
 
+/*
+ * rago_flat_search_f16: the same search over IEEE binary16 ("FP16") embeddings, the format in which
+ * Section 5.2 caches the vectors of an encoded context for reuse.  corpus_f16 DEVICE [R][n][d] and
+ * queries_f16 DEVICE [R][nqr][d] hold binary16 numbers (finite; subnormals keep their value); scores
+ * are sums of exact fp16 products accumulated in fp32.  Every other argument, limit, the order of
+ * the results and the errors are those of rago_flat_search.
+ */
+int rago_flat_search_f16(const void* corpus_f16, const void* queries_f16, int32_t R, int64_t n, int32_t nqr,
+                         int32_t d, int32_t k, int64_t* out_ids, float* out_scores, int device, void* stream);
+
 /* Thread-local message of the last error on this thread ("" if none). */
 const char* rago_last_error(void);
 

@@ -39,6 +39,7 @@ _lib.rago_index_free.argtypes = [_vp]
 _lib.rago_index_info.argtypes = [_vp, ctypes.POINTER(IndexDesc)]
 _lib.rago_ivfpq_search.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.rago_flat_search.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _vp, _vp, _int, _vp]
+_lib.rago_flat_search_f16.argtypes = _lib.rago_flat_search.argtypes
 _lib.rago_index_set_upper_level.argtypes = [_vp, _i32, _vp, _vp, _vp, _int]
 _lib.rago_index_set_upper_probe.argtypes = [_vp, _i32]
 _lib.rago_debug_select_tree.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp]
@@ -149,9 +150,18 @@ def rago_ivfpq_search(h, queries: torch.Tensor, nprobe: int, k: int, want_iscore
     return ids, scores, isc
 
 
+def rago_flat_search_f16(corpus: torch.Tensor, queries: torch.Tensor, k: int, out=None):
+    """corpus fp16 [R][n][d], queries fp16 [R][nqr][d] on the GPU -> (ids i64 [R][nqr][k], scores f32)."""
+    return _flat(_lib.rago_flat_search_f16, torch.float16, corpus, queries, k, out)
+
+
 def rago_flat_search(corpus: torch.Tensor, queries: torch.Tensor, k: int, out=None):
     """corpus bf16 [R][n][d], queries bf16 [R][nqr][d] on the GPU -> (ids i64 [R][nqr][k], scores f32)."""
-    assert corpus.is_cuda and queries.is_cuda and corpus.dtype == torch.bfloat16 and queries.dtype == torch.bfloat16
+    return _flat(_lib.rago_flat_search, torch.bfloat16, corpus, queries, k, out)
+
+
+def _flat(fn, dtype, corpus, queries, k, out):
+    assert corpus.is_cuda and queries.is_cuda and corpus.dtype == dtype and queries.dtype == dtype
     assert corpus.is_contiguous() and queries.is_contiguous()
     R, n, d = corpus.shape
     nqr, dev = queries.shape[1], corpus.device
@@ -160,8 +170,7 @@ def rago_flat_search(corpus: torch.Tensor, queries: torch.Tensor, k: int, out=No
         scores = torch.empty(R, nqr, k, dtype=torch.float32, device=dev)
     else:
         ids, scores = out
-    _chk(_lib.rago_flat_search(_ptr(corpus), _ptr(queries), R, n, nqr, d, k, _ptr(ids), _ptr(scores),
-                               dev.index or 0, _stream(dev)))
+    _chk(fn(_ptr(corpus), _ptr(queries), R, n, nqr, d, k, _ptr(ids), _ptr(scores), dev.index or 0, _stream(dev)))
     return ids, scores
 
 

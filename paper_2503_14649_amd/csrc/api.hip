@@ -476,8 +476,8 @@ int rago_debug_stage_ms(rago_index* idx, float* out_ms, int32_t* out_calls) {
     return RAGO_OK;
 }
 
-int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
-                     int64_t* out_ids, float* out_scores, int device, void* stream) {
+static int flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
+                       int64_t* out_ids, float* out_scores, int device, bool half, void* stream) {
     if (R < 0 || n < 0) return fail(RAGO_INVALID_ARG, "negative size");
     if (nqr < 1 || nqr > 16) return fail(RAGO_INVALID_ARG, "nqr must be in [1, 16]");
     if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
@@ -489,7 +489,17 @@ int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t
     if (R == 0) return RAGO_OK;
     DeviceGuard g(device);
     if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
-    return launch_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, (hipStream_t)stream);
+    return launch_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, (hipStream_t)stream);
+}
+
+int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
+                     int64_t* out_ids, float* out_scores, int device, void* stream) {
+    return flat_search(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, false, stream);
+}
+
+int rago_flat_search_f16(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
+                         int64_t* out_ids, float* out_scores, int device, void* stream) {
+    return flat_search(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, true, stream);
 }
 
 int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream) {

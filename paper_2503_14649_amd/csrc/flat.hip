@@ -26,6 +26,15 @@ namespace rago {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// One 16x16x32 product-accumulate on eight 16-bit numbers per lane and operand: bf16, or IEEE
+// binary16 (the format of the embedding cache of Section 5.2) when HALF.
+template <bool HALF>
+__device__ __forceinline__ v4f mma16(const uint4& a, const uint4& b, v4f acc) {
+    if constexpr (HALF) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
 
 constexpr int FLAT_THREADS = 256;
 constexpr int FLAT_WAVES = 4;
@@ -122,7 +131,7 @@ struct FlatParams {
 typedef uint32_t f_u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) f_u32x4* f_global_ptr;
 
-template <int D>
+template <int D, bool HALF>
 __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatParams P) {
     constexpr int NP = D / 64;              // 128-byte segments per row
     constexpr int QS = D * 2 + 16;          // padded query row stride in LDS (bytes)
@@ -171,8 +180,8 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
         for (int sp = 0; sp < NP; ++sp) {
             const uint4 b0 = *reinterpret_cast<const uint4*>(qrow + sp * 128);
             const uint4 b1 = *reinterpret_cast<const uint4*>(qrow + sp * 128 + 64);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp]), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[2 * sp + 1]), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+            acc = mma16<HALF>(src[2 * sp], b0, acc);
+            acc = mma16<HALF>(src[2 * sp + 1], b1, acc);
         }
         // acc[e] = score of row rb + 4*g + e with query i16.  One counter update per lane for its (up to
         // four) candidates; the histogram updates and the key stores need no reply.
@@ -349,21 +358,26 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
 
 static DevBuf g_flat_keys[16], g_flat_cnt[16], g_flat_tbin[16];
 
-template <int D>
-static int launch_flat_d(const FlatParams& P, int grid, size_t lds, hipStream_t st) {
+template <int D, bool HALF>
+static int launch_flat_dh(const FlatParams& P, int grid, size_t lds, hipStream_t st) {
     static bool attr_done = false;
     if (!attr_done) {
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(flat_scan_kernel<D>),
+        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(flat_scan_kernel<D, HALF>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (D * 2 + 16) + 16 * FLAT_BINS * 2 + 256));
         attr_done = true;
     }
-    flat_scan_kernel<D><<<grid, FLAT_THREADS, lds, st>>>(P);
+    flat_scan_kernel<D, HALF><<<grid, FLAT_THREADS, lds, st>>>(P);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
 
+template <int D>
+static int launch_flat_d(const FlatParams& P, int grid, size_t lds, bool half, hipStream_t st) {
+    return half ? launch_flat_dh<D, true>(P, grid, lds, st) : launch_flat_dh<D, false>(P, grid, lds, st);
+}
+
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k, int64_t* out_ids,
-                float* out_scores, int device, hipStream_t st) {
+                float* out_scores, int device, bool half, hipStream_t st) {
     if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
     if (d % 64 || d > FLAT_MAXD) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 64, at most 1024");
     FlatParams P;
@@ -396,13 +410,13 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
     const size_t lds = 16 * (size_t)(d * 2 + 16) + 16 * FLAT_BINS * 2 + 256;
     const int grid = R * nslab;
     switch (d) {
-        case 64: rc = launch_flat_d<64>(P, grid, lds, st); break;
-        case 128: rc = launch_flat_d<128>(P, grid, lds, st); break;
-        case 256: rc = launch_flat_d<256>(P, grid, lds, st); break;
-        case 384: rc = launch_flat_d<384>(P, grid, lds, st); break;
-        case 512: rc = launch_flat_d<512>(P, grid, lds, st); break;
-        case 768: rc = launch_flat_d<768>(P, grid, lds, st); break;
-        case 1024: rc = launch_flat_d<1024>(P, grid, lds, st); break;
+        case 64: rc = launch_flat_d<64>(P, grid, lds, half, st); break;
+        case 128: rc = launch_flat_d<128>(P, grid, lds, half, st); break;
+        case 256: rc = launch_flat_d<256>(P, grid, lds, half, st); break;
+        case 384: rc = launch_flat_d<384>(P, grid, lds, half, st); break;
+        case 512: rc = launch_flat_d<512>(P, grid, lds, half, st); break;
+        case 768: rc = launch_flat_d<768>(P, grid, lds, half, st); break;
+        case 1024: rc = launch_flat_d<1024>(P, grid, lds, half, st); break;
         default: return fail(RAGO_UNSUPPORTED, "d must be one of 64, 128, 256, 384, 512, 768, 1024");
     }
     if (rc) return rc;

@@ -20,15 +20,18 @@ def _bits(t):
 
 
 def _check(rb, corpus, queries, k):
-    gi, gs = rb.rago_flat_search(corpus.cuda(), queries.cuda(), k)
+    """bf16 tensors go through rago_flat_search, fp16 tensors through rago_flat_search_f16."""
+    half = corpus.dtype == torch.float16
+    fn = rb.rago_flat_search_f16 if half else rb.rago_flat_search
+    gi, gs = fn(corpus.cuda(), queries.cuda(), k)
     torch.cuda.synchronize()
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
-    oi, osc = oracle.flat_search(_bits(corpus), _bits(queries), k)
+    oi, osc = oracle.flat_search(_bits(corpus), _bits(queries), k, fmt="f16" if half else "bf16")
     R, nq = queries.shape[:2]
     n = corpus.shape[1]
     kk = min(k, n)
     assert np.all(gi[:, :, kk:] == -1) and np.all(np.isneginf(gs[:, :, kk:]))
-    # scores: bf16 products are exact in fp32, only the accumulation order differs; |q||x| ~ 1
+    # scores: bf16 (and fp16) products are exact in fp32, only the accumulation order differs; |q||x| ~ 1
     assert np.max(np.abs(gs[:, :, :kk] - osc[:, :, :kk])) < 1e-4
     ov = np.mean([len(set(gi[r, q, :kk].tolist()) & set(oi[r, q, :kk].tolist())) / kk for r in range(R) for q in range(nq)])
     assert ov >= 0.999, ov
@@ -81,3 +84,33 @@ def test_flat_other_dims_and_errors(rb):
     assert e.value.code == -1
     gi, gs = rb.rago_flat_search(c[:, :0].contiguous(), q[:, :4].contiguous(), 4)   # empty corpus: all padding
     assert torch.all(gi == -1)
+
+
+# ------------------------------------------------------------------ IEEE binary16 embeddings
+@pytest.mark.parametrize("R,n,nq,k", [(2, 700, 16, 32), (3, 5000, 5, 128), (1, 20, 16, 32), (2, 1, 3, 4), (2, 30000, 16, 32)])
+def test_flat_f16_matches_oracle(rb, R, n, nq, k):
+    print(f"[flat f16] R={R} n={n} nq={nq} k={k}", flush=True)
+    corpus, queries = synth.make_flat(synth.FLAT, requests=R, n=n)
+    corpus, queries = corpus.float().half(), queries[:, :nq].float().half().contiguous()
+    _check(rb, corpus, queries, k)
+
+
+def test_flat_f16_ties_subnormals_and_dims(rb):
+    corpus, queries = synth.make_flat(synth.FLAT, requests=1, n=3000)
+    corpus, queries = corpus.float().half(), queries.float().half()
+    for i in (17, 300, 301, 1700, 2999):
+        corpus[0, i] = corpus[0, 5]
+    queries[0, 0] = corpus[0, 5]
+    gi, gs, oi, osc = _check(rb, corpus, queries, 32)
+    assert gi[0, 0, :6].tolist() == [5, 17, 300, 301, 1700, 2999]
+    # a corpus scaled by 2^-12: nearly every entry is a subnormal fp16 number and must keep its value
+    g = torch.Generator().manual_seed(11)
+    for d in (64, 256, 768, 1024):
+        c = (torch.nn.functional.normalize(torch.randn(2, 900, d, generator=g), dim=2) * 2.0 ** -12).half()
+        q = (torch.nn.functional.normalize(torch.randn(2, 7, d, generator=g), dim=2) * 2.0 ** 10).half()
+        bits = _bits(c)
+        assert np.mean(((bits >> 10) & 31) == 0) > 0.5
+        gi, gs, oi, osc = _check(rb, c, q, 10)
+        assert np.all(np.abs(gs[:, :, 0]) > 1e-3)                       # scores of order 2^-2 cos: nothing was flushed to zero
+    with pytest.raises(AssertionError):                                  # the binding refuses the wrong number format
+        rb.rago_flat_search_f16(torch.zeros(1, 10, 128, dtype=torch.bfloat16).cuda(), torch.zeros(1, 2, 128, dtype=torch.bfloat16).cuda(), 4)
