@@ -14,8 +14,11 @@
 //  * a workgroup (4 waves) streams one slab of one request; a wave takes 16-row blocks, the next
 //    block's 24 loads are in flight while the current block is multiplied.
 //  * selection: a score is a candidate when its histogram bin (width 1/128) is not below the
-//    query's threshold bin; candidates are appended as 64-bit keys (ordered score bits << 32 |
-//    ~row) to a per-(slab, query) area in HBM and counted in a per-query LDS histogram.  Every 256
+//    query's threshold bin; in the stream that is four compares and one wave-uniform branch per
+//    block.  A candidate first goes to the wave's staging area in LDS (positions from ballots, so
+//    nothing is waited for); at the end of a round the wave appends its staged candidates as 64-bit
+//    keys (ordered score bits << 32 | ~row) to a per-(slab, query) area in HBM and counts them in
+//    a per-query LDS histogram (atomics and stores with all lanes busy instead of one or two).  Every 256
 //    rows the workgroup synchronises and 16 lanes move each query's threshold to the highest bin
 //    that still has k candidates at or above it, so after the first round only ~k/round new keys
 //    appear.  An area that could overflow is cut back to its best k with a wave-level radix select
@@ -43,6 +46,8 @@ constexpr int FLAT_ROUND_ROWS = FLAT_WAVES * FLAT_RB * 16;  // 256 rows per work
 constexpr int FLAT_MAXD = 1024;
 constexpr int FLAT_CAP = 1024;                              // candidate keys per (slab, query) in the HBM scratch
 constexpr int FLAT_BINS = 256;                              // score histogram bins per query
+constexpr int FLAT_STAGE = 1024;                            // staged candidates per wave (LDS), flushed past 512 or at a round's end
+constexpr size_t flat_lds_bytes(int d) { return 16 * (size_t)(d * 2 + 16) + 16 * FLAT_BINS * 2 + 256 + (size_t)FLAT_WAVES * FLAT_STAGE * 8; }
 
 __device__ __forceinline__ uint32_t fkey(float f) {
     const uint32_t u = __float_as_uint(f);
@@ -140,6 +145,7 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
     uint16_t* hist = reinterpret_cast<uint16_t*>(smem + 16 * QS);             // [16][FLAT_BINS] candidates per score bin
     int32_t* cnt = reinterpret_cast<int32_t*>(hist + 16 * FLAT_BINS);         // [16]
     int32_t* tbin = cnt + 16;                                                 // [16] lowest bin that can still hold a top-k score
+    uint64_t* stage = reinterpret_cast<uint64_t*>(smem + 16 * QS + 16 * FLAT_BINS * 2 + 256) + (threadIdx.x >> 6) * FLAT_STAGE;   // this wave's
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int r = blockIdx.x / P.nslab, slab = blockIdx.x % P.nslab;
@@ -160,6 +166,10 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
     __syncthreads();
 
     const uint16_t* X = P.corpus + (int64_t)r * P.n * D;
+    const float never = __builtin_huge_valf();
+    float thrx = i16 < P.nqr ? -never : never;   // this lane's query: threshold bin as a float, -inf while it is bin 0
+    int nstage = 0;                              // candidates in this wave's staging area (wave-uniform)
+    int64_t round_base = row0;                   // first row of the current round
     uint4 a[2 * NP], an[2 * NP];
     // loads are unconditional (row clamped into the corpus): a conditional prefetch would make the
     // compiler wait for every outstanding load before each use
@@ -183,29 +193,36 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
             acc = mma16<HALF>(src[2 * sp], b0, acc);
             acc = mma16<HALF>(src[2 * sp + 1], b1, acc);
         }
-        // acc[e] = score of row rb + 4*g + e with query i16.  One counter update per lane for its (up to
-        // four) candidates; the histogram updates and the key stores need no reply.
-        const int tb = tbin[i16];
-        int bins[4];
-        int npass = 0;
+        // acc[e] = score of row rb + 4*g + e with query i16.  A score is a candidate when its bin is not
+        // below the query's threshold bin, i.e. (for a threshold >= 1) when x = (s + 1) * 128 >= threshold:
+        // the same x the bin is the integer part of.  Candidates are rare once the thresholds have risen,
+        // so the common path is four compares and one wave-uniform branch; a candidate goes to the wave's
+        // staging area in LDS (positions from ballots: no atomics, nothing to wait for).
+        bool pass[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            bins[e] = score_bin(acc[e]);
-            const bool pass = rb + 4 * g + e < row1 && i16 < P.nqr && bins[e] >= tb;
-            if (!pass) bins[e] = -1;
-            npass += pass;
-        }
-        if (npass) {
-            int pos = atomicAdd(&cnt[i16], npass);                  // < FLAT_CAP: see the round-end check
+        for (int e = 0; e < 4; ++e) pass[e] = (acc[e] + 1.0f) * 128.0f >= thrx;
+        if (__ballot(pass[0] | pass[1] | pass[2] | pass[3])) {
+            const bool partial = rb + 16 > row1;                    // only a slab's last block: rows past its end are repeats
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (bins[e] >= 0) {
-                    atomicAdd(reinterpret_cast<unsigned int*>(hist) + ((i16 * FLAT_BINS + bins[e]) >> 1), (bins[e] & 1) ? 0x10000u : 1u);
-                    mycand[(int64_t)i16 * FLAT_CAP + pos++] =
-                        ((uint64_t)fkey(acc[e]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(rb + 4 * g + e));
-                }
+                const bool pe = pass[e] && (!partial || rb + 4 * g + e < row1);
+                const uint64_t mask = __ballot(pe);
+                if (pe) stage[nstage + lane_rank64(mask)] =
+                    ((uint64_t)fkey(acc[e]) << 32) | (uint32_t)(i16 << 16) | (uint32_t)(rb - round_base + 4 * g + e);
+                nstage += __popcll(mask);
             }
         }
+    };
+    // Move the wave's staged candidates into the per-query areas in HBM and count them in the histograms.
+    auto flush = [&]() {
+        for (int e = lane; e < nstage; e += 64) {
+            const uint64_t s = stage[e];
+            const int q = (int)((uint32_t)s >> 16), bin = score_bin(fkey_inv((uint32_t)(s >> 32)));
+            const int pos = atomicAdd(&cnt[q], 1);                  // < FLAT_CAP: see the round-end check
+            atomicAdd(reinterpret_cast<unsigned int*>(hist) + ((q * FLAT_BINS + bin) >> 1), (bin & 1) ? 0x10000u : 1u);
+            mycand[(int64_t)q * FLAT_CAP + pos] = (s & 0xFFFFFFFF00000000ull) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(round_base + (int64_t)(s & 0xFFFFu)));
+        }
+        nstage = 0;
     };
 
     int shared_seen = 0;   // what the request-wide threshold word held one round ago (threads < nqr)
@@ -218,10 +235,12 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
             int64_t r2 = r0 + 32;
             if (bb + 2 >= FLAT_RB) r2 = round0 + FLAT_ROUND_ROWS + (int64_t)wave * FLAT_RB * 16;   // first block of next round
             load_rows(an, r1);
+            if (nstage > FLAT_STAGE - 512) flush();      // two blocks follow: up to 512 candidates while nothing is filtered
             if (r0 < row1) multiply(a, r0);
             load_rows(a, r2);
             if (r1 < row1) multiply(an, r1);
         }
+        if (nstage) flush();
         __syncthreads();
         // Per query (one wave each, four queries per wave): first cut an area back to its best k if it
         // could overflow in the next round (256 more keys at worst) and rebuild its histogram from the
@@ -271,6 +290,11 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
             shared_seen = atomicMax(P.shared_tbin + r * 16 + tid, tbin[tid]);
         }
         __syncthreads();
+        if (i16 < P.nqr) {
+            const int tb = tbin[i16];
+            thrx = tb > 0 ? (float)tb : -never;
+        }
+        round_base = round0 + FLAT_ROUND_ROWS;
     }
     // slab result: everything collected (the merge filters it with the request's final threshold bin)
     if (tid < P.nqr) {
@@ -363,7 +387,7 @@ static int launch_flat_dh(const FlatParams& P, int grid, size_t lds, hipStream_t
     static bool attr_done = false;
     if (!attr_done) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(flat_scan_kernel<D, HALF>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 16 * (D * 2 + 16) + 16 * FLAT_BINS * 2 + 256));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)flat_lds_bytes(D)));
         attr_done = true;
     }
     flat_scan_kernel<D, HALF><<<grid, FLAT_THREADS, lds, st>>>(P);
@@ -407,7 +431,7 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
         }
         P.shared_tbin = g_flat_tbin[device].as<int32_t>();
     }
-    const size_t lds = 16 * (size_t)(d * 2 + 16) + 16 * FLAT_BINS * 2 + 256;
+    const size_t lds = flat_lds_bytes(d);
     const int grid = R * nslab;
     switch (d) {
         case 64: rc = launch_flat_d<64>(P, grid, lds, half, st); break;
