@@ -266,31 +266,6 @@ __global__ void __launch_bounds__(256) lut_swizzle_kernel(const uint8_t* __restr
 // HBM is contiguous), bias and, for inspection, plain copies.  One workgroup per pair, one wave per
 // sub-quantiser at a time, lane = codewords lane, lane + 64, lane + 128, lane + 192.
 template <int DSUB>
-__device__ __forceinline__ float l2_entry(const float* __restrict__ qv, const float* __restrict__ cv, const float* __restrict__ cb,
-                                          int dsub) {
-    double acc = 0.0;
-    if constexpr (DSUB == 8) {
-        const float4 q0 = *reinterpret_cast<const float4*>(qv), q1 = *reinterpret_cast<const float4*>(qv + 4);
-        const float4 c0 = *reinterpret_cast<const float4*>(cv), c1 = *reinterpret_cast<const float4*>(cv + 4);
-        const float4 b0 = *reinterpret_cast<const float4*>(cb), b1 = *reinterpret_cast<const float4*>(cb + 4);
-        const float qa[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-        const float ca[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-        const float ba[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const double diff = (double)qa[t] - ((double)ca[t] + (double)ba[t]);
-            acc = acc + diff * diff;
-        }
-    } else {
-        for (int t = 0; t < dsub; ++t) {
-            const double diff = (double)qv[t] - ((double)cv[t] + (double)cb[t]);
-            acc = acc + diff * diff;
-        }
-    }
-    return (float)(-acc);
-}
-
-template <int DSUB>
 __global__ void __launch_bounds__(256) lut_l2_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                            const float* __restrict__ CB, const int32_t* __restrict__ probes,
                                                            int nprobe, int d, int m, float* __restrict__ lo_out,
@@ -444,16 +419,28 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
     float* lo = ws.pair_lo.as<float>();
     fill_u32_kernel<<<(unsigned)std::min<int64_t>(1024, (nq + 255) / 256), 256, 0, st>>>(range_bits, 0u, nq);
     fill_u32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<uint32_t*>(ws.counters.as<int64_t>() + 4), 0u, 4);   // counters [4], [5]
-    if (d / m == 8 && d % 4 == 0) {
-        lut_l2_range_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
-        lut_l2_quant_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
-                                                                ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
-                                                                out_L_f32, out_LUT8);
-    } else {
-        lut_l2_range_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
-        lut_l2_quant_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
-                                                                ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
-                                                                out_L_f32, out_LUT8);
+    // The fp32 path with exact fix-ups produces the tables, bias and step; the plain fp32 tables (an inspection
+    // output) and sub-vector lengths without a fast path come from the kernels that evaluate every entry in fp64.
+    const bool fast = lut_l2_fast_supported(idx);
+    if (!fast || out_L_f32) {
+        if (d / m == 8 && d % 4 == 0) {
+            lut_l2_range_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
+            lut_l2_quant_kernel<8><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
+                                                                    ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                                                                    out_L_f32, fast ? nullptr : out_LUT8);
+        } else {
+            lut_l2_range_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits);
+            lut_l2_quant_kernel<0><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nprobe, d, m, lo, range_bits,
+                                                                    ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), ws.delta.as<float>(),
+                                                                    out_L_f32, fast ? nullptr : out_LUT8);
+        }
+    }
+    if (fast) {
+        if (out_L_f32) {           // start the fast path from scratch, so that it is what the caller's tables come from
+            fill_u32_kernel<<<(unsigned)std::min<int64_t>(1024, (nq + 255) / 256), 256, 0, st>>>(range_bits, 0u, nq);
+            fill_u32_kernel<<<(unsigned)std::min<int64_t>(4096, (npairs * m + 255) / 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(lo), 0x7fc00000u, npairs * m);
+        }
+        if ((rc = launch_lut_l2_fast(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st))) return rc;
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;

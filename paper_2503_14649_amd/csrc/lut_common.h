@@ -27,6 +27,33 @@ __device__ __forceinline__ uint8_t lut_entry(double Tv, double t, float lo, floa
     return (uint8_t)r;
 }
 
+// Euclidean metric: table entry -|q_j - (c_j + codeword)|^2 accumulated in fp64 in index order, one rounding to fp32
+// (the expression and order that define the entry).  DSUB = 0: any length (`dsub`).
+template <int DSUB>
+__device__ __forceinline__ float l2_entry(const float* __restrict__ qv, const float* __restrict__ cv, const float* __restrict__ cb,
+                                          int dsub) {
+    double acc = 0.0;
+    if constexpr (DSUB == 8) {
+        const float4 q0 = *reinterpret_cast<const float4*>(qv), q1 = *reinterpret_cast<const float4*>(qv + 4);
+        const float4 c0 = *reinterpret_cast<const float4*>(cv), c1 = *reinterpret_cast<const float4*>(cv + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(cb), b1 = *reinterpret_cast<const float4*>(cb + 4);
+        const float qa[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        const float ca[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float ba[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const double diff = (double)qa[t] - ((double)ca[t] + (double)ba[t]);
+            acc = acc + diff * diff;
+        }
+    } else {
+        for (int t = 0; t < dsub; ++t) {
+            const double diff = (double)qv[t] - ((double)cv[t] + (double)cb[t]);
+            acc = acc + diff * diff;
+        }
+    }
+    return (float)(-acc);
+}
+
 // Everything a consumer needs to obtain the table of one (query, list) pair.
 struct LutTables {
     const uint8_t* lut_base;    // [nq][plane][256][32] base tables

@@ -236,6 +236,11 @@ L2_CASES = {
     "l2_m16_ties_empty": (3000, 32, 16, 8, 7, 4, 25, dict(empty_lists=(3,), dup_codes=60, shuffle_ids=True)),
     "l2_m64": (9000, 128, 64, 16, 9, 3, 128, dict(dup_codes=10)),
     "l2_m128_dsub5": (6000, 640, 128, 10, 4, 7, 10, dict()),
+    "l2_m32_dsub16": (6000, 512, 32, 10, 5, 5, 50, dict()),
+    "l2_m128_d2048": (3000, 2048, 128, 6, 3, 3, 20, dict()),
+    # codewords far smaller than centroids: the tables are flat relative to their magnitude, fp32 decides no entry,
+    # and the library must evaluate all of them by the fp64 definition
+    "l2_m16_dsub4_flat": (4000, 64, 16, 6, 5, 4, 20, dict(cb_scale=3e-6)),
 }
 
 
@@ -268,6 +273,17 @@ def test_l2_stages_equal_oracle(l2case, rb):
     assert np.array_equal(gL.cpu().numpy(), L)              # same fp64 expression, same order: bit-identical
     assert np.array_equal(gd.cpu().numpy(), delta)
     assert np.array_equal(gL8.cpu().numpy(), LUT8) and np.array_equal(gB.cpu().numpy(), B)
+    # the same call without the fp32-table output (the configuration a search runs in)
+    _, gL8b, gBb, gdb = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda(), want_f32=False)
+    assert np.array_equal(gL8b.cpu().numpy(), LUT8) and np.array_equal(gBb.cpu().numpy(), B) and np.array_equal(gdb.cpu().numpy(), delta)
+    d, m = Q.shape[1], ix["codes"].shape[1]
+    if d // m in (4, 8, 16):        # fp32 evaluation with exact re-evaluation of what it cannot decide
+        cnt = rb.rago_debug_counters(h)
+        entries = 2 * len(Q) * nprobe * m * 256                                 # both passes
+        if np.abs(ix["codebooks"]).max() < 1e-4:
+            assert cnt[5] > 0 and cnt[4] == entries                             # every workgroup fell back, both passes
+        else:
+            assert cnt[5] == 0 and 0 < cnt[4] < 0.05 * entries
 
 
 def test_l2_search_end_to_end(l2case, rb, scan_kernel):
