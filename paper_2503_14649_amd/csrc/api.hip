@@ -29,7 +29,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r};
     for (DevBuf* b : all) b->release();
 }
 
@@ -47,7 +47,7 @@ struct DeviceGuard {
 
 static void destroy(rago_index* idx) {
     if (!idx) return;
-    hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cn2); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->cb_absmax); hipFree(idx->list_off);
+    hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cn2); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->cb_absmax); hipFree(idx->cbx); hipFree(idx->list_off);
     hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
     hipFree(idx->sup_cen); hipFree(idx->sup_off); hipFree(idx->sup_lists); hipFree(idx->sup_of);
     idx->ws.release();
@@ -94,6 +94,7 @@ static int prepare(rago_index* idx, int d, int m, int ksub, int nlist, int64_t n
         hipMalloc(&idx->cen_lo, sizeof(uint16_t) * (size_t)nlist * d) != hipSuccess ||
         hipMalloc(&idx->codebooks, sizeof(float) * (size_t)m * KSUB * idx->dsub) != hipSuccess ||
         hipMalloc(&idx->cb_absmax, sizeof(float) * (size_t)d) != hipSuccess ||
+        hipMalloc(&idx->cbx, sizeof(float) * (size_t)m * KSUB * (idx->dsub + 4)) != hipSuccess ||
         hipMalloc(&idx->list_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
         hipMalloc(&idx->blk_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
         hipMalloc(&idx->codes_blk, code_bytes + 16) != hipSuccess ||
@@ -126,7 +127,7 @@ static int finish(rago_index* idx, const uint8_t* d_codes_plain) {
     int rc = build_layout(idx, d_codes_plain, nullptr);
     if (rc) return rc;
     if ((rc = launch_split_centroids(idx, nullptr))) return rc;
-    if ((rc = launch_cb_absmax(idx, nullptr))) return rc;
+    if ((rc = launch_cb_stats(idx, nullptr))) return rc;
     std::vector<float> cn(idx->nlist);
     RAGO_HIP(hipMemcpy(cn.data(), idx->cnorm, sizeof(float) * cn.size(), hipMemcpyDeviceToHost));
     float mx = 0.f;

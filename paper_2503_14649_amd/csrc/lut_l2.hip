@@ -7,7 +7,9 @@
 // Here both passes evaluate in fp32 with a proven error bound and go back to the fp64 definition
 // only for the entries whose outcome the bound cannot decide:
 //
-//   fp32 evaluation  r_t = fl(q_t - c_t), e_t = fl(r_t - cb_t), acc = fma(e_t, e_t, acc):
+//   fp32 evaluation  r_t = fl(q_t - c_t), L~ = fl(fma(2, dot, -rr) - cc) with dot = <r, cb> and
+//   rr = |r|^2 by fma chains and cc = fl(|cb|^2): the chains err by at most dsub u times the sum of
+//   the absolute terms, the two last roundings and cc by u each, the rounding of r_t by 2 u:
 //   |L~ - L64| <= (dsub + 4) u M,  M = sum_t (|q_t| + |c_t| + max_c |cb_t|)^2,  u = 2^-24;
 //   E = 2 (dsub + 6) u M is used (twice the bound, which also covers the rounding of E itself).
 //
@@ -25,7 +27,10 @@
 //
 // A workgroup handles P consecutive pairs so that one load of a codeword serves P tables (the
 // codebooks are the same for every pair; one pair per workgroup re-reads m*256*dsub*4 bytes from
-// L2 per pair and pass).  Pass 1: wave = sub-quantiser, lane = codewords lane + 64 i (min/max are
+// L2 per pair and pass).  What is the same for all lanes (r_j, |r_j|^2, E, the minimum) is written
+// per pair by a small kernel first and read with uniform addresses, so it arrives in scalar
+// registers and costs neither LDS reads nor vector instructions; wave reductions use DPP moves.
+// Pass 1: wave = sub-quantiser, lane = codewords lane + 64 i (min/max are
 // lane-local over i, then one wave reduction).  Pass 2: wave = (plane, 64 codewords), lane =
 // codeword, loop over the 32 slots of the plane, the 32 code bytes of (codeword, plane) packed in
 // registers and written with two 16-byte stores per lane: the plane-major table
@@ -39,6 +44,7 @@ namespace {
 
 constexpr int L2F_THREADS = 256;
 constexpr int L2F_LIST = 4096;          // list entries (4 bytes each) per workgroup
+constexpr float L2F_U = 5.9604644775390625e-08f;   // 2^-24
 
 __device__ __forceinline__ uint32_t okey(float f) {            // order-preserving map float -> uint32
     const uint32_t u = __float_as_uint(f);
@@ -48,93 +54,133 @@ __device__ __forceinline__ float okey_inv(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// One entry of the packed codebook: DSUB coordinates, then the squared norm (and three unused floats, so that an
+// entry is a whole number of 16-byte loads from one address).
 template <int DSUB>
-__device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&v)[DSUB]) {
+__device__ __forceinline__ void load_codeword(const float* __restrict__ cbx, uint32_t entry, float (&v)[DSUB], float& cc) {
     static_assert(DSUB % 4 == 0, "16-byte loads");
+    const float4* p = reinterpret_cast<const float4*>(cbx + entry * (uint32_t)(DSUB + 4));
 #pragma unroll
     for (int t = 0; t < DSUB; t += 4) {
-        const float4 x = *reinterpret_cast<const float4*>(p + t);
+        const float4 x = p[t / 4];
         v[t] = x.x; v[t + 1] = x.y; v[t + 2] = x.z; v[t + 3] = x.w;
     }
+    cc = p[DSUB / 4].x;
 }
 
+// -|r - cb|^2 = 2 <r, cb> - |r|^2 - |cb|^2 with the two norms precomputed: dsub + 2 operations.  `r` and `rr`
+// are the same for all lanes (they sit in scalar registers).
 template <int DSUB>
-__device__ __forceinline__ float l2_approx(const float* __restrict__ r, const float (&cb)[DSUB]) {
-    float acc = 0.0f;
+__device__ __forceinline__ float l2_approx(const float* __restrict__ r, float rr, const float (&cb)[DSUB], float cc) {
+    float dot = 0.0f;
 #pragma unroll
-    for (int t = 0; t < DSUB; ++t) {
-        const float e = r[t] - cb[t];
-        acc = __fmaf_rn(e, e, acc);
-    }
-    return -acc;
+    for (int t = 0; t < DSUB; ++t) dot = __fmaf_rn(r[t], cb[t], dot);
+    return __fmaf_rn(2.0f, dot, -rr) - cc;
 }
 
-// r[p][t] = fl(q_t - c_t), E[p][j] for the workgroup's pairs.
+// Cross-lane moves inside the vector ALU (no LDS traffic): value of another lane of the same row of 16,
+// or of the last lane of the previous row(s); lanes the pattern does not reach keep their own value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_mov(float v) {
+    const int x = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, ROW_MASK, 0xF, false));
+}
+// Minimum and maximum over the 64 lanes, returned in every lane.
+__device__ __forceinline__ void wave_min_max(float& mn, float& mx) {
+    mn = fminf(mn, dpp_mov<0xB1, 0xF>(mn));  mx = fmaxf(mx, dpp_mov<0xB1, 0xF>(mx));     // lane ^ 1
+    mn = fminf(mn, dpp_mov<0x4E, 0xF>(mn));  mx = fmaxf(mx, dpp_mov<0x4E, 0xF>(mx));     // lane ^ 2
+    mn = fminf(mn, dpp_mov<0x141, 0xF>(mn)); mx = fmaxf(mx, dpp_mov<0x141, 0xF>(mx));    // mirror inside each 8
+    mn = fminf(mn, dpp_mov<0x140, 0xF>(mn)); mx = fmaxf(mx, dpp_mov<0x140, 0xF>(mx));    // mirror inside each 16: rows done
+    mn = fminf(mn, dpp_mov<0x142, 0xA>(mn)); mx = fmaxf(mx, dpp_mov<0x142, 0xA>(mx));    // rows 1, 3 <- last lane of rows 0, 2
+    mn = fminf(mn, dpp_mov<0x143, 0xC>(mn)); mx = fmaxf(mx, dpp_mov<0x143, 0xC>(mx));    // rows 2, 3 <- lane 31: lane 63 holds all
+    mn = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mn), 63));
+    mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
+}
+
+// Per (pair, sub-quantiser) one record of DSUB + 4 floats: r[t] = fl(q_t - c_t), |r|^2 (fp32), the bound E,
+// and (filled in after pass 1) the sub-table's exact minimum.  Both passes read records with addresses that
+// are the same in all lanes.
 template <int DSUB>
-__device__ __forceinline__ void prepare_pairs(const float* __restrict__ Q, const float* __restrict__ C, const float* __restrict__ cbmax,
-                                              const int32_t* __restrict__ probes, int64_t pair0, int np, int nprobe, int d, int m,
-                                              float* __restrict__ r, float* __restrict__ E, float* __restrict__ Mj) {
-    for (int idx = threadIdx.x; idx < np * d; idx += L2F_THREADS) {
-        const int p = idx / d, t = idx - p * d;
-        const int64_t q = (pair0 + p) / nprobe;
-        const int l = probes[pair0 + p];
-        r[p * d + t] = Q[q * d + t] - C[(int64_t)l * d + t];
-    }
-    for (int idx = threadIdx.x; idx < np * m; idx += L2F_THREADS) {
-        const int p = idx / m, j = idx - p * m;
-        const int64_t q = (pair0 + p) / nprobe;
-        const int l = probes[pair0 + p];
-        float M = 0.0f;
+__global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                          const float* __restrict__ cbmax, const int32_t* __restrict__ probes,
+                                                          int nprobe, int d, int m, float* __restrict__ rec) {
+    constexpr int RS = DSUB + 4;
+    const int64_t pair = blockIdx.x;
+    const int64_t q = pair / nprobe;
+    const int l = probes[pair];
+    const float* qv = Q + q * d;
+    const float* cv = C + (int64_t)l * d;
+    for (int j = threadIdx.x; j < m; j += 256) {
+        float* e = rec + (pair * m + j) * RS;
+        float rr = 0.0f, M = 0.0f;
+#pragma unroll
         for (int t = 0; t < DSUB; ++t) {
             const int x = j * DSUB + t;
-            const float a = fabsf(Q[q * d + x]) + fabsf(C[(int64_t)l * d + x]) + cbmax[x];
+            const float r = qv[x] - cv[x];
+            e[t] = r;
+            rr = __fmaf_rn(r, r, rr);
+            const float a = fabsf(qv[x]) + fabsf(cv[x]) + cbmax[x];
             M = __fmaf_rn(a, a, M);
         }
-        Mj[p * m + j] = M;
-        E[p * m + j] = 2.0f * (float)(DSUB + 6) * 5.9604644775390625e-08f * M;
+        e[DSUB] = rr;
+        e[DSUB + 1] = 2.0f * (float)(DSUB + 6) * L2F_U * M;
+        e[DSUB + 2] = 0.0f;
+        e[DSUB + 3] = 0.0f;
     }
+}
+
+// Between the passes: the exact minimum and, now that the query's step dq is known, the half-width eta of the zone
+// around a half-integer inside which pass 2 does not trust b~: (E + u M) / dq + 2^-13 with M = E / (2 (dsub + 6) u).
+template <int DSUB>
+__global__ void __launch_bounds__(256) l2f_store_lo_kernel(const float* __restrict__ lo, const uint32_t* __restrict__ range_bits,
+                                                           int64_t n, int m, int nprobe, float* __restrict__ rec) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float* e = rec + i * (DSUB + 4);
+    const float inv = 1.0f / lut_step(__uint_as_float(range_bits[i / m / nprobe]));
+    e[DSUB + 2] = lo[i];
+    e[DSUB + 3] = __fmaf_rn(e[DSUB + 1], (1.0f + 1.0f / (2.0f * (float)(DSUB + 6))) * inv * 1.001f, 1.220703125e-4f);
 }
 
 // ---- pass 1
 template <int DSUB, int P>
 __global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
-                                                                const float* __restrict__ CB, const float* __restrict__ cbmax,
+                                                                const float* __restrict__ CB, const float* __restrict__ cbx,
+                                                                const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
                                                                 int m, float* __restrict__ lo_out, uint32_t* __restrict__ range_bits,
                                                                 int64_t* __restrict__ counters) {
     extern __shared__ __align__(16) uint8_t smem[];
-    float* r = reinterpret_cast<float*>(smem);                       // [P][d]
-    float* E = r + P * d;                                            // [P][m]
-    float* Mj = E + P * m;                                           // [P][m]
-    uint32_t* lo_key = reinterpret_cast<uint32_t*>(Mj + P * m);      // [P][m]
+    uint32_t* lo_key = reinterpret_cast<uint32_t*>(smem);            // [P][m]
     uint32_t* hi_key = lo_key + P * m;                               // [P][m]
     uint32_t* list = hi_key + P * m;                                 // [L2F_LIST]  p << 16 | j << 8 | c
     __shared__ int nlist;
     __shared__ float s_rng[P];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
-    prepare_pairs<DSUB>(Q, C, cbmax, probes, pair0, np, nprobe, d, m, r, E, Mj);
     for (int idx = threadIdx.x; idx < P * m; idx += L2F_THREADS) { lo_key[idx] = 0xFFFFFFFFu; hi_key[idx] = 0u; }
     if (threadIdx.x == 0) nlist = 0;
     if (threadIdx.x < P) s_rng[threadIdx.x] = 0.0f;
     __syncthreads();
+    constexpr int RS = DSUB + 4;
+    const float* rec0 = rec + pair0 * m * RS;
 
     for (int j = wave; j < m; j += 4) {
-        float cb[4][DSUB];
+        float cb[4][DSUB], cc[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_vec<DSUB>(CB + ((int64_t)j * KSUB + lane + 64 * i) * DSUB, cb[i]);
+        for (int i = 0; i < 4; ++i) load_codeword<DSUB>(cbx, (uint32_t)(j * KSUB + lane + 64 * i), cb[i], cc[i]);
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             if (p < np) {
-                const float* rp = r + p * d + j * DSUB;
+                const float* e = rec0 + (uint32_t)((p * m + j) * RS);       // same address in all lanes: scalar loads
                 float v[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = l2_approx<DSUB>(rp, cb[i]);
+                for (int i = 0; i < 4; ++i) v[i] = l2_approx<DSUB>(e, e[DSUB], cb[i], cc[i]);
                 float mn = fminf(fminf(v[0], v[1]), fminf(v[2], v[3]));
                 float mx = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-                for (int o = 32; o; o >>= 1) { mn = fminf(mn, __shfl_xor(mn, o)); mx = fmaxf(mx, __shfl_xor(mx, o)); }
-                const float marg = 2.0f * E[p * m + j];
+                wave_min_max(mn, mx);
+                const float marg = 2.0f * e[DSUB + 1];
                 const float lo_cut = mn + marg, hi_cut = mx - marg;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -180,99 +226,121 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __r
 }
 
 // ---- pass 2
-template <int DSUB, int P>
+// One (plane, 64 codewords) unit of a workgroup's pairs: 32 code bytes per (lane, pair) in registers, two 16-byte
+// stores per lane and pair.  FULL: all P pairs exist (no guards in the loop).
+template <int DSUB, int P, bool FULL, bool DBG>
+__device__ __forceinline__ void l2f_quant_unit(const float* __restrict__ cbx, const float* __restrict__ rec0,
+                                               int np, int m, int S, int plane, int c, const float (&inv)[P],
+                                               uint8_t* __restrict__ tab0, uint8_t* __restrict__ dbg0, uint32_t* __restrict__ list,
+                                               int* __restrict__ nlist) {
+    constexpr int RS = DSUB + 4;
+    // pk[p][0..7]: the 32 code bytes of (codeword c, this plane) for pair p.  The words are produced in
+    // order and shifted in at the top, so that no register is indexed by a loop variable.
+    uint32_t pk[P][8];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int w = 0; w < 8; ++w) pk[p][w] = 0u;
+    // Steps (sub-quantiser j, pair p) run j-major; the codeword of sub-quantiser j + 1 is requested while the P
+    // steps of j run (past the end of the plane: its last sub-quantiser again).  The records come from the copy in
+    // LDS (the same address in all lanes: a broadcast read).
+    const int jfirst = plane * 32, jlast = plane * 32 + S - 1;
+    float cbc[DSUB], ccc;
+    load_codeword<DSUB>(cbx, (uint32_t)(jfirst * KSUB + c), cbc, ccc);
+#pragma unroll 1
+    for (int w = 0; w < S / 4; ++w) {
+        uint32_t word[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) word[p] = 0u;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int j = jfirst + w * 4 + s4, jn = min(j + 1, jlast);
+            float cbn[DSUB], ccn;
+            load_codeword<DSUB>(cbx, (uint32_t)(jn * KSUB + c), cbn, ccn);
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                if (FULL || p < np) {
+                    const float* e = rec0 + (p * m + j) * RS;
+                    float r[DSUB];
+#pragma unroll
+                    for (int t = 0; t < DSUB; t += 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(e + t);
+                        r[t] = x.x; r[t + 1] = x.y; r[t + 2] = x.z; r[t + 3] = x.w;
+                    }
+                    const float4 a = *reinterpret_cast<const float4*>(e + DSUB);     // |r|^2, E, minimum, eta
+                    const float Lt = l2_approx<DSUB>(r, a.x, cbc, ccc);
+                    const float b = (Lt - a.z) * inv[p];
+                    const float rr = fminf(fmaxf(rintf(b), 0.0f), 255.0f);
+                    word[p] |= (uint32_t)rr << (8 * s4);
+                    // undecided (about one entry in a thousand): on the list
+                    if (fabsf(__builtin_amdgcn_fractf(b) - 0.5f) <= a.w) {
+                        const int pos = atomicAdd(nlist, 1);
+                        if (pos < L2F_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | c);
+                    }
+                    if (DBG) dbg0[((int64_t)p * m + j) * KSUB + c] = (uint8_t)rr;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < DSUB; ++t) cbc[t] = cbn[t];
+            ccc = ccn;
+        }
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+#pragma unroll
+            for (int x = 0; x < 7; ++x) pk[p][x] = pk[p][x + 1];
+            pk[p][7] = word[p];
+        }
+    }
+    if (S == 16) {                  // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) pk[p][x] = pk[p][x + 4];
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        if (FULL || p < np) {
+            uint4* dst = reinterpret_cast<uint4*>(tab0 + (int64_t)p * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
+            dst[0] = make_uint4(pk[p][0], pk[p][1], pk[p][2], pk[p][3]);
+            dst[1] = make_uint4(pk[p][4], pk[p][5], pk[p][6], pk[p][7]);
+        }
+    }
+}
+
+template <int DSUB, int P, bool DBG>
 __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
-                                                                const float* __restrict__ CB, const float* __restrict__ cbmax,
+                                                                const float* __restrict__ CB, const float* __restrict__ cbx,
+                                                                const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
                                                                 int m, const float* __restrict__ lo_in, const uint32_t* __restrict__ range_bits,
                                                                 uint8_t* __restrict__ tables, int32_t* __restrict__ bias,
                                                                 float* __restrict__ delta, uint8_t* __restrict__ out_LUT8,
                                                                 int64_t* __restrict__ counters) {
     extern __shared__ __align__(16) uint8_t smem[];
-    float* r = reinterpret_cast<float*>(smem);                       // [P][d]
-    float* E = r + P * d;                                            // [P][m]   here: eta, the undecided zone of b~
-    float* Mj = E + P * m;                                           // [P][m]
-    float* lo = Mj + P * m;                                          // [P][m]
-    uint32_t* list = reinterpret_cast<uint32_t*>(lo + P * m);        // [L2F_LIST]
+    uint32_t* list = reinterpret_cast<uint32_t*>(smem);                        // [L2F_LIST]
+    float* rec_s = reinterpret_cast<float*>(smem + L2F_LIST * 4);              // [P][m][DSUB + 4] this workgroup's records
     __shared__ int nlist;
-    __shared__ float s_dq[P], s_inv[P];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
     const int S = rago_steps(m), planes = rago_planes(m);
-    prepare_pairs<DSUB>(Q, C, cbmax, probes, pair0, np, nprobe, d, m, r, E, Mj);
     if (threadIdx.x == 0) nlist = 0;
-    if (threadIdx.x < np) {
-        const float dq = lut_step(__uint_as_float(range_bits[(pair0 + threadIdx.x) / nprobe]));
-        s_dq[threadIdx.x] = dq;
-        s_inv[threadIdx.x] = 1.0f / dq;
+    {
+        const float4* src = reinterpret_cast<const float4*>(rec + pair0 * m * (DSUB + 4));
+        float4* dst = reinterpret_cast<float4*>(rec_s);
+        for (int i = threadIdx.x; i < np * m * (DSUB + 4) / 4; i += L2F_THREADS) dst[i] = src[i];
     }
+    float inv[P];                          // per pair: the reciprocal of the query's step
+#pragma unroll
+    for (int p = 0; p < P; ++p) inv[p] = 1.0f / lut_step(__uint_as_float(range_bits[(pair0 + min(p, np - 1)) / nprobe]));
     __syncthreads();
-    for (int idx = threadIdx.x; idx < np * m; idx += L2F_THREADS) {
-        const int p = idx / m;
-        lo[idx] = lo_in[(pair0 + p) * m + (idx - p * m)];
-        E[idx] = (E[idx] + 5.9604644775390625e-08f * Mj[idx]) * s_inv[p] * 1.001f + 1.220703125e-4f;
-    }
-    __syncthreads();
-
+    const float* rec0 = rec_s;
+    uint8_t* tab0 = tables + pair0 * LUT_BYTES;
+    uint8_t* dbg0 = DBG ? out_LUT8 + pair0 * m * KSUB : nullptr;
     for (int u = wave; u < planes * 4; u += 4) {
         const int plane = u >> 2, c = (u & 3) * 64 + lane;
-        // pk[p][0..7]: the 32 code bytes of (codeword c, this plane) for pair p.  The words are produced in
-        // order and shifted in at the top, so that no register is indexed by a loop variable.
-        uint32_t pk[P][8];
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int w = 0; w < 8; ++w) pk[p][w] = 0u;
-#pragma unroll 1
-        for (int w = 0; w < S / 4; ++w) {
-            uint32_t word[P];
-#pragma unroll
-            for (int p = 0; p < P; ++p) word[p] = 0u;
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-                const int j = plane * 32 + w * 4 + s4;
-                float cb[DSUB];
-                load_vec<DSUB>(CB + ((int64_t)j * KSUB + c) * DSUB, cb);
-#pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    if (p < np) {
-                        const float Lt = l2_approx<DSUB>(r + p * d + j * DSUB, cb);
-                        const float b = (Lt - lo[p * m + j]) * s_inv[p];
-                        float rr = rintf(b);
-                        rr = rr < 0.0f ? 0.0f : (rr > 255.0f ? 255.0f : rr);
-                        const uint32_t v = (uint32_t)rr;
-                        const float fr = b - floorf(b);
-                        if (fabsf(fr - 0.5f) <= E[p * m + j]) {
-                            const int pos = atomicAdd(&nlist, 1);
-                            if (pos < L2F_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | c);
-                        }
-                        word[p] |= v << (8 * s4);
-                        if (out_LUT8) out_LUT8[((pair0 + p) * m + j) * KSUB + c] = (uint8_t)v;
-                    }
-                }
-            }
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-#pragma unroll
-                for (int x = 0; x < 7; ++x) pk[p][x] = pk[p][x + 1];
-                pk[p][7] = word[p];
-            }
-        }
-        if (S == 16) {                  // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) pk[p][x] = pk[p][x + 4];
-        }
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            if (p < np) {
-                uint4* dst = reinterpret_cast<uint4*>(tables + (pair0 + p) * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
-                dst[0] = make_uint4(pk[p][0], pk[p][1], pk[p][2], pk[p][3]);
-                dst[1] = make_uint4(pk[p][4], pk[p][5], pk[p][6], pk[p][7]);
-            }
-        }
+        if (np == P) l2f_quant_unit<DSUB, P, true, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
+        else l2f_quant_unit<DSUB, P, false, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
     }
     __threadfence();
     __syncthreads();                                 // the packed stores are complete before single bytes are corrected
@@ -285,19 +353,21 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
         const int64_t q = (pair0 + p) / nprobe;
         const int l = probes[pair0 + p];
         const float L = l2_entry<DSUB>(Q + q * d + j * DSUB, C + (int64_t)l * d + j * DSUB, CB + ((int64_t)j * KSUB + c) * DSUB, DSUB);
-        float rr = rintf(__fdiv_rn(L - lo[p * m + j], s_dq[p]));
+        const float step = lut_step(__uint_as_float(range_bits[q]));
+        float rr = rintf(__fdiv_rn(L - lo_in[(pair0 + p) * m + j], step));
         rr = rr < 0.0f ? 0.0f : (rr > 255.0f ? 255.0f : rr);
         const uint8_t v = (uint8_t)rr;
         uint8_t* tab = tables + (pair0 + p) * LUT_BYTES + (int64_t)(j >> 5) * LUT_PLANE + c * 32;
         for (int rep = j & (S - 1); rep < 32; rep += S) tab[rep] = v;
-        if (out_LUT8) out_LUT8[((pair0 + p) * m + j) * KSUB + c] = v;
+        if (DBG) out_LUT8[((pair0 + p) * m + j) * KSUB + c] = v;
     }
     if (threadIdx.x < np) {
         const int p = threadIdx.x;
+        const float step = lut_step(__uint_as_float(range_bits[(pair0 + p) / nprobe]));
         double losum = 0.0;
-        for (int j = 0; j < m; ++j) losum = losum + (double)lo[p * m + j];
-        bias[pair0 + p] = (int32_t)rint(losum / (double)s_dq[p]);
-        if ((pair0 + p) % nprobe == 0) delta[(pair0 + p) / nprobe] = s_dq[p];
+        for (int j = 0; j < m; ++j) losum = losum + (double)lo_in[(pair0 + p) * m + j];
+        bias[pair0 + p] = (int32_t)rint(losum / (double)step);
+        if ((pair0 + p) % nprobe == 0) delta[(pair0 + p) / nprobe] = step;
     }
     if (threadIdx.x == 0) {
         atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)total);
@@ -305,14 +375,24 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
     }
 }
 
-// max over codewords of |CB[j][c][t]| for every dimension (j, t)
-__global__ void __launch_bounds__(256) cb_absmax_kernel(const float* __restrict__ CB, int d, int dsub, float* __restrict__ out) {
+// Per dimension the largest |codeword coordinate|; the packed codebook [m][256][dsub + 4]: coordinates, squared
+// norm (fp64 sum, one rounding), three zeros.
+__global__ void __launch_bounds__(256) cb_stats_kernel(const float* __restrict__ CB, int d, int m, int dsub, float* __restrict__ absmax,
+                                                       float* __restrict__ cbx) {
     const int x = blockIdx.x * 256 + threadIdx.x;
-    if (x >= d) return;
-    const int j = x / dsub, t = x - j * dsub;
-    float mx = 0.0f;
-    for (int c = 0; c < KSUB; ++c) mx = fmaxf(mx, fabsf(CB[((int64_t)j * KSUB + c) * dsub + t]));
-    out[x] = mx;
+    if (x < d) {
+        const int j = x / dsub, t = x - j * dsub;
+        float mx = 0.0f;
+        for (int c = 0; c < KSUB; ++c) mx = fmaxf(mx, fabsf(CB[((int64_t)j * KSUB + c) * dsub + t]));
+        absmax[x] = mx;
+    }
+    if (x < m * KSUB) {
+        double acc = 0.0;
+        float* o = cbx + (int64_t)x * (dsub + 4);
+        for (int t = 0; t < dsub; ++t) { const float f = CB[(int64_t)x * dsub + t]; o[t] = f; acc = acc + (double)f * (double)f; }
+        o[dsub] = (float)acc;
+        o[dsub + 1] = 0.0f; o[dsub + 2] = 0.0f; o[dsub + 3] = 0.0f;
+    }
 }
 
 template <int DSUB, int P>
@@ -320,49 +400,56 @@ int launch_l2f(rago_index* idx, const float* q, const int32_t* probes, int64_t n
                uint8_t* out_LUT8, hipStream_t st) {
     Workspace& ws = idx->ws;
     const int d = idx->d, m = idx->m;
-    const size_t lds1 = (size_t)P * d * 4 + (size_t)P * m * 16 + (size_t)L2F_LIST * 4;
-    const size_t lds2 = (size_t)P * d * 4 + (size_t)P * m * 12 + (size_t)L2F_LIST * 4;
+    int rc;
+    if ((rc = ws.l2_r.reserve((size_t)npairs * m * (DSUB + 4) * 4))) return rc;
+    float* rec = ws.l2_r.as<float>();
+    const size_t lds1 = (size_t)P * m * 8 + (size_t)L2F_LIST * 4;
+    const size_t lds2 = (size_t)L2F_LIST * 4 + (size_t)P * m * (DSUB + 4) * 4;
     static bool attr_done = false;
     if (!attr_done) {
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_range_kernel<DSUB, P>), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_quant_kernel<DSUB, P>), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_quant_kernel<DSUB, P, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_quant_kernel<DSUB, P, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
         attr_done = true;
     }
     const unsigned grid = (unsigned)((npairs + P - 1) / P);
-    l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cb_absmax, probes, npairs, nprobe, d, m,
-                                                               lo, range_bits, ws.counters.as<int64_t>());
-    l2f_quant_kernel<DSUB, P><<<grid, L2F_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cb_absmax, probes, npairs, nprobe, d, m,
-                                                               lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                               ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
+    l2f_prepare_kernel<DSUB><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, nprobe, d, m, rec);
+    l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
+                                                               d, m, lo, range_bits, ws.counters.as<int64_t>());
+    l2f_store_lo_kernel<DSUB><<<(unsigned)((npairs * m + 255) / 256), 256, 0, st>>>(lo, range_bits, npairs * m, m, nprobe, rec);
+    if (out_LUT8)
+        l2f_quant_kernel<DSUB, P, true><<<grid, L2F_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                      m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                      ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
+    else
+        l2f_quant_kernel<DSUB, P, false><<<grid, L2F_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                       m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                       ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
 
 }  // namespace
 
-int launch_cb_absmax(rago_index* idx, hipStream_t st) {
-    cb_absmax_kernel<<<(idx->d + 255) / 256, 256, 0, st>>>(idx->codebooks, idx->d, idx->dsub, idx->cb_absmax);
+int launch_cb_stats(rago_index* idx, hipStream_t st) {
+    const int n = std::max(idx->d, idx->m * KSUB);
+    cb_stats_kernel<<<(n + 255) / 256, 256, 0, st>>>(idx->codebooks, idx->d, idx->m, idx->dsub, idx->cb_absmax, idx->cbx);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
 
 bool lut_l2_fast_supported(const rago_index* idx) {
     const int dsub = idx->dsub;
-    return (dsub == 4 || dsub == 8 || dsub == 16) && idx->d <= 4096;
+    return dsub == 4 || dsub == 8 || dsub == 16;
 }
 
 // Both passes for all pairs.  `lo` [npairs][m] fp32 and `range_bits` [nq] (zeroed) are workspace; the
 // tables, bias and step land in the workspace members the scan reads.
 int launch_lut_l2_fast(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
                        uint8_t* out_LUT8, hipStream_t st) {
-    const bool wide = idx->d <= 1024;              // eight pairs per workgroup fit the LDS; else two
     switch (idx->dsub) {
-        case 4: return wide ? launch_l2f<4, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st)
-                            : launch_l2f<4, 2>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
-        case 8: return wide ? launch_l2f<8, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st)
-                            : launch_l2f<8, 2>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
-        case 16: return wide ? launch_l2f<16, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st)
-                             : launch_l2f<16, 2>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 4: return launch_l2f<4, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 8: return launch_l2f<8, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 16: return launch_l2f<16, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
     }
     return fail(RAGO_UNSUPPORTED, "sub-vector length without a fast Euclidean table path");
 }

@@ -36,7 +36,7 @@ struct DevBuf {
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched, qn2;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r;
     void release();
 };
 
@@ -71,6 +71,7 @@ struct rago_index {
     uint16_t* cen_lo = nullptr;    // [nlist][d] bf16(centroid - cen_hi): centroid = hi + lo to 2^-18 relative
     float* codebooks = nullptr;    // [m][256][dsub]
     float* cb_absmax = nullptr;    // [d] largest |codeword coordinate| per dimension (error bounds of the fp32 table path)
+    float* cbx = nullptr;          // [m][256][dsub + 4] codeword, its squared norm, three zeros (one address per entry)
     int64_t* list_off = nullptr;   // [nlist+1] vector offsets (list-major rows)
     int64_t* blk_off = nullptr;    // [nlist+1] offsets in 64-vector blocks into codes_blk
     uint8_t* codes_blk = nullptr;  // total_blocks * 64 * m bytes, skewed lane-major layout
@@ -111,7 +112,7 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
 // Euclidean metric: one full table per pair (plane-major, stride LUT_BYTES) into ws.tmp_lut8sw, biases into
 // ws.bias, steps into ws.delta; optional plain copies for inspection.
-int launch_cb_absmax(rago_index* idx, hipStream_t st);
+int launch_cb_stats(rago_index* idx, hipStream_t st);
 bool lut_l2_fast_supported(const rago_index* idx);
 int launch_lut_l2_fast(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
                        uint8_t* out_LUT8, hipStream_t st);
