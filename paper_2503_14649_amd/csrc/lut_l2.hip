@@ -226,37 +226,49 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __r
 }
 
 // ---- pass 2
-// One (plane, 64 codewords) unit of a workgroup's pairs: 32 code bytes per (lane, pair) in registers, two 16-byte
-// stores per lane and pair.  FULL: all P pairs exist (no guards in the loop).
+constexpr int L2Q_THREADS = 128;        // two waves: a plane splits into two units of 128 codewords, two per lane
+constexpr int L2Q_PAIRS = 4;
+constexpr int L2Q_LIST = 2048;
+
+// One (plane, 128 codewords) unit of a workgroup's pairs: lane = codewords c and c + 64; per (lane, pair, codeword)
+// 32 code bytes in registers, written with two 16-byte stores.  One read of a record (LDS, the same address in all
+// lanes) serves two entries per lane.  FULL: all P pairs exist (no guards in the loop).
 template <int DSUB, int P, bool FULL, bool DBG>
 __device__ __forceinline__ void l2f_quant_unit(const float* __restrict__ cbx, const float* __restrict__ rec0,
                                                int np, int m, int S, int plane, int c, const float (&inv)[P],
                                                uint8_t* __restrict__ tab0, uint8_t* __restrict__ dbg0, uint32_t* __restrict__ list,
                                                int* __restrict__ nlist) {
     constexpr int RS = DSUB + 4;
-    // pk[p][0..7]: the 32 code bytes of (codeword c, this plane) for pair p.  The words are produced in
+    // pk[p][i][0..7]: the 32 code bytes of (codeword c + 64 i, this plane) for pair p.  The words are produced in
     // order and shifted in at the top, so that no register is indexed by a loop variable.
-    uint32_t pk[P][8];
+    uint32_t pk[P][2][8];
 #pragma unroll
     for (int p = 0; p < P; ++p)
 #pragma unroll
-        for (int w = 0; w < 8; ++w) pk[p][w] = 0u;
-    // Steps (sub-quantiser j, pair p) run j-major; the codeword of sub-quantiser j + 1 is requested while the P
-    // steps of j run (past the end of the plane: its last sub-quantiser again).  The records come from the copy in
-    // LDS (the same address in all lanes: a broadcast read).
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int w = 0; w < 8; ++w) pk[p][i][w] = 0u;
+    // Steps (sub-quantiser j, pair p) run j-major; the codewords of sub-quantiser j + 2 are requested while the P
+    // steps of j run (past the end of the plane: its last sub-quantiser again): a load from L2 takes longer than
+    // the steps of one sub-quantiser.
     const int jfirst = plane * 32, jlast = plane * 32 + S - 1;
-    float cbc[DSUB], ccc;
-    load_codeword<DSUB>(cbx, (uint32_t)(jfirst * KSUB + c), cbc, ccc);
+    float cbc[2][DSUB], ccc[2], cbm[2][DSUB], ccm[2];          // codewords of sub-quantisers j and j + 1 (j + 2 is on its way)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        load_codeword<DSUB>(cbx, (uint32_t)(jfirst * KSUB + c + 64 * i), cbc[i], ccc[i]);
+        load_codeword<DSUB>(cbx, (uint32_t)(min(jfirst + 1, jlast) * KSUB + c + 64 * i), cbm[i], ccm[i]);
+    }
 #pragma unroll 1
     for (int w = 0; w < S / 4; ++w) {
-        uint32_t word[P];
+        uint32_t word[P][2];
 #pragma unroll
-        for (int p = 0; p < P; ++p) word[p] = 0u;
+        for (int p = 0; p < P; ++p) { word[p][0] = 0u; word[p][1] = 0u; }
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
-            const int j = jfirst + w * 4 + s4, jn = min(j + 1, jlast);
-            float cbn[DSUB], ccn;
-            load_codeword<DSUB>(cbx, (uint32_t)(jn * KSUB + c), cbn, ccn);
+            const int j = jfirst + w * 4 + s4, jn = min(j + 2, jlast);
+            float cbn[2][DSUB], ccn[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) load_codeword<DSUB>(cbx, (uint32_t)(jn * KSUB + c + 64 * i), cbn[i], ccn[i]);
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 if (FULL || p < np) {
@@ -268,47 +280,60 @@ __device__ __forceinline__ void l2f_quant_unit(const float* __restrict__ cbx, co
                         r[t] = x.x; r[t + 1] = x.y; r[t + 2] = x.z; r[t + 3] = x.w;
                     }
                     const float4 a = *reinterpret_cast<const float4*>(e + DSUB);     // |r|^2, E, minimum, eta
-                    const float Lt = l2_approx<DSUB>(r, a.x, cbc, ccc);
-                    const float b = (Lt - a.z) * inv[p];
-                    const float rr = fminf(fmaxf(rintf(b), 0.0f), 255.0f);
-                    word[p] |= (uint32_t)rr << (8 * s4);
-                    // undecided (about one entry in a thousand): on the list
-                    if (fabsf(__builtin_amdgcn_fractf(b) - 0.5f) <= a.w) {
-                        const int pos = atomicAdd(nlist, 1);
-                        if (pos < L2F_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | c);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const float Lt = l2_approx<DSUB>(r, a.x, cbc[i], ccc[i]);
+                        const float b = (Lt - a.z) * inv[p];
+                        const float rr = fminf(fmaxf(rintf(b), 0.0f), 255.0f);
+                        word[p][i] |= (uint32_t)rr << (8 * s4);
+                        // undecided (about one entry in a thousand): on the list
+                        if (fabsf(__builtin_amdgcn_fractf(b) - 0.5f) <= a.w) {
+                            const int pos = atomicAdd(nlist, 1);
+                            if (pos < L2Q_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | (c + 64 * i));
+                        }
+                        if (DBG) dbg0[((int64_t)p * m + j) * KSUB + c + 64 * i] = (uint8_t)rr;
                     }
-                    if (DBG) dbg0[((int64_t)p * m + j) * KSUB + c] = (uint8_t)rr;
                 }
             }
 #pragma unroll
-            for (int t = 0; t < DSUB; ++t) cbc[t] = cbn[t];
-            ccc = ccn;
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int t = 0; t < DSUB; ++t) { cbc[i][t] = cbm[i][t]; cbm[i][t] = cbn[i][t]; }
+                ccc[i] = ccm[i]; ccm[i] = ccn[i];
+            }
         }
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
+        for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int x = 0; x < 7; ++x) pk[p][x] = pk[p][x + 1];
-            pk[p][7] = word[p];
-        }
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int x = 0; x < 7; ++x) pk[p][i][x] = pk[p][i][x + 1];
+                pk[p][i][7] = word[p][i];
+            }
     }
     if (S == 16) {                  // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
 #pragma unroll
         for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int x = 0; x < 4; ++x) pk[p][x] = pk[p][x + 4];
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) pk[p][i][x] = pk[p][i][x + 4];
     }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         if (FULL || p < np) {
-            uint4* dst = reinterpret_cast<uint4*>(tab0 + (int64_t)p * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
-            dst[0] = make_uint4(pk[p][0], pk[p][1], pk[p][2], pk[p][3]);
-            dst[1] = make_uint4(pk[p][4], pk[p][5], pk[p][6], pk[p][7]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint4* dst = reinterpret_cast<uint4*>(tab0 + (int64_t)p * LUT_BYTES + (int64_t)plane * LUT_PLANE + (c + 64 * i) * 32);
+                dst[0] = make_uint4(pk[p][i][0], pk[p][i][1], pk[p][i][2], pk[p][i][3]);
+                dst[1] = make_uint4(pk[p][i][4], pk[p][i][5], pk[p][i][6], pk[p][i][7]);
+            }
         }
     }
 }
 
-template <int DSUB, int P, bool DBG>
-__global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+template <int DSUB, bool DBG>
+__global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
@@ -316,9 +341,10 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
                                                                 uint8_t* __restrict__ tables, int32_t* __restrict__ bias,
                                                                 float* __restrict__ delta, uint8_t* __restrict__ out_LUT8,
                                                                 int64_t* __restrict__ counters) {
+    constexpr int P = L2Q_PAIRS;
     extern __shared__ __align__(16) uint8_t smem[];
-    uint32_t* list = reinterpret_cast<uint32_t*>(smem);                        // [L2F_LIST]
-    float* rec_s = reinterpret_cast<float*>(smem + L2F_LIST * 4);              // [P][m][DSUB + 4] this workgroup's records
+    uint32_t* list = reinterpret_cast<uint32_t*>(smem);                        // [L2Q_LIST]
+    float* rec_s = reinterpret_cast<float*>(smem + L2Q_LIST * 4);              // [P][m][DSUB + 4] this workgroup's records
     __shared__ int nlist;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t pair0 = (int64_t)blockIdx.x * P;
@@ -328,7 +354,7 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
     {
         const float4* src = reinterpret_cast<const float4*>(rec + pair0 * m * (DSUB + 4));
         float4* dst = reinterpret_cast<float4*>(rec_s);
-        for (int i = threadIdx.x; i < np * m * (DSUB + 4) / 4; i += L2F_THREADS) dst[i] = src[i];
+        for (int i = threadIdx.x; i < np * m * (DSUB + 4) / 4; i += L2Q_THREADS) dst[i] = src[i];
     }
     float inv[P];                          // per pair: the reciprocal of the query's step
 #pragma unroll
@@ -337,24 +363,26 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
     const float* rec0 = rec_s;
     uint8_t* tab0 = tables + pair0 * LUT_BYTES;
     uint8_t* dbg0 = DBG ? out_LUT8 + pair0 * m * KSUB : nullptr;
-    for (int u = wave; u < planes * 4; u += 4) {
-        const int plane = u >> 2, c = (u & 3) * 64 + lane;
+    for (int u = wave; u < planes * 2; u += 2) {
+        const int plane = u >> 1, c = (u & 1) * 128 + lane;
         if (np == P) l2f_quant_unit<DSUB, P, true, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
         else l2f_quant_unit<DSUB, P, false, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
     }
-    __threadfence();
-    __syncthreads();                                 // the packed stores are complete before single bytes are corrected
+    // The packed stores are ordered before the single-byte corrections by the barrier's workgroup-scope release:
+    // both come from this workgroup and go through the same L2.  (A device-scope fence here makes every
+    // workgroup write back its XCD's L2 and costs more than the whole computation.)
+    __syncthreads();
     const int n = nlist;
-    const bool all = n > L2F_LIST;
+    const bool all = n > L2Q_LIST;
     const int total = all ? np * m * KSUB : n;
-    for (int e = threadIdx.x; e < total; e += L2F_THREADS) {
+    for (int e = threadIdx.x; e < total; e += L2Q_THREADS) {
         const uint32_t w = all ? (uint32_t)((e / (m * KSUB)) << 16 | ((e / KSUB) % m) << 8 | (e % KSUB)) : list[e];
         const int p = w >> 16, j = (w >> 8) & 255, c = w & 255;
         const int64_t q = (pair0 + p) / nprobe;
         const int l = probes[pair0 + p];
         const float L = l2_entry<DSUB>(Q + q * d + j * DSUB, C + (int64_t)l * d + j * DSUB, CB + ((int64_t)j * KSUB + c) * DSUB, DSUB);
         const float step = lut_step(__uint_as_float(range_bits[q]));
-        float rr = rintf(__fdiv_rn(L - lo_in[(pair0 + p) * m + j], step));
+        float rr = rintf(__fdiv_rn(L - rec_s[(p * m + j) * (DSUB + 4) + DSUB + 2], step));
         rr = rr < 0.0f ? 0.0f : (rr > 255.0f ? 255.0f : rr);
         const uint8_t v = (uint8_t)rr;
         uint8_t* tab = tables + (pair0 + p) * LUT_BYTES + (int64_t)(j >> 5) * LUT_PLANE + c * 32;
@@ -364,8 +392,8 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_quant_kernel(const float* __r
     if (threadIdx.x < np) {
         const int p = threadIdx.x;
         const float step = lut_step(__uint_as_float(range_bits[(pair0 + p) / nprobe]));
-        double losum = 0.0;
-        for (int j = 0; j < m; ++j) losum = losum + (double)lo_in[(pair0 + p) * m + j];
+        double losum = 0.0;                      // in index order (the order that defines the bias), minima from the records in LDS
+        for (int j = 0; j < m; ++j) losum = losum + (double)rec_s[(p * m + j) * (DSUB + 4) + DSUB + 2];
         bias[pair0 + p] = (int32_t)rint(losum / (double)step);
         if ((pair0 + p) % nprobe == 0) delta[(pair0 + p) / nprobe] = step;
     }
@@ -404,26 +432,20 @@ int launch_l2f(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     if ((rc = ws.l2_r.reserve((size_t)npairs * m * (DSUB + 4) * 4))) return rc;
     float* rec = ws.l2_r.as<float>();
     const size_t lds1 = (size_t)P * m * 8 + (size_t)L2F_LIST * 4;
-    const size_t lds2 = (size_t)L2F_LIST * 4 + (size_t)P * m * (DSUB + 4) * 4;
-    static bool attr_done = false;
-    if (!attr_done) {
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_quant_kernel<DSUB, P, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2f_quant_kernel<DSUB, P, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-        attr_done = true;
-    }
-    const unsigned grid = (unsigned)((npairs + P - 1) / P);
+    const size_t lds2 = (size_t)L2Q_LIST * 4 + (size_t)L2Q_PAIRS * m * (DSUB + 4) * 4;     // <= 42 KB
+    const unsigned grid = (unsigned)((npairs + P - 1) / P), grid2 = (unsigned)((npairs + L2Q_PAIRS - 1) / L2Q_PAIRS);
     l2f_prepare_kernel<DSUB><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, nprobe, d, m, rec);
     l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
                                                                d, m, lo, range_bits, ws.counters.as<int64_t>());
     l2f_store_lo_kernel<DSUB><<<(unsigned)((npairs * m + 255) / 256), 256, 0, st>>>(lo, range_bits, npairs * m, m, nprobe, rec);
     if (out_LUT8)
-        l2f_quant_kernel<DSUB, P, true><<<grid, L2F_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
-                                                                      m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                      ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
-    else
-        l2f_quant_kernel<DSUB, P, false><<<grid, L2F_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+        l2f_quant_kernel<DSUB, true><<<grid2, L2Q_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
                                                                        m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                       ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
+                                                                       ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
+    else
+        l2f_quant_kernel<DSUB, false><<<grid2, L2Q_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                        m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                        ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
