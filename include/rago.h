@@ -207,7 +207,8 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
  * (sum over (query, probe) of list length * m), [3] queries whose probe choice was not
  * provably independent of fp32 rounding, [4] table entries whose rounding had to be evaluated per
  * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
- * for every pair, [6..7] reserved. */
+ * for every pair (Euclidean metric: [4] entries re-evaluated in fp64 over both table passes, [5]
+ * workgroups that re-evaluated all their entries, counted once per pass), [6..7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
 /* Plain copy kernel (rago_calib_copy_kernel) of `bytes` bytes, DEVICE src -> DEVICE dst, both

@@ -265,6 +265,8 @@ __global__ void __launch_bounds__(256) lut_swizzle_kernel(const uint8_t* __restr
 // again, quantises them and writes the pair's plane-major table (staged in LDS so that the store to
 // HBM is contiguous), bias and, for inspection, plain copies.  One workgroup per pair, one wave per
 // sub-quantiser at a time, lane = codewords lane, lane + 64, lane + 128, lane + 192.
+// These two kernels evaluate EVERY entry by the fp64 definition.  They serve sub-vector lengths that the
+// fp32 path with exact re-evaluation (lut_l2.hip) does not cover, and the plain fp32 tables of the inspection call.
 template <int DSUB>
 __global__ void __launch_bounds__(256) lut_l2_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                            const float* __restrict__ CB, const int32_t* __restrict__ probes,
