@@ -98,8 +98,7 @@ __device__ __forceinline__ void wave_min_max(float& mn, float& mx) {
 }
 
 // Per (pair, sub-quantiser) one record of DSUB + 4 floats: r[t] = fl(q_t - c_t), |r|^2 (fp32), the bound E,
-// and (filled in after pass 1) the sub-table's exact minimum.  Both passes read records with addresses that
-// are the same in all lanes.
+// and two fields that pass 2 fills in while it copies its records to LDS.
 template <int DSUB>
 __global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                           const float* __restrict__ cbmax, const int32_t* __restrict__ probes,
@@ -127,19 +126,6 @@ __global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restric
         e[DSUB + 2] = 0.0f;
         e[DSUB + 3] = 0.0f;
     }
-}
-
-// Between the passes: the exact minimum and, now that the query's step dq is known, the half-width eta of the zone
-// around a half-integer inside which pass 2 does not trust b~: (E + u M) / dq + 2^-13 with M = E / (2 (dsub + 6) u).
-template <int DSUB>
-__global__ void __launch_bounds__(256) l2f_store_lo_kernel(const float* __restrict__ lo, const uint32_t* __restrict__ range_bits,
-                                                           int64_t n, int m, int nprobe, float* __restrict__ rec) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    float* e = rec + i * (DSUB + 4);
-    const float inv = 1.0f / lut_step(__uint_as_float(range_bits[i / m / nprobe]));
-    e[DSUB + 2] = lo[i];
-    e[DSUB + 3] = __fmaf_rn(e[DSUB + 1], (1.0f + 1.0f / (2.0f * (float)(DSUB + 6))) * inv * 1.001f, 1.220703125e-4f);
 }
 
 // ---- pass 1
@@ -351,14 +337,29 @@ __global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __r
     const int np = (int)min((int64_t)P, npairs - pair0);
     const int S = rago_steps(m), planes = rago_planes(m);
     if (threadIdx.x == 0) nlist = 0;
-    {
-        const float4* src = reinterpret_cast<const float4*>(rec + pair0 * m * (DSUB + 4));
-        float4* dst = reinterpret_cast<float4*>(rec_s);
-        for (int i = threadIdx.x; i < np * m * (DSUB + 4) / 4; i += L2Q_THREADS) dst[i] = src[i];
-    }
     float inv[P];                          // per pair: the reciprocal of the query's step
 #pragma unroll
     for (int p = 0; p < P; ++p) inv[p] = 1.0f / lut_step(__uint_as_float(range_bits[(pair0 + min(p, np - 1)) / nprobe]));
+    {
+        // Records into LDS.  Their last two fields are filled in here: the sub-table's exact minimum (pass 1) and, now
+        // that the query's step dq is known, the half-width eta of the zone around a half-integer inside which b~ is
+        // not trusted: (E + u M) / dq + 2^-13 with M = E / (2 (dsub + 6) u).
+        const float4* src = reinterpret_cast<const float4*>(rec + pair0 * m * (DSUB + 4));
+        float4* dst = reinterpret_cast<float4*>(rec_s);
+        constexpr int Q4 = (DSUB + 4) / 4;                 // 16-byte pieces per record
+        for (int i = threadIdx.x; i < np * m * Q4; i += L2Q_THREADS) {
+            float4 v = src[i];
+            if (i % Q4 == Q4 - 1) {
+                const int pj = i / Q4, p = pj / m;
+                float ip = inv[0];
+#pragma unroll
+                for (int x = 1; x < P; ++x) ip = p == x ? inv[x] : ip;
+                v.z = lo_in[pair0 * m + pj];
+                v.w = __fmaf_rn(v.y, (1.0f + 1.0f / (2.0f * (float)(DSUB + 6))) * ip * 1.001f, 1.220703125e-4f);
+            }
+            dst[i] = v;
+        }
+    }
     __syncthreads();
     const float* rec0 = rec_s;
     uint8_t* tab0 = tables + pair0 * LUT_BYTES;
@@ -437,7 +438,6 @@ int launch_l2f(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     l2f_prepare_kernel<DSUB><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, nprobe, d, m, rec);
     l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
                                                                d, m, lo, range_bits, ws.counters.as<int64_t>());
-    l2f_store_lo_kernel<DSUB><<<(unsigned)((npairs * m + 255) / 256), 256, 0, st>>>(lo, range_bits, npairs * m, m, nprobe, rec);
     if (out_LUT8)
         l2f_quant_kernel<DSUB, true><<<grid2, L2Q_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
                                                                        m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
