@@ -384,11 +384,10 @@ static DevBuf g_flat_keys[16], g_flat_cnt[16], g_flat_tbin[16];
 
 template <int D, bool HALF>
 static int launch_flat_dh(const FlatParams& P, int grid, size_t lds, hipStream_t st) {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static OncePerDevice attr;
+    if (attr.first()) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(flat_scan_kernel<D, HALF>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)flat_lds_bytes(D)));
-        attr_done = true;
     }
     flat_scan_kernel<D, HALF><<<grid, FLAT_THREADS, lds, st>>>(P);
     RAGO_HIP(hipGetLastError());

@@ -17,6 +17,20 @@ constexpr int LUT_BYTES = 4 * LUT_PLANE;   // stride of one 8-bit table in HBM (
 
 void set_error(const std::string& msg);
 int fail(int code, const std::string& msg);
+
+// "Has this been done on the current device yet?"  Kernel attributes (a larger dynamic LDS limit) are per device,
+// so a process that drives several GPUs has to set them on each.  Races between threads are harmless: the
+// attribute call is idempotent.
+struct OncePerDevice {
+    bool done[64] = {};
+    bool first() {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;
+        if (done[dev]) return false;
+        done[dev] = true;
+        return true;
+    }
+};
 #define RAGO_HIP(call)                                                                       \
     do {                                                                                     \
         hipError_t e_ = (call);                                                              \

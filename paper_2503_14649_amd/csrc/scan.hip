@@ -890,11 +890,10 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
 // ------------------------------------------------------------------ host side
 template <int MPAD>
 static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static OncePerDevice attr;
+    if (attr.first()) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kernel<MPAD>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, ScanShape<MPAD>::LDS));
-        attr_done = true;
     }
     scan_kernel<MPAD><<<grid, ScanShape<MPAD>::NT, ScanShape<MPAD>::LDS, st>>>(P);
     RAGO_HIP(hipGetLastError());

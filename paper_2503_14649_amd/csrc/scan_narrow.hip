@@ -437,11 +437,10 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
 
 template <int MPAD>
 static int launch_one(const ScanParams& P, int grid, hipStream_t st) {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static OncePerDevice attr;
+    if (attr.first()) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kernel<MPAD>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      SCAN_LDS));
-        attr_done = true;
     }
     scan_kernel<MPAD><<<grid, SCAN_THREADS, SCAN_LDS, st>>>(P);
     RAGO_HIP(hipGetLastError());

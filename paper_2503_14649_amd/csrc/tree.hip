@@ -153,10 +153,9 @@ int launch_select_tree(rago_index* idx, const float* q, int64_t nq, int nprobe, 
     int32_t* kept = ws.cand_idx.as<int32_t>();
     tree_score_groups_kernel<<<dim3((unsigned)nq, (unsigned)((nsuper + TREE_ROWS - 1) / TREE_ROWS)), 256, 0, st>>>(q, idx->sup_cen, nsuper, d,
                                                                                                             idx->metric, keys);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static OncePerDevice attr;
+    if (attr.first()) {
         RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(tree_pick_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, TREE_CAP * 8));
-        attr_done = true;
     }
     auto pow2 = [](int n) { int p = 1; while (p < n) p <<= 1; return p; };
     tree_pick_kernel<<<(unsigned)nq, 1024, (size_t)pow2(nsuper) * 8, st>>>(keys, nsuper, nullptr, 0, nullptr, nullptr, 0, nsp, kept);
