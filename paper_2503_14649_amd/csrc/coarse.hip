@@ -458,15 +458,34 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     float qn = 0.f;
     for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
     for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
-    // (eight candidates per wave at a time: the rows come from HBM at random, and the time of this step is
-    // the number of such rounds times the latency of a loaded memory system)
+    // (RU candidates per wave at a time: the rows come from HBM at random, and the time of this step is the
+    // number of such rounds times the latency of a loaded memory system; with 16-byte loads a lane has
+    // d / 256 loads per row, so a whole round is in flight at once)
     constexpr int RU = 8;
+    const bool vec4 = (d & 3) == 0;
     for (int c0 = wave * RU; c0 < want; c0 += SEL_WAVES * RU) {
         double acc[RU];
         const float* cv[RU];
 #pragma unroll
         for (int u = 0; u < RU; ++u) { acc[u] = 0.0; cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d; }
-        if (metric == 1) {
+        if (vec4) {
+            for (int t = lane * 4; t < d; t += 256) {
+                const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
+                float4 c4[RU];
+#pragma unroll
+                for (int u = 0; u < RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
+                const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const double ca[4] = {(double)c4[u].x, (double)c4[u].y, (double)c4[u].z, (double)c4[u].w};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        if (metric == 1) { const double diff = qa[x] - ca[x]; acc[u] = acc[u] + diff * diff; }
+                        else acc[u] = acc[u] + qa[x] * ca[x];
+                    }
+                }
+            }
+        } else if (metric == 1) {
             for (int t = lane; t < d; t += 64) {
                 const double qt = (double)qv[t];
 #pragma unroll
@@ -490,18 +509,31 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     }
     __syncthreads();
     if (want <= SEL_THREADS) {
-        // ---- order by (score desc, list asc): every candidate counts those that come before it
-        // (all lanes read the same LDS word at a time: a broadcast) and writes its list to that rank
-        int mine_i = 0x7fffffff, rank = 0;
-        float mine_v = -INFINITY;
-        if (tid < want) { mine_i = c_idx[tid]; mine_v = c_val[tid]; }
-        for (int j = 0; j < want; ++j) {
-            const float vj = c_val[j];
-            const int ij = c_idx[j];
-            rank += (vj > mine_v || (vj == mine_v && ij < mine_i)) ? 1 : 0;
+        // ---- order by (score desc, list asc): one 64-bit key per candidate (ordered score bits, then the complement
+        // of the list number), and every candidate counts the keys above its own: that count is its rank (lists are
+        // distinct, so the ranks are a permutation).  The G = 1024 / want thread groups each count a residue class
+        // of j; the lanes of a wave read the same key at a time (a broadcast).
+        uint64_t* key64 = reinterpret_cast<uint64_t*>(hist32);              // [want]   (the histograms are no longer needed)
+        int* rank = hist32 + 2 * SEL_CAP;                                  // [want]
+        if (tid < want) {
+            key64[tid] = ((uint64_t)float_key(c_val[tid] + 0.0f) << 32)   /* (-0 counts as +0) */
+                         | (uint32_t)(0xFFFFFFFFu - (uint32_t)c_idx[tid]);
+            rank[tid] = 0;
         }
+        __syncthreads();
+        const int G = SEL_THREADS / want, c = tid % want, g = tid / want;
+        if (g < G) {
+            const uint64_t mine = key64[c];
+            int above = 0;
+            for (int j = g; j < want; j += G) above += key64[j] > mine ? 1 : 0;
+            if (above) atomicAdd(&rank[c], above);
+        }
+        __syncthreads();
+        int mine_i = 0, r = 0;
+        float mine_v = 0.f;
+        if (tid < want) { mine_i = c_idx[tid]; mine_v = c_val[tid]; r = rank[tid]; }
         __syncthreads();                             // every c_idx / c_val read is done
-        if (tid < want) { c_idx[rank] = mine_i; c_val[rank] = mine_v; }   // (ranks are a permutation: lists are distinct)
+        if (tid < want) { c_idx[r] = mine_i; c_val[r] = mine_v; }
         __syncthreads();
     } else {
         int n2 = 1;
