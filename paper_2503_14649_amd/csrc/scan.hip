@@ -828,8 +828,26 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
     }
     if (threadIdx.x == 0) s_pre[0] = 0;
     __syncthreads();
-    if (threadIdx.x == 0)
-        for (int p = 0; p < P.nprobe; ++p) s_pre[p + 1] += s_pre[p];
+    {
+        // inclusive prefix sum of s_pre[1 .. nprobe]: every thread sums a run of consecutive entries, the runs'
+        // totals are scanned inside each wave (shuffles) and across the waves (LDS), then each run is rewritten
+        __shared__ int s_wsum[MERGE_THREADS / 64];
+        const int per = (P.nprobe + MERGE_THREADS - 1) / MERGE_THREADS;       // <= 8
+        const int a = 1 + threadIdx.x * per, b = min(a + per, P.nprobe + 1);
+        int run = 0;
+        for (int i = a; i < b; ++i) run += s_pre[i];
+        int inc = run;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(inc, o);
+            if (lane >= o) inc += v;
+        }
+        if (lane == 63) s_wsum[wave] = inc;
+        __syncthreads();
+        int before = inc - run;
+        for (int w = 0; w < wave; ++w) before += s_wsum[w];
+        for (int i = a; i < b; ++i) { before += s_pre[i]; s_pre[i] = before; }
+    }
     __syncthreads();
     const int nslots = s_pre[P.nprobe];
     auto gather = [&](int s0, int s1, int base_fill) {
