@@ -33,9 +33,9 @@ def scaled_cfg(cfg, f):
                       components=max(16, int(cfg.components * f)), train_n=max(20000, int(cfg.train_n * f)))
 
 
-def read_traffic(workload):
-    """HBM bytes per scan-kernel launch from the committed rocprofv3 --pmc summary, if present."""
-    p = os.path.join(ROOT, "profiles", f"scan_m96_{workload}_pmc.txt")
+def read_traffic(workload, name=None):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
+    p = os.path.join(ROOT, "profiles", name or f"scan_m96_{workload}_pmc.txt")
     if not os.path.exists(p):
         return None
     vals = {}
@@ -310,6 +310,13 @@ def run_flat(args):
     if half:
         corpus, queries = corpus.to(torch.float16), queries.to(torch.float16)   # same embeddings, stored as binary16
     search = rb.rago_flat_search_f16 if half else rb.rago_flat_search
+    if args.calib_copy_gib > 0:     # a copy of known size for scaling hardware byte counters
+        a = torch.empty(int(args.calib_copy_gib * (1 << 30)), dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        rb.rago_debug_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
     out = (torch.empty(R, cfg.nq, cfg.k, dtype=torch.int64, device="cuda"),
            torch.empty(R, cfg.nq, cfg.k, dtype=torch.float32, device="cuda"))
     for _ in range(args.warmup):
@@ -342,7 +349,9 @@ def run_flat(args):
            "dtype": args.flat_format, "data": "synthetic",
            "config": {"workload": f"flat: R={R} n={cfg.n} d={cfg.d} nq={cfg.nq} k={cfg.k}", "scale": args.scale},
            "roofline": {"bound": "hbm", "kernel": "flat_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                        "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes_per_launch": algo},
+                        "frac": achieved / HBM_PEAK_GBPS,
+                        "traffic": read_traffic("flat", "flat_32x100k_pmc.txt") if R == cfg.requests and not half else None,
+                        "algorithmic_bytes_per_launch": algo},
            "cpu_baseline": cpu}
     print(json.dumps(rec), flush=True)
 
