@@ -203,7 +203,7 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
         lat = []
         out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
                torch.empty(b, k, dtype=torch.int32, device="cuda"))
-        chains = max(args.steps, 4)
+        chains = max(args.steps, 100)       # request chains of 8 rounds each: median and p99 over >= 800 rounds
         rb.rago_debug_profile(h, False)
         for c in range(chains + 1):
             if c == 1:
@@ -265,7 +265,7 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
             out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
                    torch.empty(b, k, dtype=torch.int32, device="cuda"))
             lat, agree = [], []
-            for c in range(max(args.steps, 4) + 1):
+            for c in range(max(args.steps, 100) + 1):
                 q = synth.make_queries(cfg, b, device="cuda", stream=20 + c)
                 for r in range(synth.ITER_ROUNDS):
                     rb.rago_index_set_upper_probe(h, nsp)
@@ -292,7 +292,8 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
            "config": {"workload": f"iterative on {cfg.name}: n={cfg.n} nlist={cfg.nlist} nprobe={nprobe} k={k} rounds=8 "
-                                  f"batches=1/4/16 drift_sigma={synth.ITER_DRIFT}", "scale": args.scale},
+                                  f"batches=1/4/16 drift_sigma={synth.ITER_DRIFT}", "scale": args.scale,
+                      "request_chains": max(args.steps, 100)},
            "per_batch": res, "upper_level": tree, "cpu_baseline": cpu}
     print(json.dumps(rec), flush=True)
     rb.rago_index_free(h)
