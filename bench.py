@@ -360,7 +360,7 @@ def run_flat(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 10; 100 for the flat workload, whose step is ~1 ms)")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="hyper", choices=["hyper", "mid", "tiny", "iter", "flat"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n/nlist/components by this factor (development runs)")
@@ -375,6 +375,8 @@ def main():
     ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
                     help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 100 if args.workload == "flat" else 10
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one GPU's shard at real shape); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
