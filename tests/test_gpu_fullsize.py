@@ -109,6 +109,30 @@ def test_mid_config_samples(rb):
     rb.rago_index_free(h)
 
 
+@pytest.mark.parametrize("variant", ["l2", "pq4", "pq4_l2"])
+def test_mid_config_other_metrics_and_code_widths(rb, variant):
+    """The mid configuration under the Euclidean metric, with 4-bit codes (192 sub-quantisers of 16 codewords =
+    96 code bytes), and both: 12 sampled queries against the oracle."""
+    metric = "l2" if variant.endswith("l2") else "ip"
+    cfg = synth.MID if variant == "l2" else synth.MID.scaled(m=192, ksub=16)
+    print(f"[fullsize] mid {variant}: m={cfg.m} ksub={cfg.ksub} metric={metric}", flush=True)
+    index = synth.build_index(cfg, device="cuda:0", keep_vectors=False)
+    Q = synth.make_queries(cfg, cfg.nq, device="cuda:0")
+    qn = Q[:12].cpu().numpy()
+    sub = host_subindex(index, oracle.select(oracle.coarse(qn, index["centroids"].cpu().numpy(), metric=metric), cfg.nprobe))
+    h = rb.rago_index_wrap(index, 0, metric=metric)
+    ids, scores, isc = rb.rago_ivfpq_search(h, Q, cfg.nprobe, cfg.k)
+    torch.cuda.synchronize()
+    ref = oracle.ivfpq_search(qn, sub, cfg.nprobe, cfg.k, metric=metric)
+    assert np.array_equal(ids.cpu().numpy()[:12], ref["ids"]) and np.array_equal(isc.cpu().numpy()[:12], ref["iscores"])
+    assert np.array_equal(scores.cpu().numpy()[:12], ref["scores"])
+    cnt = rb.rago_debug_counters(h)
+    assert cnt[3] == 0
+    if metric == "l2":
+        assert cnt[5] == 0 and cnt[4] < 0.02 * 2 * cfg.nq * cfg.nprobe * 96 * 256   # fp32 decided all but a few entries
+    rb.rago_index_free(h)
+
+
 def test_flat_full_size_matches_oracle_on_samples(rb):
     cfg = synth.FLAT
     corpus, queries = synth.make_flat(cfg, device="cuda:0")                   # 32 x 100000 x 768 bf16
@@ -124,3 +148,14 @@ def test_flat_full_size_matches_oracle_on_samples(rb):
         assert ov >= 0.999, ov
     assert gi.min() >= 0 and gi.max() < cfg.n
     assert np.all(np.diff(gs, axis=2) <= 0)
+    # the same embeddings as IEEE binary16
+    ch, qh = corpus.to(torch.float16), queries.to(torch.float16)
+    hi, hs = rb.rago_flat_search_f16(ch, qh, cfg.k)
+    torch.cuda.synchronize()
+    hi, hs = hi.cpu().numpy(), hs.cpu().numpy()
+    r = 5
+    cb = ch[r:r + 1].cpu().view(torch.int16).numpy().view(np.uint16)
+    qb = qh[r:r + 1].cpu().view(torch.int16).numpy().view(np.uint16)
+    oi, osc = oracle.flat_search(cb, qb, cfg.k, fmt="f16")
+    assert np.max(np.abs(hs[r] - osc[0])) < 1e-4
+    assert np.mean([len(set(hi[r, q].tolist()) & set(oi[0, q].tolist())) / cfg.k for q in range(cfg.nq)]) >= 0.999
