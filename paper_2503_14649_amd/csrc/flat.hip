@@ -11,8 +11,8 @@
 //    load 64 contiguous bytes per instruction and the two halves of each 128-byte row segment are
 //    consumed by back-to-back instructions (two dwordx4 per lane, two MFMA steps).
 //  * queries sit in LDS (row stride padded by 16 B so the 16 query rows fall in different banks).
-//  * a workgroup (4 waves) streams one slab of one request; a wave takes 16-row blocks, the next
-//    block's 24 loads are in flight while the current block is multiplied.
+//  * a workgroup (4 waves) streams one slab of one request; a wave takes 16-row blocks, one in
+//    registers at a time (its 24 loads are issued right after the previous block's multiply).
 //  * selection: a score is a candidate when its histogram bin (width 1/128) is not below the
 //    query's threshold bin; in the stream that is four compares and one wave-uniform branch per
 //    block.  A candidate first goes to the wave's staging area in LDS (positions from ballots, so
@@ -46,7 +46,7 @@ constexpr int FLAT_ROUND_ROWS = FLAT_WAVES * FLAT_RB * 16;  // 256 rows per work
 constexpr int FLAT_MAXD = 1024;
 constexpr int FLAT_CAP = 1024;                              // candidate keys per (slab, query) in the HBM scratch
 constexpr int FLAT_BINS = 256;                              // score histogram bins per query
-constexpr int FLAT_STAGE = 1024;                            // staged candidates per wave (LDS), flushed past 512 or at a round's end
+constexpr int FLAT_STAGE = 1024;                            // staged candidates per wave (LDS), flushed past 768 or at a round's end
 constexpr size_t flat_lds_bytes(int d) { return 16 * (size_t)(d * 2 + 16) + 16 * FLAT_BINS * 2 + 256 + (size_t)FLAT_WAVES * FLAT_STAGE * 8; }
 
 __device__ __forceinline__ uint32_t fkey(float f) {
@@ -170,7 +170,7 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
     float thrx = i16 < P.nqr ? -never : never;   // this lane's query: threshold bin as a float, -inf while it is bin 0
     int nstage = 0;                              // candidates in this wave's staging area (wave-uniform)
     int64_t round_base = row0;                   // first row of the current round
-    uint4 a[2 * NP], an[2 * NP];
+    uint4 a[2 * NP];
     // loads are unconditional (row clamped into the corpus): a conditional prefetch would make the
     // compiler wait for every outstanding load before each use
     auto load_rows = [&](uint4 (&dst)[2 * NP], int64_t rb) {   // rb = first row of a 16-row block
@@ -229,16 +229,16 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
     // rounds of 256 rows: wave w owns blocks w*FLAT_RB .. +FLAT_RB of the round
     if (row0 < row1) load_rows(a, row0 + (int64_t)wave * FLAT_RB * 16);
     for (int64_t round0 = row0; round0 < row1; round0 += FLAT_ROUND_ROWS) {
+        // One block per wave in registers: the next block is requested as soon as the current one has gone through
+        // the matrix unit, and the other seven waves of the CU cover the wait.  (Two blocks per wave, the second
+        // in flight during the multiply, measured the same at d = 768 and does not fit the registers at d = 1024.)
 #pragma unroll 1
-        for (int bb = 0; bb < FLAT_RB; bb += 2) {
-            const int64_t r0 = round0 + ((int64_t)wave * FLAT_RB + bb) * 16, r1 = r0 + 16;
-            int64_t r2 = r0 + 32;
-            if (bb + 2 >= FLAT_RB) r2 = round0 + FLAT_ROUND_ROWS + (int64_t)wave * FLAT_RB * 16;   // first block of next round
-            load_rows(an, r1);
-            if (nstage > FLAT_STAGE - 512) flush();      // two blocks follow: up to 512 candidates while nothing is filtered
+        for (int bb = 0; bb < FLAT_RB; ++bb) {
+            const int64_t r0 = round0 + ((int64_t)wave * FLAT_RB + bb) * 16;
+            const int64_t rn = bb + 1 < FLAT_RB ? r0 + 16 : round0 + FLAT_ROUND_ROWS + (int64_t)wave * FLAT_RB * 16;   // or the first of the next round
+            if (nstage > FLAT_STAGE - 256) flush();      // a block adds up to 256 candidates while nothing is filtered
             if (r0 < row1) multiply(a, r0);
-            load_rows(a, r2);
-            if (r1 < row1) multiply(an, r1);
+            load_rows(a, rn);
         }
         if (nstage) flush();
         __syncthreads();
