@@ -11,7 +11,8 @@
 //   rr = |r|^2 by fma chains and cc = fl(|cb|^2): the chains err by at most dsub u times the sum of
 //   the absolute terms, the two last roundings and cc by u each, the rounding of r_t by 2 u:
 //   |L~ - L64| <= (dsub + 4) u M,  M = sum_t (|q_t| + |c_t| + max_c |cb_t|)^2,  u = 2^-24;
-//   E = 2 (dsub + 6) u M is used (twice the bound, which also covers the rounding of E itself).
+//   E = 2 (dsub + 6) (u M + 2^-126) is used: twice the bound, which also covers the rounding of E itself, plus
+//   the smallest normal number per operation, which covers results that underflow.
 //
 //   pass 1 (minima, range): the entry attaining the exact minimum of a sub-table has
 //   L~ <= min L~ + 2E, so the exact minimum is the least fp32(fp64) value among those candidates;
@@ -122,7 +123,7 @@ __global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restric
             M = __fmaf_rn(a, a, M);
         }
         e[DSUB] = rr;
-        e[DSUB + 1] = 2.0f * (float)(DSUB + 6) * L2F_U * M;
+        e[DSUB + 1] = 2.0f * (float)(DSUB + 6) * (L2F_U * M + 1.17549435e-38f);   // (+ one smallest normal number per operation: underflow)
         e[DSUB + 2] = 0.0f;
         e[DSUB + 3] = 0.0f;
     }
@@ -170,7 +171,7 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __r
                 const float lo_cut = mn + marg, hi_cut = mx - marg;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if (v[i] <= lo_cut || v[i] >= hi_cut) {
+                    if (!(v[i] > lo_cut && v[i] < hi_cut)) {          // (written so that a NaN anywhere means "candidate")
                         const int pos = atomicAdd(&nlist, 1);
                         if (pos < L2F_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | (lane + 64 * i));
                     }
@@ -273,7 +274,7 @@ __device__ __forceinline__ void l2f_quant_unit(const float* __restrict__ cbx, co
                         const float rr = fminf(fmaxf(rintf(b), 0.0f), 255.0f);
                         word[p][i] |= (uint32_t)rr << (8 * s4);
                         // undecided (about one entry in a thousand): on the list
-                        if (fabsf(__builtin_amdgcn_fractf(b) - 0.5f) <= a.w) {
+                        if (!(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > a.w)) {      // (a NaN or infinite b~ or eta means "undecided")
                             const int pos = atomicAdd(nlist, 1);
                             if (pos < L2Q_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | (c + 64 * i));
                         }

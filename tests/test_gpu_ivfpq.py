@@ -286,6 +286,28 @@ def test_l2_stages_equal_oracle(l2case, rb):
             assert cnt[5] == 0 and 0 < cnt[4] < 0.05 * entries
 
 
+@pytest.mark.parametrize("scale", [1e-19, 1e18])
+def test_l2_tables_at_the_ends_of_the_fp32_range(rb, scale):
+    """Everything scaled by 1e-19: squared distances (~1e-38 and below) underflow in fp32, where the relative error
+    bound of the fp32 evaluation means nothing (and 1 / step overflows); scaled by 1e18 they come close to the
+    largest fp32 number.  The tables must still be the oracle's."""
+    ix = to_np(synth.random_index(n=3000, d=64, m=16, nlist=6, seed=77))
+    ix["centroids"] = (ix["centroids"] * scale).astype(np.float32)
+    ix["codebooks"] = (ix["codebooks"] * scale).astype(np.float32)
+    Q = (_queries(5, 64, 78) * scale).astype(np.float32)
+    probes = np.tile(np.arange(4, dtype=np.int32), (5, 1))
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="l2")
+    assert np.all(np.isfinite(L)) and (np.abs(L).max() < 1e-36 if scale < 1 else np.abs(L).max() > 1e35)
+    LUT8, B, delta = oracle.quantise(L)
+    h = rb.rago_index_wrap(dev_index(ix), metric="l2")
+    try:
+        gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+        assert np.array_equal(gL.cpu().numpy(), L) and np.array_equal(gd.cpu().numpy(), delta)
+        assert np.array_equal(gL8.cpu().numpy(), LUT8) and np.array_equal(gB.cpu().numpy(), B)
+    finally:
+        rb.rago_index_free(h)
+
+
 def test_l2_search_end_to_end(l2case, rb, scan_kernel):
     ix, Q, nprobe, k, h = l2case
     r = oracle.ivfpq_search(Q, ix, nprobe, k, metric="l2")
