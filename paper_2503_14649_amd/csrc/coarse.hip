@@ -563,6 +563,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         // (Euclidean: twice the product's error, plus the roundings of the two squared norms and of the sum)
         float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
         if (metric == 1) E = 2.0f * E + 4.76837158203125e-07f * (qn + max_cnorm * max_cnorm);
+        E += (float)d * 2.4e-38f;        // products that underflow (the matrix cores may flush subnormal numbers)
         if (!(c_val[nprobe - 1] > s_cut + E)) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull);
     }
 }

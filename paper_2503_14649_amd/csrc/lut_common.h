@@ -14,9 +14,12 @@ __device__ __forceinline__ float lut_step(float range) {
 }
 
 // Half-width of the zone around a half-integer in which the per-pair fp32 result may differ from
-// rne((T - Tmin) / delta): twice the bound 2^-24 * ((2 M + range) / delta + 256).
+// rne((T - Tmin) / delta): twice the bound 2^-24 * ((2 M + range) / delta + 256), plus, for tables so small that
+// their entries are subnormal fp32 numbers (absolute rounding error 2^-150 instead of a relative one), four
+// smallest subnormals over delta.
 __device__ __forceinline__ double lut_eta(float range, float mag, float dq) {
-    return 2.0 * 5.9604644775390625e-08 * ((2.0 * (double)mag + (double)range) / (double)dq + 256.0);
+    return 2.0 * 5.9604644775390625e-08 * ((2.0 * (double)mag + (double)range) / (double)dq + 256.0) +
+           4.0 * 1.401298464324817e-45 / (double)dq;
 }
 
 // LUT8 entry from the fp64 per-query part Tv, the fp64 per-pair part t and the pair's fp32 minimum.

@@ -142,6 +142,29 @@ def test_tables_equal_oracle(case, rb):
         assert cnt[5] == 0 and 0 < cnt[4] < 0.02 * len(Q) * m * 256     # base table + a few per-pair entries
 
 
+@pytest.mark.parametrize("scale", [1e-19, 1e18])
+@pytest.mark.parametrize("shape", [(64, 16), (768, 96)])
+def test_tables_at_the_ends_of_the_fp32_range(rb, scale, shape):
+    """Inner-product tables of vectors scaled by 1e-19 (products underflow, the table step is subnormal) and by 1e18
+    (products near the largest fp32 number): LUT8, bias and step as the oracle defines them."""
+    d, m = shape
+    ix = to_np(synth.random_index(n=3000, d=d, m=m, nlist=6, seed=91))
+    ix["centroids"] = (ix["centroids"] * scale).astype(np.float32)
+    ix["codebooks"] = (ix["codebooks"] * scale).astype(np.float32)
+    Q = (_queries(4, d, 92) * scale).astype(np.float32)
+    probes = np.tile(np.arange(3, dtype=np.int32), (4, 1))
+    L = oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes)
+    assert np.all(np.isfinite(L))
+    LUT8, B, delta = oracle.quantise(L)
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+        assert np.array_equal(gd.cpu().numpy(), delta)
+        assert np.array_equal(gL8.cpu().numpy(), LUT8) and np.array_equal(gB.cpu().numpy(), B)
+    finally:
+        rb.rago_index_free(h)
+
+
 def test_search_end_to_end(case, rb, scan_kernel):
     ix, Q, nprobe, k, h = case
     r = oracle.ivfpq_search(Q, ix, nprobe, k)
