@@ -114,3 +114,35 @@ def test_flat_f16_ties_subnormals_and_dims(rb):
         assert np.all(np.abs(gs[:, :, 0]) > 1e-3)                       # scores of order 2^-2 cos: nothing was flushed to zero
     with pytest.raises(AssertionError):                                  # the binding refuses the wrong number format
         rb.rago_flat_search_f16(torch.zeros(1, 10, 128, dtype=torch.bfloat16).cuda(), torch.zeros(1, 2, 128, dtype=torch.bfloat16).cuda(), 4)
+
+
+@pytest.mark.parametrize("kind", ["large_scores", "ascending_scores", "all_equal"])
+def test_flat_scores_outside_the_histogram_range(rb, kind):
+    """The selection's histogram covers scores in [-1, 1]; embeddings that are not normalised fall outside it, where
+    the filter passes everything and the candidate areas are cut back again and again.  Results must not change.
+    `ascending_scores`: every row beats all rows before it (every row is a candidate in any case);
+    `all_equal`: one score for the whole corpus (ties by row)."""
+    g = torch.Generator().manual_seed(21)
+    R, n, d, nq, k = 2, 20000, 128, 16, 32
+    if kind == "large_scores":
+        corpus = (torch.randn(R, n, d, generator=g) * 3.0).to(torch.bfloat16)
+        queries = (torch.randn(R, nq, d, generator=g) * 3.0).to(torch.bfloat16)
+    elif kind == "ascending_scores":
+        base = torch.nn.functional.normalize(torch.randn(R, 1, d, generator=g), dim=2)
+        corpus = (base * torch.linspace(0.5, 40.0, n).view(1, n, 1)).to(torch.bfloat16)
+        queries = base.expand(R, nq, d).contiguous().to(torch.bfloat16)
+    else:
+        base = torch.nn.functional.normalize(torch.randn(R, 1, d, generator=g), dim=2)
+        corpus = base.expand(R, n, d).contiguous().to(torch.bfloat16)
+        queries = base.expand(R, nq, d).contiguous().to(torch.bfloat16)
+    gi, gs = rb.rago_flat_search(corpus.cuda(), queries.cuda(), k)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    oi, osc = oracle.flat_search(_bits(corpus), _bits(queries), k)
+    scale = float(np.abs(osc).max())
+    assert np.max(np.abs(gs - osc)) <= 1e-4 * max(scale, 1.0)
+    if kind == "all_equal":
+        assert np.array_equal(gi, oi)                          # rows 0 .. k-1
+    else:
+        ov = np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / k for r in range(R) for q in range(nq)])
+        assert ov >= 0.999, ov
