@@ -130,7 +130,7 @@ int rago_index_info(const rago_index* idx, rago_index_desc* out);
  * -|q - c|^2 and the tables -|q_j - (c_j + codeword)|^2; they then no longer split into a
  * per-query and a per-list part, so a full table is computed for every (query, list) pair.
  *   queries     DEVICE [nq][d] fp32 row-major, 16-byte aligned
- *   nq >= 0, 1 <= nprobe <= min(nlist, 2048), nq * nprobe <= 2^30, 1 <= k <= 128
+ *   nq >= 0, 1 <= nprobe <= min(nlist, 2016) (up to 2048 when nprobe = nlist), nq * nprobe <= 2^30, 1 <= k <= 128
  *   (RAGO_INVALID_ARG for nprobe > nlist or k < 1, RAGO_UNSUPPORTED beyond the other limits)
  *   out_ids     DEVICE [nq][k] int64, best first, padded with -1
  *   out_scores  DEVICE [nq][k] fp32 = integer score * the query's table step; pad = -inf

@@ -199,6 +199,43 @@ def test_select_with_massive_ties(rb, scan_kernel):
     rb.rago_index_free(h)
 
 
+def test_one_code_for_every_vector(rb, scan_kernel):
+    """All vectors carry the same code: inside a list every score ties, and the order is by id alone."""
+    ix = to_np(synth.random_index(n=6000, d=64, m=32, nlist=5, seed=41, shuffle_ids=True))
+    ix["codes"][:] = ix["codes"][0]
+    Q = _queries(4, 64, 42)
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        for metric_k in (1, 100, 128):
+            r = oracle.ivfpq_search(Q, ix, 3, metric_k)
+            gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 3, metric_k)
+            assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    finally:
+        rb.rago_index_free(h)
+
+
+def test_many_probes(rb, scan_kernel):
+    """Probe counts beyond a workgroup's thread count (the selection then sorts its candidates by a bitonic network
+    instead of ranking them) up to the largest the library serves, and the first one it refuses."""
+    ix = to_np(synth.random_index(n=30000, d=32, m=16, nlist=2600, seed=31, shuffle_ids=True))
+    Q = _queries(3, 32, 32)
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        S = oracle.coarse(Q, ix["centroids"])
+        gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+        for nprobe in (1000, 1500, 2016):
+            gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, nprobe).cpu().numpy()
+            assert np.array_equal(gp, oracle.select(S, nprobe)), nprobe
+        r = oracle.ivfpq_search(Q, ix, 1500, 20)
+        gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 1500, 20)
+        assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+        with pytest.raises(rb.RagoError) as e:
+            rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 2017, 20)
+        assert e.value.code == -6
+    finally:
+        rb.rago_index_free(h)
+
+
 def test_padding_and_argument_errors(rb, scan_kernel):
     ix = to_np(synth.random_index(n=300, d=32, m=16, nlist=8, seed=5, empty_lists=(0, 1, 2, 3, 4)))
     h = rb.rago_index_wrap(dev_index(ix))
