@@ -382,6 +382,11 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
 
 static DevBuf g_flat_keys[16], g_flat_cnt[16], g_flat_tbin[16];
 
+// (a kernel rather than a memset node: the call may be recorded into a HIP graph by the caller)
+__global__ void flat_zero_kernel(int32_t* p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
 template <int D, bool HALF>
 static int launch_flat_dh(const FlatParams& P, int grid, size_t lds, hipStream_t st) {
     static OncePerDevice attr;
@@ -426,7 +431,8 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
         const size_t need = (size_t)R * 16 * 4;
         if (need > g_flat_tbin[device].cap) {          // (re)allocation: start from all-zero bins
             if ((rc = g_flat_tbin[device].reserve(need))) return rc;
-            RAGO_HIP(hipMemsetAsync(g_flat_tbin[device].p, 0, g_flat_tbin[device].cap, st));
+            flat_zero_kernel<<<64, 256, 0, st>>>(g_flat_tbin[device].as<int32_t>(), (int64_t)(g_flat_tbin[device].cap / 4));
+            RAGO_HIP(hipGetLastError());
         }
         P.shared_tbin = g_flat_tbin[device].as<int32_t>();
     }

@@ -146,3 +146,31 @@ def test_flat_scores_outside_the_histogram_range(rb, kind):
     else:
         ov = np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / k for r in range(R) for q in range(nq)])
         assert ov >= 0.999, ov
+
+
+def test_flat_search_replayed_from_a_hip_graph(rb):
+    """After one call that sizes the library's workspace the flat search only enqueues kernels, so a caller may capture
+    it; every replay (with eager calls and synchronisation in between) must equal the eager call on the same data."""
+    cfg = synth.FLAT
+    corpus, queries = synth.make_flat(cfg, requests=3, n=9000)
+    c_static, q_static = corpus.cuda(), queries.cuda()
+    k = 20
+    out = (torch.empty(3, cfg.nq, k, dtype=torch.int64, device="cuda"), torch.empty(3, cfg.nq, k, dtype=torch.float32, device="cuda"))
+    rb.rago_flat_search(c_static, q_static, k, out=out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rb.rago_flat_search(c_static, q_static, k, out=out)
+    g = torch.Generator().manual_seed(5)
+    for rep in range(4):
+        perm = torch.randperm(9000, generator=g)
+        c_new = corpus[:, perm].contiguous()                           # the same rows in another order
+        c_static.copy_(c_new.cuda())
+        graph.replay()
+        torch.cuda.synchronize()
+        gi, gs = out[0].cpu().numpy().copy(), out[1].cpu().numpy().copy()
+        ei, es = rb.rago_flat_search(c_new.cuda(), q_static, k)        # eager work between replays
+        torch.cuda.synchronize()
+        assert np.array_equal(ei.cpu().numpy(), gi) and np.array_equal(es.cpu().numpy(), gs), rep
+        oi, osc = oracle.flat_search(_bits(c_new), _bits(queries), k)
+        assert np.max(np.abs(gs - osc)) < 1e-4
