@@ -720,17 +720,32 @@ __global__ void __launch_bounds__(256) touched_values_kernel(const int32_t* __re
     }
 }
 
-// Exclusive prefix sums (in place) of the per-list pair and task counts: one workgroup, coalesced.
+// Exclusive prefix sums (in place) of the per-list pair and task counts: one workgroup; a thread takes eight
+// consecutive entries per tile (two 16-byte loads per array), so a tile is 8192 entries and the number of
+// load -> wave scan -> barrier rounds, each of which costs a memory latency, is n / 8192.
 __global__ void __launch_bounds__(1024) touched_scan_kernel(int32_t* __restrict__ vp, int32_t* __restrict__ vt,
                                                             int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
     __shared__ int s_wp[16], s_wt[16];
+    constexpr int E = 8;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int n = ctrl[2];
     int carry_p = 0, carry_t = 0;
-    for (int base = 0; base < n; base += 1024) {
-        const int i = base + t;
-        const int p = i < n ? vp[i] : 0, q = i < n ? vt[i] : 0;
-        int ip = p, it = q;                        // inclusive scan across the wave
+    for (int base = 0; base < n; base += 1024 * E) {
+        const int i0 = base + t * E;
+        int p[E], q[E];
+        if (i0 + E <= n) {
+            const int4 a0 = *reinterpret_cast<const int4*>(vp + i0), a1 = *reinterpret_cast<const int4*>(vp + i0 + 4);
+            const int4 b0 = *reinterpret_cast<const int4*>(vt + i0), b1 = *reinterpret_cast<const int4*>(vt + i0 + 4);
+            p[0] = a0.x; p[1] = a0.y; p[2] = a0.z; p[3] = a0.w; p[4] = a1.x; p[5] = a1.y; p[6] = a1.z; p[7] = a1.w;
+            q[0] = b0.x; q[1] = b0.y; q[2] = b0.z; q[3] = b0.w; q[4] = b1.x; q[5] = b1.y; q[6] = b1.z; q[7] = b1.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) { p[e] = i0 + e < n ? vp[i0 + e] : 0; q[e] = i0 + e < n ? vt[i0 + e] : 0; }
+        }
+        int sp = 0, sq = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) { sp += p[e]; sq += q[e]; }
+        int ip = sp, it = sq;                      // inclusive scan of the threads' sums across the wave
         for (int o = 1; o < 64; o <<= 1) {
             const int a = __shfl_up(ip, o), b = __shfl_up(it, o);
             if (lane >= o) { ip += a; it += b; }
@@ -743,7 +758,23 @@ __global__ void __launch_bounds__(1024) touched_scan_kernel(int32_t* __restrict_
             if (w < wave) { wp += s_wp[w]; wt += s_wt[w]; }
             tot_p += s_wp[w]; tot_t += s_wt[w];
         }
-        if (i < n) { vp[i] = carry_p + wp + ip - p; vt[i] = carry_t + wt + it - q; }
+        int ep = carry_p + wp + ip - sp, et = carry_t + wt + it - sq;      // exclusive prefix of this thread's first entry
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int pe = p[e], qe = q[e];
+            p[e] = ep; q[e] = et;
+            ep += pe; et += qe;
+        }
+        if (i0 + E <= n) {
+            *reinterpret_cast<int4*>(vp + i0) = make_int4(p[0], p[1], p[2], p[3]);
+            *reinterpret_cast<int4*>(vp + i0 + 4) = make_int4(p[4], p[5], p[6], p[7]);
+            *reinterpret_cast<int4*>(vt + i0) = make_int4(q[0], q[1], q[2], q[3]);
+            *reinterpret_cast<int4*>(vt + i0 + 4) = make_int4(q[4], q[5], q[6], q[7]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                if (i0 + e < n) { vp[i0 + e] = p[e]; vt[i0 + e] = q[e]; }
+        }
         carry_p += tot_p; carry_t += tot_t;
     }
     if (t == 0) {
