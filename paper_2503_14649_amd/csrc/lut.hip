@@ -172,23 +172,31 @@ __global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict_
     }
 }
 
-// Per pair: bias and the exact values of the query's ambiguous entries.
-__global__ void __launch_bounds__(128) lut_patch_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+// Per pair: bias and the exact values of the query's ambiguous entries.  One wave per pair, four pairs per
+// workgroup (a pair has little work: m minima and a few dozen entries).
+__global__ void __launch_bounds__(256) lut_patch_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
                                                         const double* __restrict__ t64, const uint32_t* __restrict__ range_bits,
                                                         const uint16_t* __restrict__ amb_addr, const int32_t* __restrict__ namb,
-                                                        int nprobe, int m, int32_t* __restrict__ bias, uint8_t* __restrict__ patch_val) {
-    __shared__ double s_t[128];
-    __shared__ float s_lo[128];
-    const int64_t pair = blockIdx.x;
+                                                        int64_t npairs, int nprobe, int m, int32_t* __restrict__ bias,
+                                                        uint8_t* __restrict__ patch_val) {
+    __shared__ double s_t4[4][128];
+    __shared__ float s_lo4[4][128];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t pair = (int64_t)blockIdx.x * 4 + wave;
+    if (pair >= npairs) return;                       // (whole waves leave; there is no workgroup barrier below)
+    double* s_t = s_t4[wave];
+    float* s_lo = s_lo4[wave];
     const int64_t q = pair / nprobe;
     const float dq = lut_step(__uint_as_float(range_bits[q]));
-    if ((int)threadIdx.x < m) {
-        const double t = t64[pair * m + threadIdx.x];
-        s_t[threadIdx.x] = t;
-        s_lo[threadIdx.x] = (float)(Tmin[q * m + threadIdx.x] + t);
+    for (int j = lane; j < m; j += 64) {
+        const double t = t64[pair * m + j];
+        s_t[j] = t;
+        s_lo[j] = (float)(Tmin[q * m + j] + t);
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
+    // (the wave's own LDS writes are visible to its later reads: LDS operations of a wave complete in order; the
+    // wave barrier only keeps the compiler from moving the reads up)
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) {
         double losum = 0.0;
         for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
         bias[pair] = (int32_t)rint(losum / (double)dq);
@@ -196,7 +204,7 @@ __global__ void __launch_bounds__(128) lut_patch_kernel(const double* __restrict
     const int n = namb[q];
     if (n > AMB_MAX) return;
     const int S = rago_steps(m);
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    for (int i = lane; i < n; i += 64) {
         const int addr = amb_addr[q * AMB_MAX + i];
         const int plane = addr / LUT_PLANE, c = (addr >> 5) & 255, slot = addr & 31;
         const int j = plane * 32 + (slot & (S - 1));
@@ -385,8 +393,8 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     }
     lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,
                                                   ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(), ws.counters.as<int64_t>());
-    lut_patch_kernel<<<(unsigned)npairs, 128, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
-                                                       amb_addr, namb, nprobe, m, ws.bias.as<int32_t>(), ws.patch.as<uint8_t>());
+    lut_patch_kernel<<<(unsigned)((npairs + 3) / 4), 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
+                                                                   amb_addr, namb, npairs, nprobe, m, ws.bias.as<int32_t>(), ws.patch.as<uint8_t>());
     if (out_L_f32 || out_LUT8)
         lut_expand_kernel<<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
                                                             ws.lut8.as<uint8_t>(), amb_addr, namb, ws.patch.as<uint8_t>(), nprobe, m,
