@@ -128,7 +128,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
 // into LDS.  v_mfma_f32_32x32x16_bf16: lane (i32, h) supplies k = 8h .. 8h+7 of row i32 of both
 // operands; 128x128 tile per workgroup, 64x64 per wave.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-constexpr int X_T = 128, X_KT = 32, X_LS = 40;   // LDS row stride in bf16 (80 B: b128 reads conflict-free)
+constexpr int X_T = 128, X_KT = 64, X_LS = X_KT + 8;   // LDS row stride in bf16 (144 B: b128 reads conflict-free)
+constexpr int X_LDS = 4 * X_T * X_LS * 2;              // bytes: hi and lo tiles of both operands
 
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
     const uint32_t u = __float_as_uint(x);
@@ -159,7 +160,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
                                                                 const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
                                                                 int nct, const float* __restrict__ qn2,
                                                                 const float* __restrict__ cn2, float* __restrict__ S) {
-    __shared__ __align__(16) uint16_t Ah[X_T * X_LS], Al[X_T * X_LS], Bh[X_T * X_LS], Bl[X_T * X_LS];
+    extern __shared__ __align__(16) uint16_t x_smem[];
+    uint16_t *Ah = x_smem, *Al = Ah + X_T * X_LS, *Bh = Al + X_T * X_LS, *Bl = Bh + X_T * X_LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int r8 = blockIdx.x >> 3;
@@ -176,18 +178,19 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    float4 pa[4];
-    uint4 pbh[2], pbl[2];
+    constexpr int NA = X_KT / 8, NB = X_KT / 16;       // 16-byte loads per thread and K tile: A (fp32), B (bf16, hi and lo)
+    float4 pa[NA];
+    uint4 pbh[NB], pbl[NB];
     auto gload = [&](int k0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {          // A: 128 rows x 8 float4
-            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+        for (int r = 0; r < NA; ++r) {         // A: 128 rows x (X_KT / 4) float4
+            const int f = tid + 256 * r, row = f / (X_KT / 4), c4 = f % (X_KT / 4);
             const int gr = min(m0 + row, nq - 1), gk = k0 + c4 * 4;
             pa[r] = gk < d ? *reinterpret_cast<const float4*>(Q + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {          // B: 128 rows x 4 x (8 bf16), twice
-            const int f = tid + 256 * r, row = f >> 2, c8 = f & 3;
+        for (int r = 0; r < NB; ++r) {         // B: 128 rows x (X_KT / 8) x (8 bf16), twice
+            const int f = tid + 256 * r, row = f / (X_KT / 8), c8 = f % (X_KT / 8);
             const int gr = min(n0 + row, nlist - 1), gk = k0 + c8 * 8;
             const bool in = gk < d;
             pbh[r] = in ? *reinterpret_cast<const uint4*>(Chi + (int64_t)gr * d + gk) : make_uint4(0u, 0u, 0u, 0u);
@@ -198,8 +201,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
     for (int k0 = 0; k0 < d; k0 += X_KT) {
         __syncthreads();  // previous tile fully consumed
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
+        for (int r = 0; r < NA; ++r) {
+            const int f = tid + 256 * r, row = f / (X_KT / 4), c4 = f % (X_KT / 4);
             const float v[4] = {pa[r].x, pa[r].y, pa[r].z, pa[r].w};
             uint32_t hh[4], ll[4];
 #pragma unroll
@@ -211,8 +214,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
             *reinterpret_cast<uint2*>(Al + row * X_LS + c4 * 4) = make_uint2(ll[0] | (ll[1] << 16), ll[2] | (ll[3] << 16));
         }
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int f = tid + 256 * r, row = f >> 2, c8 = f & 3;
+        for (int r = 0; r < NB; ++r) {
+            const int f = tid + 256 * r, row = f / (X_KT / 8), c8 = f % (X_KT / 8);
             *reinterpret_cast<uint4*>(Bh + row * X_LS + c8 * 8) = pbh[r];
             *reinterpret_cast<uint4*>(Bl + row * X_LS + c8 * 8) = pbl[r];
         }
@@ -286,7 +289,10 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         const int nqt = (int)((nq + X_T - 1) / X_T), nct = (nlist + X_T - 1) / X_T;
         const int64_t grid = (int64_t)((nct + 7) / 8) * 8 * nqt;
         if (grid > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq * nlist too large");
-        coarse_gemm_split_kernel<<<(unsigned)grid, 256, 0, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S);
+        static OncePerDevice attr;
+        if (attr.first())
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
+        coarse_gemm_split_kernel<<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S);
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
