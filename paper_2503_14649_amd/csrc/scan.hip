@@ -884,7 +884,9 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
     auto gather = [&](int s0, int s1, int base_fill) {
         if (threadIdx.x == 0) s_cnt = base_fill;
         __syncthreads();
-        for (int s = s0 + threadIdx.x; s < s1; s += MERGE_THREADS) {
+        // a wave per slot, a lane per entry: the entries of a slot (up to k) are read side by side instead of one
+        // after the other by one thread (each read is a trip to memory, and the id read depends on the row read)
+        for (int s = s0 + (int)(threadIdx.x >> 6); s < s1; s += MERGE_THREADS / 64) {
             int lo = 0, hi = P.nprobe;     // probe p with s_pre[p] <= s < s_pre[p + 1]
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
@@ -892,7 +894,7 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
             }
             const int64_t gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (s - s_pre[lo]);
             const int n = P.part_cnt[gs];
-            for (int r = 0; r < n; ++r) {
+            for (int r = threadIdx.x & 63; r < n; r += 64) {
                 const int32_t I = P.part_I[gs * k + r];
                 if (I >= tau) {
                     const int o = atomicAdd(&s_cnt, 1);
