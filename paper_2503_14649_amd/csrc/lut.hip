@@ -133,6 +133,7 @@ __global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict_
     const float range = __uint_as_float(range_bits[q]);
     const float dq = lut_step(range);
     const double eta = lut_eta(range, __uint_as_float(mag_bits[q]), dq);
+    const double inv_dq = 1.0 / (double)dq;
     const double* Tq = T64 + q * m * KSUB + c;
     const int S = rago_steps(m), planes = rago_planes(m);
     for (int plane = 0; plane < planes; ++plane) {
@@ -143,7 +144,7 @@ __global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict_
         for (int slot = 0; slot < 32; ++slot) {
             if (slot >= S) continue;
             const int j = plane * 32 + slot;
-            const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) / (double)dq;
+            const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) * inv_dq;   // (2^-52 relative off the quotient: far inside eta)
             double r = rint(u);
             r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
             row[slot >> 2] |= (uint32_t)r << (8 * (slot & 3));
