@@ -103,30 +103,38 @@ __device__ __forceinline__ void wave_min_max(float& mn, float& mx) {
 template <int DSUB>
 __global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                           const float* __restrict__ cbmax, const int32_t* __restrict__ probes,
-                                                          int nprobe, int d, int m, float* __restrict__ rec) {
+                                                          int64_t npairs, int nprobe, int d, int m, float* __restrict__ rec) {
     constexpr int RS = DSUB + 4;
-    const int64_t pair = blockIdx.x;
-    const int64_t q = pair / nprobe;
-    const int l = probes[pair];
-    const float* qv = Q + q * d;
-    const float* cv = C + (int64_t)l * d;
-    for (int j = threadIdx.x; j < m; j += 256) {
-        float* e = rec + (pair * m + j) * RS;
-        float rr = 0.0f, M = 0.0f;
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one thread per (pair, sub-quantiser)
+    if (g >= npairs * m) return;
+    const int64_t pair = g / m;
+    const int j = (int)(g - pair * m);
+    const float* qv = Q + (pair / nprobe) * d + j * DSUB;
+    const float* cv = C + (int64_t)probes[pair] * d + j * DSUB;
+    float q[DSUB], c[DSUB];
 #pragma unroll
-        for (int t = 0; t < DSUB; ++t) {
-            const int x = j * DSUB + t;
-            const float r = qv[x] - cv[x];
-            e[t] = r;
-            rr = __fmaf_rn(r, r, rr);
-            const float a = fabsf(qv[x]) + fabsf(cv[x]) + cbmax[x];
-            M = __fmaf_rn(a, a, M);
-        }
-        e[DSUB] = rr;
-        e[DSUB + 1] = 2.0f * (float)(DSUB + 6) * (L2F_U * M + 1.17549435e-38f);   // (+ one smallest normal number per operation: underflow)
-        e[DSUB + 2] = 0.0f;
-        e[DSUB + 3] = 0.0f;
+    for (int t = 0; t < DSUB; t += 4) {
+        const float4 a = *reinterpret_cast<const float4*>(qv + t), b = *reinterpret_cast<const float4*>(cv + t);
+        q[t] = a.x; q[t + 1] = a.y; q[t + 2] = a.z; q[t + 3] = a.w;
+        c[t] = b.x; c[t + 1] = b.y; c[t + 2] = b.z; c[t + 3] = b.w;
     }
+    float out[RS];
+    float rr = 0.0f, M = 0.0f;
+#pragma unroll
+    for (int t = 0; t < DSUB; ++t) {
+        const float r = q[t] - c[t];
+        out[t] = r;
+        rr = __fmaf_rn(r, r, rr);
+        const float a = fabsf(q[t]) + fabsf(c[t]) + cbmax[j * DSUB + t];
+        M = __fmaf_rn(a, a, M);
+    }
+    out[DSUB] = rr;
+    out[DSUB + 1] = 2.0f * (float)(DSUB + 6) * (L2F_U * M + 1.17549435e-38f);   // (+ one smallest normal number per operation: underflow)
+    out[DSUB + 2] = 0.0f;
+    out[DSUB + 3] = 0.0f;
+    float4* e = reinterpret_cast<float4*>(rec + g * RS);
+#pragma unroll
+    for (int t = 0; t < RS; t += 4) e[t / 4] = make_float4(out[t], out[t + 1], out[t + 2], out[t + 3]);
 }
 
 // ---- pass 1
@@ -436,7 +444,7 @@ int launch_l2f(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     const size_t lds1 = (size_t)P * m * 8 + (size_t)L2F_LIST * 4;
     const size_t lds2 = (size_t)L2Q_LIST * 4 + (size_t)L2Q_PAIRS * m * (DSUB + 4) * 4;     // <= 42 KB
     const unsigned grid = (unsigned)((npairs + P - 1) / P), grid2 = (unsigned)((npairs + L2Q_PAIRS - 1) / L2Q_PAIRS);
-    l2f_prepare_kernel<DSUB><<<(unsigned)npairs, 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, nprobe, d, m, rec);
+    l2f_prepare_kernel<DSUB><<<(unsigned)((npairs * m + 255) / 256), 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, npairs, nprobe, d, m, rec);
     l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
                                                                d, m, lo, range_bits, ws.counters.as<int64_t>());
     if (out_LUT8)
