@@ -884,23 +884,69 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
     auto gather = [&](int s0, int s1, int base_fill) {
         if (threadIdx.x == 0) s_cnt = base_fill;
         __syncthreads();
-        // a wave per slot, a lane per entry: the entries of a slot (up to k) are read side by side instead of one
-        // after the other by one thread (each read is a trip to memory, and the id read depends on the row read)
-        for (int s = s0 + (int)(threadIdx.x >> 6); s < s1; s += MERGE_THREADS / 64) {
-            int lo = 0, hi = P.nprobe;     // probe p with s_pre[p] <= s < s_pre[p + 1]
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (s_pre[mid] <= s) lo = mid; else hi = mid;
-            }
-            const int64_t gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (s - s_pre[lo]);
-            const int n = P.part_cnt[gs];
-            for (int r = threadIdx.x & 63; r < n; r += 64) {
-                const int32_t I = P.part_I[gs * k + r];
-                if (I >= tau) {
-                    const int o = atomicAdd(&s_cnt, 1);
-                    if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[gs * k + r]]; }
+        // 256 slots at a time, dealt to the four waves in turn; a lane reads its slot's count, a scan over the wave
+        // turns the 64 counts into offsets, and then the wave's lanes share out ALL entries of its 64 slots evenly
+        // (entry e belongs to the slot whose offset range holds e).  A thread per slot would walk up to k entries
+        // one after the other, each a dependent trip to memory; a wave per slot idles when slots hold few entries.
+        __shared__ int s_wpre[MERGE_THREADS / 64][64];
+        __shared__ int64_t s_wgs[MERGE_THREADS / 64][64];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        if (k <= 16 && s1 - s0 > 4 * MERGE_THREADS) {
+            // many slots of few entries each (small k, many probes and chunks): a thread per slot has less to wait for
+            for (int sl = s0 + (int)threadIdx.x; sl < s1; sl += MERGE_THREADS) {
+                int lo = 0, hi = P.nprobe;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_pre[mid] <= sl) lo = mid; else hi = mid;
+                }
+                const int64_t gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (sl - s_pre[lo]);
+                const int n = P.part_cnt[gs];
+                for (int r = 0; r < n; ++r) {
+                    const int32_t I = P.part_I[gs * k + r];
+                    if (I >= tau) {
+                        const int o = atomicAdd(&s_cnt, 1);
+                        if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[gs * k + r]]; }
+                    }
                 }
             }
+        } else
+        for (int b = s0; b < s1; b += MERGE_THREADS) {
+            const int sl = b + lane * (MERGE_THREADS / 64) + wave;
+            int n = 0;
+            int64_t gs = 0;
+            if (sl < s1) {
+                int lo = 0, hi = P.nprobe;     // probe p with s_pre[p] <= sl < s_pre[p + 1]
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_pre[mid] <= sl) lo = mid; else hi = mid;
+                }
+                gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (sl - s_pre[lo]);
+                n = P.part_cnt[gs];
+            }
+            int inc = n;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(inc, o);
+                if (lane >= o) inc += v;
+            }
+            const int total = __shfl(inc, 63);
+            s_wpre[wave][lane] = inc - n;
+            s_wgs[wave][lane] = gs;
+            __builtin_amdgcn_wave_barrier();       // (a wave's LDS operations complete in order; this only pins the compiler)
+            for (int e = lane; e < total; e += 64) {
+                int lo = 0, hi = 64;               // the last slot whose offset is <= e (empty slots share an offset with their successor)
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_wpre[wave][mid] <= e) lo = mid; else hi = mid;
+                }
+                const int64_t g = s_wgs[wave][lo];
+                const int r = e - s_wpre[wave][lo];
+                const int32_t I = P.part_I[g * k + r];
+                if (I >= tau) {
+                    const int o = atomicAdd(&s_cnt, 1);
+                    if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[g * k + r]]; }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
         return s_cnt;
