@@ -421,7 +421,7 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
     const int64_t npairs = nq * nprobe;
     int rc;
     if ((rc = ws.tmp_lut8sw.reserve((size_t)npairs * LUT_BYTES))) return rc;
-    if ((rc = ws.pair_lo.reserve((size_t)npairs * m * 8))) return rc;         // per-(pair, sub-quantiser) minima (fp32)
+    if ((rc = ws.pair_lo.reserve((size_t)(npairs + 32) * m * 8))) return rc;  // per-(pair, sub-quantiser) minima (fp32; the fast path rounds the pairs up to 32)
     if ((rc = ws.Tmax.reserve((size_t)nq * m * 8 + (size_t)nq * 8))) return rc;   // the range words live behind the fp64 maxima
     if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
@@ -449,7 +449,7 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
     if (fast) {
         if (out_L_f32) {           // start the fast path from scratch, so that it is what the caller's tables come from
             fill_u32_kernel<<<(unsigned)std::min<int64_t>(1024, (nq + 255) / 256), 256, 0, st>>>(range_bits, 0u, nq);
-            fill_u32_kernel<<<(unsigned)std::min<int64_t>(4096, (npairs * m + 255) / 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(lo), 0x7fc00000u, npairs * m);
+            fill_u32_kernel<<<(unsigned)std::min<int64_t>(4096, ((npairs + 32) * m + 255) / 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(lo), 0x7fc00000u, (npairs + 32) * m);
         }
         if ((rc = launch_lut_l2_fast(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st))) return rc;
     }

@@ -4,38 +4,48 @@
 // The entry is DEFINED by an fp64 accumulation rounded once to fp32, and everything derived from it
 // (sub-table minima, the query's step, the 8-bit codes) must come out as from that definition.
 // Evaluating all m*256 entries of all pairs twice in fp64 costs ~5 fp64-rate operations per term.
-// Here both passes evaluate in fp32 with a proven error bound and go back to the fp64 definition
-// only for the entries whose outcome the bound cannot decide:
+// Here both passes evaluate in fp32 on the matrix cores with a proven error bound and go back to the
+// fp64 definition only for the entries whose outcome the bound cannot decide.
 //
-//   fp32 evaluation  r_t = fl(q_t - c_t), L~ = fl(fma(2, dot, -rr) - cc) with dot = <r, cb> and
-//   rr = |r|^2 by fma chains and cc = fl(|cb|^2): the chains err by at most dsub u times the sum of
-//   the absolute terms, the two last roundings and cc by u each, the rounding of r_t by 2 u:
-//   |L~ - L64| <= (dsub + 4) u M,  M = sum_t (|q_t| + |c_t| + max_c |cb_t|)^2,  u = 2^-24;
-//   E = 2 (dsub + 6) (u M + 2^-126) is used: twice the bound, which also covers the rounding of E itself, plus
-//   the smallest normal number per operation, which covers results that underflow.
+//   The contraction.  Per sub-quantiser j the table of 32 pairs is a product of a [256 x K] and a [K x 32]
+//   matrix with K = dsub + 2:
+//       codeword side  a = (cb_0 .. cb_{dsub-1}, 1, |cb|^2)          (|cb|^2: fp64 sum, one rounding)
+//       pair side      b = (2 r_0 .. 2 r_{dsub-1}, -|r|^2, -1)       (r_t = fl(q_t - c_t), |r|^2 by an fma chain)
+//       L~ = sum_k a_k b_k = 2 <r, cb> - |r|^2 - |cb|^2
+//   on v_mfma_f32_32x32x2_f32 (rows = codewords, columns = pairs).  That instruction accumulates like a
+//   chain of fmaf in k order (checked bit for bit on 4e5 random products including subnormal ones), so with
+//   x_t = q_t - c_t exact, y_t = cb_t, u = 2^-24:
+//       inputs:  |2 r_t y_t - 2 x_t y_t| <= 2u |x_t||y_t|;  | |r|^2 - sum x_t^2 | <= (dsub + 2) u sum x_t^2;
+//                | fl|cb|^2 - sum y_t^2 | <= u sum y_t^2
+//       chain:   K roundings, each relative to a partial sum of absolute value <= sum_k |a_k b_k|
+//                <= (dsub + 2) u (2 sum |x||y| + sum x^2 + sum y^2)
+//       |L~ - L64| <= (2 dsub + 4) u M (1 + 1e-5),   M = sum_t (|q_t| + |c_t| + max_c |cb_t|)^2.
+//   E = (3 dsub + 8) (u M + 2^-126) is used: at least 1.5 times the bound (which also covers the rounding of
+//   M and E themselves) plus a smallest normal number per operation for results that underflow.  Overflow
+//   gives infinities or NaNs, which every comparison below treats as "undecided".
 //
-//   pass 1 (minima, range): the entry attaining the exact minimum of a sub-table has
-//   L~ <= min L~ + 2E, so the exact minimum is the least fp32(fp64) value among those candidates;
-//   same for the maximum.  Typically 2-4 candidates per sub-table.
-//   pass 2 (codes): b~ = (L~ - lo) * (1/dq) differs from the defining fp32 value
-//   b = fl(fl(L - lo) / dq) by at most eta = (E + u M)/dq + 2^-13; if b~ is farther than eta from
-//   every half-integer, rint(b~) = rint(b).  Otherwise (about one entry in a thousand) the entry
-//   is put on a list and evaluated by the definition.
+//   pass 1 (minima, range): the entry attaining the exact minimum of a sub-table has L~ <= min L~ + 2E, so
+//   the exact minimum is the least fp32(fp64) value among those candidates; same for the maximum.  The
+//   minimum is taken as a running one over the eight tiles of 32 codewords, which only adds candidates
+//   (about 6 per sub-table).
+//   pass 2 (codes): b~ = fma(L~, 1/dq, fl(-lo/dq)) differs from the defining fp32 value
+//   b = fl(fl(L - lo) / dq) by at most (E + 4 u M)/dq + 3 * 2^-16 (L~ against L64: E; L64 against its fp32
+//   rounding L, the rounding of 1/dq applied to L~ <= M, and the two roundings in fl(-lo/dq) with |lo| <= M:
+//   u M each; the roundings of b~ and b: 3 u 256); eta = E (1 + 4/(3 dsub + 8)) 1.001/dq + 2^-13 is used.
+//   If b~ is farther than eta from every half-integer, rint(b~) = rint(b): v_cvt_pk_u8_f32 (round to nearest
+//   even, clamped to 0..255, NaN -> 0) writes it into its byte.  Otherwise (one entry in ~300) the entry goes
+//   on a list and is evaluated by the definition afterwards, all lanes busy.
 //
-// Candidates and undecided entries are collected in LDS and evaluated afterwards with all lanes
-// busy.  If a list overflows (tables that are flat relative to their magnitude make every entry
-// undecidable) the workgroup evaluates all its entries by the definition.
+// If a list overflows (tables that are flat relative to their magnitude make every entry undecidable) the
+// workgroup evaluates all the entries concerned by the definition.
 //
-// A workgroup handles P consecutive pairs so that one load of a codeword serves P tables (the
-// codebooks are the same for every pair; one pair per workgroup re-reads m*256*dsub*4 bytes from
-// L2 per pair and pass).  What is the same for all lanes (r_j, |r_j|^2, E, the minimum) is written
-// per pair by a small kernel first and read with uniform addresses, so it arrives in scalar
-// registers and costs neither LDS reads nor vector instructions; wave reductions use DPP moves.
-// Pass 1: wave = sub-quantiser, lane = codewords lane + 64 i (min/max are
-// lane-local over i, then one wave reduction).  Pass 2: wave = (plane, 64 codewords), lane =
-// codeword, loop over the 32 slots of the plane, the 32 code bytes of (codeword, plane) packed in
-// registers and written with two 16-byte stores per lane: the plane-major table
-// [plane][codeword][slot] goes to HBM coalesced without a copy in LDS.
+// Layout.  Both operand sides are stored per (row, half): a lane of the MFMA supplies, for its row or column
+// (lane mod 32), the k values of its half (lane / 32): KH = dsub/2 + 1 of them, in a slot of KS = KH + 1
+// floats (8-byte aligned; the spare float of a pair-side slot holds E).  Pass 1: workgroup = 64 pairs, wave
+// = sub-quantiser, loop over the 8 tiles of 32 codewords, each codeword load serving both column tiles;
+// pass 2: workgroup = 64 pairs, wave = (column tile, 16 sub-quantisers), loop over the 8 codeword tiles;
+// a lane holds column = pair and 16 codewords, packs their 16 code bytes and writes 16 bytes per
+// (pair, codeword) into the plane-major table [plane][codeword][slot].
 #include "rago_internal.h"
 #include "lut_common.h"
 
@@ -43,9 +53,23 @@ namespace rago {
 
 namespace {
 
-constexpr int L2F_THREADS = 256;
-constexpr int L2F_LIST = 4096;          // list entries (4 bytes each) per workgroup
-constexpr float L2F_U = 5.9604644775390625e-08f;   // 2^-24
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int L2M_THREADS = 256;
+constexpr int L2M_PAIRS = 64;           // pairs per workgroup (two column tiles)
+constexpr int L2M_LIST1 = 1024;         // pass 1: candidates per wave and round (its sub-quantiser, 64 pairs: ~400)
+constexpr int L2M_LIST2 = 2048;         // pass 2: undecided entries per wave (of 393 216 per three units: ~1300)
+constexpr int L2M_AHEAD = 4;          // pass 2: operands are requested this many steps ahead (1, 2 or 4)
+constexpr int L2M_TRS = 8 * 16 + 16;    // pass 2: bytes per pair in the transposition buffer (16 bytes of padding: no bank conflicts)
+constexpr float L2M_U = 5.9604644775390625e-08f;   // 2^-24
+
+template <int DSUB>
+struct L2M {
+    static_assert(DSUB % 2 == 0, "two halves");
+    static constexpr int KH = DSUB / 2 + 1;      // k values per half = MFMA steps per tile
+    static constexpr int KS = KH + 1;            // floats per (row, half) slot
+    static constexpr float CE = (float)(3 * DSUB + 8);
+};
 
 __device__ __forceinline__ uint32_t okey(float f) {            // order-preserving map float -> uint32
     const uint32_t u = __float_as_uint(f);
@@ -55,159 +79,172 @@ __device__ __forceinline__ float okey_inv(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// One entry of the packed codebook: DSUB coordinates, then the squared norm (and three unused floats, so that an
-// entry is a whole number of 16-byte loads from one address).
-template <int DSUB>
-__device__ __forceinline__ void load_codeword(const float* __restrict__ cbx, uint32_t entry, float (&v)[DSUB], float& cc) {
-    static_assert(DSUB % 4 == 0, "16-byte loads");
-    const float4* p = reinterpret_cast<const float4*>(cbx + entry * (uint32_t)(DSUB + 4));
+// Pair-side operands and sub-table minima are stored per tile of 32 consecutive pairs, so that what the 64 lanes of
+// a wave load together is contiguous: slot (pair, j, half) and minimum (pair, j).
+__device__ __forceinline__ int64_t rec_slot(int64_t pair, int j, int half, int m) { return (((pair >> 5) * m + j) * 2 + half) * 32 + (pair & 31); }
+__device__ __forceinline__ int64_t lo_index(int64_t pair, int j, int m) { return ((pair >> 5) * m + j) * 32 + (pair & 31); }
+
+template <int KS>
+__device__ __forceinline__ void load_slot(const float* __restrict__ p, float (&v)[KS]) {
+    static_assert(KS % 2 == 0, "8-byte loads");
 #pragma unroll
-    for (int t = 0; t < DSUB; t += 4) {
-        const float4 x = p[t / 4];
-        v[t] = x.x; v[t + 1] = x.y; v[t + 2] = x.z; v[t + 3] = x.w;
+    for (int t = 0; t < KS; t += 2) {
+        const float2 x = *reinterpret_cast<const float2*>(p + t);
+        v[t] = x.x; v[t + 1] = x.y;
     }
-    cc = p[DSUB / 4].x;
 }
 
-// -|r - cb|^2 = 2 <r, cb> - |r|^2 - |cb|^2 with the two norms precomputed: dsub + 2 operations.  `r` and `rr`
-// are the same for all lanes (they sit in scalar registers).
-template <int DSUB>
-__device__ __forceinline__ float l2_approx(const float* __restrict__ r, float rr, const float (&cb)[DSUB], float cc) {
-    float dot = 0.0f;
+// One 32 x 32 tile: rows = the codewords of `a`, columns = the pairs of `b`.  Lane l holds column l mod 32 and
+// rows tile_row(i, l / 32), i = 0..15.
+template <int KH, int KS>
+__device__ __forceinline__ f32x16 tile_product(const float (&a)[KS], const float (&b)[KS]) {
+    f32x16 acc = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int t = 0; t < DSUB; ++t) dot = __fmaf_rn(r[t], cb[t], dot);
-    return __fmaf_rn(2.0f, dot, -rr) - cc;
+    for (int s = 0; s < KH; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s], acc, 0, 0, 0);
+    return acc;
 }
+__device__ __forceinline__ int tile_row(int i, int half) { return (i >> 2) * 8 + half * 4 + (i & 3); }
 
-// Cross-lane moves inside the vector ALU (no LDS traffic): value of another lane of the same row of 16,
-// or of the last lane of the previous row(s); lanes the pattern does not reach keep their own value.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_mov(float v) {
-    const int x = __builtin_bit_cast(int, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, ROW_MASK, 0xF, false));
-}
-// Minimum and maximum over the 64 lanes, returned in every lane.
-__device__ __forceinline__ void wave_min_max(float& mn, float& mx) {
-    mn = fminf(mn, dpp_mov<0xB1, 0xF>(mn));  mx = fmaxf(mx, dpp_mov<0xB1, 0xF>(mx));     // lane ^ 1
-    mn = fminf(mn, dpp_mov<0x4E, 0xF>(mn));  mx = fmaxf(mx, dpp_mov<0x4E, 0xF>(mx));     // lane ^ 2
-    mn = fminf(mn, dpp_mov<0x141, 0xF>(mn)); mx = fmaxf(mx, dpp_mov<0x141, 0xF>(mx));    // mirror inside each 8
-    mn = fminf(mn, dpp_mov<0x140, 0xF>(mn)); mx = fmaxf(mx, dpp_mov<0x140, 0xF>(mx));    // mirror inside each 16: rows done
-    mn = fminf(mn, dpp_mov<0x142, 0xA>(mn)); mx = fmaxf(mx, dpp_mov<0x142, 0xA>(mx));    // rows 1, 3 <- last lane of rows 0, 2
-    mn = fminf(mn, dpp_mov<0x143, 0xC>(mn)); mx = fmaxf(mx, dpp_mov<0x143, 0xC>(mx));    // rows 2, 3 <- lane 31: lane 63 holds all
-    mn = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mn), 63));
-    mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
-}
-
-// Per (pair, sub-quantiser) one record of DSUB + 4 floats: r[t] = fl(q_t - c_t), |r|^2 (fp32), the bound E,
-// and two fields that pass 2 fills in while it copies its records to LDS.
+// Per (pair, sub-quantiser) the pair-side operand: two slots of KS floats (see the head of the file).
 template <int DSUB>
-__global__ void __launch_bounds__(256) l2f_prepare_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+__global__ void __launch_bounds__(256) l2m_prepare_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                           const float* __restrict__ cbmax, const int32_t* __restrict__ probes,
                                                           int64_t npairs, int nprobe, int d, int m, float* __restrict__ rec) {
-    constexpr int RS = DSUB + 4;
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one thread per (pair, sub-quantiser)
-    if (g >= npairs * m) return;
-    const int64_t pair = g / m;
-    const int j = (int)(g - pair * m);
+    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, H = DSUB / 2;
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one thread per (tile of 32 pairs, sub-quantiser, pair in the tile)
+    const int64_t tj = g >> 5;
+    const int64_t pair = (tj / m) * 32 + (g & 31);
+    const int j = (int)(tj % m);
+    if (pair >= npairs) return;
     const float* qv = Q + (pair / nprobe) * d + j * DSUB;
     const float* cv = C + (int64_t)probes[pair] * d + j * DSUB;
-    float q[DSUB], c[DSUB];
-#pragma unroll
-    for (int t = 0; t < DSUB; t += 4) {
-        const float4 a = *reinterpret_cast<const float4*>(qv + t), b = *reinterpret_cast<const float4*>(cv + t);
-        q[t] = a.x; q[t + 1] = a.y; q[t + 2] = a.z; q[t + 3] = a.w;
-        c[t] = b.x; c[t + 1] = b.y; c[t + 2] = b.z; c[t + 3] = b.w;
-    }
-    float out[RS];
+    float out[2 * KS];
     float rr = 0.0f, M = 0.0f;
 #pragma unroll
     for (int t = 0; t < DSUB; ++t) {
-        const float r = q[t] - c[t];
-        out[t] = r;
+        const float q = qv[t], c = cv[t];
+        const float r = q - c;
+        out[(t / H) * KS + (t % H)] = 2.0f * r;
         rr = __fmaf_rn(r, r, rr);
-        const float a = fabsf(q[t]) + fabsf(c[t]) + cbmax[j * DSUB + t];
+        const float a = fabsf(q) + fabsf(c) + cbmax[j * DSUB + t];
         M = __fmaf_rn(a, a, M);
     }
-    out[DSUB] = rr;
-    out[DSUB + 1] = 2.0f * (float)(DSUB + 6) * (L2F_U * M + 1.17549435e-38f);   // (+ one smallest normal number per operation: underflow)
-    out[DSUB + 2] = 0.0f;
-    out[DSUB + 3] = 0.0f;
-    float4* e = reinterpret_cast<float4*>(rec + g * RS);
+    const float E = L2M<DSUB>::CE * (L2M_U * M + 1.17549435e-38f);
+    out[KH - 1] = -rr;       out[KH] = E;
+    out[KS + KH - 1] = -1.0f; out[KS + KH] = E;
 #pragma unroll
-    for (int t = 0; t < RS; t += 4) e[t / 4] = make_float4(out[t], out[t + 1], out[t + 2], out[t + 3]);
+    for (int h = 0; h < 2; ++h) {
+        float2* e = reinterpret_cast<float2*>(rec + rec_slot(pair, j, h, m) * KS);
+#pragma unroll
+        for (int t = 0; t < KS; t += 2) e[t / 2] = make_float2(out[h * KS + t], out[h * KS + t + 1]);
+    }
 }
 
 // ---- pass 1
-template <int DSUB, int P>
-__global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+template <int DSUB>
+__global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
                                                                 int m, float* __restrict__ lo_out, uint32_t* __restrict__ range_bits,
                                                                 int64_t* __restrict__ counters) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    uint32_t* lo_key = reinterpret_cast<uint32_t*>(smem);            // [P][m]
-    uint32_t* hi_key = lo_key + P * m;                               // [P][m]
-    uint32_t* list = hi_key + P * m;                                 // [L2F_LIST]  p << 16 | j << 8 | c
-    __shared__ int nlist;
+    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = L2M_PAIRS;
+    __shared__ uint32_t lo_key[P * 4], hi_key[P * 4];        // this round's four sub-quantisers
+    __shared__ uint32_t list[4][L2M_LIST1];                  // per wave: pair << 16 | j << 8 | codeword
+    __shared__ int s_cnt[4];
     __shared__ float s_rng[P];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
-    for (int idx = threadIdx.x; idx < P * m; idx += L2F_THREADS) { lo_key[idx] = 0xFFFFFFFFu; hi_key[idx] = 0u; }
-    if (threadIdx.x == 0) nlist = 0;
+    lo_key[threadIdx.x] = 0xFFFFFFFFu; hi_key[threadIdx.x] = 0u;       // (P * 4 = L2M_THREADS)
     if (threadIdx.x < P) s_rng[threadIdx.x] = 0.0f;
-    __syncthreads();
-    constexpr int RS = DSUB + 4;
-    const float* rec0 = rec + pair0 * m * RS;
+    unsigned long long evaluated = 0, overflows = 0;                   // thread 0's tally
+    const float inf = __builtin_inff();
 
-    for (int j = wave; j < m; j += 4) {
-        float cb[4][DSUB], cc[4];
+    for (int j0 = 0; j0 < m; j0 += 4) {
+        __syncthreads();                                               // keys reset, the previous round's list consumed
+        const int j = j0 + wave;
+        float bv[2][KS];
+        int pl[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_codeword<DSUB>(cbx, (uint32_t)(j * KSUB + lane + 64 * i), cb[i], cc[i]);
+        for (int ct = 0; ct < 2; ++ct) {
+            pl[ct] = ct * 32 + col;
+            load_slot<KS>(rec + rec_slot(pair0 + min(pl[ct], np - 1), j, half, m) * KS, bv[ct]);
+        }
+        float rmn[2] = {inf, inf}, rmx[2] = {-inf, -inf};
+        int cnt = 0;                                                   // wave-uniform: entries on this wave's list
+        float av[KS];
+        load_slot<KS>(cbx + (((uint32_t)j * KSUB + col) * 2 + half) * KS, av);
+#pragma unroll 1
+        for (int t = 0; t < 8; ++t) {
+            float an[KS];
+            load_slot<KS>(cbx + (((uint32_t)j * KSUB + min(t + 1, 7) * 32 + col) * 2 + half) * KS, an);
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            if (p < np) {
-                const float* e = rec0 + (uint32_t)((p * m + j) * RS);       // same address in all lanes: scalar loads
-                float v[4];
+            for (int ct = 0; ct < 2; ++ct) {
+                const f32x16 v = tile_product<KH, KS>(av, bv[ct]);
+                float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
+                mn = fminf(mn, fminf(fminf(fminf(v[8], v[9]), fminf(v[10], v[11])), fminf(fminf(v[12], v[13]), fminf(v[14], v[15]))));
+                float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+                mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(v[8], v[9]), fmaxf(v[10], v[11])), fmaxf(fmaxf(v[12], v[13]), fmaxf(v[14], v[15]))));
+                mn = fminf(mn, __shfl_xor(mn, 32));                    // the column's other 16 rows
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                rmn[ct] = fminf(rmn[ct], mn);
+                rmx[ct] = fmaxf(rmx[ct], mx);
+                const float marg = 2.0f * bv[ct][KH];
+                const float lo_cut = rmn[ct] + marg, hi_cut = rmx[ct] - marg;
+                uint32_t mask = 0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = l2_approx<DSUB>(e, e[DSUB], cb[i], cc[i]);
-                float mn = fminf(fminf(v[0], v[1]), fminf(v[2], v[3]));
-                float mx = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-                wave_min_max(mn, mx);
-                const float marg = 2.0f * e[DSUB + 1];
-                const float lo_cut = mn + marg, hi_cut = mx - marg;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (!(v[i] > lo_cut && v[i] < hi_cut)) {          // (written so that a NaN anywhere means "candidate")
-                        const int pos = atomicAdd(&nlist, 1);
-                        if (pos < L2F_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | (lane + 64 * i));
+                for (int i = 0; i < 16; ++i) mask |= (!(v[i] > lo_cut && v[i] < hi_cut) ? 1u : 0u) << i;   // (a NaN anywhere: candidate)
+                if (pl[ct] >= np) mask = 0;
+                // Lanes with candidates append them to the wave's list, one per lane and turn: positions from a
+                // ballot, the count in a scalar register, nothing to wait for.
+                while (true) {
+                    const uint64_t b = __builtin_amdgcn_ballot_w64(mask != 0);
+                    if (!b) break;
+                    if (mask) {
+                        const int i = __builtin_ctz(mask);
+                        mask &= mask - 1;
+                        const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0));
+                        if (pos < L2M_LIST1) list[wave][pos] = (uint32_t)(pl[ct] << 16 | j << 8 | (t * 32 + tile_row(i, half)));
                     }
+                    cnt += __builtin_popcountll(b);
                 }
             }
+#pragma unroll
+            for (int x = 0; x < KS; ++x) av[x] = an[x];
         }
-    }
-    __syncthreads();
-    const int n = nlist;
-    const bool all = n > L2F_LIST;                 // undecidable almost everywhere: evaluate every entry by the definition
-    const int total = all ? np * m * KSUB : n;
-    for (int e = threadIdx.x; e < total; e += L2F_THREADS) {
-        const uint32_t w = all ? (uint32_t)((e / (m * KSUB)) << 16 | ((e / KSUB) % m) << 8 | (e % KSUB)) : list[e];
-        const int p = w >> 16, j = (w >> 8) & 255, c = w & 255;
-        const int64_t q = (pair0 + p) / nprobe;
-        const int l = probes[pair0 + p];
-        const float L = l2_entry<DSUB>(Q + q * d + j * DSUB, C + (int64_t)l * d + j * DSUB, CB + ((int64_t)j * KSUB + c) * DSUB, DSUB);
-        const uint32_t k = okey(L);
-        atomicMin(&lo_key[p * m + j], k);
-        atomicMax(&hi_key[p * m + j], k);
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < np * m; idx += L2F_THREADS) {
-        const int p = idx / m;
-        const float lo = okey_inv(lo_key[idx]), hi = okey_inv(hi_key[idx]);
-        lo_out[(pair0 + p) * m + (idx - p * m)] = lo;
-        const float rng = hi - lo;
-        if (rng > 0.0f) atomicMax(reinterpret_cast<uint32_t*>(&s_rng[p]), __float_as_uint(rng));
+        if (lane == 0) s_cnt[wave] = cnt;
+        __syncthreads();
+        // The candidates by the definition; a wave whose list overflowed makes the round evaluate every entry.
+        const int c0 = s_cnt[0], c1 = s_cnt[1], c2 = s_cnt[2], c3 = s_cnt[3];
+        const bool all = c0 > L2M_LIST1 || c1 > L2M_LIST1 || c2 > L2M_LIST1 || c3 > L2M_LIST1;
+        const int total = all ? np * 4 * KSUB : c0 + c1 + c2 + c3;
+        for (int e = threadIdx.x; e < total; e += L2M_THREADS) {
+            uint32_t w;
+            if (all) w = (uint32_t)((e / (4 * KSUB)) << 16 | (j0 + (e / KSUB) % 4) << 8 | (e % KSUB));
+            else w = e < c0 ? list[0][e] : e < c0 + c1 ? list[1][e - c0] : e < c0 + c1 + c2 ? list[2][e - c0 - c1] : list[3][e - c0 - c1 - c2];
+            const int p = w >> 16, jj = (w >> 8) & 255, c = w & 255;
+            const int64_t q = (pair0 + p) / nprobe;
+            const int l = probes[pair0 + p];
+            const float L = l2_entry<DSUB>(Q + q * d + jj * DSUB, C + (int64_t)l * d + jj * DSUB, CB + ((int64_t)jj * KSUB + c) * DSUB, DSUB);
+            const uint32_t k = okey(L);
+            atomicMin(&lo_key[p * 4 + (jj - j0)], k);
+            atomicMax(&hi_key[p * 4 + (jj - j0)], k);
+        }
+        __syncthreads();
+        {
+            const int p = threadIdx.x >> 2, jj = threadIdx.x & 3;
+            if (p < np) {
+                const float lo = okey_inv(lo_key[threadIdx.x]), hi = okey_inv(hi_key[threadIdx.x]);
+                lo_out[lo_index(pair0 + p, j0 + jj, m)] = lo;
+                const float rng = hi - lo;
+                if (rng > 0.0f) atomicMax(reinterpret_cast<uint32_t*>(&s_rng[p]), __float_as_uint(rng));
+            }
+            lo_key[threadIdx.x] = 0xFFFFFFFFu; hi_key[threadIdx.x] = 0u;
+        }
+        evaluated += (unsigned long long)total;
+        overflows += all ? 1ull : 0ull;
     }
     __syncthreads();
     if (threadIdx.x < np) {
@@ -215,120 +252,14 @@ __global__ void __launch_bounds__(L2F_THREADS) l2f_range_kernel(const float* __r
         if (rng > 0.0f) atomicMax(range_bits + (pair0 + threadIdx.x) / nprobe, __float_as_uint(rng));
     }
     if (threadIdx.x == 0) {
-        atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)total);
-        if (all) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), 1ull);
+        atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), evaluated);
+        if (overflows) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), overflows);
     }
 }
 
 // ---- pass 2
-constexpr int L2Q_THREADS = 128;        // two waves: a plane splits into two units of 128 codewords, two per lane
-constexpr int L2Q_PAIRS = 4;
-constexpr int L2Q_LIST = 2048;
-
-// One (plane, 128 codewords) unit of a workgroup's pairs: lane = codewords c and c + 64; per (lane, pair, codeword)
-// 32 code bytes in registers, written with two 16-byte stores.  One read of a record (LDS, the same address in all
-// lanes) serves two entries per lane.  FULL: all P pairs exist (no guards in the loop).
-template <int DSUB, int P, bool FULL, bool DBG>
-__device__ __forceinline__ void l2f_quant_unit(const float* __restrict__ cbx, const float* __restrict__ rec0,
-                                               int np, int m, int S, int plane, int c, const float (&inv)[P],
-                                               uint8_t* __restrict__ tab0, uint8_t* __restrict__ dbg0, uint32_t* __restrict__ list,
-                                               int* __restrict__ nlist) {
-    constexpr int RS = DSUB + 4;
-    // pk[p][i][0..7]: the 32 code bytes of (codeword c + 64 i, this plane) for pair p.  The words are produced in
-    // order and shifted in at the top, so that no register is indexed by a loop variable.
-    uint32_t pk[P][2][8];
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int w = 0; w < 8; ++w) pk[p][i][w] = 0u;
-    // Steps (sub-quantiser j, pair p) run j-major; the codewords of sub-quantiser j + 2 are requested while the P
-    // steps of j run (past the end of the plane: its last sub-quantiser again): a load from L2 takes longer than
-    // the steps of one sub-quantiser.
-    const int jfirst = plane * 32, jlast = plane * 32 + S - 1;
-    float cbc[2][DSUB], ccc[2], cbm[2][DSUB], ccm[2];          // codewords of sub-quantisers j and j + 1 (j + 2 is on its way)
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        load_codeword<DSUB>(cbx, (uint32_t)(jfirst * KSUB + c + 64 * i), cbc[i], ccc[i]);
-        load_codeword<DSUB>(cbx, (uint32_t)(min(jfirst + 1, jlast) * KSUB + c + 64 * i), cbm[i], ccm[i]);
-    }
-#pragma unroll 1
-    for (int w = 0; w < S / 4; ++w) {
-        uint32_t word[P][2];
-#pragma unroll
-        for (int p = 0; p < P; ++p) { word[p][0] = 0u; word[p][1] = 0u; }
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            const int j = jfirst + w * 4 + s4, jn = min(j + 2, jlast);
-            float cbn[2][DSUB], ccn[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) load_codeword<DSUB>(cbx, (uint32_t)(jn * KSUB + c + 64 * i), cbn[i], ccn[i]);
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                if (FULL || p < np) {
-                    const float* e = rec0 + (p * m + j) * RS;
-                    float r[DSUB];
-#pragma unroll
-                    for (int t = 0; t < DSUB; t += 4) {
-                        const float4 x = *reinterpret_cast<const float4*>(e + t);
-                        r[t] = x.x; r[t + 1] = x.y; r[t + 2] = x.z; r[t + 3] = x.w;
-                    }
-                    const float4 a = *reinterpret_cast<const float4*>(e + DSUB);     // |r|^2, E, minimum, eta
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const float Lt = l2_approx<DSUB>(r, a.x, cbc[i], ccc[i]);
-                        const float b = (Lt - a.z) * inv[p];
-                        const float rr = fminf(fmaxf(rintf(b), 0.0f), 255.0f);
-                        word[p][i] |= (uint32_t)rr << (8 * s4);
-                        // undecided (about one entry in a thousand): on the list
-                        if (!(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > a.w)) {      // (a NaN or infinite b~ or eta means "undecided")
-                            const int pos = atomicAdd(nlist, 1);
-                            if (pos < L2Q_LIST) list[pos] = (uint32_t)(p << 16 | j << 8 | (c + 64 * i));
-                        }
-                        if (DBG) dbg0[((int64_t)p * m + j) * KSUB + c + 64 * i] = (uint8_t)rr;
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-#pragma unroll
-                for (int t = 0; t < DSUB; ++t) { cbc[i][t] = cbm[i][t]; cbm[i][t] = cbn[i][t]; }
-                ccc[i] = ccm[i]; ccm[i] = ccn[i];
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-#pragma unroll
-                for (int x = 0; x < 7; ++x) pk[p][i][x] = pk[p][i][x + 1];
-                pk[p][i][7] = word[p][i];
-            }
-    }
-    if (S == 16) {                  // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) pk[p][i][x] = pk[p][i][x + 4];
-    }
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        if (FULL || p < np) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                uint4* dst = reinterpret_cast<uint4*>(tab0 + (int64_t)p * LUT_BYTES + (int64_t)plane * LUT_PLANE + (c + 64 * i) * 32);
-                dst[0] = make_uint4(pk[p][i][0], pk[p][i][1], pk[p][i][2], pk[p][i][3]);
-                dst[1] = make_uint4(pk[p][i][4], pk[p][i][5], pk[p][i][6], pk[p][i][7]);
-            }
-        }
-    }
-}
-
 template <int DSUB, bool DBG>
-__global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+__global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
@@ -336,63 +267,131 @@ __global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __r
                                                                 uint8_t* __restrict__ tables, int32_t* __restrict__ bias,
                                                                 float* __restrict__ delta, uint8_t* __restrict__ out_LUT8,
                                                                 int64_t* __restrict__ counters) {
-    constexpr int P = L2Q_PAIRS;
+    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = L2M_PAIRS;
     extern __shared__ __align__(16) uint8_t smem[];
-    uint32_t* list = reinterpret_cast<uint32_t*>(smem);                        // [L2Q_LIST]
-    float* rec_s = reinterpret_cast<float*>(smem + L2Q_LIST * 4);              // [P][m][DSUB + 4] this workgroup's records
-    __shared__ int nlist;
+    uint32_t* list = reinterpret_cast<uint32_t*>(smem);            // [4][L2M_LIST2] per wave: pair << 16 | j << 8 | codeword
+    __shared__ int s_cnt[4];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
-    const int S = rago_steps(m), planes = rago_planes(m);
-    if (threadIdx.x == 0) nlist = 0;
-    float inv[P];                          // per pair: the reciprocal of the query's step
+    const int S = rago_steps(m);
+    const int groups = m / 16;                                      // units of 16 sub-quantisers (half a plane)
+    constexpr float ETA_SCALE = (1.0f + 4.0f / L2M<DSUB>::CE) * 1.001f;
+    int cnt = 0;                                                    // wave-uniform: entries on this wave's list
+    uint32_t* mylist = list + wave * L2M_LIST2;
+    uint8_t* tr = smem + 4 * L2M_LIST2 * 4 + wave * (32 * L2M_TRS);  // per wave: [32 pairs][8 codewords][16 bytes], rows padded
+
+    for (int unit = wave; unit < 2 * groups; unit += 4) {
+        const int ct = unit / groups, jg = unit - ct * groups;
+        const int pl = ct * 32 + col;
+        const bool valid = pl < np;
+        const int64_t pair = pair0 + min(pl, np - 1);
+        const float inv = 1.0f / lut_step(__uint_as_float(range_bits[pair / nprobe]));
+        const float* recp = rec + rec_slot(pair, 0, half, m) * KS;      // + j * 64 KS: the slot of sub-quantiser j
+        const float* lop = lo_in + lo_index(pair, 0, m);                // + j * 32
+        uint8_t* tab0 = tables + pair0 * LUT_BYTES + (int64_t)(jg >> 1) * LUT_PLANE + (jg & 1) * 16;      // (of the workgroup's first pair)
+        uint8_t* dbg = DBG ? out_LUT8 + pair * m * KSUB : nullptr;
+        // Operands of step (t, jj): codeword slot, pair slot, the sub-table's minimum.  They are requested L2M_AHEAD
+        // steps ahead (past the end of the unit: steps of its last tile again).
+        auto load_step = [&](int t, int jj, float (&a)[KS], float (&b)[KS], float& lo) {
+            const int j = jg * 16 + jj;
+            load_slot<KS>(cbx + (((uint32_t)j * KSUB + t * 32 + col) * 2 + half) * KS, a);
+            load_slot<KS>(recp + (uint32_t)j * 64 * KS, b);
+            lo = lop[j * 32];
+        };
+        float an[L2M_AHEAD][KS], bn[L2M_AHEAD][KS], lon[L2M_AHEAD];      // ring: slot s mod L2M_AHEAD holds step s, then is refilled for step s + L2M_AHEAD
 #pragma unroll
-    for (int p = 0; p < P; ++p) inv[p] = 1.0f / lut_step(__uint_as_float(range_bits[(pair0 + min(p, np - 1)) / nprobe]));
-    {
-        // Records into LDS.  Their last two fields are filled in here: the sub-table's exact minimum (pass 1) and, now
-        // that the query's step dq is known, the half-width eta of the zone around a half-integer inside which b~ is
-        // not trusted: (E + u M) / dq + 2^-13 with M = E / (2 (dsub + 6) u).
-        const float4* src = reinterpret_cast<const float4*>(rec + pair0 * m * (DSUB + 4));
-        float4* dst = reinterpret_cast<float4*>(rec_s);
-        constexpr int Q4 = (DSUB + 4) / 4;                 // 16-byte pieces per record
-        for (int i = threadIdx.x; i < np * m * Q4; i += L2Q_THREADS) {
-            float4 v = src[i];
-            if (i % Q4 == Q4 - 1) {
-                const int pj = i / Q4, p = pj / m;
-                float ip = inv[0];
+        for (int s = 0; s < L2M_AHEAD; ++s) load_step(0, s, an[s], bn[s], lon[s]);
+#pragma unroll 1
+        for (int t = 0; t < 8; ++t) {
+            // pk[i][0..3]: the 16 code bytes of (pair, codeword row i).  A word of four bytes is built per group of four
+            // sub-quantisers and shifted in at the top, so that no register is indexed by a loop variable.
+            uint32_t pk[16][4];
 #pragma unroll
-                for (int x = 1; x < P; ++x) ip = p == x ? inv[x] : ip;
-                v.z = lo_in[pair0 * m + pj];
-                v.w = __fmaf_rn(v.y, (1.0f + 1.0f / (2.0f * (float)(DSUB + 6))) * ip * 1.001f, 1.220703125e-4f);
+            for (int i = 0; i < 16; ++i) { pk[i][0] = 0u; pk[i][1] = 0u; pk[i][2] = 0u; pk[i][3] = 0u; }
+#pragma unroll 1
+            for (int g = 0; g < 4; ++g) {
+                uint32_t word[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) word[i] = 0u;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int j = jg * 16 + g * 4 + s;
+                    float av[KS], bv[KS];
+                    constexpr int R = L2M_AHEAD;
+#pragma unroll
+                    for (int x = 0; x < KS; ++x) { av[x] = an[s % R][x]; bv[x] = bn[s % R][x]; }
+                    const float lo = lon[s % R];
+                    {
+                        const int nx = g * 4 + s + R;
+                        load_step(min(t + (nx >> 4), 7), nx & 15, an[s % R], bn[s % R], lon[s % R]);
+                    }
+                    const float nlo = -lo * inv;
+                    const float eta = __fmaf_rn(bv[KH], ETA_SCALE * inv, 1.220703125e-4f);
+                    const f32x16 v = tile_product<KH, KS>(av, bv);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float b = __fmaf_rn(v[i], inv, nlo);
+                        word[i] = __builtin_amdgcn_cvt_pk_u8_f32(b, s, word[i]);
+                        // undecided (a NaN or infinite b~ or eta included): on the list
+                        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > eta)) != 0, 0)) {
+                            const bool amb = valid && !(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > eta);
+                            const uint64_t bal = __builtin_amdgcn_ballot_w64(amb);
+                            if (amb) {
+                                const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+                                if (pos < L2M_LIST2) mylist[pos] = (uint32_t)(pl << 16 | j << 8 | (t * 32 + tile_row(i, half)));
+                            }
+                            cnt += __builtin_popcountll(bal);
+                        }
+                        if (DBG && valid) dbg[(int64_t)j * KSUB + t * 32 + tile_row(i, half)] = (uint8_t)(word[i] >> (8 * s));
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { pk[i][0] = pk[i][1]; pk[i][1] = pk[i][2]; pk[i][2] = pk[i][3]; pk[i][3] = word[i]; }
             }
-            dst[i] = v;
+            // To HBM through a transposition in LDS: a lane holds one pair and 16 codewords, but lanes that store
+            // together should cover consecutive codewords of one pair (tables of different pairs lie 32 KiB apart).
+            // Four turns of 8 codewords; the wave's LDS operations execute in order, so no barrier is needed.
+#pragma unroll
+            for (int qt = 0; qt < 4; ++qt) {
+#pragma unroll
+                for (int i = qt * 4; i < qt * 4 + 4; ++i)
+                    *reinterpret_cast<uint4*>(tr + col * L2M_TRS + (half * 4 + (i & 3)) * 16) = make_uint4(pk[i][0], pk[i][1], pk[i][2], pk[i][3]);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int pr = r * 8 + (lane >> 3), lc = lane & 7;
+                    const uint4 w = *reinterpret_cast<const uint4*>(tr + pr * L2M_TRS + lc * 16);
+                    if (ct * 32 + pr < np) {
+                        uint8_t* dst = tab0 + (int64_t)(ct * 32 + pr) * LUT_BYTES + (t * 32 + qt * 8 + lc) * 32;
+                        *reinterpret_cast<uint4*>(dst) = w;
+                        if (S == 16) *reinterpret_cast<uint4*>(dst + 16) = w;      // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
         }
     }
-    __syncthreads();
-    const float* rec0 = rec_s;
-    uint8_t* tab0 = tables + pair0 * LUT_BYTES;
-    uint8_t* dbg0 = DBG ? out_LUT8 + pair0 * m * KSUB : nullptr;
-    for (int u = wave; u < planes * 2; u += 2) {
-        const int plane = u >> 1, c = (u & 1) * 128 + lane;
-        if (np == P) l2f_quant_unit<DSUB, P, true, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
-        else l2f_quant_unit<DSUB, P, false, DBG>(cbx, rec0, np, m, S, plane, c, inv, tab0, dbg0, list, &nlist);
-    }
+    if (lane == 0) s_cnt[wave] = cnt;
     // The packed stores are ordered before the single-byte corrections by the barrier's workgroup-scope release:
     // both come from this workgroup and go through the same L2.  (A device-scope fence here makes every
     // workgroup write back its XCD's L2 and costs more than the whole computation.)
     __syncthreads();
-    const int n = nlist;
-    const bool all = n > L2Q_LIST;
-    const int total = all ? np * m * KSUB : n;
-    for (int e = threadIdx.x; e < total; e += L2Q_THREADS) {
-        const uint32_t w = all ? (uint32_t)((e / (m * KSUB)) << 16 | ((e / KSUB) % m) << 8 | (e % KSUB)) : list[e];
+    const int c0 = s_cnt[0], c1 = s_cnt[1], c2 = s_cnt[2], c3 = s_cnt[3];
+    const bool all = c0 > L2M_LIST2 || c1 > L2M_LIST2 || c2 > L2M_LIST2 || c3 > L2M_LIST2;
+    const int total = all ? np * m * KSUB : c0 + c1 + c2 + c3;
+    for (int e = threadIdx.x; e < total; e += L2M_THREADS) {
+        uint32_t w;
+        if (all) w = (uint32_t)((e / (m * KSUB)) << 16 | ((e / KSUB) % m) << 8 | (e % KSUB));
+        else w = e < c0 ? list[e] : e < c0 + c1 ? list[L2M_LIST2 + e - c0] : e < c0 + c1 + c2 ? list[2 * L2M_LIST2 + e - c0 - c1]
+                                                                                               : list[3 * L2M_LIST2 + e - c0 - c1 - c2];
         const int p = w >> 16, j = (w >> 8) & 255, c = w & 255;
         const int64_t q = (pair0 + p) / nprobe;
         const int l = probes[pair0 + p];
         const float L = l2_entry<DSUB>(Q + q * d + j * DSUB, C + (int64_t)l * d + j * DSUB, CB + ((int64_t)j * KSUB + c) * DSUB, DSUB);
         const float step = lut_step(__uint_as_float(range_bits[q]));
-        float rr = rintf(__fdiv_rn(L - rec_s[(p * m + j) * (DSUB + 4) + DSUB + 2], step));
+        float rr = rintf(__fdiv_rn(L - lo_in[lo_index(pair0 + p, j, m)], step));
         rr = rr < 0.0f ? 0.0f : (rr > 255.0f ? 255.0f : rr);
         const uint8_t v = (uint8_t)rr;
         uint8_t* tab = tables + (pair0 + p) * LUT_BYTES + (int64_t)(j >> 5) * LUT_PLANE + c * 32;
@@ -402,8 +401,8 @@ __global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __r
     if (threadIdx.x < np) {
         const int p = threadIdx.x;
         const float step = lut_step(__uint_as_float(range_bits[(pair0 + p) / nprobe]));
-        double losum = 0.0;                      // in index order (the order that defines the bias), minima from the records in LDS
-        for (int j = 0; j < m; ++j) losum = losum + (double)rec_s[(p * m + j) * (DSUB + 4) + DSUB + 2];
+        double losum = 0.0;                      // in index order (the order that defines the bias)
+        for (int j = 0; j < m; ++j) losum = losum + (double)lo_in[lo_index(pair0 + p, j, m)];
         bias[pair0 + p] = (int32_t)rint(losum / (double)step);
         if ((pair0 + p) % nprobe == 0) delta[(pair0 + p) / nprobe] = step;
     }
@@ -413,8 +412,8 @@ __global__ void __launch_bounds__(L2Q_THREADS) l2f_quant_kernel(const float* __r
     }
 }
 
-// Per dimension the largest |codeword coordinate|; the packed codebook [m][256][dsub + 4]: coordinates, squared
-// norm (fp64 sum, one rounding), three zeros.
+// Per dimension the largest |codeword coordinate|; the codeword-side operand [m][256][2][KS] (see the head of
+// the file; |cb|^2 is an fp64 sum rounded once).
 __global__ void __launch_bounds__(256) cb_stats_kernel(const float* __restrict__ CB, int d, int m, int dsub, float* __restrict__ absmax,
                                                        float* __restrict__ cbx) {
     const int x = blockIdx.x * 256 + threadIdx.x;
@@ -424,37 +423,47 @@ __global__ void __launch_bounds__(256) cb_stats_kernel(const float* __restrict__
         for (int c = 0; c < KSUB; ++c) mx = fmaxf(mx, fabsf(CB[((int64_t)j * KSUB + c) * dsub + t]));
         absmax[x] = mx;
     }
-    if (x < m * KSUB) {
+    if (x < m * KSUB && dsub % 2 == 0) {
+        const int H = dsub / 2, KH = H + 1, KS = KH + 1;
         double acc = 0.0;
-        float* o = cbx + (int64_t)x * (dsub + 4);
-        for (int t = 0; t < dsub; ++t) { const float f = CB[(int64_t)x * dsub + t]; o[t] = f; acc = acc + (double)f * (double)f; }
-        o[dsub] = (float)acc;
-        o[dsub + 1] = 0.0f; o[dsub + 2] = 0.0f; o[dsub + 3] = 0.0f;
+        float* o = cbx + (int64_t)x * 2 * KS;
+        for (int t = 0; t < dsub; ++t) {
+            const float f = CB[(int64_t)x * dsub + t];
+            o[(t / H) * KS + (t % H)] = f;
+            acc = acc + (double)f * (double)f;
+        }
+        o[KH - 1] = 1.0f;           o[KH] = 0.0f;
+        o[KS + KH - 1] = (float)acc; o[KS + KH] = 0.0f;
     }
 }
 
-template <int DSUB, int P>
-int launch_l2f(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
+template <int DSUB>
+int launch_l2m(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
                uint8_t* out_LUT8, hipStream_t st) {
     Workspace& ws = idx->ws;
     const int d = idx->d, m = idx->m;
     int rc;
-    if ((rc = ws.l2_r.reserve((size_t)npairs * m * (DSUB + 4) * 4))) return rc;
+    const int64_t npad = (npairs + 31) / 32 * 32;                     // whole tiles of 32 pairs
+    if ((rc = ws.l2_r.reserve((size_t)npad * m * 2 * L2M<DSUB>::KS * 4))) return rc;
     float* rec = ws.l2_r.as<float>();
-    const size_t lds1 = (size_t)P * m * 8 + (size_t)L2F_LIST * 4;
-    const size_t lds2 = (size_t)L2Q_LIST * 4 + (size_t)L2Q_PAIRS * m * (DSUB + 4) * 4;     // <= 42 KB
-    const unsigned grid = (unsigned)((npairs + P - 1) / P), grid2 = (unsigned)((npairs + L2Q_PAIRS - 1) / L2Q_PAIRS);
-    l2f_prepare_kernel<DSUB><<<(unsigned)((npairs * m + 255) / 256), 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, npairs, nprobe, d, m, rec);
-    l2f_range_kernel<DSUB, P><<<grid, L2F_THREADS, lds1, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
-                                                               d, m, lo, range_bits, ws.counters.as<int64_t>());
+    const size_t lds2 = (size_t)4 * L2M_LIST2 * 4 + (size_t)4 * 32 * L2M_TRS;      // 50 KB
+    const unsigned grid = (unsigned)((npairs + L2M_PAIRS - 1) / L2M_PAIRS);
+    static OncePerDevice attr;
+    if (attr.first()) {
+        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2m_quant_kernel<DSUB, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
+        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2m_quant_kernel<DSUB, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
+    }
+    l2m_prepare_kernel<DSUB><<<(unsigned)((npad * m + 255) / 256), 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, npairs, nprobe, d, m, rec);
+    l2m_range_kernel<DSUB><<<grid, L2M_THREADS, 0, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
+                                                         d, m, lo, range_bits, ws.counters.as<int64_t>());
     if (out_LUT8)
-        l2f_quant_kernel<DSUB, true><<<grid2, L2Q_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
-                                                                       m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                       ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
+        l2m_quant_kernel<DSUB, true><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                      m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                      ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
     else
-        l2f_quant_kernel<DSUB, false><<<grid2, L2Q_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
-                                                                        m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                        ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
+        l2m_quant_kernel<DSUB, false><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                       m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                       ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }
@@ -470,17 +479,18 @@ int launch_cb_stats(rago_index* idx, hipStream_t st) {
 
 bool lut_l2_fast_supported(const rago_index* idx) {
     const int dsub = idx->dsub;
-    return dsub == 4 || dsub == 8 || dsub == 16;
+    return (dsub == 4 || dsub == 8 || dsub == 16) && idx->m % 16 == 0;
 }
 
-// Both passes for all pairs.  `lo` [npairs][m] fp32 and `range_bits` [nq] (zeroed) are workspace; the
+// Both passes for all pairs.  `lo` (fp32, m floats per pair with the number of pairs rounded up to a multiple of 32)
+// and `range_bits` [nq] (zeroed) are workspace; the
 // tables, bias and step land in the workspace members the scan reads.
 int launch_lut_l2_fast(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
                        uint8_t* out_LUT8, hipStream_t st) {
     switch (idx->dsub) {
-        case 4: return launch_l2f<4, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
-        case 8: return launch_l2f<8, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
-        case 16: return launch_l2f<16, 8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 4: return launch_l2m<4>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 8: return launch_l2m<8>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
+        case 16: return launch_l2m<16>(idx, q, probes, npairs, nprobe, lo, range_bits, out_LUT8, st);
     }
     return fail(RAGO_UNSUPPORTED, "sub-vector length without a fast Euclidean table path");
 }
