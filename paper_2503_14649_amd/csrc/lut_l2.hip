@@ -43,9 +43,14 @@
 // (lane mod 32), the k values of its half (lane / 32): KH = dsub/2 + 1 of them, in a slot of KS = KH + 1
 // floats (8-byte aligned; the spare float of a pair-side slot holds E).  Pass 1: workgroup = 64 pairs, wave
 // = sub-quantiser, loop over the 8 tiles of 32 codewords, each codeword load serving both column tiles;
-// pass 2: workgroup = 64 pairs, wave = (column tile, 16 sub-quantisers), loop over the 8 codeword tiles;
-// a lane holds column = pair and 16 codewords, packs their 16 code bytes and writes 16 bytes per
-// (pair, codeword) into the plane-major table [plane][codeword][slot].
+// pass 2: workgroup = 64 pairs, round = (column tile, plane), wave = 8 of the plane's 32 sub-quantisers, loop
+// over the 8 codeword tiles; a lane holds column = pair and 16 codewords and packs their 8 code bytes; the four
+// waves put the pieces of each 32-byte row [plane][codeword][32 slots] together in LDS (a lane's neighbours
+// hold other PAIRS, whose tables lie 32 KiB apart) and store contiguous 256-byte runs per pair.  Pair
+// operands and minima are stored per tile of 32 pairs so that the 64 lanes' loads are contiguous (a load
+// whose lanes hit 32 different cache lines occupied the CU's memory pipeline longer than the arithmetic).
+// Registers decide the rest: 168 per lane keep three workgroups per CU resident; 8 sub-quantisers per wave
+// instead of 16 (32 fewer packing registers) bought the third, worth 12 %.
 #include "rago_internal.h"
 #include "lut_common.h"
 
@@ -58,9 +63,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int L2M_THREADS = 256;
 constexpr int L2M_PAIRS = 64;           // pairs per workgroup (two column tiles)
 constexpr int L2M_LIST1 = 1024;         // pass 1: candidates per wave and round (its sub-quantiser, 64 pairs: ~400)
-constexpr int L2M_LIST2 = 2048;         // pass 2: undecided entries per wave (of 393 216 per three units: ~1300)
-constexpr int L2M_AHEAD = 4;          // pass 2: operands are requested this many steps ahead (1, 2 or 4)
-constexpr int L2M_TRS = 8 * 16 + 16;    // pass 2: bytes per pair in the transposition buffer (16 bytes of padding: no bank conflicts)
+constexpr int L2M_LIST2 = 2048;         // pass 2: undecided entries per wave (of 393 216 it evaluates at m = 96: ~1300)
+constexpr int L2M_AHEAD = 2;          // pass 2: operands are requested this many steps ahead (1, 2 or 4)
+constexpr int L2M_TRS = 8 * 32 + 16;    // pass 2: bytes per pair in the transposition buffer (16 bytes of padding)
 constexpr float L2M_U = 5.9604644775390625e-08f;   // 2^-24
 
 template <int DSUB>
@@ -259,7 +264,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* 
 
 // ---- pass 2
 template <int DSUB, bool DBG>
-__global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+__global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
@@ -276,26 +281,31 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* 
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
     const int S = rago_steps(m);
-    const int groups = m / 16;                                      // units of 16 sub-quantisers (half a plane)
+    const int planes = rago_planes(m);
     constexpr float ETA_SCALE = (1.0f + 4.0f / L2M<DSUB>::CE) * 1.001f;
     int cnt = 0;                                                    // wave-uniform: entries on this wave's list
     uint32_t* mylist = list + wave * L2M_LIST2;
-    uint8_t* tr = smem + 4 * L2M_LIST2 * 4 + wave * (32 * L2M_TRS);  // per wave: [32 pairs][8 codewords][16 bytes], rows padded
+    uint8_t* tr = smem + 4 * L2M_LIST2 * 4;                         // [32 pairs][8 codewords][32 bytes], rows padded
 
-    for (int unit = wave; unit < 2 * groups; unit += 4) {
-        const int ct = unit / groups, jg = unit - ct * groups;
+    // A round = (column tile of 32 pairs, plane); the four waves take a quarter of the plane's 32 slots each (8
+    // sub-quantisers) and put their 8-byte pieces of every 32-byte row together in LDS before storing.  With
+    // m = 16 the slots 16..31 repeat the slots 0..15: waves 2 and 3 compute what waves 0 and 1 compute.
+    for (int rd = 0; rd < 2 * planes; ++rd) {
+        const int ct = rd / planes, plane = rd - ct * planes;
         const int pl = ct * 32 + col;
         const bool valid = pl < np;
+        const bool lists = valid && wave * 8 < S;                   // (a repeated slot's undecided entries are listed once)
         const int64_t pair = pair0 + min(pl, np - 1);
         const float inv = 1.0f / lut_step(__uint_as_float(range_bits[pair / nprobe]));
         const float* recp = rec + rec_slot(pair, 0, half, m) * KS;      // + j * 64 KS: the slot of sub-quantiser j
         const float* lop = lo_in + lo_index(pair, 0, m);                // + j * 32
-        uint8_t* tab0 = tables + pair0 * LUT_BYTES + (int64_t)(jg >> 1) * LUT_PLANE + (jg & 1) * 16;      // (of the workgroup's first pair)
+        uint8_t* tab0 = tables + pair0 * LUT_BYTES + (int64_t)plane * LUT_PLANE;      // (of the workgroup's first pair)
         uint8_t* dbg = DBG ? out_LUT8 + pair * m * KSUB : nullptr;
+        const int jfirst = plane * 32 + ((wave * 8) & (S - 1));
         // Operands of step (t, jj): codeword slot, pair slot, the sub-table's minimum.  They are requested L2M_AHEAD
-        // steps ahead (past the end of the unit: steps of its last tile again).
+        // steps ahead (past the end of the round: steps of its last tile again): a load from L2 or HBM takes several steps.
         auto load_step = [&](int t, int jj, float (&a)[KS], float (&b)[KS], float& lo) {
-            const int j = jg * 16 + jj;
+            const int j = jfirst + jj;
             load_slot<KS>(cbx + (((uint32_t)j * KSUB + t * 32 + col) * 2 + half) * KS, a);
             load_slot<KS>(recp + (uint32_t)j * 64 * KS, b);
             lo = lop[j * 32];
@@ -305,19 +315,19 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* 
         for (int s = 0; s < L2M_AHEAD; ++s) load_step(0, s, an[s], bn[s], lon[s]);
 #pragma unroll 1
         for (int t = 0; t < 8; ++t) {
-            // pk[i][0..3]: the 16 code bytes of (pair, codeword row i).  A word of four bytes is built per group of four
+            // pk[i][0..1]: the 8 code bytes of (pair, codeword row i).  A word of four bytes is built per group of four
             // sub-quantisers and shifted in at the top, so that no register is indexed by a loop variable.
-            uint32_t pk[16][4];
+            uint32_t pk[16][2];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { pk[i][0] = 0u; pk[i][1] = 0u; pk[i][2] = 0u; pk[i][3] = 0u; }
+            for (int i = 0; i < 16; ++i) { pk[i][0] = 0u; pk[i][1] = 0u; }
 #pragma unroll 1
-            for (int g = 0; g < 4; ++g) {
+            for (int g = 0; g < 2; ++g) {
                 uint32_t word[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) word[i] = 0u;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const int j = jg * 16 + g * 4 + s;
+                    const int j = jfirst + g * 4 + s;
                     float av[KS], bv[KS];
                     constexpr int R = L2M_AHEAD;
 #pragma unroll
@@ -325,7 +335,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* 
                     const float lo = lon[s % R];
                     {
                         const int nx = g * 4 + s + R;
-                        load_step(min(t + (nx >> 4), 7), nx & 15, an[s % R], bn[s % R], lon[s % R]);
+                        load_step(min(t + (nx >> 3), 7), nx & 7, an[s % R], bn[s % R], lon[s % R]);
                     }
                     const float nlo = -lo * inv;
                     const float eta = __fmaf_rn(bv[KH], ETA_SCALE * inv, 1.220703125e-4f);
@@ -336,7 +346,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* 
                         word[i] = __builtin_amdgcn_cvt_pk_u8_f32(b, s, word[i]);
                         // undecided (a NaN or infinite b~ or eta included): on the list
                         if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > eta)) != 0, 0)) {
-                            const bool amb = valid && !(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > eta);
+                            const bool amb = lists && !(fabsf(__builtin_amdgcn_fractf(b) - 0.5f) > eta);
                             const uint64_t bal = __builtin_amdgcn_ballot_w64(amb);
                             if (amb) {
                                 const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
@@ -344,32 +354,31 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_quant_kernel(const float* 
                             }
                             cnt += __builtin_popcountll(bal);
                         }
-                        if (DBG && valid) dbg[(int64_t)j * KSUB + t * 32 + tile_row(i, half)] = (uint8_t)(word[i] >> (8 * s));
+                        if (DBG && lists) dbg[(int64_t)j * KSUB + t * 32 + tile_row(i, half)] = (uint8_t)(word[i] >> (8 * s));
                     }
                 }
 #pragma unroll
-                for (int i = 0; i < 16; ++i) { pk[i][0] = pk[i][1]; pk[i][1] = pk[i][2]; pk[i][2] = pk[i][3]; pk[i][3] = word[i]; }
+                for (int i = 0; i < 16; ++i) { pk[i][0] = pk[i][1]; pk[i][1] = word[i]; }
             }
             // To HBM through a transposition in LDS: a lane holds one pair and 16 codewords, but lanes that store
-            // together should cover consecutive codewords of one pair (tables of different pairs lie 32 KiB apart).
-            // Four turns of 8 codewords; the wave's LDS operations execute in order, so no barrier is needed.
+            // together should cover consecutive bytes of one pair's table (tables of different pairs lie 32 KiB apart)
+            // and whole 32-byte rows should reach memory at once.  Four turns of 8 codewords: every wave writes its
+            // 8-byte pieces, then stores a quarter of the 8 KiB.
 #pragma unroll
             for (int qt = 0; qt < 4; ++qt) {
 #pragma unroll
-                for (int i = qt * 4; i < qt * 4 + 4; ++i)
-                    *reinterpret_cast<uint4*>(tr + col * L2M_TRS + (half * 4 + (i & 3)) * 16) = make_uint4(pk[i][0], pk[i][1], pk[i][2], pk[i][3]);
-                __builtin_amdgcn_wave_barrier();
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<uint2*>(tr + col * L2M_TRS + (half * 4 + q) * 32 + wave * 8) = make_uint2(pk[qt * 4 + q][0], pk[qt * 4 + q][1]);
+                __syncthreads();
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int pr = r * 8 + (lane >> 3), lc = lane & 7;
-                    const uint4 w = *reinterpret_cast<const uint4*>(tr + pr * L2M_TRS + lc * 16);
-                    if (ct * 32 + pr < np) {
-                        uint8_t* dst = tab0 + (int64_t)(ct * 32 + pr) * LUT_BYTES + (t * 32 + qt * 8 + lc) * 32;
-                        *reinterpret_cast<uint4*>(dst) = w;
-                        if (S == 16) *reinterpret_cast<uint4*>(dst + 16) = w;      // fewer than 32 sub-quantisers: slots 16..31 repeat slots 0..15
-                    }
+                for (int r = 0; r < 2; ++r) {
+                    const int x = (wave * 2 + r) * 64 + lane;              // 16-byte piece of the buffer
+                    const int pr = x >> 4, within = x & 15;
+                    const uint4 w = *reinterpret_cast<const uint4*>(tr + pr * L2M_TRS + within * 16);
+                    if (ct * 32 + pr < np)
+                        *reinterpret_cast<uint4*>(tab0 + (int64_t)(ct * 32 + pr) * LUT_BYTES + (t * 32 + qt * 8) * 32 + within * 16) = w;
                 }
-                __builtin_amdgcn_wave_barrier();
+                __syncthreads();
             }
         }
     }
@@ -446,7 +455,7 @@ int launch_l2m(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     const int64_t npad = (npairs + 31) / 32 * 32;                     // whole tiles of 32 pairs
     if ((rc = ws.l2_r.reserve((size_t)npad * m * 2 * L2M<DSUB>::KS * 4))) return rc;
     float* rec = ws.l2_r.as<float>();
-    const size_t lds2 = (size_t)4 * L2M_LIST2 * 4 + (size_t)4 * 32 * L2M_TRS;      // 50 KB
+    const size_t lds2 = (size_t)4 * L2M_LIST2 * 4 + (size_t)32 * L2M_TRS;      // 41 KB
     const unsigned grid = (unsigned)((npairs + L2M_PAIRS - 1) / L2M_PAIRS);
     static OncePerDevice attr;
     if (attr.first()) {
