@@ -41,9 +41,10 @@
 //
 // Layout.  Both operand sides are stored per (row, half): a lane of the MFMA supplies, for its row or column
 // (lane mod 32), the k values of its half (lane / 32): KH = dsub/2 + 1 of them, in a slot of KS = KH + 1
-// floats (8-byte aligned; the spare float of a pair-side slot holds E).  Pass 1: workgroup = 64 pairs, wave
+// floats (8-byte aligned; the spare float of a pair-side slot holds E).  Workgroups take 64 pairs (32 and a
+// slice of the sub-quantisers each when the batch is small).  Pass 1: wave
 // = sub-quantiser, loop over the 8 tiles of 32 codewords, each codeword load serving both column tiles;
-// pass 2: workgroup = 64 pairs, round = (column tile, plane), wave = 8 of the plane's 32 sub-quantisers, loop
+// pass 2: round = (column tile, plane), wave = 8 of the plane's 32 sub-quantisers, loop
 // over the 8 codeword tiles; a lane holds column = pair and 16 codewords and packs their 8 code bytes; the four
 // waves put the pieces of each 32-byte row [plane][codeword][32 slots] together in LDS (a lane's neighbours
 // hold other PAIRS, whose tables lie 32 KiB apart) and store contiguous 256-byte runs per pair.  Pair
@@ -61,7 +62,6 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int L2M_THREADS = 256;
-constexpr int L2M_PAIRS = 64;           // pairs per workgroup (two column tiles)
 constexpr int L2M_LIST1 = 1024;         // pass 1: candidates per wave and round (its sub-quantiser, 64 pairs: ~400)
 constexpr int L2M_LIST2 = 2048;         // pass 2: undecided entries per wave (of 393 216 it evaluates at m = 96: ~1300)
 constexpr int L2M_AHEAD = 2;          // pass 2: operands are requested this many steps ahead (1, 2 or 4)
@@ -145,16 +145,17 @@ __global__ void __launch_bounds__(256) l2m_prepare_kernel(const float* __restric
     }
 }
 
-// ---- pass 1
-template <int DSUB>
+// ---- pass 1.  CT column tiles of 32 pairs per workgroup; blockIdx.y picks a slice of the sub-quantisers (small
+// batches are split that way so that the launch still fills the chip).
+template <int DSUB, int CT>
 __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
                                                                 const int32_t* __restrict__ probes, int64_t npairs, int nprobe, int d,
                                                                 int m, float* __restrict__ lo_out, uint32_t* __restrict__ range_bits,
                                                                 int64_t* __restrict__ counters) {
-    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = L2M_PAIRS;
-    __shared__ uint32_t lo_key[P * 4], hi_key[P * 4];        // this round's four sub-quantisers
+    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = 32 * CT;
+    __shared__ uint32_t lo_key[L2M_THREADS], hi_key[L2M_THREADS];        // [pair][4]: this round's four sub-quantisers
     __shared__ uint32_t list[4][L2M_LIST1];                  // per wave: pair << 16 | j << 8 | codeword
     __shared__ int s_cnt[4];
     __shared__ float s_rng[P];
@@ -162,22 +163,25 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* 
     const int col = lane & 31, half = lane >> 5;
     const int64_t pair0 = (int64_t)blockIdx.x * P;
     const int np = (int)min((int64_t)P, npairs - pair0);
-    lo_key[threadIdx.x] = 0xFFFFFFFFu; hi_key[threadIdx.x] = 0u;       // (P * 4 = L2M_THREADS)
+    lo_key[threadIdx.x] = 0xFFFFFFFFu; hi_key[threadIdx.x] = 0u;
     if (threadIdx.x < P) s_rng[threadIdx.x] = 0.0f;
     unsigned long long evaluated = 0, overflows = 0;                   // thread 0's tally
     const float inf = __builtin_inff();
 
-    for (int j0 = 0; j0 < m; j0 += 4) {
+    const int jslice = m / (int)gridDim.y;                            // (a multiple of 4)
+    for (int j0 = blockIdx.y * jslice; j0 < (int)(blockIdx.y + 1) * jslice; j0 += 4) {
         __syncthreads();                                               // keys reset, the previous round's list consumed
         const int j = j0 + wave;
-        float bv[2][KS];
-        int pl[2];
+        float bv[CT][KS];
+        int pl[CT];
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
+        for (int ct = 0; ct < CT; ++ct) {
             pl[ct] = ct * 32 + col;
             load_slot<KS>(rec + rec_slot(pair0 + min(pl[ct], np - 1), j, half, m) * KS, bv[ct]);
         }
-        float rmn[2] = {inf, inf}, rmx[2] = {-inf, -inf};
+        float rmn[CT], rmx[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) { rmn[ct] = inf; rmx[ct] = -inf; }
         int cnt = 0;                                                   // wave-uniform: entries on this wave's list
         float av[KS];
         load_slot<KS>(cbx + (((uint32_t)j * KSUB + col) * 2 + half) * KS, av);
@@ -186,7 +190,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* 
             float an[KS];
             load_slot<KS>(cbx + (((uint32_t)j * KSUB + min(t + 1, 7) * 32 + col) * 2 + half) * KS, an);
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
+            for (int ct = 0; ct < CT; ++ct) {
                 const f32x16 v = tile_product<KH, KS>(av, bv[ct]);
                 float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
                 mn = fminf(mn, fminf(fminf(fminf(v[8], v[9]), fminf(v[10], v[11])), fminf(fminf(v[12], v[13]), fminf(v[14], v[15]))));
@@ -263,7 +267,8 @@ __global__ void __launch_bounds__(L2M_THREADS, 2) l2m_range_kernel(const float* 
 }
 
 // ---- pass 2
-template <int DSUB, bool DBG>
+// CT column tiles of 32 pairs per workgroup; with gridDim.y > 1, blockIdx.y picks the plane.
+template <int DSUB, int CT, bool DBG>
 __global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                 const float* __restrict__ CB, const float* __restrict__ cbx,
                                                                 const float* __restrict__ rec,
@@ -272,7 +277,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* 
                                                                 uint8_t* __restrict__ tables, int32_t* __restrict__ bias,
                                                                 float* __restrict__ delta, uint8_t* __restrict__ out_LUT8,
                                                                 int64_t* __restrict__ counters) {
-    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = L2M_PAIRS;
+    constexpr int KH = L2M<DSUB>::KH, KS = L2M<DSUB>::KS, P = 32 * CT;
     extern __shared__ __align__(16) uint8_t smem[];
     uint32_t* list = reinterpret_cast<uint32_t*>(smem);            // [4][L2M_LIST2] per wave: pair << 16 | j << 8 | codeword
     __shared__ int s_cnt[4];
@@ -290,8 +295,9 @@ __global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* 
     // A round = (column tile of 32 pairs, plane); the four waves take a quarter of the plane's 32 slots each (8
     // sub-quantisers) and put their 8-byte pieces of every 32-byte row together in LDS before storing.  With
     // m = 16 the slots 16..31 repeat the slots 0..15: waves 2 and 3 compute what waves 0 and 1 compute.
-    for (int rd = 0; rd < 2 * planes; ++rd) {
-        const int ct = rd / planes, plane = rd - ct * planes;
+    const int pb = gridDim.y > 1 ? (int)blockIdx.y : 0, pn = gridDim.y > 1 ? 1 : planes;      // this workgroup's planes
+    for (int rd = 0; rd < CT * pn; ++rd) {
+        const int ct = rd / pn, plane = pb + rd - ct * pn;
         const int pl = ct * 32 + col;
         const bool valid = pl < np;
         const bool lists = valid && wave * 8 < S;                   // (a repeated slot's undecided entries are listed once)
@@ -389,10 +395,11 @@ __global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* 
     __syncthreads();
     const int c0 = s_cnt[0], c1 = s_cnt[1], c2 = s_cnt[2], c3 = s_cnt[3];
     const bool all = c0 > L2M_LIST2 || c1 > L2M_LIST2 || c2 > L2M_LIST2 || c3 > L2M_LIST2;
-    const int total = all ? np * m * KSUB : c0 + c1 + c2 + c3;
+    const int jb = pb * 32, jn = gridDim.y > 1 ? S : m;            // this workgroup's sub-quantisers
+    const int total = all ? np * jn * KSUB : c0 + c1 + c2 + c3;
     for (int e = threadIdx.x; e < total; e += L2M_THREADS) {
         uint32_t w;
-        if (all) w = (uint32_t)((e / (m * KSUB)) << 16 | ((e / KSUB) % m) << 8 | (e % KSUB));
+        if (all) w = (uint32_t)((e / (jn * KSUB)) << 16 | (jb + (e / KSUB) % jn) << 8 | (e % KSUB));
         else w = e < c0 ? list[e] : e < c0 + c1 ? list[L2M_LIST2 + e - c0] : e < c0 + c1 + c2 ? list[2 * L2M_LIST2 + e - c0 - c1]
                                                                                                : list[3 * L2M_LIST2 + e - c0 - c1 - c2];
         const int p = w >> 16, j = (w >> 8) & 255, c = w & 255;
@@ -407,7 +414,7 @@ __global__ void __launch_bounds__(L2M_THREADS, 3) l2m_quant_kernel(const float* 
         for (int rep = j & (S - 1); rep < 32; rep += S) tab[rep] = v;
         if (DBG) out_LUT8[((pair0 + p) * m + j) * KSUB + c] = v;
     }
-    if (threadIdx.x < np) {
+    if (threadIdx.x < np && blockIdx.y == 0) {
         const int p = threadIdx.x;
         const float step = lut_step(__uint_as_float(range_bits[(pair0 + p) / nprobe]));
         double losum = 0.0;                      // in index order (the order that defines the bias)
@@ -446,6 +453,27 @@ __global__ void __launch_bounds__(256) cb_stats_kernel(const float* __restrict__
     }
 }
 
+template <int DSUB, int CT>
+int launch_l2m_passes(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, const float* rec, float* lo,
+                      uint32_t* range_bits, uint8_t* out_LUT8, int gy, hipStream_t st) {
+    Workspace& ws = idx->ws;
+    const int d = idx->d, m = idx->m;
+    const size_t lds2 = (size_t)4 * L2M_LIST2 * 4 + (size_t)32 * L2M_TRS;      // 41 KB
+    const dim3 grid((unsigned)((npairs + 32 * CT - 1) / (32 * CT)), (unsigned)gy);
+    l2m_range_kernel<DSUB, CT><<<grid, L2M_THREADS, 0, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
+                                                             d, m, lo, range_bits, ws.counters.as<int64_t>());
+    if (out_LUT8)
+        l2m_quant_kernel<DSUB, CT, true><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                          m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                          ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
+    else
+        l2m_quant_kernel<DSUB, CT, false><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
+                                                                           m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
+                                                                           ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
+    RAGO_HIP(hipGetLastError());
+    return RAGO_OK;
+}
+
 template <int DSUB>
 int launch_l2m(rago_index* idx, const float* q, const int32_t* probes, int64_t npairs, int nprobe, float* lo, uint32_t* range_bits,
                uint8_t* out_LUT8, hipStream_t st) {
@@ -455,26 +483,11 @@ int launch_l2m(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     const int64_t npad = (npairs + 31) / 32 * 32;                     // whole tiles of 32 pairs
     if ((rc = ws.l2_r.reserve((size_t)npad * m * 2 * L2M<DSUB>::KS * 4))) return rc;
     float* rec = ws.l2_r.as<float>();
-    const size_t lds2 = (size_t)4 * L2M_LIST2 * 4 + (size_t)32 * L2M_TRS;      // 41 KB
-    const unsigned grid = (unsigned)((npairs + L2M_PAIRS - 1) / L2M_PAIRS);
-    static OncePerDevice attr;
-    if (attr.first()) {
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2m_quant_kernel<DSUB, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
-        RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(l2m_quant_kernel<DSUB, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
-    }
     l2m_prepare_kernel<DSUB><<<(unsigned)((npad * m + 255) / 256), 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, npairs, nprobe, d, m, rec);
-    l2m_range_kernel<DSUB><<<grid, L2M_THREADS, 0, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe,
-                                                         d, m, lo, range_bits, ws.counters.as<int64_t>());
-    if (out_LUT8)
-        l2m_quant_kernel<DSUB, true><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
-                                                                      m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                      ws.delta.as<float>(), out_LUT8, ws.counters.as<int64_t>());
-    else
-        l2m_quant_kernel<DSUB, false><<<grid, L2M_THREADS, lds2, st>>>(q, idx->centroids, idx->codebooks, idx->cbx, rec, probes, npairs, nprobe, d,
-                                                                       m, lo, range_bits, ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(),
-                                                                       ws.delta.as<float>(), nullptr, ws.counters.as<int64_t>());
-    RAGO_HIP(hipGetLastError());
-    return RAGO_OK;
+    // Large batches: 64 pairs per workgroup (each codeword load serves two column tiles).  Fewer than ~4 such
+    // workgroups per CU: 32 pairs per workgroup and one workgroup per plane, so that the launch still fills the chip.
+    if ((npairs + 63) / 64 >= 1024) return launch_l2m_passes<DSUB, 2>(idx, q, probes, npairs, nprobe, rec, lo, range_bits, out_LUT8, 1, st);
+    return launch_l2m_passes<DSUB, 1>(idx, q, probes, npairs, nprobe, rec, lo, range_bits, out_LUT8, rago_planes(m), st);
 }
 
 }  // namespace
