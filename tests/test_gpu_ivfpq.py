@@ -346,6 +346,33 @@ def test_l2_stages_equal_oracle(l2case, rb):
             assert cnt[5] == 0 and 0 < cnt[4] < 0.05 * entries
 
 
+def test_l2_large_batch_tables_and_search(rb):
+    """65 659 (query, list) pairs: the launch shape of large batches (64 pairs per workgroup, ragged last workgroup),
+    which the small cases above do not reach.  Tables, biases, steps and search results against the oracle."""
+    n, d, m, nlist, nq, nprobe, k = 20000, 64, 16, 130, 517, 127, 10
+    ix = to_np(synth.random_index(n=n, d=d, m=m, nlist=nlist, seed=4242, dup_codes=5))
+    Q = _queries(nq, d, 99)
+    h = rb.rago_index_wrap(dev_index(ix), metric="l2")
+    try:
+        Qd = torch.from_numpy(Q).cuda()
+        S = oracle.coarse(Q, ix["centroids"], metric="l2")
+        probes = oracle.select(S, nprobe)
+        gp = rb.rago_debug_select(h, Qd, rb.rago_debug_coarse(h, Qd), nprobe).cpu().numpy()
+        assert np.array_equal(gp, probes)
+        LUT8, B, delta = oracle.quantise(oracle.lut_f32(Q, ix["centroids"], ix["codebooks"], probes, metric="l2"))
+        _, gL8, gB, gd = rb.rago_debug_build_lut(h, Qd, torch.from_numpy(probes).cuda(), want_f32=False)
+        assert np.array_equal(gd.cpu().numpy(), delta) and np.array_equal(gB.cpu().numpy(), B)
+        assert np.array_equal(gL8.cpu().numpy(), LUT8)
+        cnt = rb.rago_debug_counters(h)
+        assert cnt[5] == 0 and 0 < cnt[4] < 0.05 * 2 * nq * nprobe * m * 256
+        r = oracle.ivfpq_search(Q, ix, nprobe, k, metric="l2")
+        gi, gs, gis = rb.rago_ivfpq_search(h, Qd, nprobe, k)
+        assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+        assert np.array_equal(gs.cpu().numpy(), r["scores"])
+    finally:
+        rb.rago_index_free(h)
+
+
 @pytest.mark.parametrize("scale", [1e-19, 1e18])
 def test_l2_tables_at_the_ends_of_the_fp32_range(rb, scale):
     """Everything scaled by 1e-19: squared distances (~1e-38 and below) underflow in fp32, where the relative error
