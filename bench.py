@@ -33,9 +33,12 @@ def scaled_cfg(cfg, f):
                       components=max(16, int(cfg.components * f)), train_n=max(20000, int(cfg.train_n * f)))
 
 
-def read_traffic(workload, name=None):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if present."""
-    p = os.path.join(ROOT, "profiles", name or f"scan_m96_{workload}_pmc.txt")
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary, if present.
+
+    Hardware byte counters cannot be read inside this run, so the figure is quoted with its source:
+    the file and the kernel time of the counter run it was taken in."""
+    p = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(p):
         return None
     vals = {}
@@ -46,9 +49,53 @@ def read_traffic(workload, name=None):
                 vals[k.strip()] = float(v.strip().split()[0])
             except ValueError:
                 pass
-    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
-        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
-    return None
+    if "FETCH_BYTES_PER_LAUNCH" not in vals or "WRITE_BYTES_PER_LAUNCH" not in vals:
+        return None
+    return {"file": "profiles/" + name, "fetch_bytes": vals["FETCH_BYTES_PER_LAUNCH"], "write_bytes": vals["WRITE_BYTES_PER_LAUNCH"],
+            "kernel_ms": vals.get("KERNEL_MS_UNDER_COUNTERS")}
+
+
+def read_stream_ceiling(rb, gib=4.0, reps=10):
+    """GB/s of the library's plain read-stream kernel over `gib` GiB, timed here with HIP events
+    (far larger than the 256 MiB Infinity Cache, so every repetition reads HBM)."""
+    import torch
+    buf = torch.empty(int(gib * (1 << 30)), dtype=torch.uint8, device="cuda").fill_(1)
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        rb.rago_debug_read_stream(buf, sink)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        rb.rago_debug_read_stream(buf, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    rate = buf.numel() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del buf, sink
+    torch.cuda.empty_cache()
+    return rate
+
+
+def hbm_roofline(kernel, hbm_bytes, kernel_ms, ceiling, prof, what, extra=None):
+    """The roofline object of a bandwidth-bound kernel: `hbm_bytes` are bytes the kernel reads from HBM
+    per launch (never bytes counted once per query that shares them), `kernel_ms` its HIP-event time."""
+    achieved = hbm_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    rec = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+           "frac": achieved / HBM_PEAK_GBPS, "achieved_is": what, "hbm_bytes_per_launch": hbm_bytes, "kernel_ms": kernel_ms,
+           "ceiling": ceiling, "ceiling_is": "plain read-stream kernel over 4 GiB, timed in this run",
+           "frac_of_ceiling": achieved / ceiling if ceiling else None, "traffic": None}
+    if prof:
+        total = prof["fetch_bytes"] + prof["write_bytes"]
+        rec["traffic"] = total
+        rec["traffic_source"] = {"file": prof["file"], "kernel_ms_in_that_run": prof["kernel_ms"],
+                                 "fetch_bytes": prof["fetch_bytes"], "write_bytes": prof["write_bytes"]}
+        if prof["kernel_ms"]:
+            rec["traffic_source"]["fetched_rate"] = prof["fetch_bytes"] / (prof["kernel_ms"] * 1e-3) / 1e9
+            rec["traffic_source"]["frac_fetched"] = rec["traffic_source"]["fetched_rate"] / HBM_PEAK_GBPS
+    if extra:
+        rec.update(extra)
+    assert rec["frac"] <= 1.0, "an HBM fraction above 1 means bytes were counted that never crossed HBM"
+    return rec
 
 
 def host_subindex(index, probes_np):
@@ -161,7 +208,7 @@ def run_ivfpq(args):
     cnt = rb.rago_debug_counters(h)
     algo_bytes, streamed = cnt[2], cnt[1]
     scan_ms = stages["scan"]
-    achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    ceiling = read_stream_ceiling(rb) if args.ceiling else None
     parity = None
     if sample_ref is not None:
         gi, gis = out[0][:ns].cpu().numpy(), out[2][:ns].cpu().numpy()
@@ -169,7 +216,17 @@ def run_ivfpq(args):
         parity = {"queries": ns, "topk_id_overlap": ov,
                   "ids_bit_exact": bool(np.array_equal(gi, sample_ref["ids"])),
                   "iscores_bit_exact": bool(np.array_equal(gis, sample_ref["iscores"]))}
-    traffic = read_traffic(cfg.name) if args.scale == 1.0 and args.metric == "ip" else None
+    mbytes = cfg.m // 2 if cfg.ksub == 16 else cfg.m
+    prof = read_traffic(f"scan_m{mbytes}_{cfg.name}_pmc.txt") if args.scale == 1.0 and args.metric == "ip" and cfg.ksub == 256 else None
+    roof = hbm_roofline(
+        f"scan_kernel<{mbytes}>", streamed, scan_ms, ceiling, prof,
+        "code bytes the scan kernel streams from HBM per launch (the library's own count: every pass over a list once, "
+        "whatever number of queries it serves) / the kernel's HIP-event time",
+        {"algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,
+         "algorithmic_rate": algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0,
+         "algorithmic_rate_is": "sum over (query, probed list) pairs of list length x code bytes, per second of kernel time: "
+                                "the user-visible rate, above the HBM rate by the reuse factor",
+         "reuse_factor": algo_bytes / streamed if streamed else None, "launches_timed": ncalls})
     rec = {
         "metric": ("ivfpq_queries_per_s_1Bx96B_shard" if cfg.name == "hyper" and args.scale == 1.0 else f"ivfpq_queries_per_s_{cfg.name}")
                   + ("" if args.metric == "ip" else "_l2"),
@@ -178,10 +235,7 @@ def run_ivfpq(args):
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n} d={cfg.d} m={cfg.m} nlist={cfg.nlist} nq={nq} nprobe={nprobe} k={k}",
                    "scale": args.scale, "similarity": args.metric, "ksub": cfg.ksub},
-        "roofline": {"bound": "hbm", "kernel": f"scan_kernel<{cfg.m // 2 if cfg.ksub == 16 else cfg.m}>", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,
-                     "kernel_ms": scan_ms, "launches_timed": ncalls},
+        "roofline": roof,
         "stage_ms": stages,
         "scan_tasks": cnt[0], "inexact_probe_queries": cnt[3],
         "list_len_min_med_max": [int(lens.min()), int(lens.median()), int(lens.max())],
@@ -323,6 +377,7 @@ def run_flat(args):
     for _ in range(args.warmup):
         search(corpus, queries, cfg.k, out=out)
     torch.cuda.synchronize()
+    rb.rago_debug_flat_profile(0, True)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
@@ -330,6 +385,9 @@ def run_flat(args):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
+    fst, _ = rb.rago_debug_flat_stage_ms(0)
+    rb.rago_debug_flat_profile(0, False)
+    scan_ms, merge_ms = fst["scan"], fst["merge"]
     algo = R * cfg.n * cfg.d * 2
     cpu = None
     if args.cpu_queries > 0:
@@ -344,15 +402,16 @@ def run_flat(args):
         ov = float(np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / cfg.k for r in range(rs) for q in range(cfg.nq)]))
         cpu = {"value": rs / dt, "unit": "requests/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{rs} of {R} requests, {dt:.2f}s wall", "topk_id_overlap": ov}
-    achieved = algo / (ms * 1e-3) / 1e9
+    ceiling = read_stream_ceiling(rb) if args.ceiling else None
+    prof = read_traffic("flat_32x100k_pmc.txt") if R == cfg.requests and not half else None
+    roof = hbm_roofline("flat_scan_kernel", algo, scan_ms, ceiling, prof,
+                        "corpus bytes (every row read once for all 16 queries of its request) / the scan kernel's HIP-event time",
+                        {"algorithmic_bytes_per_launch": algo, "whole_call_rate": algo / (ms * 1e-3) / 1e9})
     rec = {"metric": "flat_requests_per_s" + ("_f16" if half else ""), "value": R / (ms * 1e-3), "unit": "requests/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": args.flat_format, "data": "synthetic",
            "config": {"workload": f"flat: R={R} n={cfg.n} d={cfg.d} nq={cfg.nq} k={cfg.k}", "scale": args.scale},
-           "roofline": {"bound": "hbm", "kernel": "flat_scan_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                        "frac": achieved / HBM_PEAK_GBPS,
-                        "traffic": read_traffic("flat", "flat_32x100k_pmc.txt") if R == cfg.requests and not half else None,
-                        "algorithmic_bytes_per_launch": algo},
+           "roofline": roof, "stage_ms": {"scan": scan_ms, "merge": merge_ms},
            "cpu_baseline": cpu}
     print(json.dumps(rec), flush=True)
 
@@ -372,6 +431,8 @@ def main():
     ap.add_argument("--ksub", type=int, default=256, choices=[256, 16],
                     help="codewords per sub-quantiser; 16 = 4-bit codes, two sub-quantisers per code byte")
     ap.add_argument("--m", type=int, default=0, help="sub-quantisers (default: the workload's)")
+    ap.add_argument("--no-ceiling", dest="ceiling", action="store_false",
+                    help="skip the read-stream ceiling measurement (a 4 GiB buffer read ten times)")
     ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
                     help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()

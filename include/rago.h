@@ -216,6 +216,13 @@ int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
  * hardware HBM byte counters are calibrated when the scan is profiled. */
 int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
+/* Plain read stream (rago_calib_read_kernel) over `bytes` bytes of DEVICE src (16-byte aligned,
+ * bytes % 16 == 0) on the current device: the rate a kernel that only reads HBM reaches, i.e. the
+ * practical ceiling the scans are measured against besides the 8 TB/s peak (Section 4, "Retrieval
+ * performance modeling": a good code scan reaches ~80 % of the memory bandwidth).  sink DEVICE
+ * [4096] uint32 receives the XOR of what each workgroup read (so the loads are not dropped). */
+int rago_debug_read_stream(const void* src, int64_t bytes, uint32_t* sink, void* stream);
+
 /* Per-stage timing of rago_ivfpq_search with HIP events recorded on the caller's stream.
  * rago_debug_profile(idx, 1) starts (and resets) recording for up to 64 following search calls,
  * (idx, 0) stops it.  rago_debug_stage_ms waits for the recorded calls and returns, averaged over
@@ -223,6 +230,13 @@ int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream);
  * merge, whole call, 0} in milliseconds and *out_calls = number of calls averaged. */
 int rago_debug_profile(rago_index* idx, int enable);
 int rago_debug_stage_ms(rago_index* idx, float* out_ms, int32_t* out_calls);
+
+/* The same for the flat searches on `device`: rago_debug_flat_profile(device, 1) starts (and resets)
+ * recording for up to 128 following rago_flat_search / rago_flat_search_f16 calls, (device, 0) stops
+ * it; rago_debug_flat_stage_ms waits for them and returns HOST out_ms[2] = {scan kernel, merge
+ * kernel} in milliseconds averaged over *out_calls calls. */
+int rago_debug_flat_profile(int device, int enable);
+int rago_debug_flat_stage_ms(int device, float* out_ms, int32_t* out_calls);
 
 #ifdef __cplusplus
 }

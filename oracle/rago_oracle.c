@@ -23,6 +23,9 @@
  * Pins (tests/, CPU-only): exhaustive reconstruct-and-matmul ADC at nprobe = nlist, the
  * look-up-table sum identity, an integer-exact worked case, quantisation error bound and
  * end points, brute-force sorts with forced ties, numpy matmul for coarse and flat scores;
+ * the rounding conventions of steps 3-4 (ties to even in the 8-bit entries and the bias, the
+ * fp32 subtract and IEEE divide, fp64 accumulation with one rounding in both kinds of table,
+ * the fp64 sum and quotient of the bias) by hand-derived worked cases and half-ulp bounds;
  * Euclidean metric: numpy distances for the coarse scores, the table sum identity against an
  * independent reconstruction, zero entries at exact matches, its relation to the inner-product
  * tables through the norms, exhaustive search at nprobe = nlist, agreement with the inner-product

@@ -49,6 +49,9 @@ _lib.rago_debug_build_lut.argtypes = [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp, 
 _lib.rago_debug_scan.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]
 _lib.rago_debug_counters.argtypes = [_vp, _vp, _vp]
 _lib.rago_debug_copy.argtypes = [_vp, _vp, _i64, _vp]
+_lib.rago_debug_read_stream.argtypes = [_vp, _i64, _vp, _vp]
+_lib.rago_debug_flat_profile.argtypes = [_int, _int]
+_lib.rago_debug_flat_stage_ms.argtypes = [_int, _vp, _vp]
 _lib.rago_debug_profile.argtypes = [_vp, _int]
 _lib.rago_debug_stage_ms.argtypes = [_vp, _vp, _vp]
 
@@ -231,6 +234,23 @@ def rago_debug_copy(src: torch.Tensor, dst: torch.Tensor):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _chk(_lib.rago_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(src.device)))
+
+
+def rago_debug_read_stream(src: torch.Tensor, sink: torch.Tensor):
+    """sink: uint32/int32 tensor of >= 4096 words on src's device."""
+    assert sink.numel() >= 4096 and sink.element_size() == 4
+    _chk(_lib.rago_debug_read_stream(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(src.device)))
+
+
+def rago_debug_flat_profile(device: int, enable: bool):
+    _chk(_lib.rago_debug_flat_profile(device, int(enable)))
+
+
+def rago_debug_flat_stage_ms(device: int):
+    out = (ctypes.c_float * 2)()
+    n = ctypes.c_int32()
+    _chk(_lib.rago_debug_flat_stage_ms(device, out, ctypes.byref(n)))
+    return {"scan": out[0], "merge": out[1]}, n.value
 
 
 STAGES = ("coarse", "select", "lut", "scan_setup", "scan", "merge", "total")

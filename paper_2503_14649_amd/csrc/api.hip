@@ -505,10 +505,29 @@ int rago_flat_search_f16(const void* corpus, const void* queries, int32_t R, int
     return flat_search(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, true, stream);
 }
 
+int rago_debug_flat_profile(int device, int enable) {
+    DeviceGuard g(device);
+    if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    return flat_profile(device, enable);
+}
+
+int rago_debug_flat_stage_ms(int device, float* out_ms, int32_t* out_calls) {
+    if (!out_ms || !out_calls) return fail(RAGO_INVALID_ARG, "null argument");
+    DeviceGuard g(device);
+    if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    return flat_stage_ms(device, out_ms, out_calls);
+}
+
 int rago_debug_copy(const void* src, void* dst, int64_t bytes, void* stream) {
     if (!src || !dst || bytes < 0 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
         return fail(RAGO_INVALID_ARG, "copy needs 16-byte aligned buffers and a size that is a multiple of 16");
     return launch_calib_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
+int rago_debug_read_stream(const void* src, int64_t bytes, uint32_t* sink, void* stream) {
+    if (!src || !sink || bytes < 0 || (bytes & 15) || ((uintptr_t)src & 15))
+        return fail(RAGO_INVALID_ARG, "read stream needs a 16-byte aligned buffer, a size that is a multiple of 16 and a sink");
+    return launch_calib_read(src, bytes, sink, (hipStream_t)stream);
 }
 
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream) {

@@ -382,6 +382,44 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
 
 static DevBuf g_flat_keys[16], g_flat_cnt[16], g_flat_tbin[16];
 
+// Optional per-kernel timing of the flat search (HIP events on the caller's stream), per device.
+constexpr int FLAT_PROF_CALLS = 128;
+struct FlatProfiler {
+    bool on = false, created = false;
+    int ncalls = 0;
+    hipEvent_t ev[FLAT_PROF_CALLS][3];
+};
+static FlatProfiler g_flat_prof[16];
+
+int flat_profile(int device, int enable) {
+    if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
+    FlatProfiler& pr = g_flat_prof[device];
+    if (enable && !pr.created) {
+        for (auto& c : pr.ev)
+            for (auto& e : c) RAGO_HIP(hipEventCreate(&e));
+        pr.created = true;
+    }
+    pr.on = enable != 0;
+    if (enable) pr.ncalls = 0;
+    return RAGO_OK;
+}
+
+int flat_stage_ms(int device, float* out_ms, int32_t* out_calls) {
+    if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
+    FlatProfiler& pr = g_flat_prof[device];
+    out_ms[0] = out_ms[1] = 0.f;
+    *out_calls = pr.ncalls;
+    for (int c = 0; c < pr.ncalls; ++c) {
+        RAGO_HIP(hipEventSynchronize(pr.ev[c][2]));
+        for (int i = 0; i < 2; ++i) {
+            float ms = 0.f;
+            RAGO_HIP(hipEventElapsedTime(&ms, pr.ev[c][i], pr.ev[c][i + 1]));
+            out_ms[i] += ms / pr.ncalls;
+        }
+    }
+    return RAGO_OK;
+}
+
 // (a kernel rather than a memset node: the call may be recorded into a HIP graph by the caller)
 __global__ void flat_zero_kernel(int32_t* p, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -438,6 +476,9 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
     }
     const size_t lds = flat_lds_bytes(d);
     const int grid = R * nslab;
+    FlatProfiler& prof = g_flat_prof[device];
+    hipEvent_t* ev = prof.on && prof.ncalls < FLAT_PROF_CALLS ? prof.ev[prof.ncalls] : nullptr;
+    if (ev) RAGO_HIP(hipEventRecord(ev[0], st));
     switch (d) {
         case 64: rc = launch_flat_d<64>(P, grid, lds, half, st); break;
         case 128: rc = launch_flat_d<128>(P, grid, lds, half, st); break;
@@ -449,8 +490,10 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
         default: return fail(RAGO_UNSUPPORTED, "d must be one of 64, 128, 256, 384, 512, 768, 1024");
     }
     if (rc) return rc;
+    if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
     flat_merge_kernel<<<R * nqr, FM_THREADS, 0, st>>>(P, out_ids, out_scores);
     RAGO_HIP(hipGetLastError());
+    if (ev) { RAGO_HIP(hipEventRecord(ev[2], st)); ++prof.ncalls; }
     return RAGO_OK;
 }
 

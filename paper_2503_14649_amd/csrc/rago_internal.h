@@ -108,6 +108,8 @@ namespace rago {
 // layout.hip
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
 int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
+int launch_calib_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t st);
+int read_stream_sink_words();
 int launch_expand_pq4(const float* d_cb16, int m, int dsub, float* d_cb256, hipStream_t st);
 
 // coarse.hip
@@ -143,5 +145,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,
                 int64_t* out_ids, float* out_scores, int device, bool half, hipStream_t st);
+int flat_profile(int device, int enable);
+int flat_stage_ms(int device, float* out_ms, int32_t* out_calls);
 
 }  // namespace rago
