@@ -16,10 +16,15 @@
  *  - "DEVICE" pointers are HIP device memory on the index's GPU; "HOST" pointers are ordinary
  *    host memory.  The caller owns every buffer it passes and must keep DEVICE buffers alive
  *    until `stream` has passed the call.  The library owns the index and its workspace.
- *  - Search calls only enqueue work on `stream` (a hipStream_t, NULL = default stream); they do
- *    not synchronise with the host.  Argument errors are detected synchronously and leave the
- *    outputs untouched.  Calls on the same index must be serialised on one stream (they share
- *    the index's workspace).
+ *  - Search calls only enqueue work on `stream` (a hipStream_t, NULL = default stream).  Argument
+ *    errors are detected synchronously and leave the outputs untouched.  Calls on the same index
+ *    must be serialised on one stream (they share the index's workspace); so must the flat
+ *    searches on one device (they share a per-device workspace: two of them in flight at once,
+ *    from different streams or threads, overwrite each other's candidates).
+ *  - Workspace: after rago_index_reserve a search within the reserved maxima allocates nothing and
+ *    does not synchronise with the host.  Without it the workspace grows on demand: the first call
+ *    at a larger size frees and allocates device memory (which synchronises the device and cannot
+ *    be captured into a HIP graph); later calls at that size or below do not.
  *  - Nothing here allocates through, links against, or knows about PyTorch.
  */
 #ifndef RAGO_H
@@ -116,6 +121,16 @@ int rago_index_set_upper_level(rago_index* idx, int32_t nsuper, const float* sup
                                const int32_t* super_lists, int arrays_on_device);
 int rago_index_set_upper_probe(rago_index* idx, int32_t nsp);
 
+/*
+ * rago_index_reserve: size the index's workspace once for every search with nq <= max_nq,
+ * nprobe <= max_nprobe and k <= max_k (either metric's tables, either scan kernel, and the stage
+ * through the upper level if the index has one at this point).  Afterwards rago_ivfpq_search within
+ * those maxima performs no allocation, free or host synchronisation, and a search beyond them fails
+ * with RAGO_UNSUPPORTED and leaves the workspace as it is (reserve again for larger maxima).  The
+ * call synchronises the device.  Limits and errors as for rago_ivfpq_search, plus RAGO_OOM.
+ */
+int rago_index_reserve(rago_index* idx, int64_t max_nq, int32_t max_nprobe, int32_t max_k);
+
 /* Release the index and its workspace (synchronises the device).  NULL is accepted. */
 int rago_index_free(rago_index* idx);
 
@@ -135,10 +150,13 @@ int rago_index_info(const rago_index* idx, rago_index_desc* out);
  *   out_ids     DEVICE [nq][k] int64, best first, padded with -1
  *   out_scores  DEVICE [nq][k] fp32 = integer score * the query's table step; pad = -inf
  *   out_iscores DEVICE [nq][k] int32 or NULL; pad = INT32_MIN
- * The workspace grows on demand (first call at a new size allocates; later calls do not).
+ * Workspace: see rago_index_reserve and the conventions at the top.
  * The scan runs one of two kernels, chosen from the batch and list sizes (long tasks with lists
- * shared by several queries: four (query, list) pairs per pass of a list; otherwise two);
- * RAGO_SCAN_KERNEL=wide|narrow in the environment forces one of them (results are identical).
+ * shared by several queries: four (query, list) pairs per pass of a list; otherwise two); results
+ * are identical (rago_debug_force_scan_kernel pins one of them for tests).
+ * ids must ascend inside every list (RAGO_FORMAT at load otherwise): the scan orders equal scores by
+ * position in the list, which is the order by id only then; an index writer sorts each list once,
+ * where it has the vectors at hand, rather than every load permuting ~100 GB of codes.
  */
 int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k,
                       int64_t* out_ids, float* out_scores, int32_t* out_iscores, void* stream);
@@ -152,7 +170,9 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
  *   out_ids      DEVICE [R][nqr][k] int64 row index inside the request's corpus, pad -1
  *   out_scores   DEVICE [R][nqr][k] fp32 (bf16 products, fp32 accumulation), pad -inf
  * Order: score descending, ties by lower index.  `device` = GPU of the buffers.
- * Uses a per-device workspace owned by the library (grown on demand).
+ * Uses a per-device workspace owned by the library, grown on demand (the first call at a larger
+ * R * n allocates, which synchronises the device); flat searches on one device must therefore be
+ * serialised on one stream.
  */
 int rago_flat_search(const void* corpus_bf16, const void* queries_bf16, int32_t R, int64_t n, int32_t nqr,
                      int32_t d, int32_t k, int64_t* out_ids, float* out_scores, int device, void* stream);
@@ -182,8 +202,10 @@ int rago_debug_select_tree(rago_index* idx, const float* queries, int64_t nq, in
                            int32_t* out_groups, void* stream);
 
 /* The nprobe best lists per query, best first, ties by lower list number.  Scores of the lists
- * near the cut are recomputed in fp64 from `queries`, so the choice does not depend on the
- * rounding of S.  S DEVICE [nq][nlist]; out_probes DEVICE [nq][nprobe] int32. */
+ * near the cut are recomputed in fp64 from `queries`, and a query whose scores are packed more
+ * closely around the cut than the rounding error of S is selected again on exact scores of all
+ * lists, so the choice never depends on the rounding of S.
+ * S DEVICE [nq][nlist] (not modified); out_probes DEVICE [nq][nprobe] int32. */
 int rago_debug_select(rago_index* idx, const float* queries, const float* S, int64_t nq, int32_t nprobe,
                       int32_t* out_probes, void* stream);
 
@@ -204,12 +226,20 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
 /* Counters of the last search on this index, HOST out[8] (synchronises `stream`):
  * [0] scan tasks, [1] code bytes streamed by the scan (a pass over a list serves up to four, or
  * two, of its pairs), [2] algorithmic code bytes
- * (sum over (query, probe) of list length * m), [3] queries whose probe choice was not
- * provably independent of fp32 rounding, [4] table entries whose rounding had to be evaluated per
+ * (sum over (query, probe) of list length * m), [3] queries whose probe choice had to be made on
+ * exact scores of all lists (it could not be shown independent of fp32 rounding otherwise), [4] table entries whose rounding had to be evaluated per
  * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
  * for every pair (Euclidean metric: [4] entries re-evaluated in fp64 over both table passes, [5]
  * workgroups that re-evaluated all their entries, counted once per pass), [6..7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
+
+/* Pin the scan kernel of every following search in this process: 0 = chosen from the sizes (default),
+ * 1 = the four-pairs-per-pass kernel, 2 = the two-pairs-per-pass kernel.  For tests. */
+int rago_debug_force_scan_kernel(int which);
+
+/* Number of device allocations the library's workspaces have made in this process so far (a test
+ * reads it before and after searches that must not allocate). */
+int64_t rago_debug_allocations(void);
 
 /* Plain copy kernel (rago_calib_copy_kernel) of `bytes` bytes, DEVICE src -> DEVICE dst, both
  * 16-byte aligned, bytes % 16 == 0, on the current device: a transfer of known size against which

@@ -36,6 +36,9 @@ _lib.rago_last_error.restype = ctypes.c_char_p
 _lib.rago_index_load.argtypes = [ctypes.c_char_p, _int, ctypes.POINTER(_vp)]
 _lib.rago_index_wrap.argtypes = [ctypes.POINTER(_Arrays), _int, _int, ctypes.POINTER(_vp)]
 _lib.rago_index_free.argtypes = [_vp]
+_lib.rago_index_reserve.argtypes = [_vp, _i64, _i32, _i32]
+_lib.rago_debug_force_scan_kernel.argtypes = [_int]
+_lib.rago_debug_allocations.restype = _i64
 _lib.rago_index_info.argtypes = [_vp, ctypes.POINTER(IndexDesc)]
 _lib.rago_ivfpq_search.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.rago_flat_search.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _vp, _vp, _int, _vp]
@@ -234,6 +237,21 @@ def rago_debug_copy(src: torch.Tensor, dst: torch.Tensor):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _chk(_lib.rago_debug_copy(_ptr(src), _ptr(dst), nbytes, _stream(src.device)))
+
+
+def rago_index_reserve(h, max_nq: int, max_nprobe: int, max_k: int):
+    _chk(_lib.rago_index_reserve(h, max_nq, max_nprobe, max_k))
+
+
+SCAN_KERNELS = {"auto": 0, "wide": 1, "narrow": 2}
+
+
+def rago_debug_force_scan_kernel(which):
+    _chk(_lib.rago_debug_force_scan_kernel(SCAN_KERNELS[which] if isinstance(which, str) else int(which)))
+
+
+def rago_debug_allocations() -> int:
+    return int(_lib.rago_debug_allocations())
 
 
 def rago_debug_read_stream(src: torch.Tensor, sink: torch.Tensor):

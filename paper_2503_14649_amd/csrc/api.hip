@@ -1,4 +1,5 @@
 // C ABI of librago: index life-cycle, argument checking, stage sequencing.
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -13,8 +14,19 @@ static thread_local std::string g_err;
 void set_error(const std::string& msg) { g_err = msg; }
 int fail(int code, const std::string& msg) { g_err = msg; return code; }
 
+static thread_local int tl_no_grow = 0;
+static std::atomic<long long> g_allocations{0};
+static std::atomic<int> g_forced_scan{0};
+NoGrowScope::NoGrowScope(bool on) : active(on) { if (active) ++tl_no_grow; }
+NoGrowScope::~NoGrowScope() { if (active) --tl_no_grow; }
+long long device_allocations() { return g_allocations.load(); }
+int forced_scan_kernel() { return g_forced_scan.load(); }
+
 int DevBuf::reserve(size_t bytes) {
     if (bytes <= cap) return RAGO_OK;
+    if (tl_no_grow)
+        return fail(RAGO_UNSUPPORTED, "the call needs more workspace than rago_index_reserve sized (" + std::to_string(bytes) +
+                                          " > " + std::to_string(cap) + " bytes); reserve again for larger maxima");
     if (p) { hipFree(p); p = nullptr; cap = 0; }
     size_t want = bytes + bytes / 8 + 256;
     if (hipMalloc(&p, want) != hipSuccess) {
@@ -22,6 +34,7 @@ int DevBuf::reserve(size_t bytes) {
         (void)hipGetLastError();
         return fail(RAGO_OOM, "device allocation of " + std::to_string(want) + " bytes failed");
     }
+    ++g_allocations;
     cap = want;
     return RAGO_OK;
 }
@@ -29,7 +42,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo};
     for (DevBuf* b : all) b->release();
 }
 
@@ -133,6 +146,9 @@ static int finish(rago_index* idx, const uint8_t* d_codes_plain) {
     float mx = 0.f;
     for (float v : cn) if (v > mx) mx = v;
     idx->max_cnorm = mx;
+    hipDeviceProp_t pr;
+    RAGO_HIP(hipGetDeviceProperties(&pr, idx->device));
+    idx->n_cu = pr.multiProcessorCount;
     return RAGO_OK;
 }
 
@@ -347,7 +363,10 @@ int rago_debug_select(rago_index* idx, const float* queries, const float* S, int
     if (nq > 0 && !queries) return fail(RAGO_INVALID_ARG, "null queries");
     if (nq == 0) return RAGO_OK;
     DeviceGuard g(idx->device);
-    return launch_select(idx, queries, S, nq, nprobe, out_probes, (hipStream_t)stream);
+    // the selection may replace a row by exact scores: it works on a copy, the caller's S stays as it is
+    if ((rc = idx->ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
+    RAGO_HIP(hipMemcpyAsync(idx->ws.S.p, S, (size_t)nq * idx->nlist * 4, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return launch_select(idx, queries, idx->ws.S.as<float>(), nq, nprobe, out_probes, (hipStream_t)stream);
 }
 
 int rago_debug_select_tree(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t* out_probes,
@@ -404,22 +423,16 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
     return launch_scan(idx, probes, ws.tmp_lut8sw.as<uint8_t>(), B, nullptr, nullptr, nq, nprobe, k, out_ids, nullptr, out_iscores, st);
 }
 
-int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids,
-                      float* out_scores, int32_t* out_iscores, void* stream) {
-    int rc = check_search_args(idx, queries, out_ids, nq, nprobe, k);
-    if (rc) return rc;
-    if (nq > 0 && !out_scores) return fail(RAGO_INVALID_ARG, "null out_scores");
-    if (((uintptr_t)queries & 15) != 0) return fail(RAGO_INVALID_ARG, "queries must be 16-byte aligned");
-    if (nq == 0) return RAGO_OK;
-    DeviceGuard g(idx->device);
+// The stages of a search in order.  With idx->reserving set every stage launcher sizes its buffers and returns
+// before launching anything, so the same code that runs a search also sizes the workspace for it.
+static int run_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids,
+                      float* out_scores, int32_t* out_iscores, hipStream_t st, hipEvent_t* ev, bool tree) {
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
+    int rc;
     if ((rc = ws.probes.reserve((size_t)npairs * 4))) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    hipEvent_t* ev = nullptr;
-    if (idx->prof.on && idx->prof.ncalls < PROF_CALLS) ev = idx->prof.ev[idx->prof.ncalls];
     if (ev) RAGO_HIP(hipEventRecord(ev[0], st));
-    if (idx->nsp > 0) {
+    if (tree) {
         // through the upper level: both steps in one (the coarse-score slot of the stage times stays empty)
         if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
         if ((rc = launch_select_tree(idx, queries, nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
@@ -437,15 +450,63 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
         rc = launch_scan(idx, ws.probes.as<int32_t>(), ws.tmp_lut8sw.as<uint8_t>(), ws.bias.as<int32_t>(), nullptr,
                          ws.delta.as<float>(), nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev);
     } else {
-        LutTables T;
+        LutTables T{};
         if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st))) return rc;
         if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
         rc = launch_scan(idx, ws.probes.as<int32_t>(), nullptr, T.bias, &T, T.delta, nq, nprobe, k, out_ids, out_scores,
                          out_iscores, st, ev);
     }
+    return rc;
+}
+
+int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t nprobe, int32_t k, int64_t* out_ids,
+                      float* out_scores, int32_t* out_iscores, void* stream) {
+    int rc = check_search_args(idx, queries, out_ids, nq, nprobe, k);
+    if (rc) return rc;
+    if (nq > 0 && !out_scores) return fail(RAGO_INVALID_ARG, "null out_scores");
+    if (((uintptr_t)queries & 15) != 0) return fail(RAGO_INVALID_ARG, "queries must be 16-byte aligned");
+    if (nq == 0) return RAGO_OK;
+    DeviceGuard g(idx->device);
+    NoGrowScope frozen(idx->ws_frozen);
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t* ev = nullptr;
+    if (idx->prof.on && idx->prof.ncalls < PROF_CALLS) ev = idx->prof.ev[idx->prof.ncalls];
+    rc = run_search(idx, queries, nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev, idx->nsp > 0);
     if (!rc && ev) ++idx->prof.ncalls;
     return rc;
 }
+
+int rago_index_reserve(rago_index* idx, int64_t max_nq, int32_t max_nprobe, int32_t max_k) {
+    if (!idx) return fail(RAGO_INVALID_ARG, "null index");
+    if (max_nq < 1 || max_nprobe < 1 || max_k < 1) return fail(RAGO_INVALID_ARG, "maxima must be >= 1");
+    if (max_nprobe > idx->nlist) max_nprobe = idx->nlist;
+    int rc = check_search_args(idx, idx, idx, max_nq, max_nprobe, max_k);
+    if (rc) return rc;
+    DeviceGuard g(idx->device);
+    RAGO_HIP(hipDeviceSynchronize());           // buffers that grow are freed: nothing may still be using them
+    idx->ws_frozen = false;
+    idx->reserving = true;
+    rc = run_search(idx, nullptr, max_nq, max_nprobe, max_k, nullptr, nullptr, nullptr, nullptr, nullptr, false);
+    if (!rc && idx->nsuper > 0) {
+        // the stage through the upper level, for any number of kept groups
+        const int nsp = idx->nsp;
+        idx->nsp = idx->nsuper;
+        rc = launch_select_tree(idx, nullptr, max_nq, max_nprobe, idx->ws.probes.as<int32_t>(), nullptr);
+        idx->nsp = nsp;
+    }
+    idx->reserving = false;
+    if (rc) return rc;
+    idx->ws_frozen = true;
+    return RAGO_OK;
+}
+
+int rago_debug_force_scan_kernel(int which) {
+    if (which < 0 || which > 2) return fail(RAGO_INVALID_ARG, "0 = pick by sizes, 1 = wide, 2 = narrow");
+    g_forced_scan.store(which);
+    return RAGO_OK;
+}
+
+int64_t rago_debug_allocations(void) { return (int64_t)device_allocations(); }
 
 int rago_debug_profile(rago_index* idx, int enable) {
     if (!idx) return fail(RAGO_INVALID_ARG, "null index");

@@ -14,7 +14,9 @@
 //    E = (d * 2^-22 + 2^-16) * |q| * max|c| bounding the accumulation error and that of the split
 //    product; when the nprobe-th exact score
 //    exceeds that, no outside list can belong to the result.  Queries where this cannot be shown
-//    are counted (never observed on the workloads here).
+//    (scores packed closer than E around the cut) are queued; a second launch of the same kernel
+//    replaces their rows by exact scores and selects again, so the result is always the one exact
+//    scores give.  (Never needed on the workloads here; the counter says how often it was.)
 #include "rago_internal.h"
 
 namespace rago {
@@ -276,10 +278,12 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
     if (idx->metric == 1) {
         int rc = idx->ws.qn2.reserve((size_t)nq * 4);
         if (rc) return rc;
+        if (idx->reserving) return RAGO_OK;
         qnorm2_kernel<<<(unsigned)((nq + 3) / 4), 256, 0, st>>>(q, nq, d, idx->ws.qn2.as<float>());
         qn2 = idx->ws.qn2.as<float>();
         cn2 = idx->cn2;
     }
+    if (idx->reserving) return RAGO_OK;
     const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
     if (nq <= 32) {
         coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S);
@@ -313,9 +317,9 @@ __device__ __forceinline__ uint32_t float_key(float f) {  // ascending uint orde
 // REG = 0: rows of any length, re-read from L2 in every pass.
 template <int REG>
 __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __restrict__ Q, const float* __restrict__ C,
-                                                             const float* __restrict__ S, int nlist, int d, int nprobe,
+                                                             float* S, int nlist, int d, int nprobe,
                                                              float max_cnorm, int metric, int32_t* __restrict__ probes,
-                                                             int64_t* __restrict__ counters) {
+                                                             int64_t* counters, int32_t* redo_q, int redo) {
     // 32 copies of every bin, copy = lane % 32: the lanes of a half-wave never share an LDS word,
     // so the atomics run at full rate even when all scores fall into one bin (pass 0: same exponent)
     __shared__ int hist32[256 * 32];
@@ -326,11 +330,81 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     __shared__ int s_weq[SEL_WAVES];
     __shared__ int c_idx[SEL_CAP];
     __shared__ float c_val[SEL_CAP];
-    const int64_t q = blockIdx.x;
-    const float* row = S + q * nlist;
+    // Second launch (`redo`): only the queries whose choice the first launch could not show independent of the
+    // rounding of S.  Their rows are replaced by exact scores (fp64 accumulation, one rounding) and selected again.
+    if (redo && (int64_t)blockIdx.x >= counters[3]) return;
+    const int64_t q = redo ? redo_q[blockIdx.x] : blockIdx.x;
+    float* row = S + q * nlist;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (redo) {
+        const float* qx = Q + q * d;
+        for (int l = wave; l < nlist; l += SEL_WAVES) {
+            const float* cx = C + (int64_t)l * d;
+            double acc = 0.0;
+            for (int t = lane; t < d; t += 64) {
+                if (metric == 1) { const double diff = (double)qx[t] - (double)cx[t]; acc = acc + diff * diff; }
+                else acc = acc + (double)qx[t] * (double)cx[t];
+            }
+            for (int o = 32; o; o >>= 1) acc = acc + __shfl_xor(acc, o);
+            if (lane == 0) row[l] = metric == 1 ? (float)(-acc) : (float)acc;
+        }
+        __threadfence();
+        __syncthreads();
+    }
     const int want = min(nprobe + SEL_EXTRA, nlist);
     constexpr int NR = REG > 0 ? REG : 1;
+    // Exact scores (fp64 accumulation, one rounding to fp32) of n rows of C, RU per wave at a time: the rows come
+    // from HBM at random, and the time of this step is the number of such rounds times the latency of a loaded
+    // memory system; with 16-byte loads a lane has d / 256 loads per row, so a whole round is in flight at once.
+    const float* qv = Q + q * d;
+    constexpr int RU = 8;
+    const bool vec4 = (d & 3) == 0;
+    auto exact_scores = [&](int n, auto row_of, auto store) {
+        for (int c0 = wave * RU; c0 < n; c0 += SEL_WAVES * RU) {
+            double acc[RU];
+            const float* cv[RU];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) { acc[u] = 0.0; cv[u] = C + (int64_t)row_of(min(c0 + u, n - 1)) * d; }
+            if (vec4) {
+                for (int t = lane * 4; t < d; t += 256) {
+                    const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
+                    float4 c4[RU];
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
+                    const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) {
+                        const double ca[4] = {(double)c4[u].x, (double)c4[u].y, (double)c4[u].z, (double)c4[u].w};
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            if (metric == 1) { const double diff = qa[x] - ca[x]; acc[u] = acc[u] + diff * diff; }
+                            else acc[u] = acc[u] + qa[x] * ca[x];
+                        }
+                    }
+                }
+            } else if (metric == 1) {
+                for (int t = lane; t < d; t += 64) {
+                    const double qt = (double)qv[t];
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) {
+                        const double diff = qt - (double)cv[u][t];
+                        acc[u] = acc[u] + diff * diff;
+                    }
+                }
+            } else {
+                for (int t = lane; t < d; t += 64) {
+                    const double qt = (double)qv[t];
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
+                if (lane == 0 && c0 + u < n) store(c0 + u, metric == 1 ? (float)(-acc[u]) : (float)acc[u]);
+            }
+        }
+    };
     uint32_t key[NR];
     if (REG > 0) {
 #pragma unroll
@@ -460,59 +534,10 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     __syncthreads();
 
     // ---- exact scores of the candidates: fp64 accumulation, one rounding to fp32
-    const float* qv = Q + q * d;
     float qn = 0.f;
     for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
     for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
-    // (RU candidates per wave at a time: the rows come from HBM at random, and the time of this step is the
-    // number of such rounds times the latency of a loaded memory system; with 16-byte loads a lane has
-    // d / 256 loads per row, so a whole round is in flight at once)
-    constexpr int RU = 8;
-    const bool vec4 = (d & 3) == 0;
-    for (int c0 = wave * RU; c0 < want; c0 += SEL_WAVES * RU) {
-        double acc[RU];
-        const float* cv[RU];
-#pragma unroll
-        for (int u = 0; u < RU; ++u) { acc[u] = 0.0; cv[u] = C + (int64_t)c_idx[min(c0 + u, want - 1)] * d; }
-        if (vec4) {
-            for (int t = lane * 4; t < d; t += 256) {
-                const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
-                float4 c4[RU];
-#pragma unroll
-                for (int u = 0; u < RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
-                const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
-#pragma unroll
-                for (int u = 0; u < RU; ++u) {
-                    const double ca[4] = {(double)c4[u].x, (double)c4[u].y, (double)c4[u].z, (double)c4[u].w};
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        if (metric == 1) { const double diff = qa[x] - ca[x]; acc[u] = acc[u] + diff * diff; }
-                        else acc[u] = acc[u] + qa[x] * ca[x];
-                    }
-                }
-            }
-        } else if (metric == 1) {
-            for (int t = lane; t < d; t += 64) {
-                const double qt = (double)qv[t];
-#pragma unroll
-                for (int u = 0; u < RU; ++u) {
-                    const double diff = qt - (double)cv[u][t];
-                    acc[u] = acc[u] + diff * diff;
-                }
-            }
-        } else {
-            for (int t = lane; t < d; t += 64) {
-                const double qt = (double)qv[t];
-#pragma unroll
-                for (int u = 0; u < RU; ++u) acc[u] = acc[u] + qt * (double)cv[u][t];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < RU; ++u) {
-            for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
-            if (lane == 0 && c0 + u < want) c_val[c0 + u] = metric == 1 ? (float)(-acc[u]) : (float)acc[u];
-        }
-    }
+    exact_scores(want, [&](int c) { return c_idx[c]; }, [&](int c, float v) { c_val[c] = v; });
     __syncthreads();
     if (want <= SEL_THREADS) {
         // ---- order by (score desc, list asc): one 64-bit key per candidate (ordered score bits, then the complement
@@ -562,7 +587,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         __syncthreads();
     }
     for (int p = tid; p < nprobe; p += SEL_THREADS) probes[q * nprobe + p] = c_idx[p];
-    if (tid == 0 && want < nlist) {
+    if (tid == 0 && !redo && want < nlist) {
         // smallest fp32 score among the candidates = score with key `kth`
         const uint32_t u = (kth & 0x80000000u) ? (kth & 0x7fffffffu) : ~kth;
         const float s_cut = __uint_as_float(u);
@@ -570,29 +595,40 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
         float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
         if (metric == 1) E = 2.0f * E + 4.76837158203125e-07f * (qn + max_cnorm * max_cnorm);
         E += (float)d * 2.4e-38f;        // products that underflow (the matrix cores may flush subnormal numbers)
-        if (!(c_val[nprobe - 1] > s_cut + E)) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull);
+        // A list outside the candidates has an exact score <= s_cut + E.  If the nprobe-th exact score is above
+        // that, the choice is the one exact scores give.  Otherwise (scores packed closer than the product's
+        // error around the cut) the query is queued for the second launch; counters[3] counts them.
+        if (!(c_val[nprobe - 1] > s_cut + E))
+            redo_q[atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull)] = (int32_t)q;
     }
 }
 
 __global__ void zero_counter_kernel(int64_t* counters) { counters[3] = 0; }
 
-int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st) {
+int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st) {
     if (nprobe + SEL_EXTRA > SEL_CAP && nprobe < idx->nlist && idx->nlist > SEL_CAP)
         return fail(RAGO_UNSUPPORTED, "nprobe > 2016 on an index with more than 2048 lists");
     if (std::min(nprobe + SEL_EXTRA, idx->nlist) > SEL_CAP) return fail(RAGO_UNSUPPORTED, "nprobe > 2016");
     int rc;
     if ((rc = idx->ws.counters.reserve(64))) return rc;
+    if ((rc = idx->ws.sel_redo.reserve((size_t)nq * 4))) return rc;
+    if (idx->reserving) return RAGO_OK;
     zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
     int64_t* cnt = idx->ws.counters.as<int64_t>();
+    int32_t* rq = idx->ws.sel_redo.as<int32_t>();
     const int nl = idx->nlist;
-    if (nl <= 8 * SEL_THREADS)
-        select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
-    else if (nl <= 32 * SEL_THREADS)
-        select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
-    else if (nl <= 64 * SEL_THREADS)
-        select_kernel<64><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
-    else
-        select_kernel<0><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt);
+    // first the whole batch on the approximate scores, then (second launch, whose workgroups leave at once when
+    // the first queued nothing) the queued queries on exact ones
+    for (int redo = 0; redo < 2; ++redo) {
+        if (nl <= 8 * SEL_THREADS)
+            select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
+        else if (nl <= 32 * SEL_THREADS)
+            select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
+        else if (nl <= 64 * SEL_THREADS)
+            select_kernel<64><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
+        else
+            select_kernel<0><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
+    }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }

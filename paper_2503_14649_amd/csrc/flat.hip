@@ -130,7 +130,7 @@ struct FlatParams {
     int64_t slab_rows;        // rows per slab (multiple of 16)
     uint64_t* cand;           // [R][nslab][16][FLAT_CAP] candidate keys of each slab (its first k = the slab's result)
     int32_t* part_cnt;        // [R][nslab][16]
-    int32_t* shared_tbin;     // [R][16] threshold bin reached by any slab of the request (zero between calls)
+    int32_t* shared_tbin;     // [R][16] threshold bin reached by any slab of the request (zeroed at the start of every call)
 };
 
 typedef uint32_t f_u32x4 __attribute__((ext_vector_type(4)));
@@ -367,7 +367,6 @@ __global__ void __launch_bounds__(FM_THREADS) flat_merge_kernel(const FlatParams
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) P.shared_tbin[r * 16 + q] = 0;   // ready for the next call
     for (int j = threadIdx.x; j < P.k; j += FM_THREADS) {
         const int64_t o = ((int64_t)r * P.nqr + q) * P.k + j;
         if (j < fill) {
@@ -442,43 +441,39 @@ static int launch_flat_d(const FlatParams& P, int grid, size_t lds, bool half, h
     return half ? launch_flat_dh<D, true>(P, grid, lds, st) : launch_flat_dh<D, false>(P, grid, lds, st);
 }
 
-int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k, int64_t* out_ids,
-                float* out_scores, int device, bool half, hipStream_t st) {
-    if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
-    if (d % 64 || d > FLAT_MAXD) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 64, at most 1024");
-    FlatParams P;
-    P.corpus = static_cast<const uint16_t*>(corpus);
-    P.queries = static_cast<const uint16_t*>(queries);
-    P.n = n; P.R = R; P.nqr = nqr; P.d = d; P.k = k;
-    // slabs: at least one round each
-    // one resident wave of workgroups (2 per CU): per-slab start-up (unfiltered first round) is paid once per slot
-    const int target = 512;
-    int nslab = (int)std::min<int64_t>((target + R - 1) / R, (n + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS);
+// Slabs of whole rounds, about `target` workgroups in all (never more when `exact`).
+static void flat_slabs(int R, int64_t n, int target, bool exact, int* nslab_out, int64_t* slab_rows_out) {
+    const int per_request = exact ? std::max(1, target / R) : (target + R - 1) / R;
+    int nslab = (int)std::min<int64_t>(per_request, (n + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS);
     nslab = std::max(1, nslab);
     int64_t slab_rows = (n + nslab - 1) / nslab;
     slab_rows = (slab_rows + FLAT_ROUND_ROWS - 1) / FLAT_ROUND_ROWS * FLAT_ROUND_ROWS;
     if (slab_rows == 0) slab_rows = FLAT_ROUND_ROWS;
-    nslab = (int)std::max<int64_t>(1, (n + slab_rows - 1) / slab_rows);
+    *nslab_out = (int)std::max<int64_t>(1, (n + slab_rows - 1) / slab_rows);
+    *slab_rows_out = slab_rows;
+}
+
+// Both kernels of a flat search on given scratch memory: cand [R * nslab][16][FLAT_CAP] keys,
+// part_cnt [R * nslab][16], tbin [R][16].
+static int run_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k, int64_t* out_ids,
+                    float* out_scores, int device, bool half, hipStream_t st, int nslab, int64_t slab_rows, uint64_t* cand,
+                    int32_t* part_cnt, int32_t* tbin) {
+    FlatParams P;
+    P.corpus = static_cast<const uint16_t*>(corpus);
+    P.queries = static_cast<const uint16_t*>(queries);
+    P.n = n; P.R = R; P.nqr = nqr; P.d = d; P.k = k;
     P.nslab = nslab; P.slab_rows = slab_rows;
-    int rc;
-    if ((rc = g_flat_keys[device].reserve((size_t)R * nslab * 16 * FLAT_CAP * 8))) return rc;
-    if ((rc = g_flat_cnt[device].reserve((size_t)R * nslab * 16 * 4))) return rc;
-    P.cand = g_flat_keys[device].as<uint64_t>();
-    P.part_cnt = g_flat_cnt[device].as<int32_t>();
-    {
-        const size_t need = (size_t)R * 16 * 4;
-        if (need > g_flat_tbin[device].cap) {          // (re)allocation: start from all-zero bins
-            if ((rc = g_flat_tbin[device].reserve(need))) return rc;
-            flat_zero_kernel<<<64, 256, 0, st>>>(g_flat_tbin[device].as<int32_t>(), (int64_t)(g_flat_tbin[device].cap / 4));
-            RAGO_HIP(hipGetLastError());
-        }
-        P.shared_tbin = g_flat_tbin[device].as<int32_t>();
-    }
+    P.cand = cand; P.part_cnt = part_cnt; P.shared_tbin = tbin;
+    // the request-wide threshold bins start at zero (a kernel, not a memset node: the call may be
+    // recorded into a HIP graph by the caller)
+    flat_zero_kernel<<<(R * 16 + 255) / 256, 256, 0, st>>>(tbin, (int64_t)R * 16);
+    RAGO_HIP(hipGetLastError());
     const size_t lds = flat_lds_bytes(d);
     const int grid = R * nslab;
     FlatProfiler& prof = g_flat_prof[device];
     hipEvent_t* ev = prof.on && prof.ncalls < FLAT_PROF_CALLS ? prof.ev[prof.ncalls] : nullptr;
     if (ev) RAGO_HIP(hipEventRecord(ev[0], st));
+    int rc;
     switch (d) {
         case 64: rc = launch_flat_d<64>(P, grid, lds, half, st); break;
         case 128: rc = launch_flat_d<128>(P, grid, lds, half, st); break;
@@ -495,6 +490,22 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
     RAGO_HIP(hipGetLastError());
     if (ev) { RAGO_HIP(hipEventRecord(ev[2], st)); ++prof.ncalls; }
     return RAGO_OK;
+}
+
+int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k, int64_t* out_ids,
+                float* out_scores, int device, bool half, hipStream_t st) {
+    if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
+    if (d % 64 || d > FLAT_MAXD) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 64, at most 1024");
+    // one resident wave of workgroups (2 per CU): per-slab start-up (unfiltered first round) is paid once per slot
+    int nslab;
+    int64_t slab_rows;
+    flat_slabs(R, n, 512, false, &nslab, &slab_rows);
+    int rc;
+    if ((rc = g_flat_keys[device].reserve((size_t)R * nslab * 16 * FLAT_CAP * 8))) return rc;
+    if ((rc = g_flat_cnt[device].reserve((size_t)R * nslab * 16 * 4))) return rc;
+    if ((rc = g_flat_tbin[device].reserve((size_t)R * 16 * 4))) return rc;
+    return run_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, st, nslab, slab_rows,
+                    g_flat_keys[device].as<uint64_t>(), g_flat_cnt[device].as<int32_t>(), g_flat_tbin[device].as<int32_t>());
 }
 
 }  // namespace rago

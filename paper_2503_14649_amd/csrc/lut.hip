@@ -379,6 +379,7 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     uint16_t* amb_addr = ws.amb.as<uint16_t>();
     int32_t* namb = reinterpret_cast<int32_t*>(amb_addr + nq * AMB_MAX);
     if ((rc = ws.counters.reserve(64))) return rc;
+    if (idx->reserving) return RAGO_OK;
     const int ppw = npairs >= 32768 ? 8 : 1;
     const unsigned tg = (unsigned)((nq * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
     if (d / m == 8 && d % 4 == 0) {      // (16-byte loads of the sub-vectors)
@@ -426,6 +427,7 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
     if ((rc = ws.bias.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.delta.reserve((size_t)nq * 4))) return rc;
     if ((rc = ws.counters.reserve(64))) return rc;
+    if (idx->reserving) return lut_l2_fast_supported(idx) ? launch_lut_l2_fast(idx, q, probes, npairs, nprobe, nullptr, nullptr, nullptr, st) : RAGO_OK;
     uint32_t* range_bits = reinterpret_cast<uint32_t*>(ws.Tmax.as<double>() + nq * m);
     float* lo = ws.pair_lo.as<float>();
     fill_u32_kernel<<<(unsigned)std::min<int64_t>(1024, (nq + 255) / 256), 256, 0, st>>>(range_bits, 0u, nq);

@@ -482,6 +482,7 @@ int launch_l2m(rago_index* idx, const float* q, const int32_t* probes, int64_t n
     int rc;
     const int64_t npad = (npairs + 31) / 32 * 32;                     // whole tiles of 32 pairs
     if ((rc = ws.l2_r.reserve((size_t)npad * m * 2 * L2M<DSUB>::KS * 4))) return rc;
+    if (idx->reserving) return RAGO_OK;
     float* rec = ws.l2_r.as<float>();
     l2m_prepare_kernel<DSUB><<<(unsigned)((npad * m + 255) / 256), 256, 0, st>>>(q, idx->centroids, idx->cb_absmax, probes, npairs, nprobe, d, m, rec);
     // Large batches: 64 pairs per workgroup (each codeword load serves two column tiles).  Fewer than ~4 such

@@ -38,19 +38,29 @@ struct OncePerDevice {
             return ::rago::fail(RAGO_DEVICE, std::string(#call) + ": " + hipGetErrorString(e_)); \
     } while (0)
 
-// Grow-only device buffer.
+// Grow-only device buffer.  Growing frees and allocates (which synchronises the device), so a caller
+// that must not do either sizes the workspace once with rago_index_reserve; searches on that index then
+// run with growth switched off (NoGrowScope) and fail with RAGO_UNSUPPORTED rather than allocate.
 struct DevBuf {
     void* p = nullptr;
     size_t cap = 0;
-    int reserve(size_t bytes);   // RAGO_OK / RAGO_OOM
+    int reserve(size_t bytes);   // RAGO_OK / RAGO_OOM / RAGO_UNSUPPORTED (growth switched off)
     void release();
     template <class T> T* as() const { return static_cast<T*>(p); }
 };
 
+struct NoGrowScope {             // while alive on this thread, DevBuf::reserve refuses to grow
+    bool active;
+    explicit NoGrowScope(bool on);
+    ~NoGrowScope();
+};
+long long device_allocations();  // number of times any DevBuf grew (process-wide)
+int forced_scan_kernel();        // 0 = pick by sizes, 1 = wide, 2 = narrow (rago_debug_force_scan_kernel)
+
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo;
     void release();
 };
 
@@ -97,6 +107,9 @@ struct rago_index {
     int64_t* sup_off = nullptr;    // [nsuper+1] into sup_lists
     int32_t* sup_lists = nullptr;  // [nlist] lists grouped by group, ascending inside a group
     int32_t* sup_of = nullptr;     // [nlist] group of each list
+    int n_cu = 0;                  // compute units of `device`
+    bool reserving = false;        // rago_index_reserve: the stage launchers size their buffers and return
+    bool ws_frozen = false;        // the workspace was sized by rago_index_reserve: searches do not grow it
     rago::Workspace ws;
     rago::Profiler prof;
     // parameters of the last scan (for rago_debug_counters)
@@ -115,7 +128,8 @@ int launch_expand_pq4(const float* d_cb16, int m, int dsub, float* d_cb256, hipS
 // coarse.hip
 int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);
 int launch_split_centroids(rago_index* idx, hipStream_t st);
-int launch_select(rago_index* idx, const float* q, const float* S, int64_t nq, int nprobe, int32_t* probes,
+// (S is read and, for a query whose choice cannot be shown independent of its rounding, overwritten with exact scores)
+int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes,
                   hipStream_t st);
 
 // tree.hip

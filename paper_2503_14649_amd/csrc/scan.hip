@@ -997,37 +997,74 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
     return RAGO_OK;
 }
 
+// Which kernel and which chunk length.  The wide kernel (four pairs per pass, one workgroup per CU) pays a
+// fixed price per task that only long tasks amortise; short lists and small batches go to the narrow one
+// (two pairs per pass, two workgroups per CU); rago_debug_force_scan_kernel overrides the choice (tests run
+// every case through both).  Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key,
+// 0xFFFF - position, then never vanishes, so a key is never 0 = "empty")
+struct ScanPlan { bool wide; int CH, group, maxchunks; };
+
+static int chunk_len(double npairs, double avgblk, double pairs_per_task, int cap) {
+    int c = 16;
+    while (c < cap && npairs * avgblk / (pairs_per_task * c) > 2048.0) c <<= 1;
+    return c;
+}
+
+static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs) {
+    const double avgblk = (double)idx->total_blocks / idx->nlist;
+    const int CH_wide = chunk_len((double)npairs, avgblk, nq > 1 ? 2.0 : 1.0, 512);
+    // (measured on a 1e9 x 96 B index with 65536 lists: the wide kernel wins from about two pairs per list up,
+    // where a good share of the lists is probed by three queries or more)
+    bool wide = std::min((double)CH_wide, avgblk) >= 64.0 && (double)npairs >= 1.5 * idx->nlist;
+    const int force = forced_scan_kernel();
+    if (force == 1) wide = true;
+    else if (force == 2) wide = false;
+    ScanPlan p;
+    p.wide = wide;
+    p.CH = wide ? CH_wide : chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256);
+    p.group = wide ? NPMAX : 2;          // pairs of one list per task
+    const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
+    p.maxchunks = (int)std::max<int64_t>(1, (maxblk + p.CH - 1) / p.CH);
+    return p;
+}
+
+// The largest npairs * maxchunks over all calls with nq <= max_nq and nprobe <= max_nprobe, whichever kernel
+// runs them.  Inside a range of npairs with one chunk length the product grows with npairs, so only the
+// upper end of every such range (and the maxima themselves) needs looking at.
+static int64_t max_result_slots(const rago_index* idx, int64_t max_nq, int max_nprobe) {
+    const double avgblk = (double)idx->total_blocks / idx->nlist;
+    const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
+    int64_t best = 1;
+    for (int single = 0; single < 2; ++single) {                    // batches of one query use other task sizes
+        const int64_t np_max = single ? max_nprobe : max_nq * max_nprobe;
+        const double ppts[2] = {single ? 1.0 : 2.0, single ? 1.0 : 1.5};
+        const int caps[2] = {512, 256};
+        for (int kern = 0; kern < 2; ++kern)
+            for (int c = 16; c <= caps[kern]; c <<= 1) {
+                const int64_t edge = (int64_t)(2048.0 * ppts[kern] * c / std::max(avgblk, 1e-9));
+                for (int64_t np : {edge - 1, edge, edge + 1, np_max}) {
+                    np = std::min(std::max<int64_t>(np, 1), np_max);
+                    const int ch = chunk_len((double)np, avgblk, ppts[kern], caps[kern]);
+                    best = std::max(best, np * std::max<int64_t>(1, (maxblk + ch - 1) / ch));
+                }
+            }
+    }
+    return best;
+}
+
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias, const LutTables* tables,
                 const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
                 hipStream_t st, hipEvent_t* ev) {
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
-    // Which kernel: the wide one (four pairs per pass, one workgroup per CU) pays a fixed price per task
-    // that only long tasks amortise; short lists and small batches go to the narrow one (two pairs per
-    // pass, two workgroups per CU).  RAGO_SCAN_KERNEL=wide|narrow in the environment overrides the choice
-    // (tests run every case through both).
-    // Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key, 0xFFFF - position, then
-    // never vanishes, so a key is never 0 = "empty")
-    const double avgblk = (double)idx->total_blocks / nlist;
-    auto chunk_len = [&](double pairs_per_task, int cap) {
-        int c = 16;
-        while (c < cap && (double)npairs * avgblk / (pairs_per_task * c) > 2048.0) c <<= 1;
-        return c;
-    };
-    const int CH_wide = chunk_len(nq > 1 ? 2.0 : 1.0, 512);
-    // (measured on a 1e9 x 96 B index with 65536 lists: the wide kernel wins from about two pairs per list up,
-    // where a good share of the lists is probed by three queries or more)
-    bool wide = std::min((double)CH_wide, avgblk) >= 64.0 && (double)npairs >= 1.5 * nlist;
-    if (const char* force = getenv("RAGO_SCAN_KERNEL")) {
-        if (!strcmp(force, "wide")) wide = true;
-        else if (!strcmp(force, "narrow")) wide = false;
-    }
-    const int CH = wide ? CH_wide : chunk_len(nq > 1 ? 1.5 : 1.0, 256);
-    const int group = wide ? NPMAX : 2;          // pairs of one list per task
-    const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
-    const int maxchunks = (int)std::max<int64_t>(1, (maxblk + CH - 1) / CH);
-    if ((double)npairs * maxchunks * k > 4.0e9) return fail(RAGO_UNSUPPORTED, "nq * nprobe * chunks * k too large for the workspace");
+    const ScanPlan plan = plan_scan(idx, nq, npairs);
+    const bool wide = plan.wide;
+    const int CH = plan.CH, group = plan.group, maxchunks = plan.maxchunks;
+    // per-task result slots: for this call, or (when the workspace is being sized) the most any call within
+    // these maxima can need (smaller batches take shorter chunks, i.e. more chunks per pair)
+    const int64_t slots = idx->reserving ? max_result_slots(idx, nq, nprobe) : npairs * maxchunks;
+    if ((double)slots * k > 4.0e9) return fail(RAGO_UNSUPPORTED, "nq * nprobe * chunks * k too large for the workspace");
     int rc;
     if ((rc = ws.list_cnt.reserve((size_t)(3 * nlist + 8) * 4))) return rc;   // list_cnt, cursor, list_slot, ctrl
     if ((rc = ws.pair_off.reserve((size_t)(npairs + 2) * 4))) return rc;      // per touched list
@@ -1035,12 +1072,13 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     if ((rc = ws.touched.reserve((size_t)(npairs + 2) * 4))) return rc;
     if ((rc = ws.pair_sorted.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.tauq.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ws.part_I.reserve((size_t)npairs * maxchunks * k * 4))) return rc;
-    if ((rc = ws.part_id.reserve((size_t)npairs * maxchunks * k * 8))) return rc;
-    if ((rc = ws.part_cnt.reserve((size_t)npairs * maxchunks * 4))) return rc;
+    if ((rc = ws.part_I.reserve((size_t)slots * k * 4))) return rc;
+    if ((rc = ws.part_id.reserve((size_t)slots * k * 8))) return rc;
+    if ((rc = ws.part_cnt.reserve((size_t)slots * 4))) return rc;
     if ((rc = ws.counters.reserve(64))) return rc;
     const int64_t max_tasks = npairs * maxchunks;
-    if ((rc = ws.task_table.reserve((size_t)max_tasks * 16))) return rc;
+    if ((rc = ws.task_table.reserve((size_t)slots * 16))) return rc;
+    if (idx->reserving) return RAGO_OK;
 
     int32_t* list_cnt = ws.list_cnt.as<int32_t>();
     int32_t* cursor = list_cnt + nlist;
@@ -1074,12 +1112,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
                                                                            ws.task_table.as<int4>());
     RAGO_HIP(hipGetLastError());
 
-    static int n_cu = 0;
-    if (!n_cu) {
-        hipDeviceProp_t pr;
-        RAGO_HIP(hipGetDeviceProperties(&pr, idx->device));
-        n_cu = pr.multiProcessorCount;
-    }
+    const int n_cu = idx->n_cu;
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
     if (!wide) {
         rc = launch_scan_narrow(P, n_cu, st);

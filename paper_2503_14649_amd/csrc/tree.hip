@@ -149,6 +149,7 @@ int launch_select_tree(rago_index* idx, const float* q, int64_t nq, int nprobe, 
     if ((rc = ws.S.reserve((size_t)nq * TREE_CAP * 8))) return rc;            // candidate keys (the score matrix is not needed)
     if ((rc = ws.cand_idx.reserve((size_t)nq * nsp * 4))) return rc;          // kept groups
     if (nq > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq too large");
+    if (idx->reserving) return RAGO_OK;
     uint64_t* keys = ws.S.as<uint64_t>();
     int32_t* kept = ws.cand_idx.as<int32_t>();
     tree_score_groups_kernel<<<dim3((unsigned)nq, (unsigned)((nsuper + TREE_ROWS - 1) / TREE_ROWS)), 256, 0, st>>>(q, idx->sup_cen, nsuper, d,

@@ -50,11 +50,11 @@ def case(request, rb):
 
 
 @pytest.fixture(params=["wide", "narrow"])
-def scan_kernel(request):
+def scan_kernel(request, rb):
     """Run the test once through each of the library's two scan kernels (the library otherwise picks by task length)."""
-    os.environ["RAGO_SCAN_KERNEL"] = request.param
+    rb.rago_debug_force_scan_kernel(request.param)
     yield request.param
-    del os.environ["RAGO_SCAN_KERNEL"]
+    rb.rago_debug_force_scan_kernel("auto")
 
 
 def test_index_info(case, rb):
@@ -178,6 +178,52 @@ def test_search_end_to_end(case, rb, scan_kernel):
     assert np.array_equal(gs, r["scores"])
 
 
+def test_search_twice_gives_identical_bytes(case, rb, scan_kernel):
+    """Run-twice determinism: pair grouping and task claiming use atomics, the results must not depend on them."""
+    ix, Q, nprobe, k, h = case
+    Qd = torch.from_numpy(Q).cuda()
+    first = [t.clone() for t in rb.rago_ivfpq_search(h, Qd, nprobe, k)]
+    for _ in range(3):
+        again = rb.rago_ivfpq_search(h, Qd, nprobe, k)
+        torch.cuda.synchronize()
+        for x, y in zip(first, again):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+
+
+def test_reserved_workspace_is_never_grown(rb):
+    """After rago_index_reserve, searches within the maxima allocate nothing (whatever their sizes and kernel)
+    and a search beyond them is refused instead of growing the workspace."""
+    ix = to_np(synth.random_index(n=30000, d=64, m=32, nlist=40, seed=77, shuffle_ids=True))
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        rb.rago_index_reserve(h, 48, 24, 50)
+        before = rb.rago_debug_allocations()
+        for kernel in ("auto", "wide", "narrow"):
+            rb.rago_debug_force_scan_kernel(kernel)
+            for nq, nprobe, k in ((48, 24, 50), (1, 24, 50), (2, 1, 1), (17, 9, 33), (48, 3, 50), (5, 24, 7)):
+                Q = _queries(nq, 64, 300 + nq)
+                r = oracle.ivfpq_search(Q, ix, nprobe, k)
+                gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+                torch.cuda.synchronize()
+                assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+        assert rb.rago_debug_allocations() == before
+        for nq, nprobe, k in ((49, 24, 50), (48, 25, 50), (48, 24, 51)):
+            with pytest.raises(rb.RagoError) as e:
+                rb.rago_ivfpq_search(h, torch.from_numpy(_queries(nq, 64, 1)).cuda(), nprobe, k)
+            assert e.value.code == -6 and "rago_index_reserve" in str(e.value)
+        assert rb.rago_debug_allocations() == before
+        Q = _queries(8, 64, 5)                                  # the index is still usable afterwards
+        r = oracle.ivfpq_search(Q, ix, 6, 10)
+        gi = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 6, 10)[0]
+        assert np.array_equal(gi.cpu().numpy(), r["ids"])
+        rb.rago_index_reserve(h, 64, 30, 60)                    # reserving again for larger maxima works
+        gi = rb.rago_ivfpq_search(h, torch.from_numpy(_queries(60, 64, 9)).cuda(), 30, 60)[0]
+        assert gi.shape == (60, 60)
+    finally:
+        rb.rago_debug_force_scan_kernel("auto")
+        rb.rago_index_free(h)
+
+
 def test_select_with_massive_ties(rb, scan_kernel):
     """Duplicate centroids and a zero query: coarse scores tie exactly across the nprobe cut; lower list wins."""
     ix = to_np(synth.random_index(n=4000, d=64, m=16, nlist=300, seed=21))
@@ -197,6 +243,39 @@ def test_select_with_massive_ties(rb, scan_kernel):
     gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 45, 10)
     assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
     rb.rago_index_free(h)
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+@pytest.mark.parametrize("nlist", [300, 9000])
+def test_select_with_scores_packed_inside_the_rounding_error(rb, metric, nlist):
+    """Centroids a few units of relative 1e-7 apart around the cut: more lists than the selection's candidate set have scores
+    within the MFMA's rounding error of each other, so the choice cannot be made on approximate scores; the
+    library must fall back to exact scores of all lists and still return the oracle's probes."""
+    g = np.random.default_rng(5 + nlist)
+    d, nq, nprobe = 64, 6, 40
+    base = g.standard_normal(d).astype(np.float32)
+    C = g.standard_normal((nlist, d)).astype(np.float32) * 0.5
+    close = g.choice(nlist, size=200, replace=False)
+    for i, l in enumerate(close):                         # 200 centroids within 2e-5 (relative) of one another
+        C[l] = base * np.float32(1.0 + (i - 100) * 2e-7) + (1e-7 * g.standard_normal(d)).astype(np.float32) * np.abs(base)
+    Q = (base[None, :] * np.linspace(0.5, 2.0, nq)[:, None] + 0.01 * g.standard_normal((nq, d))).astype(np.float32)
+    ix = to_np(synth.random_index(n=4 * nlist, d=d, m=16, nlist=nlist, seed=3))
+    ix["centroids"] = C
+    h = rb.rago_index_wrap(dev_index(ix), metric=metric)
+    try:
+        S = oracle.coarse(Q, C, metric=metric)
+        ref = oracle.select(S, nprobe)
+        assert len(set(np.sort(S[0])[::-1][nprobe - 20:nprobe + 60].tolist())) > 20    # packed, but not plain ties
+        Sd = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+        got = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), Sd, nprobe)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), ref)
+        assert rb.rago_debug_counters(h)[3] > 0            # the exact path did run
+        r = oracle.ivfpq_search(Q, ix, nprobe, 10, metric=metric)
+        gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, 10)
+        assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    finally:
+        rb.rago_index_free(h)
 
 
 def test_one_code_for_every_vector(rb, scan_kernel):

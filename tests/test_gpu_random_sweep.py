@@ -64,26 +64,21 @@ def test_ivfpq_random_configurations(rb, seed):
             g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
             Q = torch.nn.functional.normalize(torch.randn(nq, d, generator=g), dim=1).numpy()
             Q = (Q * float(rng.choice([1.0, 1.0, 0.01, 30.0])) * big).astype(np.float32)
-            if kernel:
-                os.environ["RAGO_SCAN_KERNEL"] = kernel
-            else:
-                os.environ.pop("RAGO_SCAN_KERNEL", None)
+            rb.rago_debug_force_scan_kernel(kernel or "auto")
             h = rb.rago_index_wrap(dev_index(ix), metric=metric)
             try:
                 r = oracle.ivfpq_search(Q, ix, nprobe, k, metric=metric)
                 gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
                 torch.cuda.synchronize()
-                if rb.rago_debug_counters(h)[3] != 0:     # the library could not show its probe choice independent of
-                    unproven += 1                         # rounding (differences near the fp32 underflow limit): the
-                    continue                              # oracle's choice may differ legitimately
+                unproven += int(rb.rago_debug_counters(h)[3] != 0)    # (probe choice made on exact scores of all lists)
                 assert np.array_equal(gi.cpu().numpy(), r["ids"]), desc
                 assert np.array_equal(gis.cpu().numpy(), r["iscores"]), desc
                 assert np.array_equal(gs.cpu().numpy(), r["scores"], equal_nan=True), desc
             finally:
                 rb.rago_index_free(h)
     finally:
-        os.environ.pop("RAGO_SCAN_KERNEL", None)
-    assert unproven <= 5
+        rb.rago_debug_force_scan_kernel("auto")
+    print(f"queries' probe choices taken on exact scores in {unproven} cases", flush=True)
 
 
 def test_flat_random_configurations(rb):
