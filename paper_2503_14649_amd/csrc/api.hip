@@ -466,6 +466,9 @@ int rago_ivfpq_search(rago_index* idx, const float* queries, int64_t nq, int32_t
     if (nq > 0 && !out_scores) return fail(RAGO_INVALID_ARG, "null out_scores");
     if (((uintptr_t)queries & 15) != 0) return fail(RAGO_INVALID_ARG, "queries must be 16-byte aligned");
     if (nq == 0) return RAGO_OK;
+    if (idx->ws_frozen && (nq > idx->res_nq || nprobe > idx->res_nprobe || k > idx->res_k))
+        return fail(RAGO_UNSUPPORTED, "the call exceeds the maxima given to rago_index_reserve (nq " + std::to_string(idx->res_nq) +
+                                          ", nprobe " + std::to_string(idx->res_nprobe) + ", k " + std::to_string(idx->res_k) + ")");
     DeviceGuard g(idx->device);
     NoGrowScope frozen(idx->ws_frozen);
     hipStream_t st = (hipStream_t)stream;
@@ -497,6 +500,7 @@ int rago_index_reserve(rago_index* idx, int64_t max_nq, int32_t max_nprobe, int3
     idx->reserving = false;
     if (rc) return rc;
     idx->ws_frozen = true;
+    idx->res_nq = max_nq; idx->res_nprobe = max_nprobe; idx->res_k = max_k;
     return RAGO_OK;
 }
 

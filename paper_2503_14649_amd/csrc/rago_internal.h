@@ -110,6 +110,8 @@ struct rago_index {
     int n_cu = 0;                  // compute units of `device`
     bool reserving = false;        // rago_index_reserve: the stage launchers size their buffers and return
     bool ws_frozen = false;        // the workspace was sized by rago_index_reserve: searches do not grow it
+    int64_t res_nq = 0;            // ... for these maxima
+    int res_nprobe = 0, res_k = 0;
     rago::Workspace ws;
     rago::Profiler prof;
     // parameters of the last scan (for rago_debug_counters)
