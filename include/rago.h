@@ -187,6 +187,23 @@ int rago_flat_search(const void* corpus_bf16, const void* queries_bf16, int32_t 
 int rago_flat_search_f16(const void* corpus_f16, const void* queries_f16, int32_t R, int64_t n, int32_t nqr,
                          int32_t d, int32_t k, int64_t* out_ids, float* out_scores, int device, void* stream);
 
+/*
+ * rago_flat_search_static: rago_flat_search / rago_flat_search_f16 for callers that cannot allocate
+ * device memory: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It performs no allocation, free or host synchronisation on any call, the first
+ * included: its scratch memory (candidate keys, counts, threshold bins: 32 MiB + 32 KiB) is a static
+ * device array inside the library, which every GPU the library runs on holds until the process ends.
+ *   format 0 = bf16, 1 = IEEE binary16; every other argument, the results and their order as in
+ *   rago_flat_search.  Limit: R <= 256 requests per call (RAGO_UNSUPPORTED beyond; split the batch).
+ *   The corpus is cut into at most 256 / R slabs per request (512 / R in rago_flat_search), so large
+ *   calls run on half as many workgroups.
+ * All calls on one GPU share that array: calls that overlap on one GPU (different streams or
+ * threads) race; serialise them on one stream.  Nothing needs clearing between calls (the call
+ * zeroes the threshold bins itself, with a kernel, so it can be captured into a HIP graph).
+ */
+int rago_flat_search_static(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d,
+                            int32_t k, int32_t format, int64_t* out_ids, float* out_scores, int device, void* stream);
+
 /* Thread-local message of the last error on this thread ("" if none). */
 const char* rago_last_error(void);
 

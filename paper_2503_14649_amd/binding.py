@@ -43,6 +43,7 @@ _lib.rago_index_info.argtypes = [_vp, ctypes.POINTER(IndexDesc)]
 _lib.rago_ivfpq_search.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.rago_flat_search.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _vp, _vp, _int, _vp]
 _lib.rago_flat_search_f16.argtypes = _lib.rago_flat_search.argtypes
+_lib.rago_flat_search_static.argtypes = [_vp, _vp, _i32, _i64, _i32, _i32, _i32, _i32, _vp, _vp, _int, _vp]
 _lib.rago_index_set_upper_level.argtypes = [_vp, _i32, _vp, _vp, _vp, _int]
 _lib.rago_index_set_upper_probe.argtypes = [_vp, _i32]
 _lib.rago_debug_select_tree.argtypes = [_vp, _vp, _i64, _i32, _vp, _vp, _vp]
@@ -164,6 +165,20 @@ def rago_flat_search_f16(corpus: torch.Tensor, queries: torch.Tensor, k: int, ou
 def rago_flat_search(corpus: torch.Tensor, queries: torch.Tensor, k: int, out=None):
     """corpus bf16 [R][n][d], queries bf16 [R][nqr][d] on the GPU -> (ids i64 [R][nqr][k], scores f32)."""
     return _flat(_lib.rago_flat_search, torch.bfloat16, corpus, queries, k, out)
+
+
+def rago_flat_search_static(corpus: torch.Tensor, queries: torch.Tensor, k: int, out):
+    """The flat search that allocates nothing: corpus / queries bf16 or fp16 (both alike), `out` = (ids i64
+    [R][nqr][k], scores f32 [R][nqr][k]) preallocated by the caller."""
+    assert corpus.is_cuda and queries.is_cuda and corpus.dtype == queries.dtype
+    assert corpus.dtype in (torch.bfloat16, torch.float16) and corpus.is_contiguous() and queries.is_contiguous()
+    R, n, d = corpus.shape
+    nqr, dev = queries.shape[1], corpus.device
+    ids, scores = out
+    assert ids.shape == (R, nqr, k) and scores.shape == (R, nqr, k) and ids.dtype == torch.int64 and scores.dtype == torch.float32
+    _chk(_lib.rago_flat_search_static(_ptr(corpus), _ptr(queries), R, n, nqr, d, k, int(corpus.dtype == torch.float16),
+                                      _ptr(ids), _ptr(scores), dev.index or 0, _stream(dev)))
+    return ids, scores
 
 
 def _flat(fn, dtype, corpus, queries, k, out):

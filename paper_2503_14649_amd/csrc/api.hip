@@ -545,7 +545,7 @@ int rago_debug_stage_ms(rago_index* idx, float* out_ms, int32_t* out_calls) {
 }
 
 static int flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
-                       int64_t* out_ids, float* out_scores, int device, bool half, void* stream) {
+                       int64_t* out_ids, float* out_scores, int device, bool half, void* stream, bool static_scratch = false) {
     if (R < 0 || n < 0) return fail(RAGO_INVALID_ARG, "negative size");
     if (nqr < 1 || nqr > 16) return fail(RAGO_INVALID_ARG, "nqr must be in [1, 16]");
     if (k < 1) return fail(RAGO_INVALID_ARG, "k must be >= 1");
@@ -557,7 +557,14 @@ static int flat_search(const void* corpus, const void* queries, int32_t R, int64
     if (R == 0) return RAGO_OK;
     DeviceGuard g(device);
     if (!g.ok) return fail(RAGO_DEVICE, "hipSetDevice failed");
+    if (static_scratch) return launch_flat_static(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, (hipStream_t)stream);
     return launch_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, (hipStream_t)stream);
+}
+
+int rago_flat_search_static(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,
+                            int32_t format, int64_t* out_ids, float* out_scores, int device, void* stream) {
+    if (format != 0 && format != 1) return fail(RAGO_INVALID_ARG, "format must be 0 (bf16) or 1 (binary16)");
+    return flat_search(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, format == 1, stream, true);
 }
 
 int rago_flat_search(const void* corpus, const void* queries, int32_t R, int64_t n, int32_t nqr, int32_t d, int32_t k,

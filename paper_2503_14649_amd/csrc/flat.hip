@@ -23,6 +23,8 @@
 //    that still has k candidates at or above it, so after the first round only ~k/round new keys
 //    appear.  An area that could overflow is cut back to its best k with a wave-level radix select
 //    (rare).  Each slab leaves <= k keys per query; a second kernel merges the slabs.
+#include <mutex>
+
 #include "rago_internal.h"
 
 namespace rago {
@@ -506,6 +508,50 @@ int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int n
     if ((rc = g_flat_tbin[device].reserve((size_t)R * 16 * 4))) return rc;
     return run_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, st, nslab, slab_rows,
                     g_flat_keys[device].as<uint64_t>(), g_flat_cnt[device].as<int32_t>(), g_flat_tbin[device].as<int32_t>());
+}
+
+// ------------------------------------------------------------------ the flat search that allocates nothing
+// Its scratch memory (candidate keys, per-slab counts, threshold bins) is a device array of the code object
+// instead of a grown workspace.  Every GPU the library runs on holds its own copy of the array at its own
+// address, looked up once per device (with that device current) and kept; host code only ever uses that looked-up
+// address, never the array's name, which on the host is a stand-in and not a device address.
+constexpr int FLAT_STATIC_SLABS = 256;                                           // workgroups (requests x slabs) per call
+constexpr size_t FLAT_STATIC_KEYS = (size_t)FLAT_STATIC_SLABS * 16 * FLAT_CAP * 8;   // 32 MiB of candidate keys
+constexpr size_t FLAT_STATIC_CNT = (size_t)FLAT_STATIC_SLABS * 16 * 4;
+constexpr size_t FLAT_STATIC_TBIN = (size_t)FLAT_STATIC_SLABS * 16 * 4;              // (requests <= slabs)
+constexpr size_t FLAT_STATIC_BYTES = FLAT_STATIC_KEYS + FLAT_STATIC_CNT + FLAT_STATIC_TBIN;
+static __device__ __align__(256) unsigned char scratch[FLAT_STATIC_BYTES];
+
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[16] = {};
+
+int flat_static_max_requests() { return FLAT_STATIC_SLABS; }
+
+int launch_flat_static(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k, int64_t* out_ids,
+                       float* out_scores, int device, bool half, hipStream_t st) {
+    if (device < 0 || device >= 16) return fail(RAGO_INVALID_ARG, "device ordinal out of range");
+    if (d % 64 || d > FLAT_MAXD) return fail(RAGO_UNSUPPORTED, "d must be a multiple of 64, at most 1024");
+    if (R > FLAT_STATIC_SLABS)
+        return fail(RAGO_UNSUPPORTED, "more than " + std::to_string(FLAT_STATIC_SLABS) + " requests in one call: beyond the static scratch memory");
+    unsigned char* base;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[device]) {          // (the caller has made `device` current)
+            void* p = nullptr;
+            RAGO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+        }
+        base = g_scratch_ptr[device];
+    }
+    int nslab;
+    int64_t slab_rows;
+    flat_slabs(R, n, FLAT_STATIC_SLABS, true, &nslab, &slab_rows);
+    if ((int64_t)R * nslab > FLAT_STATIC_SLABS) return fail(RAGO_UNSUPPORTED, "internal: slab count beyond the static scratch memory");
+    // nothing in the scratch memory needs clearing beyond the threshold bins, which run_flat zeroes with a kernel:
+    // the counts are written by every workgroup before the merge reads them, and keys are only read below a count
+    return run_flat(corpus, queries, R, n, nqr, d, k, out_ids, out_scores, device, half, st, nslab, slab_rows,
+                    reinterpret_cast<uint64_t*>(base), reinterpret_cast<int32_t*>(base + FLAT_STATIC_KEYS),
+                    reinterpret_cast<int32_t*>(base + FLAT_STATIC_KEYS + FLAT_STATIC_CNT));
 }
 
 }  // namespace rago

@@ -161,6 +161,8 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,
                 int64_t* out_ids, float* out_scores, int device, bool half, hipStream_t st);
+int launch_flat_static(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,
+                       int64_t* out_ids, float* out_scores, int device, bool half, hipStream_t st);
 int flat_profile(int device, int enable);
 int flat_stage_ms(int device, float* out_ms, int32_t* out_calls);
 
