@@ -172,6 +172,7 @@ def run_ivfpq(args):
         del sub
 
     torch.cuda.empty_cache()
+    rb.rago_debug_force_scan_kernel(args.scan_kernel)
     h = rb.rago_index_wrap(index, 0, metric=args.metric)
     info = rb.rago_index_info(h)
     del index["codes"]
@@ -433,6 +434,8 @@ def main():
     ap.add_argument("--m", type=int, default=0, help="sub-quantisers (default: the workload's)")
     ap.add_argument("--no-ceiling", dest="ceiling", action="store_false",
                     help="skip the read-stream ceiling measurement (a 4 GiB buffer read ten times)")
+    ap.add_argument("--scan-kernel", default="auto", choices=["auto", "wide", "narrow", "wave"],
+                    help="pin one of the library's scan kernels (development runs; the default lets the library choose)")
     ap.add_argument("--metric", default="ip", choices=["ip", "l2"],
                     help="similarity of the IVF-PQ workloads: inner product (the headline) or minus squared Euclidean distance")
     args = ap.parse_args()

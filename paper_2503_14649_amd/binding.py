@@ -258,7 +258,7 @@ def rago_index_reserve(h, max_nq: int, max_nprobe: int, max_k: int):
     _chk(_lib.rago_index_reserve(h, max_nq, max_nprobe, max_k))
 
 
-SCAN_KERNELS = {"auto": 0, "wide": 1, "narrow": 2}
+SCAN_KERNELS = {"auto": 0, "wide": 1, "narrow": 2, "wave": 3}
 
 
 def rago_debug_force_scan_kernel(which):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librago.so")
-SOURCES = ["api.hip", "layout.hip", "coarse.hip", "tree.hip", "lut.hip", "lut_l2.hip", "scan.hip", "scan_narrow.hip", "flat.hip"]
+SOURCES = ["api.hip", "layout.hip", "coarse.hip", "tree.hip", "lut.hip", "lut_l2.hip", "scan.hip", "scan_narrow.hip", "scan_wave.hip", "flat.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value"]
 

@@ -42,7 +42,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo, &wave_items, &wave_q};
     for (DevBuf* b : all) b->release();
 }
 
@@ -505,7 +505,7 @@ int rago_index_reserve(rago_index* idx, int64_t max_nq, int32_t max_nprobe, int3
 }
 
 int rago_debug_force_scan_kernel(int which) {
-    if (which < 0 || which > 2) return fail(RAGO_INVALID_ARG, "0 = pick by sizes, 1 = wide, 2 = narrow");
+    if (which < 0 || which > 3) return fail(RAGO_INVALID_ARG, "0 = pick by sizes, 1 = wide, 2 = narrow, 3 = wave per item");
     g_forced_scan.store(which);
     return RAGO_OK;
 }

@@ -99,23 +99,24 @@ int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st)
 
 // Plain read stream of known size: what a kernel that only reads HBM reaches on this device, the
 // practical ceiling the scans are also held against (Section 4, "Retrieval performance modeling",
-// takes ~80 % of the memory bandwidth as what a good code scan reaches).  Four independent 16-byte
-// loads per lane in flight, 1 KiB contiguous per wave and load; every workgroup leaves the XOR of
-// what it read in sink[blockIdx.x] so the loads cannot be dropped.
+// takes ~80 % of the memory bandwidth as what a good code scan reaches).  Every workgroup leaves the XOR
+// of what it read in sink[blockIdx.x] so the loads cannot be dropped.
 constexpr int READ_STREAM_BLOCKS = 4096;
-__global__ void __launch_bounds__(256) rago_calib_read_kernel(const uint4* __restrict__ src, int64_t n16, uint32_t* __restrict__ sink) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc.x ^= a.x ^ b.x ^ c.x ^ d.x; acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-        acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+typedef uint32_t rs_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) rago_calib_read_kernel(const rs_u32x4* __restrict__ src, int64_t n16, uint32_t* __restrict__ sink) {
+    // every workgroup reads one contiguous run; eight independent non-temporal 16-byte loads per lane in flight
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const int64_t first = blockIdx.x * per, end = first + per < n16 ? first + per : n16;
+    rs_u32x4 acc = {0u, 0u, 0u, 0u};
+    int64_t i = first + threadIdx.x;
+    for (; i + 7 * 256 < end; i += 8 * 256) {
+        rs_u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
     }
-    for (; i < n16; i += stride) {
-        const uint4 a = src[i];
-        acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
-    }
+    for (; i < end; i += 256) acc ^= __builtin_nontemporal_load(src + i);
     uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
     for (int o = 32; o; o >>= 1) v ^= __shfl_xor(v, o);
     if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], v);
@@ -124,7 +125,7 @@ __global__ void __launch_bounds__(256) rago_calib_read_kernel(const uint4* __res
 int read_stream_sink_words() { return READ_STREAM_BLOCKS; }
 
 int launch_calib_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t st) {
-    rago_calib_read_kernel<<<READ_STREAM_BLOCKS, 256, 0, st>>>(static_cast<const uint4*>(src), bytes / 16, sink);
+    rago_calib_read_kernel<<<READ_STREAM_BLOCKS, 256, 0, st>>>(static_cast<const rs_u32x4*>(src), bytes / 16, sink);
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
 }

@@ -55,12 +55,12 @@ struct NoGrowScope {             // while alive on this thread, DevBuf::reserve 
     ~NoGrowScope();
 };
 long long device_allocations();  // number of times any DevBuf grew (process-wide)
-int forced_scan_kernel();        // 0 = pick by sizes, 1 = wide, 2 = narrow (rago_debug_force_scan_kernel)
+int forced_scan_kernel();        // 0 = pick by sizes, 1 = wide, 2 = narrow, 3 = wave per item (rago_debug_force_scan_kernel)
 
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo, wave_items, wave_q;
     void release();
 };
 

@@ -529,7 +529,7 @@ __global__ void __launch_bounds__(ScanShape<MPAD>::NT) scan_kernel(const ScanPar
     // The wave's first block.  The stream's loads are issued unconditionally and at fixed places of
     // the program, this one included: the compiler counts outstanding loads statically, and a load
     // that is issued on some paths only makes it wait for ALL outstanding loads before each use.
-    load_block<MPAD>(cur_w, T.base + (int64_t)min(wave, T.nb - 1) * BLK_BYTES, lane);
+    load_block<MPAD, true>(cur_w, T.base + (int64_t)min(wave, T.nb - 1) * BLK_BYTES, lane);
     bool have_prev = false;
     for (int cur = 0;; cur = cur == 2 ? 0 : cur + 1) {
         const int32_t* D = desc + cur * DESC_INTS;
@@ -613,15 +613,15 @@ __global__ void __launch_bounds__(ScanShape<MPAD>::NT) scan_kernel(const ScanPar
                 }
             };
             int bn = claim();
-            load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
+            load_block<MPAD, true>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
             while (b < nb) {                       // ping-pong between the two register sets
                 process(cur_w, b);
                 b = claim();
-                load_block<MPAD>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane);
+                load_block<MPAD, true>(cur_w, base + (int64_t)min(b, nb - 1) * BLK_BYTES, lane);
                 if (bn >= nb) break;               // claims are monotonic: nothing newer can be valid either
                 process(nxt_w, bn);
                 bn = claim();
-                load_block<MPAD>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
+                load_block<MPAD, true>(nxt_w, base + (int64_t)min(bn, nb - 1) * BLK_BYTES, lane);
             }
         };
         if (np <= 2) stream(std::integral_constant<int, 2>{});
@@ -633,7 +633,7 @@ __global__ void __launch_bounds__(ScanShape<MPAD>::NT) scan_kernel(const ScanPar
         decode(Dn, Tn);
         issue_tables(Dn, Tn);
         // (and the wave's first block of it; after the last task: any readable block)
-        load_block<MPAD>(cur_w, Tn.tid >= 0 ? Tn.base + (int64_t)min(wave, Tn.nb - 1) * BLK_BYTES : T.base, lane);
+        load_block<MPAD, true>(cur_w, Tn.tid >= 0 ? Tn.base + (int64_t)min(wave, Tn.nb - 1) * BLK_BYTES : T.base, lane);
         // ---- the first wave to run out of blocks claims the task after the next while the others finish (its
         // descriptor replaces the previous task's, whose merge ended before this task's stream began)
         {
@@ -1002,7 +1002,8 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
 // (two pairs per pass, two workgroups per CU); rago_debug_force_scan_kernel overrides the choice (tests run
 // every case through both).  Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key,
 // 0xFFFF - position, then never vanishes, so a key is never 0 = "empty")
-struct ScanPlan { bool wide; int CH, group, maxchunks; };
+enum { SCAN_WIDE = 0, SCAN_NARROW = 1, SCAN_WAVE = 2 };
+struct ScanPlan { int kind; int CH, group, maxchunks; };
 
 static int chunk_len(double npairs, double avgblk, double pairs_per_task, int cap) {
     int c = 16;
@@ -1017,12 +1018,13 @@ static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs) {
     // where a good share of the lists is probed by three queries or more)
     bool wide = std::min((double)CH_wide, avgblk) >= 64.0 && (double)npairs >= 1.5 * idx->nlist;
     const int force = forced_scan_kernel();
-    if (force == 1) wide = true;
-    else if (force == 2) wide = false;
     ScanPlan p;
-    p.wide = wide;
-    p.CH = wide ? CH_wide : chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256);
-    p.group = wide ? NPMAX : 2;          // pairs of one list per task
+    p.kind = wide ? SCAN_WIDE : SCAN_NARROW;
+    if (force >= 1 && force <= 3) p.kind = force - 1;
+    if (p.kind == SCAN_WIDE) p.CH = CH_wide;
+    else if (p.kind == SCAN_NARROW) p.CH = chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256);
+    else p.CH = wave_chunk_len((double)npairs * avgblk, idx->n_cu);
+    p.group = p.kind == SCAN_WIDE ? NPMAX : 2;          // pairs of one list per task
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
     p.maxchunks = (int)std::max<int64_t>(1, (maxblk + p.CH - 1) / p.CH);
     return p;
@@ -1032,22 +1034,32 @@ static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs) {
 // runs them.  Inside a range of npairs with one chunk length the product grows with npairs, so only the
 // upper end of every such range (and the maxima themselves) needs looking at.
 static int64_t max_result_slots(const rago_index* idx, int64_t max_nq, int max_nprobe) {
-    const double avgblk = (double)idx->total_blocks / idx->nlist;
+    const double avgblk = std::max((double)idx->total_blocks / idx->nlist, 1e-9);
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
     int64_t best = 1;
+    auto look = [&](int64_t np, int64_t np_max, int ch_of_np) {
+        (void)np_max;
+        best = std::max(best, np * std::max<int64_t>(1, (maxblk + ch_of_np - 1) / ch_of_np));
+    };
     for (int single = 0; single < 2; ++single) {                    // batches of one query use other task sizes
         const int64_t np_max = single ? max_nprobe : max_nq * max_nprobe;
         const double ppts[2] = {single ? 1.0 : 2.0, single ? 1.0 : 1.5};
         const int caps[2] = {512, 256};
         for (int kern = 0; kern < 2; ++kern)
             for (int c = 16; c <= caps[kern]; c <<= 1) {
-                const int64_t edge = (int64_t)(2048.0 * ppts[kern] * c / std::max(avgblk, 1e-9));
+                const int64_t edge = (int64_t)(2048.0 * ppts[kern] * c / avgblk);
                 for (int64_t np : {edge - 1, edge, edge + 1, np_max}) {
                     np = std::min(std::max<int64_t>(np, 1), np_max);
-                    const int ch = chunk_len((double)np, avgblk, ppts[kern], caps[kern]);
-                    best = std::max(best, np * std::max<int64_t>(1, (maxblk + ch - 1) / ch));
+                    look(np, np_max, chunk_len((double)np, avgblk, ppts[kern], caps[kern]));
                 }
             }
+        for (int c = 8; c <= 512; c <<= 1) {                        // the kernel with one wave per item
+            const int64_t edge = (int64_t)(3.0 * 2 * 8 * idx->n_cu * c / avgblk);
+            for (int64_t np : {edge - 1, edge, edge + 1, np_max}) {
+                np = std::min(std::max<int64_t>(np, 1), np_max);
+                look(np, np_max, wave_chunk_len((double)np * avgblk, idx->n_cu));
+            }
+        }
     }
     return best;
 }
@@ -1059,7 +1071,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
     const ScanPlan plan = plan_scan(idx, nq, npairs);
-    const bool wide = plan.wide;
+    const bool wide = plan.kind == SCAN_WIDE;
     const int CH = plan.CH, group = plan.group, maxchunks = plan.maxchunks;
     // per-task result slots: for this call, or (when the workspace is being sized) the most any call within
     // these maxima can need (smaller batches take shorter chunks, i.e. more chunks per pair)
@@ -1078,6 +1090,10 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     if ((rc = ws.counters.reserve(64))) return rc;
     const int64_t max_tasks = npairs * maxchunks;
     if ((rc = ws.task_table.reserve((size_t)slots * 16))) return rc;
+    if (idx->reserving || plan.kind == SCAN_WAVE) {
+        if ((rc = ws.wave_items.reserve((size_t)slots * wave_item_bytes()))) return rc;
+        if ((rc = ws.wave_q.reserve((size_t)nq * 32))) return rc;
+    }
     if (idx->reserving) return RAGO_OK;
 
     int32_t* list_cnt = ws.list_cnt.as<int32_t>();
@@ -1095,6 +1111,19 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     P.part_cnt = ws.part_cnt.as<int32_t>();
     P.nlist = nlist; P.nprobe = nprobe; P.k = k; P.CH = CH; P.maxchunks = maxchunks;
 
+    const int n_cu = idx->n_cu;
+    if (plan.kind == SCAN_WAVE) {
+        int4* qinfo = ws.wave_q.as<int4>();
+        if ((rc = launch_scan_wave(P, nq, n_cu, (double)idx->total_blocks / nlist, ws.wave_items.p, ws.task_table.as<int4>(),
+                                   ws.pair_sorted.as<int32_t>(), qinfo, reinterpret_cast<int64_t*>(qinfo + nq), ws.counters.as<int64_t>(),
+                                   ev ? ev[4] : nullptr, st)))
+            return rc;
+        if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
+        merge_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
+        RAGO_HIP(hipGetLastError());
+        if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
+        return RAGO_OK;
+    }
     const unsigned pg = (unsigned)((npairs + 255) / 256);
     scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl, ws.counters.as<int64_t>());
     if (nq >= 64) {
@@ -1112,7 +1141,6 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
                                                                            ws.task_table.as<int4>());
     RAGO_HIP(hipGetLastError());
 
-    const int n_cu = idx->n_cu;
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
     if (!wide) {
         rc = launch_scan_narrow(P, n_cu, st);

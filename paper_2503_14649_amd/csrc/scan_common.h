@@ -92,17 +92,27 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
 typedef const __attribute__((address_space(1))) u32x2* global_u32x2_ptr;
 
-template <int MPAD>
+// NT: non-temporal loads, for streams that are read once by one workgroup and far larger than the caches (the
+// billion-vector batch: 14.2 ms against 14.6 ms per scan with ordinary loads; a plain read stream of 8 GiB reaches
+// 6.9 TB/s against 6.1 TB/s).  Where lists are probed again soon afterwards by other tasks (batches over a database
+// of about the size of the 256 MiB last-level cache) ordinary loads are the faster ones, by 6 %.
+template <int MPAD, bool NT = false>
 __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t* blk, int lane) {
     global_u32x4_ptr p = (global_u32x4_ptr)(reinterpret_cast<const u32x4*>(blk) + lane);
 #pragma unroll
     for (int i = 0; i < MPAD / 16; ++i) {
-        const u32x4 v = p[i * 64];
+        const u32x4 v = NT ? __builtin_nontemporal_load(p + i * 64) : p[i * 64];
         w[i] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
 
 // scan_narrow.hip: the two-pairs-per-pass kernel on 2 * n_cu workgroups (task records with 1 or 2 pairs)
 int launch_scan_narrow(const ScanParams& P, int n_cu, hipStream_t st);
+
+// scan_wave.hip: one wave per (pair, chunk) item, pairs grouped by query.  Plans its items and tasks itself.
+int wave_chunk_len(double total_blocks, int n_cu);
+size_t wave_item_bytes();
+int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* items, int4* tasks, int32_t* pair_items,
+                     int4* qinfo, int64_t* qbytes, int64_t* counters, hipEvent_t ev_scan, hipStream_t st);
 
 }  // namespace rago

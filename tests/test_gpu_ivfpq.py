@@ -49,9 +49,9 @@ def case(request, rb):
     rb.rago_index_free(h)
 
 
-@pytest.fixture(params=["wide", "narrow"])
+@pytest.fixture(params=["wide", "narrow", "wave"])
 def scan_kernel(request, rb):
-    """Run the test once through each of the library's two scan kernels (the library otherwise picks by task length)."""
+    """Run the test once through each of the library's three scan kernels (the library otherwise picks by the sizes)."""
     rb.rago_debug_force_scan_kernel(request.param)
     yield request.param
     rb.rago_debug_force_scan_kernel("auto")
@@ -198,7 +198,7 @@ def test_reserved_workspace_is_never_grown(rb):
     try:
         rb.rago_index_reserve(h, 48, 24, 50)
         before = rb.rago_debug_allocations()
-        for kernel in ("auto", "wide", "narrow"):
+        for kernel in ("auto", "wide", "narrow", "wave"):
             rb.rago_debug_force_scan_kernel(kernel)
             for nq, nprobe, k in ((48, 24, 50), (1, 24, 50), (2, 1, 1), (17, 9, 33), (48, 3, 50), (5, 24, 7)):
                 Q = _queries(nq, 64, 300 + nq)

@@ -44,7 +44,7 @@ def test_ivfpq_random_configurations(rb, seed):
             nprobe = int(rng.integers(1, nlist + 1))
             k = int(rng.choice([1, 2, 10, 100, 128]))
             metric = "l2" if rng.random() < 0.4 else "ip"
-            kernel = str(rng.choice(["wide", "narrow", ""]))
+            kernel = str(rng.choice(["wide", "narrow", "wave", ""]))
             kw = {}
             if rng.random() < 0.3 and n > 100:
                 kw["dup_codes"] = int(rng.integers(1, 50))
