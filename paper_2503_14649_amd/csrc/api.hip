@@ -42,7 +42,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo, &wave_items, &wave_q};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo, &wave_items, &wave_q, &wave_stage};
     for (DevBuf* b : all) b->release();
 }
 
@@ -438,9 +438,9 @@ static int run_search(rago_index* idx, const float* queries, int64_t nq, int32_t
         if ((rc = launch_select_tree(idx, queries, nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
     } else {
         if ((rc = ws.S.reserve((size_t)nq * idx->nlist * 4))) return rc;
-        if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st))) return rc;
+        if ((rc = launch_coarse(idx, queries, nq, ws.S.as<float>(), st, true))) return rc;
         if (ev) RAGO_HIP(hipEventRecord(ev[1], st));
-        if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st))) return rc;
+        if ((rc = launch_select(idx, queries, ws.S.as<float>(), nq, nprobe, ws.probes.as<int32_t>(), st, true))) return rc;
     }
     if (ev) RAGO_HIP(hipEventRecord(ev[2], st));
     if (idx->metric == 1) {

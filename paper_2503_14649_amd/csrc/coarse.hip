@@ -33,7 +33,8 @@ __device__ __forceinline__ float coarse_score(float ip, int row, int col, const 
 template <int TM>
 __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restrict__ Q, const float* __restrict__ C, int nq,
                                                           int nlist, int d, const float* __restrict__ qn2,
-                                                          const float* __restrict__ cn2, float* __restrict__ S) {
+                                                          const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
+    if (zero_me && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_me = 0;   // (the selection's counter of queued queries)
     constexpr int MT = TM == 128 ? 2 : 1;  // 32x32 MFMA tiles per wave along M
     constexpr int NT = TM == 128 ? 2 : 1;  //                         and along N
     constexpr int AF = TM * 8 / 256;       // float4 loads per thread for the A tile
@@ -161,7 +162,8 @@ int launch_split_centroids(rago_index* idx, hipStream_t st) {
 __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
                                                                 const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
                                                                 int nct, const float* __restrict__ qn2,
-                                                                const float* __restrict__ cn2, float* __restrict__ S) {
+                                                                const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
+    if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;   // (the selection's counter of queued queries)
     extern __shared__ __align__(16) uint16_t x_smem[];
     uint16_t *Ah = x_smem, *Al = Ah + X_T * X_LS, *Bh = Al + X_T * X_LS, *Bl = Bh + X_T * X_LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -271,7 +273,7 @@ __global__ void __launch_bounds__(256) qnorm2_kernel(const float* __restrict__ Q
     if ((threadIdx.x & 63) == 0) out[q] = (float)acc;
 }
 
-int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st) {
+int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st, bool zero_select_counter) {
     const int nlist = idx->nlist, d = idx->d;
     if (nq > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq too large");
     const float *qn2 = nullptr, *cn2 = nullptr;
@@ -284,11 +286,17 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         cn2 = idx->cn2;
     }
     if (idx->reserving) return RAGO_OK;
+    int64_t* zero_me = nullptr;
+    if (zero_select_counter) {
+        int rc = idx->ws.counters.reserve(64);
+        if (rc) return rc;
+        zero_me = idx->ws.counters.as<int64_t>() + 3;
+    }
     const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
     if (nq <= 32) {
-        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S);
+        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
-        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S);
+        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else {
         const int nqt = (int)((nq + X_T - 1) / X_T), nct = (nlist + X_T - 1) / X_T;
         const int64_t grid = (int64_t)((nct + 7) / 8) * 8 * nqt;
@@ -296,7 +304,7 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         static OncePerDevice attr;
         if (attr.first())
             RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
-        coarse_gemm_split_kernel<<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S);
+        coarse_gemm_split_kernel<<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
@@ -605,7 +613,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
 
 __global__ void zero_counter_kernel(int64_t* counters) { counters[3] = 0; }
 
-int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st) {
+int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st, bool counter_is_zero) {
     if (nprobe + SEL_EXTRA > SEL_CAP && nprobe < idx->nlist && idx->nlist > SEL_CAP)
         return fail(RAGO_UNSUPPORTED, "nprobe > 2016 on an index with more than 2048 lists");
     if (std::min(nprobe + SEL_EXTRA, idx->nlist) > SEL_CAP) return fail(RAGO_UNSUPPORTED, "nprobe > 2016");
@@ -613,7 +621,7 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
     if ((rc = idx->ws.counters.reserve(64))) return rc;
     if ((rc = idx->ws.sel_redo.reserve((size_t)nq * 4))) return rc;
     if (idx->reserving) return RAGO_OK;
-    zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
+    if (!counter_is_zero) zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
     int64_t* cnt = idx->ws.counters.as<int64_t>();
     int32_t* rq = idx->ws.sel_redo.as<int32_t>();
     const int nl = idx->nlist;

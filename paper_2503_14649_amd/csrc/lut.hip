@@ -53,163 +53,193 @@ __device__ __forceinline__ double subdot(const float* __restrict__ a, const floa
     return acc;
 }
 
-// T64[q][j][c], Tmin/Tmax[q][j].  One wave per (query, sub-quantiser): lane handles codewords
-// lane, lane + 64, lane + 128, lane + 192; 4 waves per block.
+// T64[q][j][c] = <q_j, CB[j][c]> with Tmin/Tmax[q][j] (one wave per (query, sub-quantiser): a lane handles codewords
+// lane, lane + 64, lane + 128, lane + 192), and the per-pair scalars t64[pair][j] = <q_j, C[l]_j> (one wave per pair,
+// lanes = sub-quantisers, `ppw` consecutive pairs per wave), in ONE launch, since neither depends on the other:
+// workgroups below `tg` do T, the others the pairs.
 template <int DSUB>
-__global__ void __launch_bounds__(256) lut_T_kernel(const float* __restrict__ Q, const float* __restrict__ CB, int64_t nq, int d, int m,
-                                                    double* __restrict__ T64, double* __restrict__ Tmin, double* __restrict__ Tmax,
-                                                    uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
-                                                    int64_t* __restrict__ counters) {
+__global__ void __launch_bounds__(256) lut_Tt_kernel(const float* __restrict__ Q, const float* __restrict__ C, const float* __restrict__ CB,
+                                                     const int32_t* __restrict__ probes, int64_t nq, int64_t npairs, int ppw, int d, int m,
+                                                     unsigned tg, double* __restrict__ T64, double* __restrict__ Tmin,
+                                                     double* __restrict__ Tmax, double* __restrict__ t64, int64_t* __restrict__ counters) {
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (w >= nq * m) return;
-    const int64_t q = w / m;
-    const int j = (int)(w - q * m);
     const int dsub = DSUB ? DSUB : d / m;
-    if (j == 0 && lane == 0) {   // running maxima of the pair kernel and the table counters start at zero
-        range_bits[q] = 0u; mag_bits[q] = 0u;
-        if (q == 0) { counters[4] = 0; counters[5] = 0; }
-    }
-    const float* qv = Q + q * d + j * dsub;
-    double mn = 0.0, mx = 0.0;
+    if (blockIdx.x < tg) {
+        const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        if (w >= nq * m) return;
+        const int64_t q = w / m;
+        const int j = (int)(w - q * m);
+        if (w == 0 && lane == 0) { counters[4] = 0; counters[5] = 0; }
+        const float* qv = Q + q * d + j * dsub;
+        double mn = 0.0, mx = 0.0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = lane + 64 * i;
-        const double acc = subdot<DSUB>(qv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
-        T64[(q * m + j) * KSUB + c] = acc;
-        mn = i ? fmin(mn, acc) : acc;
-        mx = i ? fmax(mx, acc) : acc;
+        for (int i = 0; i < 4; ++i) {
+            const int c = lane + 64 * i;
+            const double acc = subdot<DSUB>(qv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
+            T64[(q * m + j) * KSUB + c] = acc;
+            mn = i ? fmin(mn, acc) : acc;
+            mx = i ? fmax(mx, acc) : acc;
+        }
+        for (int o = 32; o; o >>= 1) {
+            mn = fmin(mn, __shfl_xor(mn, o));
+            mx = fmax(mx, __shfl_xor(mx, o));
+        }
+        if (lane == 0) { Tmin[q * m + j] = mn; Tmax[q * m + j] = mx; }
+        return;
     }
-    for (int o = 32; o; o >>= 1) {
-        mn = fmin(mn, __shfl_xor(mn, o));
-        mx = fmax(mx, __shfl_xor(mx, o));
-    }
-    if (lane == 0) { Tmin[q * m + j] = mn; Tmax[q * m + j] = mx; }
-}
-
-// Per pair: t64[pair][j]; per query: running max of (hi - lo) and of |lo|,|hi| as float bits (>= 0).
-// One wave per pair (lanes = sub-quantisers), `ppw` consecutive pairs per wave, 4 waves per block.
-template <int DSUB>
-__global__ void __launch_bounds__(256) lut_pair_kernel(const float* __restrict__ Q, const float* __restrict__ C,
-                                                       const int32_t* __restrict__ probes, int64_t npairs, int ppw, int nprobe, int d, int m,
-                                                       const double* __restrict__ Tmin, const double* __restrict__ Tmax,
-                                                       double* __restrict__ t64, uint32_t* __restrict__ range_bits,
-                                                       uint32_t* __restrict__ mag_bits) {
-    const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int dsub = DSUB ? DSUB : d / m;
+    const int64_t w = (int64_t)(blockIdx.x - tg) * 4 + (threadIdx.x >> 6);
     for (int pp = 0; pp < ppw; ++pp) {
         const int64_t pair = w * ppw + pp;
         if (pair >= npairs) return;
-        const int64_t q = pair / nprobe;
+        const int64_t q = pair / (npairs / nq);
         const int l = probes[pair];
+        for (int j = lane; j < m; j += 64) t64[pair * m + j] = subdot<DSUB>(Q + q * d + j * dsub, C + (int64_t)l * d + j * dsub, dsub);
+    }
+}
+
+// Everything of one query that follows from T and the pairs' scalars, in workgroups of 16 waves: the query's range
+// and step (maxima over its pairs of the fp32 expressions the definition prescribes), its base table and ambiguous
+// entries, then bias and patches of its pairs (a wave per pair at a time).  gridDim.y workgroups share a query's
+// pairs (small batches: one workgroup per query would leave the chip idle); each of them derives the range and the
+// list of ambiguous entries for itself, in the same order (positions from a prefix sum over the threads, not from
+// an atomic counter), and the first one writes the per-query outputs.
+constexpr int LQ_THREADS = 1024;
+__global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+                                                               const double* __restrict__ Tmax, const double* __restrict__ t64, int nprobe,
+                                                               int m, uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
+                                                               uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
+                                                               int32_t* __restrict__ namb, float* __restrict__ delta,
+                                                               int32_t* __restrict__ bias, uint8_t* __restrict__ patch_val,
+                                                               int64_t* __restrict__ counters) {
+    __shared__ uint32_t s_rng, s_mag;
+    __shared__ int s_n;
+    __shared__ int s_wcnt[LQ_THREADS / 64];
+    __shared__ uint16_t s_amb[AMB_MAX];
+    __shared__ double s_t16[LQ_THREADS / 64][128];
+    __shared__ float s_lo16[LQ_THREADS / 64][128];
+    __shared__ double s_Tmin[128], s_Tmax[128];
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { s_rng = 0u; s_mag = 0u; s_n = 0; }
+    for (int j = tid; j < m; j += LQ_THREADS) { s_Tmin[j] = Tmin[q * m + j]; s_Tmax[j] = Tmax[q * m + j]; }
+    __syncthreads();
+    // ---- range and magnitude over the query's (pair, sub-quantiser) entries
+    {
         float rng = 0.f, mag = 0.f;
-        for (int j = lane; j < m; j += 64) {
-            const double acc = subdot<DSUB>(Q + q * d + j * dsub, C + (int64_t)l * d + j * dsub, dsub);
-            t64[pair * m + j] = acc;
-            const float lo = (float)(Tmin[q * m + j] + acc), hi = (float)(Tmax[q * m + j] + acc);
+        const double* tq = t64 + q * nprobe * m;
+        for (int i = tid; i < nprobe * m; i += LQ_THREADS) {
+            const int j = i % m;
+            const double t = tq[i];
+            const float lo = (float)(s_Tmin[j] + t), hi = (float)(s_Tmax[j] + t);
             rng = fmaxf(rng, hi - lo);
             mag = fmaxf(mag, fmaxf(fabsf(lo), fabsf(hi)));
         }
         for (int o = 32; o; o >>= 1) { rng = fmaxf(rng, __shfl_xor(rng, o)); mag = fmaxf(mag, __shfl_xor(mag, o)); }
-        if (lane == 0) {
-            if (rng > 0.f) atomicMax(range_bits + q, __float_as_uint(rng));
-            if (mag > 0.f) atomicMax(mag_bits + q, __float_as_uint(mag));
+        if (lane == 0) {     // (non-negative floats order like their bit patterns)
+            if (rng > 0.f) atomicMax(&s_rng, __float_as_uint(rng));
+            if (mag > 0.f) atomicMax(&s_mag, __float_as_uint(mag));
         }
     }
-}
-
-// Per query: base table (plane-major) + list of ambiguous entries.  256 threads = one per codeword.
-__global__ void __launch_bounds__(256) lut_base_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
-                                                       const uint32_t* __restrict__ range_bits, const uint32_t* __restrict__ mag_bits,
-                                                       int m, uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
-                                                       int32_t* __restrict__ namb, float* __restrict__ delta,
-                                                       int64_t* __restrict__ counters) {
-    __shared__ int s_n;
-    const int64_t q = blockIdx.x;
-    const int c = threadIdx.x;
-    if (c == 0) s_n = 0;
     __syncthreads();
-    const float range = __uint_as_float(range_bits[q]);
+    const float range = __uint_as_float(s_rng);
     const float dq = lut_step(range);
-    const double eta = lut_eta(range, __uint_as_float(mag_bits[q]), dq);
-    const double inv_dq = 1.0 / (double)dq;
-    const double* Tq = T64 + q * m * KSUB + c;
-    const int S = rago_steps(m), planes = rago_planes(m);
-    for (int plane = 0; plane < planes; ++plane) {
+    const bool writer = blockIdx.y == 0;
+    if (tid == 0 && writer) { range_bits[q] = s_rng; mag_bits[q] = s_mag; delta[q] = dq; }
+    // ---- base table and ambiguous entries: thread = (plane, codeword)
+    {
+        const double eta = lut_eta(range, __uint_as_float(s_mag), dq);
+        const double inv_dq = 1.0 / (double)dq;
+        const int S = rago_steps(m), planes = rago_planes(m);
+        const int plane = tid >> 8, c = tid & 255;
         uint32_t row[8];                      // 32 slots of this plane, one byte each
 #pragma unroll
         for (int i = 0; i < 8; ++i) row[i] = 0;
+        uint32_t flagged = 0;                 // slots of (plane, c) whose rounding depends on the pair
+        if (plane < planes) {
+            const double* Tq = T64 + q * m * KSUB + c;
 #pragma unroll
-        for (int slot = 0; slot < 32; ++slot) {
-            if (slot >= S) continue;
-            const int j = plane * 32 + slot;
-            const double u = (Tq[(int64_t)j * KSUB] - Tmin[q * m + j]) * inv_dq;   // (2^-52 relative off the quotient: far inside eta)
-            double r = rint(u);
-            r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
-            row[slot >> 2] |= (uint32_t)r << (8 * (slot & 3));
-            if (fabs((u - floor(u)) - 0.5) <= eta) {
-                for (int rep = slot; rep < 32; rep += S) {     // every replica of the sub-table (m < 32)
-                    const int i = atomicAdd(&s_n, 1);
-                    if (i < AMB_MAX) amb_addr[q * AMB_MAX + i] = (uint16_t)(plane * LUT_PLANE + c * 32 + rep);
-                }
+            for (int slot = 0; slot < 32; ++slot) {
+                if (slot >= S) continue;
+                const int j = plane * 32 + slot;
+                const double u = (Tq[(int64_t)j * KSUB] - s_Tmin[j]) * inv_dq;   // (2^-52 relative off the quotient: far inside eta)
+                double r = rint(u);
+                r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
+                row[slot >> 2] |= (uint32_t)r << (8 * (slot & 3));
+                if (fabs((u - floor(u)) - 0.5) <= eta) flagged |= 1u << slot;
+            }
+            if (S < 32) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (i * 4 >= S) row[i] = row[i & (S / 4 - 1)];
+            }
+            if (writer) {
+                uint4* dst = reinterpret_cast<uint4*>(lut_base + q * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
+                dst[0] = make_uint4(row[0], row[1], row[2], row[3]);
+                dst[1] = make_uint4(row[4], row[5], row[6], row[7]);
             }
         }
-        if (S < 32) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i * 4 >= S) row[i] = row[i & (S / 4 - 1)];
+        // positions of the flagged entries in the query's list: exclusive prefix sum over the threads (every replica
+        // of a sub-table counts, m < 32), so that every workgroup of the query builds the same list
+        const int mine = __popc(flagged) * (32 / S);
+        int inc = mine;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(inc, o);
+            if (lane >= o) inc += v;
         }
-        uint4* dst = reinterpret_cast<uint4*>(lut_base + q * LUT_BYTES + (int64_t)plane * LUT_PLANE + c * 32);
-        dst[0] = make_uint4(row[0], row[1], row[2], row[3]);
-        dst[1] = make_uint4(row[4], row[5], row[6], row[7]);
+        if (lane == 63) s_wcnt[wave] = inc;
+        __syncthreads();
+        int at = inc - mine;
+        for (int w = 0; w < wave; ++w) at += s_wcnt[w];
+        if (tid == LQ_THREADS - 1) s_n = at + mine;
+        for (uint32_t f = flagged; f; f &= f - 1) {
+            const int slot = __ffs(f) - 1;
+            for (int rep = slot; rep < 32; rep += S) {
+                if (at < AMB_MAX) {
+                    const uint16_t a = (uint16_t)(plane * LUT_PLANE + c * 32 + rep);
+                    s_amb[at] = a;
+                    if (writer) amb_addr[q * AMB_MAX + at] = a;
+                }
+                ++at;
+            }
+        }
     }
     __syncthreads();
-    if (c == 0) {
-        namb[q] = s_n > AMB_MAX ? AMB_MAX + 1 : s_n;   // AMB_MAX + 1 = "evaluate per pair"
-        delta[q] = dq;
-        if (s_n > AMB_MAX) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), 1ull);
-        else atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)s_n);
+    const int n = s_n;
+    if (tid == 0 && writer) {
+        namb[q] = n > AMB_MAX ? AMB_MAX + 1 : n;   // AMB_MAX + 1 = "evaluate per pair"
+        if (n > AMB_MAX) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), 1ull);
+        else atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)n);
     }
-}
-
-// Per pair: bias and the exact values of the query's ambiguous entries.  One wave per pair, four pairs per
-// workgroup (a pair has little work: m minima and a few dozen entries).
-__global__ void __launch_bounds__(256) lut_patch_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
-                                                        const double* __restrict__ t64, const uint32_t* __restrict__ range_bits,
-                                                        const uint16_t* __restrict__ amb_addr, const int32_t* __restrict__ namb,
-                                                        int64_t npairs, int nprobe, int m, int32_t* __restrict__ bias,
-                                                        uint8_t* __restrict__ patch_val) {
-    __shared__ double s_t4[4][128];
-    __shared__ float s_lo4[4][128];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t pair = (int64_t)blockIdx.x * 4 + wave;
-    if (pair >= npairs) return;                       // (whole waves leave; there is no workgroup barrier below)
-    double* s_t = s_t4[wave];
-    float* s_lo = s_lo4[wave];
-    const int64_t q = pair / nprobe;
-    const float dq = lut_step(__uint_as_float(range_bits[q]));
-    for (int j = lane; j < m; j += 64) {
-        const double t = t64[pair * m + j];
-        s_t[j] = t;
-        s_lo[j] = (float)(Tmin[q * m + j] + t);
-    }
-    // (the wave's own LDS writes are visible to its later reads: LDS operations of a wave complete in order; the
-    // wave barrier only keeps the compiler from moving the reads up)
-    __builtin_amdgcn_wave_barrier();
-    if (lane == 0) {
-        double losum = 0.0;
-        for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
-        bias[pair] = (int32_t)rint(losum / (double)dq);
-    }
-    const int n = namb[q];
-    if (n > AMB_MAX) return;
-    const int S = rago_steps(m);
-    for (int i = lane; i < n; i += 64) {
-        const int addr = amb_addr[q * AMB_MAX + i];
-        const int plane = addr / LUT_PLANE, c = (addr >> 5) & 255, slot = addr & 31;
-        const int j = plane * 32 + (slot & (S - 1));
-        patch_val[pair * AMB_MAX + i] = lut_entry(T64[(q * m + j) * KSUB + c], s_t[j], s_lo[j], dq);
+    // ---- bias and patches: a wave per pair
+    {
+        double* s_t = s_t16[wave];
+        float* s_lo = s_lo16[wave];
+        const int S = rago_steps(m);
+        for (int p = blockIdx.y * (LQ_THREADS / 64) + wave; p < nprobe; p += gridDim.y * (LQ_THREADS / 64)) {
+            const int64_t pair = q * nprobe + p;
+            for (int j = lane; j < m; j += 64) {
+                const double t = t64[pair * m + j];
+                s_t[j] = t;
+                s_lo[j] = (float)(s_Tmin[j] + t);
+            }
+            // (the wave's own LDS writes are visible to its later reads: LDS operations of a wave complete in order;
+            // the wave barrier only keeps the compiler from moving the reads up)
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0) {
+                double losum = 0.0;
+                for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
+                bias[pair] = (int32_t)rint(losum / (double)dq);
+            }
+            if (n <= AMB_MAX) {
+                for (int i = lane; i < n; i += 64) {
+                    const int addr = s_amb[i];
+                    const int plane = addr / LUT_PLANE, c = (addr >> 5) & 255, slot = addr & 31;
+                    const int j = plane * 32 + (slot & (S - 1));
+                    patch_val[pair * AMB_MAX + i] = lut_entry(T64[(q * m + j) * KSUB + c], s_t[j], s_lo[j], dq);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 }
 
@@ -382,21 +412,18 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     if (idx->reserving) return RAGO_OK;
     const int ppw = npairs >= 32768 ? 8 : 1;
     const unsigned tg = (unsigned)((nq * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
-    if (d / m == 8 && d % 4 == 0) {      // (16-byte loads of the sub-vectors)
-        lut_T_kernel<8><<<tg, 256, 0, st>>>(q, idx->codebooks, nq, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, range_bits, mag_bits,
-                                            ws.counters.as<int64_t>());
-        lut_pair_kernel<8><<<pgrid, 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
-                                                  ws.pair_lo.as<double>(), range_bits, mag_bits);
-    } else {
-        lut_T_kernel<0><<<tg, 256, 0, st>>>(q, idx->codebooks, nq, d, m, ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, range_bits, mag_bits,
-                                            ws.counters.as<int64_t>());
-        lut_pair_kernel<0><<<pgrid, 256, 0, st>>>(q, idx->centroids, probes, npairs, ppw, nprobe, d, m, ws.Tmin.as<double>(), Tmax,
-                                                  ws.pair_lo.as<double>(), range_bits, mag_bits);
-    }
-    lut_base_kernel<<<(unsigned)nq, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), range_bits, mag_bits, m,
-                                                  ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(), ws.counters.as<int64_t>());
-    lut_patch_kernel<<<(unsigned)((npairs + 3) / 4), 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
-                                                                   amb_addr, namb, npairs, nprobe, m, ws.bias.as<int32_t>(), ws.patch.as<uint8_t>());
+    // two launches: the per-query tables together with the per-pair scalars, then everything else of a query
+    if (d / m == 8 && d % 4 == 0)        // (16-byte loads of the sub-vectors)
+        lut_Tt_kernel<8><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, ws.T64.as<double>(),
+                                                     ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
+    else
+        lut_Tt_kernel<0><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, ws.T64.as<double>(),
+                                                     ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
+    // (workgroups per query: enough to fill the chip on a small batch, at most one per 32 pairs)
+    const unsigned lq_y = (unsigned)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(512 / nq, (nprobe + 31) / 32), 16));
+    lut_query_kernel<<<dim3((unsigned)nq, lq_y), LQ_THREADS, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), nprobe, m,
+                                                          range_bits, mag_bits, ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(),
+                                                          ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>());
     if (out_L_f32 || out_LUT8)
         lut_expand_kernel<<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
                                                             ws.lut8.as<uint8_t>(), amb_addr, namb, ws.patch.as<uint8_t>(), nprobe, m,

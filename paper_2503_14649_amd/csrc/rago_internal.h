@@ -60,7 +60,7 @@ int forced_scan_kernel();        // 0 = pick by sizes, 1 = wide, 2 = narrow, 3 =
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo, wave_items, wave_q;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo, wave_items, wave_q, wave_stage;
     void release();
 };
 
@@ -128,11 +128,12 @@ int read_stream_sink_words();
 int launch_expand_pq4(const float* d_cb16, int m, int dsub, float* d_cb256, hipStream_t st);
 
 // coarse.hip
-int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st);
+// (zero_select_counter: also clear the counter launch_select adds to, which then need not launch a kernel for it)
+int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStream_t st, bool zero_select_counter = false);
 int launch_split_centroids(rago_index* idx, hipStream_t st);
 // (S is read and, for a query whose choice cannot be shown independent of its rounding, overwritten with exact scores)
 int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes,
-                  hipStream_t st);
+                  hipStream_t st, bool counter_is_zero = false);
 
 // tree.hip
 int launch_select_tree(rago_index* idx, const float* q, int64_t nq, int nprobe, int32_t* probes, hipStream_t st);

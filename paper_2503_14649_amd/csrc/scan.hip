@@ -404,7 +404,7 @@ __device__ __forceinline__ void merge_task(const ScanParams& P, const int32_t* D
     if (lane == 0) {
         P.part_cnt[slot] = base_o;
         // k entries reach the k-th key's score: a valid lower bound of the query's k-th best
-        if (total >= k) atomicMax(P.tauq + q, bias + (int32_t)(kth >> 16));
+        if (total >= k) publish_bound(P.tauq + q, bias + (int32_t)(kth >> 16));
     }
 }
 
@@ -815,32 +815,6 @@ __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restri
 }
 
 // ------------------------------------------------------------------ per-query merge of the task results
-constexpr int MERGE_THREADS = 256;
-constexpr int MERGE_CAP = 2048;
-
-__device__ __forceinline__ bool entry_before(int32_t ia, int64_t da, int32_t ib, int64_t db) {
-    return ia > ib || (ia == ib && da < db);
-}
-
-// Sort sI/sId[0..n2) (n2 a power of two) by (I desc, id asc).
-__device__ void bitonic_sort(int32_t* sI, int64_t* sId, int n2) {
-    for (int size = 2; size <= n2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int t = threadIdx.x; t < n2 / 2; t += MERGE_THREADS) {
-                const int i = 2 * t - (t & (stride - 1));
-                const int j = i + stride;
-                const bool up = (i & size) == 0;  // this sub-sequence ends best-first
-                const int32_t ia = sI[i], ib = sI[j];
-                const int64_t da = sId[i], db = sId[j];
-                const bool swap = up ? entry_before(ib, db, ia, da) : entry_before(ia, da, ib, db);
-                if (swap) { sI[i] = ib; sI[j] = ia; sId[i] = db; sId[j] = da; }
-            }
-        }
-    }
-    __syncthreads();
-}
-
 __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P, const float* __restrict__ delta,
                                                               int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
                                                               int32_t* __restrict__ out_iscores) {
@@ -998,9 +972,9 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
 }
 
 // Which kernel and which chunk length.  The wide kernel (four pairs per pass, one workgroup per CU) pays a
-// fixed price per task that only long tasks amortise; short lists and small batches go to the narrow one
-// (two pairs per pass, two workgroups per CU); rago_debug_force_scan_kernel overrides the choice (tests run
-// every case through both).  Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key,
+// fixed price per task that only long tasks amortise; small batches go to the narrow one (two pairs per pass,
+// two workgroups per CU), short lists to the one with a wave per item (scan_wave.hip);
+// rago_debug_force_scan_kernel overrides the choice (tests run every case through all three).  Chunk length: aim at ~2048 tasks.  (<= 512 blocks: the position half of a key,
 // 0xFFFF - position, then never vanishes, so a key is never 0 = "empty")
 enum { SCAN_WIDE = 0, SCAN_NARROW = 1, SCAN_WAVE = 2 };
 struct ScanPlan { int kind; int CH, group, maxchunks; };
@@ -1011,7 +985,7 @@ static int chunk_len(double npairs, double avgblk, double pairs_per_task, int ca
     return c;
 }
 
-static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs) {
+static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs, bool base_tables) {
     const double avgblk = (double)idx->total_blocks / idx->nlist;
     const int CH_wide = chunk_len((double)npairs, avgblk, nq > 1 ? 2.0 : 1.0, 512);
     // (measured on a 1e9 x 96 B index with 65536 lists: the wide kernel wins from about two pairs per list up,
@@ -1020,6 +994,11 @@ static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs) {
     const int force = forced_scan_kernel();
     ScanPlan p;
     p.kind = wide ? SCAN_WIDE : SCAN_NARROW;
+    // Short lists under the inner product (a query's pairs share its base table): one wave per item, pairs grouped
+    // by query.  Measured on 10M x 96 B with 16384 lists of ~10 blocks, 256 queries x 64 lists: 0.20 ms against
+    // 0.25 ms, and 8 us of planning against 40.  On lists of hundreds of blocks the kernels that put eight waves on
+    // neighbouring blocks stream 15 % faster (1e9 x 96 B, 1 to 16 queries x 256 lists).
+    if (!wide && base_tables && avgblk <= 32.0) p.kind = SCAN_WAVE;
     if (force >= 1 && force <= 3) p.kind = force - 1;
     if (p.kind == SCAN_WIDE) p.CH = CH_wide;
     else if (p.kind == SCAN_NARROW) p.CH = chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256);
@@ -1053,8 +1032,8 @@ static int64_t max_result_slots(const rago_index* idx, int64_t max_nq, int max_n
                     look(np, np_max, chunk_len((double)np, avgblk, ppts[kern], caps[kern]));
                 }
             }
-        for (int c = 8; c <= 512; c <<= 1) {                        // the kernel with one wave per item
-            const int64_t edge = (int64_t)(3.0 * 2 * 8 * idx->n_cu * c / avgblk);
+        for (int c = 1; c <= 512; c <<= 1) {                        // the kernel with one wave per item
+            const int64_t edge = (int64_t)(4.0 * 2 * 8 * idx->n_cu * c / avgblk);
             for (int64_t np : {edge - 1, edge, edge + 1, np_max}) {
                 np = std::min(std::max<int64_t>(np, 1), np_max);
                 look(np, np_max, wave_chunk_len((double)np * avgblk, idx->n_cu));
@@ -1070,7 +1049,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     Workspace& ws = idx->ws;
     const int64_t npairs = nq * nprobe;
     const int nlist = idx->nlist;
-    const ScanPlan plan = plan_scan(idx, nq, npairs);
+    const ScanPlan plan = plan_scan(idx, nq, npairs, tables != nullptr);
     const bool wide = plan.kind == SCAN_WIDE;
     const int CH = plan.CH, group = plan.group, maxchunks = plan.maxchunks;
     // per-task result slots: for this call, or (when the workspace is being sized) the most any call within
@@ -1091,8 +1070,9 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     const int64_t max_tasks = npairs * maxchunks;
     if ((rc = ws.task_table.reserve((size_t)slots * 16))) return rc;
     if (idx->reserving || plan.kind == SCAN_WAVE) {
-        if ((rc = ws.wave_items.reserve((size_t)slots * wave_item_bytes()))) return rc;
-        if ((rc = ws.wave_q.reserve((size_t)nq * 32))) return rc;
+        if ((rc = ws.wave_items.reserve((size_t)npairs * wave_pair_bytes()))) return rc;
+        if ((rc = ws.wave_q.reserve((size_t)nq * 48))) return rc;
+        if ((rc = ws.wave_stage.reserve(wave_stage_bytes(nq, k)))) return rc;
     }
     if (idx->reserving) return RAGO_OK;
 
@@ -1112,18 +1092,10 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     P.nlist = nlist; P.nprobe = nprobe; P.k = k; P.CH = CH; P.maxchunks = maxchunks;
 
     const int n_cu = idx->n_cu;
-    if (plan.kind == SCAN_WAVE) {
-        int4* qinfo = ws.wave_q.as<int4>();
-        if ((rc = launch_scan_wave(P, nq, n_cu, (double)idx->total_blocks / nlist, ws.wave_items.p, ws.task_table.as<int4>(),
-                                   ws.pair_sorted.as<int32_t>(), qinfo, reinterpret_cast<int64_t*>(qinfo + nq), ws.counters.as<int64_t>(),
-                                   ev ? ev[4] : nullptr, st)))
-            return rc;
-        if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
-        merge_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
-        RAGO_HIP(hipGetLastError());
-        if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
-        return RAGO_OK;
-    }
+    if (plan.kind == SCAN_WAVE)
+        return launch_scan_wave(P, nq, n_cu, (double)idx->total_blocks / nlist, ws.wave_items.p, ws.pair_sorted.as<int32_t>(),
+                                ws.wave_q.as<int32_t>(), ws.wave_stage.p, ws.counters.as<int64_t>(), delta, out_ids, out_scores, out_iscores,
+                                ev, st);
     const unsigned pg = (unsigned)((npairs + 255) / 256);
     scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl, ws.counters.as<int64_t>());
     if (nq >= 64) {

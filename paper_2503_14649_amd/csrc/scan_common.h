@@ -29,6 +29,15 @@ struct ScanParams {
 };
 
 // ------------------------------------------------------------------ small helpers
+// Publish a bound on a query's k-th best score.  Any value ever published is a valid bound, so a plain store is
+// enough (a late smaller store only weakens the word until the next one): read-modify-write operations on ONE address
+// in HBM run at a few tens of millions per second and, on this hardware, hold up every later load of the wave that
+// issued them, which costs tens of microseconds when hundreds of workgroups work on a handful of queries.
+__device__ __forceinline__ void publish_bound(int32_t* tauq, int32_t value) {
+    if (value > __hip_atomic_load(tauq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        __hip_atomic_store(tauq, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ int lane_rank(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
@@ -106,13 +115,42 @@ __device__ __forceinline__ void load_block(uint4 (&w)[MPAD / 16], const uint8_t*
     }
 }
 
+// ------------------------------------------------------------------ final per-query merge: shared pieces
+constexpr int MERGE_THREADS = 256;
+constexpr int MERGE_CAP = 2048;
+
+__device__ __forceinline__ bool entry_before(int32_t ia, int64_t da, int32_t ib, int64_t db) {
+    return ia > ib || (ia == ib && da < db);
+}
+
+// Sort sI/sId[0..n2) (n2 a power of two) by (I desc, id asc).
+__device__ inline void bitonic_sort(int32_t* sI, int64_t* sId, int n2) {
+    for (int size = 2; size <= n2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < n2 / 2; t += MERGE_THREADS) {
+                const int i = 2 * t - (t & (stride - 1));
+                const int j = i + stride;
+                const bool up = (i & size) == 0;  // this sub-sequence ends best-first
+                const int32_t ia = sI[i], ib = sI[j];
+                const int64_t da = sId[i], db = sId[j];
+                const bool swap = up ? entry_before(ib, db, ia, da) : entry_before(ia, da, ib, db);
+                if (swap) { sI[i] = ib; sI[j] = ia; sId[i] = db; sId[j] = da; }
+            }
+        }
+    }
+    __syncthreads();
+}
+
 // scan_narrow.hip: the two-pairs-per-pass kernel on 2 * n_cu workgroups (task records with 1 or 2 pairs)
 int launch_scan_narrow(const ScanParams& P, int n_cu, hipStream_t st);
 
-// scan_wave.hip: one wave per (pair, chunk) item, pairs grouped by query.  Plans its items and tasks itself.
+// scan_wave.hip: one wave per (pair, chunk) item, pairs grouped by query.  Plans, scans and sorts the results itself.
 int wave_chunk_len(double total_blocks, int n_cu);
-size_t wave_item_bytes();
-int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* items, int4* tasks, int32_t* pair_items,
-                     int4* qinfo, int64_t* qbytes, int64_t* counters, hipEvent_t ev_scan, hipStream_t st);
+size_t wave_pair_bytes();
+size_t wave_stage_bytes(int64_t nq, int k);
+int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* pdesc, int32_t* pair_pre, int32_t* qwork,
+                     void* stage, int64_t* counters, const float* delta, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
+                     hipEvent_t* ev, hipStream_t st);
 
 }  // namespace rago

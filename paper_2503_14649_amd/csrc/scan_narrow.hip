@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(SCAN_THREADS, 4) scan_kernel(const ScanParams 
             if (lane == 0) {
                 P.part_cnt[slot] = base_o;
                 // k entries reach the k-th key's score: a valid lower bound of the query's k-th best
-                if (total >= k) atomicMax(P.tauq + (wave == 0 ? qA : qB), bias + (int32_t)(kth >> 16));
+                if (total >= k) publish_bound(P.tauq + (wave == 0 ? qA : qB), bias + (int32_t)(kth >> 16));
             }
         }
         __syncthreads();

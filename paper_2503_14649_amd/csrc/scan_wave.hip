@@ -3,25 +3,41 @@
 // per-task fixed work.  Same results as the kernels of scan.hip and scan_narrow.hip, which group
 // the pairs by list; this one groups them by QUERY:
 //
-//  * a task = a run of consecutive items of one query; the workgroup (8 waves, two workgroups per
-//    CU) brings that query's 8-bit base table into LDS once, then its waves claim items from an
-//    LDS counter and work through them independently.  Under the inner product the tables of a
-//    query's pairs differ from its base table only in the few entries whose rounding depends on
-//    the pair (lut.hip).  Those entries are not patched into the shared table: a wave turns the
-//    pair's patches into corrections (sub-quantiser, code, +-difference), sums with the base
-//    table, and applies the corrections, from the code bytes it holds in registers, only to blocks
-//    in which some vector comes within the corrections' reach of the threshold.
+//  * a workgroup (8 waves, two workgroups per CU) attaches to a query: it brings that query's
+//    8-bit base table into LDS once, then its waves claim items of the query (in batches, from a
+//    per-query counter in HBM) and work through them independently (the item after the current one
+//    is claimed and resolved while the current one streams).  Any number of workgroups may be
+//    attached to one query; a workgroup whose query has run out of items attaches to the query
+//    with the most items left per attached workgroup, and leaves when no query has any.  With one
+//    query all workgroups share it; with thousands each workgroup takes whole queries.
+//  * under the inner product the tables of a query's pairs differ from its base table only in the
+//    few entries whose rounding depends on the pair (lut.hip).  Those entries are not patched into
+//    the shared table: a wave turns the pair's patches into corrections (sub-quantiser, code,
+//    +-difference), sums with the base table, and applies the corrections, from the code bytes it
+//    holds in registers, only to blocks in which some vector comes within the corrections' reach
+//    of the threshold.
 //  * per-pair tables (Euclidean metric, caller-supplied tables, queries whose tables are too flat
-//    for the base + patch form) are installed pair by pair, with a barrier before and after, and
-//    the waves share out that pair's items.
+//    for the base + patch form): the workgroup claims whole pairs, installs the pair's table
+//    between two barriers, and its waves share out that pair's items.
 //  * LDS table layout (32 KiB): byte address = code * 128 + slot * 4 + plane.  `slot` selects the
 //    bank, so a sub-table lives in ONE bank; the 32 lanes of a half-wave always work on 32
 //    different slots (layout.hip), so every ds_read_u8 is conflict-free whatever the codes are.
 //    One v_perm_b32 places two code bytes next to the lane's slot * 8 bytes; a bit-field extract
 //    and a shift by one bit turn the halves into addresses; the plane rides in the immediate.
-//  * an item leaves <= k (score, row) entries in its own slot of the per-task result arrays; the
-//    per-query bound on the k-th best score is shared through LDS and a word in HBM; the final
-//    merge is the one of scan.hip.
+//  * an item leaves its best <= k entries that still reach the query's bound in its own slot of
+//    the result arrays (slot = number of the item inside its query: nothing to synchronise); the
+//    bound on the k-th best score is shared through LDS and a word in HBM; the final merge runs
+//    in two stages when a query has thousands of items (slices of the slots, then the slices'
+//    results).
+//  * the k-th best score of a single item is a weak bound when lists are short and k is large (the
+//    100th of 600 vectors, where the query's answer is the 100th of 40 000).  Every workgroup
+//    therefore counts the candidates of all its items of the query in a histogram of their
+//    scores above its first bound (LDS): k candidates at or above a bin edge make that edge a
+//    bound.  With it an item leaves a handful of entries instead of k.
+//  * a single address in HBM takes only a few tens of millions of atomic operations per second,
+//    so nothing here issues one per item: a workgroup claims items of its query sixteen at a time
+//    (its waves share them out through LDS), the first sixteen come with the attachment, and the
+//    bound goes to HBM only when the workgroup's own copy improved.
 #include <algorithm>
 
 #include "scan_common.h"
@@ -33,13 +49,19 @@ constexpr int WAVES = 8;
 constexpr int THREADS = WAVES * 64;
 constexpr int LUT_LDS = 32768;
 constexpr int CORR_CAP = AMB_MAX;
-// LDS: table | key buffers [wave][CAPW] | corrections [wave][CORR_CAP] | ambiguous entries of the query: address u16, base value u8 | scalars
+constexpr int BATCH = 2 * WAVES;                // items a workgroup claims at a time
+constexpr int PRE_CAP = 2048 + 1;               // first item of every pair of the query (nprobe <= 2048) and the total
+// LDS: table | key buffers [wave][CAPW] | corrections [wave][CORR_CAP] | ambiguous entries of the query: address u16,
+// base value u8 | first item of each pair | scalars | histogram of candidate scores
 constexpr int OFF_CAND = LUT_LDS;
 constexpr int OFF_CORR = OFF_CAND + WAVES * CAPW * 4;
 constexpr int OFF_AMB = OFF_CORR + WAVES * CORR_CAP * 4;
 constexpr int OFF_AMBV = OFF_AMB + AMB_MAX * 2;
-constexpr int OFF_SH = OFF_AMBV + AMB_MAX;
-constexpr int SCAN_LDS = OFF_SH + 64 * 4;
+constexpr int OFF_PRE = OFF_AMBV + AMB_MAX;
+constexpr int OFF_SH = OFF_PRE + ((PRE_CAP * 4 + 15) & ~15);
+constexpr int HIST_BINS = 1024, HIST_SHIFT = 2;  // scores of the workgroup's candidates above its first bound, 4 to a bin
+constexpr int OFF_HIST = OFF_SH + 64 * 4;
+constexpr int SCAN_LDS = OFF_HIST + HIST_BINS * 4;
 
 #define RAGO_WSEL_A 0x05010400u   // {code1, slot1*8, code0, slot0*8}
 #define RAGO_WSEL_B 0x07030602u   // {code3, slot3*8, code2, slot2*8}
@@ -133,12 +155,24 @@ __device__ __forceinline__ uint32_t code_of(const uint4 (&w)[MPAD / 16], int j, 
     return (dw >> (8 * (step & 3))) & 255u;
 }
 
-struct Item { int64_t blk0, row0; int32_t nb, cvecs, pair, chunk; };   // 32 bytes: one (pair, chunk of the list)
+// One probed list of one query: where its codes and rows start, how long it is, and the query-local number of
+// its first item.
+struct PairDesc { int64_t blk0, row0; int32_t nblk, len, pre, pad; };   // 32 bytes
 
 struct WaveParams {
-    ScanParams S;              // codes, tables, result arrays, nprobe, k, CH (= blocks per item), maxchunks
-    const Item* items;         // [nitems] grouped by query, then pair, then chunk
-    const int4* tasks;         // [ntasks] {query, first item, end item, 0}
+    ScanParams S;              // codes, tables, nprobe, k, CH (= blocks per item), maxchunks; part_* = per-item result slots
+    const PairDesc* pdesc;     // [npairs]
+    const int32_t* pair_pre;   // [npairs] first item of the pair inside its query
+    const int4* qinfo;         // [nq] {units (items, or pairs when tables come per pair), items, per-pair tables?, 0}
+    int32_t* qnext;            // [nq] next unclaimed unit
+    int32_t* qatt;             // [nq] workgroups attached
+    const int64_t* qbytes;     // [nq][2] code bytes streamed / algorithmic code bytes of the query
+    int64_t* counters;
+    int nq;
+    int64_t qslots;            // result slots per query (= nprobe * maxchunks >= its items)
+    int nslice;                // slices of a query's slots in the first stage of the merge (1: the only stage)
+    int32_t* stage_I;          // [nq][nslice][k] first-stage results (score, id), INT32_MIN = none
+    int64_t* stage_id;
 };
 
 // Interleave one plane-major table (HBM, [plane][c][slot] bytes) into the LDS table: the planes of a (code, slot)
@@ -188,6 +222,8 @@ __device__ __forceinline__ void eval_table(const ScanParams& P, int pair, int q,
     }
 }
 
+struct ItemDesc { int64_t blk0, row0; int nb, cvecs, pair, valid, item; };   // item = its number inside the query
+
 template <int MPAD>
 __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
     constexpr int S = MPAD < 32 ? MPAD : 32;
@@ -201,8 +237,14 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
     uint32_t* corr = reinterpret_cast<uint32_t*>(smem + OFF_CORR) + wave * CORR_CAP;
     uint16_t* s_amb = reinterpret_cast<uint16_t*>(smem + OFF_AMB);
     uint8_t* s_ambv = smem + OFF_AMBV;
+    int32_t* s_pre = reinterpret_cast<int32_t*>(smem + OFF_PRE);
     int32_t* sh = reinterpret_cast<int32_t*>(smem + OFF_SH);
-    // sh[0] task, sh[1] item counter, sh[2] bound on the query's k-th best score (absolute integer score)
+    int32_t* hist = reinterpret_cast<int32_t*>(smem + OFF_HIST);
+    // sh[0] query, sh[1] unit / chunk counter, sh[2] bound on the query's k-th best score (absolute integer score),
+    // sh[3] the first bound the workgroup had for this query = origin of its score histogram (INT32_MIN: none yet),
+    // sh[4..5] best (work left per attached workgroup, query) of the search for a query, sh[8..9] the workgroup's
+    // batch of items as one 64-bit word (end << 32 | next), sh[10] lock of the wave that fetches a new batch,
+    // sh[11] the query's counter may still have items
 
     uint32_t off[S / 4];
 #pragma unroll
@@ -217,208 +259,374 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
         off[g] = v;
     }
     uint32_t sa = RAGO_WSEL_A, sb = RAGO_WSEL_B;
-    const int ntasks = P.ctrl[1];
-    const int k = P.k;
+    const int k = P.k, nq = W.nq, nprobe = P.nprobe, CH = P.CH;
     int loaded_q = -1;                         // query whose base table (and ambiguous entries) sit in LDS
 
-    for (;;) {
-        __syncthreads();                       // every wave is done with the previous task's table and scalars
-        if (threadIdx.x == 0) sh[0] = atomicAdd(P.ctrl, 1);
-        __syncthreads();
-        const int t = __builtin_amdgcn_readfirstlane(sh[0]);
-        if (t >= ntasks) break;                // every wave reads the same word: all leave together
-        const int4 rec = W.tasks[t];
-        const int q = __builtin_amdgcn_readfirstlane(rec.x);
-        const int i0 = __builtin_amdgcn_readfirstlane(rec.y), i1 = __builtin_amdgcn_readfirstlane(rec.z);
-        const int namb = P.lut8sw ? 0 : __builtin_amdgcn_readfirstlane(P.T.namb[q]);
-        const bool shared_base = !P.lut8sw && namb <= AMB_MAX;
-        if (threadIdx.x == 0) sh[2] = __hip_atomic_load(P.tauq + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (shared_base && loaded_q != q) {        // (consecutive tasks of one query, a batch of one query: nothing to do)
-            install_table<planes>(P.T.lut_base + (int64_t)q * LUT_BYTES, lut);
-            for (int i = threadIdx.x; i < namb; i += THREADS) s_amb[i] = P.T.amb_addr[(int64_t)q * AMB_MAX + i];
-            __syncthreads();
-            for (int i = threadIdx.x; i < namb; i += THREADS) s_ambv[i] = lut[entry_lds(s_amb[i])];
+    if (blockIdx.x == 0) {                     // the batch's byte counts (sums of the planning kernel's per-query figures)
+        unsigned long long st = 0, al = 0, it = 0;
+        for (int i = threadIdx.x; i < nq; i += THREADS) {
+            st += (unsigned long long)W.qbytes[2 * i]; al += (unsigned long long)W.qbytes[2 * i + 1]; it += (unsigned long long)W.qinfo[i].y;
         }
-        loaded_q = shared_base ? q : -1;
-        // Segments: the whole task when the waves share the query's base table; else one segment per pair, whose
-        // table is installed between two barriers.
-        int seg0 = i0;
-        while (seg0 < i1) {
-            int seg1 = i1;
-            if (!shared_base) {
-                const int pr = W.items[seg0].pair;
-                seg1 = seg0 + 1;
-                while (seg1 < i1 && W.items[seg1].pair == pr) ++seg1;
-                __syncthreads();               // the previous pair's table is no longer read
-                if (P.lut8sw) install_table<planes>(P.lut8sw + (int64_t)pr * LUT_BYTES, lut);
-                else eval_table(P, pr, q, lut);
-            }
-            if (threadIdx.x == 0) sh[1] = seg0;
-            __syncthreads();
+        for (int o = 32; o; o >>= 1) { st += __shfl_xor(st, o); al += __shfl_xor(al, o); it += __shfl_xor(it, o); }
+        if (lane == 0) {
+            atomicAdd(reinterpret_cast<unsigned long long*>(W.counters + 1), st);
+            atomicAdd(reinterpret_cast<unsigned long long*>(W.counters + 2), al);
+            atomicAdd(reinterpret_cast<unsigned long long*>(W.counters + 0), it);
+        }
+    }
 
-            // ---- the wave's items of this segment
-            auto claim = [&]() {
-                int v = 0;
-                if (lane == 0) v = atomicAdd(&sh[1], 1);
-                return __builtin_amdgcn_readfirstlane(v);
-            };
-            auto load_item = [&](int i) {
-                // (every lane loads the same 32 bytes: one request; the index is clamped so the load is always legal)
-                const int4* p = reinterpret_cast<const int4*>(W.items + min(i, seg1 - 1));
-                const int4 a = p[0], b = p[1];
-                Item it;
-                it.blk0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.y) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.x);
-                it.row0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.w) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.z);
-                it.nb = __builtin_amdgcn_readfirstlane(b.x); it.cvecs = __builtin_amdgcn_readfirstlane(b.y);
-                it.pair = __builtin_amdgcn_readfirstlane(b.z); it.chunk = __builtin_amdgcn_readfirstlane(b.w);
-                return it;
-            };
-            uint4 wa[MPAD / 16], wb[MPAD / 16];
-            int cur_i = claim();
-            Item cur = load_item(cur_i);
-            int nxt_i = claim();
-            Item nxt = load_item(nxt_i);
-            if (cur_i < seg1) load_block<MPAD>(wa, P.codes + cur.blk0 * BLK_BYTES, lane);
-            while (cur_i < seg1) {
-                const int pair = cur.pair, nb = cur.nb, cvecs = cur.cvecs;
-                const uint8_t* base = P.codes + cur.blk0 * BLK_BYTES;
-                const uint8_t* after = nxt_i < seg1 ? P.codes + nxt.blk0 * BLK_BYTES : base;   // what follows this item's last block
-                const int bias = __builtin_amdgcn_readfirstlane(P.bias[pair]);
-                // ---- corrections of this pair: entries whose exact value differs from the base table's
-                int ncorr = 0, maxpos = 0;
-#ifdef RAGO_WV_NOCORR
-                if (false) {
-#else
-                if (shared_base) {
-#endif
-                    for (int i0c = 0; i0c < namb; i0c += 64) {
-                        const int i = i0c + lane;
-                        int dlt = 0;
-                        uint32_t e = 0;
-                        if (i < namb) {
-                            e = s_amb[i];
-                            dlt = (int)P.T.patch_val[(int64_t)pair * AMB_MAX + i] - (int)s_ambv[i];
-                            if ((int)(e & 31u) >= S) dlt = 0;        // a replica of a sub-table (m < 32): counted once
-                        }
-                        const uint64_t mask = __ballot(dlt != 0);
-                        if (dlt != 0) {
-                            const uint32_t j = (e >> 13) * 32u + (e & 31u), c = (e >> 5) & 255u;
-                            corr[ncorr + lane_rank(mask)] = (j << 16) | (c << 8) | ((uint32_t)dlt & 255u);
-                        }
-                        ncorr += __popcll(mask);
-                        int pos = dlt > 0 ? dlt : 0;
-                        for (int o = 32; o; o >>= 1) pos += __shfl_xor(pos, o);
-                        maxpos += pos;
-                    }
-                    maxpos = __builtin_amdgcn_readfirstlane(maxpos);
-                }
-                int cnt = 0;
-                auto bound = [&]() {            // the query's bound in units of this pair's sums
-                    const int64_t d = (int64_t)sh[2] - bias;
-                    return (uint32_t)(d <= 0 ? 0 : (d > 0x7fffffff ? 0x7fffffff : d));
-                };
-                uint32_t thr = bound();
-                auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
-                    const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
-                    const bool valid = (int)pos < cvecs;
-                    uint32_t sum = 0;
-                    block_sum_chunk<MPAD, 0>(w, off, sa, sb, sum);
-                    const uint32_t tb = bound();
-                    if (tb > thr) thr = tb;
-                    if (ncorr && __ballot(valid && sum + (uint32_t)maxpos >= thr)) {
-                        for (int ci = 0; ci < ncorr; ++ci) {
-                            const uint32_t e = __builtin_amdgcn_readfirstlane(corr[ci]);
-                            const uint32_t code = code_of<MPAD>(w, (int)(e >> 16), lane);
-                            if (code == ((e >> 8) & 255u)) sum += (uint32_t)(int)(int8_t)(e & 255u);
-                        }
-                    }
-                    const bool c = valid && sum >= thr;
-                    const uint64_t mask = __ballot(c);
-                    if (mask) {
-                        const int add = __popcll(mask);
-                        if (cnt + add > CAPW) {
-                            const uint32_t kth = wave_prune(buf, cnt, k, lane);
-                            if ((kth >> 16) > thr) thr = kth >> 16;
-                            if (lane == 0) atomicMax(&sh[2], bias + (int32_t)thr);
-                        }
-                        if (c) buf[cnt + lane_rank(mask)] = (sum << 16) | (0xFFFFu - pos);
-                        cnt += add;
-                    }
-                };
-                // ---- stream the item's blocks: the block after the current one is always in flight (the first
-                // block of the wave's next item after the last); unconditional loads from clamped addresses
-                int b = 0;
-                for (;;) {
-                    load_block<MPAD>(wb, b + 1 < nb ? base + (int64_t)(b + 1) * BLK_BYTES : after, lane);
-                    process(wa, b);
-                    if (++b == nb) {                       // the next item's first block sits in wb: move it over
-#pragma unroll
-                        for (int i = 0; i < MPAD / 16; ++i) wa[i] = wb[i];
-                        break;
-                    }
-                    load_block<MPAD>(wa, b + 1 < nb ? base + (int64_t)(b + 1) * BLK_BYTES : after, lane);
-                    process(wb, b);
-                    if (++b == nb) break;
-                }
-                // ---- the item's result: its best k by (sum desc, position asc), and what they say about the query
-                uint32_t kth = 0;
-                if (cnt > k) kth = wave_prune(buf, cnt, k, lane);
-                else if (cnt == k) {
-                    uint32_t r[CAPW / 64];
-#pragma unroll
-                    for (int i = 0; i < CAPW / 64; ++i) r[i] = (lane + 64 * i < cnt) ? buf[lane + 64 * i] : 0u;
-                    kth = select_kth<CAPW / 64>(r, k);
-                }
-                const int64_t slot = (int64_t)pair * P.maxchunks + cur.chunk;
-                int32_t* oI = P.part_I + slot * k;
-                int64_t* orow = P.part_row + slot * k;
-                for (int e = lane; e < cnt; e += 64) {
-                    const uint32_t key = buf[e];
-                    oI[e] = bias + (int32_t)(key >> 16);
-                    orow[e] = cur.row0 + (int64_t)(0xFFFFu - (key & 0xFFFFu));
-                }
-                if (lane == 0) {
-                    P.part_cnt[slot] = cnt;
-                    if (cnt >= k) {                    // k entries reach the k-th key's score: a bound on the query's k-th best
-                        const int32_t tq = bias + (int32_t)(kth >> 16);
-                        atomicMax(&sh[2], tq);
-                        atomicMax(P.tauq + q, tq);
-                    }
-                }
-                cur_i = nxt_i;
-                cur = nxt;
-                nxt_i = claim();
-                nxt = load_item(nxt_i);
-            }
-            seg0 = seg1;
+    // ---- one item: stream its blocks, keep its best k, append what still matters to the query's candidate list.
+    // `wa` holds the item's first block when `first_loaded`; on return it holds the first block at `after` (the
+    // wave's next item, if it has one).
+    uint4 wa[MPAD / 16], wb[MPAD / 16];
+    auto run_item = [&](const ItemDesc& d, int q, bool shared_base, int namb, const uint8_t* after_or_null, bool first_loaded) {
+        if (lane == 0) {                       // bounds found by other workgroups meanwhile (a plain load: cheap)
+            const int32_t g = __hip_atomic_load(P.tauq + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (g > sh[2]) atomicMax(&sh[2], g);
         }
+        const int pair = d.pair, nb = d.nb, cvecs = d.cvecs;
+        const uint8_t* base = P.codes + d.blk0 * BLK_BYTES;
+        const uint8_t* after = after_or_null ? after_or_null : base;
+        if (!first_loaded) load_block<MPAD>(wa, base, lane);
+        const int bias = __builtin_amdgcn_readfirstlane(P.bias[pair]);
+        // ---- corrections of this pair: entries whose exact value differs from the base table's
+        int ncorr = 0, maxpos = 0;
+#ifndef RAGO_WV_NOCORR
+        if (shared_base) {
+            for (int i0c = 0; i0c < namb; i0c += 64) {
+                const int i = i0c + lane;
+                int dlt = 0;
+                uint32_t e = 0;
+                if (i < namb) {
+                    e = s_amb[i];
+                    dlt = (int)P.T.patch_val[(int64_t)pair * AMB_MAX + i] - (int)s_ambv[i];
+                    if ((int)(e & 31u) >= S) dlt = 0;        // a replica of a sub-table (m < 32): counted once
+                }
+                const uint64_t mask = __ballot(dlt != 0);
+                if (dlt != 0) {
+                    const uint32_t j = (e >> 13) * 32u + (e & 31u), c = (e >> 5) & 255u;
+                    corr[ncorr + lane_rank(mask)] = (j << 16) | (c << 8) | ((uint32_t)dlt & 255u);
+                }
+                ncorr += __popcll(mask);
+                int pos = dlt > 0 ? dlt : 0;
+                for (int o = 32; o; o >>= 1) pos += __shfl_xor(pos, o);
+                maxpos += pos;
+            }
+            maxpos = __builtin_amdgcn_readfirstlane(maxpos);
+        }
+#endif
+        int cnt = 0;
+        auto bound = [&]() {            // the query's bound in units of this pair's sums
+            const int64_t dd = (int64_t)sh[2] - bias;
+            return (uint32_t)(dd <= 0 ? 0 : (dd > 0x7fffffff ? 0x7fffffff : dd));
+        };
+        uint32_t thr = bound();
+        auto process = [&](const uint4 (&w)[MPAD / 16], int blk) {
+            const uint32_t pos = (uint32_t)(blk * BLOCK_VECS + lane);
+            const bool valid = (int)pos < cvecs;
+            uint32_t sum = 0;
+            block_sum_chunk<MPAD, 0>(w, off, sa, sb, sum);
+            const uint32_t tb = bound();
+            if (tb > thr) thr = tb;
+            if (ncorr && __ballot(valid && sum + (uint32_t)maxpos >= thr)) {
+                for (int ci = 0; ci < ncorr; ++ci) {
+                    const uint32_t e = __builtin_amdgcn_readfirstlane(corr[ci]);
+                    const uint32_t code = code_of<MPAD>(w, (int)(e >> 16), lane);
+                    if (code == ((e >> 8) & 255u)) sum += (uint32_t)(int)(int8_t)(e & 255u);
+                }
+            }
+            const bool c = valid && sum >= thr;
+            const uint64_t mask = __ballot(c);
+            if (mask) {
+                const int32_t origin = sh[3];
+                if (c && origin != INT32_MIN) {
+                    const int64_t dd = (int64_t)bias + (int64_t)sum - origin;
+                    if (dd >= 0) atomicAdd(&hist[(int)min(dd >> HIST_SHIFT, (int64_t)(HIST_BINS - 1))], 1);
+                }
+                const int add = __popcll(mask);
+                if (cnt + add > CAPW) {
+                    const uint32_t kth = wave_prune(buf, cnt, k, lane);
+                    if ((kth >> 16) > thr) thr = kth >> 16;
+                    if (lane == 0) atomicMax(&sh[2], bias + (int32_t)thr);
+                }
+                if (c) buf[cnt + lane_rank(mask)] = (sum << 16) | (0xFFFFu - pos);
+                cnt += add;
+            }
+        };
+        // ---- stream the item's blocks: the block after the current one is always in flight (the first block of
+        // the wave's next item after the last); unconditional loads from addresses that are always legal
+        int b = 0;
+        for (;;) {
+            load_block<MPAD>(wb, b + 1 < nb ? base + (int64_t)(b + 1) * BLK_BYTES : after, lane);
+            process(wa, b);
+            if (++b == nb) {                       // the next item's first block sits in wb: move it over
+#pragma unroll
+                for (int i = 0; i < MPAD / 16; ++i) wa[i] = wb[i];
+                break;
+            }
+            load_block<MPAD>(wa, b + 1 < nb ? base + (int64_t)(b + 1) * BLK_BYTES : after, lane);
+            process(wb, b);
+            if (++b == nb) break;
+        }
+        // ---- the item's result: its best k by (sum desc, position asc), and what they say about the query
+        uint32_t kth = 0;
+        if (cnt > k) kth = wave_prune(buf, cnt, k, lane);
+        else if (cnt == k) {
+            uint32_t r[CAPW / 64];
+#pragma unroll
+            for (int i = 0; i < CAPW / 64; ++i) r[i] = (lane + 64 * i < cnt) ? buf[lane + 64 * i] : 0u;
+            kth = select_kth<CAPW / 64>(r, k);
+        }
+        if (cnt >= k && lane == 0) {          // k entries reach the k-th key's score: a bound on the query's k-th best
+            const int32_t tq = bias + (int32_t)(kth >> 16);
+            if (atomicMax(&sh[2], tq) < tq) publish_bound(P.tauq + q, tq);  // (to HBM only when it is news to this workgroup)
+        }
+        // ---- the bound from the histogram of all the workgroup's candidates of this query: the highest bin edge with
+        // k candidates at or above it (lane L owns bins 16 L .. 16 L + 15)
+        {
+            const int32_t origin = sh[3];
+            if (origin != INT32_MIN) {
+                int tot = 0;
+                for (int i = 0; i < HIST_BINS / 64; ++i) tot += hist[lane * (HIST_BINS / 64) + i];
+                int sfx = tot;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int v = __shfl_down(sfx, o);
+                    if (lane + o < 64) sfx += v;
+                }
+                const uint64_t reach = __ballot(sfx >= k);
+                if (reach) {
+                    const int L = 63 - __builtin_clzll(reach);
+                    if (lane == L) {
+                        // (counts may have grown since the first look: more candidates only make the edge more valid)
+                        int cum = sfx - tot, b = L * (HIST_BINS / 64);
+                        for (int i = HIST_BINS / 64 - 1; i >= 0; --i) {
+                            cum += hist[L * (HIST_BINS / 64) + i];
+                            if (cum >= k) { b = L * (HIST_BINS / 64) + i; break; }
+                        }
+                        const int64_t edge = (int64_t)origin + ((int64_t)b << HIST_SHIFT);
+                        const int32_t tq = (int32_t)min(edge, (int64_t)0x7fffffff);
+                        if (atomicMax(&sh[2], tq) < tq) publish_bound(P.tauq + q, tq);
+                    }
+                }
+            } else if (lane == 0 && sh[2] != INT32_MIN) {
+                atomicCAS(&sh[3], INT32_MIN, sh[2]);       // the histogram starts here
+            }
+        }
+        // entries below the bound can never be in the query's result: only the others go to the item's slot
+        const int32_t tau_now = sh[2];
+        uint32_t k0 = 0, k1 = 0;               // (cnt <= k <= 128: two keys per lane)
+        if (lane < cnt) k0 = buf[lane];
+        if (lane + 64 < cnt) k1 = buf[lane + 64];
+        const bool w0 = lane < cnt && bias + (int32_t)(k0 >> 16) >= tau_now, w1 = lane + 64 < cnt && bias + (int32_t)(k1 >> 16) >= tau_now;
+        const uint64_t m0 = __ballot(w0), m1 = __ballot(w1);
+        const int n0 = __popcll(m0), n1 = __popcll(m1);
+        const int64_t slot = (int64_t)q * W.qslots + d.item;
+        int32_t* oI = P.part_I + slot * k;
+        int64_t* orow = P.part_row + slot * k;
+        if (w0) { const int o = lane_rank(m0); oI[o] = bias + (int32_t)(k0 >> 16); orow[o] = d.row0 + (int64_t)(0xFFFFu - (k0 & 0xFFFFu)); }
+        if (w1) { const int o = n0 + lane_rank(m1); oI[o] = bias + (int32_t)(k1 >> 16); orow[o] = d.row0 + (int64_t)(0xFFFFu - (k1 & 0xFFFFu)); }
+        if (lane == 0) P.part_cnt[slot] = n0 + n1;
+    };
+
+    // chunk c of a pair as an item
+    auto item_of = [&](const PairDesc& pd, int pair, int c, bool valid) {
+        ItemDesc d;
+        d.blk0 = pd.blk0 + (int64_t)c * CH;
+        d.row0 = pd.row0 + (int64_t)c * CH * BLOCK_VECS;
+        d.nb = min(CH, pd.nblk - c * CH);
+        d.cvecs = min(pd.len - c * CH * BLOCK_VECS, d.nb * BLOCK_VECS);
+        d.pair = pair;
+        d.valid = valid;
+        d.item = pd.pre + c;
+        return d;
+    };
+    auto load_pdesc = [&](int64_t pair) {       // (every lane loads the same 32 bytes: one request)
+        const int4* p = reinterpret_cast<const int4*>(W.pdesc + pair);
+        const int4 a = p[0], b = p[1];
+        PairDesc pd;
+        pd.blk0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.y) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.x);
+        pd.row0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.w) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.z);
+        pd.nblk = __builtin_amdgcn_readfirstlane(b.x); pd.len = __builtin_amdgcn_readfirstlane(b.y);
+        pd.pre = __builtin_amdgcn_readfirstlane(b.z); pd.pad = 0;
+        return pd;
+    };
+
+    // first attachment: workgroup b takes query b mod nq, as number b / nq of those that do
+    int q = blockIdx.x % nq;
+    int rank = blockIdx.x / nq;
+    bool first_round = true;
+    for (;;) {
+        __syncthreads();                       // every wave is done with the previous query's table and scalars
+        if (!first_round) {
+            // ---- look for the query with the most work left per attached workgroup
+            if (threadIdx.x == 0) { sh[4] = 0; sh[5] = 0; }     // one 64-bit word: (work left per workgroup + 1) << 32 | query; 0 = none
+            __syncthreads();
+            int best = 0, bq = -1;
+            for (int i = threadIdx.x; i < nq; i += THREADS) {
+                const int left = W.qinfo[i].x - __hip_atomic_load(W.qnext + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (left > 0) {
+                    const int att = __hip_atomic_load(W.qatt + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const int score = left / (att + 1) + 1;
+                    if (score > best) { best = score; bq = i; }
+                }
+            }
+            for (int o = 32; o; o >>= 1) {
+                const int ob = __shfl_xor(best, o), oq = __shfl_xor(bq, o);
+                if (ob > best || (ob == best && oq > bq)) { best = ob; bq = oq; }
+            }
+            if (lane == 0 && bq >= 0) atomicMax(reinterpret_cast<unsigned long long*>(sh + 4), ((unsigned long long)(uint32_t)best << 32) | (uint32_t)bq);
+            __syncthreads();
+            const unsigned long long pick = *reinterpret_cast<const unsigned long long*>(sh + 4);
+            if ((pick >> 32) == 0) break;      // no query has anything left: every wave reads the same word, all leave together
+            q = (int)(uint32_t)pick;
+            rank = -1;
+            __syncthreads();
+        }
+        first_round = false;
+        const int4 qi = W.qinfo[q];
+        const int nunits = __builtin_amdgcn_readfirstlane(qi.x);
+        const bool per_pair = __builtin_amdgcn_readfirstlane(qi.z) != 0;
+        const int namb = per_pair ? 0 : __builtin_amdgcn_readfirstlane(P.T.namb[q]);
+        if (threadIdx.x == 0) {
+            sh[2] = __hip_atomic_load(P.tauq + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            atomicAdd(W.qatt + q, 1);
+            // the first batch comes with the first attachment (the query's counter starts behind those batches)
+            const int b0 = rank >= 0 ? rank * BATCH : 0, b1 = rank >= 0 ? min(b0 + BATCH, nunits) : 0;
+            sh[8] = b0; sh[9] = max(b0, b1);
+            sh[10] = 0; sh[11] = 1;
+            sh[3] = sh[2];                     // (a bound found by others already: the histogram can start at once)
+        }
+        for (int i = threadIdx.x; i < HIST_BINS; i += THREADS) hist[i] = 0;
+        if (!per_pair) {
+            if (loaded_q != q) {               // (a batch of one query, or the same query again: nothing to install)
+                install_table<planes>(P.T.lut_base + (int64_t)q * LUT_BYTES, lut);
+                for (int i = threadIdx.x; i < namb; i += THREADS) s_amb[i] = P.T.amb_addr[(int64_t)q * AMB_MAX + i];
+                for (int i = threadIdx.x; i < nprobe; i += THREADS) s_pre[i] = W.pair_pre[(int64_t)q * nprobe + i];
+                if (threadIdx.x == 0) s_pre[nprobe] = qi.y;
+                __syncthreads();
+                for (int i = threadIdx.x; i < namb; i += THREADS) s_ambv[i] = lut[entry_lds(s_amb[i])];
+            }
+            loaded_q = q;
+            __syncthreads();
+            // ---- the waves' items: the first by rank (first attachment), the others from the query's counter
+            // An item from the workgroup's batch; when the batch is used up, one wave fetches the next from the
+            // query's counter while the others back off (a wave only ever waits for a wave that holds the lock, and
+            // that wave waits for nobody).  INT_MAX = the query has no items left.
+            unsigned long long* s_batch = reinterpret_cast<unsigned long long*>(sh + 8);
+            auto claim = [&]() {
+                for (;;) {
+                    unsigned long long old = 0;
+                    if (lane == 0) old = atomicAdd(s_batch, 1ull);
+                    const uint32_t cur = __builtin_amdgcn_readfirstlane((uint32_t)old), end = __builtin_amdgcn_readfirstlane((uint32_t)(old >> 32));
+                    if (cur < end) return (int)cur;
+                    int state = 0;             // 0: go round again, 1: nothing left
+                    if (lane == 0) {
+                        if (__hip_atomic_load(&sh[11], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) state = 1;
+                        else if (atomicCAS(&sh[10], 0, 1) == 0) {
+                            const unsigned long long now = __hip_atomic_load(s_batch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            if ((uint32_t)now >= (uint32_t)(now >> 32)) {          // still used up: nobody refilled it meanwhile
+                                const int base = atomicAdd(W.qnext + q, BATCH);
+                                if (base >= nunits) __hip_atomic_store(&sh[11], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                                else atomicExch(s_batch, ((unsigned long long)(uint32_t)min(base + BATCH, nunits) << 32) | (uint32_t)base);
+                            }
+                            __hip_atomic_store(&sh[10], 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        } else {
+                            __builtin_amdgcn_s_sleep(8);
+                        }
+                    }
+                    if (__builtin_amdgcn_readfirstlane(state)) return 0x7fffffff;
+                }
+            };
+            auto resolve = [&](int i) {
+                const bool valid = i < nunits;
+                const int ii = valid ? i : nunits - 1;
+                int lo = 0, hi = nprobe;       // pair p with s_pre[p] <= ii < s_pre[p + 1] (pairs without items share a value with their successor)
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_pre[mid] <= ii) lo = mid; else hi = mid;
+                }
+                const int64_t pair = (int64_t)q * nprobe + lo;
+                const PairDesc pd = load_pdesc(pair);
+                return item_of(pd, (int)pair, ii - pd.pre, valid);
+            };
+            if (nunits > 0) {
+                int i_cur = claim();
+                int i_nxt = claim();
+                ItemDesc cur = resolve(i_cur);
+                bool first_loaded = false;
+                while (cur.valid) {
+                    const ItemDesc nxt = resolve(i_nxt);
+                    const int i_nn = claim();
+                    run_item(cur, q, true, namb, nxt.valid ? P.codes + nxt.blk0 * BLK_BYTES : nullptr, first_loaded);
+                    first_loaded = true;
+                    cur = nxt;
+                    i_nxt = i_nn;
+                }
+            }
+        } else {
+            // ---- per-pair tables: the workgroup takes whole pairs, its waves share out the pair's items
+            loaded_q = -1;
+            for (bool first_pair = true;; first_pair = false) {
+                __syncthreads();               // the previous pair's table is no longer read
+                if (threadIdx.x == 0) {
+                    sh[0] = first_pair && rank >= 0 ? rank : atomicAdd(W.qnext + q, 1);
+                    sh[1] = 0;
+                }
+                __syncthreads();
+                const int p = __builtin_amdgcn_readfirstlane(sh[0]);
+                if (p >= nunits) break;
+                const int64_t pair = (int64_t)q * nprobe + p;
+                if (P.lut8sw) install_table<planes>(P.lut8sw + pair * LUT_BYTES, lut);
+                else eval_table(P, (int)pair, q, lut);
+                const PairDesc pd = load_pdesc(pair);
+                const int nchunks = (pd.nblk + CH - 1) / CH;
+                __syncthreads();
+                for (;;) {
+                    int c = 0;
+                    if (lane == 0) c = atomicAdd(&sh[1], 1);
+                    c = __builtin_amdgcn_readfirstlane(c);
+                    if (c >= nchunks) break;
+                    run_item(item_of(pd, (int)pair, c, true), q, false, 0, nullptr, false);
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) atomicSub(W.qatt + q, 1);
     }
 }
 
-// ------------------------------------------------------------------ planning kernels
-// Items of one query: its pairs in probe order, each cut into chunks of CH blocks.  One workgroup per query:
-// counts, an exclusive scan inside the query, and the query's totals for the scan over the queries.
-// qinfo[q] = {items, tasks, item base, task base}; qbytes[q] = {code bytes streamed, algorithmic code bytes}.
-__global__ void __launch_bounds__(256) count_kernel(const int32_t* __restrict__ probes, const int64_t* __restrict__ blk_off,
-                                                    const int64_t* __restrict__ list_off, int nprobe, int CH, int ipt, int m,
-                                                    int32_t* __restrict__ pair_items, int4* __restrict__ qinfo,
-                                                    int64_t* __restrict__ qbytes, int32_t* __restrict__ tauq) {
+// ------------------------------------------------------------------ planning kernel
+// One workgroup per query: the descriptor of every pair, the query-local number of each pair's first item, the
+// query's totals, its counters and its bound.  `nwg` = workgroups of the scan kernel: workgroup b first attaches to
+// query b mod nq, and the r-th of them takes items r * BATCH .. without asking, so the query's counter starts
+// behind those.
+__global__ void __launch_bounds__(256) plan_kernel(const int32_t* __restrict__ probes, const int64_t* __restrict__ blk_off,
+                                                   const int64_t* __restrict__ list_off, int nprobe, int CH, int m, int nq, int nwg,
+                                                   const int32_t* __restrict__ namb, int all_per_pair,
+                                                   PairDesc* __restrict__ pdesc, int32_t* __restrict__ pair_pre, int4* __restrict__ qinfo,
+                                                   int32_t* __restrict__ qnext, int32_t* __restrict__ qatt,
+                                                   int64_t* __restrict__ qbytes, int32_t* __restrict__ tauq, int64_t* __restrict__ counters) {
     __shared__ int s_w[4];
     __shared__ int s_carry;
     __shared__ unsigned long long s_bytes[2];
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) { s_carry = 0; s_bytes[0] = 0; s_bytes[1] = 0; tauq[q] = INT32_MIN; }
+    if (tid == 0) { s_carry = 0; s_bytes[0] = 0; s_bytes[1] = 0; }
+    if (q == 0 && tid < 3) counters[tid] = 0;          // (the scan kernel adds the batch's totals)
     __syncthreads();
     unsigned long long streamed = 0, algo = 0;
     for (int p0 = 0; p0 < nprobe; p0 += 256) {
         const int p = p0 + tid;
         int n = 0;
+        PairDesc pd = {0, 0, 0, 0, 0, 0};
         if (p < nprobe) {
             const int l = probes[(int64_t)q * nprobe + p];
-            const int nblk = (int)(blk_off[l + 1] - blk_off[l]);
-            n = (nblk + CH - 1) / CH;
-            streamed += (unsigned long long)nblk * (BLOCK_VECS * m);
-            algo += (unsigned long long)(list_off[l + 1] - list_off[l]) * m;
+            pd.blk0 = blk_off[l];
+            pd.row0 = list_off[l];
+            pd.nblk = (int)(blk_off[l + 1] - pd.blk0);
+            pd.len = (int)(list_off[l + 1] - pd.row0);
+            n = (pd.nblk + CH - 1) / CH;
+            streamed += (unsigned long long)pd.nblk * (BLOCK_VECS * m);
+            algo += (unsigned long long)pd.len * m;
         }
         int inc = n;
         for (int o = 1; o < 64; o <<= 1) {
@@ -429,7 +637,11 @@ __global__ void __launch_bounds__(256) count_kernel(const int32_t* __restrict__ 
         __syncthreads();
         int before = s_carry;
         for (int w = 0; w < wave; ++w) before += s_w[w];
-        if (p < nprobe) pair_items[(int64_t)q * nprobe + p] = before + inc - n;     // first item of the pair inside its query
+        if (p < nprobe) {
+            pd.pre = before + inc - n;
+            pdesc[(int64_t)q * nprobe + p] = pd;
+            pair_pre[(int64_t)q * nprobe + p] = pd.pre;
+        }
         __syncthreads();
         if (tid == 255) s_carry = before + inc;
         __syncthreads();
@@ -439,75 +651,217 @@ __global__ void __launch_bounds__(256) count_kernel(const int32_t* __restrict__ 
     __syncthreads();
     if (tid == 0) {
         const int items = s_carry;
-        qinfo[q] = make_int4(items, (items + ipt - 1) / ipt, 0, 0);
+        const int per_pair = all_per_pair || namb[q] > AMB_MAX;
+        qinfo[q] = make_int4(per_pair ? nprobe : items, items, per_pair, 0);
+        const int attached = q < nwg ? (nwg - 1 - q) / nq + 1 : 0;
+        qnext[q] = attached * (per_pair ? 1 : BATCH);
+        qatt[q] = 0;
+        tauq[q] = INT32_MIN;
         qbytes[2 * q] = (int64_t)s_bytes[0];
         qbytes[2 * q + 1] = (int64_t)s_bytes[1];
     }
 }
 
-// Exclusive scan over the queries (one workgroup): item and task bases, totals, counters.
-__global__ void __launch_bounds__(1024) bases_kernel(int4* __restrict__ qinfo, const int64_t* __restrict__ qbytes, int nq,
-                                                     int32_t* __restrict__ ctrl, int64_t* __restrict__ counters) {
-    __shared__ int s_wi[16], s_wt[16];
-    __shared__ unsigned long long s_b[2];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) { s_b[0] = 0; s_b[1] = 0; }
-    int carry_i = 0, carry_t = 0;
-    unsigned long long streamed = 0, algo = 0;
-    for (int q0 = 0; q0 < nq; q0 += 1024) {
-        const int q = q0 + tid;
-        int4 r = make_int4(0, 0, 0, 0);
-        if (q < nq) { r = qinfo[q]; streamed += (unsigned long long)qbytes[2 * q]; algo += (unsigned long long)qbytes[2 * q + 1]; }
-        int ii = r.x, it = r.y;
-        for (int o = 1; o < 64; o <<= 1) {
-            const int a = __shfl_up(ii, o), b = __shfl_up(it, o);
-            if (lane >= o) { ii += a; it += b; }
-        }
-        __syncthreads();
-        if (lane == 63) { s_wi[wave] = ii; s_wt[wave] = it; }
-        __syncthreads();
-        int bi = carry_i, bt = carry_t, ti = 0, tt = 0;
-        for (int w = 0; w < 16; ++w) {
-            if (w < wave) { bi += s_wi[w]; bt += s_wt[w]; }
-            ti += s_wi[w]; tt += s_wt[w];
-        }
-        if (q < nq) qinfo[q] = make_int4(r.x, r.y, bi + ii - r.x, bt + it - r.y);
-        carry_i += ti; carry_t += tt;
+// ------------------------------------------------------------------ per-query merge of the items' results
+// Stage 1: workgroup (query, slice) takes the slots of its slice of the query's items, keeps the entries that reach
+// the query's final bound, looks up their ids, sorts by (score desc, id asc) and keeps k.  With one slice per query
+// that is the result; else it goes to the stage arrays and stage 2 (one workgroup per query) merges the slices'.
+struct TopK {
+    int32_t* sI;
+    int64_t* sId;
+    int* s_cnt;
+    int k;
+    // sort the first `have` entries of the buffer, keep k
+    __device__ int sort_keep_k(int have) {
+        int n2 = 1;
+        while (n2 < have) n2 <<= 1;
+        for (int i = have + threadIdx.x; i < n2; i += MERGE_THREADS) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
+        if (n2 > 1) bitonic_sort(sI, sId, n2); else __syncthreads();
+        return min(have, k);
     }
-    for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
-    if (lane == 0) { atomicAdd(&s_b[0], streamed); atomicAdd(&s_b[1], algo); }
+};
+
+__global__ void __launch_bounds__(MERGE_THREADS) merge_slots_kernel(const WaveParams W, const float* __restrict__ delta,
+                                                                    int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
+                                                                    int32_t* __restrict__ out_iscores) {
+    __shared__ int32_t sI[MERGE_CAP];
+    __shared__ int64_t sId[MERGE_CAP];
+    __shared__ int s_cnt;
+    const ScanParams& P = W.S;
+    const int q = blockIdx.x / W.nslice, slice = blockIdx.x % W.nslice, k = P.k;
+    int32_t tau = P.tauq[q];   // k candidates of this query reach tau: nothing below can be in the result
+    const int nitems = W.qinfo[q].y;
+    const int per = (nitems + W.nslice - 1) / W.nslice;
+    const int i0 = slice * per, i1 = min(nitems, i0 + per);
+    const int64_t slot0 = (int64_t)q * W.qslots;
+    TopK T{sI, sId, &s_cnt, k};
+    // Every entry of the slots [a, b): 256 slots at a time, 64 per wave: a lane reads its slot's count, a scan over the
+    // wave turns the counts into offsets, and then the wave's lanes share out ALL entries of its 64 slots evenly (entry
+    // e belongs to the slot whose offset range holds e): a thread per slot would walk up to k entries one after the
+    // other, each a trip to memory.  f(score, position in the result arrays).
+    __shared__ int s_wpre[MERGE_THREADS / 64][64];
+    __shared__ int s_max;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    auto each_entry = [&](int a, int b, auto f) {
+        for (int b0 = a; b0 < b; b0 += MERGE_THREADS) {
+            const int first = b0 + wave * 64, sl = first + lane;
+            const int n = sl < b ? P.part_cnt[slot0 + sl] : 0;
+            int inc = n;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(inc, o);
+                if (lane >= o) inc += v;
+            }
+            const int total = __shfl(inc, 63);
+            s_wpre[wave][lane] = inc - n;
+            __builtin_amdgcn_wave_barrier();       // (a wave's LDS operations complete in order; this only pins the compiler)
+            for (int e = lane; e < total; e += 64) {
+                int lo = 0, hi = 64;               // the last slot whose offset is <= e (empty slots share an offset with their successor)
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_wpre[wave][mid] <= e) lo = mid; else hi = mid;
+                }
+                const int64_t at = (slot0 + first + lo) * k + (e - s_wpre[wave][lo]);
+                f(P.part_I[at], at);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+    // entries that reach tau, appended behind the first base_fill entries of the buffer
+    auto gather = [&](int a, int b, int base_fill) {
+        if (threadIdx.x == 0) s_cnt = base_fill;
+        __syncthreads();
+        each_entry(a, b, [&](int32_t I, int64_t at) {
+            if (I >= tau) {
+                const int o = atomicAdd(&s_cnt, 1);
+                if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[at]]; }
+            }
+        });
+        __syncthreads();
+        return s_cnt;
+    };
+    // The bound the scan leaves is the best k-th score of a single item, which is weak when lists are short and k is
+    // large: most entries then pass it.  If more pass than the buffer holds, a histogram of their scores gives a bound
+    // with at least k entries at or above it that is within one bin of the slice's true k-th score.
+    {
+        if (threadIdx.x == 0) { s_cnt = 0; s_max = 0; }
+        __syncthreads();
+        int c = 0, mx = 0;
+        each_entry(i0, i1, [&](int32_t I, int64_t) {
+            if (I >= tau) { ++c; mx = max(mx, (int)min((int64_t)I - tau, (int64_t)0x7fffffff)); }
+        });
+        for (int o = 32; o; o >>= 1) { c += __shfl_xor(c, o); mx = max(mx, __shfl_xor(mx, o)); }
+        if (lane == 0) { atomicAdd(&s_cnt, c); atomicMax(&s_max, mx); }
+        __syncthreads();
+        const int passing = s_cnt, maxd = s_max;
+        __syncthreads();
+        if (passing > MERGE_CAP) {
+            constexpr int BINS = 1024;
+            int* hist = reinterpret_cast<int*>(sI);                  // (the buffer is not in use yet)
+            int shift = 0;
+            while ((maxd >> shift) >= BINS) ++shift;
+            for (int i = threadIdx.x; i < BINS; i += MERGE_THREADS) hist[i] = 0;
+            __syncthreads();
+            each_entry(i0, i1, [&](int32_t I, int64_t) {
+                if (I >= tau) atomicAdd(&hist[(int)(((int64_t)I - tau) >> shift)], 1);
+            });
+            __syncthreads();
+            // the highest bin with at least k entries in it and above: thread t owns bins 4t .. 4t + 3
+            __shared__ int s_wsum[MERGE_THREADS / 64];
+            __shared__ int s_bin;
+            const int t = threadIdx.x;
+            const int h0 = hist[4 * t], h1 = hist[4 * t + 1], h2 = hist[4 * t + 2], h3 = hist[4 * t + 3];
+            int sfx = h0 + h1 + h2 + h3;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_down(sfx, o);
+                if (lane + o < 64) sfx += v;
+            }
+            if (lane == 0) s_wsum[wave] = sfx;
+            if (t == 0) s_bin = 0;
+            __syncthreads();
+            int above = 0;
+            for (int w = wave + 1; w < MERGE_THREADS / 64; ++w) above += s_wsum[w];
+            const int mine = sfx + above;                            // entries in bins >= 4t
+            const int next = mine - (h0 + h1 + h2 + h3);             // entries in bins >= 4t + 4
+            if (mine >= k && next < k) {                             // exactly one thread
+                int cum = next, bsel = 4 * t;
+                const int hh[4] = {h0, h1, h2, h3};
+                for (int i = 3; i >= 0; --i) {
+                    cum += hh[i];
+                    if (cum >= k) { bsel = 4 * t + i; break; }
+                }
+                s_bin = bsel;
+            }
+            __syncthreads();
+            tau += (int32_t)((int64_t)s_bin << shift);
+            __syncthreads();
+        }
+    }
+    int have = gather(i0, i1, 0);   // optimistic: everything that passes tau fits the buffer (the usual case by far)
+    int fill;
+    if (have <= MERGE_CAP) {
+        fill = T.sort_keep_k(have);
+    } else {
+        const int per_round = max(1, (MERGE_CAP - k) / k);      // slots per round that cannot overflow the buffer
+        fill = 0;
+        for (int a = i0; a < i1; a += per_round) {
+            __syncthreads();
+            have = gather(a, min(i1, a + per_round), fill);
+            fill = T.sort_keep_k(have);
+            if (fill == k && sI[k - 1] > tau) tau = sI[k - 1];
+        }
+    }
     __syncthreads();
-    if (tid == 0) {
-        ctrl[0] = 0; ctrl[1] = carry_t;
-        counters[0] = carry_t; counters[1] = (int64_t)s_b[0]; counters[2] = (int64_t)s_b[1];
+    if (W.nslice > 1) {
+        const int64_t o = ((int64_t)q * W.nslice + slice) * k;
+        for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+            W.stage_I[o + r] = r < fill ? sI[r] : INT32_MIN;
+            W.stage_id[o + r] = r < fill ? sId[r] : -1;
+        }
+        return;
+    }
+    for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+        const bool ok = r < fill;
+        const int32_t I = ok ? sI[r] : INT32_MIN;
+        out_ids[(int64_t)q * k + r] = ok ? sId[r] : -1;
+        if (out_iscores) out_iscores[(int64_t)q * k + r] = I;
+        if (out_scores) out_scores[(int64_t)q * k + r] = ok ? (float)I * (delta ? delta[q] : 1.0f) : -INFINITY;
     }
 }
 
-// The item and task records of one query (one workgroup per query).
-__global__ void __launch_bounds__(256) items_kernel(const int32_t* __restrict__ probes, const int64_t* __restrict__ blk_off,
-                                                    const int64_t* __restrict__ list_off, int nprobe, int CH, int ipt,
-                                                    const int32_t* __restrict__ pair_items, const int4* __restrict__ qinfo,
-                                                    Item* __restrict__ items, int4* __restrict__ tasks) {
-    const int q = blockIdx.x;
-    const int4 qi = qinfo[q];
-    for (int lt = threadIdx.x; lt < qi.y; lt += 256)
-        tasks[qi.w + lt] = make_int4(q, qi.z + lt * ipt, qi.z + min(qi.x, (lt + 1) * ipt), 0);
-    for (int p = threadIdx.x; p < nprobe; p += 256) {
-        const int64_t pair = (int64_t)q * nprobe + p;
-        const int l = probes[pair];
-        const int64_t b0 = blk_off[l], v0 = list_off[l];
-        const int nblk = (int)(blk_off[l + 1] - b0), len = (int)(list_off[l + 1] - v0);
-        Item* out = items + qi.z + pair_items[pair];
-        for (int c = 0; c * CH < nblk; ++c) {
-            Item it;
-            it.blk0 = b0 + (int64_t)c * CH;
-            it.row0 = v0 + (int64_t)c * CH * BLOCK_VECS;
-            it.nb = min(CH, nblk - c * CH);
-            it.cvecs = min(len - c * CH * BLOCK_VECS, it.nb * BLOCK_VECS);
-            it.pair = (int32_t)pair;
-            it.chunk = c;
-            out[c] = it;
+// Stage 2: the slices' results of one query (nslice * k entries, ids already looked up).
+__global__ void __launch_bounds__(MERGE_THREADS) merge_stage2_kernel(const WaveParams W, const float* __restrict__ delta,
+                                                                     int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
+                                                                     int32_t* __restrict__ out_iscores) {
+    __shared__ int32_t sI[MERGE_CAP];
+    __shared__ int64_t sId[MERGE_CAP];
+    __shared__ int s_cnt;
+    const int q = blockIdx.x, k = W.S.k;
+    const int64_t o = (int64_t)q * W.nslice * k;
+    const int n = W.nslice * k;
+    TopK T{sI, sId, &s_cnt, k};
+    int fill = 0;
+    const int per_round = MERGE_CAP - k;                         // entries per round that cannot overflow the buffer
+    for (int a = 0; a < n; a += per_round) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_cnt = fill;
+        __syncthreads();
+        for (int e = a + (int)threadIdx.x; e < min(n, a + per_round); e += MERGE_THREADS) {
+            const int32_t I = W.stage_I[o + e];
+            if (I != INT32_MIN) {
+                const int at = atomicAdd(&s_cnt, 1);
+                sI[at] = I; sId[at] = W.stage_id[o + e];
+            }
         }
+        __syncthreads();
+        fill = T.sort_keep_k(s_cnt);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+        const bool ok = r < fill;
+        const int32_t I = ok ? sI[r] : INT32_MIN;
+        out_ids[(int64_t)q * k + r] = ok ? sId[r] : -1;
+        if (out_iscores) out_iscores[(int64_t)q * k + r] = I;
+        if (out_scores) out_scores[(int64_t)q * k + r] = ok ? (float)I * (delta ? delta[q] : 1.0f) : -INFINITY;
     }
 }
 
@@ -525,11 +879,17 @@ static int launch_one(const WaveParams& W, int grid, hipStream_t st) {
 
 }  // namespace wavescan
 
-// Blocks per item: about three items per resident wave, at least 8 blocks (a wave keeps one block in flight while
-// it works on another, so an item shorter than that is mostly start and end) and at most 512 (position field).
+// Blocks per item: enough items for every resident wave to take many (a wave works through an item alone, so what
+// is left at the end of the kernel is the longest item still running), at most 512 blocks (position field).
+#ifndef RAGO_WV_PERWAVE
+#define RAGO_WV_PERWAVE 4.0
+#endif
+#ifndef RAGO_WV_MINCH
+#define RAGO_WV_MINCH 8
+#endif
 int wave_chunk_len(double total_blocks, int n_cu) {
-    const double want = 3.0 * 2 * wavescan::WAVES * n_cu;
-    int c = 8;
+    const double want = RAGO_WV_PERWAVE * 2 * wavescan::WAVES * n_cu;
+    int c = RAGO_WV_MINCH;
     while (c < 512 && total_blocks / c > want) c <<= 1;
 #ifdef RAGO_WV_CH
     c = RAGO_WV_CH;
@@ -537,39 +897,61 @@ int wave_chunk_len(double total_blocks, int n_cu) {
     return c;
 }
 
-size_t wave_item_bytes() { return sizeof(wavescan::Item); }
+size_t wave_pair_bytes() { return sizeof(wavescan::PairDesc); }
 
-// Plans the items and tasks on the device (three small kernels), then runs the scan.  P.CH / P.maxchunks are the
-// blocks per item and the most items any pair can have; items / tasks / pair_items / qinfo / qbytes are workspace.
-int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* items, int4* tasks, int32_t* pair_items,
-                     int4* qinfo, int64_t* qbytes, int64_t* counters, hipEvent_t ev_scan, hipStream_t st) {
+// Slices of a query's item slots in the first merge stage: one per ~256 items (one round of its workgroup), at most 32.
+constexpr int MAX_SLICES = 32;
+int wave_merge_slices(double items_per_query) {
+    int r = 1;
+    while (r < MAX_SLICES && items_per_query / r > 256.0) r <<= 1;
+    return r;
+}
+size_t wave_stage_bytes(int64_t nq, int k) { return (size_t)nq * MAX_SLICES * k * 12; }
+
+// Plans on the device (one small kernel), scans, merges the items' results.  P.CH / P.maxchunks are the blocks per
+// item and the most items any pair can have; pdesc [npairs], pair_pre [npairs], qwork [nq * 12 ints], stage
+// [wave_stage_bytes] are workspace; P.part_* hold the items' results (nprobe * maxchunks slots per query).
+int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* pdesc, int32_t* pair_pre, int32_t* qwork,
+                     void* stage, int64_t* counters, const float* delta, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
+                     hipEvent_t* ev, hipStream_t st) {
     using namespace wavescan;
     const int grid = 2 * n_cu;
-    // items per task: about two tasks per workgroup, one item per wave at least
-    const double est_items = std::max(1.0, (double)nq * P.nprobe * std::max(1.0, avgblk / P.CH));
-    int ipt = 8;
-    while (ipt < 256 && est_items / ipt > 2.0 * grid) ipt <<= 1;
-#ifdef RAGO_WV_IPT
-    ipt = RAGO_WV_IPT;
-#endif
-    count_kernel<<<(unsigned)nq, 256, 0, st>>>(P.probes, P.blk_off, P.list_off, P.nprobe, P.CH, ipt, P.m, pair_items, qinfo, qbytes, P.tauq);
-    bases_kernel<<<1, 1024, 0, st>>>(qinfo, qbytes, (int)nq, P.ctrl, counters);
-    items_kernel<<<(unsigned)nq, 256, 0, st>>>(P.probes, P.blk_off, P.list_off, P.nprobe, P.CH, ipt, pair_items, qinfo,
-                                               static_cast<Item*>(items), tasks);
-    RAGO_HIP(hipGetLastError());
-    if (ev_scan) RAGO_HIP(hipEventRecord(ev_scan, st));
     WaveParams W;
     W.S = P;
-    W.items = static_cast<const Item*>(items);
-    W.tasks = tasks;
+    W.pdesc = static_cast<const PairDesc*>(pdesc);
+    W.pair_pre = pair_pre;
+    int4* qinfo = reinterpret_cast<int4*>(qwork);
+    W.qinfo = qinfo;
+    W.qnext = qwork + 4 * nq;
+    W.qatt = qwork + 5 * nq;
+    int64_t* qbytes = reinterpret_cast<int64_t*>(qwork + 8 * nq);
+    W.qbytes = qbytes;
+    W.counters = counters;
+    W.nq = (int)nq;
+    W.qslots = (int64_t)P.nprobe * P.maxchunks;
+    W.nslice = wave_merge_slices((double)P.nprobe * std::max(1.0, avgblk / P.CH));
+    W.stage_id = static_cast<int64_t*>(stage);
+    W.stage_I = reinterpret_cast<int32_t*>(W.stage_id + nq * MAX_SLICES * P.k);
+    plan_kernel<<<(unsigned)nq, 256, 0, st>>>(P.probes, P.blk_off, P.list_off, P.nprobe, P.CH, P.m, (int)nq, grid, P.T.namb, P.lut8sw != nullptr,
+                                              static_cast<PairDesc*>(pdesc), pair_pre, qinfo, W.qnext, W.qatt, qbytes, P.tauq, counters);
+    RAGO_HIP(hipGetLastError());
+    if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
+    int rc;
     switch (P.m) {
-        case 16: return launch_one<16>(W, grid, st);
-        case 32: return launch_one<32>(W, grid, st);
-        case 64: return launch_one<64>(W, grid, st);
-        case 96: return launch_one<96>(W, grid, st);
-        case 128: return launch_one<128>(W, grid, st);
+        case 16: rc = launch_one<16>(W, grid, st); break;
+        case 32: rc = launch_one<32>(W, grid, st); break;
+        case 64: rc = launch_one<64>(W, grid, st); break;
+        case 96: rc = launch_one<96>(W, grid, st); break;
+        case 128: rc = launch_one<128>(W, grid, st); break;
         default: return fail(RAGO_UNSUPPORTED, "code width");
     }
+    if (rc) return rc;
+    if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
+    merge_slots_kernel<<<(unsigned)(nq * W.nslice), MERGE_THREADS, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
+    if (W.nslice > 1) merge_stage2_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
+    RAGO_HIP(hipGetLastError());
+    if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
+    return RAGO_OK;
 }
 
 }  // namespace rago
