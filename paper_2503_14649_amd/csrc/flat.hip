@@ -164,39 +164,71 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
         *reinterpret_cast<uint4*>(qs + qrow * QS + c * 16) = v;
     }
     for (int idx = tid; idx < 16 * FLAT_BINS; idx += FLAT_THREADS) hist[idx] = 0;
-    if (tid < 16) { cnt[tid] = 0; tbin[tid] = 0; }
+    // A slab that starts after others of its request have made progress takes over the bin they have reached.
+    if (tid < 16) {
+        cnt[tid] = 0;
+        tbin[tid] = tid < P.nqr ? __hip_atomic_load(P.shared_tbin + r * 16 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    }
     __syncthreads();
 
     const uint16_t* X = P.corpus + (int64_t)r * P.n * D;
     const float never = __builtin_huge_valf();
-    float thrx = i16 < P.nqr ? -never : never;   // this lane's query: threshold bin as a float, -inf while it is bin 0
+    float thrx = i16 < P.nqr ? (tbin[i16] > 0 ? (float)tbin[i16] : -never) : never;   // this lane's query: threshold bin as a float, -inf while it is bin 0
     int nstage = 0;                              // candidates in this wave's staging area (wave-uniform)
     int64_t round_base = row0;                   // first row of the current round
     uint4 a[2 * NP];
     // loads are unconditional (row clamped into the corpus): a conditional prefetch would make the
     // compiler wait for every outstanding load before each use
+    // Load layout: lane l fetches 16 bytes of row l / 8 at byte (l % 8) * 16 of a 128-byte segment, so one load
+    // instruction asks for whole 128-byte lines of 8 rows, and two instructions (rows 0..7 -> A, rows 8..15 -> B) cover
+    // a segment of the block.  Whole lines in one instruction let the loads be non-temporal (a line is used once and
+    // not kept), which is what a plain read stream needs to reach its best rate; and the address unit looks up 8
+    // cache tags per instruction.  (In the matrix unit's own operand layout, row = lane % 16, the four lanes the
+    // address unit handles together belong to four different rows and every instruction costs 64 tag lookups:
+    // counters showed the address unit stalled behind the cache for 80 % of the kernel, and non-temporal loads,
+    // each touching half a line, measured 8 % slower than ordinary ones.)
+    // The matrix unit wants lane (i16, g) to hold bytes g * 16 .. + 16 of one 64-byte half of row i16's segment.
+    // For the first half these sit in A's lanes with l % 8 < 4 (rows 0..7) and in B's (rows 8..15).  One DPP move
+    // folds both into one register: A's value stays in the lanes that loaded the first half, B's first-half values
+    // shift by four lanes into the lanes that loaded the second half; one lane permutation through the LDS crossbar
+    // (no LDS memory) then puts every value into its operand lane.  The second half mirrors this.
+    const int lrow = lane >> 3, lc = lane & 7;
+    const bool upper = i16 >= 8;
+    const int take0 = ((i16 & 7) * 8 + g + (upper ? 4 : 0)) << 2, take1 = ((i16 & 7) * 8 + g + (upper ? 0 : 4)) << 2;
+    // loads are unconditional (rows clamped into the corpus): a conditional prefetch would make the
+    // compiler wait for every outstanding load before each use
     auto load_rows = [&](uint4 (&dst)[2 * NP], int64_t rb) {   // rb = first row of a 16-row block
-        const int64_t row = max((int64_t)0, min(rb + i16, P.n - 1));
-        f_global_ptr p = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + row * D + g * 8));
+        const int64_t rowa = max((int64_t)0, min(rb + lrow, P.n - 1));
+        const int64_t rowb = max((int64_t)0, min(rb + 8 + lrow, P.n - 1));
+        f_global_ptr pa = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + rowa * D + lc * 8));
+        f_global_ptr pb = (f_global_ptr)(reinterpret_cast<const f_u32x4*>(X + rowb * D + lc * 8));
 #pragma unroll
         for (int sp = 0; sp < NP; ++sp) {
-            // (ordinary loads: each of the two touches one half of the same 128-byte lines, and non-temporal
-            // loads, which do not keep a line, measured 8 % slower here)
-            const f_u32x4 v0 = p[sp * 8], v1 = p[sp * 8 + 4];
+            const f_u32x4 v0 = __builtin_nontemporal_load(pa + sp * 8), v1 = __builtin_nontemporal_load(pb + sp * 8);
             dst[2 * sp] = make_uint4(v0.x, v0.y, v0.z, v0.w);
             dst[2 * sp + 1] = make_uint4(v1.x, v1.y, v1.z, v1.w);
         }
     };
-    auto multiply = [&](const uint4 (&src)[2 * NP], int64_t rb) {
+    auto first_half = [&](uint32_t a, uint32_t b) {      // row_shr:4 into lanes 4..7 and 12..15 of every 16
+        return (uint32_t)__builtin_amdgcn_ds_bpermute(take0, __builtin_amdgcn_update_dpp((int)a, (int)b, 0x114, 0xF, 0xA, false));
+    };
+    auto second_half = [&](uint32_t a, uint32_t b) {     // row_shl:4 into lanes 0..3 and 8..11 of every 16
+        return (uint32_t)__builtin_amdgcn_ds_bpermute(take1, __builtin_amdgcn_update_dpp((int)a, (int)b, 0x104, 0xF, 0x5, false));
+    };
+    auto multiply = [&](const uint4 (&src)[2 * NP]) {
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         const uint8_t* qrow = qs + i16 * QS + g * 16;
 #pragma unroll
         for (int sp = 0; sp < NP; ++sp) {
             const uint4 b0 = *reinterpret_cast<const uint4*>(qrow + sp * 128);
             const uint4 b1 = *reinterpret_cast<const uint4*>(qrow + sp * 128 + 64);
-            acc = mma16<HALF>(src[2 * sp], b0, acc);
-            acc = mma16<HALF>(src[2 * sp + 1], b1, acc);
+            const uint4 &A = src[2 * sp], &B = src[2 * sp + 1];
+            acc = mma16<HALF>(make_uint4(first_half(A.x, B.x), first_half(A.y, B.y), first_half(A.z, B.z), first_half(A.w, B.w)), b0, acc);
+            acc = mma16<HALF>(make_uint4(second_half(A.x, B.x), second_half(A.y, B.y), second_half(A.z, B.z), second_half(A.w, B.w)), b1, acc);
         }
+        return acc;
+    };
+    auto select = [&](const v4f acc, int64_t rb) {
         // acc[e] = score of row rb + 4*g + e with query i16.  A score is a candidate when its bin is not
         // below the query's threshold bin, i.e. (for a threshold >= 1) when x = (s + 1) * 128 >= threshold:
         // the same x the bin is the integer part of.  Candidates are rare once the thresholds have risen,
@@ -241,7 +273,8 @@ __global__ void __launch_bounds__(FLAT_THREADS, 2) flat_scan_kernel(const FlatPa
             const int64_t r0 = round0 + ((int64_t)wave * FLAT_RB + bb) * 16;
             const int64_t rn = bb + 1 < FLAT_RB ? r0 + 16 : round0 + FLAT_ROUND_ROWS + (int64_t)wave * FLAT_RB * 16;   // or the first of the next round
             if (nstage > FLAT_STAGE - 256) flush();      // a block adds up to 256 candidates while nothing is filtered
-            if (r0 < row1) multiply(a, r0);
+            const v4f acc = multiply(a);
+            if (r0 < row1) select(acc, r0);
             load_rows(a, rn);
         }
         if (nstage) flush();
