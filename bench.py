@@ -254,7 +254,8 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
     nprobe, k = synth.ITER_NPROBE, synth.ITER_K
     g = torch.Generator(device="cuda").manual_seed(cfg.seed * 10 + 9)
     res = {}
-    for b in synth.ITER_BATCHES:
+    batches = tuple(int(x) for x in args.iter_batches.split(",")) if args.iter_batches else synth.ITER_BATCHES
+    for b in batches:
         lat = []
         out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
                torch.empty(b, k, dtype=torch.int32, device="cuda"))
@@ -316,7 +317,7 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
             f"{int(sizes.min())}/{int(sizes.median())}/{int(sizes.max())}; keeping {nsp} groups per query")
         tree = {"nsuper": nsuper, "nsp": nsp, "group_size_min_med_max": [int(sizes.min()), int(sizes.median()), int(sizes.max())],
                 "per_batch": {}}
-        for b in synth.ITER_BATCHES:
+        for b in batches:
             out = (torch.empty(b, k, dtype=torch.int64, device="cuda"), torch.empty(b, k, dtype=torch.float32, device="cuda"),
                    torch.empty(b, k, dtype=torch.int32, device="cuda"))
             lat, agree = [], []
@@ -343,8 +344,8 @@ def run_iter(args, rb, h, Q, cfg, cpu, cen_dev):
                                          "topk_overlap_with_exhaustive_coarse_round0": agree[0],
                                          "topk_overlap_with_exhaustive_coarse_all_rounds": float(np.mean(agree))}
         rb.rago_index_set_upper_probe(h, 0)
-    rec = {"metric": "ivfpq_iterative_round_latency", "value": res["1"]["round_ms_median"], "unit": "ms", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["1"]["round_ms_median"], "higher_is_better": False,
+    rec = {"metric": "ivfpq_iterative_round_latency", "value": res[str(batches[0])]["round_ms_median"], "unit": "ms", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": res[str(batches[0])]["round_ms_median"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
            "config": {"workload": f"iterative on {cfg.name}: n={cfg.n} nlist={cfg.nlist} nprobe={nprobe} k={k} rounds=8 "
                                   f"batches=1/4/16 drift_sigma={synth.ITER_DRIFT}", "scale": args.scale,
@@ -428,6 +429,7 @@ def main():
                     help="also run the library's plain copy kernel over this many GiB (profiling yardstick)")
     ap.add_argument("--cpu-queries", type=int, default=64, help="queries in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--upper", default="", help="iter workload: also run with an upper level over the lists, 'groups,kept' (e.g. 256,8)")
+    ap.add_argument("--iter-batches", default="", help="iter workload: batch sizes to run, e.g. '1' or '1,16' (default 1,4,16; profiling runs)")
     ap.add_argument("--flat-format", default="bf16", choices=["bf16", "f16"], help="flat workload: number format of the embeddings")
     ap.add_argument("--ksub", type=int, default=256, choices=[256, 16],
                     help="codewords per sub-quantiser; 16 = 4-bit codes, two sub-quantisers per code byte")

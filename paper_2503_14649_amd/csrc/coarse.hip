@@ -611,6 +611,236 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     }
 }
 
+// ------------------------------------------------------------------ selection, few queries
+// One workgroup per query leaves the chip idle when a batch has a handful of queries, and its time is then the
+// latency of a request (iterative retrieval, Section 5.3: batches of 1 to 16).  Here SS_G workgroups share a query.
+// Each of them finds the same candidate set by itself (the row of scores comes from L2; a histogram over a linear
+// map of the row's range finds the cut in one pass; the scores in and above the cut's bin are ordered exactly by
+// their fp32 keys), then the exact scores of the candidates - random rows of C from HBM, the expensive step on one
+// compute unit - are divided among the workgroups, and the one that finishes last orders the exact scores and
+// writes the probes.  A row this scheme cannot handle (not-a-number or infinite scores, no spread, more than
+// SS_CAP scores in and above the cut's bin) is queued for the exact second launch of select_kernel.
+constexpr int SS_G = 16;            // workgroups per query
+constexpr int SS_BINS = 4096;
+constexpr int SS_CAP = 1024;        // scores in and above the cut's bin that are ordered in LDS
+constexpr int SS_REG = 64;          // scores per thread: nlist <= 65536
+constexpr int SS_MAX_NQ = 32;
+constexpr int SS_MAX_WANT = 512;    // nprobe + SEL_EXTRA
+constexpr int SS_RU = 2;            // rows of C a wave scores at a time
+
+struct SelectSmallScratch {         // in HBM, per index; `done` is zero between launches (the last workgroup resets it)
+    float exact[SS_MAX_NQ][SS_MAX_WANT];
+    int done[SS_MAX_NQ];
+};
+
+// rank[c] = number of keys above key[c] (keys distinct), counted by n threads or by several groups of n threads
+__device__ __forceinline__ void rank_keys(const uint64_t* key, int n, int* rank, int tid) {
+    for (int i = tid; i < n; i += SEL_THREADS) rank[i] = 0;
+    __syncthreads();
+    const int G = SEL_THREADS / n;              // n <= SEL_THREADS
+    const int c = tid % n, gg = tid / n;
+    if (gg < G) {
+        const uint64_t mine = key[c];
+        int above = 0;
+#pragma unroll 8
+        for (int j = gg; j < n; j += G) above += key[j] > mine ? 1 : 0;      // (independent LDS reads, several in flight)
+        if (above) atomicAdd(&rank[c], above);
+    }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* __restrict__ Q, const float* __restrict__ C,
+                                                                   const float* __restrict__ S, int nlist, int d, int nprobe,
+                                                                   float max_cnorm, int metric, int32_t* __restrict__ probes,
+                                                                   int64_t* counters, int32_t* redo_q, SelectSmallScratch* scratch) {
+    __shared__ int hist[SS_BINS];
+    __shared__ uint64_t c_key[SS_CAP];          // (ordered score bits << 32) | ~list: descending = (score desc, list asc)
+    __shared__ int rank[SS_CAP];
+    __shared__ uint64_t sel_key[SS_MAX_WANT];   // the chosen candidates in descending key order
+    __shared__ float s_red[2 * SEL_WAVES];
+    __shared__ int s_wtot[SEL_WAVES];
+    __shared__ int s_bin, s_ncand, s_cnt, s_last;
+    const int q = blockIdx.y, g = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* row = S + (int64_t)q * nlist;
+    const int want = nprobe + SEL_EXTRA;        // < nlist and <= SS_MAX_WANT (the launcher's conditions)
+    if (tid == 0) s_cnt = 0;
+
+    // ---- the row, its range
+    // (unconditional loads from a clamped index: a branch per element would make every load wait for the one before)
+    float v[SS_REG];
+    float lo = INFINITY, hi = -INFINITY;
+    bool odd = false;
+#pragma unroll
+    for (int r = 0; r < SS_REG; ++r) v[r] = row[min(r * SEL_THREADS + tid, nlist - 1)];
+#pragma unroll
+    for (int r = 0; r < SS_REG; ++r) {          // (a repeated last element changes neither the range nor `odd`)
+        lo = fminf(lo, v[r]); hi = fmaxf(hi, v[r]);
+        odd |= !(fabsf(v[r]) <= 3.0e38f);       // not a number, or infinite
+    }
+    for (int o = 32; o; o >>= 1) { lo = fminf(lo, __shfl_xor(lo, o)); hi = fmaxf(hi, __shfl_xor(hi, o)); }
+    if (lane == 0) { s_red[wave] = lo; s_red[SEL_WAVES + wave] = hi; }
+    for (int i = tid; i < SS_BINS; i += SEL_THREADS) hist[i] = 0;
+    const int any_odd = __syncthreads_or(odd ? 1 : 0);
+    for (int w = 0; w < SEL_WAVES; ++w) { lo = fminf(lo, s_red[w]); hi = fmaxf(hi, s_red[SEL_WAVES + w]); }
+    const float scale = (float)SS_BINS / (hi - lo);
+    // (every workgroup of the query takes the same decisions: they depend on the row only)
+    // (a row whose scores all lie within 2^-9 of their magnitude goes to the exact launch: the bins would be as
+    // narrow as the rounding errors of the map)
+    bool give_up = any_odd || !(hi > lo) || !(scale <= 3.0e38f) || !((hi - lo) * 512.f > fmaxf(fabsf(lo), fabsf(hi)));
+    // monotone in the score: subtraction, multiplication by a positive number and truncation all are
+    auto bin_of = [&](float x) { return (int)fminf(fmaxf((x - lo) * scale, 0.f), (float)(SS_BINS - 1)); };
+    if (!give_up) {
+#pragma unroll
+        for (int r = 0; r < SS_REG; ++r)
+            if (r * SEL_THREADS + tid < nlist) atomicAdd(&hist[bin_of(v[r])], 1);
+    }
+    __syncthreads();
+    // ---- the highest bin b with at least `want` scores in bins >= b: thread t owns bins 4t .. 4t+3
+    {
+        const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+        const int own = h0 + h1 + h2 + h3;
+        int sfx = own;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_down(sfx, o);
+            if (lane + o < 64) sfx += t;
+        }
+        if (lane == 0) s_wtot[wave] = sfx;
+        __syncthreads();
+        int above = 0;
+        for (int w = wave + 1; w < SEL_WAVES; ++w) above += s_wtot[w];
+        const int incl = sfx + above, excl = incl - own;          // scores in bins >= 4t, in bins > 4t+3
+        if (!give_up && incl >= want && excl < want) {            // exactly one thread (nlist > want)
+            int cum = excl, b = 4 * tid + 3;
+            const int hh[4] = {h0, h1, h2, h3};
+            for (;; --b) {
+                cum += hh[b - 4 * tid];
+                if (cum >= want || b == 4 * tid) break;
+            }
+            s_bin = b; s_ncand = cum;
+        }
+        __syncthreads();
+    }
+    if (give_up || s_ncand > SS_CAP - 64) {
+        if (g == 0 && tid == 0) redo_q[atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull)] = q;
+        return;
+    }
+    // ---- the candidates: every score whose bin is at least the cut's lies above `floor_v`, one bin width below the
+    // cut's lower edge (a bin width is at least 8 times the rounding errors of the map and of `floor_v`: the range is
+    // more than 2^-9 of the magnitudes, a bin 2^-12 of the range, an error 2^-24 of the magnitudes), and one
+    // comparison per score is cheaper than the map; the few extra scores between the two are ordered like the rest.  They are ordered
+    // by their exact 64-bit keys, the first `want` are chosen.
+    const float floor_v = lo + (float)(s_bin - 1) / scale;
+#pragma unroll
+    for (int r = 0; r < SS_REG; ++r) {
+        const int i = r * SEL_THREADS + tid;
+        const bool in = i < nlist && v[r] >= floor_v;
+        const uint64_t m = __ballot(in);
+        if (m) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_cnt, __popcll(m));
+            base = __builtin_amdgcn_readfirstlane(base);
+            const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+            if (in && pos < SS_CAP) c_key[pos] = ((uint64_t)float_key(v[r]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
+        }
+    }
+    __syncthreads();
+    const int ncand = s_cnt;
+    if (ncand > SS_CAP) {                       // (the same in every workgroup of the query)
+        if (g == 0 && tid == 0) redo_q[atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull)] = q;
+        return;
+    }
+    rank_keys(c_key, ncand, rank, tid);
+    if (tid < ncand && rank[tid] < want) sel_key[rank[tid]] = c_key[tid];
+    __syncthreads();
+
+    // ---- exact scores (fp64 accumulation, one rounding to fp32) of this workgroup's share: ranks g, g + SS_G, ...
+    const float* qv = Q + (int64_t)q * d;
+    const bool vec4 = (d & 3) == 0;
+    const int nmine = (want - g + SS_G - 1) / SS_G;
+    for (int c0 = wave * SS_RU; c0 < nmine; c0 += SEL_WAVES * SS_RU) {
+        double acc[SS_RU];
+        const float* cv[SS_RU];
+#pragma unroll
+        for (int u = 0; u < SS_RU; ++u) {
+            acc[u] = 0.0;
+            const int pos = g + min(c0 + u, nmine - 1) * SS_G;
+            cv[u] = C + (int64_t)(0xFFFFFFFFu - (uint32_t)sel_key[pos]) * d;
+        }
+        if (vec4) {
+            for (int t = lane * 4; t < d; t += 256) {
+                const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
+                float4 c4[SS_RU];
+#pragma unroll
+                for (int u = 0; u < SS_RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
+                const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
+#pragma unroll
+                for (int u = 0; u < SS_RU; ++u) {
+                    const double ca[4] = {(double)c4[u].x, (double)c4[u].y, (double)c4[u].z, (double)c4[u].w};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        if (metric == 1) { const double diff = qa[x] - ca[x]; acc[u] = acc[u] + diff * diff; }
+                        else acc[u] = acc[u] + qa[x] * ca[x];
+                    }
+                }
+            }
+        } else {
+            for (int t = lane; t < d; t += 64) {
+                const double qt = (double)qv[t];
+#pragma unroll
+                for (int u = 0; u < SS_RU; ++u) {
+                    if (metric == 1) { const double diff = qt - (double)cv[u][t]; acc[u] = acc[u] + diff * diff; }
+                    else acc[u] = acc[u] + qt * (double)cv[u][t];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SS_RU; ++u) {
+            for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
+            if (lane == 0 && c0 + u < nmine)
+                __hip_atomic_store(&scratch->exact[q][g + (c0 + u) * SS_G], metric == 1 ? (float)(-acc[u]) : (float)acc[u],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    // ---- the workgroup that finishes last goes on.  The exact scores were written by device-scope atomic stores, which
+    // go through to where every compute unit's device-scope loads read them; once they are acknowledged (the wait)
+    // the count may be raised.  (A release fence would also write back every dirty line of this chiplet's L2 -
+    // here the whole score matrix the kernel before has just written - and was measured at 4 to 55 us.)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) s_last = atomicAdd(&scratch->done[q], 1) == SS_G - 1;
+    __syncthreads();
+    if (!s_last) return;
+    // ---- order by (exact score desc, list asc); c_key and rank are free again
+    if (tid < want) {
+        const float ex = __hip_atomic_load(&scratch->exact[q][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        c_key[tid] = ((uint64_t)float_key(ex + 0.0f) << 32) /* (-0 counts as +0) */ | (uint32_t)sel_key[tid];
+    }
+    __syncthreads();
+    rank_keys(c_key, want, rank, tid);
+    if (tid < want && rank[tid] < nprobe) probes[(int64_t)q * nprobe + rank[tid]] = (int32_t)(0xFFFFFFFFu - (uint32_t)c_key[tid]);
+    if (tid < want && rank[tid] == nprobe - 1) hist[0] = (int)(c_key[tid] >> 32);     // key of the nprobe-th exact score
+    float qn = 0.f;
+    if (wave == 0) {
+        for (int t = lane; t < d; t += 64) qn += qv[t] * qv[t];
+        for (int o = 32; o; o >>= 1) qn += __shfl_xor(qn, o);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        scratch->done[q] = 0;
+        auto unkey = [](uint32_t kk) { return __uint_as_float((kk & 0x80000000u) ? (kk & 0x7fffffffu) : ~kk); };
+        const float s_cut = unkey((uint32_t)(sel_key[want - 1] >> 32));   // smallest fp32 score among the candidates
+        const float nth = unkey((uint32_t)hist[0]);
+        // (the same bound and the same rule as in select_kernel)
+        float E = ((float)d * 2.384185791015625e-07f + 1.52587890625e-05f) * sqrtf(qn) * max_cnorm;
+        if (metric == 1) E = 2.0f * E + 4.76837158203125e-07f * (qn + max_cnorm * max_cnorm);
+        E += (float)d * 2.4e-38f;
+        if (!(nth > s_cut + E))
+            redo_q[atomicAdd(reinterpret_cast<unsigned long long*>(counters + 3), 1ull)] = q;
+    }
+}
+
 __global__ void zero_counter_kernel(int64_t* counters) { counters[3] = 0; }
 
 int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int nprobe, int32_t* probes, hipStream_t st, bool counter_is_zero) {
@@ -620,6 +850,10 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
     int rc;
     if ((rc = idx->ws.counters.reserve(64))) return rc;
     if ((rc = idx->ws.sel_redo.reserve((size_t)nq * 4))) return rc;
+    if (!idx->ws.sel_small.p) {      // (whatever the batch: a later, smaller batch must not have to allocate)
+        if ((rc = idx->ws.sel_small.reserve(sizeof(SelectSmallScratch)))) return rc;
+        RAGO_HIP(hipMemset(idx->ws.sel_small.p, 0, sizeof(SelectSmallScratch)));     // the `done` words start at zero
+    }
     if (idx->reserving) return RAGO_OK;
     if (!counter_is_zero) zero_counter_kernel<<<1, 1, 0, st>>>(idx->ws.counters.as<int64_t>());
     int64_t* cnt = idx->ws.counters.as<int64_t>();
@@ -627,8 +861,12 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
     const int nl = idx->nlist;
     // first the whole batch on the approximate scores, then (second launch, whose workgroups leave at once when
     // the first queued nothing) the queued queries on exact ones
+    const bool small = nq <= SS_MAX_NQ && nl <= SS_REG * SEL_THREADS && nprobe + SEL_EXTRA < nl && nprobe + SEL_EXTRA <= SS_MAX_WANT;
     for (int redo = 0; redo < 2; ++redo) {
-        if (nl <= 8 * SEL_THREADS)
+        if (small && !redo)
+            select_small_kernel<<<dim3(SS_G, (unsigned)nq), SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric,
+                                                                                  probes, cnt, rq, idx->ws.sel_small.as<SelectSmallScratch>());
+        else if (nl <= 8 * SEL_THREADS)
             select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
         else if (nl <= 32 * SEL_THREADS)
             select_kernel<32><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);

@@ -245,6 +245,49 @@ def test_select_with_massive_ties(rb, scan_kernel):
     rb.rago_index_free(h)
 
 
+@pytest.mark.parametrize("nlist,d", [(700, 48), (20000, 32), (65536, 32)])
+def test_select_for_few_queries(rb, nlist, d):
+    """Batches of up to 32 queries share each query among several workgroups (one histogram pass over a linear map
+    of the row's range, exact scores divided among the workgroups); 33 queries take the one-workgroup-per-query
+    kernel.  Both must give the oracle's probes, also when one outlying score squeezes all others into a few
+    histogram bins (the row is then handed to the exact second launch)."""
+    g = np.random.default_rng(nlist)
+    C = (g.standard_normal((nlist, d)) * 0.3).astype(np.float32)
+    ix = dict(to_np(synth.random_index(n=2 * nlist, d=d, m=16, nlist=nlist, seed=9)))
+    ix["centroids"] = C
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        for nq in (1, 7, 32, 33):
+            Q = _queries(nq, d, 100 + nq)
+            S = oracle.coarse(Q, C)
+            Qd = torch.from_numpy(Q).cuda()
+            gS = rb.rago_debug_coarse(h, Qd)
+            for nprobe in (1, 64, 256, 480):
+                if nprobe >= nlist:
+                    continue
+                gp = rb.rago_debug_select(h, Qd, gS, nprobe).cpu().numpy()
+                assert np.array_equal(gp, oracle.select(S, nprobe)), (nq, nprobe)
+                assert rb.rago_debug_counters(h)[3] == 0, (nq, nprobe)
+        # an outlier: list 5 scores a thousand times higher than the rest
+        C2 = C.copy()
+        C2[5] = 1000.0 * np.sign(_queries(3, d, 7)[0])
+        ix["centroids"] = C2
+        h2 = rb.rago_index_wrap(dev_index(ix))
+        try:
+            Q = _queries(3, d, 7)
+            S = oracle.coarse(Q, C2)
+            Qd = torch.from_numpy(Q).cuda()
+            gS = rb.rago_debug_coarse(h2, Qd)
+            gp = rb.rago_debug_select(h2, Qd, gS, 64).cpu().numpy()
+            assert np.array_equal(gp, oracle.select(S, 64))
+            if nlist > 20000:
+                assert rb.rago_debug_counters(h2)[3] > 0     # too many scores share the cut's bin: the exact launch ran
+        finally:
+            rb.rago_index_free(h2)
+    finally:
+        rb.rago_index_free(h)
+
+
 @pytest.mark.parametrize("metric", ["ip", "l2"])
 @pytest.mark.parametrize("nlist", [300, 9000])
 def test_select_with_scores_packed_inside_the_rounding_error(rb, metric, nlist):
