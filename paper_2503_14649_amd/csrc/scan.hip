@@ -814,19 +814,180 @@ __global__ void __launch_bounds__(256) task_table_kernel(const int32_t* __restri
     table[t] = make_int4(touched[lo], chunk, pair_off[lo] + first, per + (grp < extra ? 1 : 0));
 }
 
+// All of the above in one workgroup, for batches of at most SSU_PAIRS pairs (iterative retrieval, Section 5.3: a few
+// queries per round, where six dependent launches cost more than the work in them).  The lists are found through
+// a hash table in LDS instead of arrays over all nlist lists, so nothing of size nlist is cleared or read.
+// Touched lists are numbered in hash-table order; the order of a list's pairs is whatever order their atomics
+// arrive in, as above.
+constexpr int SSU_PAIRS = 4096, SSU_HASH = 8192, SSU_THREADS = 1024;
+constexpr size_t SSU_LDS = (size_t)(2 * SSU_HASH + 3 * (SSU_PAIRS + 2)) * 4 + 1024;
+
+__global__ void __launch_bounds__(SSU_THREADS) small_setup_kernel(const int32_t* __restrict__ probes, int npairs, int nq,
+                                                                  const int64_t* __restrict__ blk_off, const int64_t* __restrict__ list_off,
+                                                                  int CH, int group, int m, int32_t* __restrict__ pair_sorted,
+                                                                  int4* __restrict__ table, int32_t* __restrict__ ctrl,
+                                                                  int32_t* __restrict__ tauq, int64_t* __restrict__ counters) {
+    extern __shared__ __align__(16) int32_t ssu[];
+    int32_t* keys = ssu;                          // [SSU_HASH] list number or -1
+    int32_t* cnt = keys + SSU_HASH;               // [SSU_HASH] pairs of that list; later: where its pairs start
+    int32_t* t_list = cnt + SSU_HASH;             // by touched slot: list, first pair, first task (one more: the totals)
+    int32_t* t_po = t_list + SSU_PAIRS + 2;       // (an even number of words each: s_acc below stays 8-byte aligned)
+    int32_t* t_to = t_po + SSU_PAIRS + 2;
+    int32_t* s_w = t_to + SSU_PAIRS + 2;          // [3][16] wave totals of the scans, [48..50] their grand totals
+    unsigned long long* s_acc = reinterpret_cast<unsigned long long*>(s_w + 52);   // streamed, algorithmic bytes (8-byte aligned)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the probes are requested before LDS is cleared, and unconditionally: the trip to memory overlaps the clearing)
+    constexpr int PER = SSU_PAIRS / SSU_THREADS;
+    int pl[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) pl[e] = probes[min(e * SSU_THREADS + tid, npairs - 1)];
+    for (int i = tid; i < SSU_HASH; i += SSU_THREADS) { keys[i] = -1; cnt[i] = 0; }
+    for (int i = tid; i < nq; i += SSU_THREADS) tauq[i] = INT32_MIN;
+    if (tid < 2) s_acc[tid] = 0ull;
+    __syncthreads();
+    // ---- every pair finds or claims its list's cell and takes a position among the list's pairs
+    int cell[PER], ppos[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int i = e * SSU_THREADS + tid;
+        cell[e] = -1; ppos[e] = 0;
+        if (i < npairs) {
+            const int l = pl[e];
+            unsigned h = ((unsigned)l * 2654435761u) >> 19;       // 13 bits
+            for (;;) {                                            // (at most SSU_PAIRS of the SSU_HASH cells are ever taken)
+                const int old = atomicCAS(&keys[h], -1, l);
+                if (old == -1 || old == l) break;
+                h = (h + 1) & (SSU_HASH - 1);
+            }
+            cell[e] = (int)h;
+            ppos[e] = atomicAdd(&cnt[h], 1);
+        }
+    }
+    __syncthreads();
+    // Exclusive sums over the workgroup of up to three values per thread: inside each wave by shuffles, across the
+    // waves by the first wave (a loop over the 16 wave totals in every thread costs 48 dependent LDS reads).
+    auto scan3 = [&](int& a, int& b, int& c, int& ta, int& tb, int& tc) {
+        int ia = a, ib = b, ic = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int x = __shfl_up(ia, o), y = __shfl_up(ib, o), z = __shfl_up(ic, o);
+            if (lane >= o) { ia += x; ib += y; ic += z; }
+        }
+        __syncthreads();
+        if (lane == 63) { s_w[wave] = ia; s_w[16 + wave] = ib; s_w[32 + wave] = ic; }
+        __syncthreads();
+        if (wave == 0) {
+            const int n = SSU_THREADS / 64;
+            int wa = lane < n ? s_w[lane] : 0, wb = lane < n ? s_w[16 + lane] : 0, wc = lane < n ? s_w[32 + lane] : 0;
+            const int oa = wa, ob = wb, oc = wc;
+            for (int o = 1; o < 16; o <<= 1) {
+                const int x = __shfl_up(wa, o), y = __shfl_up(wb, o), z = __shfl_up(wc, o);
+                if (lane >= o) { wa += x; wb += y; wc += z; }
+            }
+            if (lane < n) { s_w[lane] = wa - oa; s_w[16 + lane] = wb - ob; s_w[32 + lane] = wc - oc; }
+            if (lane == n - 1) { s_w[48] = wa; s_w[49] = wb; s_w[50] = wc; }
+        }
+        __syncthreads();
+        a = ia - a + s_w[wave]; b = ib - b + s_w[16 + wave]; c = ic - c + s_w[32 + wave];
+        ta = s_w[48]; tb = s_w[49]; tc = s_w[50];
+    };
+    // ---- per cell (eight per thread): is it taken, how many pairs; exclusive sums give every touched list its slot
+    // number and its first pair
+    constexpr int CPT = SSU_HASH / SSU_THREADS;
+    int cl[CPT], cc[CPT];
+    int bo = 0, bc = 0, unused = 0, tot_o, tot_c, tot_t;
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) {
+        cl[e] = keys[tid * CPT + e]; cc[e] = cnt[tid * CPT + e];
+        bo += cl[e] >= 0 ? 1 : 0; bc += cl[e] >= 0 ? cc[e] : 0;
+    }
+    scan3(bo, bc, unused, tot_o, tot_c, tot_t);
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) {
+        if (cl[e] >= 0) {
+            t_list[bo] = cl[e]; t_po[bo] = bc;
+            cnt[tid * CPT + e] = bc;
+            bo += 1; bc += cc[e];
+        }
+    }
+    if (tid == 0) t_po[tot_o] = tot_c;
+    __syncthreads();
+    // ---- per touched list (four consecutive slots per thread): its tasks; their exclusive sums.  The loads are
+    // unconditional, from a clamped slot: one trip to memory for all of them.
+    constexpr int SPT = SSU_PAIRS / SSU_THREADS;
+    int st[SPT], pc[SPT], bt = 0, u1 = 0, u2 = 0, x1, x2;
+    unsigned long long streamed = 0, algo = 0;
+    {
+        int64_t b0[SPT], b1[SPT], v0[SPT], v1[SPT];
+#pragma unroll
+        for (int e = 0; e < SPT; ++e) {
+            const int sl = min(tid * SPT + e, max(tot_o - 1, 0));
+            const int l = t_list[sl];
+            pc[e] = t_po[sl + 1] - t_po[sl];
+            b0[e] = blk_off[l]; b1[e] = blk_off[l + 1]; v0[e] = list_off[l]; v1[e] = list_off[l + 1];
+        }
+#pragma unroll
+        for (int e = 0; e < SPT; ++e) {
+            const bool live = tid * SPT + e < tot_o;
+            const int c = pc[e], nblk = (int)(b1[e] - b0[e]);
+            st[e] = live ? ((c + group - 1) / group) * ((nblk + CH - 1) / CH) : 0;
+            streamed += live ? (unsigned long long)((c + group - 1) / group) * nblk * (BLOCK_VECS * m) : 0ull;
+            algo += live ? (unsigned long long)c * (unsigned long long)(v1[e] - v0[e]) * m : 0ull;
+            bt += st[e];
+        }
+    }
+    for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
+    if (lane == 0 && (streamed | algo)) { atomicAdd(&s_acc[0], streamed); atomicAdd(&s_acc[1], algo); }
+    scan3(bt, u1, u2, tot_t, x1, x2);
+    // ---- pairs grouped by list
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+        if (cell[e] >= 0) pair_sorted[cnt[cell[e]] + ppos[e]] = e * SSU_THREADS + tid;
+#pragma unroll
+    for (int e = 0; e < SPT; ++e) {
+        if (tid * SPT + e < tot_o) t_to[tid * SPT + e] = bt;
+        bt += st[e];
+    }
+    if (tid == 0) t_to[tot_o] = tot_t;
+    __syncthreads();
+    // ---- one record per task (as task_table_kernel)
+    for (int t = tid; t < tot_t; t += SSU_THREADS) {
+        int lo = 0, hi = tot_o;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (t_to[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int rem = t - t_to[lo];
+        const int npl = t_po[lo + 1] - t_po[lo];
+        const int ngroups = (npl + group - 1) / group;
+        const int chunk = rem / ngroups, grp = rem - chunk * ngroups;
+        const int per = npl / ngroups, extra = npl - per * ngroups;
+        const int first = grp * per + min(grp, extra);
+        table[t] = make_int4(t_list[lo], chunk, t_po[lo] + first, per + (grp < extra ? 1 : 0));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ctrl[0] = 0; ctrl[1] = tot_t; ctrl[2] = tot_o; ctrl[3] = 0;
+        counters[0] = tot_t; counters[1] = (int64_t)s_acc[0]; counters[2] = (int64_t)s_acc[1];
+    }
+}
+
 // ------------------------------------------------------------------ per-query merge of the task results
-__global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P, const float* __restrict__ delta,
+// NT threads: 256 when a batch brings a workgroup per compute unit or more, 1024 for the few queries of a latency-bound round.
+template <int NT>
+__global__ void __launch_bounds__(NT) merge_kernel(const ScanParams P, const float* __restrict__ delta,
                                                               int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
                                                               int32_t* __restrict__ out_iscores) {
     __shared__ int32_t sI[MERGE_CAP];
     __shared__ int64_t sId[MERGE_CAP];
     __shared__ int s_cnt;
+    constexpr int MERGE_TILE = 2048;
+    __shared__ __align__(8) int s_slot[MERGE_TILE];      // per slot of the current tile: (place in the result arrays << 8) | entries
     const int q = blockIdx.x, k = P.k;
     int32_t tau = P.tauq[q];   // k candidates of this query reach tau: nothing below can be in the result
     // Slots = (probe, chunk) pairs that exist: chunk counts per probe are prefix-summed in LDS
     // (s_pre), then one thread per slot reads the slot's count and its few surviving entries.
     __shared__ int s_pre[2049];            // nprobe <= 2048 (enforced by the selection stage / argument check)
-    for (int p = threadIdx.x; p < P.nprobe; p += MERGE_THREADS) {
+    for (int p = threadIdx.x; p < P.nprobe; p += NT) {
         const int l = P.probes[q * P.nprobe + p];
         const int nblk = (int)(P.blk_off[l + 1] - P.blk_off[l]);
         s_pre[p + 1] = (nblk + P.CH - 1) / P.CH;
@@ -836,8 +997,8 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
     {
         // inclusive prefix sum of s_pre[1 .. nprobe]: every thread sums a run of consecutive entries, the runs'
         // totals are scanned inside each wave (shuffles) and across the waves (LDS), then each run is rewritten
-        __shared__ int s_wsum[MERGE_THREADS / 64];
-        const int per = (P.nprobe + MERGE_THREADS - 1) / MERGE_THREADS;       // <= 8
+        __shared__ int s_wsum[NT / 64];
+        const int per = (P.nprobe + NT - 1) / NT;       // <= 8
         const int a = 1 + threadIdx.x * per, b = min(a + per, P.nprobe + 1);
         int run = 0;
         for (int i = a; i < b; ++i) run += s_pre[i];
@@ -862,30 +1023,58 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
         // turns the 64 counts into offsets, and then the wave's lanes share out ALL entries of its 64 slots evenly
         // (entry e belongs to the slot whose offset range holds e).  A thread per slot would walk up to k entries
         // one after the other, each a dependent trip to memory; a wave per slot idles when slots hold few entries.
-        __shared__ int s_wpre[MERGE_THREADS / 64][64];
-        __shared__ int64_t s_wgs[MERGE_THREADS / 64][64];
+        __shared__ int s_wpre[NT / 64][64];
+        __shared__ int64_t s_wgs[NT / 64][64];
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        if (k <= 16 && s1 - s0 > 4 * MERGE_THREADS) {
-            // many slots of few entries each (small k, many probes and chunks): a thread per slot has less to wait for
-            for (int sl = s0 + (int)threadIdx.x; sl < s1; sl += MERGE_THREADS) {
-                int lo = 0, hi = P.nprobe;
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (s_pre[mid] <= sl) lo = mid; else hi = mid;
+        if ((int64_t)P.nprobe * P.maxchunks < (1 << 23)) {
+            // Tiles of MERGE_TILE slots.  A thread per slot finds the slot's place in the result arrays and reads its
+            // count (neighbouring slots are neighbours in memory); both go into one LDS word.  Then the tile's
+            // entries are walked as one flat array, entry f = slot f / k, position f % k: neighbouring lanes read
+            // neighbouring words, stale positions beyond a slot's count are skipped.  (A thread per slot reading its
+            // k entries itself makes every load instruction touch 64 cache lines, and the merge of one query's
+            // 2000 slots took 38 us in the address unit.)
+            const int64_t qbase = (int64_t)q * P.nprobe * P.maxchunks;
+            constexpr int U = 4;
+            for (int t0 = s0; t0 < s1; t0 += MERGE_TILE) {
+                const int ts = min(MERGE_TILE, s1 - t0);
+                __syncthreads();
+                for (int j = threadIdx.x; j < ts; j += NT) {
+                    const int sl = t0 + j;
+                    int lo = 0, hi = P.nprobe;
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (s_pre[mid] <= sl) lo = mid; else hi = mid;
+                    }
+                    const int rel = lo * P.maxchunks + (sl - s_pre[lo]);
+                    s_slot[j] = (rel << 8) | P.part_cnt[qbase + rel];       // counts are <= k <= 128
                 }
-                const int64_t gs = ((int64_t)q * P.nprobe + lo) * P.maxchunks + (sl - s_pre[lo]);
-                const int n = P.part_cnt[gs];
-                for (int r = 0; r < n; ++r) {
-                    const int32_t I = P.part_I[gs * k + r];
-                    if (I >= tau) {
-                        const int o = atomicAdd(&s_cnt, 1);
-                        if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[gs * k + r]]; }
+                __syncthreads();
+                const int total = ts * k;
+                for (int f0 = threadIdx.x; f0 < total; f0 += NT * U) {
+                    int32_t I[U];
+                    int64_t at[U];
+                    bool live[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int f = f0 + u * NT;
+                        const int j = min(f / k, ts - 1), r = f - j * k;
+                        const int word = s_slot[j];
+                        live[u] = f < total && r < (word & 255);
+                        at[u] = (qbase + (word >> 8)) * k + (live[u] ? r : 0);
+                        I[u] = P.part_I[at[u]];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        if (live[u] && I[u] >= tau) {
+                            const int o = atomicAdd(&s_cnt, 1);
+                            if (o < MERGE_CAP) { sI[o] = I[u]; sId[o] = P.ids[P.part_row[at[u]]]; }
+                        }
                     }
                 }
             }
         } else
-        for (int b = s0; b < s1; b += MERGE_THREADS) {
-            const int sl = b + lane * (MERGE_THREADS / 64) + wave;
+        for (int b = s0; b < s1; b += NT) {
+            const int sl = b + lane * (NT / 64) + wave;
             int n = 0;
             int64_t gs = 0;
             if (sl < s1) {
@@ -926,9 +1115,28 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
         return s_cnt;
     };
     auto sort_keep_k = [&](int have) {
+        if (NT >= 1024 && have <= NT && have > 1) {
+            // one entry per thread: its rank is the number of entries that come before it (entries are distinct:
+            // a vector lies in one list and one chunk); ranks below k are the result, already in order
+            int32_t* oI = reinterpret_cast<int32_t*>(s_slot);                 // [k]   (the tile words are no longer needed)
+            int64_t* oId = reinterpret_cast<int64_t*>(s_slot + 256);          // [k]
+            const int t = threadIdx.x;
+            int32_t mi = 0; int64_t md = 0; int before = 0;
+            if (t < have) {
+                mi = sI[t]; md = sId[t];
+#pragma unroll 8
+                for (int j = 0; j < have; ++j) before += entry_before(sI[j], sId[j], mi, md) ? 1 : 0;
+                if (before < k) { oI[before] = mi; oId[before] = md; }
+            }
+            __syncthreads();
+            const int keep = min(have, k);
+            if (t < keep) { sI[t] = oI[t]; sId[t] = oId[t]; }
+            __syncthreads();
+            return keep;
+        }
         int n2 = 1;
         while (n2 < have) n2 <<= 1;
-        for (int i = have + threadIdx.x; i < n2; i += MERGE_THREADS) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
+        for (int i = have + threadIdx.x; i < n2; i += NT) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
         if (n2 > 1) bitonic_sort(sI, sId, n2); else __syncthreads();
         return min(have, k);
     };
@@ -949,7 +1157,7 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_kernel(const ScanParams P
         }
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+    for (int r = threadIdx.x; r < k; r += NT) {
         const bool ok = r < fill;
         const int32_t I = ok ? sI[r] : INT32_MIN;
         out_ids[(int64_t)q * k + r] = ok ? sId[r] : -1;
@@ -1097,6 +1305,14 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
                                 ws.wave_q.as<int32_t>(), ws.wave_stage.p, ws.counters.as<int64_t>(), delta, out_ids, out_scores, out_iscores,
                                 ev, st);
     const unsigned pg = (unsigned)((npairs + 255) / 256);
+    if (npairs <= SSU_PAIRS) {
+        static OncePerDevice once;
+        if (once.first())
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small_setup_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)SSU_LDS));
+        small_setup_kernel<<<1, SSU_THREADS, SSU_LDS, st>>>(probes, (int)npairs, (int)nq, idx->blk_off, idx->list_off, CH, group, idx->m,
+                                                            ws.pair_sorted.as<int32_t>(), ws.task_table.as<int4>(), ctrl, P.tauq,
+                                                            ws.counters.as<int64_t>());
+    } else {
     scan_init_kernel<<<(unsigned)std::min<int64_t>(256, (2 * nlist + nq + 255) / 256 + 1), 256, 0, st>>>(list_cnt, 2 * (int64_t)nlist, P.tauq, nq, ctrl, ws.counters.as<int64_t>());
     if (nq >= 64) {
         count_pairs_kernel<<<pg, 256, 0, st>>>(probes, npairs, nprobe, 0, list_cnt, ws.touched.as<int32_t>(), ctrl);
@@ -1111,6 +1327,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     task_table_kernel<<<(unsigned)((max_tasks + 255) / 256), 256, 0, st>>>(ws.task_off.as<int32_t>(), ws.pair_off.as<int32_t>(),
                                                                            ws.touched.as<int32_t>(), group, ctrl, max_tasks,
                                                                            ws.task_table.as<int4>());
+    }
     RAGO_HIP(hipGetLastError());
 
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
@@ -1129,7 +1346,8 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     }
     if (rc) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
-    merge_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
+    if (nq <= 32) merge_kernel<1024><<<(unsigned)nq, 1024, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
+    else merge_kernel<MERGE_THREADS><<<(unsigned)nq, MERGE_THREADS, 0, st>>>(P, delta, out_ids, out_scores, out_iscores);
     RAGO_HIP(hipGetLastError());
     if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
     return RAGO_OK;

@@ -128,7 +128,7 @@ __device__ inline void bitonic_sort(int32_t* sI, int64_t* sId, int n2) {
     for (int size = 2; size <= n2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             __syncthreads();
-            for (int t = threadIdx.x; t < n2 / 2; t += MERGE_THREADS) {
+            for (int t = threadIdx.x; t < n2 / 2; t += blockDim.x) {
                 const int i = 2 * t - (t & (stride - 1));
                 const int j = i + stride;
                 const bool up = (i & size) == 0;  // this sub-sequence ends best-first
