@@ -127,13 +127,23 @@ __global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __r
     {
         float rng = 0.f, mag = 0.f;
         const double* tq = t64 + q * nprobe * m;
-        for (int i = tid; i < nprobe * m; i += LQ_THREADS) {
+        // (eight loads at a time while eight are left: one load per trip round the loop is a trip to memory each)
+        const int total = nprobe * m;
+        auto look = [&](int i, double t) {
             const int j = i % m;
-            const double t = tq[i];
             const float lo = (float)(s_Tmin[j] + t), hi = (float)(s_Tmax[j] + t);
             rng = fmaxf(rng, hi - lo);
             mag = fmaxf(mag, fmaxf(fabsf(lo), fabsf(hi)));
+        };
+        int i0 = tid;
+        for (; i0 + 7 * LQ_THREADS < total; i0 += 8 * LQ_THREADS) {
+            double t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = tq[i0 + u * LQ_THREADS];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) look(i0 + u * LQ_THREADS, t[u]);
         }
+        for (; i0 < total; i0 += LQ_THREADS) look(i0, tq[i0]);
         for (int o = 32; o; o >>= 1) { rng = fmaxf(rng, __shfl_xor(rng, o)); mag = fmaxf(mag, __shfl_xor(mag, o)); }
         if (lane == 0) {     // (non-negative floats order like their bit patterns)
             if (rng > 0.f) atomicMax(&s_rng, __float_as_uint(rng));
@@ -217,18 +227,42 @@ __global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __r
         const int S = rago_steps(m);
         for (int p = blockIdx.y * (LQ_THREADS / 64) + wave; p < nprobe; p += gridDim.y * (LQ_THREADS / 64)) {
             const int64_t pair = q * nprobe + p;
-            for (int j = lane; j < m; j += 64) {
-                const double t = t64[pair * m + j];
-                s_t[j] = t;
-                s_lo[j] = (float)(s_Tmin[j] + t);
+            float lo_reg[2] = {0.f, 0.f};                  // lane holds sub-quantisers lane and lane + 64 (m <= 128)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int j = lane + 64 * h;
+                if (j < m) {
+                    const double t = t64[pair * m + j];
+                    s_t[j] = t;
+                    lo_reg[h] = (float)(s_Tmin[j] + t);
+                    s_lo[j] = lo_reg[h];
+                }
             }
             // (the wave's own LDS writes are visible to its later reads: LDS operations of a wave complete in order;
             // the wave barrier only keeps the compiler from moving the reads up)
             __builtin_amdgcn_wave_barrier();
-            if (lane == 0) {
-                double losum = 0.0;
-                for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
-                bias[pair] = (int32_t)rint(losum / (double)dq);
+            {
+                // The definition sums the minima over the sub-quantisers in order, in fp64.  When every partial sum
+                // of any order is exactly representable - all terms multiples of 2^(emin - 23), all sums below
+                // 2^(emax + 8), and emax - emin <= 22 leaves them 53 bits - the order does not matter and a
+                // tree over the lanes gives that sum; otherwise one lane adds them in order.
+                const uint32_t e0 = (__float_as_uint(lo_reg[0]) >> 23) & 255u, e1 = (__float_as_uint(lo_reg[1]) >> 23) & 255u;
+                int emax = (int)max(e0, e1);
+                int emin = (int)min(lo_reg[0] != 0.f ? e0 : 255u, lo_reg[1] != 0.f ? e1 : 255u);
+                double losum = (double)lo_reg[0] + (double)lo_reg[1];
+                for (int o = 32; o; o >>= 1) {
+                    losum = losum + __shfl_xor(losum, o);
+                    emax = max(emax, __shfl_xor(emax, o));
+                    emin = min(emin, __shfl_xor(emin, o));
+                }
+                // (exponent field 0: subnormal terms, multiples of 2^-149 like those of field 1; 255: infinities and
+                // not-a-numbers go the ordered way)
+                if (emax == 255 || emax - max(emin, 1) > 22) {
+                    losum = 0.0;
+                    if (lane == 0)
+                        for (int j = 0; j < m; ++j) losum = losum + (double)s_lo[j];
+                }
+                if (lane == 0) bias[pair] = (int32_t)rint(losum / (double)dq);
             }
             if (n <= AMB_MAX) {
                 for (int i = lane; i < n; i += 64) {
@@ -420,7 +454,8 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
         lut_Tt_kernel<0><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, ws.T64.as<double>(),
                                                      ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
     // (workgroups per query: enough to fill the chip on a small batch, at most one per 32 pairs)
-    const unsigned lq_y = (unsigned)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(512 / nq, (nprobe + 31) / 32), 16));
+    // workgroups per query: a wave per pair at a time; one round of pairs per workgroup while the batch leaves room
+    const unsigned lq_y = (unsigned)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(512 / nq, (nprobe + 15) / 16), 32));
     lut_query_kernel<<<dim3((unsigned)nq, lq_y), LQ_THREADS, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), nprobe, m,
                                                           range_bits, mag_bits, ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(),
                                                           ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>());

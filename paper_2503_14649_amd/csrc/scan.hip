@@ -1187,9 +1187,9 @@ static int launch_scan_kernel(const ScanParams& P, int grid, hipStream_t st) {
 enum { SCAN_WIDE = 0, SCAN_NARROW = 1, SCAN_WAVE = 2 };
 struct ScanPlan { int kind; int CH, group, maxchunks; };
 
-static int chunk_len(double npairs, double avgblk, double pairs_per_task, int cap) {
+static int chunk_len(double npairs, double avgblk, double pairs_per_task, int cap, double tasks = 2048.0) {
     int c = 16;
-    while (c < cap && npairs * avgblk / (pairs_per_task * c) > 2048.0) c <<= 1;
+    while (c < cap && npairs * avgblk / (pairs_per_task * c) > tasks) c <<= 1;
     return c;
 }
 
@@ -1209,7 +1209,9 @@ static ScanPlan plan_scan(const rago_index* idx, int64_t nq, int64_t npairs, boo
     if (!wide && base_tables && avgblk <= 32.0) p.kind = SCAN_WAVE;
     if (force >= 1 && force <= 3) p.kind = force - 1;
     if (p.kind == SCAN_WIDE) p.CH = CH_wide;
-    else if (p.kind == SCAN_NARROW) p.CH = chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256);
+    // (a single query: ~1000 tasks, two per resident workgroup, measured best on 256 lists of ~240 blocks - 0.218 ms a
+    // round against 0.232 with 2000 tasks and 0.239 with 250: what a task costs to start outweighs the uneven end)
+    else if (p.kind == SCAN_NARROW) p.CH = chunk_len((double)npairs, avgblk, nq > 1 ? 1.5 : 1.0, 256, nq > 1 ? 2048.0 : 1024.0);
     else p.CH = wave_chunk_len((double)npairs * avgblk, idx->n_cu);
     p.group = p.kind == SCAN_WIDE ? NPMAX : 2;          // pairs of one list per task
     const int64_t maxblk = (idx->max_list_len + BLOCK_VECS - 1) / BLOCK_VECS;
@@ -1234,10 +1236,11 @@ static int64_t max_result_slots(const rago_index* idx, int64_t max_nq, int max_n
         const int caps[2] = {512, 256};
         for (int kern = 0; kern < 2; ++kern)
             for (int c = 16; c <= caps[kern]; c <<= 1) {
-                const int64_t edge = (int64_t)(2048.0 * ppts[kern] * c / avgblk);
+                const double tasks = kern == 1 && single ? 1024.0 : 2048.0;
+                const int64_t edge = (int64_t)(tasks * ppts[kern] * c / avgblk);
                 for (int64_t np : {edge - 1, edge, edge + 1, np_max}) {
                     np = std::min(std::max<int64_t>(np, 1), np_max);
-                    look(np, np_max, chunk_len((double)np, avgblk, ppts[kern], caps[kern]));
+                    look(np, np_max, chunk_len((double)np, avgblk, ppts[kern], caps[kern], tasks));
                 }
             }
         for (int c = 1; c <= 512; c <<= 1) {                        // the kernel with one wave per item

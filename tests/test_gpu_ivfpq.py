@@ -121,6 +121,35 @@ def test_select_equals_oracle(case, rb):
     assert rb.rago_debug_counters(h)[3] == 0
 
 
+@pytest.mark.parametrize("m", [16, 96])
+def test_bias_when_sub_table_minima_differ_by_many_orders(rb, m):
+    """The bias is the rounded fp64 sum of the sub-tables' minima, taken in order.  The library adds them in a tree when
+    every partial sum is exact whatever the order, and in order otherwise: here one sub-quantiser works at 1e-9 of the
+    scale of the others (its minimum then is not a multiple of the others' unit in the last place), another at 1e6."""
+    d = 4 * m
+    ix = dict(to_np(synth.random_index(n=3000, d=d, m=m, nlist=6, seed=50 + m)))
+    dsub = d // m
+    cb, cen = ix["codebooks"].copy(), ix["centroids"].copy()
+    cb[0] *= 1e-9
+    cen[:, :dsub] *= 1e-9
+    cb[1] *= 1e6
+    cen[:, dsub:2 * dsub] *= 1e6
+    ix["codebooks"], ix["centroids"] = cb, cen
+    Q = _queries(5, d, 8)
+    h = rb.rago_index_wrap(dev_index(ix))
+    try:
+        S, probes, L, LUT8, B, delta = oracle_stages(ix, Q, 4)
+        gL, gL8, gB, gd = rb.rago_debug_build_lut(h, torch.from_numpy(Q).cuda(), torch.from_numpy(probes).cuda())
+        assert np.array_equal(gd.cpu().numpy(), delta)
+        assert np.array_equal(gB.cpu().numpy(), B)
+        assert np.array_equal(gL8.cpu().numpy(), LUT8)
+        r = oracle.ivfpq_search(Q, ix, 4, 10)
+        gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), 4, 10)
+        assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+    finally:
+        rb.rago_index_free(h)
+
+
 def test_tables_equal_oracle(case, rb):
     ix, Q, nprobe, k, h = case
     S, probes, L, LUT8, B, delta = oracle_stages(ix, Q, nprobe)
