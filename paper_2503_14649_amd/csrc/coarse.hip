@@ -263,6 +263,59 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
             }
 }
 
+// ---- one or two queries: the product is a stream over C (a round of iterative retrieval, Section 5.3, reads all
+// of C for a handful of queries), so the only thing that matters is how many bytes are in flight.  A wave takes
+// GV_R rows of C at a time, its lanes 16 bytes each of every 1 KiB of a row; the queries sit in LDS; partial
+// sums are added up across the lanes at the end of the rows.  Plain fp32: the selection only needs the scores to
+// within its bound (d * 2^-22 |q||c|), which any order of fp32 products and sums stays inside.
+constexpr int GV_R = 8, GV_THREADS = 256;
+template <int NQ>
+__global__ void __launch_bounds__(GV_THREADS) coarse_gemv_kernel(const float* __restrict__ Q, const float* __restrict__ C, int nq,
+                                                                 int nlist, int d, const float* __restrict__ qn2,
+                                                                 const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
+    extern __shared__ __align__(16) float gv_q[];          // [NQ][d]
+    if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < NQ * d; i += GV_THREADS) gv_q[i] = i / d < nq ? Q[i] : 0.f;
+    __syncthreads();
+    const int wave_id = blockIdx.x * (GV_THREADS / 64) + (tid >> 6), nwaves = gridDim.x * (GV_THREADS / 64);
+    for (int r0 = wave_id * GV_R; r0 < nlist; r0 += nwaves * GV_R) {
+        float acc[GV_R][NQ];
+#pragma unroll
+        for (int r = 0; r < GV_R; ++r)
+#pragma unroll
+            for (int qi = 0; qi < NQ; ++qi) acc[r][qi] = 0.f;
+        const float* rows[GV_R];
+#pragma unroll
+        for (int r = 0; r < GV_R; ++r) rows[r] = C + (int64_t)min(r0 + r, nlist - 1) * d;
+        for (int t = lane * 4; t < d; t += 256) {
+            typedef float gv_f4 __attribute__((ext_vector_type(4)));
+            gv_f4 c4[GV_R];
+#pragma unroll
+            for (int r = 0; r < GV_R; ++r) c4[r] = __builtin_nontemporal_load(reinterpret_cast<const gv_f4*>(rows[r] + t));
+#pragma unroll
+            for (int qi = 0; qi < NQ; ++qi) {
+                const float4 q4 = *reinterpret_cast<const float4*>(gv_q + qi * d + t);
+#pragma unroll
+                for (int r = 0; r < GV_R; ++r)
+                    acc[r][qi] += c4[r].x * q4.x + c4[r].y * q4.y + c4[r].z * q4.z + c4[r].w * q4.w;
+            }
+        }
+#pragma unroll
+        for (int qi = 0; qi < NQ; ++qi) {
+            float mine = 0.f;                               // lane r keeps row r0 + r
+#pragma unroll
+            for (int r = 0; r < GV_R; ++r) {
+                float v = acc[r][qi];
+                for (int o = 32; o; o >>= 1) v += __shfl_xor(v, o);
+                mine = lane == r ? v : mine;
+            }
+            if (lane < GV_R && r0 + lane < nlist && qi < nq)
+                S[(int64_t)qi * nlist + r0 + lane] = coarse_score(mine, qi, r0 + lane, qn2, cn2);
+        }
+    }
+}
+
 // |q|^2 per query (fp64 accumulation, one rounding): one wave per query
 __global__ void __launch_bounds__(256) qnorm2_kernel(const float* __restrict__ Q, int64_t nq, int d, float* __restrict__ out) {
     const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -293,7 +346,13 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         zero_me = idx->ws.counters.as<int64_t>() + 3;
     }
     const unsigned gx = (unsigned)((nlist + G_TN - 1) / G_TN);
-    if (nq <= 32) {
+    if (nq <= 2 && d % 4 == 0 && (size_t)2 * d * 4 <= 48 * 1024) {
+        // (measured on 65536 x 768: 38 us against the tile kernel's 45 for one query; four queries are level)
+        const unsigned grid = (unsigned)std::min<int64_t>((nlist + GV_R * 4 - 1) / (GV_R * 4), (int64_t)idx->n_cu * 8);
+        const size_t lds = (size_t)nq * d * 4;
+        if (nq == 1) coarse_gemv_kernel<1><<<grid, GV_THREADS, lds, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
+        else coarse_gemv_kernel<2><<<grid, GV_THREADS, lds, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
+    } else if (nq <= 32) {
         coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
         coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);

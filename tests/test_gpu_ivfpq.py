@@ -286,11 +286,13 @@ def test_select_for_few_queries(rb, nlist, d):
     ix["centroids"] = C
     h = rb.rago_index_wrap(dev_index(ix))
     try:
-        for nq in (1, 7, 32, 33):
+        for nq in (1, 2, 7, 32, 33):
             Q = _queries(nq, d, 100 + nq)
             S = oracle.coarse(Q, C)
             Qd = torch.from_numpy(Q).cuda()
             gS = rb.rago_debug_coarse(h, Qd)
+            scale = np.linalg.norm(Q, axis=1)[:, None] * np.linalg.norm(C, axis=1)[None, :]
+            assert np.max(np.abs(gS.cpu().numpy() - S) / scale) < 1e-4
             for nprobe in (1, 64, 256, 480):
                 if nprobe >= nlist:
                     continue
@@ -556,6 +558,24 @@ def test_l2_search_end_to_end(l2case, rb, scan_kernel):
     assert np.array_equal(gs, r["scores"])
     have = r["ids"] >= 0
     assert np.all(gs[have] <= 0)                            # minus a squared distance (up to the table step)
+
+
+@pytest.mark.parametrize("nq", [1, 2, 3])
+def test_l2_coarse_and_select_for_one_or_two_queries(rb, nq):
+    """The streaming kernel that scores one or two queries against all centroids, with the Euclidean epilogue
+    (three queries take the tile kernel), on a ragged number of lists and a dimension of several 1 KiB steps plus a rest."""
+    ix = to_np(synth.random_index(n=9000, d=336, m=16, nlist=1003, seed=79))
+    Q = _queries(nq, 336, 11 + nq)
+    h = rb.rago_index_wrap(dev_index(ix), metric="l2")
+    try:
+        S = oracle.coarse(Q, ix["centroids"], metric="l2")
+        gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+        scale = (np.linalg.norm(Q, axis=1)[:, None] + np.linalg.norm(ix["centroids"], axis=1)[None, :]) ** 2
+        assert np.max(np.abs(gS.cpu().numpy() - S) / scale) < 1e-4
+        gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, 20).cpu().numpy()
+        assert np.array_equal(gp, oracle.select(S, 20))
+    finally:
+        rb.rago_index_free(h)
 
 
 def test_l2_large_batch_coarse(rb):
