@@ -42,7 +42,7 @@ void DevBuf::release() { if (p) hipFree(p); p = nullptr; cap = 0; }
 void Workspace::release() {
     DevBuf* all[] = {&S, &cand_idx, &probes, &probe_scores, &T64, &Tmin, &Tmax, &lut8, &bias, &delta, &pair_lo, &Lf32,
                      &list_cnt, &pair_off, &task_off, &task_table, &pair_sorted, &tauq, &part_I, &part_id, &part_cnt,
-                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo, &sel_small, &wave_items, &wave_q, &wave_stage};
+                     &counters, &tmp_lut8sw, &amb, &patch, &touched, &qn2, &l2_r, &sel_redo, &sel_small, &sel_done, &wave_items, &wave_q, &wave_stage};
     for (DevBuf* b : all) b->release();
 }
 

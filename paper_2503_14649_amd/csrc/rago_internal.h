@@ -60,7 +60,7 @@ int forced_scan_kernel();        // 0 = pick by sizes, 1 = wide, 2 = narrow, 3 =
 struct Workspace {
     DevBuf S, cand_idx, probes, probe_scores, T64, Tmin, Tmax, lut8, bias, delta, pair_lo, Lf32;
     DevBuf list_cnt, pair_off, task_off, task_table, pair_sorted, tauq, part_I, part_id, part_cnt, counters;
-    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo, sel_small, wave_items, wave_q, wave_stage;
+    DevBuf tmp_lut8sw, amb, patch, touched, qn2, l2_r, sel_redo, sel_small, sel_done, wave_items, wave_q, wave_stage;
     void release();
 };
 
