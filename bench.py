@@ -76,25 +76,37 @@ def read_stream_ceiling(rb, gib=4.0, reps=10):
     return rate
 
 
-def hbm_roofline(kernel, hbm_bytes, kernel_ms, ceiling, prof, what, extra=None):
-    """The roofline object of a bandwidth-bound kernel: `hbm_bytes` are bytes the kernel reads from HBM
-    per launch (never bytes counted once per query that shares them), `kernel_ms` its HIP-event time."""
-    achieved = hbm_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
-    rec = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-           "frac": achieved / HBM_PEAK_GBPS, "achieved_is": what, "hbm_bytes_per_launch": hbm_bytes, "kernel_ms": kernel_ms,
-           "ceiling": ceiling, "ceiling_is": "plain read-stream kernel over 4 GiB, timed in this run",
-           "frac_of_ceiling": achieved / ceiling if ceiling else None, "traffic": None}
+def hbm_roofline(kernel, useful_bytes, kernel_ms, ceiling, prof, what, extra=None):
+    """The roofline object of a bandwidth-bound kernel.
+
+    `achieved` = bytes the kernel moves to and from HBM per launch / its HIP-event time in this run.  The bytes are
+    hardware counters (FETCH_SIZE + WRITE_SIZE per launch) from the committed rocprofv3 summary named in
+    `traffic_source`, taken on this same command; hardware counters cannot be read inside this process, so the
+    summary's own kernel time is quoted beside them.  Without a summary for the workload the kernel's own count of
+    the bytes it streams stands in and `achieved_is` says so.  `useful` = bytes of database codes (or corpus rows)
+    streamed per launch / the same time: never bytes counted once per query that shares them."""
+    useful = useful_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    rec = {"bound": "hbm", "kernel": kernel, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "kernel_ms": kernel_ms,
+           "useful": useful, "useful_is": what, "useful_bytes_per_launch": useful_bytes,
+           "ceiling": ceiling, "ceiling_is": "plain read-stream kernel over 4 GiB, timed in this run", "traffic": None}
     if prof:
         total = prof["fetch_bytes"] + prof["write_bytes"]
         rec["traffic"] = total
+        rec["achieved"] = total / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+        rec["achieved_is"] = "FETCH_SIZE + WRITE_SIZE bytes per launch (rocprofv3 counters, scaled by a copy of known size) / the kernel's HIP-event time in this run"
         rec["traffic_source"] = {"file": prof["file"], "kernel_ms_in_that_run": prof["kernel_ms"],
                                  "fetch_bytes": prof["fetch_bytes"], "write_bytes": prof["write_bytes"]}
         if prof["kernel_ms"]:
-            rec["traffic_source"]["fetched_rate"] = prof["fetch_bytes"] / (prof["kernel_ms"] * 1e-3) / 1e9
-            rec["traffic_source"]["frac_fetched"] = rec["traffic_source"]["fetched_rate"] / HBM_PEAK_GBPS
+            rec["traffic_source"]["rate_in_that_run"] = total / (prof["kernel_ms"] * 1e-3) / 1e9
+    else:
+        rec["achieved"] = useful
+        rec["achieved_is"] = "no counter summary for this workload: the bytes the kernel streams by its own count / its HIP-event time"
+    rec["frac"] = rec["achieved"] / HBM_PEAK_GBPS
+    rec["frac_useful"] = useful / HBM_PEAK_GBPS
+    rec["frac_of_ceiling"] = rec["achieved"] / ceiling if ceiling else None
     if extra:
         rec.update(extra)
-    assert rec["frac"] <= 1.0, "an HBM fraction above 1 means bytes were counted that never crossed HBM"
+    assert rec["frac"] <= 1.0 and rec["frac_useful"] <= 1.0, "an HBM fraction above 1 means bytes were counted that never crossed HBM"
     return rec
 
 
