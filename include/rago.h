@@ -151,9 +151,10 @@ int rago_index_info(const rago_index* idx, rago_index_desc* out);
  *   out_scores  DEVICE [nq][k] fp32 = integer score * the query's table step; pad = -inf
  *   out_iscores DEVICE [nq][k] int32 or NULL; pad = INT32_MIN
  * Workspace: see rago_index_reserve and the conventions at the top.
- * The scan runs one of two kernels, chosen from the batch and list sizes (long tasks with lists
- * shared by several queries: four (query, list) pairs per pass of a list; otherwise two); results
- * are identical (rago_debug_force_scan_kernel pins one of them for tests).
+ * The scan runs one of three kernels, chosen from the batch and list sizes (long tasks with lists
+ * shared by several queries: four (query, list) pairs per pass of a list; short lists: one wavefront
+ * per (pair, chunk of a list), pairs grouped by query; otherwise two pairs per pass); results are
+ * identical (rago_debug_force_scan_kernel pins one of them for tests).
  * ids must ascend inside every list (RAGO_FORMAT at load otherwise): the scan orders equal scores by
  * position in the list, which is the order by id only then; an index writer sorts each list once,
  * where it has the vectors at hand, rather than every load permuting ~100 GB of codes.
@@ -241,8 +242,8 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
                     void* stream);
 
 /* Counters of the last search on this index, HOST out[8] (synchronises `stream`):
- * [0] scan tasks, [1] code bytes streamed by the scan (a pass over a list serves up to four, or
- * two, of its pairs), [2] algorithmic code bytes
+ * [0] scan tasks (the wavefront-per-item kernel: items), [1] code bytes streamed by the scan (a pass
+ * over a list serves up to four, two or one of its pairs, by kernel), [2] algorithmic code bytes
  * (sum over (query, probe) of list length * m), [3] queries whose probe choice had to be made on
  * exact scores of all lists (it could not be shown independent of fp32 rounding otherwise), [4] table entries whose rounding had to be evaluated per
  * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
@@ -251,7 +252,10 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
 /* Pin the scan kernel of every following search in this process: 0 = chosen from the sizes (default),
- * 1 = the four-pairs-per-pass kernel, 2 = the two-pairs-per-pass kernel.  For tests. */
+ * 1 = the four-pairs-per-pass kernel, 2 = the two-pairs-per-pass kernel, 3 = the kernel with one
+ * wavefront per (pair, chunk) (chosen by itself only for short lists with per-query base tables;
+ * when pinned with full tables per pair - Euclidean metric, rago_debug_scan - a workgroup installs
+ * each pair's table in turn).  RAGO_INVALID_ARG for other values.  For tests. */
 int rago_debug_force_scan_kernel(int which);
 
 /* Number of device allocations the library's workspaces have made in this process so far (a test
