@@ -31,6 +31,7 @@
 #include <algorithm>
 
 #include "lut_common.h"
+#include "scan_setup.h"
 #include "rago_internal.h"
 
 namespace rago {
@@ -110,7 +111,15 @@ __global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __r
                                                                uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
                                                                int32_t* __restrict__ namb, float* __restrict__ delta,
                                                                int32_t* __restrict__ bias, uint8_t* __restrict__ patch_val,
-                                                               int64_t* __restrict__ counters) {
+                                                               int64_t* __restrict__ counters, int lq_y, const SmallSetupArgs setup) {
+    // One extra row of workgroups, the first to be dispatched, when the scan's bookkeeping rides along: its first
+    // workgroup does that work, which needs nothing from the tables, the others leave.
+    const int ty = (int)blockIdx.y - (setup.enable ? 1 : 0);       // this workgroup's row among the query's lq_y
+    if (ty < 0) {
+        extern __shared__ __align__(16) int32_t ssu[];
+        if (blockIdx.x == 0) small_setup_body(setup, ssu);
+        return;
+    }
     __shared__ uint32_t s_rng, s_mag;
     __shared__ int s_n;
     __shared__ int s_wcnt[LQ_THREADS / 64];
@@ -153,7 +162,7 @@ __global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __r
     __syncthreads();
     const float range = __uint_as_float(s_rng);
     const float dq = lut_step(range);
-    const bool writer = blockIdx.y == 0;
+    const bool writer = ty == 0;
     if (tid == 0 && writer) { range_bits[q] = s_rng; mag_bits[q] = s_mag; delta[q] = dq; }
     // ---- base table and ambiguous entries: thread = (plane, codeword)
     {
@@ -225,7 +234,7 @@ __global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __r
         double* s_t = s_t16[wave];
         float* s_lo = s_lo16[wave];
         const int S = rago_steps(m);
-        for (int p = blockIdx.y * (LQ_THREADS / 64) + wave; p < nprobe; p += gridDim.y * (LQ_THREADS / 64)) {
+        for (int p = ty * (LQ_THREADS / 64) + wave; p < nprobe; p += lq_y * (LQ_THREADS / 64)) {
             const int64_t pair = q * nprobe + p;
             float lo_reg[2] = {0.f, 0.f};                  // lane holds sub-quantisers lane and lane + 64 (m <= 128)
 #pragma unroll
@@ -423,7 +432,7 @@ int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npair
 }
 
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, LutTables* out,
-                     float* out_L_f32, uint8_t* out_LUT8, hipStream_t st) {
+                     float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup) {
     Workspace& ws = idx->ws;
     const int m = idx->m, d = idx->d;
     const int64_t npairs = nq * nprobe;
@@ -456,9 +465,17 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     // (workgroups per query: enough to fill the chip on a small batch, at most one per 32 pairs)
     // workgroups per query: a wave per pair at a time; one round of pairs per workgroup while the batch leaves room
     const unsigned lq_y = (unsigned)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(512 / nq, (nprobe + 15) / 16), 32));
-    lut_query_kernel<<<dim3((unsigned)nq, lq_y), LQ_THREADS, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), nprobe, m,
-                                                          range_bits, mag_bits, ws.lut8.as<uint8_t>(), amb_addr, namb, ws.delta.as<float>(),
-                                                          ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>());
+    SmallSetupArgs su{};
+    if (setup && setup->enable) {
+        static_assert(SSU_THREADS == LQ_THREADS, "the bookkeeping rides in a workgroup of the table kernel");
+        su = *setup;
+        static OncePerDevice once;
+        if (once.first())
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(lut_query_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)SSU_LDS));
+    }
+    lut_query_kernel<<<dim3((unsigned)nq, lq_y + (su.enable ? 1u : 0u)), LQ_THREADS, su.enable ? SSU_LDS : 0, st>>>(
+        ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), nprobe, m, range_bits, mag_bits, ws.lut8.as<uint8_t>(), amb_addr,
+        namb, ws.delta.as<float>(), ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>(), (int)lq_y, su);
     if (out_L_f32 || out_LUT8)
         lut_expand_kernel<<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
                                                             ws.lut8.as<uint8_t>(), amb_addr, namb, ws.patch.as<uint8_t>(), nprobe, m,

@@ -120,6 +120,8 @@ struct rago_index {
 
 namespace rago {
 
+struct SmallSetupArgs;      // scan_setup.h
+
 // layout.hip
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
 int launch_calib_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
@@ -141,7 +143,7 @@ int tree_cap();
 
 // lut.hip
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,
-                     LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st);
+                     LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup = nullptr);
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
 // Euclidean metric: one full table per pair (plane-major, stride LUT_BYTES) into ws.tmp_lut8sw, biases into
 // ws.bias, steps into ws.delta; optional plain copies for inspection.
@@ -155,9 +157,11 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
 // scan.hip
 // Tables come either per pair (`lut8sw` [npairs][plane][256][32] + `bias`, `tables` null) or as per-query
 // base tables with per-pair patches (`tables`, `lut8sw` null).
+// (setup_done: the bookkeeping of a small batch has been run by the caller's kernel, see plan_small_setup)
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
                 const LutTables* tables, const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids,
-                float* out_scores, int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr);
+                float* out_scores, int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr, bool setup_done = false);
+int plan_small_setup(rago_index* idx, const int32_t* probes, int64_t nq, int nprobe, int k, bool base_tables, SmallSetupArgs* out);
 
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,
