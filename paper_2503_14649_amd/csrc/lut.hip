@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) lut_Tt_kernel(const float* __restrict__ Q
 // list of ambiguous entries for itself, in the same order (positions from a prefix sum over the threads, not from
 // an atomic counter), and the first one writes the per-query outputs.
 constexpr int LQ_THREADS = 1024;
-__global__ void __launch_bounds__(LQ_THREADS) lut_query_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
+__global__ void __launch_bounds__(LQ_THREADS, 8) lut_query_kernel(const double* __restrict__ T64, const double* __restrict__ Tmin,
                                                                const double* __restrict__ Tmax, const double* __restrict__ t64, int nprobe,
                                                                int m, uint32_t* __restrict__ range_bits, uint32_t* __restrict__ mag_bits,
                                                                uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
