@@ -670,9 +670,10 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
     }
 }
 
-// ------------------------------------------------------------------ selection, few queries
+// ------------------------------------------------------------------ selection, rows of up to 65536 scores
 // One workgroup per query leaves the chip idle when a batch has a handful of queries, and its time is then the
-// latency of a request (iterative retrieval, Section 5.3: batches of 1 to 16).  Here SS_G workgroups share a query.
+// latency of a request (iterative retrieval, Section 5.3: batches of 1 to 16).  Here up to SS_G workgroups share a
+// query (one per query once the batch fills the chip: the single histogram pass still beats four radix passes).
 // Each of them finds the same candidate set by itself (the row of scores comes from L2; a histogram over a linear
 // map of the row's range finds the cut in one pass; the scores in and above the cut's bin are ordered exactly by
 // their fp32 keys), then the exact scores of the candidates - random rows of C from HBM, the expensive step on one
@@ -716,7 +717,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
     __shared__ float s_red[2 * SEL_WAVES];
     __shared__ int s_wtot[SEL_WAVES];
     __shared__ int s_bin, s_ncand, s_cnt, s_last;
-    const int q = blockIdx.y, g = blockIdx.x, G = gridDim.x;
+    const int q = blockIdx.x, g = blockIdx.y, G = gridDim.y;     // (queries along x: any batch size fits the grid)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* row = S + (int64_t)q * nlist;
     exact += (int64_t)q * SS_MAX_WANT;
@@ -922,15 +923,16 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
     // the first queued nothing) the queued queries on exact ones
     // rows of at most 65536 scores: one histogram pass instead of four, and the exact rescoring shared among a query's
     // workgroups while the batch leaves compute units idle
-    // (up to 32 queries; measured with 256 queries x 16384 lists: 59 us against 44 for a workgroup per query that passes
-    // over its registers four times, because every workgroup of a query repeats the histogram)
-    const bool small = nq <= 32 && nl <= SS_REG * SEL_THREADS && nprobe + SEL_EXTRA < nl && nprobe + SEL_EXTRA <= SS_MAX_WANT;
-    const unsigned ss_g = (unsigned)std::max<int64_t>(1, std::min<int64_t>(SS_G, 512 / nq));
+    // As many workgroups per query as leave every workgroup a compute unit of its own (each repeats the histogram;
+    // measured with 256 queries x 16384 lists: two per query 59 us, one 40, the kernel that passes over its
+    // registers four times 44; with 1024 queries x 65536 lists: one per query 0.21 ms against 0.34).
+    const bool small = nl <= SS_REG * SEL_THREADS && nprobe + SEL_EXTRA < nl && nprobe + SEL_EXTRA <= SS_MAX_WANT;
+    const unsigned ss_g = (unsigned)std::max<int64_t>(1, std::min<int64_t>(SS_G, idx->n_cu / nq));
     float* ss_exact = idx->ws.sel_small.as<float>();
     int* ss_done = idx->ws.sel_done.as<int>();      // (nothing else ever writes here: zero between launches)
     for (int redo = 0; redo < 2; ++redo) {
         if (small && !redo)
-            select_small_kernel<<<dim3(ss_g, (unsigned)nq), SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric,
+            select_small_kernel<<<dim3((unsigned)nq, ss_g), SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric,
                                                                                   probes, cnt, rq, ss_exact, ss_done);
         else if (nl <= 8 * SEL_THREADS)
             select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
