@@ -18,6 +18,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+CPU_SECONDS = 10.0       # oracle time spent on the cpu_baseline sample
 HBM_PEAK_GBPS = 8000.0
 
 
@@ -174,13 +175,19 @@ def run_ivfpq(args):
         sub = host_subindex(index, pr)
         log(f"oracle sample: {ns} queries, {sub['codes'].nbytes / 1e9:.2f} GB of codes on the host")
         oracle.ivfpq_search(Qs[:1], sub, nprobe, k, metric=args.metric)   # warm-up (library load, page-in)
+        # the sample is searched again and again until about CPU_SECONDS of oracle time have been spent (a sample
+        # with more queries would need more of the billion-vector index on the host)
         t1 = time.time()
         sample_ref = oracle.ivfpq_search(Qs, sub, nprobe, k, metric=args.metric)
+        reps = 1
+        while time.time() - t1 < CPU_SECONDS and reps < 200:
+            oracle.ivfpq_search(Qs, sub, nprobe, k, metric=args.metric)
+            reps += 1
         dt = time.time() - t1
-        cpu = {"value": ns / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{ns} of {nq} queries on the full index (only the lists they probe copied to the host), "
-                         f"{dt:.2f}s wall, OpenMP over queries"}
-        log(f"oracle: {ns / dt:.2f} queries/s on {oracle.num_threads()} threads")
+        cpu = {"value": ns * reps / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{ns} of {nq} queries on the full index (only the lists they probe copied to the host), searched {reps} "
+                         f"times in {dt:.2f}s wall, OpenMP over queries"}
+        log(f"oracle: {ns * reps / dt:.2f} queries/s on {oracle.num_threads()} threads")
         del sub
 
     torch.cuda.empty_cache()
@@ -411,11 +418,15 @@ def run_flat(args):
         qb = queries[:rs].cpu().view(torch.int16).numpy().view(np.uint16)
         t1 = time.time()
         oi, osc = oracle.flat_search(cb, qb, cfg.k, fmt=args.flat_format)
+        reps = 1
+        while time.time() - t1 < CPU_SECONDS and reps < 200:
+            oracle.flat_search(cb, qb, cfg.k, fmt=args.flat_format)
+            reps += 1
         dt = time.time() - t1
         gi = out[0][:rs].cpu().numpy()
         ov = float(np.mean([len(set(gi[r, q].tolist()) & set(oi[r, q].tolist())) / cfg.k for r in range(rs) for q in range(cfg.nq)]))
-        cpu = {"value": rs / dt, "unit": "requests/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{rs} of {R} requests, {dt:.2f}s wall", "topk_id_overlap": ov}
+        cpu = {"value": rs * reps / dt, "unit": "requests/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{rs} of {R} requests, searched {reps} times in {dt:.2f}s wall", "topk_id_overlap": ov}
     ceiling = read_stream_ceiling(rb) if args.ceiling else None
     prof = read_traffic("flat_32x100k_pmc.txt") if R == cfg.requests and not half else None
     roof = hbm_roofline("flat_scan_kernel", algo, scan_ms, ceiling, prof,
