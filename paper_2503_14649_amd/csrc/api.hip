@@ -62,7 +62,7 @@ struct DeviceGuard {
 static void destroy(rago_index* idx) {
     if (!idx) return;
     hipFree(idx->centroids); hipFree(idx->cnorm); hipFree(idx->cn2); hipFree(idx->cen_hi); hipFree(idx->cen_lo); hipFree(idx->codebooks); hipFree(idx->cb_absmax); hipFree(idx->cbx); hipFree(idx->list_off);
-    hipFree(idx->blk_off); hipFree(idx->codes_blk); hipFree(idx->ids);
+    hipFree(idx->blk_off); hipFree(idx->list_meta); hipFree(idx->codes_blk); hipFree(idx->ids);
     hipFree(idx->sup_cen); hipFree(idx->sup_off); hipFree(idx->sup_lists); hipFree(idx->sup_of);
     idx->ws.release();
     if (idx->prof.created)
@@ -111,6 +111,7 @@ static int prepare(rago_index* idx, int d, int m, int ksub, int nlist, int64_t n
         hipMalloc(&idx->cbx, sizeof(float) * (size_t)m * KSUB * (idx->dsub + 4)) != hipSuccess ||
         hipMalloc(&idx->list_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
         hipMalloc(&idx->blk_off, sizeof(int64_t) * (size_t)(nlist + 1)) != hipSuccess ||
+        hipMalloc(&idx->list_meta, sizeof(int2) * (size_t)nlist) != hipSuccess ||
         hipMalloc(&idx->codes_blk, code_bytes + 16) != hipSuccess ||
         hipMalloc(&idx->ids, sizeof(int64_t) * (size_t)(n + 1)) != hipSuccess) {
         (void)hipGetLastError();
@@ -118,6 +119,11 @@ static int prepare(rago_index* idx, int d, int m, int ksub, int nlist, int64_t n
     }
     RAGO_HIP(hipMemcpy(idx->list_off, h_list_off, sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
     RAGO_HIP(hipMemcpy(idx->blk_off, blk.data(), sizeof(int64_t) * (size_t)(nlist + 1), hipMemcpyHostToDevice));
+    {   // blocks and vectors of every list in one 8-byte word (lists are shorter than 2^31 vectors: checked above)
+        std::vector<int2> meta((size_t)nlist);
+        for (int l = 0; l < nlist; ++l) meta[l] = make_int2((int)(blk[l + 1] - blk[l]), (int)(h_list_off[l + 1] - h_list_off[l]));
+        RAGO_HIP(hipMemcpy(idx->list_meta, meta.data(), sizeof(int2) * (size_t)nlist, hipMemcpyHostToDevice));
+    }
     return RAGO_OK;
 }
 

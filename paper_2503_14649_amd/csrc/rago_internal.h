@@ -98,6 +98,7 @@ struct rago_index {
     float* cbx = nullptr;          // [m][256][dsub + 4] codeword, its squared norm, three zeros (one address per entry)
     int64_t* list_off = nullptr;   // [nlist+1] vector offsets (list-major rows)
     int64_t* blk_off = nullptr;    // [nlist+1] offsets in 64-vector blocks into codes_blk
+    int2* list_meta = nullptr;     // [nlist] {blocks, vectors} of each list: one load where the bookkeeping wants both
     uint8_t* codes_blk = nullptr;  // total_blocks * 64 * m bytes, skewed lane-major layout
     int64_t* ids = nullptr;        // [n]
     float max_cnorm = 0.f;

@@ -1136,7 +1136,7 @@ static void fill_small_setup(rago_index* idx, const int32_t* probes, int64_t nq,
     Workspace& ws = idx->ws;
     A->enable = 1;
     A->probes = probes; A->npairs = (int)(nq * nprobe); A->nq = (int)nq;
-    A->blk_off = idx->blk_off; A->list_off = idx->list_off;
+    A->list_meta = idx->list_meta;
     A->CH = plan.CH; A->group = plan.group; A->m = idx->m;
     A->pair_sorted = ws.pair_sorted.as<int32_t>();
     A->table = ws.task_table.as<int4>();

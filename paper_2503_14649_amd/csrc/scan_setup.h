@@ -18,8 +18,7 @@ struct SmallSetupArgs {
     int enable;                 // 0: nothing to do (the caller launches the bookkeeping kernels itself)
     const int32_t* probes;      // [npairs]
     int npairs, nq;
-    const int64_t* blk_off;
-    const int64_t* list_off;
+    const int2* list_meta;      // [nlist] {blocks, vectors} of each list
     int CH, group, m;
     int32_t* pair_sorted;       // out [npairs]
     int4* table;                // out: one record per task
@@ -32,8 +31,7 @@ struct SmallSetupArgs {
 __device__ __forceinline__ void small_setup_body(const SmallSetupArgs& A, int32_t* ssu) {
     const int32_t* __restrict__ probes = A.probes;
     const int npairs = A.npairs, nq = A.nq, CH = A.CH, group = A.group, m = A.m;
-    const int64_t* __restrict__ blk_off = A.blk_off;
-    const int64_t* __restrict__ list_off = A.list_off;
+    const int2* __restrict__ list_meta = A.list_meta;
     int32_t* __restrict__ pair_sorted = A.pair_sorted;
     int4* __restrict__ table = A.table;
     int32_t* __restrict__ ctrl = A.ctrl;
@@ -128,21 +126,20 @@ __device__ __forceinline__ void small_setup_body(const SmallSetupArgs& A, int32_
     int st[SPT], pc[SPT], bt = 0, u1 = 0, u2 = 0, x1, x2;
     unsigned long long streamed = 0, algo = 0;
     {
-        int64_t b0[SPT], b1[SPT], v0[SPT], v1[SPT];
+        int2 meta[SPT];
 #pragma unroll
         for (int e = 0; e < SPT; ++e) {
             const int sl = min(tid * SPT + e, max(tot_o - 1, 0));
-            const int l = t_list[sl];
             pc[e] = t_po[sl + 1] - t_po[sl];
-            b0[e] = blk_off[l]; b1[e] = blk_off[l + 1]; v0[e] = list_off[l]; v1[e] = list_off[l + 1];
+            meta[e] = list_meta[t_list[sl]];
         }
 #pragma unroll
         for (int e = 0; e < SPT; ++e) {
             const bool live = tid * SPT + e < tot_o;
-            const int c = pc[e], nblk = (int)(b1[e] - b0[e]);
+            const int c = pc[e], nblk = meta[e].x;
             st[e] = live ? ((c + group - 1) / group) * ((nblk + CH - 1) / CH) : 0;
             streamed += live ? (unsigned long long)((c + group - 1) / group) * nblk * (BLOCK_VECS * m) : 0ull;
-            algo += live ? (unsigned long long)c * (unsigned long long)(v1[e] - v0[e]) * m : 0ull;
+            algo += live ? (unsigned long long)c * (unsigned long long)meta[e].y * m : 0ull;
             bt += st[e];
         }
     }
