@@ -37,11 +37,18 @@ def hyper(rb):
         samples[name] = (qn, host_subindex(index, pr))
     torch.cuda.empty_cache()
     h = rb.rago_index_wrap(index, 0)
-    del index["codes"]
-    torch.cuda.empty_cache()
     print("[fullsize] index wrapped", flush=True)
+    # (the generator's plain arrays stay: the Euclidean test at the end of this file wraps them once more, after
+    # freeing this handle - two laid-out copies of the codes would not fit beside them)
+    state = {"h": h, "index": index, "cen": cen}
+    _HYPER_STATE.update(state=state)
     yield cfg, h, Q, Qi, samples
-    rb.rago_index_free(h)
+    if state["h"] is not None:
+        rb.rago_index_free(state["h"])
+    _HYPER_STATE.clear()
+
+
+_HYPER_STATE = {}
 
 
 def test_hyperscale_batch_matches_oracle_on_samples(hyper, rb):
@@ -170,3 +177,29 @@ def test_flat_full_size_matches_oracle_on_samples(rb):
     oi, osc = oracle.flat_search(cb, qb, cfg.k, fmt="f16")
     assert np.max(np.abs(hs[r] - osc[0])) < 1e-4
     assert np.mean([len(set(hi[r, q].tolist()) & set(oi[0, q].tolist())) / cfg.k for q in range(cfg.nq)]) >= 0.999
+
+
+def test_hyperscale_batch_under_the_euclidean_metric(hyper, rb):
+    """The same billion-vector arrays wrapped with the Euclidean metric (per-pair tables built on the matrix cores, the
+    wide scan fed full tables): 8 sampled queries of the 1024 x 128 x 100 batch against the oracle.  Runs last in this
+    file: it frees the inner-product handle first."""
+    cfg, h, Q, Qi, samples = hyper
+    state = _HYPER_STATE["state"]
+    rb.rago_index_free(state["h"])
+    state["h"] = None
+    torch.cuda.empty_cache()
+    h2 = rb.rago_index_wrap(state["index"], 0, metric="l2")
+    try:
+        ns = 8
+        qn = Q[:ns].cpu().numpy()
+        pr = oracle.select(oracle.coarse(qn, state["cen"], metric="l2"), cfg.nprobe)
+        sub = host_subindex(state["index"], pr)
+        ids, scores, isc = rb.rago_ivfpq_search(h2, Q, cfg.nprobe, cfg.k)
+        torch.cuda.synchronize()
+        ref = oracle.ivfpq_search(qn, sub, cfg.nprobe, cfg.k, metric="l2")
+        assert np.array_equal(ids[:ns].cpu().numpy(), ref["ids"]) and np.array_equal(isc[:ns].cpu().numpy(), ref["iscores"])
+        assert np.array_equal(scores[:ns].cpu().numpy(), ref["scores"])
+        assert bool((scores <= 0).all())                     # similarities are minus squared distances
+        assert rb.rago_debug_counters(h2)[3] == 0
+    finally:
+        rb.rago_index_free(h2)
