@@ -203,3 +203,33 @@ def test_hyperscale_batch_under_the_euclidean_metric(hyper, rb):
         assert rb.rago_debug_counters(h2)[3] == 0
     finally:
         rb.rago_index_free(h2)
+
+
+def test_hyperscale_batch_with_4bit_codes(hyper, rb):
+    """A billion-vector index with 4-bit codes (192 sub-quantisers of 16 codewords = the same 96 bytes per vector):
+    8 sampled queries of the 1024 x 128 x 100 batch against the oracle.  Frees what the tests before it hold first
+    (two billion-vector indexes do not fit side by side)."""
+    state = _HYPER_STATE["state"]
+    if state["h"] is not None:
+        rb.rago_index_free(state["h"])
+        state["h"] = None
+    state["index"].clear()
+    torch.cuda.empty_cache()
+    cfg = synth.HYPER.scaled(m=192, ksub=16)
+    print(f"[fullsize] building {cfg.name} with 4-bit codes: n={cfg.n} nlist={cfg.nlist}", flush=True)
+    index = synth.build_index(cfg, device="cuda:0", keep_vectors=False)
+    Q = synth.make_queries(cfg, cfg.nq, device="cuda:0")
+    ns = 8
+    qn = Q[:ns].cpu().numpy()
+    sub = host_subindex(index, oracle.select(oracle.coarse(qn, index["centroids"].cpu().numpy()), cfg.nprobe))
+    torch.cuda.empty_cache()
+    h = rb.rago_index_wrap(index, 0)
+    try:
+        ids, scores, isc = rb.rago_ivfpq_search(h, Q, cfg.nprobe, cfg.k)
+        torch.cuda.synchronize()
+        ref = oracle.ivfpq_search(qn, sub, cfg.nprobe, cfg.k)
+        assert np.array_equal(ids[:ns].cpu().numpy(), ref["ids"]) and np.array_equal(isc[:ns].cpu().numpy(), ref["iscores"])
+        assert np.array_equal(scores[:ns].cpu().numpy(), ref["scores"])
+        assert rb.rago_debug_counters(h)[3] == 0
+    finally:
+        rb.rago_index_free(h)
