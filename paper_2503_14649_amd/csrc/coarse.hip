@@ -159,35 +159,39 @@ int launch_split_centroids(rago_index* idx, hipStream_t st) {
 // nqt workgroups that share a centroid tile are dispatched back to back onto the same XCD
 // (workgroups go round-robin over the 8 XCDs), so the tile is fetched from HBM once and then
 // served by that XCD's L2.
+// TM = query rows per workgroup: 128 (a wave takes 64 x 64), or 64 (a wave takes 64 x 32) for batches that would
+// otherwise leave a workgroup alone on its compute unit with nothing to hide its loads behind.
+template <int TM>
 __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
                                                                 const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
                                                                 int nct, const float* __restrict__ qn2,
                                                                 const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
     if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;   // (the selection's counter of queued queries)
     extern __shared__ __align__(16) uint16_t x_smem[];
-    uint16_t *Ah = x_smem, *Al = Ah + X_T * X_LS, *Bh = Al + X_T * X_LS, *Bl = Bh + X_T * X_LS;
+    uint16_t *Ah = x_smem, *Al = Ah + TM * X_LS, *Bh = Al + TM * X_LS, *Bl = Bh + X_T * X_LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int r8 = blockIdx.x >> 3;
     const int ct = (r8 / nqt) * 8 + (blockIdx.x & 7), qt = r8 % nqt;
     if (ct >= nct) return;
-    const int n0 = ct * X_T, m0 = qt * X_T;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    constexpr int NBT = TM == 128 ? 2 : 1;          // 32-column tiles per wave
+    const int n0 = ct * X_T, m0 = qt * TM;
+    const int wm = TM == 128 ? (wave >> 1) * 64 : 0, wn = TM == 128 ? (wave & 1) * 64 : wave * 32;
 
-    v16f acc[2][2];
+    v16f acc[2][NBT];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NBT; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    constexpr int NA = X_KT / 8, NB = X_KT / 16;       // 16-byte loads per thread and K tile: A (fp32), B (bf16, hi and lo)
+    constexpr int NA = TM * (X_KT / 4) / 256, NB = X_KT / 16;       // 16-byte loads per thread and K tile: A (fp32), B (bf16, hi and lo)
     float4 pa[NA];
     uint4 pbh[NB], pbl[NB];
     auto gload = [&](int k0) {
 #pragma unroll
-        for (int r = 0; r < NA; ++r) {         // A: 128 rows x (X_KT / 4) float4
+        for (int r = 0; r < NA; ++r) {         // A: TM rows x (X_KT / 4) float4
             const int f = tid + 256 * r, row = f / (X_KT / 4), c4 = f % (X_KT / 4);
             const int gr = min(m0 + row, nq - 1), gk = k0 + c4 * 4;
             pa[r] = gk < d ? *reinterpret_cast<const float4*>(Q + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -227,7 +231,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
         if (k0 + X_KT < d) gload(k0 + X_KT);
 #pragma unroll
         for (int ks = 0; ks < X_KT / 16; ++ks) {
-            bf16x8 ah[2], al[2], bh[2], bl[2];
+            bf16x8 ah[2], al[2], bh[NBT], bl[NBT];
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 const int o = (wm + a * 32 + i32) * X_LS + ks * 16 + h * 8;
@@ -235,7 +239,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
                 al[a] = *reinterpret_cast<const bf16x8*>(Al + o);
             }
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
+            for (int b = 0; b < NBT; ++b) {
                 const int o = (wn + b * 32 + i32) * X_LS + ks * 16 + h * 8;
                 bh[b] = *reinterpret_cast<const bf16x8*>(Bh + o);
                 bl[b] = *reinterpret_cast<const bf16x8*>(Bl + o);
@@ -243,7 +247,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int b = 0; b < NBT; ++b) {
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
@@ -254,7 +258,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NBT; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -357,13 +361,22 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
     } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
         coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else {
-        const int nqt = (int)((nq + X_T - 1) / X_T), nct = (nlist + X_T - 1) / X_T;
+        // query rows per workgroup: 64 while 128 would give the chip fewer than two workgroups per compute unit
+        const int nct = (nlist + X_T - 1) / X_T;
+        const bool half_tile = (int64_t)((nq + X_T - 1) / X_T) * nct < 2 * (int64_t)idx->n_cu;
+        const int tm = half_tile ? 64 : X_T;
+        const int nqt = (int)((nq + tm - 1) / tm);
         const int64_t grid = (int64_t)((nct + 7) / 8) * 8 * nqt;
         if (grid > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq * nlist too large");
         static OncePerDevice attr;
-        if (attr.first())
-            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
-        coarse_gemm_split_kernel<<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
+        if (attr.first()) {
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
+        }
+        if (half_tile)
+            coarse_gemm_split_kernel<64><<<(unsigned)grid, 256, (64 * 2 + X_T * 2) * X_LS * 2, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
+        else
+            coarse_gemm_split_kernel<128><<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;

@@ -111,6 +111,22 @@ def test_coarse_and_select_by_batch_size(rb, nq):
     rb.rago_index_free(h)
 
 
+def test_coarse_with_enough_tiles_for_the_128_row_kernel(rb):
+    """The split-bf16 kernel takes 64 query rows per workgroup while 128 would leave the chip short of workgroups;
+    1100 queries on 7300 lists (9 x 58 tiles of 128) is past that point on 256 compute units, both edges ragged."""
+    ix = to_np(synth.random_index(n=20000, d=80, m=16, nlist=7300, seed=79))
+    Q = _queries(1100, 80, 7)
+    h = rb.rago_index_wrap(dev_index(ix))
+    S = oracle.coarse(Q, ix["centroids"])
+    gS = rb.rago_debug_coarse(h, torch.from_numpy(Q).cuda())
+    scale = np.linalg.norm(Q, axis=1)[:, None] * np.linalg.norm(ix["centroids"], axis=1)[None, :]
+    assert np.max(np.abs(gS.cpu().numpy() - S) / scale) < 1e-4
+    gp = rb.rago_debug_select(h, torch.from_numpy(Q).cuda(), gS, 20).cpu().numpy()
+    assert np.array_equal(gp, oracle.select(S, 20))
+    assert rb.rago_debug_counters(h)[3] == 0
+    rb.rago_index_free(h)
+
+
 def test_select_equals_oracle(case, rb):
     ix, Q, nprobe, k, h = case
     S = oracle.coarse(Q, ix["centroids"])
