@@ -827,11 +827,12 @@ template <int NT>
 __global__ void __launch_bounds__(NT) merge_kernel(const ScanParams P, const float* __restrict__ delta,
                                                               int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
                                                               int32_t* __restrict__ out_iscores) {
-    __shared__ int32_t sI[MERGE_CAP];
+    __shared__ __align__(16) int32_t sI[MERGE_CAP];
     __shared__ int64_t sId[MERGE_CAP];
     __shared__ int s_cnt;
     constexpr int MERGE_TILE = 2048;
     __shared__ __align__(8) int s_slot[MERGE_TILE];      // per slot of the current tile: (place in the result arrays << 8) | entries
+    static_assert(MERGE_TILE >= 3 * RANK_CAND + 1 && MERGE_CAP >= 1024 + 4, "rank_top_k's side buffer and padding");
     const int q = blockIdx.x, k = P.k;
     int32_t tau = P.tauq[q];   // k candidates of this query reach tau: nothing below can be in the result
     // Slots = (probe, chunk) pairs that exist: chunk counts per probe are prefix-summed in LDS
@@ -965,25 +966,8 @@ __global__ void __launch_bounds__(NT) merge_kernel(const ScanParams P, const flo
         return s_cnt;
     };
     auto sort_keep_k = [&](int have) {
-        if (NT >= 1024 && have <= NT && have > 1) {
-            // one entry per thread: its rank is the number of entries that come before it (entries are distinct:
-            // a vector lies in one list and one chunk); ranks below k are the result, already in order
-            int32_t* oI = reinterpret_cast<int32_t*>(s_slot);                 // [k]   (the tile words are no longer needed)
-            int64_t* oId = reinterpret_cast<int64_t*>(s_slot + 256);          // [k]
-            const int t = threadIdx.x;
-            int32_t mi = 0; int64_t md = 0; int before = 0;
-            if (t < have) {
-                mi = sI[t]; md = sId[t];
-#pragma unroll 8
-                for (int j = 0; j < have; ++j) before += entry_before(sI[j], sId[j], mi, md) ? 1 : 0;
-                if (before < k) { oI[before] = mi; oId[before] = md; }
-            }
-            __syncthreads();
-            const int keep = min(have, k);
-            if (t < keep) { sI[t] = oI[t]; sId[t] = oId[t]; }
-            __syncthreads();
-            return keep;
-        }
+        // (the tile words are no longer needed)
+        if (NT >= 1024 && have <= NT && have > 1 && rank_top_k(sI, sId, have, k, s_slot)) return min(have, k);
         int n2 = 1;
         while (n2 < have) n2 <<= 1;
         for (int i = have + threadIdx.x; i < n2; i += NT) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }

@@ -142,6 +142,57 @@ __device__ inline void bitonic_sort(int32_t* sI, int64_t* sId, int n2) {
     __syncthreads();
 }
 
+// The best k of sI/sId[0..have), have <= blockDim.x, into sI/sId[0..min(have, k)) in order, one entry per thread and
+// without a sorting network.  First by score alone: an entry with k or more strictly better scores above it cannot be
+// in the result; the others (k plus ties at the k-th score) move to a side buffer.  Then a full rank among those:
+// every entry of the result has only entries of the result before it, so its rank there is its place.  (Equal entries
+// - an id the caller stored twice - rank by position, so every place is taken once.)  Returns false, with the first
+// `have` entries untouched, when more than RANK_CAND entries reach the side buffer (massive ties).
+// sI: 16-byte aligned, room for have + 4 entries; tmp: 3 * RANK_CAND + 1 words of LDS, 8-byte aligned.
+constexpr int RANK_CAND = 256;
+__device__ inline bool rank_top_k(int32_t* sI, int64_t* sId, int have, int k, int32_t* tmp) {
+    int32_t* cI = tmp;
+    int64_t* cId = reinterpret_cast<int64_t*>(tmp + RANK_CAND);
+    int* nc = tmp + 3 * RANK_CAND;
+    const int t = threadIdx.x;
+    if (t == 0) *nc = 0;
+    if (t < 4) sI[have + t] = INT32_MIN;             // the scores are read four at a time
+    __syncthreads();
+    int32_t mi = 0;
+    int64_t md = 0;
+    bool cand = false;
+    if (t < have) {
+        mi = sI[t]; md = sId[t];
+        int gt = 0;
+#pragma unroll 4
+        for (int j = 0; j < have; j += 4) {
+            const int4 v = *reinterpret_cast<const int4*>(sI + j);
+            gt += (v.x > mi ? 1 : 0) + (v.y > mi ? 1 : 0) + (v.z > mi ? 1 : 0) + (v.w > mi ? 1 : 0);
+        }
+        cand = gt < k;
+    }
+    if (cand) {
+        const int o = atomicAdd(nc, 1);
+        if (o < RANK_CAND) { cI[o] = mi; cId[o] = md; }
+    }
+    __syncthreads();
+    const int n = *nc;
+    if (n > RANK_CAND) return false;
+    if (t < n) {
+        mi = cI[t]; md = cId[t];
+        int before = 0;
+#pragma unroll 8
+        for (int j = 0; j < n; ++j) {
+            const int32_t oi = cI[j];
+            const int64_t od = cId[j];
+            before += entry_before(oi, od, mi, md) || (oi == mi && od == md && j < t) ? 1 : 0;
+        }
+        if (before < k) { sI[before] = mi; sId[before] = md; }
+    }
+    __syncthreads();
+    return true;
+}
+
 // scan_narrow.hip: the two-pairs-per-pass kernel on 2 * n_cu workgroups (task records with 1 or 2 pairs)
 int launch_scan_narrow(const ScanParams& P, int n_cu, hipStream_t st);
 

@@ -671,20 +671,25 @@ struct TopK {
     int64_t* sId;
     int* s_cnt;
     int k;
+    int32_t* tmp;        // LDS for rank_top_k, the one-entry-per-thread path (may be null)
     // sort the first `have` entries of the buffer, keep k
     __device__ int sort_keep_k(int have) {
+        if (tmp && have <= (int)blockDim.x && have > 1 && rank_top_k(sI, sId, have, k, tmp)) return min(have, k);
         int n2 = 1;
         while (n2 < have) n2 <<= 1;
-        for (int i = have + threadIdx.x; i < n2; i += MERGE_THREADS) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
+        for (int i = have + threadIdx.x; i < n2; i += blockDim.x) { sI[i] = INT32_MIN; sId[i] = INT64_MAX; }
         if (n2 > 1) bitonic_sort(sI, sId, n2); else __syncthreads();
         return min(have, k);
     }
 };
 
-__global__ void __launch_bounds__(MERGE_THREADS) merge_slots_kernel(const WaveParams W, const float* __restrict__ delta,
-                                                                    int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
-                                                                    int32_t* __restrict__ out_iscores) {
-    __shared__ int32_t sI[MERGE_CAP];
+// NT threads: 256, or 1024 while the batch has no more workgroups than the chip has room for (the walks over the slots are
+// chains of dependent round trips, four times shorter then).
+template <int NT>
+__global__ void __launch_bounds__(NT) merge_slots_kernel(const WaveParams W, const float* __restrict__ delta,
+                                                         int64_t* __restrict__ out_ids, float* __restrict__ out_scores,
+                                                         int32_t* __restrict__ out_iscores) {
+    __shared__ __align__(16) int32_t sI[MERGE_CAP];
     __shared__ int64_t sId[MERGE_CAP];
     __shared__ int s_cnt;
     const ScanParams& P = W.S;
@@ -694,112 +699,111 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_slots_kernel(const WavePa
     const int per = (nitems + W.nslice - 1) / W.nslice;
     const int i0 = slice * per, i1 = min(nitems, i0 + per);
     const int64_t slot0 = (int64_t)q * W.qslots;
-    TopK T{sI, sId, &s_cnt, k};
+    TopK T{sI, sId, &s_cnt, k, nullptr};
     // Every entry of the slots [a, b), in tiles of MS_TILE slots: a thread per slot reads the slot's count into LDS, then the
     // tile's entries are walked as ONE flat array (entry f = slot f / k, position f % k; positions beyond a slot's count
     // are stale and skipped): neighbouring lanes read neighbouring words, four loads per lane in flight.  (Sharing out
     // only the live entries needs a search per entry and left one dependent load per trip round the loop: the three
     // passes of a query's ~190 slots x 100 entries took 53 us.)  f(score, position in the result arrays).
     constexpr int MS_TILE = 1024;
-    __shared__ int s_n[MS_TILE];
+    __shared__ __align__(8) int s_n[MS_TILE];
     __shared__ int s_max;
+    static_assert(MS_TILE >= 3 * RANK_CAND + 1, "the slot counts' words double as the ranking path's side buffer");
+    if (NT >= 1024) T.tmp = s_n;          // (with fewer threads the buffer seldom fits one entry per thread)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     auto each_entry = [&](int a, int b, auto f) {
         for (int t0 = a; t0 < b; t0 += MS_TILE) {
             const int ts = min(MS_TILE, b - t0);
             __syncthreads();
-            for (int j = threadIdx.x; j < ts; j += MERGE_THREADS) s_n[j] = P.part_cnt[slot0 + t0 + j];
+            for (int j = threadIdx.x; j < ts; j += NT) s_n[j] = P.part_cnt[slot0 + t0 + j];
             __syncthreads();
             const int total = ts * k;
             const int64_t base = (slot0 + t0) * k;
             constexpr int U = 4;
-            for (int f0 = threadIdx.x; f0 < total; f0 += MERGE_THREADS * U) {
+            for (int f0 = threadIdx.x; f0 < total; f0 += NT * U) {
                 int32_t I[U];
                 bool live[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int fi = min(f0 + u * MERGE_THREADS, total - 1);
+                    const int fi = min(f0 + u * NT, total - 1);
                     const int j = fi / k;
-                    live[u] = f0 + u * MERGE_THREADS < total && fi - j * k < s_n[j];
+                    live[u] = f0 + u * NT < total && fi - j * k < s_n[j];
                     I[u] = P.part_I[base + fi];
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (live[u]) f(I[u], base + f0 + u * MERGE_THREADS);
+                    if (live[u]) f(I[u], base + f0 + u * NT);
             }
         }
     };
-    // entries that reach tau, appended behind the first base_fill entries of the buffer
+    // entries that reach tau, appended behind the first base_fill entries of the buffer; returns how many reach it (those
+    // beyond the buffer's capacity are counted, not kept) and leaves the largest margin over tau in s_max
     auto gather = [&](int a, int b, int base_fill) {
-        if (threadIdx.x == 0) s_cnt = base_fill;
+        if (threadIdx.x == 0) { s_cnt = base_fill; s_max = 0; }
         __syncthreads();
+        int mx = 0;
         each_entry(a, b, [&](int32_t I, int64_t at) {
             if (I >= tau) {
+                mx = max(mx, (int)min((int64_t)I - tau, (int64_t)0x7fffffff));
                 const int o = atomicAdd(&s_cnt, 1);
                 if (o < MERGE_CAP) { sI[o] = I; sId[o] = P.ids[P.part_row[at]]; }
             }
         });
+        for (int o = 32; o; o >>= 1) mx = max(mx, __shfl_xor(mx, o));
+        if (lane == 0 && mx > 0) atomicMax(&s_max, mx);
         __syncthreads();
         return s_cnt;
     };
-    // The bound the scan leaves is the best k-th score of a single item, which is weak when lists are short and k is
-    // large: most entries then pass it.  If more pass than the buffer holds, a histogram of their scores gives a bound
-    // with at least k entries at or above it that is within one bin of the slice's true k-th score.
-    {
-        if (threadIdx.x == 0) { s_cnt = 0; s_max = 0; }
+    // Optimistic: everything that passes tau fits the buffer (the usual case by far).  The bound the scan leaves is the
+    // best k-th score of a single item, which is weak when lists are short and k is large: if more entries pass it than
+    // the buffer holds, a histogram of their scores gives a bound with at least k entries at or above it that is within
+    // one bin of the slice's true k-th score, and the entries are gathered again.
+    int have = gather(i0, i1, 0);
+    if (have > MERGE_CAP) {
+        const int maxd = s_max;
         __syncthreads();
-        int c = 0, mx = 0;
+        constexpr int BINS = 1024;
+        int* hist = reinterpret_cast<int*>(sI);                  // (what the buffer holds is gathered again below)
+        int shift = 0;
+        while ((maxd >> shift) >= BINS) ++shift;
+        for (int i = threadIdx.x; i < BINS; i += NT) hist[i] = 0;
+        __syncthreads();
         each_entry(i0, i1, [&](int32_t I, int64_t) {
-            if (I >= tau) { ++c; mx = max(mx, (int)min((int64_t)I - tau, (int64_t)0x7fffffff)); }
+            if (I >= tau) atomicAdd(&hist[(int)(((int64_t)I - tau) >> shift)], 1);
         });
-        for (int o = 32; o; o >>= 1) { c += __shfl_xor(c, o); mx = max(mx, __shfl_xor(mx, o)); }
-        if (lane == 0) { atomicAdd(&s_cnt, c); atomicMax(&s_max, mx); }
         __syncthreads();
-        const int passing = s_cnt, maxd = s_max;
-        __syncthreads();
-        if (passing > MERGE_CAP) {
-            constexpr int BINS = 1024;
-            int* hist = reinterpret_cast<int*>(sI);                  // (the buffer is not in use yet)
-            int shift = 0;
-            while ((maxd >> shift) >= BINS) ++shift;
-            for (int i = threadIdx.x; i < BINS; i += MERGE_THREADS) hist[i] = 0;
-            __syncthreads();
-            each_entry(i0, i1, [&](int32_t I, int64_t) {
-                if (I >= tau) atomicAdd(&hist[(int)(((int64_t)I - tau) >> shift)], 1);
-            });
-            __syncthreads();
-            // the highest bin with at least k entries in it and above: thread t owns bins 4t .. 4t + 3
-            __shared__ int s_wsum[MERGE_THREADS / 64];
-            __shared__ int s_bin;
-            const int t = threadIdx.x;
-            const int h0 = hist[4 * t], h1 = hist[4 * t + 1], h2 = hist[4 * t + 2], h3 = hist[4 * t + 3];
-            int sfx = h0 + h1 + h2 + h3;
-            for (int o = 1; o < 64; o <<= 1) {
-                const int v = __shfl_down(sfx, o);
-                if (lane + o < 64) sfx += v;
-            }
-            if (lane == 0) s_wsum[wave] = sfx;
-            if (t == 0) s_bin = 0;
-            __syncthreads();
-            int above = 0;
-            for (int w = wave + 1; w < MERGE_THREADS / 64; ++w) above += s_wsum[w];
-            const int mine = sfx + above;                            // entries in bins >= 4t
-            const int next = mine - (h0 + h1 + h2 + h3);             // entries in bins >= 4t + 4
-            if (mine >= k && next < k) {                             // exactly one thread
-                int cum = next, bsel = 4 * t;
-                const int hh[4] = {h0, h1, h2, h3};
-                for (int i = 3; i >= 0; --i) {
-                    cum += hh[i];
-                    if (cum >= k) { bsel = 4 * t + i; break; }
-                }
-                s_bin = bsel;
-            }
-            __syncthreads();
-            tau += (int32_t)((int64_t)s_bin << shift);
-            __syncthreads();
+        // the highest bin with at least k entries in it and above: thread t < 256 owns bins 4t .. 4t + 3
+        __shared__ int s_wsum[NT / 64];
+        __shared__ int s_bin;
+        const int t = threadIdx.x;
+        const bool own = t < BINS / 4;
+        const int h0 = own ? hist[4 * t] : 0, h1 = own ? hist[4 * t + 1] : 0, h2 = own ? hist[4 * t + 2] : 0, h3 = own ? hist[4 * t + 3] : 0;
+        int sfx = h0 + h1 + h2 + h3;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_down(sfx, o);
+            if (lane + o < 64) sfx += v;
         }
+        if (lane == 0) s_wsum[wave] = sfx;
+        if (t == 0) s_bin = 0;
+        __syncthreads();
+        int above = 0;
+        for (int w = wave + 1; w < NT / 64; ++w) above += s_wsum[w];
+        const int mine = sfx + above;                            // entries in bins >= 4t
+        const int next = mine - (h0 + h1 + h2 + h3);             // entries in bins >= 4t + 4
+        if (mine >= k && next < k) {                             // exactly one thread
+            int cum = next, bsel = 4 * t;
+            const int hh[4] = {h0, h1, h2, h3};
+            for (int i = 3; i >= 0; --i) {
+                cum += hh[i];
+                if (cum >= k) { bsel = 4 * t + i; break; }
+            }
+            s_bin = bsel;
+        }
+        __syncthreads();
+        tau += (int32_t)((int64_t)s_bin << shift);
+        __syncthreads();
+        have = gather(i0, i1, 0);
     }
-    int have = gather(i0, i1, 0);   // optimistic: everything that passes tau fits the buffer (the usual case by far)
     int fill;
     if (have <= MERGE_CAP) {
         fill = T.sort_keep_k(have);
@@ -816,13 +820,13 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_slots_kernel(const WavePa
     __syncthreads();
     if (W.nslice > 1) {
         const int64_t o = ((int64_t)q * W.nslice + slice) * k;
-        for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+        for (int r = threadIdx.x; r < k; r += NT) {
             W.stage_I[o + r] = r < fill ? sI[r] : INT32_MIN;
             W.stage_id[o + r] = r < fill ? sId[r] : -1;
         }
         return;
     }
-    for (int r = threadIdx.x; r < k; r += MERGE_THREADS) {
+    for (int r = threadIdx.x; r < k; r += NT) {
         const bool ok = r < fill;
         const int32_t I = ok ? sI[r] : INT32_MIN;
         out_ids[(int64_t)q * k + r] = ok ? sId[r] : -1;
@@ -841,7 +845,7 @@ __global__ void __launch_bounds__(MERGE_THREADS) merge_stage2_kernel(const WaveP
     const int q = blockIdx.x, k = W.S.k;
     const int64_t o = (int64_t)q * W.nslice * k;
     const int n = W.nslice * k;
-    TopK T{sI, sId, &s_cnt, k};
+    TopK T{sI, sId, &s_cnt, k, nullptr};
     int fill = 0;
     const int per_round = MERGE_CAP - k;                         // entries per round that cannot overflow the buffer
     for (int a = 0; a < n; a += per_round) {
@@ -950,7 +954,8 @@ int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, v
     }
     if (rc) return rc;
     if (ev) RAGO_HIP(hipEventRecord(ev[5], st));
-    merge_slots_kernel<<<(unsigned)(nq * W.nslice), MERGE_THREADS, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
+    if (nq * W.nslice <= 2 * n_cu) merge_slots_kernel<1024><<<(unsigned)(nq * W.nslice), 1024, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
+    else merge_slots_kernel<MERGE_THREADS><<<(unsigned)(nq * W.nslice), MERGE_THREADS, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
     if (W.nslice > 1) merge_stage2_kernel<<<(unsigned)nq, MERGE_THREADS, 0, st>>>(W, delta, out_ids, out_scores, out_iscores);
     RAGO_HIP(hipGetLastError());
     if (ev) RAGO_HIP(hipEventRecord(ev[6], st));
