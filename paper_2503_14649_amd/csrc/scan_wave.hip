@@ -157,7 +157,9 @@ __device__ __forceinline__ uint32_t code_of(const uint4 (&w)[MPAD / 16], int j, 
 
 // One probed list of one query: where its codes and rows start, how long it is, and the query-local number of
 // its first item.
-struct PairDesc { int64_t blk0, row0; int32_t nblk, len, pre, pad; };   // 32 bytes
+// 32 bytes.  The descriptors of a query stand in the order its items are handed out (plan_kernel), `pair` says whose
+// they are: probe number `pair` of the query.
+struct PairDesc { int64_t blk0, row0; int32_t nblk, len, pre, pair; };
 
 struct WaveParams {
     ScanParams S;              // codes, tables, nprobe, k, CH (= blocks per item), maxchunks; part_* = per-item result slots
@@ -447,7 +449,7 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
         pd.blk0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.y) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.x);
         pd.row0 = ((int64_t)__builtin_amdgcn_readfirstlane(a.w) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(a.z);
         pd.nblk = __builtin_amdgcn_readfirstlane(b.x); pd.len = __builtin_amdgcn_readfirstlane(b.y);
-        pd.pre = __builtin_amdgcn_readfirstlane(b.z); pd.pad = 0;
+        pd.pre = __builtin_amdgcn_readfirstlane(b.z); pd.pair = __builtin_amdgcn_readfirstlane(b.w);
         return pd;
     };
 
@@ -545,9 +547,8 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
                     const int mid = (lo + hi) >> 1;
                     if (s_pre[mid] <= ii) lo = mid; else hi = mid;
                 }
-                const int64_t pair = (int64_t)q * nprobe + lo;
-                const PairDesc pd = load_pdesc(pair);
-                return item_of(pd, (int)pair, ii - pd.pre, valid);
+                const PairDesc pd = load_pdesc((int64_t)q * nprobe + lo);
+                return item_of(pd, q * nprobe + pd.pair, ii - pd.pre, valid);
             };
             if (nunits > 0) {
                 int i_cur = claim();
@@ -575,10 +576,10 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
                 __syncthreads();
                 const int p = __builtin_amdgcn_readfirstlane(sh[0]);
                 if (p >= nunits) break;
-                const int64_t pair = (int64_t)q * nprobe + p;
+                const PairDesc pd = load_pdesc((int64_t)q * nprobe + p);
+                const int64_t pair = (int64_t)q * nprobe + pd.pair;
                 if (P.lut8sw) install_table<planes>(P.lut8sw + pair * LUT_BYTES, lut);
                 else eval_table(P, (int)pair, q, lut);
-                const PairDesc pd = load_pdesc(pair);
                 const int nchunks = (pd.nblk + CH - 1) / CH;
                 __syncthreads();
                 for (;;) {
@@ -609,14 +610,15 @@ __global__ void __launch_bounds__(256) plan_kernel(const int32_t* __restrict__ p
     __shared__ int s_w[4];
     __shared__ int s_carry;
     __shared__ unsigned long long s_bytes[2];
+    __shared__ int s_key[256];
+    __shared__ PairDesc s_pd[256];
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) { s_carry = 0; s_bytes[0] = 0; s_bytes[1] = 0; }
     if (q == 0 && tid < 3) counters[tid] = 0;          // (the scan kernel adds the batch's totals)
     __syncthreads();
     unsigned long long streamed = 0, algo = 0;
     for (int p0 = 0; p0 < nprobe; p0 += 256) {
-        const int p = p0 + tid;
-        int n = 0;
+        const int p = p0 + tid, np = min(256, nprobe - p0);
         PairDesc pd = {0, 0, 0, 0, 0, 0};
         if (p < nprobe) {
             const int l = probes[(int64_t)q * nprobe + p];
@@ -624,10 +626,26 @@ __global__ void __launch_bounds__(256) plan_kernel(const int32_t* __restrict__ p
             pd.row0 = list_off[l];
             pd.nblk = (int)(blk_off[l + 1] - pd.blk0);
             pd.len = (int)(list_off[l + 1] - pd.row0);
-            n = (pd.nblk + CH - 1) / CH;
+            pd.pair = p;
             streamed += (unsigned long long)pd.nblk * (BLOCK_VECS * m);
             algo += (unsigned long long)pd.len * m;
         }
+        // Longest first among these (up to) 256 pairs: a query's items are handed out in this order, and what its
+        // waves wait for at the end - the last items still running - are then the short ones.
+        s_key[tid] = pd.nblk;
+        __syncthreads();
+        if (p < nprobe) {
+            int pos = 0;
+#pragma unroll 8
+            for (int j = 0; j < np; ++j) {
+                const int o = s_key[j];
+                pos += o > pd.nblk || (o == pd.nblk && j < tid) ? 1 : 0;
+            }
+            s_pd[pos] = pd;
+        }
+        __syncthreads();
+        if (p < nprobe) pd = s_pd[tid];
+        const int n = p < nprobe ? (pd.nblk + CH - 1) / CH : 0;
         int inc = n;
         for (int o = 1; o < 64; o <<= 1) {
             const int v = __shfl_up(inc, o);

@@ -368,6 +368,26 @@ def test_select_with_scores_packed_inside_the_rounding_error(rb, metric, nlist):
         rb.rago_index_free(h)
 
 
+@pytest.mark.parametrize("nq,nlist,nprobe", [(128, 40, 7), (300, 500, 33), (700, 64, 64)])
+def test_many_queries_through_the_wave_kernel(rb, nq, nlist, nprobe):
+    """Batches with as many queries as the wave-per-item kernel has workgroups, and more: a workgroup then serves one
+    query after another (its items are handed out longest list first), queries without items (empty lists) among them."""
+    ix = to_np(synth.random_index(n=20000, d=64, m=32, nlist=nlist, seed=61, shuffle_ids=True, empty_lists=(1, 5)))
+    Q = _queries(nq, 64, 62)
+    h = rb.rago_index_wrap(dev_index(ix))
+    rb.rago_debug_force_scan_kernel("wave")
+    try:
+        for k in (1, 100):
+            r = oracle.ivfpq_search(Q, ix, nprobe, k)
+            gi, gs, gis = rb.rago_ivfpq_search(h, torch.from_numpy(Q).cuda(), nprobe, k)
+            assert np.array_equal(gi.cpu().numpy(), r["ids"]) and np.array_equal(gis.cpu().numpy(), r["iscores"])
+        c = rb.rago_debug_counters(h)
+        assert c[0] > 0 and c[1] >= c[2] > 0
+    finally:
+        rb.rago_debug_force_scan_kernel("auto")
+        rb.rago_index_free(h)
+
+
 def test_one_code_for_every_vector(rb, scan_kernel):
     """All vectors carry the same code: inside a list every score ties, and the order is by id alone."""
     ix = to_np(synth.random_index(n=6000, d=64, m=32, nlist=5, seed=41, shuffle_ids=True))
