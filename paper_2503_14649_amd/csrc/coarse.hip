@@ -696,9 +696,8 @@ __global__ void __launch_bounds__(SEL_THREADS) select_kernel(const float* __rest
 constexpr int SS_G = 16;            // workgroups per query at most (fewer when the batch fills the chip anyway)
 constexpr int SS_BINS = 4096;
 constexpr int SS_CAP = 1024;        // scores in and above the cut's bin that are ordered in LDS
-constexpr int SS_REG = 64;          // scores per thread: nlist <= 65536
+constexpr int SS_REG = 64;          // scores per thread at most: nlist <= 65536
 constexpr int SS_MAX_WANT = 512;    // nprobe + SEL_EXTRA
-constexpr int SS_RU = 2;            // rows of C a wave scores at a time
 
 // scratch in HBM, per index: exact scores [nq][SS_MAX_WANT], then a count per query of the workgroups that are done
 // (zero between launches: the last workgroup resets it)
@@ -719,6 +718,10 @@ __device__ __forceinline__ void rank_keys(const uint64_t* key, int n, int* rank,
     __syncthreads();
 }
 
+// REG = scores per thread (nlist <= REG * SEL_THREADS: a short row should not pay for 64 loads, clamped or not);
+// RU = rows of C a wave scores at a time (random rows from HBM, one round trip per round of the workgroup's waves:
+// a workgroup that has a query to itself takes its ~100 rows in one round, one of sixteen has only a few).
+template <int REG, int RU>
 __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                    const float* __restrict__ S, int nlist, int d, int nprobe,
                                                                    float max_cnorm, int metric, int32_t* __restrict__ probes,
@@ -739,13 +742,13 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
 
     // ---- the row, its range
     // (unconditional loads from a clamped index: a branch per element would make every load wait for the one before)
-    float v[SS_REG];
+    float v[REG];
     float lo = INFINITY, hi = -INFINITY;
     bool odd = false;
 #pragma unroll
-    for (int r = 0; r < SS_REG; ++r) v[r] = row[min(r * SEL_THREADS + tid, nlist - 1)];
+    for (int r = 0; r < REG; ++r) v[r] = row[min(r * SEL_THREADS + tid, nlist - 1)];
 #pragma unroll
-    for (int r = 0; r < SS_REG; ++r) {          // (a repeated last element changes neither the range nor `odd`)
+    for (int r = 0; r < REG; ++r) {          // (a repeated last element changes neither the range nor `odd`)
         lo = fminf(lo, v[r]); hi = fmaxf(hi, v[r]);
         odd |= !(fabsf(v[r]) <= 3.0e38f);       // not a number, or infinite
     }
@@ -763,7 +766,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
     auto bin_of = [&](float x) { return (int)fminf(fmaxf((x - lo) * scale, 0.f), (float)(SS_BINS - 1)); };
     if (!give_up) {
 #pragma unroll
-        for (int r = 0; r < SS_REG; ++r)
+        for (int r = 0; r < REG; ++r)
             if (r * SEL_THREADS + tid < nlist) atomicAdd(&hist[bin_of(v[r])], 1);
     }
     __syncthreads();
@@ -804,7 +807,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
     // by their exact 64-bit keys, the first `want` are chosen.
     const float floor_v = lo + (float)(s_bin - 1) / scale;
 #pragma unroll
-    for (int r = 0; r < SS_REG; ++r) {
+    for (int r = 0; r < REG; ++r) {
         const int i = r * SEL_THREADS + tid;
         const bool in = i < nlist && v[r] >= floor_v;
         const uint64_t m = __ballot(in);
@@ -830,11 +833,11 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
     const float* qv = Q + (int64_t)q * d;
     const bool vec4 = (d & 3) == 0;
     const int nmine = (want - g + G - 1) / G;
-    for (int c0 = wave * SS_RU; c0 < nmine; c0 += SEL_WAVES * SS_RU) {
-        double acc[SS_RU];
-        const float* cv[SS_RU];
+    for (int c0 = wave * RU; c0 < nmine; c0 += SEL_WAVES * RU) {
+        double acc[RU];
+        const float* cv[RU];
 #pragma unroll
-        for (int u = 0; u < SS_RU; ++u) {
+        for (int u = 0; u < RU; ++u) {
             acc[u] = 0.0;
             const int pos = g + min(c0 + u, nmine - 1) * G;
             cv[u] = C + (int64_t)(0xFFFFFFFFu - (uint32_t)sel_key[pos]) * d;
@@ -842,12 +845,12 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
         if (vec4) {
             for (int t = lane * 4; t < d; t += 256) {
                 const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
-                float4 c4[SS_RU];
+                float4 c4[RU];
 #pragma unroll
-                for (int u = 0; u < SS_RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
+                for (int u = 0; u < RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
                 const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
 #pragma unroll
-                for (int u = 0; u < SS_RU; ++u) {
+                for (int u = 0; u < RU; ++u) {
                     const double ca[4] = {(double)c4[u].x, (double)c4[u].y, (double)c4[u].z, (double)c4[u].w};
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
@@ -860,14 +863,14 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
             for (int t = lane; t < d; t += 64) {
                 const double qt = (double)qv[t];
 #pragma unroll
-                for (int u = 0; u < SS_RU; ++u) {
+                for (int u = 0; u < RU; ++u) {
                     if (metric == 1) { const double diff = qt - (double)cv[u][t]; acc[u] = acc[u] + diff * diff; }
                     else acc[u] = acc[u] + qt * (double)cv[u][t];
                 }
             }
         }
 #pragma unroll
-        for (int u = 0; u < SS_RU; ++u) {
+        for (int u = 0; u < RU; ++u) {
             for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
             if (lane == 0 && c0 + u < nmine)
                 __hip_atomic_store(&exact[g + (c0 + u) * G], metric == 1 ? (float)(-acc[u]) : (float)acc[u],
@@ -944,9 +947,16 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
     float* ss_exact = idx->ws.sel_small.as<float>();
     int* ss_done = idx->ws.sel_done.as<int>();      // (nothing else ever writes here: zero between launches)
     for (int redo = 0; redo < 2; ++redo) {
-        if (small && !redo)
-            select_small_kernel<<<dim3((unsigned)nq, ss_g), SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric,
-                                                                                  probes, cnt, rq, ss_exact, ss_done);
+        if (small && !redo) {
+            auto go = [&](auto kern) {
+                kern<<<dim3((unsigned)nq, ss_g), SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt,
+                                                                       rq, ss_exact, ss_done);
+            };
+            const bool alone = ss_g == 1;
+            if (nl <= 16 * SEL_THREADS) { if (alone) go(select_small_kernel<16, 6>); else go(select_small_kernel<16, 2>); }
+            else if (nl <= 32 * SEL_THREADS) { if (alone) go(select_small_kernel<32, 6>); else go(select_small_kernel<32, 2>); }
+            else { if (alone) go(select_small_kernel<64, 6>); else go(select_small_kernel<64, 2>); }
+        }
         else if (nl <= 8 * SEL_THREADS)
             select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
         else if (nl <= 32 * SEL_THREADS)

@@ -292,9 +292,10 @@ def test_select_with_massive_ties(rb, scan_kernel):
 
 @pytest.mark.parametrize("nlist,d", [(700, 48), (20000, 32), (65536, 32)])
 def test_select_for_few_queries(rb, nlist, d):
-    """Batches of up to 32 queries share each query among several workgroups (one histogram pass over a linear map
-    of the row's range, exact scores divided among the workgroups); 33 queries take the one-workgroup-per-query
-    kernel.  Both must give the oracle's probes, also when one outlying score squeezes all others into a few
+    """Small batches share each query among several workgroups (one histogram pass over a linear map of the row's
+    range, exact scores divided among the workgroups), fewer the more queries there are; from as many queries as the
+    chip has compute units a workgroup has a query to itself and scores more candidates at a time (260 queries).
+    The three row lengths take the kernel's three sizes of per-thread score arrays.  All must give the oracle's probes, also when one outlying score squeezes all others into a few
     histogram bins (the row is then handed to the exact second launch)."""
     g = np.random.default_rng(nlist)
     C = (g.standard_normal((nlist, d)) * 0.3).astype(np.float32)
@@ -302,7 +303,7 @@ def test_select_for_few_queries(rb, nlist, d):
     ix["centroids"] = C
     h = rb.rago_index_wrap(dev_index(ix))
     try:
-        for nq in (1, 2, 7, 32, 33):
+        for nq in (1, 2, 7, 32, 33, 260):
             Q = _queries(nq, d, 100 + nq)
             S = oracle.coarse(Q, C)
             Qd = torch.from_numpy(Q).cuda()
