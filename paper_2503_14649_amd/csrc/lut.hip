@@ -61,31 +61,47 @@ __device__ __forceinline__ double subdot(const float* __restrict__ a, const floa
 template <int DSUB>
 __global__ void __launch_bounds__(256) lut_Tt_kernel(const float* __restrict__ Q, const float* __restrict__ C, const float* __restrict__ CB,
                                                      const int32_t* __restrict__ probes, int64_t nq, int64_t npairs, int ppw, int d, int m,
-                                                     unsigned tg, double* __restrict__ T64, double* __restrict__ Tmin,
+                                                     unsigned tg, int qb, double* __restrict__ T64, double* __restrict__ Tmin,
                                                      double* __restrict__ Tmax, double* __restrict__ t64, int64_t* __restrict__ counters) {
     const int lane = threadIdx.x & 63;
     const int dsub = DSUB ? DSUB : d / m;
     if (blockIdx.x < tg) {
+        // a wave takes sub-quantiser j for `qb` consecutive queries: its codewords come from L2 once, not once per query
         const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-        if (w >= nq * m) return;
-        const int64_t q = w / m;
-        const int j = (int)(w - q * m);
+        const int64_t nqb = (nq + qb - 1) / qb;
+        if (w >= nqb * m) return;
+        const int64_t q0 = (w / m) * qb, q1 = q0 + qb < nq ? q0 + qb : nq;
+        const int j = (int)(w % m);
         if (w == 0 && lane == 0) { counters[4] = 0; counters[5] = 0; }
-        const float* qv = Q + q * d + j * dsub;
-        double mn = 0.0, mx = 0.0;
+        __attribute__((aligned(16))) float cw[4][DSUB ? DSUB : 4];
+        if constexpr (DSUB != 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = lane + 64 * i;
-            const double acc = subdot<DSUB>(qv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
-            T64[(q * m + j) * KSUB + c] = acc;
-            mn = i ? fmin(mn, acc) : acc;
-            mx = i ? fmax(mx, acc) : acc;
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int t = 0; t < DSUB; t += 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(CB + ((int64_t)j * KSUB + lane + 64 * i) * DSUB + t);
+                    cw[i][t] = x.x; cw[i][t + 1] = x.y; cw[i][t + 2] = x.z; cw[i][t + 3] = x.w;
+                }
         }
-        for (int o = 32; o; o >>= 1) {
-            mn = fmin(mn, __shfl_xor(mn, o));
-            mx = fmax(mx, __shfl_xor(mx, o));
+        for (int64_t q = q0; q < q1; ++q) {
+            const float* qv = Q + q * d + j * dsub;
+            double mn = 0.0, mx = 0.0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = lane + 64 * i;
+                double acc;
+                if constexpr (DSUB != 0) acc = subdot<DSUB>(qv, cw[i], dsub);
+                else acc = subdot<DSUB>(qv, CB + ((int64_t)j * KSUB + c) * dsub, dsub);
+                T64[(q * m + j) * KSUB + c] = acc;
+                mn = i ? fmin(mn, acc) : acc;
+                mx = i ? fmax(mx, acc) : acc;
+            }
+            for (int o = 32; o; o >>= 1) {
+                mn = fmin(mn, __shfl_xor(mn, o));
+                mx = fmax(mx, __shfl_xor(mx, o));
+            }
+            if (lane == 0) { Tmin[q * m + j] = mn; Tmax[q * m + j] = mx; }
         }
-        if (lane == 0) { Tmin[q * m + j] = mn; Tmax[q * m + j] = mx; }
         return;
     }
     const int64_t w = (int64_t)(blockIdx.x - tg) * 4 + (threadIdx.x >> 6);
@@ -454,13 +470,16 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     if ((rc = ws.counters.reserve(64))) return rc;
     if (idx->reserving) return RAGO_OK;
     const int ppw = npairs >= 32768 ? 8 : 1;
-    const unsigned tg = (unsigned)((nq * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
+    // queries per wave of the T part: eight once that still leaves every compute unit eight waves (256 queries x 96
+    // sub-quantisers: both kernels of this file 66 -> 57 us; 4 per wave the same, 16 per wave 64)
+    const int qb = nq * m >= (int64_t)64 * idx->n_cu ? 8 : 1;
+    const unsigned tg = (unsigned)(((nq + qb - 1) / qb * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
     // two launches: the per-query tables together with the per-pair scalars, then everything else of a query
     if (d / m == 8 && d % 4 == 0)        // (16-byte loads of the sub-vectors)
-        lut_Tt_kernel<8><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, ws.T64.as<double>(),
+        lut_Tt_kernel<8><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, qb, ws.T64.as<double>(),
                                                      ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
     else
-        lut_Tt_kernel<0><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, ws.T64.as<double>(),
+        lut_Tt_kernel<0><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, qb, ws.T64.as<double>(),
                                                      ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
     // (workgroups per query: enough to fill the chip on a small batch, at most one per 32 pairs)
     // workgroups per query: a wave per pair at a time; one round of pairs per workgroup while the batch leaves room
