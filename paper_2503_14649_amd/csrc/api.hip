@@ -8,6 +8,7 @@
 
 #include "rago_internal.h"
 #include "scan_setup.h"
+#include "scan_plan.h"
 
 namespace rago {
 
@@ -458,15 +459,17 @@ static int run_search(rago_index* idx, const float* queries, int64_t nq, int32_t
                          ws.delta.as<float>(), nq, nprobe, k, out_ids, out_scores, out_iscores, st, ev);
     } else {
         LutTables T{};
-        // the bookkeeping of a small batch's scan rides in the table kernel (it needs only the probes)
+        // The scan's bookkeeping rides in the table kernels (it needs only the probes): the plan of the wave-per-item
+        // kernel always, the pairs-by-list bookkeeping of the other two for up to 16 queries (the latency-bound rounds
+        // of Section 5.3: with more, the table kernel fills the chip and the extra workgroup, which needs most of a
+        // compute unit's LDS, would wait for one of its workgroups to finish).
         SmallSetupArgs su{};
-        // (up to 16 queries, the latency-bound rounds of Section 5.3: with more, the table kernel fills the chip and the
-        // extra workgroup, which needs most of a compute unit's LDS, would wait for one of its workgroups to finish)
-        if (nq <= 16 && (rc = plan_small_setup(idx, ws.probes.as<int32_t>(), nq, nprobe, k, true, &su))) return rc;
-        if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st, &su))) return rc;
+        WavePlanArgs wp{};
+        if ((rc = plan_scan_setup(idx, ws.probes.as<int32_t>(), nq, nprobe, k, true, nq <= 16 ? &su : nullptr, &wp))) return rc;
+        if ((rc = launch_build_lut(idx, queries, ws.probes.as<int32_t>(), nq, nprobe, &T, nullptr, nullptr, st, &su, &wp))) return rc;
         if (ev) RAGO_HIP(hipEventRecord(ev[3], st));
         rc = launch_scan(idx, ws.probes.as<int32_t>(), nullptr, T.bias, &T, T.delta, nq, nprobe, k, out_ids, out_scores,
-                         out_iscores, st, ev, su.enable != 0);
+                         out_iscores, st, ev, su.enable != 0 || wp.enable != 0);
     }
     return rc;
 }

@@ -32,6 +32,7 @@
 
 #include "lut_common.h"
 #include "scan_setup.h"
+#include "scan_plan.h"
 #include "rago_internal.h"
 
 namespace rago {
@@ -57,17 +58,25 @@ __device__ __forceinline__ double subdot(const float* __restrict__ a, const floa
 // T64[q][j][c] = <q_j, CB[j][c]> with Tmin/Tmax[q][j] (one wave per (query, sub-quantiser): a lane handles codewords
 // lane, lane + 64, lane + 128, lane + 192), and the per-pair scalars t64[pair][j] = <q_j, C[l]_j> (one wave per pair,
 // lanes = sub-quantisers, `ppw` consecutive pairs per wave), in ONE launch, since neither depends on the other:
-// workgroups below `tg` do T, the others the pairs.
+// after `first` workgroups, `tg` do T, the others the pairs.  The first `first` plan the wave-per-item scan, a query
+// each (scan_plan.h), when that rides along: it needs only the probes (first: they are chains of dependent steps, short
+// on work, and at the end of the grid they would run on after everything else is done).
 template <int DSUB>
 __global__ void __launch_bounds__(256) lut_Tt_kernel(const float* __restrict__ Q, const float* __restrict__ C, const float* __restrict__ CB,
                                                      const int32_t* __restrict__ probes, int64_t nq, int64_t npairs, int ppw, int d, int m,
-                                                     unsigned tg, int qb, double* __restrict__ T64, double* __restrict__ Tmin,
-                                                     double* __restrict__ Tmax, double* __restrict__ t64, int64_t* __restrict__ counters) {
+                                                     unsigned first, unsigned tg, int qb, double* __restrict__ T64, double* __restrict__ Tmin,
+                                                     double* __restrict__ Tmax, double* __restrict__ t64, int64_t* __restrict__ counters,
+                                                     const WavePlanArgs plan) {
     const int lane = threadIdx.x & 63;
     const int dsub = DSUB ? DSUB : d / m;
-    if (blockIdx.x < tg) {
+    if (blockIdx.x < first) {
+        wave_plan_body(plan, (int)blockIdx.x);
+        return;
+    }
+    const unsigned bx = blockIdx.x - first;
+    if (bx < tg) {
         // a wave takes sub-quantiser j for `qb` consecutive queries: its codewords come from L2 once, not once per query
-        const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        const int64_t w = (int64_t)bx * 4 + (threadIdx.x >> 6);
         const int64_t nqb = (nq + qb - 1) / qb;
         if (w >= nqb * m) return;
         const int64_t q0 = (w / m) * qb, q1 = q0 + qb < nq ? q0 + qb : nq;
@@ -104,7 +113,7 @@ __global__ void __launch_bounds__(256) lut_Tt_kernel(const float* __restrict__ Q
         }
         return;
     }
-    const int64_t w = (int64_t)(blockIdx.x - tg) * 4 + (threadIdx.x >> 6);
+    const int64_t w = (int64_t)(bx - tg) * 4 + (threadIdx.x >> 6);
     for (int pp = 0; pp < ppw; ++pp) {
         const int64_t pair = w * ppw + pp;
         if (pair >= npairs) return;
@@ -127,7 +136,8 @@ __global__ void __launch_bounds__(LQ_THREADS, 8) lut_query_kernel(const double* 
                                                                uint8_t* __restrict__ lut_base, uint16_t* __restrict__ amb_addr,
                                                                int32_t* __restrict__ namb, float* __restrict__ delta,
                                                                int32_t* __restrict__ bias, uint8_t* __restrict__ patch_val,
-                                                               int64_t* __restrict__ counters, int lq_y, const SmallSetupArgs setup) {
+                                                               int64_t* __restrict__ counters, int lq_y, const SmallSetupArgs setup,
+                                                               const WaveFixArgs fix) {
     // One extra row of workgroups, the first to be dispatched, when the scan's bookkeeping rides along: its first
     // workgroup does that work, which needs nothing from the tables, the others leave.
     const int ty = (int)blockIdx.y - (setup.enable ? 1 : 0);       // this workgroup's row among the query's lq_y
@@ -242,6 +252,7 @@ __global__ void __launch_bounds__(LQ_THREADS, 8) lut_query_kernel(const double* 
     const int n = s_n;
     if (tid == 0 && writer) {
         namb[q] = n > AMB_MAX ? AMB_MAX + 1 : n;   // AMB_MAX + 1 = "evaluate per pair"
+        if (fix.enable && n > AMB_MAX) wave_fix_per_pair(fix, (int)q);      // (the plan took the query's tables to be shared)
         if (n > AMB_MAX) atomicAdd(reinterpret_cast<unsigned long long*>(counters + 5), 1ull);
         else atomicAdd(reinterpret_cast<unsigned long long*>(counters + 4), (unsigned long long)n);
     }
@@ -448,7 +459,7 @@ int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npair
 }
 
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe, LutTables* out,
-                     float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup) {
+                     float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup, const WavePlanArgs* wave_plan) {
     Workspace& ws = idx->ws;
     const int m = idx->m, d = idx->d;
     const int64_t npairs = nq * nprobe;
@@ -475,12 +486,21 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     const int qb = nq * m >= (int64_t)64 * idx->n_cu ? 8 : 1;
     const unsigned tg = (unsigned)(((nq + qb - 1) / qb * m + 3) / 4), pgrid = (unsigned)((npairs + 4 * ppw - 1) / (4 * ppw));
     // two launches: the per-query tables together with the per-pair scalars, then everything else of a query
+    WavePlanArgs wp{};
+    WaveFixArgs fix{};
+    if (wave_plan && wave_plan->enable) {
+        wp = *wave_plan;
+        fix.enable = 1; fix.qinfo = wp.qinfo; fix.qnext = wp.qnext; fix.nq = wp.nq; fix.nwg = wp.nwg; fix.nprobe = wp.nprobe;
+    }
+    const unsigned plan_wgs = wp.enable ? (unsigned)nq : 0u;
     if (d / m == 8 && d % 4 == 0)        // (16-byte loads of the sub-vectors)
-        lut_Tt_kernel<8><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, qb, ws.T64.as<double>(),
-                                                     ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
+        lut_Tt_kernel<8><<<tg + pgrid + plan_wgs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, plan_wgs, tg, qb,
+                                                                ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(),
+                                                                ws.counters.as<int64_t>(), wp);
     else
-        lut_Tt_kernel<0><<<tg + pgrid, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, tg, qb, ws.T64.as<double>(),
-                                                     ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), ws.counters.as<int64_t>());
+        lut_Tt_kernel<0><<<tg + pgrid + plan_wgs, 256, 0, st>>>(q, idx->centroids, idx->codebooks, probes, nq, npairs, ppw, d, m, plan_wgs, tg, qb,
+                                                                ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(),
+                                                                ws.counters.as<int64_t>(), wp);
     // (workgroups per query: enough to fill the chip on a small batch, at most one per 32 pairs)
     // workgroups per query: a wave per pair at a time; one round of pairs per workgroup while the batch leaves room
     const unsigned lq_y = (unsigned)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(512 / nq, (nprobe + 15) / 16), 32));
@@ -494,7 +514,7 @@ int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int
     }
     lut_query_kernel<<<dim3((unsigned)nq, lq_y + (su.enable ? 1u : 0u)), LQ_THREADS, su.enable ? SSU_LDS : 0, st>>>(
         ws.T64.as<double>(), ws.Tmin.as<double>(), Tmax, ws.pair_lo.as<double>(), nprobe, m, range_bits, mag_bits, ws.lut8.as<uint8_t>(), amb_addr,
-        namb, ws.delta.as<float>(), ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>(), (int)lq_y, su);
+        namb, ws.delta.as<float>(), ws.bias.as<int32_t>(), ws.patch.as<uint8_t>(), ws.counters.as<int64_t>(), (int)lq_y, su, fix);
     if (out_L_f32 || out_LUT8)
         lut_expand_kernel<<<(unsigned)npairs, 256, 0, st>>>(ws.T64.as<double>(), ws.Tmin.as<double>(), ws.pair_lo.as<double>(), range_bits,
                                                             ws.lut8.as<uint8_t>(), amb_addr, namb, ws.patch.as<uint8_t>(), nprobe, m,

@@ -122,6 +122,7 @@ struct rago_index {
 namespace rago {
 
 struct SmallSetupArgs;      // scan_setup.h
+struct WavePlanArgs;        // scan_plan.h
 
 // layout.hip
 int build_layout(rago_index* idx, const uint8_t* d_codes_plain, hipStream_t st);
@@ -143,8 +144,10 @@ int launch_select_tree(rago_index* idx, const float* q, int64_t nq, int nprobe, 
 int tree_cap();
 
 // lut.hip
+// (setup / wave_plan: bookkeeping of the scan that rides in the two kernels, see plan_scan_setup)
 int launch_build_lut(rago_index* idx, const float* q, const int32_t* probes, int64_t nq, int nprobe,
-                     LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup = nullptr);
+                     LutTables* out, float* out_L_f32, uint8_t* out_LUT8, hipStream_t st, const SmallSetupArgs* setup = nullptr,
+                     const WavePlanArgs* wave_plan = nullptr);
 int launch_swizzle_lut(rago_index* idx, const uint8_t* lut8_plain, int64_t npairs, uint8_t* lut8sw, hipStream_t st);
 // Euclidean metric: one full table per pair (plane-major, stride LUT_BYTES) into ws.tmp_lut8sw, biases into
 // ws.bias, steps into ws.delta; optional plain copies for inspection.
@@ -158,11 +161,12 @@ int launch_build_lut_l2(rago_index* idx, const float* q, const int32_t* probes, 
 // scan.hip
 // Tables come either per pair (`lut8sw` [npairs][plane][256][32] + `bias`, `tables` null) or as per-query
 // base tables with per-pair patches (`tables`, `lut8sw` null).
-// (setup_done: the bookkeeping of a small batch has been run by the caller's kernel, see plan_small_setup)
+// (setup_done: the scan's bookkeeping has been run by the caller's kernels, see plan_scan_setup)
 int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, const int32_t* bias,
                 const LutTables* tables, const float* delta, int64_t nq, int nprobe, int k, int64_t* out_ids,
                 float* out_scores, int32_t* out_iscores, hipStream_t st, hipEvent_t* ev = nullptr, bool setup_done = false);
-int plan_small_setup(rago_index* idx, const int32_t* probes, int64_t nq, int nprobe, int k, bool base_tables, SmallSetupArgs* out);
+int plan_scan_setup(rago_index* idx, const int32_t* probes, int64_t nq, int nprobe, int k, bool base_tables, SmallSetupArgs* small,
+                    WavePlanArgs* wave);
 
 // flat.hip
 int launch_flat(const void* corpus, const void* queries, int R, int64_t n, int nqr, int d, int k,

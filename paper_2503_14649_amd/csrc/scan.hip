@@ -43,6 +43,7 @@
 
 #include "scan_common.h"
 #include "scan_setup.h"
+#include "scan_plan.h"
 
 namespace rago {
 
@@ -1129,15 +1130,28 @@ static void fill_small_setup(rago_index* idx, const int32_t* probes, int64_t nq,
     A->counters = ws.counters.as<int64_t>();
 }
 
-// For a caller that runs the small batch's bookkeeping inside a kernel of its own (the table kernel of the
-// inner-product path): sizes the scan's workspace and says what that workgroup has to do; `enable` stays 0 when the
-// scan of this call does its bookkeeping itself.  launch_scan is then told that it is done.
-int plan_small_setup(rago_index* idx, const int32_t* probes, int64_t nq, int nprobe, int k, bool base_tables, SmallSetupArgs* out) {
-    out->enable = 0;
+// For a caller that runs the scan's bookkeeping inside kernels of its own (the table kernels of the inner-product
+// path): sizes the scan's workspace and says what those workgroups have to do - `small` (may be null) for a small
+// batch's pairs-by-list bookkeeping, `wave` (may be null) for the plan of the wave-per-item kernel; `enable` stays 0
+// in both when the scan of this call does its bookkeeping itself.  launch_scan is then told that it is done.
+int plan_scan_setup(rago_index* idx, const int32_t* probes, int64_t nq, int nprobe, int k, bool base_tables, SmallSetupArgs* small,
+                    WavePlanArgs* wave) {
+    if (small) small->enable = 0;
+    if (wave) wave->enable = 0;
     const ScanPlan plan = plan_scan(idx, nq, nq * nprobe, base_tables);
     int rc = reserve_scan(idx, nq, nprobe, k, plan);
     if (rc || idx->reserving) return rc;
-    if (nq * nprobe <= SSU_PAIRS && plan.kind != SCAN_WAVE) fill_small_setup(idx, probes, nq, nprobe, plan, out);
+    Workspace& ws = idx->ws;
+    if (plan.kind == SCAN_WAVE) {
+        if (wave) {
+            ScanParams P{};         // (what the plan reads of it; the tables do not exist yet: namb stays null)
+            P.probes = probes; P.blk_off = idx->blk_off; P.list_off = idx->list_off;
+            P.nprobe = nprobe; P.CH = plan.CH; P.m = idx->m; P.tauq = ws.tauq.as<int32_t>();
+            fill_wave_plan(P, nq, idx->n_cu, ws.wave_items.p, ws.pair_sorted.as<int32_t>(), ws.wave_q.as<int32_t>(), ws.counters.as<int64_t>(), wave);
+        }
+    } else if (small && nq * nprobe <= SSU_PAIRS) {
+        fill_small_setup(idx, probes, nq, nprobe, plan, small);
+    }
     return RAGO_OK;
 }
 
@@ -1174,10 +1188,10 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     if (plan.kind == SCAN_WAVE)
         return launch_scan_wave(P, nq, n_cu, (double)idx->total_blocks / nlist, ws.wave_items.p, ws.pair_sorted.as<int32_t>(),
                                 ws.wave_q.as<int32_t>(), ws.wave_stage.p, ws.counters.as<int64_t>(), delta, out_ids, out_scores, out_iscores,
-                                ev, st);
+                                ev, st, setup_done);
     const unsigned pg = (unsigned)((npairs + 255) / 256);
     if (setup_done) {
-        // (the caller's kernel has done it: plan_small_setup)
+        // (the caller's kernel has done it: plan_scan_setup)
     } else if (npairs <= SSU_PAIRS) {
         static OncePerDevice once;
         if (once.first())

@@ -200,8 +200,11 @@ int launch_scan_narrow(const ScanParams& P, int n_cu, hipStream_t st);
 int wave_chunk_len(double total_blocks, int n_cu);
 size_t wave_pair_bytes();
 size_t wave_stage_bytes(int64_t nq, int k);
+struct WavePlanArgs;        // scan_plan.h
+void fill_wave_plan(const ScanParams& P, int64_t nq, int n_cu, void* pdesc, int32_t* pair_pre, int32_t* qwork, int64_t* counters,
+                    WavePlanArgs* A);
 int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* pdesc, int32_t* pair_pre, int32_t* qwork,
                      void* stage, int64_t* counters, const float* delta, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
-                     hipEvent_t* ev, hipStream_t st);
+                     hipEvent_t* ev, hipStream_t st, bool plan_done);
 
 }  // namespace rago

@@ -41,6 +41,7 @@
 #include <algorithm>
 
 #include "scan_common.h"
+#include "scan_plan.h"
 
 namespace rago {
 namespace wavescan {
@@ -49,7 +50,8 @@ constexpr int WAVES = 8;
 constexpr int THREADS = WAVES * 64;
 constexpr int LUT_LDS = 32768;
 constexpr int CORR_CAP = AMB_MAX;
-constexpr int BATCH = 2 * WAVES;                // items a workgroup claims at a time
+constexpr int BATCH = WAVE_BATCH;               // items a workgroup claims at a time (two per wave)
+static_assert(WAVE_BATCH == 2 * WAVES, "two items per wave");
 constexpr int PRE_CAP = 2048 + 1;               // first item of every pair of the query (nprobe <= 2048) and the total
 // LDS: table | key buffers [wave][CAPW] | corrections [wave][CORR_CAP] | ambiguous entries of the query: address u16,
 // base value u8 | first item of each pair | scalars | histogram of candidate scores
@@ -155,11 +157,7 @@ __device__ __forceinline__ uint32_t code_of(const uint4 (&w)[MPAD / 16], int j, 
     return (dw >> (8 * (step & 3))) & 255u;
 }
 
-// One probed list of one query: where its codes and rows start, how long it is, and the query-local number of
-// its first item.
-// 32 bytes.  The descriptors of a query stand in the order its items are handed out (plan_kernel), `pair` says whose
-// they are: probe number `pair` of the query.
-struct PairDesc { int64_t blk0, row0; int32_t nblk, len, pre, pair; };
+using PairDesc = WavePairDesc;      // scan_plan.h
 
 struct WaveParams {
     ScanParams S;              // codes, tables, nprobe, k, CH (= blocks per item), maxchunks; part_* = per-item result slots
@@ -597,88 +595,8 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
 }
 
 // ------------------------------------------------------------------ planning kernel
-// One workgroup per query: the descriptor of every pair, the query-local number of each pair's first item, the
-// query's totals, its counters and its bound.  `nwg` = workgroups of the scan kernel: workgroup b first attaches to
-// query b mod nq, and the r-th of them takes items r * BATCH .. without asking, so the query's counter starts
-// behind those.
-__global__ void __launch_bounds__(256) plan_kernel(const int32_t* __restrict__ probes, const int64_t* __restrict__ blk_off,
-                                                   const int64_t* __restrict__ list_off, int nprobe, int CH, int m, int nq, int nwg,
-                                                   const int32_t* __restrict__ namb, int all_per_pair,
-                                                   PairDesc* __restrict__ pdesc, int32_t* __restrict__ pair_pre, int4* __restrict__ qinfo,
-                                                   int32_t* __restrict__ qnext, int32_t* __restrict__ qatt,
-                                                   int64_t* __restrict__ qbytes, int32_t* __restrict__ tauq, int64_t* __restrict__ counters) {
-    __shared__ int s_w[4];
-    __shared__ int s_carry;
-    __shared__ unsigned long long s_bytes[2];
-    __shared__ int s_key[256];
-    __shared__ PairDesc s_pd[256];
-    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) { s_carry = 0; s_bytes[0] = 0; s_bytes[1] = 0; }
-    if (q == 0 && tid < 3) counters[tid] = 0;          // (the scan kernel adds the batch's totals)
-    __syncthreads();
-    unsigned long long streamed = 0, algo = 0;
-    for (int p0 = 0; p0 < nprobe; p0 += 256) {
-        const int p = p0 + tid, np = min(256, nprobe - p0);
-        PairDesc pd = {0, 0, 0, 0, 0, 0};
-        if (p < nprobe) {
-            const int l = probes[(int64_t)q * nprobe + p];
-            pd.blk0 = blk_off[l];
-            pd.row0 = list_off[l];
-            pd.nblk = (int)(blk_off[l + 1] - pd.blk0);
-            pd.len = (int)(list_off[l + 1] - pd.row0);
-            pd.pair = p;
-            streamed += (unsigned long long)pd.nblk * (BLOCK_VECS * m);
-            algo += (unsigned long long)pd.len * m;
-        }
-        // Longest first among these (up to) 256 pairs: a query's items are handed out in this order, and what its
-        // waves wait for at the end - the last items still running - are then the short ones.
-        s_key[tid] = pd.nblk;
-        __syncthreads();
-        if (p < nprobe) {
-            int pos = 0;
-#pragma unroll 8
-            for (int j = 0; j < np; ++j) {
-                const int o = s_key[j];
-                pos += o > pd.nblk || (o == pd.nblk && j < tid) ? 1 : 0;
-            }
-            s_pd[pos] = pd;
-        }
-        __syncthreads();
-        if (p < nprobe) pd = s_pd[tid];
-        const int n = p < nprobe ? (pd.nblk + CH - 1) / CH : 0;
-        int inc = n;
-        for (int o = 1; o < 64; o <<= 1) {
-            const int v = __shfl_up(inc, o);
-            if (lane >= o) inc += v;
-        }
-        if (lane == 63) s_w[wave] = inc;
-        __syncthreads();
-        int before = s_carry;
-        for (int w = 0; w < wave; ++w) before += s_w[w];
-        if (p < nprobe) {
-            pd.pre = before + inc - n;
-            pdesc[(int64_t)q * nprobe + p] = pd;
-            pair_pre[(int64_t)q * nprobe + p] = pd.pre;
-        }
-        __syncthreads();
-        if (tid == 255) s_carry = before + inc;
-        __syncthreads();
-    }
-    for (int o = 32; o; o >>= 1) { streamed += __shfl_xor(streamed, o); algo += __shfl_xor(algo, o); }
-    if (lane == 0) { atomicAdd(&s_bytes[0], streamed); atomicAdd(&s_bytes[1], algo); }
-    __syncthreads();
-    if (tid == 0) {
-        const int items = s_carry;
-        const int per_pair = all_per_pair || namb[q] > AMB_MAX;
-        qinfo[q] = make_int4(per_pair ? nprobe : items, items, per_pair, 0);
-        const int attached = q < nwg ? (nwg - 1 - q) / nq + 1 : 0;
-        qnext[q] = attached * (per_pair ? 1 : BATCH);
-        qatt[q] = 0;
-        tauq[q] = INT32_MIN;
-        qbytes[2 * q] = (int64_t)s_bytes[0];
-        qbytes[2 * q + 1] = (int64_t)s_bytes[1];
-    }
-}
+// (the work itself: scan_plan.h)
+__global__ void __launch_bounds__(256) plan_kernel(const WavePlanArgs A) { wave_plan_body(A, (int)blockIdx.x); }
 
 // ------------------------------------------------------------------ per-query merge of the items' results
 // Stage 1: workgroup (query, slice) takes the slots of its slice of the query's items, keeps the entries that reach
@@ -933,32 +851,48 @@ int wave_merge_slices(double items_per_query) {
 }
 size_t wave_stage_bytes(int64_t nq, int k) { return (size_t)nq * MAX_SLICES * k * 12; }
 
-// Plans on the device (one small kernel), scans, merges the items' results.  P.CH / P.maxchunks are the blocks per
-// item and the most items any pair can have; pdesc [npairs], pair_pre [npairs], qwork [nq * 12 ints], stage
-// [wave_stage_bytes] are workspace; P.part_* hold the items' results (nprobe * maxchunks slots per query).
+// Where the plan's outputs live in the workspace arrays (pdesc [npairs], pair_pre [npairs], qwork [nq * 12 ints]).
+void fill_wave_plan(const ScanParams& P, int64_t nq, int n_cu, void* pdesc, int32_t* pair_pre, int32_t* qwork, int64_t* counters,
+                    WavePlanArgs* A) {
+    A->enable = 1;
+    A->probes = P.probes; A->blk_off = P.blk_off; A->list_off = P.list_off;
+    A->nprobe = P.nprobe; A->CH = P.CH; A->m = P.m; A->nq = (int)nq; A->nwg = 2 * n_cu;
+    A->namb = P.T.namb; A->all_per_pair = P.lut8sw != nullptr;
+    A->pdesc = static_cast<WavePairDesc*>(pdesc);
+    A->pair_pre = pair_pre;
+    A->qinfo = reinterpret_cast<int4*>(qwork);
+    A->qnext = qwork + 4 * nq;
+    A->qatt = qwork + 5 * nq;
+    A->qbytes = reinterpret_cast<int64_t*>(qwork + 8 * nq);
+    A->tauq = P.tauq;
+    A->counters = counters;
+}
+
+// Plans on the device (one small kernel, unless `plan_done`), scans, merges the items' results.  P.CH / P.maxchunks
+// are the blocks per item and the most items any pair can have; pdesc [npairs], pair_pre [npairs], qwork [nq * 12
+// ints], stage [wave_stage_bytes] are workspace; P.part_* hold the items' results (nprobe * maxchunks slots per query).
 int launch_scan_wave(const ScanParams& P, int64_t nq, int n_cu, double avgblk, void* pdesc, int32_t* pair_pre, int32_t* qwork,
                      void* stage, int64_t* counters, const float* delta, int64_t* out_ids, float* out_scores, int32_t* out_iscores,
-                     hipEvent_t* ev, hipStream_t st) {
+                     hipEvent_t* ev, hipStream_t st, bool plan_done) {
     using namespace wavescan;
-    const int grid = 2 * n_cu;
+    WavePlanArgs A;
+    fill_wave_plan(P, nq, n_cu, pdesc, pair_pre, qwork, counters, &A);
+    const int grid = A.nwg;
     WaveParams W;
     W.S = P;
-    W.pdesc = static_cast<const PairDesc*>(pdesc);
+    W.pdesc = A.pdesc;
     W.pair_pre = pair_pre;
-    int4* qinfo = reinterpret_cast<int4*>(qwork);
-    W.qinfo = qinfo;
-    W.qnext = qwork + 4 * nq;
-    W.qatt = qwork + 5 * nq;
-    int64_t* qbytes = reinterpret_cast<int64_t*>(qwork + 8 * nq);
-    W.qbytes = qbytes;
+    W.qinfo = A.qinfo;
+    W.qnext = A.qnext;
+    W.qatt = A.qatt;
+    W.qbytes = A.qbytes;
     W.counters = counters;
     W.nq = (int)nq;
     W.qslots = (int64_t)P.nprobe * P.maxchunks;
     W.nslice = wave_merge_slices((double)P.nprobe * std::max(1.0, avgblk / P.CH));
     W.stage_id = static_cast<int64_t*>(stage);
     W.stage_I = reinterpret_cast<int32_t*>(W.stage_id + nq * MAX_SLICES * P.k);
-    plan_kernel<<<(unsigned)nq, 256, 0, st>>>(P.probes, P.blk_off, P.list_off, P.nprobe, P.CH, P.m, (int)nq, grid, P.T.namb, P.lut8sw != nullptr,
-                                              static_cast<PairDesc*>(pdesc), pair_pre, qinfo, W.qnext, W.qatt, qbytes, P.tauq, counters);
+    if (!plan_done) plan_kernel<<<(unsigned)nq, 256, 0, st>>>(A);      // (else a kernel of the caller's has done it)
     RAGO_HIP(hipGetLastError());
     if (ev) RAGO_HIP(hipEventRecord(ev[4], st));
     int rc;
