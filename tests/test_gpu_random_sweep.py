@@ -25,12 +25,15 @@ def _bits(t):
     return t.cpu().view(torch.int16).numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
-def test_ivfpq_random_configurations(rb, seed):
+# (seed, number of cases, batch sizes): the last line draws batches with as many queries as the chip has compute units and
+# more, where the selection, the table kernels and the wave-per-item scan's merge take their large-batch forms
+@pytest.mark.parametrize("seed,ncases,batches", [(11, 70, (1, 2, 7, 33, 130)), (12, 70, (1, 2, 7, 33, 130)), (13, 70, (1, 2, 7, 33, 130)),
+                                                 (14, 25, (140, 260, 300, 520, 1100))])
+def test_ivfpq_random_configurations(rb, seed, ncases, batches):
     rng = np.random.default_rng(seed)
     unproven = 0
     try:
-        for case in range(70):
+        for case in range(ncases):
             ksub = 16 if rng.random() < 0.25 else 256
             mbytes = int(rng.choice([16, 32, 64, 96, 128]))
             m = mbytes * 2 if ksub == 16 else mbytes
@@ -40,7 +43,7 @@ def test_ivfpq_random_configurations(rb, seed):
             d = m * dsub
             nlist = int(rng.choice([1, 2, 5, 17, 64, 300]))
             n = int(rng.choice([0, 1, 63, 64, 65, 1000, 7000, 30000]))
-            nq = int(rng.choice([1, 2, 7, 33, 130]))
+            nq = int(rng.choice(list(batches)))
             nprobe = int(rng.integers(1, nlist + 1))
             k = int(rng.choice([1, 2, 10, 100, 128]))
             metric = "l2" if rng.random() < 0.4 else "ip"
