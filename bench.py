@@ -238,8 +238,9 @@ def run_ivfpq(args):
                   "iscores_bit_exact": bool(np.array_equal(gis, sample_ref["iscores"]))}
     mbytes = cfg.m // 2 if cfg.ksub == 16 else cfg.m
     prof = read_traffic(f"scan_m{mbytes}_{cfg.name}_pmc.txt") if args.scale == 1.0 and args.metric == "ip" and cfg.ksub == 256 else None
+    scan_name = {1: "rago::scan_kernel", 2: "rago::narrow::scan_kernel", 3: "rago::wavescan::scan_kernel"}.get(cnt[6], "scan_kernel")
     roof = hbm_roofline(
-        f"scan_kernel<{mbytes}>", streamed, scan_ms, ceiling, prof,
+        f"{scan_name}<{mbytes}>", streamed, scan_ms, ceiling, prof,
         "code bytes the scan kernel streams from HBM per launch (the library's own count: every pass over a list once, "
         "whatever number of queries it serves) / the kernel's HIP-event time",
         {"algorithmic_bytes_per_launch": algo_bytes, "code_bytes_streamed_per_launch": streamed,

@@ -248,7 +248,8 @@ int rago_debug_scan(rago_index* idx, const int32_t* probes, const uint8_t* LUT8,
  * exact scores of all lists (it could not be shown independent of fp32 rounding otherwise), [4] table entries whose rounding had to be evaluated per
  * (query, list) pair (summed over queries), [5] queries whose tables were evaluated entry by entry
  * for every pair (Euclidean metric: [4] entries re-evaluated in fp64 over both table passes, [5]
- * workgroups that re-evaluated all their entries, counted once per pass), [6..7] reserved. */
+ * workgroups that re-evaluated all their entries, counted once per pass), [6] the scan kernel that ran, numbered
+ * as in rago_debug_force_scan_kernel (1, 2 or 3), [7] reserved. */
 int rago_debug_counters(rago_index* idx, int64_t* out, void* stream);
 
 /* Pin the scan kernel of every following search in this process: 0 = chosen from the sizes (default),

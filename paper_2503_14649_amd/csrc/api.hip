@@ -624,6 +624,7 @@ int rago_debug_counters(rago_index* idx, int64_t* out, void* stream) {
     if (!idx->ws.counters.p) return RAGO_OK;
     RAGO_HIP(hipMemcpyAsync(out, idx->ws.counters.p, 8 * sizeof(int64_t), hipMemcpyDeviceToHost, (hipStream_t)stream));
     RAGO_HIP(hipStreamSynchronize((hipStream_t)stream));
+    out[6] = idx->last_scan_kernel;
     return RAGO_OK;
 }
 

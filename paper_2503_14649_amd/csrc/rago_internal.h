@@ -115,8 +115,8 @@ struct rago_index {
     int res_nprobe = 0, res_k = 0;
     rago::Workspace ws;
     rago::Profiler prof;
-    // parameters of the last scan (for rago_debug_counters)
-    int64_t last_algo_bytes_valid = 0;
+    // the scan kernel of the last search (for rago_debug_counters): 1 four pairs per pass, 2 two pairs, 3 wave per item
+    int last_scan_kernel = 0;
 };
 
 namespace rago {

@@ -1168,6 +1168,7 @@ int launch_scan(rago_index* idx, const int32_t* probes, const uint8_t* lut8sw, c
     if ((rc = reserve_scan(idx, nq, nprobe, k, plan))) return rc;
     const int64_t max_tasks = npairs * maxchunks;
     if (idx->reserving) return RAGO_OK;
+    idx->last_scan_kernel = plan.kind + 1;
 
     int32_t* list_cnt = ws.list_cnt.as<int32_t>();
     int32_t* cursor = list_cnt + nlist;

@@ -221,6 +221,7 @@ def test_search_end_to_end(case, rb, scan_kernel):
     assert overlap >= 0.999
     assert np.array_equal(gi, r["ids"]) and np.array_equal(gis, r["iscores"])
     assert np.array_equal(gs, r["scores"])
+    assert rb.rago_debug_counters(h)[6] == {"wide": 1, "narrow": 2, "wave": 3}[scan_kernel]     # the pinned kernel is the one that ran
 
 
 def test_search_twice_gives_identical_bytes(case, rb, scan_kernel):
