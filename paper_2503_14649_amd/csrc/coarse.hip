@@ -238,8 +238,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
             *reinterpret_cast<uint4*>(Bh + row * X_LS + c8 * 8) = pbh[r];
             *reinterpret_cast<uint4*>(Bl + row * X_LS + c8 * 8) = pbl[r];
         }
+        if (k0 + X_KT < d) gload(k0 + X_KT);     // (the registers are free again: the next tile's loads go out ahead of the barrier)
         __syncthreads();
-        if (k0 + X_KT < d) gload(k0 + X_KT);
 #pragma unroll
         for (int ks = 0; ks < X_KT / 16; ++ks) {
             bf16x8 ah[2], al[2], bh[NBT], bl[NBT];
