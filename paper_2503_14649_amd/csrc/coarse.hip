@@ -732,7 +732,9 @@ __device__ __forceinline__ void rank_keys(const uint64_t* key, int n, int* rank,
 // REG = scores per thread (nlist <= REG * SEL_THREADS: a short row should not pay for 64 loads, clamped or not);
 // RU = rows of C a wave scores at a time (random rows from HBM, one round trip per round of the workgroup's waves:
 // a workgroup that has a query to itself takes its ~100 rows in one round, one of sixteen has only a few).
-template <int REG, int RU>
+// ALONE: gridDim.y == 1, the workgroup has the query to itself: the exact scores stay in LDS, and the two round trips
+// to memory that pass them between workgroups (store and acknowledge, count and read back) fall away.
+template <int REG, int RU, bool ALONE>
 __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* __restrict__ Q, const float* __restrict__ C,
                                                                    const float* __restrict__ S, int nlist, int d, int nprobe,
                                                                    float max_cnorm, int metric, int32_t* __restrict__ probes,
@@ -854,11 +856,26 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
             cv[u] = C + (int64_t)(0xFFFFFFFFu - (uint32_t)sel_key[pos]) * d;
         }
         if (vec4) {
+            // (the loads of the next trip round the loop go out ahead of this trip's arithmetic: one round trip to the
+            // rows in all instead of one per 256 dimensions)
+            float4 q4n = make_float4(0.f, 0.f, 0.f, 0.f), c4n[RU];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) c4n[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (lane * 4 < d) {
+                q4n = *reinterpret_cast<const float4*>(qv + lane * 4);
+#pragma unroll
+                for (int u = 0; u < RU; ++u) c4n[u] = *reinterpret_cast<const float4*>(cv[u] + lane * 4);
+            }
             for (int t = lane * 4; t < d; t += 256) {
-                const float4 q4 = *reinterpret_cast<const float4*>(qv + t);
+                const float4 q4 = q4n;
                 float4 c4[RU];
 #pragma unroll
-                for (int u = 0; u < RU; ++u) c4[u] = *reinterpret_cast<const float4*>(cv[u] + t);
+                for (int u = 0; u < RU; ++u) c4[u] = c4n[u];
+                if (t + 256 < d) {
+                    q4n = *reinterpret_cast<const float4*>(qv + t + 256);
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) c4n[u] = *reinterpret_cast<const float4*>(cv[u] + t + 256);
+                }
                 const double qa[4] = {(double)q4.x, (double)q4.y, (double)q4.z, (double)q4.w};
 #pragma unroll
                 for (int u = 0; u < RU; ++u) {
@@ -883,23 +900,29 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
             for (int o = 32; o; o >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], o);
-            if (lane == 0 && c0 + u < nmine)
-                __hip_atomic_store(&exact[g + (c0 + u) * G], metric == 1 ? (float)(-acc[u]) : (float)acc[u],
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0 && c0 + u < nmine) {
+                const float ex = metric == 1 ? (float)(-acc[u]) : (float)acc[u];
+                if constexpr (ALONE) reinterpret_cast<float*>(hist)[c0 + u] = ex;      // (the histogram has served; G = 1: position c0 + u)
+                else __hip_atomic_store(&exact[g + (c0 + u) * G], ex, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
     // ---- the workgroup that finishes last goes on.  The exact scores were written by device-scope atomic stores, which
     // go through to where every compute unit's device-scope loads read them; once they are acknowledged (the wait)
     // the count may be raised.  (A release fence would also write back every dirty line of this chiplet's L2 -
     // here the whole score matrix the kernel before has just written - and was measured at 4 to 55 us.)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (tid == 0) s_last = atomicAdd(&done[q], 1) == G - 1;
-    __syncthreads();
-    if (!s_last) return;
+    if constexpr (ALONE) {
+        __syncthreads();
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) s_last = atomicAdd(&done[q], 1) == G - 1;
+        __syncthreads();
+        if (!s_last) return;
+    }
     // ---- order by (exact score desc, list asc); c_key and rank are free again
     if (tid < want) {
-        const float ex = __hip_atomic_load(&exact[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float ex = ALONE ? reinterpret_cast<const float*>(hist)[tid] : __hip_atomic_load(&exact[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         c_key[tid] = ((uint64_t)float_key(ex + 0.0f) << 32) /* (-0 counts as +0) */ | (uint32_t)sel_key[tid];
     }
     __syncthreads();
@@ -913,7 +936,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_small_kernel(const float* 
     }
     __syncthreads();
     if (tid == 0) {
-        done[q] = 0;
+        if (!ALONE) done[q] = 0;
         auto unkey = [](uint32_t kk) { return __uint_as_float((kk & 0x80000000u) ? (kk & 0x7fffffffu) : ~kk); };
         const float s_cut = unkey((uint32_t)(sel_key[want - 1] >> 32));   // smallest fp32 score among the candidates
         const float nth = unkey((uint32_t)hist[0]);
@@ -964,9 +987,9 @@ int launch_select(rago_index* idx, const float* q, float* S, int64_t nq, int npr
                                                                        rq, ss_exact, ss_done);
             };
             const bool alone = ss_g == 1;
-            if (nl <= 16 * SEL_THREADS) { if (alone) go(select_small_kernel<16, 6>); else go(select_small_kernel<16, 2>); }
-            else if (nl <= 32 * SEL_THREADS) { if (alone) go(select_small_kernel<32, 6>); else go(select_small_kernel<32, 2>); }
-            else { if (alone) go(select_small_kernel<64, 6>); else go(select_small_kernel<64, 2>); }
+            if (nl <= 16 * SEL_THREADS) { if (alone) go(select_small_kernel<16, 6, true>); else go(select_small_kernel<16, 2, false>); }
+            else if (nl <= 32 * SEL_THREADS) { if (alone) go(select_small_kernel<32, 6, true>); else go(select_small_kernel<32, 2, false>); }
+            else { if (alone) go(select_small_kernel<64, 6, true>); else go(select_small_kernel<64, 2, false>); }
         }
         else if (nl <= 8 * SEL_THREADS)
             select_kernel<8><<<(unsigned)nq, SEL_THREADS, 0, st>>>(q, idx->centroids, S, nl, idx->d, nprobe, idx->max_cnorm, idx->metric, probes, cnt, rq, redo);
