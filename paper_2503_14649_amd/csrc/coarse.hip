@@ -131,8 +131,11 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
 // into LDS.  v_mfma_f32_32x32x16_bf16: lane (i32, h) supplies k = 8h .. 8h+7 of row i32 of both
 // operands; 128x128 tile per workgroup, 64x64 per wave.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-constexpr int X_T = 128, X_KT = 64, X_LS = X_KT + 8;   // LDS row stride in bf16 (144 B: b128 reads conflict-free)
-constexpr int X_LDS = 4 * X_T * X_LS * 2;              // bytes: hi and lo tiles of both operands
+constexpr int X_T = 128;
+// LDS row stride in bf16 for a K tile of KT: 8 more (144 or 80 B: the b128 reads of 8 consecutive rows cover all banks once)
+constexpr int x_ls(int KT) { return KT + 8; }
+// bytes: hi and lo tiles of both operands (TM query rows, X_T centroid rows)
+constexpr int x_lds(int TM, int KT) { return (TM * 2 + X_T * 2) * x_ls(KT) * 2; }
 
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
     const uint32_t u = __float_as_uint(x);
@@ -142,8 +145,8 @@ __device__ __forceinline__ uint32_t bf16_rne(float x) {
 // Two floats -> their bf16 parts, packed (first in the low half): hi = bf16(x), lo = bf16(x - hi), both rounded to
 // nearest even by the chip's packed conversion (v_cvt_pk_bf16_f32: one instruction per pair, where the bit arithmetic of
 // bf16_rne takes four per number).  The split of the query tile was two thirds of the tile kernel's vector instructions
-// (384 of 422 per wave and K tile, 104 now); the kernel gained 4 % (0.41 -> 0.39 ms per 1024 x 65536 x 768): what it
-// waits for is the next tile's loads, 64 KB per workgroup and K tile from L2 with two workgroups per compute unit.
+// (384 of 422 per wave and K tile of 64, 104 now); the kernel gained 4 % (0.41 -> 0.39 ms per 1024 x 65536 x 768): what
+// it waits for is the next tile's loads from L2, with two workgroups per compute unit then.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void split_bf16_pair(float a, float b, uint32_t& hi, uint32_t& lo) {
@@ -176,14 +179,17 @@ int launch_split_centroids(rago_index* idx, hipStream_t st) {
 // served by that XCD's L2.
 // TM = query rows per workgroup: 128 (a wave takes 64 x 64), or 64 (a wave takes 64 x 32) for batches that would
 // otherwise leave a workgroup alone on its compute unit with nothing to hide its loads behind.
-template <int TM>
-__global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
+// KT = dimensions per K tile: 64, or 32 for the 128-row tile, whose registers then allow a third workgroup per compute unit
+// (1024 x 65536 x 768: 0.39 -> 0.35 ms; the 64-row tile on 256 queries loses 10 % with it).
+template <int TM, int KT>
+__global__ void __launch_bounds__(256, KT == 32 ? 3 : 1) coarse_gemm_split_kernel(const float* __restrict__ Q, const uint16_t* __restrict__ Chi,
                                                                 const uint16_t* __restrict__ Clo, int nq, int nlist, int d, int nqt,
                                                                 int nct, const float* __restrict__ qn2,
                                                                 const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
     if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;   // (the selection's counter of queued queries)
+    constexpr int LS = x_ls(KT);
     extern __shared__ __align__(16) uint16_t x_smem[];
-    uint16_t *Ah = x_smem, *Al = Ah + TM * X_LS, *Bh = Al + TM * X_LS, *Bl = Bh + X_T * X_LS;
+    uint16_t *Ah = x_smem, *Al = Ah + TM * LS, *Bh = Al + TM * LS, *Bl = Bh + X_T * LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int r8 = blockIdx.x >> 3;
@@ -201,19 +207,19 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    constexpr int NA = TM * (X_KT / 4) / 256, NB = X_KT / 16;       // 16-byte loads per thread and K tile: A (fp32), B (bf16, hi and lo)
+    constexpr int NA = TM * (KT / 4) / 256, NB = KT / 16;       // 16-byte loads per thread and K tile: A (fp32), B (bf16, hi and lo)
     float4 pa[NA];
     uint4 pbh[NB], pbl[NB];
     auto gload = [&](int k0) {
 #pragma unroll
-        for (int r = 0; r < NA; ++r) {         // A: TM rows x (X_KT / 4) float4
-            const int f = tid + 256 * r, row = f / (X_KT / 4), c4 = f % (X_KT / 4);
+        for (int r = 0; r < NA; ++r) {         // A: TM rows x (KT / 4) float4
+            const int f = tid + 256 * r, row = f / (KT / 4), c4 = f % (KT / 4);
             const int gr = min(m0 + row, nq - 1), gk = k0 + c4 * 4;
             pa[r] = gk < d ? *reinterpret_cast<const float4*>(Q + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int r = 0; r < NB; ++r) {         // B: 128 rows x (X_KT / 8) x (8 bf16), twice
-            const int f = tid + 256 * r, row = f / (X_KT / 8), c8 = f % (X_KT / 8);
+        for (int r = 0; r < NB; ++r) {         // B: 128 rows x (KT / 8) x (8 bf16), twice
+            const int f = tid + 256 * r, row = f / (KT / 8), c8 = f % (KT / 8);
             const int gr = min(n0 + row, nlist - 1), gk = k0 + c8 * 8;
             const bool in = gk < d;
             pbh[r] = in ? *reinterpret_cast<const uint4*>(Chi + (int64_t)gr * d + gk) : make_uint4(0u, 0u, 0u, 0u);
@@ -221,37 +227,37 @@ __global__ void __launch_bounds__(256) coarse_gemm_split_kernel(const float* __r
         }
     };
     gload(0);
-    for (int k0 = 0; k0 < d; k0 += X_KT) {
+    for (int k0 = 0; k0 < d; k0 += KT) {
         __syncthreads();  // previous tile fully consumed
 #pragma unroll
         for (int r = 0; r < NA; ++r) {
-            const int f = tid + 256 * r, row = f / (X_KT / 4), c4 = f % (X_KT / 4);
+            const int f = tid + 256 * r, row = f / (KT / 4), c4 = f % (KT / 4);
             uint32_t h01, l01, h23, l23;
             split_bf16_pair(pa[r].x, pa[r].y, h01, l01);
             split_bf16_pair(pa[r].z, pa[r].w, h23, l23);
-            *reinterpret_cast<uint2*>(Ah + row * X_LS + c4 * 4) = make_uint2(h01, h23);
-            *reinterpret_cast<uint2*>(Al + row * X_LS + c4 * 4) = make_uint2(l01, l23);
+            *reinterpret_cast<uint2*>(Ah + row * LS + c4 * 4) = make_uint2(h01, h23);
+            *reinterpret_cast<uint2*>(Al + row * LS + c4 * 4) = make_uint2(l01, l23);
         }
 #pragma unroll
         for (int r = 0; r < NB; ++r) {
-            const int f = tid + 256 * r, row = f / (X_KT / 8), c8 = f % (X_KT / 8);
-            *reinterpret_cast<uint4*>(Bh + row * X_LS + c8 * 8) = pbh[r];
-            *reinterpret_cast<uint4*>(Bl + row * X_LS + c8 * 8) = pbl[r];
+            const int f = tid + 256 * r, row = f / (KT / 8), c8 = f % (KT / 8);
+            *reinterpret_cast<uint4*>(Bh + row * LS + c8 * 8) = pbh[r];
+            *reinterpret_cast<uint4*>(Bl + row * LS + c8 * 8) = pbl[r];
         }
-        if (k0 + X_KT < d) gload(k0 + X_KT);     // (the registers are free again: the next tile's loads go out ahead of the barrier)
+        if (k0 + KT < d) gload(k0 + KT);     // (the registers are free again: the next tile's loads go out ahead of the barrier)
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < X_KT / 16; ++ks) {
+        for (int ks = 0; ks < KT / 16; ++ks) {
             bf16x8 ah[2], al[2], bh[NBT], bl[NBT];
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
-                const int o = (wm + a * 32 + i32) * X_LS + ks * 16 + h * 8;
+                const int o = (wm + a * 32 + i32) * LS + ks * 16 + h * 8;
                 ah[a] = *reinterpret_cast<const bf16x8*>(Ah + o);
                 al[a] = *reinterpret_cast<const bf16x8*>(Al + o);
             }
 #pragma unroll
             for (int b = 0; b < NBT; ++b) {
-                const int o = (wn + b * 32 + i32) * X_LS + ks * 16 + h * 8;
+                const int o = (wn + b * 32 + i32) * LS + ks * 16 + h * 8;
                 bh[b] = *reinterpret_cast<const bf16x8*>(Bh + o);
                 bl[b] = *reinterpret_cast<const bf16x8*>(Bl + o);
             }
@@ -381,13 +387,13 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         if (grid > 0x7fffffff) return fail(RAGO_UNSUPPORTED, "nq * nlist too large");
         static OncePerDevice attr;
         if (attr.first()) {
-            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
-            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, X_LDS));
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<128, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, x_lds(128, 32)));
+            RAGO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coarse_gemm_split_kernel<64, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, x_lds(64, 64)));
         }
         if (half_tile)
-            coarse_gemm_split_kernel<64><<<(unsigned)grid, 256, (64 * 2 + X_T * 2) * X_LS * 2, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
+            coarse_gemm_split_kernel<64, 64><<<(unsigned)grid, 256, x_lds(64, 64), st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
         else
-            coarse_gemm_split_kernel<128><<<(unsigned)grid, 256, X_LDS, st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
+            coarse_gemm_split_kernel<128, 32><<<(unsigned)grid, 256, x_lds(128, 32), st>>>(q, idx->cen_hi, idx->cen_lo, (int)nq, nlist, d, nqt, nct, qn2, cn2, S, zero_me);
     }
     RAGO_HIP(hipGetLastError());
     return RAGO_OK;
