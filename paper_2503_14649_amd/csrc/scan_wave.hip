@@ -291,7 +291,6 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
         const int bias = __builtin_amdgcn_readfirstlane(P.bias[pair]);
         // ---- corrections of this pair: entries whose exact value differs from the base table's
         int ncorr = 0, maxpos = 0;
-#ifndef RAGO_WV_NOCORR
         if (shared_base) {
             for (int i0c = 0; i0c < namb; i0c += 64) {
                 const int i = i0c + lane;
@@ -314,7 +313,6 @@ __global__ void __launch_bounds__(THREADS, 4) scan_kernel(const WaveParams W) {
             }
             maxpos = __builtin_amdgcn_readfirstlane(maxpos);
         }
-#endif
         int cnt = 0;
         auto bound = [&]() {            // the query's bound in units of this pair's sums
             const int64_t dd = (int64_t)sh[2] - bias;
@@ -824,19 +822,12 @@ static int launch_one(const WaveParams& W, int grid, hipStream_t st) {
 
 // Blocks per item: enough items for every resident wave to take many (a wave works through an item alone, so what
 // is left at the end of the kernel is the longest item still running), at most 512 blocks (position field).
-#ifndef RAGO_WV_PERWAVE
-#define RAGO_WV_PERWAVE 4.0
-#endif
-#ifndef RAGO_WV_MINCH
-#define RAGO_WV_MINCH 8
-#endif
+constexpr double WV_ITEMS_PER_WAVE = 4.0;   // items aimed at per resident wave
+constexpr int WV_MIN_CHUNK = 8;
 int wave_chunk_len(double total_blocks, int n_cu) {
-    const double want = RAGO_WV_PERWAVE * 2 * wavescan::WAVES * n_cu;
-    int c = RAGO_WV_MINCH;
+    const double want = WV_ITEMS_PER_WAVE * 2 * wavescan::WAVES * n_cu;
+    int c = WV_MIN_CHUNK;
     while (c < 512 && total_blocks / c > want) c <<= 1;
-#ifdef RAGO_WV_CH
-    c = RAGO_WV_CH;
-#endif
     return c;
 }
 
