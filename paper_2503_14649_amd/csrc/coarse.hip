@@ -30,13 +30,12 @@ __device__ __forceinline__ float coarse_score(float ip, int row, int col, const 
     return qn2 ? 2.0f * ip - cn2[col] - qn2[row] : ip;
 }
 
-template <int TM>
 __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restrict__ Q, const float* __restrict__ C, int nq,
                                                           int nlist, int d, const float* __restrict__ qn2,
                                                           const float* __restrict__ cn2, float* __restrict__ S, int64_t* zero_me) {
     if (zero_me && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_me = 0;   // (the selection's counter of queued queries)
-    constexpr int MT = TM == 128 ? 2 : 1;  // 32x32 MFMA tiles per wave along M
-    constexpr int NT = TM == 128 ? 2 : 1;  //                         and along N
+    constexpr int TM = 32;                 // query rows per workgroup: one 32x32 MFMA tile per wave, the four waves side by side
+    constexpr int MT = 1, NT = 1;
     constexpr int AF = TM * 8 / 256;       // float4 loads per thread for the A tile
     constexpr int BF = G_TN * 8 / 256;
     __shared__ __align__(16) float As[TM * G_LS];
@@ -44,8 +43,7 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int n0 = blockIdx.x * G_TN, m0 = blockIdx.y * TM;
-    const int wm = TM == 128 ? (wave >> 1) * 64 : 0;
-    const int wn = TM == 128 ? (wave & 1) * 64 : wave * 32;
+    const int wm = 0, wn = wave * 32;
 
     v16f acc[MT][NT];
 #pragma unroll
@@ -55,8 +53,12 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    float4 pa[AF], pb[BF];
-    auto gload = [&](int k0) {
+    // Two K tiles are on their way at any time, in two sets of registers.  (It changed nothing measurable: what bounds
+    // this kernel is the fp32 matrix instruction itself, 64 cycles for two steps of k: 3.2 GFLOP of 32 padded rows x
+    // 65536 x 768 take 46 us where the centroids' stream alone would take 33.)
+    constexpr int AHEAD = 2;
+    float4 pa0[AF], pb0[BF], pa1[AF], pb1[BF];
+    auto gload = [&](float4 (&pa)[AF], float4 (&pb)[BF], int k0) {
 #pragma unroll
         for (int r = 0; r < AF; ++r) {
             const int f = tid + 256 * r, row = f >> 3, c4 = f & 7;
@@ -70,8 +72,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
             pb[r] = gk < d ? *reinterpret_cast<const float4*>(C + (int64_t)gr * d + gk) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
-    gload(0);
-    for (int k0 = 0; k0 < d; k0 += G_KT) {
+    // one K tile: the registers that hold it go to LDS and are sent for the tile after the next; then the products
+    auto step = [&](float4 (&pa)[AF], float4 (&pb)[BF], int k0) {
         __syncthreads();  // previous tile fully consumed
 #pragma unroll
         for (int r = 0; r < AF; ++r) {
@@ -83,8 +85,8 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
             const int f = tid + 256 * r;
             *reinterpret_cast<float4*>(Bs + (f >> 3) * G_LS + (f & 7) * 4) = pb[r];
         }
+        if (k0 + AHEAD * G_KT < d) gload(pa, pb, k0 + AHEAD * G_KT);
         __syncthreads();
-        if (k0 + G_KT < d) gload(k0 + G_KT);
         // lane (i32, h) owns k = h*16 .. h*16+15 of this tile for both operands
         float af[MT][16], bf[NT][16];
 #pragma unroll
@@ -108,6 +110,12 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
 #pragma unroll
                 for (int b = 0; b < NT; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a][s], bf[b][s], acc[a][b], 0, 0, 0);
+    };
+    gload(pa0, pb0, 0);
+    gload(pa1, pb1, G_KT);                // (beyond d: zeros, no loads)
+    for (int k0 = 0; k0 < d; k0 += 2 * G_KT) {
+        step(pa0, pb0, k0);
+        if (k0 + G_KT < d) step(pa1, pb1, k0 + G_KT);
     }
     // D layout of the 32x32 tile: register r, lane (i32, h) -> row 8*(r/4) + 4*h + r%4, column i32
 #pragma unroll
@@ -374,10 +382,11 @@ int launch_coarse(rago_index* idx, const float* q, int64_t nq, float* S, hipStre
         if (nq == 1) coarse_gemv_kernel<1><<<grid, GV_THREADS, lds, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
         else coarse_gemv_kernel<2><<<grid, GV_THREADS, lds, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else if (nq <= 32) {
-        coarse_gemm_kernel<32><<<dim3(gx, (unsigned)((nq + 31) / 32)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
-    } else if (nq < 128 || d % 8) {      // (the split kernel reads the centroids 8 bf16 at a time)
-        coarse_gemm_kernel<128><<<dim3(gx, (unsigned)((nq + 127) / 128)), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
+        // (up to 32 queries the fp32 products of one 32-row tile keep pace with the centroids' stream: 46 us for
+        // 65536 x 768 against 55 with the split kernel's 64-row tile; from 33 on they do not: 48 queries 122 us against 58)
+        coarse_gemm_kernel<<<dim3(gx, 1), 256, 0, st>>>(q, idx->centroids, (int)nq, nlist, d, qn2, cn2, S, zero_me);
     } else {
+        // (the split kernel reads the centroids 8 bf16 at a time: d is a multiple of 16, since m is one and d one of m)
         // query rows per workgroup: 64 while 128 would give the chip fewer than two workgroups per compute unit
         const int nct = (nlist + X_T - 1) / X_T;
         const bool half_tile = (int64_t)((nq + X_T - 1) / X_T) * nct < 2 * (int64_t)idx->n_cu;

@@ -93,8 +93,8 @@ def test_coarse_scores_within_1e4(case, rb):
 
 @pytest.mark.parametrize("nq", [20, 100, 300])
 def test_coarse_and_select_by_batch_size(rb, nq):
-    """The three coarse-score kernels (32-row and 128-row fp32 tiles, split-bf16 tiles from 128 queries up) on
-    ragged tiles: nlist and nq are not multiples of 128, d is not a multiple of the 32-wide K tile."""
+    """The tile kernels for coarse scores (32-row fp32 tiles up to 32 queries, split-bf16 tiles of 64 rows beyond) on
+    ragged tiles: nlist and nq are not multiples of the tile sizes, d is not a multiple of the K tiles."""
     ix = to_np(synth.random_index(n=20000, d=80, m=16, nlist=1000, seed=77))
     Q = _queries(nq, 80, 5)
     h = rb.rago_index_wrap(dev_index(ix))
@@ -617,7 +617,7 @@ def test_l2_coarse_and_select_for_one_or_two_queries(rb, nq):
 
 
 def test_l2_large_batch_coarse(rb):
-    """The split-bf16 coarse kernel (128 queries and more) with the Euclidean epilogue."""
+    """The split-bf16 coarse kernel (more than 32 queries) with the Euclidean epilogue."""
     ix = to_np(synth.random_index(n=20000, d=80, m=16, nlist=1000, seed=78))
     Q = _queries(300, 80, 6)
     h = rb.rago_index_wrap(dev_index(ix), metric="l2")
