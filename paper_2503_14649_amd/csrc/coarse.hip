@@ -53,9 +53,10 @@ __global__ void __launch_bounds__(256) coarse_gemm_kernel(const float* __restric
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // Two K tiles are on their way at any time, in two sets of registers.  (It changed nothing measurable: what bounds
-    // this kernel is the fp32 matrix instruction itself, 64 cycles for two steps of k: 3.2 GFLOP of 32 padded rows x
-    // 65536 x 768 take 46 us where the centroids' stream alone would take 33.)
+    // Two K tiles are on their way at any time, in two sets of registers.  (Neither that nor 16-row tiles on the
+    // 16x16x4 instruction - half the matrix cycles - changed the 40 us this kernel takes for 65536 x 768, where the
+    // streaming kernel for one or two queries takes 33: what it pays for is the trip of every tile through LDS, two
+    // barriers per 20 KB.)
     constexpr int AHEAD = 2;
     float4 pa0[AF], pb0[BF], pa1[AF], pb1[BF];
     auto gload = [&](float4 (&pa)[AF], float4 (&pb)[BF], int k0) {
